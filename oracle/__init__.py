@@ -1,0 +1,138 @@
+"""CPU oracle (TEST INFRASTRUCTURE, not the product).
+
+Thin ctypes wrappers around ``lwp_oracle.c`` (plain C, compiled with gcc) plus
+``brute.py`` (exhaustive enumeration of Eq. 1).  Nothing in the GPU package
+imports this; only tests, the smoke check and the benchmark's cpu_baseline leg do.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = [os.path.join(_HERE, "lwp_oracle.c"), os.path.join(_HERE, "cost_model_oracle.c")]
+_LIB_PATH = os.path.join(_HERE, "liblwp_oracle.so")
+_lib = None
+
+OK, E_INVAL, E_NOT_REDUCIBLE, E_OVERFLOW, E_NOMEM = 0, -1, -3, -4, -5
+SCHEDULE_ROUNDS, SCHEDULE_LEFT_FOLD = 0, 1
+
+_i32p = ctypes.POINTER(ctypes.c_int32)
+_i64p = ctypes.POINTER(ctypes.c_int64)
+
+
+class OracleError(RuntimeError):
+    def __init__(self, code, what):
+        super().__init__(f"{what}: oracle status {code}")
+        self.code = code
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle's C sources into a shared library next to them."""
+    srcs = [s for s in _SRC if os.path.exists(s)]
+    if not force and os.path.exists(_LIB_PATH) and all(
+            os.path.getmtime(_LIB_PATH) >= os.path.getmtime(s) for s in srcs):
+        return _LIB_PATH
+    cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-Wextra",
+           "-o", _LIB_PATH] + srcs
+    subprocess.run(cmd, check=True)
+    return _LIB_PATH
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB_PATH)
+    return _lib
+
+
+def _p(a):
+    return a.ctypes.data_as(_i32p)
+
+
+def _c(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def omp_threads() -> int:
+    """Threads the C loops use (OpenMP default unless OMP_NUM_THREADS is set)."""
+    n = os.environ.get("OMP_NUM_THREADS")
+    return int(n) if n else (os.cpu_count() or 1)
+
+
+def strategy_cost(n_nodes, edges, C, tc, ts, tx, S) -> int:
+    """Eq. 1 for a complete strategy S, from the original tables."""
+    lib = _load()
+    edges, tc, ts, tx, S = _c(edges).reshape(-1, 2), _c(tc), _c(ts), _c(tx), _c(S)
+    out = ctypes.c_int64(0)
+    rc = lib.orc_strategy_cost(n_nodes, len(edges), _p(edges), C, _p(tc), _p(ts), _p(tx), _p(S),
+                               ctypes.byref(out))
+    if rc:
+        raise OracleError(rc, "strategy_cost")
+    return out.value
+
+
+def minplus_argmin(A, w, B):
+    """Eq. 2: returns (out[Ci][Ck], arg[Ci][Ck]) for A[Ci][Cj], w[Cj], B[Cj][Ck]."""
+    lib = _load()
+    A, w, B = _c(A), _c(w), _c(B)
+    Ci, Cj = A.shape
+    Ck = B.shape[1]
+    assert B.shape[0] == Cj and w.shape == (Cj,)
+    out = np.empty((Ci, Ck), np.int32)
+    arg = np.empty((Ci, Ck), np.int32)
+    rc = lib.orc_minplus_argmin(Ci, Cj, Ck, _p(A), _p(w), _p(B), _p(out), _p(arg))
+    if rc:
+        raise OracleError(rc, "minplus_argmin")
+    return out, arg
+
+
+def edge_sum(e1, e2):
+    """Eq. 3."""
+    lib = _load()
+    e1, e2 = _c(e1), _c(e2)
+    out = np.empty_like(e1)
+    rc = lib.orc_edge_sum(e1.shape[0], e1.shape[1], _p(e1), _p(e2), _p(out))
+    if rc:
+        raise OracleError(rc, "edge_sum")
+    return out
+
+
+def final_pair(wi, T, wk):
+    """Residual two-node graph: (cost, a, b) with the lowest flat index among equals."""
+    lib = _load()
+    wi, T, wk = _c(wi), _c(T), _c(wk)
+    cost = ctypes.c_int64(0)
+    a, b = ctypes.c_int32(0), ctypes.c_int32(0)
+    rc = lib.orc_final_pair(T.shape[0], _p(wi), _p(T), _p(wk), ctypes.byref(cost),
+                            ctypes.byref(a), ctypes.byref(b))
+    if rc:
+        raise OracleError(rc, "final_pair")
+    return cost.value, a.value, b.value
+
+
+STEP_DTYPE = np.dtype([("kind", "<i4"), ("j", "<i4"), ("i", "<i4"), ("k", "<i4"),
+                       ("e1", "<i4"), ("e2", "<i4"), ("round", "<i4")])
+
+
+def search(n_nodes, edges, C, tc, ts, tx, schedule=SCHEDULE_ROUNDS):
+    """Alg. 1.  Returns dict(cost, strategy, steps, n_rounds)."""
+    lib = _load()
+    edges, tc, ts, tx = _c(edges).reshape(-1, 2), _c(tc), _c(ts), _c(tx)
+    E = len(edges)
+    assert tc.shape == (n_nodes, C) and ts.shape == (n_nodes, C) and tx.shape == (E, C, C)
+    S = np.empty(n_nodes, np.int32)
+    steps = np.zeros(max(E, 1), STEP_DTYPE)
+    cost = ctypes.c_int64(0)
+    n_steps, n_rounds = ctypes.c_int32(0), ctypes.c_int32(0)
+    rc = lib.orc_search(n_nodes, E, _p(edges), C, _p(tc), _p(ts), _p(tx), int(schedule),
+                        ctypes.byref(cost), _p(S), steps.ctypes.data_as(ctypes.c_void_p),
+                        ctypes.byref(n_steps), ctypes.byref(n_rounds))
+    if rc:
+        raise OracleError(rc, "search")
+    return {"cost": cost.value, "strategy": S, "steps": steps[:n_steps.value],
+            "n_rounds": n_rounds.value}

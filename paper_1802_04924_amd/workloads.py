@@ -1,0 +1,205 @@
+"""Seeded synthetic inputs for the strategy search (graphs, cost tables, layer
+and configuration descriptors).
+
+This module only *draws inputs*.  It contains none of the method's arithmetic
+(no cost formula, no elimination, no min-plus); both the CPU oracle's tests and
+the GPU library's tests feed on the arrays produced here so that the two sides
+see identical bits.
+
+All random tables come from ``numpy.random.Generator(PCG64(seed))`` with
+``integers(lo, hi, endpoint=True)`` drawn in the fixed order t_c, t_s, t_x.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+# Schedules understood by both the oracle and the GPU library.
+SCHEDULE_ROUNDS = 0      # batched rounds of independent eliminations
+SCHEDULE_LEFT_FOLD = 1   # one node elimination per round, lowest eligible id
+
+# Layer kinds for the analytic cost model inputs.
+KIND_CONV, KIND_POOL, KIND_FC = 0, 1, 2
+
+LAYER_FIELDS = ("kind", "N", "Cin", "Hin", "Win", "Cout", "Hout", "Wout",
+                "kh", "kw", "sh", "sw", "ph", "pw")
+CONFIG_FIELDS = ("n", "h", "w", "c", "dev_offset", "pad")
+
+
+def _rng(seed: int) -> np.random.Generator:
+    return np.random.Generator(np.random.PCG64(seed))
+
+
+def chain_edges(n_nodes: int) -> np.ndarray:
+    """Edge list (l, l+1) of a chain of ``n_nodes`` layers."""
+    e = np.stack([np.arange(n_nodes - 1), np.arange(1, n_nodes)], axis=1)
+    return np.ascontiguousarray(e, dtype=np.int32).reshape(-1, 2)
+
+
+def random_tables(n_nodes, edges, C, seed, tc_range, ts_range, tx_range):
+    """Uniform int32 tables t_c[N][C], t_s[N][C], t_x[E][C][C]."""
+    rng = _rng(seed)
+    E = len(edges)
+    tc = rng.integers(tc_range[0], tc_range[1], size=(n_nodes, C), endpoint=True, dtype=np.int32)
+    ts = rng.integers(ts_range[0], ts_range[1], size=(n_nodes, C), endpoint=True, dtype=np.int32)
+    tx = rng.integers(tx_range[0], tx_range[1], size=(E, C, C), endpoint=True, dtype=np.int32)
+    return tc, ts, tx
+
+
+def _problem(name, n_nodes, edges, C, tc, ts, tx, schedule):
+    return {"name": name, "n_nodes": int(n_nodes), "edges": np.ascontiguousarray(edges, dtype=np.int32),
+            "C": int(C), "tc": tc, "ts": ts, "tx": tx, "schedule": schedule}
+
+
+def chain_problem(n_layers, C, seed, tc_range=(1, 1000), ts_range=(1, 1000), tx_range=(0, 1000),
+                  schedule=SCHEDULE_ROUNDS, name="chain"):
+    edges = chain_edges(n_layers)
+    tc, ts, tx = random_tables(n_layers, edges, C, seed, tc_range, ts_range, tx_range)
+    return _problem(name, n_layers, edges, C, tc, ts, tx, schedule)
+
+
+def config0():
+    """Chain of 6 layers, 16 configurations each, seed 0 (LeNet-5-sized, cf. Table 3)."""
+    return chain_problem(6, 16, 0, name="cfg0_chain6_C16")
+
+
+def forkjoin_edges(n_modules: int, seed: int):
+    """Inception-shaped DAG: ``n_modules`` fork/join modules of 12 nodes.
+
+    Module m has a fork node F, four branches and a join node J.  Even modules
+    use branch lengths (3,3,2,2), odd modules (3,3,3,1), each in a seeded
+    permutation, so every module has 10 branch nodes with 1-3 nodes per branch.
+    Node ids are topological: F, then the branches one after another, then J.
+    Edges: along every branch F->b1->...->bk->J, the last edge of every branch
+    twice (a parallel pair), and J_m -> F_{m+1}.
+    """
+    rng = _rng(seed)
+    edges = []
+    for m in range(n_modules):
+        base = 12 * m
+        lens = np.array([3, 3, 2, 2] if m % 2 == 0 else [3, 3, 3, 1])
+        lens = lens[rng.permutation(4)]
+        F, J = base, base + 11
+        nid = base + 1
+        for L in lens:
+            prev = F
+            for _ in range(int(L)):
+                edges.append((prev, nid))
+                prev = nid
+                nid += 1
+            edges.append((prev, J))
+            edges.append((prev, J))          # duplicated tail edge
+        assert nid == J
+        if m + 1 < n_modules:
+            edges.append((J, base + 12))
+    return 12 * n_modules, np.asarray(edges, dtype=np.int32).reshape(-1, 2)
+
+
+def forkjoin_problem(n_modules, C, seed, lo=1, hi=100000, schedule=SCHEDULE_ROUNDS, name="forkjoin"):
+    n_nodes, edges = forkjoin_edges(n_modules, seed)
+    # the graph draws come first from their own generator; tables use seed too but a fresh stream
+    tc, ts, tx = random_tables(n_nodes, edges, C, seed + 1000003, (lo, hi), (lo, hi), (lo, hi))
+    return _problem(name, n_nodes, edges, C, tc, ts, tx, schedule)
+
+
+def config2(C: int = 512, n_modules: int = 10):
+    """Inception-shaped DAG, 120 nodes / 189 edges at the default size."""
+    return forkjoin_problem(n_modules, C, 2, name=f"cfg2_forkjoin{n_modules}_C{C}")
+
+
+def batched_products(batch, Ci, Cj, Ck, seed, hi=1 << 20):
+    """Independent (A, w, B) triples for the isolated node-elimination kernel."""
+    rng = _rng(seed)
+    A = rng.integers(0, hi, size=(batch, Ci, Cj), endpoint=True, dtype=np.int32)
+    w = rng.integers(0, hi, size=(batch, Cj), endpoint=True, dtype=np.int32)
+    B = rng.integers(0, hi, size=(batch, Cj, Ck), endpoint=True, dtype=np.int32)
+    return A, w, B
+
+
+def config3(batch: int = 4096, C: int = 256):
+    return batched_products(batch, C, C, C, 3)
+
+
+def config4(n_layers: int = 64, C: int = 4096):
+    """Long chain with many configurations per layer; left-fold schedule."""
+    hi = 1 << 20
+    return chain_problem(n_layers, C, 4, (0, hi), (0, hi), (0, hi),
+                         schedule=SCHEDULE_LEFT_FOLD, name=f"cfg4_chain{n_layers}_C{C}")
+
+
+# ---------------------------------------------------------------------------
+# Inputs of the analytic cost model (config 1): layer shapes, configuration
+# enumeration, machine constants.  Pure descriptors; the formulas live elsewhere.
+# ---------------------------------------------------------------------------
+
+def alexnet_layers(batch: int = 256) -> np.ndarray:
+    """11-layer AlexNet-shaped chain as an int32 array [11][14] (LAYER_FIELDS).
+
+    Shapes agree with the two AlexNet rows the paper lists (conv2: 64->192
+    channels at 27x27 with a 5x5 kernel; conv5: 256->256 at 13x13 with 3x3).
+    """
+    def conv(cin, hin, cout, k, s, p):
+        hout = (hin + 2 * p - k) // s + 1
+        return (KIND_CONV, batch, cin, hin, hin, cout, hout, hout, k, k, s, s, p, p)
+
+    def pool(c, hin, k, s):
+        hout = (hin - k) // s + 1
+        return (KIND_POOL, batch, c, hin, hin, c, hout, hout, k, k, s, s, 0, 0)
+
+    def fc(cin, hin, cout):
+        return (KIND_FC, batch, cin, hin, hin, cout, 1, 1, hin, hin, 1, 1, 0, 0)
+
+    layers = [
+        conv(3, 224, 64, 11, 4, 2),    # conv1 -> 55
+        pool(64, 55, 3, 2),            # pool1 -> 27
+        conv(64, 27, 192, 5, 1, 2),    # conv2 -> 27
+        pool(192, 27, 3, 2),           # pool2 -> 13
+        conv(192, 13, 384, 3, 1, 1),   # conv3
+        conv(384, 13, 256, 3, 1, 1),   # conv4
+        conv(256, 13, 256, 3, 1, 1),   # conv5
+        pool(256, 13, 3, 2),           # pool3 -> 6
+        fc(256, 6, 4096),              # fc6
+        fc(4096, 1, 4096),             # fc7
+        fc(4096, 1, 1000),             # fc8
+    ]
+    return np.asarray(layers, dtype=np.int32)
+
+
+def config_table(n_devices: int = 16, n_rows: int = 256) -> np.ndarray:
+    """Configuration enumeration as int32 [n_rows][6] (CONFIG_FIELDS).
+
+    Rows: every (n, h, w, c) of power-of-two degrees whose product d divides
+    into ``n_devices`` (d <= n_devices), each with the device-block offsets
+    0, d, 2d, ... ; sorted lexicographically by (n, h, w, c, offset); then
+    padding rows (all zeros, ``n == 0`` marks padding) up to ``n_rows``.
+    """
+    pows = [1 << i for i in range(n_devices.bit_length()) if (1 << i) <= n_devices]
+    rows = []
+    for n in pows:
+        for h in pows:
+            for w in pows:
+                for c in pows:
+                    d = n * h * w * c
+                    if d > n_devices:
+                        continue
+                    for off in range(0, n_devices - d + 1, d):
+                        rows.append((n, h, w, c, off, 0))
+    rows.sort()
+    if len(rows) > n_rows:
+        raise ValueError("enumeration larger than the requested table")
+    rows += [(0, 0, 0, 0, 0, 0)] * (n_rows - len(rows))
+    return np.asarray(rows, dtype=np.int32)
+
+
+def machine(n_devices: int = 16, flop_per_ns: int = 10_000, byte_per_ns: int = 10,
+            invalid_cost: int = 1 << 28):
+    """Machine constants: 10 TFLOP/s per device, 10 GB/s links, 2^28 ns sentinel."""
+    return {"n_devices": n_devices, "flop_per_ns": flop_per_ns, "byte_per_ns": byte_per_ns,
+            "invalid_cost": invalid_cost}
+
+
+def config1(batch: int = 256):
+    """Descriptors for the AlexNet-shaped chain whose tables the cost model builds."""
+    layers = alexnet_layers(batch)
+    return {"name": "cfg1_alexnet11_C256", "layers": layers, "edges": chain_edges(len(layers)),
+            "configs": config_table(16, 256), "machine": machine(), "C": 256,
+            "n_nodes": len(layers), "schedule": SCHEDULE_ROUNDS}

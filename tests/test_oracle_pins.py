@@ -1,0 +1,286 @@
+"""Pins for the CPU oracle: every oracle function is checked against something
+other than itself -- exhaustive enumeration of Eq. 1, a library broadcast form
+of Eq. 2, closed forms, the textbook layered shortest path on chains, and the
+invariants Thm. 1 / Thm. 2 state.  No GPU needed."""
+import itertools
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import brute
+from paper_1802_04924_amd import workloads as wl
+
+
+def numpy_minplus(A, w, B):
+    """Eq. 2 through numpy broadcasting; argmin returns the first (lowest) index."""
+    s = A.astype(np.int64)[:, :, None] + w.astype(np.int64)[None, :, None] + B.astype(np.int64)[None, :, :]
+    return s.min(axis=1), s.argmin(axis=1)
+
+
+def viterbi_chain(tc, ts, tx):
+    """Textbook layered-graph shortest path (independent of the elimination algorithm)."""
+    w = tc.astype(np.int64) + ts.astype(np.int64)
+    d = w[0].copy()
+    for l in range(1, len(w)):
+        d = (d[:, None] + tx[l - 1].astype(np.int64)).min(axis=0) + w[l]
+    return int(d.min())
+
+
+def rand_problem(rng, n_nodes, edges, C, hi):
+    E = len(edges)
+    tc = rng.integers(0, hi, size=(n_nodes, C), endpoint=True, dtype=np.int32)
+    ts = rng.integers(0, hi, size=(n_nodes, C), endpoint=True, dtype=np.int32)
+    tx = rng.integers(0, hi, size=(E, C, C), endpoint=True, dtype=np.int32)
+    return tc, ts, tx
+
+
+# ------------------------------------------------------------------ Eq. 2
+@pytest.mark.parametrize("shape", [(1, 1, 1), (3, 5, 4), (17, 33, 9), (64, 64, 64), (40, 129, 70)])
+@pytest.mark.parametrize("hi", [1, 3, 1 << 20])
+def test_minplus_matches_numpy_broadcast(shape, hi):
+    rng = np.random.default_rng(hash((shape, hi)) % (1 << 32))
+    Ci, Cj, Ck = shape
+    A = rng.integers(0, hi, size=(Ci, Cj), endpoint=True, dtype=np.int32)
+    w = rng.integers(0, hi, size=(Cj,), endpoint=True, dtype=np.int32)
+    B = rng.integers(0, hi, size=(Cj, Ck), endpoint=True, dtype=np.int32)
+    out, arg = oracle.minplus_argmin(A, w, B)
+    ref, refarg = numpy_minplus(A, w, B)
+    assert np.array_equal(out, ref)
+    assert np.array_equal(arg, refarg)          # lowest index among ties
+
+
+def test_minplus_rectangular_is_not_transposed():
+    # A and B of different, non-square shapes with distinct values: a transposed operand
+    # or swapped index cannot reproduce the broadcast form.
+    rng = np.random.default_rng(7)
+    A = rng.permutation(6 * 11).reshape(6, 11).astype(np.int32)
+    B = (1000 * rng.permutation(11 * 4)).reshape(11, 4).astype(np.int32)
+    w = (100000 * np.arange(11)[::-1]).astype(np.int32)
+    out, arg = oracle.minplus_argmin(A, w, B)
+    ref, refarg = numpy_minplus(A, w, B)
+    assert np.array_equal(out, ref) and np.array_equal(arg, refarg)
+
+
+def test_minplus_tropical_identity():
+    # B = tropical identity (0 on the diagonal, large elsewhere), w = 0  =>  out == A, arg[a][b] == b
+    rng = np.random.default_rng(1)
+    C = 37
+    A = rng.integers(0, 1000, size=(21, C), dtype=np.int32)
+    B = np.full((C, C), 1 << 24, np.int32)
+    np.fill_diagonal(B, 0)
+    out, arg = oracle.minplus_argmin(A, np.zeros(C, np.int32), B)
+    assert np.array_equal(out, A)
+    assert np.array_equal(arg, np.tile(np.arange(C, dtype=np.int32), (21, 1)))
+
+
+def test_minplus_all_equal_and_single_config():
+    out, arg = oracle.minplus_argmin(np.full((5, 9), 4, np.int32), np.full(9, 2, np.int32), np.full((9, 6), 1, np.int32))
+    assert (out == 7).all() and (arg == 0).all()
+    A = np.arange(5, dtype=np.int32).reshape(5, 1)
+    B = np.arange(10, 16, dtype=np.int32).reshape(1, 6)
+    out, arg = oracle.minplus_argmin(A, np.array([100], np.int32), B)
+    assert np.array_equal(out, A + 100 + B) and (arg == 0).all()
+
+
+def test_minplus_uses_w_exactly_once():
+    # with A = B = 0 the result is min(w) and its first position
+    w = np.array([9, 4, 7, 4, 8], np.int32)
+    out, arg = oracle.minplus_argmin(np.zeros((3, 5), np.int32), w, np.zeros((5, 2), np.int32))
+    assert (out == 4).all() and (arg == 1).all()
+
+
+def test_minplus_negative_and_overflow():
+    A = np.array([[-5, 3]], np.int32)
+    B = np.array([[2], [-20]], np.int32)
+    out, arg = oracle.minplus_argmin(A, np.array([0, 1], np.int32), B)
+    assert out[0, 0] == -16 and arg[0, 0] == 1
+    big = np.full((1, 1), 2**31 - 1, np.int32)
+    with pytest.raises(oracle.OracleError) as e:
+        oracle.minplus_argmin(big, np.array([1], np.int32), np.zeros((1, 1), np.int32))
+    assert e.value.code == oracle.E_OVERFLOW
+
+
+# ------------------------------------------------------------------ Eq. 3 and the residual pair
+def test_edge_sum_and_final_pair():
+    rng = np.random.default_rng(3)
+    e1 = rng.integers(0, 1 << 20, size=(13, 7), dtype=np.int32)
+    e2 = rng.integers(0, 1 << 20, size=(13, 7), dtype=np.int32)
+    assert np.array_equal(oracle.edge_sum(e1, e2), e1 + e2)
+    with pytest.raises(oracle.OracleError):
+        oracle.edge_sum(np.full((1, 1), 2**31 - 1, np.int32), np.ones((1, 1), np.int32))
+    C = 9
+    wi = rng.integers(0, 3, size=C, dtype=np.int32)
+    wk = rng.integers(0, 3, size=C, dtype=np.int32)
+    T = rng.integers(0, 3, size=(C, C), dtype=np.int32)      # many ties
+    cost, a, b = oracle.final_pair(wi, T, wk)
+    full = wi[:, None].astype(np.int64) + T + wk[None, :]
+    assert cost == full.min()
+    assert a * C + b == int(np.argmin(full))                 # lowest flat index
+
+
+# ------------------------------------------------------------------ Eq. 1
+def test_strategy_cost_hand_example():
+    # 3 nodes, edges (0,1), (1,2), (0,2); every term distinct so a dropped or doubled term shows.
+    edges = np.array([[0, 1], [1, 2], [0, 2]], np.int32)
+    C = 2
+    tc = np.array([[1, 2], [10, 20], [100, 200]], np.int32)
+    ts = np.array([[1000, 2000], [10000, 20000], [100000, 200000]], np.int32)
+    tx = (np.arange(12, dtype=np.int32).reshape(3, 2, 2) + 1) * 1000000
+    # S = (1, 0, 1): t_c: 2+10+200, t_s: 2000+10000+200000,
+    # t_x: e0[1][0] = 3e6, e1[0][1] = 6e6, e2[1][1] = 12e6
+    assert oracle.strategy_cost(3, edges, C, tc, ts, tx, [1, 0, 1]) == 212 + 212000 + 21000000
+    costs = brute.all_costs(3, edges, C, tc, ts, tx)
+    assert costs[1, 0, 1] == 212 + 212000 + 21000000
+
+
+def test_brute_force_orientation_of_backward_edge():
+    # edge (2,0): the table is [cfg of node 2][cfg of node 0]
+    edges = np.array([[2, 0]], np.int32)
+    tc = np.zeros((3, 2), np.int32)
+    tx = np.array([[[0, 5], [7, 9]]], np.int32)
+    costs = brute.all_costs(3, edges, 2, tc, tc, tx)
+    assert costs[1, 0, 0] == 5 and costs[0, 0, 1] == 7
+    assert oracle.strategy_cost(3, edges, 2, tc, tc, tx, [1, 0, 0]) == 5
+
+
+# ------------------------------------------------------------------ Alg. 1 against enumeration
+def test_config0_equals_brute_force_over_all_16_pow_6():
+    p = wl.config0()
+    best, S_lex, n_opt = brute.brute_force(p["n_nodes"], p["edges"], p["C"], p["tc"], p["ts"], p["tx"])
+    for schedule in (oracle.SCHEDULE_ROUNDS, oracle.SCHEDULE_LEFT_FOLD):
+        r = oracle.search(p["n_nodes"], p["edges"], p["C"], p["tc"], p["ts"], p["tx"], schedule)
+        assert r["cost"] == best
+        assert oracle.strategy_cost(p["n_nodes"], p["edges"], p["C"], p["tc"], p["ts"], p["tx"], r["strategy"]) == best
+        if n_opt == 1:
+            assert np.array_equal(r["strategy"], S_lex)
+        assert sum(s["kind"] == 0 for s in r["steps"]) == 4     # nodes 1..4
+    assert viterbi_chain(p["tc"], p["ts"], p["tx"]) == best
+
+
+def small_graphs():
+    g = {}
+    g["chain2"] = (2, [(0, 1)])
+    g["chain5"] = (5, [(0, 1), (1, 2), (2, 3), (3, 4)])
+    g["single"] = (1, [])
+    g["two_isolated"] = (2, [])
+    g["parallel3"] = (2, [(0, 1), (0, 1), (0, 1)])
+    g["diamond"] = (4, [(0, 1), (0, 2), (1, 3), (2, 3)])
+    g["diamond_skip"] = (4, [(0, 1), (0, 2), (1, 3), (2, 3), (0, 3)])
+    g["backward_ids"] = (4, [(3, 1), (1, 0), (0, 2)])              # chain 3->1->0->2
+    g["two_chains"] = (6, [(0, 1), (1, 2), (3, 4), (4, 5)])
+    g["residual"] = (6, [(0, 1), (1, 2), (2, 3), (1, 4), (4, 3), (3, 5), (3, 5)])
+    n, e = wl.forkjoin_edges(1, 5)
+    g["forkjoin1"] = (n, [tuple(x) for x in e])
+    return g
+
+
+@pytest.mark.parametrize("name", sorted(small_graphs()))
+@pytest.mark.parametrize("hi", [1, 50])
+@pytest.mark.parametrize("schedule", [oracle.SCHEDULE_ROUNDS, oracle.SCHEDULE_LEFT_FOLD])
+def test_search_equals_brute_force_on_tiny_graphs(name, hi, schedule):
+    n_nodes, edges = small_graphs()[name]
+    edges = np.asarray(edges, np.int32).reshape(-1, 2)
+    C = 2 if n_nodes > 8 else 3
+    for seed in range(4):
+        rng = np.random.default_rng(1000 * seed + hi)
+        tc, ts, tx = rand_problem(rng, n_nodes, edges, C, hi)
+        best, S_lex, n_opt = brute.brute_force(n_nodes, edges, C, tc, ts, tx)
+        r = oracle.search(n_nodes, edges, C, tc, ts, tx, schedule)
+        assert r["cost"] == best
+        assert oracle.strategy_cost(n_nodes, edges, C, tc, ts, tx, r["strategy"]) == best
+        if n_opt == 1:
+            assert np.array_equal(r["strategy"], S_lex)
+        # each elimination removes exactly one edge
+        assert len(r["steps"]) < max(len(edges), 1) or len(edges) == 0
+
+
+def test_forkjoin_two_modules_small_C():
+    p = wl.forkjoin_problem(2, 2, 11, lo=0, hi=3)
+    # 24 nodes, C = 2: 2^24 strategies
+    best, S_lex, n_opt = brute.brute_force(p["n_nodes"], p["edges"], 2, p["tc"], p["ts"], p["tx"])
+    r = oracle.search(p["n_nodes"], p["edges"], 2, p["tc"], p["ts"], p["tx"])
+    assert r["cost"] == best
+    assert oracle.strategy_cost(p["n_nodes"], p["edges"], 2, p["tc"], p["ts"], p["tx"], r["strategy"]) == best
+    kinds = [s["kind"] for s in r["steps"]]
+    assert kinds.count(0) == 22 and kinds.count(1) == 14      # K = 2 remains; 8 duplicate + 6 branch merges
+
+
+def test_single_configuration_graph_is_the_plain_sum():
+    p = wl.forkjoin_problem(3, 1, 5)
+    r = oracle.search(p["n_nodes"], p["edges"], 1, p["tc"], p["ts"], p["tx"])
+    assert r["cost"] == int(p["tc"].astype(np.int64).sum() + p["ts"].astype(np.int64).sum() + p["tx"].astype(np.int64).sum())
+    assert (r["strategy"] == 0).all()
+
+
+# ------------------------------------------------------------------ Thm. 1 / Thm. 2 as invariants
+def test_single_node_elimination_preserves_the_optimum():
+    # graph 0->1->2->3 plus 0->3; eliminate node 1 by Eq. 2 and compare enumerations before/after
+    rng = np.random.default_rng(5)
+    C = 3
+    edges = np.array([[0, 1], [1, 2], [2, 3], [0, 3]], np.int32)
+    tc, ts, tx = rand_problem(rng, 4, edges, C, 9)
+    before, _, _ = brute.brute_force(4, edges, C, tc, ts, tx)
+    new_tab, arg = oracle.minplus_argmin(tx[0], tc[1] + ts[1], tx[1])
+    # relabel: nodes (0,2,3) -> (0,1,2)
+    edges2 = np.array([[0, 1], [1, 2], [0, 2]], np.int32)
+    tc2, ts2 = tc[[0, 2, 3]], ts[[0, 2, 3]]
+    tx2 = np.stack([new_tab, tx[2], tx[3]])
+    after, S2, _ = brute.brute_force(3, edges2, C, tc2, ts2, tx2)
+    assert before == after
+    # Thm. 1: S' + argmin is optimal for the original graph
+    S = [S2[0], arg[S2[0], S2[1]], S2[1], S2[2]]
+    assert oracle.strategy_cost(4, edges, C, tc, ts, tx, S) == before
+
+
+def test_single_edge_elimination_preserves_every_strategy_cost():
+    rng = np.random.default_rng(6)
+    C = 3
+    edges = np.array([[0, 1], [0, 1], [1, 2]], np.int32)
+    tc, ts, tx = rand_problem(rng, 3, edges, C, 9)
+    merged = oracle.edge_sum(tx[0], tx[1])
+    a = brute.all_costs(3, edges, C, tc, ts, tx)
+    b = brute.all_costs(3, np.array([[0, 1], [1, 2]], np.int32), C, tc, ts, np.stack([merged, tx[2]]))
+    assert np.array_equal(a, b)
+
+
+# ------------------------------------------------------------------ chains, schedules, larger sizes
+@pytest.mark.parametrize("n_layers,C", [(2, 7), (3, 5), (11, 24), (33, 16)])
+def test_chain_cost_equals_layered_shortest_path(n_layers, C):
+    p = wl.chain_problem(n_layers, C, seed=n_layers * 100 + C)
+    want = viterbi_chain(p["tc"], p["ts"], p["tx"])
+    for schedule in (oracle.SCHEDULE_ROUNDS, oracle.SCHEDULE_LEFT_FOLD):
+        r = oracle.search(n_layers, p["edges"], C, p["tc"], p["ts"], p["tx"], schedule)
+        assert r["cost"] == want
+        assert oracle.strategy_cost(n_layers, p["edges"], C, p["tc"], p["ts"], p["tx"], r["strategy"]) == want
+
+
+def test_schedule_shapes():
+    p = wl.chain_problem(6, 4, 1)
+    r = oracle.search(6, p["edges"], 4, p["tc"], p["ts"], p["tx"], oracle.SCHEDULE_ROUNDS)
+    assert [(s["j"], s["round"]) for s in r["steps"]] == [(1, 0), (3, 0), (2, 1), (4, 2)]
+    r = oracle.search(6, p["edges"], 4, p["tc"], p["ts"], p["tx"], oracle.SCHEDULE_LEFT_FOLD)
+    assert [(s["j"], s["i"], s["k"]) for s in r["steps"]] == [(1, 0, 2), (2, 0, 3), (3, 0, 4), (4, 0, 5)]
+
+
+def test_forkjoin_full_topology_counts():
+    n_nodes, edges = wl.forkjoin_edges(10, 2)
+    assert n_nodes == 120 and len(edges) == 189
+    C = 2
+    tc, ts, tx = wl.random_tables(n_nodes, edges, C, 9, (1, 9), (1, 9), (1, 9))
+    r = oracle.search(n_nodes, edges, C, tc, ts, tx)
+    kinds = [int(s["kind"]) for s in r["steps"]]
+    assert kinds.count(0) == 118 and kinds.count(1) == 70
+    assert len(r["steps"]) == 189 - 1
+    assert oracle.strategy_cost(n_nodes, edges, C, tc, ts, tx, r["strategy"]) == r["cost"]
+    r2 = oracle.search(n_nodes, edges, C, tc, ts, tx, oracle.SCHEDULE_LEFT_FOLD)
+    assert r2["cost"] == r["cost"]
+
+
+def test_not_reducible_graph_is_reported():
+    # node 0 feeds three nodes that never rejoin: the residual graph is a star
+    edges = np.array([[0, 1], [0, 2], [0, 3]], np.int32)
+    tc, ts, tx = rand_problem(np.random.default_rng(0), 4, edges, 2, 5)
+    with pytest.raises(oracle.OracleError) as e:
+        oracle.search(4, edges, 2, tc, ts, tx)
+    assert e.value.code == oracle.E_NOT_REDUCIBLE
