@@ -1,0 +1,171 @@
+/*
+ * lwp.h -- C ABI of the layer-wise-parallelism strategy search for one AMD MI355X (gfx950).
+ *
+ * The library finds, for a computation graph whose nodes are layers and whose edges are
+ * tensors, one parallelization configuration per layer minimising the cost model of the
+ * paper (Sec. 5.1, Eq. 1) with the graph search of Sec. 5.2 (Alg. 1): node eliminations
+ * (Eq. 2), edge eliminations (Eq. 3), solution of the small residual graph and undoing the
+ * eliminations in reverse order.
+ *
+ * Conventions
+ *   - All costs are int32 nanoseconds.  Sums are exact; every minimum takes the LOWEST index
+ *     among equal candidates.  A sum that could leave int32 is refused (LWP_E_OVERFLOW).
+ *   - A cost table of an edge e = (l_i, l_j) is row-major [cfg of l_i][cfg of l_j].
+ *   - "DEVICE" pointers are HIP device memory on the context's device, owned by the caller;
+ *     the library never frees or keeps them.  "HOST" pointers are ordinary host memory.
+ *   - Every kernel is enqueued on the context's stream.  lwp_eliminate_edge only enqueues;
+ *     lwp_eliminate_node synchronises once (it reads back value ranges before it picks a
+ *     kernel variant) and then enqueues; lwp_search_graph and lwp_build_cost_tables return
+ *     after the stream has drained.
+ *   - Errors are return codes; on error the outputs are untouched unless stated.  Argument
+ *     and graph validation happen before any GPU work.  lwp_last_error gives the reason.
+ *   - A context must not be used from two threads at once.
+ */
+#ifndef LWP_H
+#define LWP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct lwp_ctx lwp_ctx;
+
+typedef enum {
+    LWP_OK = 0,
+    LWP_E_INVAL = -1,          /* null pointer, non-positive size, misaligned pointer        */
+    LWP_E_GRAPH = -2,          /* endpoint out of range, self loop, cycle                    */
+    LWP_E_NOT_REDUCIBLE = -3,  /* residual graph is not isolated nodes + single-edge pairs   */
+    LWP_E_OVERFLOW = -4,       /* value ranges do not guarantee that every sum fits int32    */
+    LWP_E_NOMEM = -5,          /* device or host allocation failed                           */
+    LWP_E_HIP = -6             /* a HIP runtime call failed                                  */
+} lwp_status;
+
+/* Order of eliminations (the paper leaves the choice open, Alg. 2 "if there exists ...").
+ * Every round first merges all parallel edges (E-phase), then eliminates nodes (N-phase):
+ *   LWP_SCHEDULE_ROUNDS     scan nodes in ascending id, take every eligible node none of whose
+ *                           two neighbours was taken in this round; all taken nodes are
+ *                           eliminated by one batched launch;
+ *   LWP_SCHEDULE_LEFT_FOLD  take only the lowest-id eligible node per round. */
+typedef enum { LWP_SCHEDULE_ROUNDS = 0, LWP_SCHEDULE_LEFT_FOLD = 1 } lwp_schedule;
+
+/* ---- context --------------------------------------------------------------------------- */
+
+/* Creates a context bound to HIP device `device` and stream `hip_stream` (a hipStream_t cast
+ * to void*, NULL = the default stream).  The context owns a device workspace that grows on
+ * demand and is released by lwp_destroy. */
+lwp_status lwp_create(lwp_ctx **out, int device, void *hip_stream);
+void lwp_destroy(lwp_ctx *ctx);
+/* Human-readable reason of the last failure on ctx; valid until the next call on ctx. */
+const char *lwp_last_error(const lwp_ctx *ctx);
+const char *lwp_status_string(lwp_status s);
+/* Blocks until the context's stream has drained. */
+lwp_status lwp_synchronize(lwp_ctx *ctx);
+
+/* ---- node elimination (Sec. 5.2, Eq. 2; argmin of Thm. 3 in the appendix) ---------------- */
+
+/* For every b in [0,batch):
+ *   out[b][a][k] = min_c ( A[b][a][c] + w[b][c] + B[b][c][k] ),  argmin[b][a][k] = lowest such c
+ * A = table of the in-edge (l_i,l_j), w = t_c(l_j,.) + t_s(l_j,.), B = table of the out-edge.
+ * DEVICE, dense, row-major: A [batch][Ci][Cj], w [batch][Cj], B [batch][Cj][Ck],
+ * out [batch][Ci][Ck], argmin [batch][Ci][Ck] (may be NULL).  out/argmin must not overlap the
+ * inputs.  Sizes: batch, Ci, Cj, Ck >= 1, Cj <= 65536.
+ * The call measures the value ranges of A, w, B on the device (one small synchronising
+ * read-back), returns LWP_E_OVERFLOW if max A + max w + max B (or the minima) could leave
+ * int32, then enqueues the product kernel and returns. */
+lwp_status lwp_eliminate_node(lwp_ctx *ctx, int32_t batch, int32_t Ci, int32_t Cj, int32_t Ck,
+                              const int32_t *d_A, const int32_t *d_w, const int32_t *d_B,
+                              int32_t *d_out, int32_t *d_argmin);
+
+/* ---- edge elimination (Sec. 5.2, Eq. 3) -------------------------------------------------- */
+
+/* out[b][i][j] = e1[b][i][j] + e2[b][i][j] (wrapping int32 add; the caller guarantees the
+ * range).  DEVICE, dense [batch][Ci][Cj]; out may alias e1 or e2.  Enqueues and returns. */
+lwp_status lwp_eliminate_edge(lwp_ctx *ctx, int32_t batch, int32_t Ci, int32_t Cj,
+                              const int32_t *d_e1, const int32_t *d_e2, int32_t *d_out);
+
+/* ---- whole search (Sec. 5.2, Alg. 1) ----------------------------------------------------- */
+
+/* One entry of the elimination log, in execution order.
+ * kind 0: node elimination of node j between i and k; in-edge e1 = (i,j), out-edge e2 = (j,k);
+ *         the new edge (i,k) keeps the id e1.
+ * kind 1: edge elimination; edge e2 is added into e1 (both (i,k)); the sum keeps the id e1; j = -1.
+ * round: index of the schedule round the step belongs to. */
+typedef struct { int32_t kind, j, i, k, e1, e2, round; } lwp_step;
+
+/* Host-only: computes the elimination schedule of a graph (no GPU, no context).
+ * edges: HOST [n_edges][2] = (src, dst), node ids in [0,n_nodes), parallel edges allowed.
+ * steps: HOST, room for max(n_edges,1) entries, may be NULL.  n_steps / n_rounds / n_residual_nodes
+ * may be NULL.  Returns LWP_E_GRAPH for a bad endpoint, self loop or cycle and
+ * LWP_E_NOT_REDUCIBLE if the residual graph has a node with more than one incident edge. */
+lwp_status lwp_plan_graph(int32_t n_nodes, int32_t n_edges, const int32_t *edges, int32_t schedule,
+                          lwp_step *steps, int32_t *n_steps, int32_t *n_rounds,
+                          int32_t *n_residual_nodes);
+
+/* Finds a strategy minimising Eq. 1.
+ * edges HOST [n_edges][2]; every node has C configurations (1 <= C <= 65536).
+ * d_tc, d_ts DEVICE [n_nodes][C]; d_tx DEVICE [n_edges][C][C]; read-only.
+ * out_cost HOST int32: t_o of the returned strategy; out_strategy HOST [n_nodes]: configuration
+ * index per node.  Among optimal strategies the one produced by the schedule and the
+ * lowest-index rule is returned.  Blocking. */
+lwp_status lwp_search_graph(lwp_ctx *ctx, int32_t n_nodes, int32_t n_edges, const int32_t *edges,
+                            int32_t C, const int32_t *d_tc, const int32_t *d_ts, const int32_t *d_tx,
+                            int32_t schedule, int32_t *out_cost, int32_t *out_strategy);
+
+/* Host-only: bytes of device workspace lwp_search_graph needs for this graph (0 on a graph it
+ * would refuse). */
+size_t lwp_search_workspace_bytes(int32_t n_nodes, int32_t n_edges, const int32_t *edges, int32_t C,
+                                  int32_t schedule);
+
+/* ---- cost tables (Sec. 5.1: t_c, t_s, t_x) ----------------------------------------------- */
+
+/* One layer: kind 0 = 2D convolution, 1 = 2D pooling, 2 = fully connected.  N = batch size;
+ * input tensor N x Cin x Hin x Win, output N x Cout x Hout x Wout; kernel kh x kw, stride
+ * sh x sw, padding ph x pw.  A fully connected layer reads its whole input per sample. */
+typedef struct {
+    int32_t kind, N, Cin, Hin, Win, Cout, Hout, Wout, kh, kw, sh, sw, ph, pw;
+} lwp_layer;
+/* One configuration (Sec. 4): degrees of parallelism in the sample, height, width and channel
+ * dimensions of the layer's OUTPUT tensor; its n*h*w*c equal parts are placed on the devices
+ * dev_offset, dev_offset+1, ... in the order ((i_n*h + i_h)*w + i_w)*c + i_c.  n == 0 marks a
+ * padding row that is invalid for every layer. */
+typedef struct { int32_t n, h, w, c, dev_offset, pad; } lwp_config;
+typedef struct {
+    int32_t n_devices;
+    int32_t flop_per_ns;    /* per-device compute rate           */
+    int32_t byte_per_ns;    /* bandwidth of every device link    */
+    int32_t invalid_cost;   /* t_c of a configuration a layer cannot use */
+} lwp_machine;
+
+/* Evaluates the analytic cost model for every layer and configuration (pair).
+ * layers HOST [n_layers]; edges HOST [n_edges][2]; cfgs HOST [C]; outputs DEVICE
+ * d_tc, d_ts [n_layers][C], d_tx [n_edges][C][C].  Blocking. */
+lwp_status lwp_build_cost_tables(lwp_ctx *ctx, const lwp_layer *layers, int32_t n_layers,
+                                 const int32_t *edges, int32_t n_edges, const lwp_config *cfgs,
+                                 int32_t C, const lwp_machine *machine,
+                                 int32_t *d_tc, int32_t *d_ts, int32_t *d_tx);
+
+/* ---- measurement ------------------------------------------------------------------------- */
+
+/* Accumulated since the last lwp_profile_reset while profiling is on: every node-elimination
+ * launch is bracketed by HIP events on the context's stream. */
+typedef struct {
+    int64_t node_launches;     /* min-plus kernel launches                         */
+    int64_t node_cell_updates; /* sum of batch*Ci*Cj*Ck over those launches        */
+    double node_ms;            /* sum of their durations (HIP events)              */
+    int64_t edge_launches;
+    int64_t edge_cells;
+    double edge_ms;
+    int64_t keyed_launches;    /* node launches that used the packed-key variant   */
+} lwp_profile;
+lwp_status lwp_profile_enable(lwp_ctx *ctx, int32_t on);
+lwp_status lwp_profile_reset(lwp_ctx *ctx);
+/* Synchronises the stream, then fills *out. */
+lwp_status lwp_profile_read(lwp_ctx *ctx, lwp_profile *out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LWP_H */

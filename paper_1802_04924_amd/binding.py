@@ -1,0 +1,229 @@
+"""Thin ctypes binding of liblwp.so (the C ABI in include/lwp.h).
+
+Argument marshalling only: every step of the search runs inside the library's
+HIP kernels.  PyTorch supplies device memory (int32 CUDA tensors) and the
+stream handle, nothing else.  There is no CPU fallback: if the library is not
+built, or no GPU is present, calls fail loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblwp.so")
+
+OK, E_INVAL, E_GRAPH, E_NOT_REDUCIBLE, E_OVERFLOW, E_NOMEM, E_HIP = 0, -1, -2, -3, -4, -5, -6
+SCHEDULE_ROUNDS, SCHEDULE_LEFT_FOLD = 0, 1
+
+EXPORTED = [
+    "lwp_create", "lwp_destroy", "lwp_last_error", "lwp_status_string", "lwp_synchronize",
+    "lwp_eliminate_node", "lwp_eliminate_edge", "lwp_plan_graph", "lwp_search_graph",
+    "lwp_search_workspace_bytes", "lwp_build_cost_tables",
+    "lwp_profile_enable", "lwp_profile_reset", "lwp_profile_read",
+]
+
+STEP_DTYPE = np.dtype([("kind", "<i4"), ("j", "<i4"), ("i", "<i4"), ("k", "<i4"),
+                       ("e1", "<i4"), ("e2", "<i4"), ("round", "<i4")])
+LAYER_DTYPE = np.dtype([(n, "<i4") for n in ("kind", "N", "Cin", "Hin", "Win", "Cout", "Hout", "Wout",
+                                             "kh", "kw", "sh", "sw", "ph", "pw")])
+CONFIG_DTYPE = np.dtype([(n, "<i4") for n in ("n", "h", "w", "c", "dev_offset", "pad")])
+MACHINE_DTYPE = np.dtype([(n, "<i4") for n in ("n_devices", "flop_per_ns", "byte_per_ns", "invalid_cost")])
+
+
+class Profile(ctypes.Structure):
+    _fields_ = [("node_launches", ctypes.c_int64), ("node_cell_updates", ctypes.c_int64),
+                ("node_ms", ctypes.c_double), ("edge_launches", ctypes.c_int64),
+                ("edge_cells", ctypes.c_int64), ("edge_ms", ctypes.c_double),
+                ("keyed_launches", ctypes.c_int64)]
+
+
+class LwpError(RuntimeError):
+    def __init__(self, code, what, detail=""):
+        super().__init__(f"{what}: status {code}" + (f" ({detail})" if detail else ""))
+        self.code = code
+
+
+_lib = None
+
+
+def load():
+    """Loads liblwp.so; raises if it has not been built (no fallback)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_1802_04924_amd.build` "
+                           "(or __graft_entry__.build()) first")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i32p = ctypes.c_void_p, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)
+    lib.lwp_create.argtypes = [ctypes.POINTER(vp), ctypes.c_int, vp]
+    lib.lwp_destroy.argtypes = [vp]
+    lib.lwp_destroy.restype = None
+    lib.lwp_last_error.argtypes = [vp]
+    lib.lwp_last_error.restype = ctypes.c_char_p
+    lib.lwp_status_string.argtypes = [ctypes.c_int]
+    lib.lwp_status_string.restype = ctypes.c_char_p
+    lib.lwp_synchronize.argtypes = [vp]
+    lib.lwp_eliminate_node.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp, vp]
+    lib.lwp_eliminate_edge.argtypes = [vp, i32, i32, i32, vp, vp, vp]
+    lib.lwp_plan_graph.argtypes = [i32, i32, vp, i32, vp, i32p, i32p, i32p]
+    lib.lwp_search_graph.argtypes = [vp, i32, i32, vp, i32, vp, vp, vp, i32, i32p, vp]
+    lib.lwp_search_workspace_bytes.argtypes = [i32, i32, vp, i32, i32]
+    lib.lwp_search_workspace_bytes.restype = ctypes.c_size_t
+    lib.lwp_build_cost_tables.argtypes = [vp, vp, i32, vp, i32, vp, i32, vp, vp, vp, vp]
+    lib.lwp_profile_enable.argtypes = [vp, i32]
+    lib.lwp_profile_reset.argtypes = [vp]
+    lib.lwp_profile_read.argtypes = [vp, ctypes.POINTER(Profile)]
+    _lib = lib
+    return lib
+
+
+def _np_i32(a, shape=None):
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    if shape is not None:
+        a = a.reshape(shape)
+    return a
+
+
+def plan_graph(n_nodes, edges, schedule=SCHEDULE_ROUNDS):
+    """Host-only elimination schedule: dict(steps, n_rounds, n_residual_nodes)."""
+    lib = load()
+    edges = _np_i32(edges, (-1, 2))
+    steps = np.zeros(max(len(edges), 1), STEP_DTYPE)
+    ns, nr, nk = ctypes.c_int32(0), ctypes.c_int32(0), ctypes.c_int32(0)
+    rc = lib.lwp_plan_graph(n_nodes, len(edges), edges.ctypes.data, int(schedule), steps.ctypes.data,
+                            ctypes.byref(ns), ctypes.byref(nr), ctypes.byref(nk))
+    if rc:
+        raise LwpError(rc, "plan_graph", lib.lwp_status_string(rc).decode())
+    return {"steps": steps[:ns.value], "n_rounds": nr.value, "n_residual_nodes": nk.value}
+
+
+def search_workspace_bytes(n_nodes, edges, C, schedule=SCHEDULE_ROUNDS) -> int:
+    lib = load()
+    edges = _np_i32(edges, (-1, 2))
+    return int(lib.lwp_search_workspace_bytes(n_nodes, len(edges), edges.ctypes.data, C, int(schedule)))
+
+
+def _dev(t, what):
+    import torch
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.int32 and t.is_contiguous()):
+        raise TypeError(f"{what} must be a contiguous int32 CUDA tensor")
+    return t.data_ptr()
+
+
+class Context:
+    """Owns one lwp_ctx bound to a device and to torch's current stream on it."""
+
+    def __init__(self, device: int = 0, stream=None):
+        import torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("no GPU visible: the strategy search has no CPU path")
+        self._lib = load()
+        self.device = int(device)
+        with torch.cuda.device(self.device):
+            self._stream = stream if stream is not None else torch.cuda.current_stream()
+        h = ctypes.c_void_p()
+        rc = self._lib.lwp_create(ctypes.byref(h), self.device, ctypes.c_void_p(self._stream.cuda_stream))
+        if rc:
+            raise LwpError(rc, "lwp_create")
+        self._h = h
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self._lib.lwp_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    def _check(self, rc, what):
+        if rc:
+            raise LwpError(rc, what, self._lib.lwp_last_error(self._h).decode())
+
+    def synchronize(self):
+        self._check(self._lib.lwp_synchronize(self._h), "synchronize")
+
+    # ---- Eq. 2 -------------------------------------------------------------
+    def eliminate_node(self, A, w, B, out=None, argmin=None, want_argmin=True):
+        """A [batch][Ci][Cj], w [batch][Cj], B [batch][Cj][Ck] -> (out, argmin) [batch][Ci][Ck]."""
+        import torch
+        if A.dim() == 2:
+            A, w, B = A[None], w[None], B[None]
+        batch, Ci, Cj = A.shape
+        Ck = B.shape[2]
+        if tuple(B.shape) != (batch, Cj, Ck) or tuple(w.shape) != (batch, Cj):
+            raise ValueError("shape mismatch between A, w and B")
+        if out is None:
+            out = torch.empty((batch, Ci, Ck), dtype=torch.int32, device=A.device)
+        if argmin is None and want_argmin:
+            argmin = torch.empty((batch, Ci, Ck), dtype=torch.int32, device=A.device)
+        rc = self._lib.lwp_eliminate_node(self._h, batch, Ci, Cj, Ck, _dev(A, "A"), _dev(w, "w"), _dev(B, "B"),
+                                          _dev(out, "out"), _dev(argmin, "argmin") if argmin is not None else None)
+        self._check(rc, "eliminate_node")
+        return out, argmin
+
+    # ---- Eq. 3 -------------------------------------------------------------
+    def eliminate_edge(self, e1, e2, out=None):
+        import torch
+        if e1.shape != e2.shape:
+            raise ValueError("shape mismatch")
+        shp = e1.shape if e1.dim() == 3 else (1,) + tuple(e1.shape)
+        if out is None:
+            out = torch.empty_like(e1)
+        rc = self._lib.lwp_eliminate_edge(self._h, shp[0], shp[1], shp[2], _dev(e1, "e1"), _dev(e2, "e2"), _dev(out, "out"))
+        self._check(rc, "eliminate_edge")
+        return out
+
+    # ---- Alg. 1 ------------------------------------------------------------
+    def search_graph(self, n_nodes, edges, C, tc, ts, tx, schedule=SCHEDULE_ROUNDS):
+        """Returns (cost, strategy[n_nodes]) with tables resident on the device."""
+        edges = _np_i32(edges, (-1, 2))
+        E = len(edges)
+        if tuple(tc.shape) != (n_nodes, C) or tuple(ts.shape) != (n_nodes, C):
+            raise ValueError("t_c / t_s must be [n_nodes][C]")
+        if E and tuple(tx.shape) != (E, C, C):
+            raise ValueError("t_x must be [n_edges][C][C]")
+        cost = ctypes.c_int32(0)
+        S = np.empty(n_nodes, np.int32)
+        rc = self._lib.lwp_search_graph(self._h, n_nodes, E, edges.ctypes.data, C, _dev(tc, "tc"), _dev(ts, "ts"),
+                                        _dev(tx, "tx") if E else None, int(schedule), ctypes.byref(cost), S.ctypes.data)
+        self._check(rc, "search_graph")
+        return cost.value, S
+
+    # ---- Sec. 5.1 ----------------------------------------------------------
+    def build_cost_tables(self, layers, edges, configs, machine):
+        """layers int32 [L][14], edges [E][2], configs int32 [C][6], machine dict -> (tc, ts, tx) on device."""
+        import torch
+        layers = _np_i32(layers, (-1, 14))
+        edges = _np_i32(edges, (-1, 2))
+        configs = _np_i32(configs, (-1, 6))
+        m = np.array([machine["n_devices"], machine["flop_per_ns"], machine["byte_per_ns"], machine["invalid_cost"]], np.int32)
+        L, E, C = len(layers), len(edges), len(configs)
+        dev = torch.device("cuda", self.device)
+        tc = torch.empty((L, C), dtype=torch.int32, device=dev)
+        ts = torch.empty((L, C), dtype=torch.int32, device=dev)
+        tx = torch.empty((E, C, C), dtype=torch.int32, device=dev)
+        rc = self._lib.lwp_build_cost_tables(self._h, layers.ctypes.data, L, edges.ctypes.data, E, configs.ctypes.data, C,
+                                             m.ctypes.data, _dev(tc, "tc"), _dev(ts, "ts"), _dev(tx, "tx") if E else None)
+        self._check(rc, "build_cost_tables")
+        return tc, ts, tx
+
+    # ---- measurement -------------------------------------------------------
+    def profile_enable(self, on=True):
+        self._check(self._lib.lwp_profile_enable(self._h, 1 if on else 0), "profile_enable")
+
+    def profile_reset(self):
+        self._check(self._lib.lwp_profile_reset(self._h), "profile_reset")
+
+    def profile_read(self) -> dict:
+        p = Profile()
+        self._check(self._lib.lwp_profile_read(self._h, ctypes.byref(p)), "profile_read")
+        return {f: getattr(p, f) for f, _ in Profile._fields_}

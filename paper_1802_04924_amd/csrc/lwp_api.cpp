@@ -1,0 +1,528 @@
+// C ABI of the strategy search: argument validation, value-range analysis, buffer planning and
+// the launch sequence of Alg. 1 (eliminate -> solve the residual graph -> undo).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "lwp.h"
+#include "lwp_kernels.h"
+#include "lwp_plan.h"
+
+using namespace lwp;
+
+struct lwp_ctx {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    std::string err;
+    char* ws = nullptr;        // device workspace
+    size_t ws_bytes = 0;
+    bool profiling = false;
+    struct Timed { hipEvent_t a, b; int kind; int64_t work; bool keyed; };
+    std::vector<Timed> timed;
+    lwp_profile prof{};
+};
+
+namespace {
+
+constexpr int64_t kI32Max = 2147483647LL, kI32Min = -2147483648LL;
+constexpr int kMaxConfigs = 65536;
+
+lwp_status fail(lwp_ctx* ctx, lwp_status s, const std::string& why) {
+    if (ctx) ctx->err = why;
+    return s;
+}
+
+#define LWP_HIP(ctx, call)                                                                     \
+    do {                                                                                       \
+        hipError_t e_ = (call);                                                                \
+        if (e_ != hipSuccess)                                                                  \
+            return fail(ctx, e_ == hipErrorOutOfMemory ? LWP_E_NOMEM : LWP_E_HIP,              \
+                        std::string(#call) + ": " + hipGetErrorString(e_));                    \
+    } while (0)
+
+size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+lwp_status ensure_workspace(lwp_ctx* ctx, size_t bytes) {
+    if (bytes <= ctx->ws_bytes) return LWP_OK;
+    LWP_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    if (ctx->ws) { LWP_HIP(ctx, hipFree(ctx->ws)); ctx->ws = nullptr; ctx->ws_bytes = 0; }
+    void* p = nullptr;
+    hipError_t e = hipMalloc(&p, bytes);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(ctx, LWP_E_NOMEM, "device workspace of " + std::to_string(bytes) + " bytes: " + hipGetErrorString(e));
+    }
+    ctx->ws = static_cast<char*>(p);
+    ctx->ws_bytes = bytes;
+    return LWP_OK;
+}
+
+struct Range { int64_t lo, hi; };
+bool fits(int64_t v) { return v >= kI32Min && v <= kI32Max; }
+
+// Picks the key width for one product from the ranges of A + w and B (see minplus.hip).
+// Returns 0 when the packed-key arithmetic does not apply.
+int choose_tb(int64_t spread, int32_t Cj) {
+    int tb_max = 0;
+    for (int tb = 17; tb >= 5; --tb)
+        if (spread <= (1LL << (32 - tb)) - 2) { tb_max = tb; break; }
+    if (!tb_max) return 0;
+    int tb_single = 17;
+    for (int tb = 5; tb <= 17; ++tb)
+        if ((((1 << tb) - 1) / 16) * 16 >= Cj) { tb_single = tb; break; }
+    return std::min(tb_max, tb_single);
+}
+
+// Timing of one launch when profiling is on.
+struct ScopedTimer {
+    lwp_ctx* ctx; size_t idx = (size_t)-1;
+    ScopedTimer(lwp_ctx* c, int kind, int64_t work, bool keyed) : ctx(c) {
+        if (!c->profiling) return;
+        lwp_ctx::Timed t{nullptr, nullptr, kind, work, keyed};
+        if (hipEventCreate(&t.a) != hipSuccess || hipEventCreate(&t.b) != hipSuccess) return;
+        hipEventRecord(t.a, c->stream);
+        c->timed.push_back(t);
+        idx = c->timed.size() - 1;
+    }
+    ~ScopedTimer() { if (idx != (size_t)-1) hipEventRecord(ctx->timed[idx].b, ctx->stream); }
+};
+
+lwp_status drain_profile(lwp_ctx* ctx) {
+    LWP_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    for (auto& t : ctx->timed) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, t.a, t.b) == hipSuccess) {
+            if (t.kind == 0) {
+                ctx->prof.node_launches++; ctx->prof.node_cell_updates += t.work; ctx->prof.node_ms += ms;
+                if (t.keyed) ctx->prof.keyed_launches++;
+            } else {
+                ctx->prof.edge_launches++; ctx->prof.edge_cells += t.work; ctx->prof.edge_ms += ms;
+            }
+        }
+        hipEventDestroy(t.a); hipEventDestroy(t.b);
+    }
+    ctx->timed.clear();
+    return LWP_OK;
+}
+
+lwp_status check_ctx(lwp_ctx* ctx) {
+    if (!ctx) return LWP_E_INVAL;
+    ctx->err.clear();
+    hipError_t e = hipSetDevice(ctx->device);
+    if (e != hipSuccess) return fail(ctx, LWP_E_HIP, std::string("hipSetDevice: ") + hipGetErrorString(e));
+    return LWP_OK;
+}
+
+// ---- buffer planning of a whole search ---------------------------------------------------------
+// Tables produced by eliminations live in equally sized slots; a slot is released once the step
+// that consumed it has been enqueued (launches of one stream run in order).
+struct TableRef { bool is_slot; int32_t id; };   // input edge table id, or slot id
+
+struct EdgeGroup { int32_t keep; std::vector<int32_t> others; int32_t round; };
+
+struct Layout {
+    std::vector<EdgeGroup> groups;            // edge eliminations grouped per (round, kept edge)
+    std::vector<TableRef> node_A, node_B;     // per node step (in plan order)
+    std::vector<int32_t> node_out_slot;
+    std::vector<std::vector<TableRef>> group_src;
+    std::vector<int32_t> group_out_slot;
+    std::vector<TableRef> final_table;        // per residual pair
+    int32_t n_slots = 0;
+};
+
+Layout plan_buffers(const Plan& plan, int32_t n_edges) {
+    Layout L;
+    std::vector<TableRef> cur(n_edges);
+    for (int32_t e = 0; e < n_edges; ++e) cur[e] = {false, e};
+    std::vector<int32_t> free_slots;
+    auto take = [&]() {
+        if (!free_slots.empty()) { int32_t s = free_slots.back(); free_slots.pop_back(); return s; }
+        return L.n_slots++;
+    };
+    size_t t = 0;
+    const size_t n = plan.steps.size();
+    while (t < n) {
+        const int32_t round = plan.steps[t].round;
+        // E-phase of this round
+        std::vector<int32_t> release;
+        while (t < n && plan.steps[t].round == round && plan.steps[t].kind == 1) {
+            EdgeGroup g{plan.steps[t].e1, {}, round};
+            while (t < n && plan.steps[t].round == round && plan.steps[t].kind == 1 && plan.steps[t].e1 == g.keep) {
+                g.others.push_back(plan.steps[t].e2);
+                ++t;
+            }
+            std::vector<TableRef> src{cur[g.keep]};
+            for (int32_t o : g.others) { src.push_back(cur[o]); if (cur[o].is_slot) release.push_back(cur[o].id); }
+            const int32_t out = cur[g.keep].is_slot ? cur[g.keep].id : take();   // in place when possible
+            cur[g.keep] = {true, out};
+            L.groups.push_back(g); L.group_src.push_back(src); L.group_out_slot.push_back(out);
+        }
+        for (int32_t s : release) free_slots.push_back(s);
+        release.clear();
+        // N-phase of this round
+        while (t < n && plan.steps[t].round == round && plan.steps[t].kind == 0) {
+            const lwp_step& st = plan.steps[t];
+            L.node_A.push_back(cur[st.e1]); L.node_B.push_back(cur[st.e2]);
+            if (cur[st.e1].is_slot) release.push_back(cur[st.e1].id);
+            if (cur[st.e2].is_slot) release.push_back(cur[st.e2].id);
+            const int32_t out = take();
+            L.node_out_slot.push_back(out);
+            cur[st.e1] = {true, out};
+            ++t;
+        }
+        for (int32_t s : release) free_slots.push_back(s);
+    }
+    for (auto& p : plan.pairs) L.final_table.push_back(cur[p.edge]);
+    return L;
+}
+
+struct WsLayout {
+    size_t w, stats, flag, node_desc, edge_desc, src_ptrs, pair_desc, singles, undo, keys, result, args, slots, total;
+};
+
+WsLayout layout_workspace(const Plan& plan, const Layout& L, int32_t n_nodes, int32_t n_edges, int32_t C) {
+    WsLayout o{};
+    size_t off = 0;
+    auto put = [&](size_t bytes) { size_t at = off; off = align_up(off + bytes, 256); return at; };
+    const size_t CC = (size_t)C * C * sizeof(int32_t);
+    size_t n_src = 0;
+    for (auto& g : L.group_src) n_src += g.size();
+    o.w = put((size_t)n_nodes * C * sizeof(int32_t));
+    o.stats = put(2 * (size_t)(n_edges + n_nodes) * sizeof(int32_t));
+    o.flag = put(sizeof(int32_t));
+    o.node_desc = put(std::max<size_t>(1, plan.n_node_steps) * sizeof(NodeDesc));
+    o.edge_desc = put(std::max<size_t>(1, L.groups.size()) * sizeof(EdgeDesc));
+    o.src_ptrs = put(std::max<size_t>(1, n_src) * sizeof(void*));
+    o.pair_desc = put(std::max<size_t>(1, plan.pairs.size()) * sizeof(PairDesc));
+    o.singles = put(std::max<size_t>(1, plan.singles.size()) * sizeof(int32_t));
+    o.undo = put(std::max<size_t>(1, plan.n_node_steps) * sizeof(UndoDesc));
+    o.keys = put(std::max<size_t>(1, plan.pairs.size() + plan.singles.size()) * sizeof(unsigned long long));
+    o.result = put((2 + (size_t)n_nodes) * sizeof(int32_t));
+    o.args = put((size_t)plan.n_node_steps * CC);
+    o.slots = put((size_t)L.n_slots * CC);
+    o.total = off;
+    return o;
+}
+
+}  // namespace
+
+// ================================================================================================
+extern "C" {
+
+const char* lwp_status_string(lwp_status s) {
+    switch (s) {
+        case LWP_OK: return "ok";
+        case LWP_E_INVAL: return "invalid argument";
+        case LWP_E_GRAPH: return "invalid graph";
+        case LWP_E_NOT_REDUCIBLE: return "graph not reducible";
+        case LWP_E_OVERFLOW: return "int32 overflow possible";
+        case LWP_E_NOMEM: return "out of memory";
+        case LWP_E_HIP: return "HIP error";
+    }
+    return "unknown status";
+}
+
+lwp_status lwp_create(lwp_ctx** out, int device, void* hip_stream) {
+    if (!out) return LWP_E_INVAL;
+    *out = nullptr;
+    int n = 0;
+    if (hipGetDeviceCount(&n) != hipSuccess || device < 0 || device >= n) return LWP_E_HIP;
+    if (hipSetDevice(device) != hipSuccess) return LWP_E_HIP;
+    lwp_ctx* c = new (std::nothrow) lwp_ctx();
+    if (!c) return LWP_E_NOMEM;
+    c->device = device;
+    c->stream = static_cast<hipStream_t>(hip_stream);
+    *out = c;
+    return LWP_OK;
+}
+
+void lwp_destroy(lwp_ctx* ctx) {
+    if (!ctx) return;
+    (void)hipSetDevice(ctx->device);
+    (void)hipStreamSynchronize(ctx->stream);
+    for (auto& t : ctx->timed) { hipEventDestroy(t.a); hipEventDestroy(t.b); }
+    if (ctx->ws) (void)hipFree(ctx->ws);
+    delete ctx;
+}
+
+const char* lwp_last_error(const lwp_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+lwp_status lwp_synchronize(lwp_ctx* ctx) {
+    if (lwp_status s = check_ctx(ctx)) return s;
+    LWP_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    return LWP_OK;
+}
+
+lwp_status lwp_profile_enable(lwp_ctx* ctx, int32_t on) {
+    if (lwp_status s = check_ctx(ctx)) return s;
+    ctx->profiling = on != 0;
+    return LWP_OK;
+}
+
+lwp_status lwp_profile_reset(lwp_ctx* ctx) {
+    if (lwp_status s = check_ctx(ctx)) return s;
+    if (lwp_status s = drain_profile(ctx)) return s;
+    ctx->prof = lwp_profile{};
+    return LWP_OK;
+}
+
+lwp_status lwp_profile_read(lwp_ctx* ctx, lwp_profile* out) {
+    if (lwp_status s = check_ctx(ctx)) return s;
+    if (!out) return fail(ctx, LWP_E_INVAL, "null output");
+    if (lwp_status s = drain_profile(ctx)) return s;
+    *out = ctx->prof;
+    return LWP_OK;
+}
+
+// ---- Eq. 2 -------------------------------------------------------------------------------------
+lwp_status lwp_eliminate_node(lwp_ctx* ctx, int32_t batch, int32_t Ci, int32_t Cj, int32_t Ck,
+                              const int32_t* d_A, const int32_t* d_w, const int32_t* d_B,
+                              int32_t* d_out, int32_t* d_argmin) {
+    if (lwp_status s = check_ctx(ctx)) return s;
+    if (batch < 1 || Ci < 1 || Cj < 1 || Ck < 1) return fail(ctx, LWP_E_INVAL, "sizes must be positive");
+    if (Cj > kMaxConfigs) return fail(ctx, LWP_E_INVAL, "Cj exceeds 65536");
+    if (!d_A || !d_w || !d_B || !d_out) return fail(ctx, LWP_E_INVAL, "null table pointer");
+    if (((uintptr_t)d_A | (uintptr_t)d_w | (uintptr_t)d_B | (uintptr_t)d_out | (uintptr_t)d_argmin) & 3)
+        return fail(ctx, LWP_E_INVAL, "table pointer not 4-byte aligned");
+    const int64_t tilesM = (Ci + kTileM - 1) / kTileM, tilesN = (Ck + kTileN - 1) / kTileN;
+    if (tilesM * tilesN * batch > 0x7fffffffLL) return fail(ctx, LWP_E_INVAL, "too many output tiles");
+
+    // value ranges of A, w, B over the whole batch
+    if (lwp_status s = ensure_workspace(ctx, 4096)) return s;
+    int32_t* d_stats = reinterpret_cast<int32_t*>(ctx->ws);
+    LWP_HIP(ctx, launch_init_ranges(d_stats, 3, ctx->stream));
+    LWP_HIP(ctx, launch_ranges(d_A, 1, (int64_t)batch * Ci * Cj, d_stats, ctx->stream));
+    LWP_HIP(ctx, launch_ranges(d_w, 1, (int64_t)batch * Cj, d_stats + 2, ctx->stream));
+    LWP_HIP(ctx, launch_ranges(d_B, 1, (int64_t)batch * Cj * Ck, d_stats + 4, ctx->stream));
+    int32_t st[6];
+    LWP_HIP(ctx, hipMemcpyAsync(st, d_stats, sizeof(st), hipMemcpyDeviceToHost, ctx->stream));
+    LWP_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    const Range rA{st[0], st[1]}, rw{st[2], st[3]}, rB{st[4], st[5]};
+    if (!fits(rA.lo + rw.lo + rB.lo) || !fits(rA.hi + rw.hi + rB.hi) || !fits(rA.lo + rw.lo) || !fits(rA.hi + rw.hi))
+        return fail(ctx, LWP_E_OVERFLOW, "A + w + B may leave int32");
+
+    NodeArgs a{};
+    a.descs = nullptr;
+    a.base.A = d_A; a.base.w = d_w; a.base.B = d_B; a.base.out = d_out; a.base.arg = d_argmin;
+    a.base.offA = (int32_t)(rA.lo + rw.lo);
+    a.base.offB = (int32_t)rB.lo;
+    const int64_t spread = (rA.hi + rw.hi - (rA.lo + rw.lo)) + (rB.hi - rB.lo);
+    a.base.tb = choose_tb(spread, Cj);
+    a.sA = (int64_t)Ci * Cj; a.sw = Cj; a.sB = (int64_t)Cj * Ck; a.sO = (int64_t)Ci * Ck;
+    a.Ci = Ci; a.Cj = Cj; a.Ck = Ck; a.batch = batch;
+    a.tilesM = (int32_t)tilesM; a.tilesN = (int32_t)tilesN;
+    {
+        ScopedTimer tm(ctx, 0, (int64_t)batch * Ci * Cj * Ck, a.base.tb > 0);
+        LWP_HIP(ctx, launch_minplus(a, a.base.tb > 0, ctx->stream));
+    }
+    return LWP_OK;
+}
+
+// ---- Eq. 3 -------------------------------------------------------------------------------------
+lwp_status lwp_eliminate_edge(lwp_ctx* ctx, int32_t batch, int32_t Ci, int32_t Cj,
+                              const int32_t* d_e1, const int32_t* d_e2, int32_t* d_out) {
+    if (lwp_status s = check_ctx(ctx)) return s;
+    if (batch < 1 || Ci < 1 || Cj < 1) return fail(ctx, LWP_E_INVAL, "sizes must be positive");
+    if (!d_e1 || !d_e2 || !d_out) return fail(ctx, LWP_E_INVAL, "null table pointer");
+    if (((uintptr_t)d_e1 | (uintptr_t)d_e2 | (uintptr_t)d_out) & 3)
+        return fail(ctx, LWP_E_INVAL, "table pointer not 4-byte aligned");
+    const int64_t cells = (int64_t)batch * Ci * Cj;
+    ScopedTimer tm(ctx, 1, cells, false);
+    LWP_HIP(ctx, launch_edge_sum_pair(d_e1, d_e2, d_out, cells, ctx->stream));
+    return LWP_OK;
+}
+
+// ---- Alg. 1 ------------------------------------------------------------------------------------
+lwp_status lwp_plan_graph(int32_t n_nodes, int32_t n_edges, const int32_t* edges, int32_t schedule,
+                          lwp_step* steps, int32_t* n_steps, int32_t* n_rounds, int32_t* n_residual_nodes) {
+    Plan plan;
+    std::string err;
+    lwp_status s = make_plan(n_nodes, n_edges, edges, schedule, plan, err);
+    if (n_steps) *n_steps = (int32_t)plan.steps.size();
+    if (n_rounds) *n_rounds = plan.n_rounds;
+    if (s != LWP_OK) return s;
+    if (steps && !plan.steps.empty()) std::memcpy(steps, plan.steps.data(), plan.steps.size() * sizeof(lwp_step));
+    if (n_residual_nodes) *n_residual_nodes = (int32_t)(2 * plan.pairs.size() + plan.singles.size());
+    return LWP_OK;
+}
+
+size_t lwp_search_workspace_bytes(int32_t n_nodes, int32_t n_edges, const int32_t* edges, int32_t C,
+                                  int32_t schedule) {
+    if (C < 1 || C > kMaxConfigs) return 0;
+    Plan plan;
+    std::string err;
+    if (make_plan(n_nodes, n_edges, edges, schedule, plan, err) != LWP_OK) return 0;
+    Layout L = plan_buffers(plan, n_edges);
+    return layout_workspace(plan, L, n_nodes, n_edges, C).total;
+}
+
+lwp_status lwp_search_graph(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, const int32_t* edges,
+                            int32_t C, const int32_t* d_tc, const int32_t* d_ts, const int32_t* d_tx,
+                            int32_t schedule, int32_t* out_cost, int32_t* out_strategy) {
+    if (lwp_status s = check_ctx(ctx)) return s;
+    if (C < 1 || C > kMaxConfigs) return fail(ctx, LWP_E_INVAL, "C must be in [1, 65536]");
+    if (!d_tc || !d_ts || (n_edges > 0 && !d_tx) || !out_cost || !out_strategy)
+        return fail(ctx, LWP_E_INVAL, "null pointer");
+    if (((uintptr_t)d_tc | (uintptr_t)d_ts | (uintptr_t)d_tx) & 3)
+        return fail(ctx, LWP_E_INVAL, "table pointer not 4-byte aligned");
+    Plan plan;
+    {
+        std::string err;
+        lwp_status s = make_plan(n_nodes, n_edges, edges, schedule, plan, err);
+        if (s != LWP_OK) return fail(ctx, s, err);
+    }
+    const Layout L = plan_buffers(plan, n_edges);
+    const WsLayout W = layout_workspace(plan, L, n_nodes, n_edges, C);
+    if (lwp_status s = ensure_workspace(ctx, W.total)) return s;
+    char* ws = ctx->ws;
+    hipStream_t st = ctx->stream;
+    const int64_t CC = (int64_t)C * C;
+    int32_t* d_w = reinterpret_cast<int32_t*>(ws + W.w);
+    int32_t* d_stats = reinterpret_cast<int32_t*>(ws + W.stats);
+    int32_t* d_flag = reinterpret_cast<int32_t*>(ws + W.flag);
+    int32_t* d_args = reinterpret_cast<int32_t*>(ws + W.args);
+    int32_t* d_slots = reinterpret_cast<int32_t*>(ws + W.slots);
+    auto table_ptr = [&](const TableRef& r) -> const int32_t* {
+        return r.is_slot ? d_slots + (int64_t)r.id * CC : d_tx + (int64_t)r.id * CC;
+    };
+
+    // 1. w = t_c + t_s, and the value range of every input table
+    LWP_HIP(ctx, hipMemsetAsync(d_flag, 0, sizeof(int32_t), st));
+    LWP_HIP(ctx, launch_add_vectors(d_tc, d_ts, d_w, (int64_t)n_nodes * C, d_flag, st));
+    LWP_HIP(ctx, launch_init_ranges(d_stats, n_edges + n_nodes, st));
+    LWP_HIP(ctx, launch_ranges(d_tx, n_edges, CC, d_stats, st));
+    LWP_HIP(ctx, launch_ranges(d_w, n_nodes, C, d_stats + 2 * (int64_t)n_edges, st));
+    std::vector<int32_t> stats(2 * (size_t)(n_edges + n_nodes) + 1);
+    LWP_HIP(ctx, hipMemcpyAsync(stats.data(), d_stats, 2 * (size_t)(n_edges + n_nodes) * sizeof(int32_t),
+                                hipMemcpyDeviceToHost, st));
+    LWP_HIP(ctx, hipMemcpyAsync(&stats.back(), d_flag, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    LWP_HIP(ctx, hipStreamSynchronize(st));
+    if (stats.back()) return fail(ctx, LWP_E_OVERFLOW, "t_c + t_s leaves int32");
+
+    // 2. propagate ranges through the plan: every sum any kernel forms must fit int32
+    std::vector<Range> er(n_edges), wr(n_nodes);
+    for (int32_t e = 0; e < n_edges; ++e) er[e] = {stats[2 * e], stats[2 * e + 1]};
+    for (int32_t v = 0; v < n_nodes; ++v) wr[v] = {stats[2 * (n_edges + v)], stats[2 * (n_edges + v) + 1]};
+    std::vector<NodeDesc> nd;
+    std::vector<UndoDesc> ud;
+    std::vector<char> nd_keyed;
+    nd.reserve(plan.n_node_steps); ud.reserve(plan.n_node_steps);
+    {
+        size_t ni = 0;
+        for (const lwp_step& s : plan.steps) {
+            if (s.kind == 1) {
+                Range r{er[s.e1].lo + er[s.e2].lo, er[s.e1].hi + er[s.e2].hi};
+                if (!fits(r.lo) || !fits(r.hi)) return fail(ctx, LWP_E_OVERFLOW, "sum of parallel edge tables may leave int32");
+                er[s.e1] = r;
+                continue;
+            }
+            const Range rA = er[s.e1], rw = wr[s.j], rB = er[s.e2];
+            if (!fits(rA.lo + rw.lo) || !fits(rA.hi + rw.hi) || !fits(rA.lo + rw.lo + rB.lo) || !fits(rA.hi + rw.hi + rB.hi))
+                return fail(ctx, LWP_E_OVERFLOW, "a node elimination may leave int32");
+            NodeDesc d{};
+            d.A = table_ptr(L.node_A[ni]); d.w = d_w + (int64_t)s.j * C; d.B = table_ptr(L.node_B[ni]);
+            d.out = d_slots + (int64_t)L.node_out_slot[ni] * CC;
+            d.arg = d_args + (int64_t)ni * CC;
+            d.offA = (int32_t)(rA.lo + rw.lo); d.offB = (int32_t)rB.lo;
+            d.tb = choose_tb((rA.hi + rw.hi - (rA.lo + rw.lo)) + (rB.hi - rB.lo), C);
+            nd.push_back(d); nd_keyed.push_back(d.tb > 0);
+            ud.push_back({d.arg, s.j, s.i, s.k, s.round});
+            // any fixed c bounds the minimum from above; take the c with the smallest w
+            er[s.e1] = {rA.lo + rw.lo + rB.lo, rA.hi + rw.lo + rB.hi};
+            ++ni;
+        }
+    }
+    int64_t total_hi = 0, total_lo = 0;
+    for (auto& p : plan.pairs) {
+        const int64_t lo = wr[p.src].lo + er[p.edge].lo + wr[p.dst].lo, hi = wr[p.src].hi + er[p.edge].hi + wr[p.dst].hi;
+        if (!fits(lo) || !fits(hi) || !fits(wr[p.src].hi + er[p.edge].hi) || !fits(wr[p.src].lo + er[p.edge].lo))
+            return fail(ctx, LWP_E_OVERFLOW, "the residual-graph sum may leave int32");
+        total_lo += lo; total_hi += wr[p.src].lo + er[p.edge].hi + wr[p.dst].lo;
+    }
+    for (int32_t v : plan.singles) { total_lo += wr[v].lo; total_hi += wr[v].lo; }
+    if (!fits(total_lo) || !fits(total_hi)) return fail(ctx, LWP_E_OVERFLOW, "the total cost may leave int32");
+
+    // 3. descriptors to the device
+    std::vector<EdgeDesc> ed(L.groups.size());
+    std::vector<const int32_t*> src_ptrs;
+    for (size_t g = 0; g < L.groups.size(); ++g) {
+        ed[g].out = d_slots + (int64_t)L.group_out_slot[g] * CC;
+        ed[g].first_src = (int32_t)src_ptrs.size();
+        ed[g].n_src = (int32_t)L.group_src[g].size();
+        for (auto& r : L.group_src[g]) src_ptrs.push_back(table_ptr(r));
+    }
+    std::vector<PairDesc> pd(plan.pairs.size());
+    for (size_t p = 0; p < plan.pairs.size(); ++p) pd[p] = {table_ptr(L.final_table[p]), plan.pairs[p].src, plan.pairs[p].dst};
+    NodeDesc* d_nd = reinterpret_cast<NodeDesc*>(ws + W.node_desc);
+    EdgeDesc* d_ed = reinterpret_cast<EdgeDesc*>(ws + W.edge_desc);
+    const int32_t** d_src = reinterpret_cast<const int32_t**>(ws + W.src_ptrs);
+    PairDesc* d_pd = reinterpret_cast<PairDesc*>(ws + W.pair_desc);
+    int32_t* d_singles = reinterpret_cast<int32_t*>(ws + W.singles);
+    UndoDesc* d_ud = reinterpret_cast<UndoDesc*>(ws + W.undo);
+    unsigned long long* d_keys = reinterpret_cast<unsigned long long*>(ws + W.keys);
+    int32_t* d_result = reinterpret_cast<int32_t*>(ws + W.result);
+    auto upload = [&](void* dst, const void* src, size_t bytes) -> hipError_t {
+        return bytes ? hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, st) : hipSuccess;
+    };
+    LWP_HIP(ctx, upload(d_nd, nd.data(), nd.size() * sizeof(NodeDesc)));
+    LWP_HIP(ctx, upload(d_ed, ed.data(), ed.size() * sizeof(EdgeDesc)));
+    LWP_HIP(ctx, upload(d_src, src_ptrs.data(), src_ptrs.size() * sizeof(void*)));
+    LWP_HIP(ctx, upload(d_pd, pd.data(), pd.size() * sizeof(PairDesc)));
+    LWP_HIP(ctx, upload(d_singles, plan.singles.data(), plan.singles.size() * sizeof(int32_t)));
+    LWP_HIP(ctx, upload(d_ud, ud.data(), ud.size() * sizeof(UndoDesc)));
+    // the host vectors must outlive the copies: pageable-memory copies are staged before return,
+    // and the final synchronisation below happens before the vectors go out of scope
+
+    // 4. eliminations, round by round
+    const int32_t tiles1 = (C + kTileM - 1) / kTileM;
+    size_t gi = 0, ni = 0, t = 0;
+    const size_t n = plan.steps.size();
+    while (t < n) {
+        const int32_t round = plan.steps[t].round;
+        size_t g0 = gi;
+        while (t < n && plan.steps[t].round == round && plan.steps[t].kind == 1) {
+            t += L.groups[gi].others.size();
+            ++gi;
+        }
+        if (gi > g0) {
+            ScopedTimer tm(ctx, 1, (int64_t)(gi - g0) * CC, false);
+            LWP_HIP(ctx, launch_edge_sum_desc(d_ed + g0, d_src, (int32_t)(gi - g0), CC, st));
+        }
+        size_t n0 = ni;
+        while (t < n && plan.steps[t].round == round && plan.steps[t].kind == 0) { ++t; ++ni; }
+        // products of one round run in one launch per arithmetic variant (contiguous runs)
+        for (size_t a = n0; a < ni;) {
+            size_t b = a;
+            while (b < ni && nd_keyed[b] == nd_keyed[a]) ++b;
+            NodeArgs na{};
+            na.descs = d_nd + a;
+            na.Ci = na.Cj = na.Ck = C; na.batch = (int32_t)(b - a);
+            na.tilesM = na.tilesN = tiles1;
+            ScopedTimer tm(ctx, 0, (int64_t)(b - a) * CC * C, nd_keyed[a]);
+            LWP_HIP(ctx, launch_minplus(na, nd_keyed[a], st));
+            a = b;
+        }
+    }
+
+    // 5. residual graph, undo, results
+    const int32_t n_comp = (int32_t)(plan.pairs.size() + plan.singles.size());
+    LWP_HIP(ctx, launch_init_keys(d_keys, n_comp, st));
+    LWP_HIP(ctx, launch_pair_min(d_pd, (int32_t)plan.pairs.size(), d_w, C, d_keys, st));
+    LWP_HIP(ctx, launch_single_min(d_singles, (int32_t)plan.singles.size(), d_w, C, d_keys + plan.pairs.size(), st));
+    LWP_HIP(ctx, launch_back_substitute(d_pd, (int32_t)plan.pairs.size(), d_singles, (int32_t)plan.singles.size(),
+                                        d_keys, d_ud, (int32_t)ud.size(), C, n_nodes, d_result, st));
+    std::vector<int32_t> result(2 + (size_t)n_nodes);
+    LWP_HIP(ctx, hipMemcpyAsync(result.data(), d_result, result.size() * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    LWP_HIP(ctx, hipStreamSynchronize(st));
+    const int64_t total = (int64_t)(((uint64_t)(uint32_t)result[1] << 32) | (uint32_t)result[0]);
+    if (!fits(total)) return fail(ctx, LWP_E_OVERFLOW, "the total cost leaves int32");
+    *out_cost = (int32_t)total;
+    std::memcpy(out_strategy, result.data() + 2, (size_t)n_nodes * sizeof(int32_t));
+    return LWP_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,84 @@
+// Device-side entry points of the strategy search, as host-callable launchers.
+// Every launcher only enqueues on `stream` and returns the hipError_t of the launch.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace lwp {
+
+// ---- node elimination (Eq. 2) --------------------------------------------------------------
+// One product of a batched launch.  `tb` > 0 selects the packed-key arithmetic for this
+// product: costs are re-based by offA (for A + w) and offB (for B) so that they are
+// non-negative and (A + w - offA) + (B - offB) <= 2^(32-tb) - 2;  5 <= tb <= 17.
+struct NodeDesc {
+    const int32_t* A;
+    const int32_t* w;
+    const int32_t* B;
+    int32_t* out;
+    int32_t* arg;      // may be null
+    int32_t offA, offB;
+    int32_t tb, pad0;
+    int64_t pad1;
+};
+static_assert(sizeof(NodeDesc) == 64, "descriptor layout");
+
+struct NodeArgs {
+    const NodeDesc* descs;   // device array [batch], or null for strided addressing
+    NodeDesc base;           // strided addressing: product 0
+    int64_t sA, sw, sB, sO;  // strided addressing: element strides between products
+    int32_t Ci, Cj, Ck, batch;
+    int32_t tilesM, tilesN;
+};
+
+constexpr int kTileM = 128, kTileN = 128, kTileK = 16, kNodeThreads = 256;
+
+// keyed = true launches the packed-key variant (every product needs 5 <= tb <= 17),
+// keyed = false the plain int32 compare/select variant (tb ignored).
+hipError_t launch_minplus(const NodeArgs& args, bool keyed, hipStream_t stream);
+
+// ---- edge elimination (Eq. 3) --------------------------------------------------------------
+// out = sum of n_src tables of `cells` elements.  srcs indexes a device array of table pointers.
+struct EdgeDesc {
+    int32_t* out;
+    int32_t first_src;   // index into the pointer array
+    int32_t n_src;
+};
+hipError_t launch_edge_sum_desc(const EdgeDesc* d_descs, const int32_t* const* d_src_ptrs, int32_t n_desc,
+                                int64_t cells, hipStream_t stream);
+hipError_t launch_edge_sum_pair(const int32_t* e1, const int32_t* e2, int32_t* out, int64_t cells,
+                                hipStream_t stream);
+
+// ---- value ranges ----------------------------------------------------------------------------
+// stats[2*t] = min, stats[2*t+1] = max of table t (n_tables tables of `cells` elements each,
+// dense one after another).  init_ranges must run first on the same stream.
+hipError_t launch_init_ranges(int32_t* d_stats, int32_t n_tables, hipStream_t stream);
+hipError_t launch_ranges(const int32_t* d_tables, int32_t n_tables, int64_t cells, int32_t* d_stats,
+                         hipStream_t stream);
+// w = tc + ts (n elements); *d_flag is OR-ed with 1 if a sum leaves int32.
+hipError_t launch_add_vectors(const int32_t* tc, const int32_t* ts, int32_t* w, int64_t n, int32_t* d_flag,
+                              hipStream_t stream);
+
+// ---- residual graph and back-substitution (Alg. 1, enumeration of the final graph and undo) --
+struct PairDesc {       // residual component with two nodes joined by one edge
+    const int32_t* T;   // [C][C]
+    int32_t src, dst;
+};
+struct UndoDesc {       // one node elimination of the log
+    const int32_t* arg; // [C][C]
+    int32_t j, i, k, round;
+};
+// keys[p] is a 64-bit (cost, flat index) minimum per component; init_keys sets all to max.
+hipError_t launch_init_keys(unsigned long long* d_keys, int32_t n, hipStream_t stream);
+hipError_t launch_pair_min(const PairDesc* d_pairs, int32_t n_pairs, const int32_t* d_w, int32_t C,
+                           unsigned long long* d_keys, hipStream_t stream);
+hipError_t launch_single_min(const int32_t* d_singles, int32_t n_singles, const int32_t* d_w, int32_t C,
+                             unsigned long long* d_keys /* after the pairs */, hipStream_t stream);
+// Decodes the component minima, then walks the undo list backwards (entries of one round are
+// independent).  result[0] = total cost low word, result[1] = high word, result[2..] = strategy.
+hipError_t launch_back_substitute(const PairDesc* d_pairs, int32_t n_pairs, const int32_t* d_singles,
+                                  int32_t n_singles, const unsigned long long* d_keys,
+                                  const UndoDesc* d_undo, int32_t n_undo, int32_t C, int32_t n_nodes,
+                                  int32_t* d_result, hipStream_t stream);
+
+}  // namespace lwp

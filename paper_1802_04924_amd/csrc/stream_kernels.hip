@@ -1,0 +1,312 @@
+// The memory-streaming and latency-bound parts of the search: edge elimination (Eq. 3), value
+// ranges of the input tables, the residual-graph minimum (Alg. 1, enumeration of the final graph
+// with K <= 2 per component) and the undo pass (Alg. 1, last loop).  All of these move each
+// table element once; they are bound by HBM bandwidth or by dependent-load latency, not by ALUs.
+#include "lwp_kernels.h"
+
+namespace lwp {
+
+namespace {
+
+constexpr int kThreads = 256;
+
+__device__ __forceinline__ int wave_min(int v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = min(v, __shfl_xor(v, o));
+    return v;
+}
+__device__ __forceinline__ int wave_max(int v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = max(v, __shfl_xor(v, o));
+    return v;
+}
+__device__ __forceinline__ unsigned long long wave_min_u64(unsigned long long v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const unsigned long long u = __shfl_xor(v, o);
+        v = u < v ? u : v;
+    }
+    return v;
+}
+
+// ---- Eq. 3 -----------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void edge_sum_desc_kernel(const EdgeDesc* __restrict__ descs,
+                                                                 const int32_t* const* __restrict__ srcs,
+                                                                 int64_t cells) {
+    const EdgeDesc d = descs[blockIdx.y];
+    const int32_t* const* sp = srcs + d.first_src;
+    const int n = d.n_src;
+    bool vec = ((cells & 3) == 0) && ((((uintptr_t)d.out) & 15) == 0);
+    for (int q = 0; q < n; ++q) vec = vec && ((((uintptr_t)sp[q]) & 15) == 0);
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    const int64_t t0 = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (vec) {
+        const int64_t n4 = cells >> 2;
+        for (int64_t x = t0; x < n4; x += stride) {
+            int4 acc = reinterpret_cast<const int4*>(sp[0])[x];
+            for (int q = 1; q < n; ++q) {
+                const int4 v = reinterpret_cast<const int4*>(sp[q])[x];
+                acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+            }
+            reinterpret_cast<int4*>(d.out)[x] = acc;
+        }
+    } else {
+        for (int64_t x = t0; x < cells; x += stride) {
+            int32_t acc = sp[0][x];
+            for (int q = 1; q < n; ++q) acc += sp[q][x];
+            d.out[x] = acc;
+        }
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void edge_sum_pair_kernel(const int32_t* e1, const int32_t* e2,
+                                                                 int32_t* out, int64_t cells) {
+    const bool vec = ((cells & 3) == 0) && (((((uintptr_t)e1) | ((uintptr_t)e2) | ((uintptr_t)out)) & 15) == 0);
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    const int64_t t0 = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (vec) {
+        const int64_t n4 = cells >> 2;
+        for (int64_t x = t0; x < n4; x += stride) {
+            const int4 a = reinterpret_cast<const int4*>(e1)[x];
+            const int4 b = reinterpret_cast<const int4*>(e2)[x];
+            reinterpret_cast<int4*>(out)[x] = make_int4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w);
+        }
+    } else {
+        for (int64_t x = t0; x < cells; x += stride) out[x] = e1[x] + e2[x];
+    }
+}
+
+// ---- value ranges ------------------------------------------------------------------------------
+__global__ void init_ranges_kernel(int32_t* stats, int32_t n_tables) {
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < n_tables) { stats[2 * t] = 0x7fffffff; stats[2 * t + 1] = (int32_t)0x80000000; }
+}
+
+__global__ __launch_bounds__(kThreads) void ranges_kernel(const int32_t* __restrict__ tables, int64_t cells,
+                                                          int32_t* __restrict__ stats) {
+    __shared__ int smin[kThreads / 64], smax[kThreads / 64];
+    const int32_t* T = tables + (int64_t)blockIdx.y * cells;
+    int lo = 0x7fffffff, hi = (int32_t)0x80000000;
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    const int64_t t0 = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (((cells & 3) == 0) && ((((uintptr_t)T) & 15) == 0)) {
+        const int64_t n4 = cells >> 2;
+        for (int64_t x = t0; x < n4; x += stride) {
+            const int4 v = reinterpret_cast<const int4*>(T)[x];
+            lo = min(min(lo, v.x), min(v.y, min(v.z, v.w)));
+            hi = max(max(hi, v.x), max(v.y, max(v.z, v.w)));
+        }
+    } else {
+        for (int64_t x = t0; x < cells; x += stride) { const int v = T[x]; lo = min(lo, v); hi = max(hi, v); }
+    }
+    lo = wave_min(lo); hi = wave_max(hi);
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) { smin[wave] = lo; smax[wave] = hi; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int q = 1; q < kThreads / 64; ++q) { lo = min(lo, smin[q]); hi = max(hi, smax[q]); }
+        atomicMin(&stats[2 * blockIdx.y], lo);
+        atomicMax(&stats[2 * blockIdx.y + 1], hi);
+    }
+}
+
+// w = tc + ts; flag[0] is set if a sum leaves int32
+__global__ __launch_bounds__(kThreads) void add_vectors_kernel(const int32_t* __restrict__ tc,
+                                                               const int32_t* __restrict__ ts,
+                                                               int32_t* __restrict__ w, int64_t n,
+                                                               int32_t* __restrict__ flag) {
+    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    bool bad = false;
+    for (int64_t x = (int64_t)blockIdx.x * kThreads + threadIdx.x; x < n; x += stride) {
+        const int64_t s = (int64_t)tc[x] + (int64_t)ts[x];
+        bad = bad || (s != (int64_t)(int32_t)s);
+        w[x] = (int32_t)s;
+    }
+    if (bad) atomicOr(flag, 1);
+}
+
+// ---- residual graph ----------------------------------------------------------------------------
+// A component minimum is kept as one 64-bit key: (cost with flipped sign bit) << 32 | flat index,
+// so an unsigned 64-bit min orders by cost first and by the lowest flat index among equal costs.
+__device__ __forceinline__ unsigned long long make_key(int32_t cost, uint32_t idx) {
+    return ((unsigned long long)((uint32_t)cost ^ 0x80000000u) << 32) | idx;
+}
+
+__global__ void init_keys_kernel(unsigned long long* keys, int32_t n) {
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < n) keys[t] = ~0ull;
+}
+
+__device__ __forceinline__ void block_min_to(unsigned long long v, unsigned long long* dst) {
+    __shared__ unsigned long long sm[kThreads / 64];
+    v = wave_min_u64(v);
+    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = v;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int q = 1; q < kThreads / 64; ++q) v = sm[q] < v ? sm[q] : v;
+        if (v != ~0ull) atomicMin(dst, v);
+    }
+}
+
+// min over (a,b) of w_i[a] + T[a][b] + w_k[b]; grid.y = component
+__global__ __launch_bounds__(kThreads) void pair_min_kernel(const PairDesc* __restrict__ pairs,
+                                                            const int32_t* __restrict__ w, int32_t C,
+                                                            unsigned long long* __restrict__ keys) {
+    const PairDesc d = pairs[blockIdx.y];
+    const int32_t* wi = w + (int64_t)d.src * C;
+    const int32_t* wk = w + (int64_t)d.dst * C;
+    unsigned long long best = ~0ull;
+    for (int a = blockIdx.x; a < C; a += gridDim.x) {
+        const int32_t wa = wi[a];
+        const int32_t* Trow = d.T + (int64_t)a * C;
+        for (int b = threadIdx.x; b < C; b += kThreads) {
+            const int32_t s = wa + Trow[b] + wk[b];
+            const unsigned long long k = make_key(s, (uint32_t)a * (uint32_t)C + (uint32_t)b);
+            best = k < best ? k : best;
+        }
+    }
+    block_min_to(best, &keys[blockIdx.y]);
+}
+
+// min over a of w[a]; grid.y = isolated node
+__global__ __launch_bounds__(kThreads) void single_min_kernel(const int32_t* __restrict__ singles,
+                                                              const int32_t* __restrict__ w, int32_t C,
+                                                              unsigned long long* __restrict__ keys) {
+    const int32_t* wl = w + (int64_t)singles[blockIdx.y] * C;
+    unsigned long long best = ~0ull;
+    for (int x = blockIdx.x * kThreads + threadIdx.x; x < C; x += gridDim.x * kThreads) {
+        const unsigned long long k = make_key(wl[x], (uint32_t)x);
+        best = k < best ? k : best;
+    }
+    block_min_to(best, &keys[blockIdx.y]);
+}
+
+// ---- undo (Alg. 1: S^(i) = S^(i+1) + c_j, c_j the stored argmin of Eq. 2 at (c_i, c_k)) ---------
+__global__ __launch_bounds__(kThreads) void back_substitute_kernel(
+    const PairDesc* __restrict__ pairs, int32_t n_pairs, const int32_t* __restrict__ singles, int32_t n_singles,
+    const unsigned long long* __restrict__ keys, const UndoDesc* __restrict__ undo, int32_t n_undo, int32_t C,
+    int32_t n_nodes, int32_t* __restrict__ result) {
+    __shared__ long long ssum[kThreads / 64];
+    int32_t* S = result + 2;
+    long long cost = 0;
+    for (int t = threadIdx.x; t < n_pairs + n_singles; t += kThreads) {
+        const unsigned long long k = keys[t];
+        const uint32_t flat = (uint32_t)k;
+        cost += (long long)(int32_t)((uint32_t)(k >> 32) ^ 0x80000000u);
+        if (t < n_pairs) { S[pairs[t].src] = (int32_t)(flat / (uint32_t)C); S[pairs[t].dst] = (int32_t)(flat % (uint32_t)C); }
+        else S[singles[t - n_pairs]] = (int32_t)flat;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) cost += __shfl_xor(cost, o);
+    if ((threadIdx.x & 63) == 0) ssum[threadIdx.x >> 6] = cost;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        long long tot = 0;
+        for (int q = 0; q < kThreads / 64; ++q) tot += ssum[q];
+        result[0] = (int32_t)(tot & 0xffffffffll);
+        result[1] = (int32_t)(tot >> 32);
+    }
+    // walk the rounds backwards; node eliminations of one round never depend on each other
+    int hi = n_undo;
+    while (hi > 0) {
+        const int r = undo[hi - 1].round;
+        int lo = hi - 1;
+        while (lo > 0 && undo[lo - 1].round == r) --lo;
+        for (int t = lo + threadIdx.x; t < hi; t += kThreads) {
+            const UndoDesc u = undo[t];
+            S[u.j] = u.arg[(int64_t)S[u.i] * C + S[u.k]];
+        }
+        __syncthreads();
+        hi = lo;
+    }
+    (void)n_nodes;
+}
+
+inline unsigned blocks_for(int64_t work_items, int64_t per_thread, unsigned cap) {
+    int64_t b = (work_items + (int64_t)kThreads * per_thread - 1) / ((int64_t)kThreads * per_thread);
+    if (b < 1) b = 1;
+    if (b > cap) b = cap;
+    return (unsigned)b;
+}
+
+}  // namespace
+
+hipError_t launch_edge_sum_desc(const EdgeDesc* d_descs, const int32_t* const* d_src_ptrs, int32_t n_desc,
+                                int64_t cells, hipStream_t stream) {
+    for (int32_t t0 = 0; t0 < n_desc; t0 += 65535) {
+        const int32_t n = (n_desc - t0) < 65535 ? (n_desc - t0) : 65535;
+        dim3 grid(blocks_for(cells, 16, 2048), (unsigned)n);
+        hipLaunchKernelGGL(edge_sum_desc_kernel, grid, dim3(kThreads), 0, stream, d_descs + t0, d_src_ptrs, cells);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_edge_sum_pair(const int32_t* e1, const int32_t* e2, int32_t* out, int64_t cells,
+                                hipStream_t stream) {
+    dim3 grid(blocks_for(cells, 16, 8192));
+    hipLaunchKernelGGL(edge_sum_pair_kernel, grid, dim3(kThreads), 0, stream, e1, e2, out, cells);
+    return hipGetLastError();
+}
+
+hipError_t launch_init_ranges(int32_t* d_stats, int32_t n_tables, hipStream_t stream) {
+    if (n_tables <= 0) return hipSuccess;
+    hipLaunchKernelGGL(init_ranges_kernel, dim3((n_tables + 255) / 256), dim3(256), 0, stream, d_stats, n_tables);
+    return hipGetLastError();
+}
+
+hipError_t launch_ranges(const int32_t* d_tables, int32_t n_tables, int64_t cells, int32_t* d_stats,
+                         hipStream_t stream) {
+    if (n_tables <= 0) return hipSuccess;
+    unsigned cap = n_tables >= 64 ? 64u : (n_tables >= 8 ? 512u : 4096u);
+    for (int32_t t0 = 0; t0 < n_tables; t0 += 65535) {
+        const int32_t n = (n_tables - t0) < 65535 ? (n_tables - t0) : 65535;
+        dim3 grid(blocks_for(cells, 16, cap), (unsigned)n);
+        hipLaunchKernelGGL(ranges_kernel, grid, dim3(kThreads), 0, stream, d_tables + (int64_t)t0 * cells, cells,
+                           d_stats + 2 * (int64_t)t0);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_add_vectors(const int32_t* tc, const int32_t* ts, int32_t* w, int64_t n, int32_t* d_flag,
+                              hipStream_t stream) {
+    hipLaunchKernelGGL(add_vectors_kernel, dim3(blocks_for(n, 4, 4096)), dim3(kThreads), 0, stream, tc, ts, w, n, d_flag);
+    return hipGetLastError();
+}
+
+hipError_t launch_init_keys(unsigned long long* d_keys, int32_t n, hipStream_t stream) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(init_keys_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, d_keys, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_pair_min(const PairDesc* d_pairs, int32_t n_pairs, const int32_t* d_w, int32_t C,
+                           unsigned long long* d_keys, hipStream_t stream) {
+    for (int32_t t0 = 0; t0 < n_pairs; t0 += 65535) {
+        const int32_t n = (n_pairs - t0) < 65535 ? (n_pairs - t0) : 65535;
+        const unsigned rows = (unsigned)C < 2048u ? (unsigned)C : 2048u;
+        dim3 grid(rows, (unsigned)n);
+        hipLaunchKernelGGL(pair_min_kernel, grid, dim3(kThreads), 0, stream, d_pairs + t0, d_w, C, d_keys + t0);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_single_min(const int32_t* d_singles, int32_t n_singles, const int32_t* d_w, int32_t C,
+                             unsigned long long* d_keys, hipStream_t stream) {
+    for (int32_t t0 = 0; t0 < n_singles; t0 += 65535) {
+        const int32_t n = (n_singles - t0) < 65535 ? (n_singles - t0) : 65535;
+        dim3 grid(blocks_for(C, 4, 64), (unsigned)n);
+        hipLaunchKernelGGL(single_min_kernel, grid, dim3(kThreads), 0, stream, d_singles + t0, d_w, C, d_keys + t0);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_back_substitute(const PairDesc* d_pairs, int32_t n_pairs, const int32_t* d_singles,
+                                  int32_t n_singles, const unsigned long long* d_keys,
+                                  const UndoDesc* d_undo, int32_t n_undo, int32_t C, int32_t n_nodes,
+                                  int32_t* d_result, hipStream_t stream) {
+    hipLaunchKernelGGL(back_substitute_kernel, dim3(1), dim3(kThreads), 0, stream, d_pairs, n_pairs, d_singles,
+                       n_singles, d_keys, d_undo, n_undo, C, n_nodes, d_result);
+    return hipGetLastError();
+}
+
+}  // namespace lwp

@@ -1,0 +1,187 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, bit for bit."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1802_04924_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    import torch
+    from paper_1802_04924_amd import Context
+    assert torch.cuda.is_available()
+    c = Context(0)
+    yield c
+    c.close()
+
+
+def dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
+
+
+def check_products(ctx, A, w, B, expect_keyed=None):
+    """A [batch][Ci][Cj] etc. as numpy; compares out and argmin of every product with the oracle."""
+    ctx.profile_enable(True)
+    ctx.profile_reset()
+    out, arg = ctx.eliminate_node(dev(A), dev(w), dev(B))
+    prof = ctx.profile_read()
+    ctx.profile_enable(False)
+    out, arg = out.cpu().numpy(), arg.cpu().numpy()
+    for b in range(A.shape[0]):
+        ro, ra = oracle.minplus_argmin(A[b], w[b], B[b])
+        assert np.array_equal(out[b], ro), f"cost mismatch in product {b}"
+        assert np.array_equal(arg[b], ra), f"argmin mismatch in product {b}"
+    if expect_keyed is not None:
+        assert (prof["keyed_launches"] == 1) == expect_keyed
+    return prof
+
+
+SHAPES = [(1, 1, 1, 1), (1, 3, 5, 4), (2, 17, 33, 9), (1, 128, 128, 128), (3, 130, 257, 140),
+          (2, 256, 256, 256), (1, 64, 512, 192), (1, 129, 16, 260), (5, 40, 100, 24)]
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("hi", [1, 3, 1 << 20])
+def test_eliminate_node_keyed_small_values(ctx, shape, hi):
+    batch, Ci, Cj, Ck = shape
+    rng = np.random.default_rng(hash((shape, hi)) % (1 << 32))
+    A = rng.integers(0, hi, size=(batch, Ci, Cj), endpoint=True, dtype=np.int32)
+    w = rng.integers(0, hi, size=(batch, Cj), endpoint=True, dtype=np.int32)
+    B = rng.integers(0, hi, size=(batch, Cj, Ck), endpoint=True, dtype=np.int32)
+    check_products(ctx, A, w, B, expect_keyed=True)
+
+
+@pytest.mark.parametrize("bits,expect_keyed", [(22, True), (24, True), (25, True), (26, False), (29, False)])
+@pytest.mark.parametrize("shape", [(2, 130, 257, 140), (1, 128, 512, 128), (1, 31, 1000, 17)])
+def test_eliminate_node_key_widths_and_plain_variant(ctx, shape, bits, expect_keyed):
+    # the spread of A + w + B decides the key width: 3 * 2^bits; wide spreads use the plain variant
+    batch, Ci, Cj, Ck = shape
+    hi = (1 << bits) - 1
+    rng = np.random.default_rng(bits * 1000 + Cj)
+    A = rng.integers(0, hi, size=(batch, Ci, Cj), endpoint=True, dtype=np.int32)
+    w = rng.integers(0, hi, size=(batch, Cj), endpoint=True, dtype=np.int32)
+    B = rng.integers(0, hi, size=(batch, Cj, Ck), endpoint=True, dtype=np.int32)
+    # force ties across chunk boundaries: duplicate some candidates exactly
+    A[:, :, Cj // 2:] = A[:, :, :Cj - Cj // 2]
+    w[:, Cj // 2:] = w[:, :Cj - Cj // 2]
+    B[:, Cj // 2:, :] = B[:, :Cj - Cj // 2, :]
+    check_products(ctx, A, w, B, expect_keyed=expect_keyed)
+
+
+def test_eliminate_node_negative_and_offset_values(ctx):
+    rng = np.random.default_rng(11)
+    A = rng.integers(-(1 << 20), 1 << 10, size=(2, 70, 90, ), dtype=np.int32).reshape(2, 70, 90)
+    w = rng.integers(-5000, 5000, size=(2, 90), dtype=np.int32)
+    B = rng.integers((1 << 29), (1 << 29) + 1000, size=(2, 90, 50), dtype=np.int32)
+    check_products(ctx, A, w, B, expect_keyed=True)       # re-based into the key range
+    A = rng.integers(-(1 << 30), 1 << 30, size=(1, 33, 47), dtype=np.int32)
+    w = rng.integers(-(1 << 20), 1 << 20, size=(1, 47), dtype=np.int32)
+    B = rng.integers(-(1 << 29), 1 << 29, size=(1, 47, 65), dtype=np.int32)
+    check_products(ctx, A, w, B, expect_keyed=False)
+
+
+def test_eliminate_node_closed_forms(ctx):
+    C = 150
+    rng = np.random.default_rng(2)
+    A = rng.integers(0, 1000, size=(1, 77, C), dtype=np.int32)
+    B = np.full((1, C, C), 1 << 24, np.int32)
+    B[0][np.arange(C), np.arange(C)] = 0
+    out, arg = ctx.eliminate_node(dev(A), dev(np.zeros((1, C), np.int32)), dev(B))
+    assert np.array_equal(out.cpu().numpy(), A)
+    assert np.array_equal(arg.cpu().numpy()[0], np.tile(np.arange(C, dtype=np.int32), (77, 1)))
+    out, arg = ctx.eliminate_node(dev(np.full((1, 9, 40), 4)), dev(np.full((1, 40), 2)), dev(np.full((1, 40, 6), 1)))
+    assert (out.cpu().numpy() == 7).all() and (arg.cpu().numpy() == 0).all()
+
+
+def test_eliminate_node_without_argmin_and_overflow(ctx):
+    from paper_1802_04924_amd import LwpError
+    rng = np.random.default_rng(5)
+    A, w, B = wl.batched_products(2, 50, 60, 70, 5)
+    out, arg = ctx.eliminate_node(dev(A), dev(w), dev(B), want_argmin=False)
+    assert arg is None
+    assert np.array_equal(out.cpu().numpy()[1], oracle.minplus_argmin(A[1], w[1], B[1])[0])
+    big = np.full((1, 4, 4), (1 << 31) - 1, np.int32)
+    with pytest.raises(LwpError) as e:
+        ctx.eliminate_node(dev(big), dev(np.ones((1, 4), np.int32)), dev(np.zeros((1, 4, 4), np.int32)))
+    assert e.value.code == -4
+
+
+@pytest.mark.parametrize("shape", [(1, 1, 1), (3, 17, 5), (2, 128, 128), (1, 1000, 999)])
+def test_eliminate_edge(ctx, shape):
+    rng = np.random.default_rng(sum(shape))
+    e1 = rng.integers(-(1 << 29), 1 << 29, size=shape, dtype=np.int32)
+    e2 = rng.integers(-(1 << 29), 1 << 29, size=shape, dtype=np.int32)
+    out = ctx.eliminate_edge(dev(e1), dev(e2)).cpu().numpy()
+    for b in range(shape[0]):
+        assert np.array_equal(out[b], oracle.edge_sum(e1[b], e2[b]))
+    d1 = dev(e1)
+    ctx.eliminate_edge(d1, dev(e2), out=d1)            # in place
+    assert np.array_equal(d1.cpu().numpy(), e1 + e2)
+
+
+def run_search(ctx, p, schedule=None):
+    schedule = p["schedule"] if schedule is None else schedule
+    cost, S = ctx.search_graph(p["n_nodes"], p["edges"], p["C"], dev(p["tc"]), dev(p["ts"]), dev(p["tx"]), schedule)
+    ref = oracle.search(p["n_nodes"], p["edges"], p["C"], p["tc"], p["ts"], p["tx"], schedule)
+    assert cost == ref["cost"]
+    assert np.array_equal(S, ref["strategy"])
+    assert oracle.strategy_cost(p["n_nodes"], p["edges"], p["C"], p["tc"], p["ts"], p["tx"], S) == cost
+    return cost, S
+
+
+def test_search_config0(ctx):
+    from oracle import brute
+    p = wl.config0()
+    cost, S = run_search(ctx, p)
+    best, _, _ = brute.brute_force(p["n_nodes"], p["edges"], p["C"], p["tc"], p["ts"], p["tx"])
+    assert cost == best
+    run_search(ctx, p, wl.SCHEDULE_LEFT_FOLD)
+
+
+@pytest.mark.parametrize("n_layers,C,hi", [(2, 7, 50), (3, 130, 1000), (11, 24, 3), (33, 200, 1 << 20), (9, 257, 1 << 24)])
+@pytest.mark.parametrize("schedule", [wl.SCHEDULE_ROUNDS, wl.SCHEDULE_LEFT_FOLD])
+def test_search_chains(ctx, n_layers, C, hi, schedule):
+    p = wl.chain_problem(n_layers, C, seed=n_layers + C, tc_range=(0, hi), ts_range=(0, hi), tx_range=(0, hi))
+    run_search(ctx, p, schedule)
+
+
+@pytest.mark.parametrize("modules,C,hi", [(1, 5, 3), (2, 33, 100000), (10, 64, 100000), (3, 128, 1)])
+@pytest.mark.parametrize("schedule", [wl.SCHEDULE_ROUNDS, wl.SCHEDULE_LEFT_FOLD])
+def test_search_forkjoin(ctx, modules, C, hi, schedule):
+    p = wl.forkjoin_problem(modules, C, seed=modules * 7 + C, lo=0, hi=hi)
+    run_search(ctx, p, schedule)
+
+
+def test_search_small_irregular_graphs(ctx):
+    graphs = {
+        "single": (1, []), "two_isolated": (2, []), "parallel3": (2, [(0, 1), (0, 1), (0, 1)]),
+        "diamond_skip": (4, [(0, 1), (0, 2), (1, 3), (2, 3), (0, 3)]),
+        "backward_ids": (4, [(3, 1), (1, 0), (0, 2)]),
+        "two_chains": (6, [(0, 1), (1, 2), (3, 4), (4, 5)]),
+        "residual": (6, [(0, 1), (1, 2), (2, 3), (1, 4), (4, 3), (3, 5), (3, 5)]),
+    }
+    for name, (n, e) in graphs.items():
+        edges = np.asarray(e, np.int32).reshape(-1, 2)
+        for C, hi in ((1, 9), (3, 2), (19, 1000)):
+            tc, ts, tx = wl.random_tables(n, edges, C, 3, (0, hi), (0, hi), (0, hi))
+            p = {"n_nodes": n, "edges": edges, "C": C, "tc": tc, "ts": ts, "tx": tx, "schedule": 0}
+            run_search(ctx, p)
+
+
+def test_search_errors(ctx):
+    from paper_1802_04924_amd import LwpError
+    edges = np.array([[0, 1], [0, 2], [0, 3]], np.int32)
+    tc, ts, tx = wl.random_tables(4, edges, 2, 0, (0, 5), (0, 5), (0, 5))
+    with pytest.raises(LwpError) as e:
+        ctx.search_graph(4, edges, 2, dev(tc), dev(ts), dev(tx))
+    assert e.value.code == -3
+    p = wl.chain_problem(4, 8, 1, tc_range=(1 << 30, (1 << 30) + 5))
+    with pytest.raises(LwpError) as e:
+        ctx.search_graph(4, p["edges"], 8, dev(p["tc"]), dev(p["ts"]), dev(p["tx"]))
+    assert e.value.code == -4
+    # the context stays usable after an error
+    run_search(ctx, wl.config0())
