@@ -1,0 +1,177 @@
+#!/usr/bin/env python3
+"""Benchmark of the strategy search on one MI355X.
+
+A step is one whole search (Alg. 1: all eliminations, residual solve, undo) over tables that
+are already resident in HBM.  Default workload: the 64-layer chain with 4096 configurations per
+layer (62 sequential 4096^3 node eliminations).  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg4|cfg3|cfg2|cfg0]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+# VALU int32 peak of MI355X: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-operations per second.
+# One cell update of Eq. 2 is one add and one min, i.e. 2 lane-operations.
+PEAK_INT32_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
+OPS_PER_UPDATE = 2
+# L2<->fabric bytes of one 4096^3 min-plus launch from the rocprofv3 --pmc passes (FETCH_SIZE and
+# WRITE_SIZE, each scaled by a 1 GiB reference copy): profiles/minplus_kernel_C4096_pmc.txt.
+PMC_TRAFFIC_BYTES_C4096 = 929_990_612
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def cpu_baseline(kind, payload):
+    """Times the CPU oracle, as it stands, on a bounded sample of the same workload."""
+    import oracle
+    threads = oracle.omp_threads()
+    if kind == "search":
+        p = payload
+        t0 = time.perf_counter()
+        oracle.search(p["n_nodes"], p["edges"], p["C"], p["tc"], p["ts"], p["tx"], p["schedule"])
+        dt = time.perf_counter() - t0
+        return {"value": p["updates"] / dt / 1e9, "unit": "G cell-updates/s", "cores": threads, "kind": "oracle",
+                "sample": f"the whole search once ({dt * 1e3:.1f} ms)", "search_ms": dt * 1e3}
+    A, w, B, what = payload
+    # calibrate on a few rows, then size the sample to roughly 12 s
+    probe = min(64, A.shape[0])
+    t0 = time.perf_counter()
+    oracle.minplus_argmin(A[:probe], w, B)
+    rate = probe * B.shape[0] * B.shape[1] / (time.perf_counter() - t0)
+    rows = int(max(probe, min(A.shape[0], 12.0 * rate / (B.shape[0] * B.shape[1]))))
+    t0 = time.perf_counter()
+    oracle.minplus_argmin(A[:rows], w, B)
+    dt = time.perf_counter() - t0
+    upd = rows * B.shape[0] * B.shape[1]
+    return {"value": upd / dt / 1e9, "unit": "G cell-updates/s", "cores": threads, "kind": "oracle",
+            "sample": f"{what}: first {rows} of {A.shape[0]} output rows ({upd:.3g} cell updates, {dt:.1f} s)"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="cfg4", choices=["cfg0", "cfg2", "cfg3", "cfg4"])
+    ap.add_argument("--layers", type=int, default=64, help="cfg4 only: chain length")
+    ap.add_argument("--configs", type=int, default=0, help="override C of the workload")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference dispatch for rocprofv3 --pmc byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        log("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
+        sys.exit(2)
+
+    import torch
+    from paper_1802_04924_amd import Context, workloads as wl
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        sys.exit(1)
+    torch.cuda.set_device(0)
+
+    def dev(a):
+        return torch.from_numpy(a).cuda()
+
+    t_gen = time.perf_counter()
+    name = args.workload
+    if name == "cfg3":
+        C = args.configs or 256
+        batch = 4096
+        A, w, B = wl.config3(batch, C)
+        dA, dw, dB = dev(A), dev(w), dev(B)
+        out = torch.empty((batch, C, C), dtype=torch.int32, device="cuda")
+        arg = torch.empty_like(out)
+        updates = batch * C ** 3
+        workload = f"cfg3: {batch} independent {C}^3 min-plus+argmin products, values in [0,2^20], seed 3"
+        ctx = Context(0)
+
+        def step():
+            ctx.eliminate_node(dA, dw, dB, out=out, argmin=arg)
+            ctx.synchronize()
+        cpu_payload = ("minplus", (A[0], w[0], B[0], "product 0"))
+        if C <= 256:   # small products: time several whole products instead of rows of one
+            cpu_payload = ("minplus", (A[:64].reshape(64 * C, C), w[0], B[0], "rows of the first 64 A tables against B[0]"))
+    else:
+        if name == "cfg4":
+            p = wl.config4(args.layers, args.configs or 4096)
+        elif name == "cfg2":
+            p = wl.config2(args.configs or 512)
+        else:
+            p = wl.config0()
+        C = p["C"]
+        dtc, dts, dtx = dev(p["tc"]), dev(p["ts"]), dev(p["tx"])
+        n_elim = p["n_nodes"] - 2
+        updates = n_elim * C ** 3
+        workload = f"{p['name']}: {p['n_nodes']} nodes, {len(p['edges'])} edges, C={C}, {n_elim} node eliminations"
+        ctx = Context(0)
+        result = {}
+
+        def step():
+            result["cost"], result["S"] = ctx.search_graph(p["n_nodes"], p["edges"], C, dtc, dts, dtx, p["schedule"])
+        if name == "cfg4":
+            cpu_payload = ("minplus", (p["tx"][0], p["tc"][1] + p["ts"][1], p["tx"][1], "first node elimination"))
+        else:
+            p["updates"] = updates
+            cpu_payload = ("search", p)
+    log(f"[bench] inputs ready in {time.perf_counter() - t_gen:.1f} s: {workload}")
+
+    if args.calibrate_copy:
+        src = torch.zeros(1 << 28, dtype=torch.int32, device="cuda")      # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        torch.add(src, 1, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ctx.profile_enable(True)
+    ctx.profile_reset()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = ctx.profile_read()
+    ctx.profile_enable(False)
+    ms_per_step = dt / args.steps * 1e3
+    value = updates / (dt / args.steps) / 1e9
+
+    node_ms = prof["node_ms"] / max(prof["node_launches"], 1)
+    upd_per_launch = prof["node_cell_updates"] / max(prof["node_launches"], 1)
+    achieved = OPS_PER_UPDATE * upd_per_launch / (node_ms * 1e-3) / 1e12 if node_ms > 0 else 0.0
+    roofline = {"bound": "alu", "kernel": "minplus_kernel", "achieved": achieved, "peak": PEAK_INT32_TOPS,
+                "unit": "TOP/s (int32 add+min, 2 per cell update)", "frac": achieved / PEAK_INT32_TOPS,
+                "traffic": PMC_TRAFFIC_BYTES_C4096 if (name == "cfg4" and C == 4096) else None,
+                "launches": prof["node_launches"], "avg_launch_ms": node_ms,
+                "cell_updates_per_launch": upd_per_launch, "keyed_launches": prof["keyed_launches"],
+                "kernel_cell_updates_per_s_G": upd_per_launch / (node_ms * 1e-3) / 1e9 if node_ms > 0 else 0.0}
+
+    line = {"metric": "min-plus cell-updates/s over the whole strategy search", "value": value, "unit": "G cell-updates/s",
+            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int32", "data": "synthetic",
+            "config": {"workload": workload, "search_latency_ms": ms_per_step},
+            "roofline": roofline}
+    if name != "cfg3":
+        line["config"]["cost"] = int(result["cost"])
+    if not args.no_cpu:
+        log("[bench] timing the CPU oracle on a bounded sample ...")
+        line["cpu_baseline"] = cpu_baseline(*cpu_payload)
+    print(json.dumps(line), flush=True)
+    ctx.close()
+
+
+if __name__ == "__main__":
+    main()

@@ -29,16 +29,23 @@ __global__ __launch_bounds__(NT, KEYED ? 2 : 1) void minplus_kernel(const NodeAr
     __shared__ __attribute__((aligned(16))) uint32_t As[2][TK][TM];   // [stage][c][a]  (A transposed)
     __shared__ __attribute__((aligned(16))) uint32_t Bs[2][TK][TN];   // [stage][c][b]
 
-    // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous range of tiles
-    // so that tiles sharing rows of A (and all tiles of a small product) meet in one L2.
+    // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Give every XCD a
+    // contiguous range of logical ids, and walk the tiles of a product in panels of 8 tile rows,
+    // column by column: 64 consecutive ids (the tiles resident on one XCD at a time) then form an
+    // 8 x 8 block that shares 8 row strips of A and 8 column strips of B.
     uint32_t bid = blockIdx.x;
     const uint32_t total = gridDim.x;
     if ((total & 7u) == 0u) bid = (bid & 7u) * (total >> 3) + (bid >> 3);
     const int tiles = p.tilesM * p.tilesN;
     const int bi = bid / tiles;
     const int tl = bid - bi * tiles;
-    const int tmi = tl / p.tilesN;
-    const int tni = tl - tmi * p.tilesN;
+    constexpr int PANEL = 8;
+    const int panel = tl / (PANEL * p.tilesN);
+    const int prow0 = panel * PANEL;
+    const int prows = min(PANEL, p.tilesM - prow0);
+    const int within = tl - panel * PANEL * p.tilesN;
+    const int tni = within / prows;
+    const int tmi = prow0 + (within - tni * prows);
     const int a0 = tmi * TM, b0 = tni * TN;
     const int Ci = p.Ci, Cj = p.Cj, Ck = p.Ck;
 

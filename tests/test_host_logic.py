@@ -1,0 +1,109 @@
+"""Host-side logic of the library that runs without a GPU: the C ABI loads and exports every
+declared symbol, and the elimination scheduler agrees with the oracle's own implementation of
+the written schedule rule."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_1802_04924_amd import binding, workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_1802_04924_amd import build
+        build.build()
+    return binding.load()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "lwp.h")).read()
+    declared = set(re.findall(r"\b(lwp_[a-z_]+)\s*\(", header))
+    assert declared, "no declarations found"
+    assert declared == set(binding.EXPORTED)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_status_strings(lib):
+    assert lib.lwp_status_string(0) == b"ok"
+    assert b"overflow" in lib.lwp_status_string(-4)
+
+
+def graphs():
+    g = {
+        "chain6": (6, wl.chain_edges(6)),
+        "chain64": (64, wl.chain_edges(64)),
+        "single": (1, np.zeros((0, 2), np.int32)),
+        "two_isolated": (2, np.zeros((0, 2), np.int32)),
+        "parallel3": (2, np.array([(0, 1), (0, 1), (0, 1)], np.int32)),
+        "diamond_skip": (4, np.array([(0, 1), (0, 2), (1, 3), (2, 3), (0, 3)], np.int32)),
+        "backward_ids": (4, np.array([(3, 1), (1, 0), (0, 2)], np.int32)),
+        "two_chains": (6, np.array([(0, 1), (1, 2), (3, 4), (4, 5)], np.int32)),
+        "residual": (6, np.array([(0, 1), (1, 2), (2, 3), (1, 4), (4, 3), (3, 5), (3, 5)], np.int32)),
+    }
+    for m, s in ((1, 5), (3, 7), (10, 2)):
+        g[f"forkjoin{m}"] = wl.forkjoin_edges(m, s)
+    return g
+
+
+@pytest.mark.parametrize("name", sorted(graphs()))
+@pytest.mark.parametrize("schedule", [0, 1])
+def test_scheduler_matches_the_oracles_log(lib, name, schedule):
+    n, edges = graphs()[name]
+    plan = binding.plan_graph(n, edges, schedule)
+    tc, ts, tx = wl.random_tables(n, edges, 1, 0, (0, 1), (0, 1), (0, 1))
+    ref = oracle.search(n, edges, 1, tc, ts, tx, schedule)
+    assert np.array_equal(plan["steps"], ref["steps"])
+    assert plan["n_rounds"] == ref["n_rounds"]
+
+
+def test_scheduler_properties_on_paper_shaped_graphs(lib):
+    # chains and fork/join networks reduce to a final graph of two nodes (K = 2)
+    for n, edges in (graphs()["chain64"], graphs()["forkjoin10"]):
+        plan = binding.plan_graph(n, edges, 0)
+        assert plan["n_residual_nodes"] == 2
+        assert len(plan["steps"]) == len(edges) - 1
+    plan = binding.plan_graph(64, wl.chain_edges(64), 0)
+    assert plan["n_rounds"] == 6                      # tree order: 62 eliminations in 6 batched rounds
+    plan = binding.plan_graph(64, wl.chain_edges(64), 1)
+    assert plan["n_rounds"] == 62 and [s["j"] for s in plan["steps"]] == list(range(1, 63))
+    n, edges = wl.forkjoin_edges(10, 2)
+    plan = binding.plan_graph(n, edges, 0)
+    kinds = [int(s["kind"]) for s in plan["steps"]]
+    assert kinds.count(0) == 118 and kinds.count(1) == 70
+
+
+def test_scheduler_rejects_bad_graphs(lib):
+    def code(n, e, schedule=0):
+        with pytest.raises(binding.LwpError) as err:
+            binding.plan_graph(n, np.asarray(e, np.int32).reshape(-1, 2), schedule)
+        return err.value.code
+    assert code(3, [(0, 3)]) == binding.E_GRAPH              # endpoint out of range
+    assert code(3, [(1, 1)]) == binding.E_GRAPH              # self loop
+    assert code(3, [(0, 1), (1, 2), (2, 0)]) == binding.E_GRAPH   # cycle
+    assert code(4, [(0, 1), (0, 2), (0, 3)]) == binding.E_NOT_REDUCIBLE
+    assert code(0, []) == binding.E_INVAL
+    assert code(2, [(0, 1)], schedule=7) == binding.E_INVAL
+
+
+def test_workspace_size(lib):
+    # left fold over a chain: 2 ping-pong tables + one argmin table per elimination
+    C, n = 4096, 64
+    b = binding.search_workspace_bytes(n, wl.chain_edges(n), C, 1)
+    assert (62 + 2) * C * C * 4 <= b <= (62 + 2) * C * C * 4 + (1 << 22)
+    assert binding.search_workspace_bytes(3, np.array([(0, 1), (1, 2), (2, 0)], np.int32), 8, 0) == 0
+
+
+def test_no_gpu_means_loud_failure():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("GPU present")
+    with pytest.raises(RuntimeError):
+        binding.Context(0)
