@@ -136,3 +136,21 @@ def search(n_nodes, edges, C, tc, ts, tx, schedule=SCHEDULE_ROUNDS):
         raise OracleError(rc, "search")
     return {"cost": cost.value, "strategy": S, "steps": steps[:n_steps.value],
             "n_rounds": n_rounds.value}
+
+
+def build_cost_tables(layers, edges, configs, machine):
+    """Analytic cost model of Sec. 5.1 (readings in cost_model_oracle.c): returns (tc, ts, tx)."""
+    lib = _load()
+    layers = _c(layers).reshape(-1, 14)
+    edges = _c(edges).reshape(-1, 2)
+    configs = _c(configs).reshape(-1, 6)
+    m = np.array([machine["n_devices"], machine["flop_per_ns"], machine["byte_per_ns"],
+                  machine["invalid_cost"]], np.int32)
+    L, E, C = len(layers), len(edges), len(configs)
+    tc = np.empty((L, C), np.int32)
+    ts = np.empty((L, C), np.int32)
+    tx = np.empty((E, C, C), np.int32)
+    rc = lib.orc_build_cost_tables(_p(layers), L, _p(edges), E, _p(configs), C, _p(m), _p(tc), _p(ts), _p(tx))
+    if rc:
+        raise OracleError(rc, "build_cost_tables")
+    return tc, ts, tx

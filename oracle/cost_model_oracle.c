@@ -1,0 +1,155 @@
+/*
+ * CPU oracle of the analytic cost model (TEST INFRASTRUCTURE, not the product).
+ *
+ * Sec. 5.1 defines three cost functions; the paper measures t_c on the device and does not
+ * print formulas for t_x and t_s beyond "size of the data to be moved / known bandwidth".
+ * The readings implemented here (also listed in the design notes):
+ *
+ *   configuration (Sec. 4): degrees (n, h, w, c) over the sample, height, width and channel
+ *     dimensions of the layer's OUTPUT tensor, equal partitioning: part t of g over an extent
+ *     D is [floor(t*D/g), floor((t+1)*D/g)).  The d = n*h*w*c parts sit on devices
+ *     dev_offset + ((i_n*h + i_h)*w + i_w)*c + i_c.  A row is invalid for a layer if it is a
+ *     padding row (n == 0), if a degree exceeds the extent, if the block leaves the machine, or
+ *     if it splits height/width of a fully connected layer (Table 1).
+ *   t_c = round(F / (d * flop_per_ns)); F = forward + backward work: 3 * 2*N*Cout*Hout*Wout*Cin*kh*kw
+ *     for a convolution, 3 * 2*N*(Cin*Hin*Win)*Cout for a fully connected layer,
+ *     2 * N*Cout*Hout*Wout*kh*kw for pooling.  Invalid rows get machine.invalid_cost.
+ *   t_s = round(P * (r-1) / (r * byte_per_ns)); P = 4 bytes * (weights + biases), r = n*h*w the
+ *     number of parameter replicas (a channel split partitions the parameters; Sec. 3, Fig. 2).
+ *   t_x = round(bytes / byte_per_ns); bytes = 4 * sum over (producer part p, consumer part q) on
+ *     DIFFERENT devices of |T(p) ^ R(q)|, T(p) the producer's output part, R(q) the region of that
+ *     tensor the consumer part reads: its samples; all input channels (pooling: its own channels);
+ *     the window-expanded, clipped spatial range (fully connected: everything).
+ *   Rounding is half-up in integers: (num + den/2) / den.  Invalid rows/columns of t_x are 0.
+ *
+ * Absolute values are PARITY UNPINNED against the paper (its t_c are device measurements); the
+ * tests pin this file through closed forms and conservation properties instead.
+ */
+#include <stdint.h>
+#include <stdlib.h>
+
+#define ORC_OK 0
+#define ORC_E_INVAL (-1)
+#define ORC_E_OVERFLOW (-4)
+
+typedef struct { int32_t kind, N, Cin, Hin, Win, Cout, Hout, Wout, kh, kw, sh, sw, ph, pw; } orc_layer;
+typedef struct { int32_t n, h, w, c, dev_offset, pad; } orc_config;
+typedef struct { int32_t n_devices, flop_per_ns, byte_per_ns, invalid_cost; } orc_machine;
+
+enum { KIND_CONV = 0, KIND_POOL = 1, KIND_FC = 2 };
+
+static int64_t imin(int64_t a, int64_t b) { return a < b ? a : b; }
+static int64_t imax(int64_t a, int64_t b) { return a > b ? a : b; }
+static int64_t round_div(int64_t num, int64_t den) { return (num + den / 2) / den; }
+
+static int config_valid(const orc_layer *L, const orc_config *c, const orc_machine *m)
+{
+    if (c->n <= 0 || c->h <= 0 || c->w <= 0 || c->c <= 0) return 0;
+    if (c->n > L->N || c->c > L->Cout || c->h > L->Hout || c->w > L->Wout) return 0;
+    if (L->kind == KIND_FC && (c->h != 1 || c->w != 1)) return 0;
+    int64_t d = (int64_t)c->n * c->h * c->w * c->c;
+    if (c->dev_offset < 0 || c->dev_offset + d > m->n_devices) return 0;
+    return 1;
+}
+
+static void part(int t, int g, int D, int64_t *lo, int64_t *hi)
+{
+    *lo = (int64_t)t * D / g;
+    *hi = (int64_t)(t + 1) * D / g;
+}
+
+/* input range read by output range [o0,o1) of a window op with stride s, padding p, kernel k */
+static void window(int64_t o0, int64_t o1, int s, int p, int k, int Din, int64_t *lo, int64_t *hi)
+{
+    *lo = imax(0, o0 * s - p);
+    *hi = imin(Din, (o1 - 1) * s - p + k);
+}
+
+static int64_t overlap(int64_t a0, int64_t a1, int64_t b0, int64_t b1)
+{
+    return imax(0, imin(a1, b1) - imax(a0, b0));
+}
+
+int orc_build_cost_tables(const orc_layer *layers, int n_layers, const int32_t *edges, int n_edges,
+                          const orc_config *cfgs, int C, const orc_machine *m,
+                          int32_t *tc, int32_t *ts, int32_t *tx)
+{
+    if (n_layers <= 0 || C <= 0 || m->flop_per_ns <= 0 || m->byte_per_ns <= 0) return ORC_E_INVAL;
+    int overflow = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        const orc_layer *L = &layers[l];
+        int64_t F, P;
+        if (L->kind == KIND_CONV) {
+            F = 3 * 2 * (int64_t)L->N * L->Cout * L->Hout * L->Wout * L->Cin * L->kh * L->kw;
+            P = 4 * ((int64_t)L->Cout * L->Cin * L->kh * L->kw + L->Cout);
+        } else if (L->kind == KIND_FC) {
+            F = 3 * 2 * (int64_t)L->N * ((int64_t)L->Cin * L->Hin * L->Win) * L->Cout;
+            P = 4 * ((int64_t)L->Cout * L->Cin * L->Hin * L->Win + L->Cout);
+        } else if (L->kind == KIND_POOL) {
+            F = 2 * (int64_t)L->N * L->Cout * L->Hout * L->Wout * L->kh * L->kw;
+            P = 0;
+        } else return ORC_E_INVAL;
+        for (int r = 0; r < C; ++r) {
+            const orc_config *c = &cfgs[r];
+            int64_t vc = m->invalid_cost, vs = 0;
+            if (config_valid(L, c, m)) {
+                int64_t d = (int64_t)c->n * c->h * c->w * c->c;
+                int64_t rep = (int64_t)c->n * c->h * c->w;
+                vc = round_div(F, d * m->flop_per_ns);
+                vs = round_div(P * (rep - 1), rep * m->byte_per_ns);
+            }
+            if (vc > INT32_MAX || vs > INT32_MAX) overflow = 1;
+            tc[(size_t)l * C + r] = (int32_t)vc;
+            ts[(size_t)l * C + r] = (int32_t)vs;
+        }
+    }
+    for (int e = 0; e < n_edges; ++e) {
+        int pi = edges[2 * e], ci = edges[2 * e + 1];
+        if (pi < 0 || pi >= n_layers || ci < 0 || ci >= n_layers) return ORC_E_INVAL;
+        const orc_layer *Pl = &layers[pi], *Cl = &layers[ci];
+        /* the tensor on the edge: the producer's output is the consumer's input */
+        if (Pl->N != Cl->N || Pl->Cout != Cl->Cin || Pl->Hout != Cl->Hin || Pl->Wout != Cl->Win) return ORC_E_INVAL;
+#pragma omp parallel for schedule(dynamic, 4) reduction(| : overflow)
+        for (int a = 0; a < C; ++a) {
+            const orc_config *ca = &cfgs[a];
+            for (int b = 0; b < C; ++b) {
+                const orc_config *cb = &cfgs[b];
+                int64_t cells = 0;
+                if (config_valid(Pl, ca, m) && config_valid(Cl, cb, m)) {
+                    for (int pn = 0; pn < ca->n; ++pn) for (int ph = 0; ph < ca->h; ++ph)
+                    for (int pw = 0; pw < ca->w; ++pw) for (int pc = 0; pc < ca->c; ++pc) {
+                        int devp = ca->dev_offset + ((pn * ca->h + ph) * ca->w + pw) * ca->c + pc;
+                        int64_t tn0, tn1, th0, th1, tw0, tw1, tc0, tc1;
+                        part(pn, ca->n, Pl->N, &tn0, &tn1);
+                        part(ph, ca->h, Pl->Hout, &th0, &th1);
+                        part(pw, ca->w, Pl->Wout, &tw0, &tw1);
+                        part(pc, ca->c, Pl->Cout, &tc0, &tc1);
+                        for (int qn = 0; qn < cb->n; ++qn) for (int qh = 0; qh < cb->h; ++qh)
+                        for (int qw = 0; qw < cb->w; ++qw) for (int qc = 0; qc < cb->c; ++qc) {
+                            int devq = cb->dev_offset + ((qn * cb->h + qh) * cb->w + qw) * cb->c + qc;
+                            if (devq == devp) continue;          /* already local */
+                            int64_t rn0, rn1, rh0, rh1, rw0, rw1, rc0, rc1, o0, o1;
+                            part(qn, cb->n, Cl->N, &rn0, &rn1);
+                            if (Cl->kind == KIND_FC) {
+                                rc0 = 0; rc1 = Cl->Cin; rh0 = 0; rh1 = Cl->Hin; rw0 = 0; rw1 = Cl->Win;
+                            } else {
+                                if (Cl->kind == KIND_POOL) part(qc, cb->c, Cl->Cout, &rc0, &rc1);
+                                else { rc0 = 0; rc1 = Cl->Cin; }
+                                part(qh, cb->h, Cl->Hout, &o0, &o1);
+                                window(o0, o1, Cl->sh, Cl->ph, Cl->kh, Cl->Hin, &rh0, &rh1);
+                                part(qw, cb->w, Cl->Wout, &o0, &o1);
+                                window(o0, o1, Cl->sw, Cl->pw, Cl->kw, Cl->Win, &rw0, &rw1);
+                            }
+                            cells += overlap(tn0, tn1, rn0, rn1) * overlap(tc0, tc1, rc0, rc1) *
+                                     overlap(th0, th1, rh0, rh1) * overlap(tw0, tw1, rw0, rw1);
+                        }
+                    }
+                }
+                int64_t v = round_div(4 * cells, m->byte_per_ns);
+                if (v > INT32_MAX) overflow = 1;
+                tx[((size_t)e * C + a) * C + b] = (int32_t)v;
+            }
+        }
+    }
+    return overflow ? ORC_E_OVERFLOW : ORC_OK;
+}
