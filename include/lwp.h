@@ -141,7 +141,13 @@ typedef struct {
 
 /* Evaluates the analytic cost model for every layer and configuration (pair).
  * layers HOST [n_layers]; edges HOST [n_edges][2]; cfgs HOST [C]; outputs DEVICE
- * d_tc, d_ts [n_layers][C], d_tx [n_edges][C][C].  Blocking. */
+ * d_tc, d_ts [n_layers][C], d_tx [n_edges][C][C].  Blocking.
+ *   t_c = round(work / (n*h*w*c * flop_per_ns)), work = forward + backward operations of the layer;
+ *   t_s = round(4 * parameters * (r-1) / (r * byte_per_ns)), r = n*h*w parameter replicas;
+ *   t_x = round(4 * elements a consumer part reads from another device / byte_per_ns);
+ *   a configuration a layer cannot use gets t_c = invalid_cost, t_s = 0 and t_x = 0.
+ * Returns LWP_E_OVERFLOW if a cost exceeds int32 (the tables then hold truncated values),
+ * LWP_E_INVAL if a producer's output shape differs from its consumer's input shape. */
 lwp_status lwp_build_cost_tables(lwp_ctx *ctx, const lwp_layer *layers, int32_t n_layers,
                                  const int32_t *edges, int32_t n_edges, const lwp_config *cfgs,
                                  int32_t C, const lwp_machine *machine,

@@ -1,8 +1,192 @@
-// Analytic cost model (Sec. 5.1): t_c, t_s, t_x tables.
-#include "lwp.h"
+// Analytic cost model (Sec. 5.1): the three cost functions t_c(l,c), t_s(l,c), t_x(e,c_i,c_j)
+// evaluated for every layer / configuration (pair).  The paper measures t_c on the device and
+// derives t_x and t_s from "data to be moved / bandwidth"; this file uses closed forms:
+//   t_c = work / (degree * device rate), t_s = replicated parameter bytes / bandwidth,
+//   t_x = bytes the consumer's parts read from OTHER devices / bandwidth.
+// All arithmetic is integer (int64 intermediates, half-up rounding), so results are exact.
+//
+// t_x is not evaluated as a double loop over (producer part, consumer part).  Because the
+// producer's parts partition its output tensor, the volume read by all consumer parts is a
+// product of per-dimension sums; what stays on the same device is subtracted part by part
+// (a producer part shares a device with at most one consumer part).
+#include <hip/hip_runtime.h>
 
-extern "C" lwp_status lwp_build_cost_tables(lwp_ctx*, const lwp_layer*, int32_t, const int32_t*, int32_t,
-                                            const lwp_config*, int32_t, const lwp_machine*, int32_t*, int32_t*,
-                                            int32_t*) {
-    return LWP_E_INVAL;   // filled in by the table-builder kernels
+#include <string>
+#include <vector>
+
+#include "lwp.h"
+#include "lwp_internal.h"
+
+namespace {
+
+enum { KIND_CONV = 0, KIND_POOL = 1, KIND_FC = 2 };
+
+__host__ __device__ inline long long div_round(long long num, long long den) { return (num + den / 2) / den; }
+
+__device__ inline bool row_valid(const lwp_layer& L, const lwp_config& c, int n_devices) {
+    if (c.n <= 0 || c.h <= 0 || c.w <= 0 || c.c <= 0) return false;
+    if (c.n > L.N || c.c > L.Cout || c.h > L.Hout || c.w > L.Wout) return false;
+    if (L.kind == KIND_FC && (c.h != 1 || c.w != 1)) return false;
+    const long long d = (long long)c.n * c.h * c.w * c.c;
+    return c.dev_offset >= 0 && c.dev_offset + d <= n_devices;
+}
+
+struct Span { long long lo, hi; };
+__device__ inline Span split(int t, int g, int D) { return {(long long)t * D / g, (long long)(t + 1) * D / g}; }
+__device__ inline Span window(Span o, int s, int p, int k, int Din) {
+    const long long lo = o.lo * s - p, hi = (o.hi - 1) * s - p + k;
+    return {lo < 0 ? 0 : lo, hi > Din ? Din : hi};
+}
+__device__ inline long long common(Span a, Span b) {
+    const long long lo = a.lo > b.lo ? a.lo : b.lo, hi = a.hi < b.hi ? a.hi : b.hi;
+    return hi > lo ? hi - lo : 0;
+}
+// what consumer part index t (of g) reads along one spatial axis of its input
+__device__ inline Span spatial_need(const lwp_layer& L, bool height, int t, int g) {
+    if (L.kind == KIND_FC) return {0, height ? L.Hin : L.Win};
+    return height ? window(split(t, g, L.Hout), L.sh, L.ph, L.kh, L.Hin)
+                  : window(split(t, g, L.Wout), L.sw, L.pw, L.kw, L.Win);
+}
+
+__global__ void node_costs_kernel(const lwp_layer* __restrict__ layers, int n_layers,
+                                  const lwp_config* __restrict__ cfgs, int C, lwp_machine m,
+                                  int32_t* __restrict__ tc, int32_t* __restrict__ ts, int32_t* __restrict__ flag) {
+    const int x = blockIdx.x * blockDim.x + threadIdx.x;
+    if (x >= n_layers * C) return;
+    const lwp_layer L = layers[x / C];
+    const lwp_config c = cfgs[x % C];
+    long long work, params;
+    if (L.kind == KIND_CONV) {
+        work = 6ll * L.N * L.Cout * L.Hout * L.Wout * L.Cin * L.kh * L.kw;
+        params = 4ll * ((long long)L.Cout * L.Cin * L.kh * L.kw + L.Cout);
+    } else if (L.kind == KIND_FC) {
+        const long long fan_in = (long long)L.Cin * L.Hin * L.Win;
+        work = 6ll * L.N * fan_in * L.Cout;
+        params = 4ll * (fan_in * L.Cout + L.Cout);
+    } else {
+        work = 2ll * L.N * L.Cout * L.Hout * L.Wout * L.kh * L.kw;
+        params = 0;
+    }
+    long long vc = m.invalid_cost, vs = 0;
+    if (row_valid(L, c, m.n_devices)) {
+        const long long degree = (long long)c.n * c.h * c.w * c.c;
+        const long long replicas = (long long)c.n * c.h * c.w;
+        vc = div_round(work, degree * m.flop_per_ns);
+        vs = div_round(params * (replicas - 1), replicas * m.byte_per_ns);
+    }
+    if (vc > 2147483647ll || vs > 2147483647ll) atomicOr(flag, 1);
+    tc[x] = (int32_t)vc;
+    ts[x] = (int32_t)vs;
+}
+
+__global__ void edge_costs_kernel(const lwp_layer* __restrict__ layers, const int32_t* __restrict__ edges,
+                                  const lwp_config* __restrict__ cfgs, int C, lwp_machine m,
+                                  int32_t* __restrict__ tx, int32_t* __restrict__ flag) {
+    const int e = blockIdx.z;
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;     // consumer configuration
+    const int a = blockIdx.y;                                // producer configuration
+    if (b >= C) return;
+    const lwp_layer P = layers[edges[2 * e]];
+    const lwp_layer Q = layers[edges[2 * e + 1]];
+    const lwp_config ca = cfgs[a], cb = cfgs[b];
+    long long cells = 0;
+    if (row_valid(P, ca, m.n_devices) && row_valid(Q, cb, m.n_devices)) {
+        // volume read by all consumer parts, wherever it lives
+        long long vol_c = (Q.kind == KIND_POOL) ? Q.Cin : (long long)cb.c * Q.Cin;
+        long long vol_h = 0, vol_w = 0;
+        for (int t = 0; t < cb.h; ++t) { const Span s = spatial_need(Q, true, t, cb.h); vol_h += s.hi - s.lo; }
+        for (int t = 0; t < cb.w; ++t) { const Span s = spatial_need(Q, false, t, cb.w); vol_w += s.hi - s.lo; }
+        const long long everything = (long long)Q.N * vol_c * vol_h * vol_w;
+        // minus what a consumer part finds on its own device
+        long long local = 0;
+        const int da = ca.n * ca.h * ca.w * ca.c, db = cb.n * cb.h * cb.w * cb.c;
+        for (int p = 0; p < da; ++p) {
+            const int q = ca.dev_offset + p - cb.dev_offset;
+            if (q < 0 || q >= db) continue;
+            int r = p;
+            const int pc = r % ca.c; r /= ca.c;
+            const int pw = r % ca.w; r /= ca.w;
+            const int ph = r % ca.h; const int pn = r / ca.h;
+            r = q;
+            const int qc = r % cb.c; r /= cb.c;
+            const int qw = r % cb.w; r /= cb.w;
+            const int qh = r % cb.h; const int qn = r / cb.h;
+            const Span need_c = (Q.kind == KIND_POOL) ? split(qc, cb.c, Q.Cout) : Span{0, Q.Cin};
+            local += common(split(pn, ca.n, P.N), split(qn, cb.n, Q.N)) *
+                     common(split(pc, ca.c, P.Cout), need_c) *
+                     common(split(ph, ca.h, P.Hout), spatial_need(Q, true, qh, cb.h)) *
+                     common(split(pw, ca.w, P.Wout), spatial_need(Q, false, qw, cb.w));
+        }
+        cells = everything - local;
+    }
+    const long long v = div_round(4 * cells, m.byte_per_ns);
+    if (v > 2147483647ll) atomicOr(flag, 1);
+    tx[((size_t)e * C + a) * C + b] = (int32_t)v;
+}
+
+}  // namespace
+
+extern "C" lwp_status lwp_build_cost_tables(lwp_ctx* ctx, const lwp_layer* layers, int32_t n_layers,
+                                            const int32_t* edges, int32_t n_edges, const lwp_config* cfgs,
+                                            int32_t C, const lwp_machine* machine,
+                                            int32_t* d_tc, int32_t* d_ts, int32_t* d_tx) {
+    if (!ctx) return LWP_E_INVAL;
+    if (lwp_status rc = lwp::ctx_enter(ctx)) return rc;
+    if (!layers || !cfgs || !machine || !d_tc || !d_ts || (n_edges > 0 && (!edges || !d_tx)))
+        return lwp::ctx_fail(ctx, LWP_E_INVAL, "null pointer");
+    if (n_layers < 1 || n_edges < 0 || C < 1 || C > 65535)
+        return lwp::ctx_fail(ctx, LWP_E_INVAL, "bad sizes");
+    if (machine->n_devices < 1 || machine->flop_per_ns < 1 || machine->byte_per_ns < 1 || machine->invalid_cost < 0)
+        return lwp::ctx_fail(ctx, LWP_E_INVAL, "machine constants must be positive");
+    for (int32_t l = 0; l < n_layers; ++l) {
+        const lwp_layer& L = layers[l];
+        if (L.kind < KIND_CONV || L.kind > KIND_FC) return lwp::ctx_fail(ctx, LWP_E_INVAL, "unknown layer kind");
+        if (L.N < 1 || L.Cin < 1 || L.Hin < 1 || L.Win < 1 || L.Cout < 1 || L.Hout < 1 || L.Wout < 1 || L.kh < 1 ||
+            L.kw < 1 || L.sh < 1 || L.sw < 1 || L.ph < 0 || L.pw < 0)
+            return lwp::ctx_fail(ctx, LWP_E_INVAL, "layer extents must be positive");
+    }
+    for (int32_t e = 0; e < n_edges; ++e) {
+        const int32_t p = edges[2 * e], q = edges[2 * e + 1];
+        if (p < 0 || p >= n_layers || q < 0 || q >= n_layers || p == q)
+            return lwp::ctx_fail(ctx, LWP_E_GRAPH, "edge endpoint out of range");
+        const lwp_layer &P = layers[p], &Q = layers[q];
+        if (P.N != Q.N || P.Cout != Q.Cin || P.Hout != Q.Hin || P.Wout != Q.Win)
+            return lwp::ctx_fail(ctx, LWP_E_INVAL, "producer output and consumer input shapes differ");
+    }
+    hipStream_t st = lwp::ctx_stream(ctx);
+    const size_t bl = (size_t)n_layers * sizeof(lwp_layer), bc = (size_t)C * sizeof(lwp_config),
+                 be = (size_t)(n_edges > 0 ? n_edges : 1) * 2 * sizeof(int32_t);
+    char* d = nullptr;
+    const size_t off_c = (bl + 255) / 256 * 256, off_e = off_c + (bc + 255) / 256 * 256,
+                 off_f = off_e + (be + 255) / 256 * 256;
+    if (hipMalloc(&d, off_f + 256) != hipSuccess) { (void)hipGetLastError(); return lwp::ctx_fail(ctx, LWP_E_NOMEM, "descriptor upload buffer"); }
+    lwp_status result = LWP_OK;
+    int32_t flag = 0;
+    hipError_t herr = hipSuccess;
+    auto ok = [&](hipError_t e) { if (e != hipSuccess && herr == hipSuccess) herr = e; return e == hipSuccess; };
+    if (ok(hipMemcpyAsync(d, layers, bl, hipMemcpyHostToDevice, st)) &&
+        ok(hipMemcpyAsync(d + off_c, cfgs, bc, hipMemcpyHostToDevice, st)) &&
+        (n_edges == 0 || ok(hipMemcpyAsync(d + off_e, edges, (size_t)n_edges * 2 * sizeof(int32_t), hipMemcpyHostToDevice, st))) &&
+        ok(hipMemsetAsync(d + off_f, 0, sizeof(int32_t), st))) {
+        const lwp_layer* dl = reinterpret_cast<const lwp_layer*>(d);
+        const lwp_config* dc = reinterpret_cast<const lwp_config*>(d + off_c);
+        const int32_t* de = reinterpret_cast<const int32_t*>(d + off_e);
+        int32_t* df = reinterpret_cast<int32_t*>(d + off_f);
+        const int total = n_layers * C;
+        hipLaunchKernelGGL(node_costs_kernel, dim3((total + 255) / 256), dim3(256), 0, st, dl, n_layers, dc, C, *machine,
+                           d_tc, d_ts, df);
+        ok(hipGetLastError());
+        for (int32_t e0 = 0; e0 < n_edges && herr == hipSuccess; e0 += 65535) {
+            const int32_t ne = (n_edges - e0) < 65535 ? (n_edges - e0) : 65535;
+            hipLaunchKernelGGL(edge_costs_kernel, dim3((C + 255) / 256, C, ne), dim3(256), 0, st, dl, de + 2 * (size_t)e0, dc,
+                               C, *machine, d_tx + (size_t)e0 * C * C, df);
+            ok(hipGetLastError());
+        }
+        ok(hipMemcpyAsync(&flag, df, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    }
+    ok(hipStreamSynchronize(st));
+    (void)hipFree(d);
+    if (herr != hipSuccess) return lwp::ctx_fail(ctx, LWP_E_HIP, hipGetErrorString(herr));
+    if (flag) result = lwp::ctx_fail(ctx, LWP_E_OVERFLOW, "a cost does not fit int32 nanoseconds");
+    return result;
 }

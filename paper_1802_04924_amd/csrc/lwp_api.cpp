@@ -9,6 +9,7 @@
 #include <vector>
 
 #include "lwp.h"
+#include "lwp_internal.h"
 #include "lwp_kernels.h"
 #include "lwp_plan.h"
 
@@ -209,6 +210,12 @@ WsLayout layout_workspace(const Plan& plan, const Layout& L, int32_t n_nodes, in
 }
 
 }  // namespace
+
+namespace lwp {
+hipStream_t ctx_stream(lwp_ctx* ctx) { return ctx->stream; }
+lwp_status ctx_enter(lwp_ctx* ctx) { return check_ctx(ctx); }
+lwp_status ctx_fail(lwp_ctx* ctx, lwp_status s, const char* why) { return fail(ctx, s, why); }
+}  // namespace lwp
 
 // ================================================================================================
 extern "C" {
