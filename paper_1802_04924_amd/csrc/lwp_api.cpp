@@ -21,6 +21,8 @@ struct lwp_ctx {
     std::string err;
     char* ws = nullptr;        // device workspace
     size_t ws_bytes = 0;
+    char* pin = nullptr;       // pinned host staging (descriptor upload, small read-backs)
+    size_t pin_bytes = 0;
     bool profiling = false;
     struct Timed { hipEvent_t a, b; int kind; int64_t work; bool keyed; };
     std::vector<Timed> timed;
@@ -62,20 +64,34 @@ lwp_status ensure_workspace(lwp_ctx* ctx, size_t bytes) {
     return LWP_OK;
 }
 
+lwp_status ensure_pinned(lwp_ctx* ctx, size_t bytes) {
+    if (bytes <= ctx->pin_bytes) return LWP_OK;
+    LWP_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    if (ctx->pin) { LWP_HIP(ctx, hipHostFree(ctx->pin)); ctx->pin = nullptr; ctx->pin_bytes = 0; }
+    void* p = nullptr;
+    bytes = align_up(bytes, 1 << 16);
+    hipError_t e = hipHostMalloc(&p, bytes, hipHostMallocDefault);
+    if (e != hipSuccess) { (void)hipGetLastError(); return fail(ctx, LWP_E_NOMEM, std::string("pinned host buffer: ") + hipGetErrorString(e)); }
+    ctx->pin = static_cast<char*>(p);
+    ctx->pin_bytes = bytes;
+    return LWP_OK;
+}
+
 struct Range { int64_t lo, hi; };
 bool fits(int64_t v) { return v >= kI32Min && v <= kI32Max; }
 
-// Picks the key width for one product from the ranges of A + w and B (see minplus.hip).
-// Returns 0 when the packed-key arithmetic does not apply.
-int choose_tb(int64_t spread, int32_t Cj) {
-    int tb_max = 0;
-    for (int tb = 17; tb >= 5; --tb)
-        if (spread <= (1LL << (32 - tb)) - 2) { tb_max = tb; break; }
-    if (!tb_max) return 0;
-    int tb_single = 17;
-    for (int tb = 5; tb <= 17; ++tb)
-        if ((((1 << tb) - 1) / 16) * 16 >= Cj) { tb_single = tb; break; }
-    return std::min(tb_max, tb_single);
+// Spread the packed-key arithmetic must represent for one product (see minplus.hip): re-based
+// A + w, clamped just above the largest possible result where that is tighter, plus re-based B.
+int64_t keyed_spread(Range rA, Range rw, Range rB) {
+    const int64_t a_max = rA.hi + rw.hi - (rA.lo + rw.lo);
+    const int64_t out_max = (rA.hi - rA.lo) + (rB.hi - rB.lo);
+    return std::min(a_max, out_max + 1) + (rB.hi - rB.lo);
+}
+
+// 64 x 64 tiles when 128 x 128 tiles would leave most of the 256 compute units without a workgroup.
+bool want_small_tiles(int32_t Ci, int32_t Ck, int64_t batch) {
+    const int64_t big = (int64_t)((Ci + kTileLarge - 1) / kTileLarge) * ((Ck + kTileLarge - 1) / kTileLarge) * batch;
+    return big < 256;
 }
 
 // Timing of one launch when profiling is on.
@@ -181,8 +197,15 @@ Layout plan_buffers(const Plan& plan, int32_t n_edges) {
     return L;
 }
 
+// Device workspace of one search.  The descriptor block is mirrored in pinned host memory and
+// uploaded with a single copy; `head` = {overflow flag, pad, [min,max] per table} is read back with
+// a single copy.  Tables with a range: input edges, w of every node, output of every node
+// elimination, output of every edge-sum group.
 struct WsLayout {
-    size_t w, stats, flag, node_desc, edge_desc, src_ptrs, pair_desc, singles, undo, keys, result, args, slots, total;
+    size_t w, head, keys, result, args, slots, total;
+    size_t desc, desc_bytes;                                   // descriptor block
+    size_t node_desc, edge_desc, src_ptrs, pair_desc, singles, undo;   // offsets inside the block
+    int32_t n_ranges;
 };
 
 WsLayout layout_workspace(const Plan& plan, const Layout& L, int32_t n_nodes, int32_t n_edges, int32_t C) {
@@ -192,17 +215,23 @@ WsLayout layout_workspace(const Plan& plan, const Layout& L, int32_t n_nodes, in
     const size_t CC = (size_t)C * C * sizeof(int32_t);
     size_t n_src = 0;
     for (auto& g : L.group_src) n_src += g.size();
+    o.n_ranges = n_edges + n_nodes + plan.n_node_steps + (int32_t)L.groups.size();
     o.w = put((size_t)n_nodes * C * sizeof(int32_t));
-    o.stats = put(2 * (size_t)(n_edges + n_nodes) * sizeof(int32_t));
-    o.flag = put(sizeof(int32_t));
-    o.node_desc = put(std::max<size_t>(1, plan.n_node_steps) * sizeof(NodeDesc));
-    o.edge_desc = put(std::max<size_t>(1, L.groups.size()) * sizeof(EdgeDesc));
-    o.src_ptrs = put(std::max<size_t>(1, n_src) * sizeof(void*));
-    o.pair_desc = put(std::max<size_t>(1, plan.pairs.size()) * sizeof(PairDesc));
-    o.singles = put(std::max<size_t>(1, plan.singles.size()) * sizeof(int32_t));
-    o.undo = put(std::max<size_t>(1, plan.n_node_steps) * sizeof(UndoDesc));
+    o.head = put((2 + 2 * (size_t)o.n_ranges) * sizeof(int32_t));
     o.keys = put(std::max<size_t>(1, plan.pairs.size() + plan.singles.size()) * sizeof(unsigned long long));
     o.result = put((2 + (size_t)n_nodes) * sizeof(int32_t));
+    {
+        size_t b = 0;
+        auto sub = [&](size_t bytes) { size_t at = b; b = align_up(b + bytes, 16); return at; };
+        o.node_desc = sub((size_t)plan.n_node_steps * sizeof(NodeDesc));
+        o.edge_desc = sub(L.groups.size() * sizeof(EdgeDesc));
+        o.src_ptrs = sub(n_src * sizeof(void*));
+        o.pair_desc = sub(plan.pairs.size() * sizeof(PairDesc));
+        o.singles = sub(plan.singles.size() * sizeof(int32_t));
+        o.undo = sub((size_t)plan.n_node_steps * sizeof(UndoDesc));
+        o.desc_bytes = std::max<size_t>(b, 16);
+    }
+    o.desc = put(o.desc_bytes);
     o.args = put((size_t)plan.n_node_steps * CC);
     o.slots = put((size_t)L.n_slots * CC);
     o.total = off;
@@ -253,6 +282,7 @@ void lwp_destroy(lwp_ctx* ctx) {
     (void)hipStreamSynchronize(ctx->stream);
     for (auto& t : ctx->timed) { hipEventDestroy(t.a); hipEventDestroy(t.b); }
     if (ctx->ws) (void)hipFree(ctx->ws);
+    if (ctx->pin) (void)hipHostFree(ctx->pin);
     delete ctx;
 }
 
@@ -295,18 +325,21 @@ lwp_status lwp_eliminate_node(lwp_ctx* ctx, int32_t batch, int32_t Ci, int32_t C
     if (!d_A || !d_w || !d_B || !d_out) return fail(ctx, LWP_E_INVAL, "null table pointer");
     if (((uintptr_t)d_A | (uintptr_t)d_w | (uintptr_t)d_B | (uintptr_t)d_out | (uintptr_t)d_argmin) & 3)
         return fail(ctx, LWP_E_INVAL, "table pointer not 4-byte aligned");
-    const int64_t tilesM = (Ci + kTileM - 1) / kTileM, tilesN = (Ck + kTileN - 1) / kTileN;
+    const bool small = want_small_tiles(Ci, Ck, batch);
+    const int tile = small ? kTileSmall : kTileLarge;
+    const int64_t tilesM = (Ci + tile - 1) / tile, tilesN = (Ck + tile - 1) / tile;
     if (tilesM * tilesN * batch > 0x7fffffffLL) return fail(ctx, LWP_E_INVAL, "too many output tiles");
 
     // value ranges of A, w, B over the whole batch
     if (lwp_status s = ensure_workspace(ctx, 4096)) return s;
+    if (lwp_status s = ensure_pinned(ctx, 4096)) return s;
     int32_t* d_stats = reinterpret_cast<int32_t*>(ctx->ws);
-    LWP_HIP(ctx, launch_init_ranges(d_stats, 3, ctx->stream));
+    LWP_HIP(ctx, launch_init_workspace(d_stats, 3, nullptr, nullptr, 0, ctx->stream));
     LWP_HIP(ctx, launch_ranges(d_A, 1, (int64_t)batch * Ci * Cj, d_stats, ctx->stream));
     LWP_HIP(ctx, launch_ranges(d_w, 1, (int64_t)batch * Cj, d_stats + 2, ctx->stream));
     LWP_HIP(ctx, launch_ranges(d_B, 1, (int64_t)batch * Cj * Ck, d_stats + 4, ctx->stream));
-    int32_t st[6];
-    LWP_HIP(ctx, hipMemcpyAsync(st, d_stats, sizeof(st), hipMemcpyDeviceToHost, ctx->stream));
+    int32_t* st = reinterpret_cast<int32_t*>(ctx->pin);
+    LWP_HIP(ctx, hipMemcpyAsync(st, d_stats, 6 * sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
     LWP_HIP(ctx, hipStreamSynchronize(ctx->stream));
     const Range rA{st[0], st[1]}, rw{st[2], st[3]}, rB{st[4], st[5]};
     if (!fits(rA.lo + rw.lo + rB.lo) || !fits(rA.hi + rw.hi + rB.hi) || !fits(rA.lo + rw.lo) || !fits(rA.hi + rw.hi))
@@ -315,16 +348,15 @@ lwp_status lwp_eliminate_node(lwp_ctx* ctx, int32_t batch, int32_t Ci, int32_t C
     NodeArgs a{};
     a.descs = nullptr;
     a.base.A = d_A; a.base.w = d_w; a.base.B = d_B; a.base.out = d_out; a.base.arg = d_argmin;
-    a.base.offA = (int32_t)(rA.lo + rw.lo);
-    a.base.offB = (int32_t)rB.lo;
-    const int64_t spread = (rA.hi + rw.hi - (rA.lo + rw.lo)) + (rB.hi - rB.lo);
-    a.base.tb = choose_tb(spread, Cj);
+    a.base.loA = (int32_t)rA.lo; a.base.hiA = (int32_t)rA.hi; a.base.loW = (int32_t)rw.lo; a.base.hiW = (int32_t)rw.hi;
+    a.base.loB = (int32_t)rB.lo; a.base.hiB = (int32_t)rB.hi;
+    const bool keyed = keyed_spread(rA, rw, rB) <= kKeyedMaxSpread;
     a.sA = (int64_t)Ci * Cj; a.sw = Cj; a.sB = (int64_t)Cj * Ck; a.sO = (int64_t)Ci * Ck;
     a.Ci = Ci; a.Cj = Cj; a.Ck = Ck; a.batch = batch;
     a.tilesM = (int32_t)tilesM; a.tilesN = (int32_t)tilesN;
     {
-        ScopedTimer tm(ctx, 0, (int64_t)batch * Ci * Cj * Ck, a.base.tb > 0);
-        LWP_HIP(ctx, launch_minplus(a, a.base.tb > 0, ctx->stream));
+        ScopedTimer tm(ctx, 0, (int64_t)batch * Ci * Cj * Ck, keyed);
+        LWP_HIP(ctx, launch_minplus(a, keyed, small, ctx->stream));
     }
     return LWP_OK;
 }
@@ -385,46 +417,78 @@ lwp_status lwp_search_graph(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, cons
     const Layout L = plan_buffers(plan, n_edges);
     const WsLayout W = layout_workspace(plan, L, n_nodes, n_edges, C);
     if (lwp_status s = ensure_workspace(ctx, W.total)) return s;
+    const size_t head_in_bytes = (2 + 2 * (size_t)(n_edges + n_nodes)) * sizeof(int32_t);
+    const size_t pin_head = 0, pin_desc = align_up(head_in_bytes, 256), pin_result = pin_desc + align_up(W.desc_bytes, 256);
+    if (lwp_status s = ensure_pinned(ctx, pin_result + (2 + (size_t)n_nodes) * sizeof(int32_t))) return s;
     char* ws = ctx->ws;
     hipStream_t st = ctx->stream;
     const int64_t CC = (int64_t)C * C;
     int32_t* d_w = reinterpret_cast<int32_t*>(ws + W.w);
-    int32_t* d_stats = reinterpret_cast<int32_t*>(ws + W.stats);
-    int32_t* d_flag = reinterpret_cast<int32_t*>(ws + W.flag);
+    int32_t* d_head = reinterpret_cast<int32_t*>(ws + W.head);
+    int32_t* d_flag = d_head;
+    int32_t* d_stats = d_head + 2;
     int32_t* d_args = reinterpret_cast<int32_t*>(ws + W.args);
     int32_t* d_slots = reinterpret_cast<int32_t*>(ws + W.slots);
+    unsigned long long* d_keys = reinterpret_cast<unsigned long long*>(ws + W.keys);
+    int32_t* d_result = reinterpret_cast<int32_t*>(ws + W.result);
+    const int32_t n_comp = (int32_t)(plan.pairs.size() + plan.singles.size());
     auto table_ptr = [&](const TableRef& r) -> const int32_t* {
         return r.is_slot ? d_slots + (int64_t)r.id * CC : d_tx + (int64_t)r.id * CC;
     };
+    // index of the range pair of: input edge e | w of node v | output of node step | output of group
+    const int32_t rng_w0 = n_edges, rng_node0 = n_edges + n_nodes, rng_group0 = rng_node0 + plan.n_node_steps;
 
-    // 1. w = t_c + t_s, and the value range of every input table
-    LWP_HIP(ctx, hipMemsetAsync(d_flag, 0, sizeof(int32_t), st));
-    LWP_HIP(ctx, launch_add_vectors(d_tc, d_ts, d_w, (int64_t)n_nodes * C, d_flag, st));
-    LWP_HIP(ctx, launch_init_ranges(d_stats, n_edges + n_nodes, st));
+    // 1. w = t_c + t_s with its ranges, and the range of every input table; one read-back
+    LWP_HIP(ctx, launch_init_workspace(d_stats, W.n_ranges, d_flag, d_keys, n_comp, st));
+    LWP_HIP(ctx, launch_add_vectors(d_tc, d_ts, d_w, n_nodes, C, d_stats + 2 * (int64_t)rng_w0, d_flag, st));
     LWP_HIP(ctx, launch_ranges(d_tx, n_edges, CC, d_stats, st));
-    LWP_HIP(ctx, launch_ranges(d_w, n_nodes, C, d_stats + 2 * (int64_t)n_edges, st));
-    std::vector<int32_t> stats(2 * (size_t)(n_edges + n_nodes) + 1);
-    LWP_HIP(ctx, hipMemcpyAsync(stats.data(), d_stats, 2 * (size_t)(n_edges + n_nodes) * sizeof(int32_t),
-                                hipMemcpyDeviceToHost, st));
-    LWP_HIP(ctx, hipMemcpyAsync(&stats.back(), d_flag, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    int32_t* h_head = reinterpret_cast<int32_t*>(ctx->pin + pin_head);
+    LWP_HIP(ctx, hipMemcpyAsync(h_head, d_head, head_in_bytes, hipMemcpyDeviceToHost, st));
     LWP_HIP(ctx, hipStreamSynchronize(st));
-    if (stats.back()) return fail(ctx, LWP_E_OVERFLOW, "t_c + t_s leaves int32");
+    if (h_head[0]) return fail(ctx, LWP_E_OVERFLOW, "t_c + t_s leaves int32");
+    const int32_t* stats = h_head + 2;
 
-    // 2. propagate ranges through the plan: every sum any kernel forms must fit int32
+    // 2. propagate ranges through the plan: every sum any kernel forms must fit int32.  Descriptors
+    //    are written straight into the pinned mirror of the device block.
+    char* hb = ctx->pin + pin_desc;
+    NodeDesc* nd = reinterpret_cast<NodeDesc*>(hb + W.node_desc);
+    EdgeDesc* ed = reinterpret_cast<EdgeDesc*>(hb + W.edge_desc);
+    const int32_t** src_ptrs = reinterpret_cast<const int32_t**>(hb + W.src_ptrs);
+    PairDesc* pd = reinterpret_cast<PairDesc*>(hb + W.pair_desc);
+    int32_t* h_singles = reinterpret_cast<int32_t*>(hb + W.singles);
+    UndoDesc* ud = reinterpret_cast<UndoDesc*>(hb + W.undo);
+    char* db = ws + W.desc;
+    const NodeDesc* d_nd = reinterpret_cast<const NodeDesc*>(db + W.node_desc);
+    const EdgeDesc* d_ed = reinterpret_cast<const EdgeDesc*>(db + W.edge_desc);
+    const int32_t* const* d_src = reinterpret_cast<const int32_t* const*>(db + W.src_ptrs);
+    const PairDesc* d_pd = reinterpret_cast<const PairDesc*>(db + W.pair_desc);
+    const int32_t* d_singles = reinterpret_cast<const int32_t*>(db + W.singles);
+    const UndoDesc* d_ud = reinterpret_cast<const UndoDesc*>(db + W.undo);
+
     std::vector<Range> er(n_edges), wr(n_nodes);
-    for (int32_t e = 0; e < n_edges; ++e) er[e] = {stats[2 * e], stats[2 * e + 1]};
-    for (int32_t v = 0; v < n_nodes; ++v) wr[v] = {stats[2 * (n_edges + v)], stats[2 * (n_edges + v) + 1]};
-    std::vector<NodeDesc> nd;
-    std::vector<UndoDesc> ud;
-    std::vector<char> nd_keyed;
-    nd.reserve(plan.n_node_steps); ud.reserve(plan.n_node_steps);
+    std::vector<int32_t> erng(n_edges);          // range-pair index of the edge's current table
+    for (int32_t e = 0; e < n_edges; ++e) { er[e] = {stats[2 * e], stats[2 * e + 1]}; erng[e] = e; }
+    for (int32_t v = 0; v < n_nodes; ++v) wr[v] = {stats[2 * (rng_w0 + v)], stats[2 * (rng_w0 + v) + 1]};
+    std::vector<char> nd_keyed(plan.n_node_steps);
     {
-        size_t ni = 0;
-        for (const lwp_step& s : plan.steps) {
-            if (s.kind == 1) {
-                Range r{er[s.e1].lo + er[s.e2].lo, er[s.e1].hi + er[s.e2].hi};
+        size_t ni = 0, gi = 0, nsrc = 0, t = 0;
+        const size_t n = plan.steps.size();
+        while (t < n) {
+            const lwp_step& s = plan.steps[t];
+            if (s.kind == 1) {                  // one group = all steps adding into the same kept edge
+                const auto& g = L.groups[gi];
+                Range r = er[g.keep];
+                for (int32_t o : g.others) r = {r.lo + er[o].lo, r.hi + er[o].hi};
                 if (!fits(r.lo) || !fits(r.hi)) return fail(ctx, LWP_E_OVERFLOW, "sum of parallel edge tables may leave int32");
-                er[s.e1] = r;
+                er[g.keep] = r;
+                erng[g.keep] = rng_group0 + (int32_t)gi;
+                ed[gi].out = d_slots + (int64_t)L.group_out_slot[gi] * CC;
+                ed[gi].rngOut = d_stats + 2 * (int64_t)erng[g.keep];
+                ed[gi].first_src = (int32_t)nsrc;
+                ed[gi].n_src = (int32_t)L.group_src[gi].size();
+                for (auto& r2 : L.group_src[gi]) src_ptrs[nsrc++] = table_ptr(r2);
+                t += g.others.size();
+                ++gi;
                 continue;
             }
             const Range rA = er[s.e1], rw = wr[s.j], rB = er[s.e2];
@@ -434,58 +498,40 @@ lwp_status lwp_search_graph(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, cons
             d.A = table_ptr(L.node_A[ni]); d.w = d_w + (int64_t)s.j * C; d.B = table_ptr(L.node_B[ni]);
             d.out = d_slots + (int64_t)L.node_out_slot[ni] * CC;
             d.arg = d_args + (int64_t)ni * CC;
-            d.offA = (int32_t)(rA.lo + rw.lo); d.offB = (int32_t)rB.lo;
-            d.tb = choose_tb((rA.hi + rw.hi - (rA.lo + rw.lo)) + (rB.hi - rB.lo), C);
-            nd.push_back(d); nd_keyed.push_back(d.tb > 0);
-            ud.push_back({d.arg, s.j, s.i, s.k, s.round});
+            d.loA = (int32_t)rA.lo; d.hiA = (int32_t)rA.hi; d.loW = (int32_t)rw.lo; d.hiW = (int32_t)rw.hi;
+            d.loB = (int32_t)rB.lo; d.hiB = (int32_t)rB.hi;
+            d.rngA = d_stats + 2 * (int64_t)erng[s.e1];
+            d.rngB = d_stats + 2 * (int64_t)erng[s.e2];
+            d.rngOut = d_stats + 2 * (int64_t)(rng_node0 + (int32_t)ni);
+            nd[ni] = d;
+            nd_keyed[ni] = keyed_spread(rA, rw, rB) <= kKeyedMaxSpread;
+            ud[ni] = {d.arg, s.j, s.i, s.k, s.round};
             // any fixed c bounds the minimum from above; take the c with the smallest w
             er[s.e1] = {rA.lo + rw.lo + rB.lo, rA.hi + rw.lo + rB.hi};
-            ++ni;
+            erng[s.e1] = rng_node0 + (int32_t)ni;
+            ++ni; ++t;
         }
     }
     int64_t total_hi = 0, total_lo = 0;
-    for (auto& p : plan.pairs) {
-        const int64_t lo = wr[p.src].lo + er[p.edge].lo + wr[p.dst].lo, hi = wr[p.src].hi + er[p.edge].hi + wr[p.dst].hi;
-        if (!fits(lo) || !fits(hi) || !fits(wr[p.src].hi + er[p.edge].hi) || !fits(wr[p.src].lo + er[p.edge].lo))
+    for (size_t q = 0; q < plan.pairs.size(); ++q) {
+        const auto& pr = plan.pairs[q];
+        const int64_t lo = wr[pr.src].lo + er[pr.edge].lo + wr[pr.dst].lo, hi = wr[pr.src].hi + er[pr.edge].hi + wr[pr.dst].hi;
+        if (!fits(lo) || !fits(hi) || !fits(wr[pr.src].hi + er[pr.edge].hi) || !fits(wr[pr.src].lo + er[pr.edge].lo))
             return fail(ctx, LWP_E_OVERFLOW, "the residual-graph sum may leave int32");
-        total_lo += lo; total_hi += wr[p.src].lo + er[p.edge].hi + wr[p.dst].lo;
+        total_lo += lo; total_hi += wr[pr.src].lo + er[pr.edge].hi + wr[pr.dst].lo;
+        pd[q] = {table_ptr(L.final_table[q]), pr.src, pr.dst};
     }
-    for (int32_t v : plan.singles) { total_lo += wr[v].lo; total_hi += wr[v].lo; }
+    for (size_t q = 0; q < plan.singles.size(); ++q) {
+        const int32_t v = plan.singles[q];
+        total_lo += wr[v].lo; total_hi += wr[v].lo;
+        h_singles[q] = v;
+    }
     if (!fits(total_lo) || !fits(total_hi)) return fail(ctx, LWP_E_OVERFLOW, "the total cost may leave int32");
 
-    // 3. descriptors to the device
-    std::vector<EdgeDesc> ed(L.groups.size());
-    std::vector<const int32_t*> src_ptrs;
-    for (size_t g = 0; g < L.groups.size(); ++g) {
-        ed[g].out = d_slots + (int64_t)L.group_out_slot[g] * CC;
-        ed[g].first_src = (int32_t)src_ptrs.size();
-        ed[g].n_src = (int32_t)L.group_src[g].size();
-        for (auto& r : L.group_src[g]) src_ptrs.push_back(table_ptr(r));
-    }
-    std::vector<PairDesc> pd(plan.pairs.size());
-    for (size_t p = 0; p < plan.pairs.size(); ++p) pd[p] = {table_ptr(L.final_table[p]), plan.pairs[p].src, plan.pairs[p].dst};
-    NodeDesc* d_nd = reinterpret_cast<NodeDesc*>(ws + W.node_desc);
-    EdgeDesc* d_ed = reinterpret_cast<EdgeDesc*>(ws + W.edge_desc);
-    const int32_t** d_src = reinterpret_cast<const int32_t**>(ws + W.src_ptrs);
-    PairDesc* d_pd = reinterpret_cast<PairDesc*>(ws + W.pair_desc);
-    int32_t* d_singles = reinterpret_cast<int32_t*>(ws + W.singles);
-    UndoDesc* d_ud = reinterpret_cast<UndoDesc*>(ws + W.undo);
-    unsigned long long* d_keys = reinterpret_cast<unsigned long long*>(ws + W.keys);
-    int32_t* d_result = reinterpret_cast<int32_t*>(ws + W.result);
-    auto upload = [&](void* dst, const void* src, size_t bytes) -> hipError_t {
-        return bytes ? hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, st) : hipSuccess;
-    };
-    LWP_HIP(ctx, upload(d_nd, nd.data(), nd.size() * sizeof(NodeDesc)));
-    LWP_HIP(ctx, upload(d_ed, ed.data(), ed.size() * sizeof(EdgeDesc)));
-    LWP_HIP(ctx, upload(d_src, src_ptrs.data(), src_ptrs.size() * sizeof(void*)));
-    LWP_HIP(ctx, upload(d_pd, pd.data(), pd.size() * sizeof(PairDesc)));
-    LWP_HIP(ctx, upload(d_singles, plan.singles.data(), plan.singles.size() * sizeof(int32_t)));
-    LWP_HIP(ctx, upload(d_ud, ud.data(), ud.size() * sizeof(UndoDesc)));
-    // the host vectors must outlive the copies: pageable-memory copies are staged before return,
-    // and the final synchronisation below happens before the vectors go out of scope
+    // 3. descriptors to the device: one copy
+    LWP_HIP(ctx, hipMemcpyAsync(db, hb, W.desc_bytes, hipMemcpyHostToDevice, st));
 
     // 4. eliminations, round by round
-    const int32_t tiles1 = (C + kTileM - 1) / kTileM;
     size_t gi = 0, ni = 0, t = 0;
     const size_t n = plan.steps.size();
     while (t < n) {
@@ -505,30 +551,30 @@ lwp_status lwp_search_graph(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, cons
         for (size_t a = n0; a < ni;) {
             size_t b = a;
             while (b < ni && nd_keyed[b] == nd_keyed[a]) ++b;
+            const bool small = want_small_tiles(C, C, (int64_t)(b - a));
+            const int tile = small ? kTileSmall : kTileLarge;
             NodeArgs na{};
             na.descs = d_nd + a;
             na.Ci = na.Cj = na.Ck = C; na.batch = (int32_t)(b - a);
-            na.tilesM = na.tilesN = tiles1;
+            na.tilesM = na.tilesN = (C + tile - 1) / tile;
             ScopedTimer tm(ctx, 0, (int64_t)(b - a) * CC * C, nd_keyed[a]);
-            LWP_HIP(ctx, launch_minplus(na, nd_keyed[a], st));
+            LWP_HIP(ctx, launch_minplus(na, nd_keyed[a], small, st));
             a = b;
         }
     }
 
     // 5. residual graph, undo, results
-    const int32_t n_comp = (int32_t)(plan.pairs.size() + plan.singles.size());
-    LWP_HIP(ctx, launch_init_keys(d_keys, n_comp, st));
     LWP_HIP(ctx, launch_pair_min(d_pd, (int32_t)plan.pairs.size(), d_w, C, d_keys, st));
     LWP_HIP(ctx, launch_single_min(d_singles, (int32_t)plan.singles.size(), d_w, C, d_keys + plan.pairs.size(), st));
     LWP_HIP(ctx, launch_back_substitute(d_pd, (int32_t)plan.pairs.size(), d_singles, (int32_t)plan.singles.size(),
-                                        d_keys, d_ud, (int32_t)ud.size(), C, n_nodes, d_result, st));
-    std::vector<int32_t> result(2 + (size_t)n_nodes);
-    LWP_HIP(ctx, hipMemcpyAsync(result.data(), d_result, result.size() * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+                                        d_keys, d_ud, plan.n_node_steps, C, n_nodes, d_result, st));
+    int32_t* result = reinterpret_cast<int32_t*>(ctx->pin + pin_result);
+    LWP_HIP(ctx, hipMemcpyAsync(result, d_result, (2 + (size_t)n_nodes) * sizeof(int32_t), hipMemcpyDeviceToHost, st));
     LWP_HIP(ctx, hipStreamSynchronize(st));
     const int64_t total = (int64_t)(((uint64_t)(uint32_t)result[1] << 32) | (uint32_t)result[0]);
     if (!fits(total)) return fail(ctx, LWP_E_OVERFLOW, "the total cost leaves int32");
     *out_cost = (int32_t)total;
-    std::memcpy(out_strategy, result.data() + 2, (size_t)n_nodes * sizeof(int32_t));
+    std::memcpy(out_strategy, result + 2, (size_t)n_nodes * sizeof(int32_t));
     return LWP_OK;
 }
 

@@ -8,39 +8,47 @@
 namespace lwp {
 
 // ---- node elimination (Eq. 2) --------------------------------------------------------------
-// One product of a batched launch.  `tb` > 0 selects the packed-key arithmetic for this
-// product: costs are re-based by offA (for A + w) and offB (for B) so that they are
-// non-negative and (A + w - offA) + (B - offB) <= 2^(32-tb) - 2;  5 <= tb <= 17.
+// One product of a batched launch.  [loX, hiX] are ranges the caller guarantees for the entries
+// of A, w and B; rngA / rngB optionally point at a measured {min, max} pair in device memory
+// (written by the launch that produced the table, earlier on the same stream) and can only
+// tighten them.  rngOut, if set, receives {min, max} of `out` by atomics and must have been
+// initialised to {INT32_MAX, INT32_MIN}.  The packed-key variant needs
+//   min(hiA + hiW - loA - loW, (hiA - loA) + (hiB - loB) + 1) + (hiB - loB) <= 2^27 - 2.
 struct NodeDesc {
     const int32_t* A;
     const int32_t* w;
     const int32_t* B;
     int32_t* out;
     int32_t* arg;      // may be null
-    int32_t offA, offB;
-    int32_t tb, pad0;
-    int64_t pad1;
+    int32_t loA, hiA, loW, hiW, loB, hiB;
+    const int32_t* rngA;
+    const int32_t* rngB;
+    int32_t* rngOut;
+    int64_t pad;
 };
-static_assert(sizeof(NodeDesc) == 64, "descriptor layout");
+static_assert(sizeof(NodeDesc) == 96, "descriptor layout");
 
 struct NodeArgs {
     const NodeDesc* descs;   // device array [batch], or null for strided addressing
     NodeDesc base;           // strided addressing: product 0
     int64_t sA, sw, sB, sO;  // strided addressing: element strides between products
     int32_t Ci, Cj, Ck, batch;
-    int32_t tilesM, tilesN;
+    int32_t tilesM, tilesN;  // output tiles of the chosen tile size per product
 };
 
-constexpr int kTileM = 128, kTileN = 128, kTileK = 16, kNodeThreads = 256;
+constexpr int kTileLarge = 128, kTileSmall = 64, kTileK = 16, kNodeThreads = 256;
+constexpr int64_t kKeyedMaxSpread = (1ll << 27) - 2;
 
-// keyed = true launches the packed-key variant (every product needs 5 <= tb <= 17),
-// keyed = false the plain int32 compare/select variant (tb ignored).
-hipError_t launch_minplus(const NodeArgs& args, bool keyed, hipStream_t stream);
+// keyed = true launches the packed-key variant, keyed = false the plain int32 compare/select
+// variant (ranges ignored).  small_tiles selects 64 x 64 output tiles instead of 128 x 128;
+// tilesM / tilesN in args must match.
+hipError_t launch_minplus(const NodeArgs& args, bool keyed, bool small_tiles, hipStream_t stream);
 
 // ---- edge elimination (Eq. 3) --------------------------------------------------------------
 // out = sum of n_src tables of `cells` elements.  srcs indexes a device array of table pointers.
 struct EdgeDesc {
     int32_t* out;
+    int32_t* rngOut;     // optional {min, max} of out, by atomics (see NodeDesc)
     int32_t first_src;   // index into the pointer array
     int32_t n_src;
 };
@@ -50,14 +58,18 @@ hipError_t launch_edge_sum_pair(const int32_t* e1, const int32_t* e2, int32_t* o
                                 hipStream_t stream);
 
 // ---- value ranges ----------------------------------------------------------------------------
+// One launch that prepares a search: stats[2*t] = INT32_MAX, stats[2*t+1] = INT32_MIN for
+// t < n_tables; *flag = 0 (if given); keys[k] = all ones for k < n_keys (if given).
+hipError_t launch_init_workspace(int32_t* d_stats, int32_t n_tables, int32_t* d_flag, unsigned long long* d_keys,
+                                 int32_t n_keys, hipStream_t stream);
 // stats[2*t] = min, stats[2*t+1] = max of table t (n_tables tables of `cells` elements each,
-// dense one after another).  init_ranges must run first on the same stream.
-hipError_t launch_init_ranges(int32_t* d_stats, int32_t n_tables, hipStream_t stream);
+// dense one after another), by atomics onto initialised pairs.
 hipError_t launch_ranges(const int32_t* d_tables, int32_t n_tables, int64_t cells, int32_t* d_stats,
                          hipStream_t stream);
-// w = tc + ts (n elements); *d_flag is OR-ed with 1 if a sum leaves int32.
-hipError_t launch_add_vectors(const int32_t* tc, const int32_t* ts, int32_t* w, int64_t n, int32_t* d_flag,
-                              hipStream_t stream);
+// w[v][c] = tc[v][c] + ts[v][c]; stats[2*v], stats[2*v+1] receive min/max of row v of w;
+// *d_flag is OR-ed with 1 if a sum leaves int32.
+hipError_t launch_add_vectors(const int32_t* tc, const int32_t* ts, int32_t* w, int32_t n_nodes, int32_t C,
+                              int32_t* d_stats, int32_t* d_flag, hipStream_t stream);
 
 // ---- residual graph and back-substitution (Alg. 1, enumeration of the final graph and undo) --
 struct PairDesc {       // residual component with two nodes joined by one edge
@@ -68,8 +80,7 @@ struct UndoDesc {       // one node elimination of the log
     const int32_t* arg; // [C][C]
     int32_t j, i, k, round;
 };
-// keys[p] is a 64-bit (cost, flat index) minimum per component; init_keys sets all to max.
-hipError_t launch_init_keys(unsigned long long* d_keys, int32_t n, hipStream_t stream);
+// keys[p] is a 64-bit (cost, flat index) minimum per component, initialised to all ones.
 hipError_t launch_pair_min(const PairDesc* d_pairs, int32_t n_pairs, const int32_t* d_w, int32_t C,
                            unsigned long long* d_keys, hipStream_t stream);
 hipError_t launch_single_min(const int32_t* d_singles, int32_t n_singles, const int32_t* d_w, int32_t C,

@@ -40,6 +40,7 @@ __global__ __launch_bounds__(kThreads) void edge_sum_desc_kernel(const EdgeDesc*
     for (int q = 0; q < n; ++q) vec = vec && ((((uintptr_t)sp[q]) & 15) == 0);
     const int64_t stride = (int64_t)gridDim.x * kThreads;
     const int64_t t0 = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    int lo = 0x7fffffff, hi = (int)0x80000000;
     if (vec) {
         const int64_t n4 = cells >> 2;
         for (int64_t x = t0; x < n4; x += stride) {
@@ -49,13 +50,20 @@ __global__ __launch_bounds__(kThreads) void edge_sum_desc_kernel(const EdgeDesc*
                 acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
             }
             reinterpret_cast<int4*>(d.out)[x] = acc;
+            lo = min(min(lo, acc.x), min(acc.y, min(acc.z, acc.w)));
+            hi = max(max(hi, acc.x), max(acc.y, max(acc.z, acc.w)));
         }
     } else {
         for (int64_t x = t0; x < cells; x += stride) {
             int32_t acc = sp[0][x];
             for (int q = 1; q < n; ++q) acc += sp[q][x];
             d.out[x] = acc;
+            lo = min(lo, acc); hi = max(hi, acc);
         }
+    }
+    if (d.rngOut) {
+        lo = wave_min(lo); hi = wave_max(hi);
+        if ((threadIdx.x & 63) == 0 && lo <= hi) { atomicMin(&d.rngOut[0], lo); atomicMax(&d.rngOut[1], hi); }
     }
 }
 
@@ -77,9 +85,12 @@ __global__ __launch_bounds__(kThreads) void edge_sum_pair_kernel(const int32_t* 
 }
 
 // ---- value ranges ------------------------------------------------------------------------------
-__global__ void init_ranges_kernel(int32_t* stats, int32_t n_tables) {
+__global__ void init_workspace_kernel(int32_t* stats, int32_t n_tables, int32_t* flag, unsigned long long* keys,
+                                      int32_t n_keys) {
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
     if (t < n_tables) { stats[2 * t] = 0x7fffffff; stats[2 * t + 1] = (int32_t)0x80000000; }
+    if (keys && t < n_keys) keys[t] = ~0ull;
+    if (flag && t == 0) *flag = 0;
 }
 
 __global__ __launch_bounds__(kThreads) void ranges_kernel(const int32_t* __restrict__ tables, int64_t cells,
@@ -110,18 +121,24 @@ __global__ __launch_bounds__(kThreads) void ranges_kernel(const int32_t* __restr
     }
 }
 
-// w = tc + ts; flag[0] is set if a sum leaves int32
+// w = tc + ts, one block row per node (grid.y); also min/max of the node's row of w, and
+// flag[0] is set if a sum leaves int32
 __global__ __launch_bounds__(kThreads) void add_vectors_kernel(const int32_t* __restrict__ tc,
                                                                const int32_t* __restrict__ ts,
-                                                               int32_t* __restrict__ w, int64_t n,
+                                                               int32_t* __restrict__ w, int32_t C,
+                                                               int32_t* __restrict__ stats,
                                                                int32_t* __restrict__ flag) {
-    const int64_t stride = (int64_t)gridDim.x * kThreads;
+    const int64_t row = (int64_t)blockIdx.y * C;
     bool bad = false;
-    for (int64_t x = (int64_t)blockIdx.x * kThreads + threadIdx.x; x < n; x += stride) {
-        const int64_t s = (int64_t)tc[x] + (int64_t)ts[x];
+    int lo = 0x7fffffff, hi = (int32_t)0x80000000;
+    for (int x = blockIdx.x * kThreads + threadIdx.x; x < C; x += gridDim.x * kThreads) {
+        const int64_t s = (int64_t)tc[row + x] + (int64_t)ts[row + x];
         bad = bad || (s != (int64_t)(int32_t)s);
-        w[x] = (int32_t)s;
+        w[row + x] = (int32_t)s;
+        lo = min(lo, (int32_t)s); hi = max(hi, (int32_t)s);
     }
+    lo = wave_min(lo); hi = wave_max(hi);
+    if ((threadIdx.x & 63) == 0 && lo <= hi) { atomicMin(&stats[2 * blockIdx.y], lo); atomicMax(&stats[2 * blockIdx.y + 1], hi); }
     if (bad) atomicOr(flag, 1);
 }
 
@@ -130,11 +147,6 @@ __global__ __launch_bounds__(kThreads) void add_vectors_kernel(const int32_t* __
 // so an unsigned 64-bit min orders by cost first and by the lowest flat index among equal costs.
 __device__ __forceinline__ unsigned long long make_key(int32_t cost, uint32_t idx) {
     return ((unsigned long long)((uint32_t)cost ^ 0x80000000u) << 32) | idx;
-}
-
-__global__ void init_keys_kernel(unsigned long long* keys, int32_t n) {
-    const int t = blockIdx.x * blockDim.x + threadIdx.x;
-    if (t < n) keys[t] = ~0ull;
 }
 
 __device__ __forceinline__ void block_min_to(unsigned long long v, unsigned long long* dst) {
@@ -248,9 +260,11 @@ hipError_t launch_edge_sum_pair(const int32_t* e1, const int32_t* e2, int32_t* o
     return hipGetLastError();
 }
 
-hipError_t launch_init_ranges(int32_t* d_stats, int32_t n_tables, hipStream_t stream) {
-    if (n_tables <= 0) return hipSuccess;
-    hipLaunchKernelGGL(init_ranges_kernel, dim3((n_tables + 255) / 256), dim3(256), 0, stream, d_stats, n_tables);
+hipError_t launch_init_workspace(int32_t* d_stats, int32_t n_tables, int32_t* d_flag, unsigned long long* d_keys,
+                                 int32_t n_keys, hipStream_t stream) {
+    const int n = n_tables > n_keys ? n_tables : n_keys;
+    hipLaunchKernelGGL(init_workspace_kernel, dim3((n + 256) / 256), dim3(256), 0, stream, d_stats, n_tables, d_flag,
+                       d_keys, n_keys);
     return hipGetLastError();
 }
 
@@ -267,15 +281,14 @@ hipError_t launch_ranges(const int32_t* d_tables, int32_t n_tables, int64_t cell
     return hipGetLastError();
 }
 
-hipError_t launch_add_vectors(const int32_t* tc, const int32_t* ts, int32_t* w, int64_t n, int32_t* d_flag,
-                              hipStream_t stream) {
-    hipLaunchKernelGGL(add_vectors_kernel, dim3(blocks_for(n, 4, 4096)), dim3(kThreads), 0, stream, tc, ts, w, n, d_flag);
-    return hipGetLastError();
-}
-
-hipError_t launch_init_keys(unsigned long long* d_keys, int32_t n, hipStream_t stream) {
-    if (n <= 0) return hipSuccess;
-    hipLaunchKernelGGL(init_keys_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, d_keys, n);
+hipError_t launch_add_vectors(const int32_t* tc, const int32_t* ts, int32_t* w, int32_t n_nodes, int32_t C,
+                              int32_t* d_stats, int32_t* d_flag, hipStream_t stream) {
+    for (int32_t v0 = 0; v0 < n_nodes; v0 += 65535) {
+        const int32_t n = (n_nodes - v0) < 65535 ? (n_nodes - v0) : 65535;
+        dim3 grid(blocks_for(C, 4, 64), (unsigned)n);
+        hipLaunchKernelGGL(add_vectors_kernel, grid, dim3(kThreads), 0, stream, tc + (int64_t)v0 * C, ts + (int64_t)v0 * C,
+                           w + (int64_t)v0 * C, C, d_stats + 2 * (int64_t)v0, d_flag);
+    }
     return hipGetLastError();
 }
 
