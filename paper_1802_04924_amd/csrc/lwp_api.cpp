@@ -350,7 +350,7 @@ lwp_status lwp_eliminate_node(lwp_ctx* ctx, int32_t batch, int32_t Ci, int32_t C
     a.base.A = d_A; a.base.w = d_w; a.base.B = d_B; a.base.out = d_out; a.base.arg = d_argmin;
     a.base.loA = (int32_t)rA.lo; a.base.hiA = (int32_t)rA.hi; a.base.loW = (int32_t)rw.lo; a.base.hiW = (int32_t)rw.hi;
     a.base.loB = (int32_t)rB.lo; a.base.hiB = (int32_t)rB.hi;
-    const bool keyed = keyed_spread(rA, rw, rB) <= kKeyedMaxSpread;
+    const bool keyed = keyed_spread(rA, rw, rB) <= (small ? kKeyedMaxSpreadSmall : kKeyedMaxSpreadLarge);
     a.sA = (int64_t)Ci * Cj; a.sw = Cj; a.sB = (int64_t)Cj * Ck; a.sO = (int64_t)Ci * Ck;
     a.Ci = Ci; a.Cj = Cj; a.Ck = Ck; a.batch = batch;
     a.tilesM = (int32_t)tilesM; a.tilesN = (int32_t)tilesN;
@@ -469,7 +469,7 @@ lwp_status lwp_search_graph(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, cons
     std::vector<int32_t> erng(n_edges);          // range-pair index of the edge's current table
     for (int32_t e = 0; e < n_edges; ++e) { er[e] = {stats[2 * e], stats[2 * e + 1]}; erng[e] = e; }
     for (int32_t v = 0; v < n_nodes; ++v) wr[v] = {stats[2 * (rng_w0 + v)], stats[2 * (rng_w0 + v) + 1]};
-    std::vector<char> nd_keyed(plan.n_node_steps);
+    std::vector<int64_t> nd_spread(plan.n_node_steps);
     {
         size_t ni = 0, gi = 0, nsrc = 0, t = 0;
         const size_t n = plan.steps.size();
@@ -504,7 +504,7 @@ lwp_status lwp_search_graph(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, cons
             d.rngB = d_stats + 2 * (int64_t)erng[s.e2];
             d.rngOut = d_stats + 2 * (int64_t)(rng_node0 + (int32_t)ni);
             nd[ni] = d;
-            nd_keyed[ni] = keyed_spread(rA, rw, rB) <= kKeyedMaxSpread;
+            nd_spread[ni] = keyed_spread(rA, rw, rB);
             ud[ni] = {d.arg, s.j, s.i, s.k, s.round};
             // any fixed c bounds the minimum from above; take the c with the smallest w
             er[s.e1] = {rA.lo + rw.lo + rB.lo, rA.hi + rw.lo + rB.hi};
@@ -548,17 +548,19 @@ lwp_status lwp_search_graph(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, cons
         size_t n0 = ni;
         while (t < n && plan.steps[t].round == round && plan.steps[t].kind == 0) { ++t; ++ni; }
         // products of one round run in one launch per arithmetic variant (contiguous runs)
+        const bool small = want_small_tiles(C, C, (int64_t)(ni - n0));
+        const int tile = small ? kTileSmall : kTileLarge;
+        const int64_t max_spread = small ? kKeyedMaxSpreadSmall : kKeyedMaxSpreadLarge;
         for (size_t a = n0; a < ni;) {
+            const bool keyed = nd_spread[a] <= max_spread;
             size_t b = a;
-            while (b < ni && nd_keyed[b] == nd_keyed[a]) ++b;
-            const bool small = want_small_tiles(C, C, (int64_t)(b - a));
-            const int tile = small ? kTileSmall : kTileLarge;
+            while (b < ni && (nd_spread[b] <= max_spread) == keyed) ++b;
             NodeArgs na{};
             na.descs = d_nd + a;
             na.Ci = na.Cj = na.Ck = C; na.batch = (int32_t)(b - a);
             na.tilesM = na.tilesN = (C + tile - 1) / tile;
-            ScopedTimer tm(ctx, 0, (int64_t)(b - a) * CC * C, nd_keyed[a]);
-            LWP_HIP(ctx, launch_minplus(na, nd_keyed[a], small, st));
+            ScopedTimer tm(ctx, 0, (int64_t)(b - a) * CC * C, keyed);
+            LWP_HIP(ctx, launch_minplus(na, keyed, small, st));
             a = b;
         }
     }

@@ -13,7 +13,7 @@ namespace lwp {
 // (written by the launch that produced the table, earlier on the same stream) and can only
 // tighten them.  rngOut, if set, receives {min, max} of `out` by atomics and must have been
 // initialised to {INT32_MAX, INT32_MIN}.  The packed-key variant needs
-//   min(hiA + hiW - loA - loW, (hiA - loA) + (hiB - loB) + 1) + (hiB - loB) <= 2^27 - 2.
+//   min(hiA + hiW - loA - loW, (hiA - loA) + (hiB - loB) + 1) + (hiB - loB) <= kKeyedMaxSpread*.
 struct NodeDesc {
     const int32_t* A;
     const int32_t* w;
@@ -36,8 +36,10 @@ struct NodeArgs {
     int32_t tilesM, tilesN;  // output tiles of the chosen tile size per product
 };
 
-constexpr int kTileLarge = 128, kTileSmall = 64, kTileK = 16, kNodeThreads = 256;
-constexpr int64_t kKeyedMaxSpread = (1ll << 27) - 2;
+constexpr int kTileLarge = 128, kTileSmall = 64, kNodeThreads = 256;
+// largest spread the packed keys can hold: 27 bits with 128 x 128 tiles (16-deep stages), 26 bits
+// with 64 x 64 tiles (32-deep stages)
+constexpr int64_t kKeyedMaxSpreadLarge = (1ll << 27) - 2, kKeyedMaxSpreadSmall = (1ll << 26) - 2;
 
 // keyed = true launches the packed-key variant, keyed = false the plain int32 compare/select
 // variant (ranges ignored).  small_tiles selects 64 x 64 output tiles instead of 128 x 128;

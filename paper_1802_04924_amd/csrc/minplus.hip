@@ -26,7 +26,7 @@ namespace lwp {
 
 namespace {
 
-constexpr int TK = kTileK, NT = kNodeThreads;
+constexpr int NT = kNodeThreads;
 
 __device__ __forceinline__ int wave_min_i32(int v) {
 #pragma unroll
@@ -39,11 +39,12 @@ __device__ __forceinline__ int wave_max_i32(int v) {
     return v;
 }
 
-template <bool KEYED, int RB>
-__global__ __launch_bounds__(NT, (KEYED || RB < 8) ? 2 : 1) void minplus_kernel(const NodeArgs p) {
+template <bool KEYED, int RB, int TK>
+__global__ __launch_bounds__(NT, KEYED ? 2 : 1) void minplus_kernel(const NodeArgs p) {
     constexpr int TM = 16 * RB, TN = 16 * RB;   // output tile
-    constexpr int EP = RB;                      // elements of A and of B each thread stages per stage
+    constexpr int EP = TM * TK / NT;            // elements of A and of B each thread stages per stage
     constexpr int QUADS = RB / 4;
+    static_assert(EP % 4 == 0 && TK % EP == 0 && TN % EP == 0 && (TN / EP) * TK == NT, "staging assignment");
     __shared__ __attribute__((aligned(16))) uint32_t As[2][TK][TM];   // [stage][c][a]  (A transposed)
     __shared__ __attribute__((aligned(16))) uint32_t Bs[2][TK][TN];   // [stage][c][b]
 
@@ -97,22 +98,24 @@ __global__ __launch_bounds__(NT, (KEYED || RB < 8) ? 2 : 1) void minplus_kernel(
         const long long capl = min(a_max, out_max + 1);
         const long long spread = capl + (hiB - loB);
         cap = (uint32_t)capl;
-        tb = 5;
-        for (int t = 17; t > 5; --t)
+        constexpr int TB_MIN = (TK <= 16) ? 5 : 6;               // a chunk holds at least one stage
+        tb = TB_MIN;
+        for (int t = 17; t > TB_MIN; --t)
             if (spread <= (1ll << (32 - t)) - 2) { tb = t; break; }
-        for (int t = 5; t < tb; ++t)
-            if ((((1 << t) - 1) >> 4) * TK >= Cj) { tb = t; break; }   // one chunk already covers all c
+        for (int t = TB_MIN; t < tb; ++t)
+            if (((1 << t) - 1) / TK * TK >= Cj) { tb = t; break; }   // one chunk already covers all c
     }
     const uint32_t fmask = KEYED ? ((1u << tb) - 1u) : 0u;
     const uint32_t padA = KEYED ? ~fmask : 0x7fffffffu;   // never strictly below any running minimum
-    const int spc = KEYED ? (int)(fmask >> 4) : 1;        // stages per chunk: 16*spc <= 2^tb - 1
+    const int spc = KEYED ? (int)(fmask / TK) : 1;        // stages per chunk: TK*spc <= 2^tb - 1
 
     const int tid = threadIdx.x;
     const int tx = tid & 15, ty = tid >> 4;
     // global -> LDS assignment: A: one row, EP consecutive c;  B: one c, EP consecutive columns
     constexpr int TPR = TK / EP;                 // threads per A row
     const int lr = tid / TPR, lseg = (tid % TPR) * EP;
-    const int br = tid >> 4, bseg = (tid & 15) * EP;
+    constexpr int TPB = TN / EP;                 // threads per B row
+    const int br = tid / TPB, bseg = (tid % TPB) * EP;
     const int arow = min(a0 + lr, Ci - 1);       // clamped: rows past the end are never stored
     const bool vecA = ((Cj & 3) == 0) && ((((uintptr_t)A) | ((uintptr_t)W)) & 15) == 0;
     const bool vecB = ((Ck & 3) == 0) && ((((uintptr_t)B) & 15) == 0) && (b0 + TN <= Ck);
@@ -281,7 +284,13 @@ __global__ __launch_bounds__(NT, (KEYED || RB < 8) ? 2 : 1) void minplus_kernel(
     }
     if (d.rngOut) {   // leave the measured range of this table for the launches that consume it
         vmin = wave_min_i32(vmin); vmax = wave_max_i32(vmax);
-        if ((tid & 63) == 0 && vmin <= vmax) { atomicMin(&d.rngOut[0], vmin); atomicMax(&d.rngOut[1], vmax); }
+        int* red = reinterpret_cast<int*>(&As[0][0][0]);      // all reads of the tiles are done
+        if ((tid & 63) == 0) { red[2 * (tid >> 6)] = vmin; red[2 * (tid >> 6) + 1] = vmax; }
+        __syncthreads();
+        if (tid == 0) {
+            for (int q = 1; q < NT / 64; ++q) { vmin = min(vmin, red[2 * q]); vmax = max(vmax, red[2 * q + 1]); }
+            if (vmin <= vmax) { atomicMin(&d.rngOut[0], vmin); atomicMax(&d.rngOut[1], vmax); }
+        }
     }
 }
 
@@ -292,11 +301,11 @@ hipError_t launch_minplus(const NodeArgs& args, bool keyed, bool small_tiles, hi
     if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     dim3 grid((unsigned)blocks), block(NT);
     if (keyed) {
-        if (small_tiles) hipLaunchKernelGGL((minplus_kernel<true, 4>), grid, block, 0, stream, args);
-        else hipLaunchKernelGGL((minplus_kernel<true, 8>), grid, block, 0, stream, args);
+        if (small_tiles) hipLaunchKernelGGL((minplus_kernel<true, 4, 32>), grid, block, 0, stream, args);
+        else hipLaunchKernelGGL((minplus_kernel<true, 8, 16>), grid, block, 0, stream, args);
     } else {
-        if (small_tiles) hipLaunchKernelGGL((minplus_kernel<false, 4>), grid, block, 0, stream, args);
-        else hipLaunchKernelGGL((minplus_kernel<false, 8>), grid, block, 0, stream, args);
+        if (small_tiles) hipLaunchKernelGGL((minplus_kernel<false, 4, 32>), grid, block, 0, stream, args);
+        else hipLaunchKernelGGL((minplus_kernel<false, 8, 16>), grid, block, 0, stream, args);
     }
     return hipGetLastError();
 }

@@ -62,8 +62,14 @@ __global__ __launch_bounds__(kThreads) void edge_sum_desc_kernel(const EdgeDesc*
         }
     }
     if (d.rngOut) {
+        __shared__ int red[2 * (kThreads / 64)];
         lo = wave_min(lo); hi = wave_max(hi);
-        if ((threadIdx.x & 63) == 0 && lo <= hi) { atomicMin(&d.rngOut[0], lo); atomicMax(&d.rngOut[1], hi); }
+        if ((threadIdx.x & 63) == 0) { red[2 * (threadIdx.x >> 6)] = lo; red[2 * (threadIdx.x >> 6) + 1] = hi; }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            for (int q = 1; q < kThreads / 64; ++q) { lo = min(lo, red[2 * q]); hi = max(hi, red[2 * q + 1]); }
+            if (lo <= hi) { atomicMin(&d.rngOut[0], lo); atomicMax(&d.rngOut[1], hi); }
+        }
     }
 }
 

@@ -55,13 +55,10 @@ def test_eliminate_node_keyed_small_values(ctx, shape, hi):
     check_products(ctx, A, w, B, expect_keyed=True)
 
 
-@pytest.mark.parametrize("bits,expect_keyed", [(22, True), (24, True), (25, True), (26, False), (29, False)])
-@pytest.mark.parametrize("shape", [(2, 130, 257, 140), (1, 128, 512, 128), (1, 31, 1000, 17)])
-def test_eliminate_node_key_widths_and_plain_variant(ctx, shape, bits, expect_keyed):
-    # the spread of A + w + B decides the key width: 3 * 2^bits; wide spreads use the plain variant
+def spread_case(shape, bits, seed):
     batch, Ci, Cj, Ck = shape
     hi = (1 << bits) - 1
-    rng = np.random.default_rng(bits * 1000 + Cj)
+    rng = np.random.default_rng(seed)
     A = rng.integers(0, hi, size=(batch, Ci, Cj), endpoint=True, dtype=np.int32)
     w = rng.integers(0, hi, size=(batch, Cj), endpoint=True, dtype=np.int32)
     B = rng.integers(0, hi, size=(batch, Cj, Ck), endpoint=True, dtype=np.int32)
@@ -69,6 +66,23 @@ def test_eliminate_node_key_widths_and_plain_variant(ctx, shape, bits, expect_ke
     A[:, :, Cj // 2:] = A[:, :, :Cj - Cj // 2]
     w[:, Cj // 2:] = w[:, :Cj - Cj // 2]
     B[:, Cj // 2:, :] = B[:, :Cj - Cj // 2, :]
+    return A, w, B
+
+
+# The spread of A + w + B (3 * 2^bits here) decides the key width; too wide a spread falls back to
+# the plain variant.  Launches with fewer than 256 tiles of 128 x 128 use 64 x 64 tiles, whose
+# deeper stages leave one bit less for the cost.
+@pytest.mark.parametrize("bits,expect_keyed", [(22, True), (24, True), (25, False), (29, False)])
+@pytest.mark.parametrize("shape", [(2, 130, 257, 140), (1, 128, 512, 128), (1, 31, 1000, 17)])
+def test_eliminate_node_key_widths_small_tiles(ctx, shape, bits, expect_keyed):
+    A, w, B = spread_case(shape, bits, bits * 1000 + shape[2])
+    check_products(ctx, A, w, B, expect_keyed=expect_keyed)
+
+
+@pytest.mark.parametrize("bits,expect_keyed", [(20, True), (23, True), (24, True), (25, True), (26, False)])
+@pytest.mark.parametrize("shape", [(64, 256, 80, 256), (17, 500, 33, 512)])
+def test_eliminate_node_key_widths_large_tiles(ctx, shape, bits, expect_keyed):
+    A, w, B = spread_case(shape, bits, bits * 77 + shape[2])
     check_products(ctx, A, w, B, expect_keyed=expect_keyed)
 
 
