@@ -88,10 +88,14 @@ int64_t keyed_spread(Range rA, Range rw, Range rB) {
     return std::min(a_max, out_max + 1) + (rB.hi - rB.lo);
 }
 
-// 64 x 64 tiles when 128 x 128 tiles would leave most of the 256 compute units without a workgroup.
-bool want_small_tiles(int32_t Ci, int32_t Ck, int64_t batch) {
-    const int64_t big = (int64_t)((Ci + kTileLarge - 1) / kTileLarge) * ((Ck + kTileLarge - 1) / kTileLarge) * batch;
-    return big < 256;
+// Tile choice.  Measured on MI355X the 64 x 64 variant (4 waves per SIMD, 32-deep stages) matches or
+// beats the 128 x 128 variant except for very large batches of short products (Cj < 512), where
+// its four times as many workgroup start-ups show; it also quantises a launch four times finer.
+int64_t large_tiles(int32_t Ci, int32_t Ck, int64_t batch) {
+    return (int64_t)((Ci + kTileLarge - 1) / kTileLarge) * ((Ck + kTileLarge - 1) / kTileLarge) * batch;
+}
+bool want_small_tiles(int32_t Ci, int32_t Cj, int32_t Ck, int64_t batch) {
+    return large_tiles(Ci, Ck, batch) < 2048 || Cj >= 512;
 }
 
 // Timing of one launch when profiling is on.
@@ -325,10 +329,9 @@ lwp_status lwp_eliminate_node(lwp_ctx* ctx, int32_t batch, int32_t Ci, int32_t C
     if (!d_A || !d_w || !d_B || !d_out) return fail(ctx, LWP_E_INVAL, "null table pointer");
     if (((uintptr_t)d_A | (uintptr_t)d_w | (uintptr_t)d_B | (uintptr_t)d_out | (uintptr_t)d_argmin) & 3)
         return fail(ctx, LWP_E_INVAL, "table pointer not 4-byte aligned");
-    const bool small = want_small_tiles(Ci, Ck, batch);
-    const int tile = small ? kTileSmall : kTileLarge;
-    const int64_t tilesM = (Ci + tile - 1) / tile, tilesN = (Ck + tile - 1) / tile;
-    if (tilesM * tilesN * batch > 0x7fffffffLL) return fail(ctx, LWP_E_INVAL, "too many output tiles");
+    const bool prefer_small = want_small_tiles(Ci, Cj, Ck, batch);
+    if ((int64_t)((Ci + kTileSmall - 1) / kTileSmall) * ((Ck + kTileSmall - 1) / kTileSmall) * batch > 0x7fffffffLL)
+        return fail(ctx, LWP_E_INVAL, "too many output tiles");
 
     // value ranges of A, w, B over the whole batch
     if (lwp_status s = ensure_workspace(ctx, 4096)) return s;
@@ -350,7 +353,13 @@ lwp_status lwp_eliminate_node(lwp_ctx* ctx, int32_t batch, int32_t Ci, int32_t C
     a.base.A = d_A; a.base.w = d_w; a.base.B = d_B; a.base.out = d_out; a.base.arg = d_argmin;
     a.base.loA = (int32_t)rA.lo; a.base.hiA = (int32_t)rA.hi; a.base.loW = (int32_t)rw.lo; a.base.hiW = (int32_t)rw.hi;
     a.base.loB = (int32_t)rB.lo; a.base.hiB = (int32_t)rB.hi;
-    const bool keyed = keyed_spread(rA, rw, rB) <= (small ? kKeyedMaxSpreadSmall : kKeyedMaxSpreadLarge);
+    const int64_t spread = keyed_spread(rA, rw, rB);
+    // one more key bit on large tiles, worth it only if they still fill the chip
+    const bool keyed = spread <= kKeyedMaxSpreadSmall ||
+                       (spread <= kKeyedMaxSpreadLarge && (!prefer_small || large_tiles(Ci, Ck, batch) >= 512));
+    const bool small = prefer_small && (spread <= kKeyedMaxSpreadSmall || !keyed);
+    const int tile = small ? kTileSmall : kTileLarge;
+    const int64_t tilesM = (Ci + tile - 1) / tile, tilesN = (Ck + tile - 1) / tile;
     a.sA = (int64_t)Ci * Cj; a.sw = Cj; a.sB = (int64_t)Cj * Ck; a.sO = (int64_t)Ci * Ck;
     a.Ci = Ci; a.Cj = Cj; a.Ck = Ck; a.batch = batch;
     a.tilesM = (int32_t)tilesM; a.tilesN = (int32_t)tilesN;
@@ -547,14 +556,22 @@ lwp_status lwp_search_graph(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, cons
         }
         size_t n0 = ni;
         while (t < n && plan.steps[t].round == round && plan.steps[t].kind == 0) { ++t; ++ni; }
-        // products of one round run in one launch per arithmetic variant (contiguous runs)
-        const bool small = want_small_tiles(C, C, (int64_t)(ni - n0));
-        const int tile = small ? kTileSmall : kTileLarge;
-        const int64_t max_spread = small ? kKeyedMaxSpreadSmall : kKeyedMaxSpreadLarge;
+        // products of one round run in one launch per variant (contiguous runs): packed keys on
+        // the preferred tile size if the spread allows, else packed keys on 128 x 128 tiles (one
+        // more bit), else the plain variant
+        const bool prefer_small = want_small_tiles(C, C, C, (int64_t)(ni - n0));
+        const bool large_fills_chip = large_tiles(C, C, (int64_t)(ni - n0)) >= 512;
+        auto variant = [&](size_t q) {
+            if (nd_spread[q] <= (prefer_small ? kKeyedMaxSpreadSmall : kKeyedMaxSpreadLarge)) return prefer_small ? 0 : 1;
+            if (nd_spread[q] <= kKeyedMaxSpreadLarge && large_fills_chip) return 1;
+            return prefer_small ? 2 : 3;
+        };   // 0 keyed small, 1 keyed large, 2 plain small, 3 plain large
         for (size_t a = n0; a < ni;) {
-            const bool keyed = nd_spread[a] <= max_spread;
+            const int v = variant(a);
             size_t b = a;
-            while (b < ni && (nd_spread[b] <= max_spread) == keyed) ++b;
+            while (b < ni && variant(b) == v) ++b;
+            const bool keyed = v < 2, small = (v == 0 || v == 2);
+            const int tile = small ? kTileSmall : kTileLarge;
             NodeArgs na{};
             na.descs = d_nd + a;
             na.Ci = na.Cj = na.Ck = C; na.batch = (int32_t)(b - a);

@@ -70,8 +70,9 @@ def spread_case(shape, bits, seed):
 
 
 # The spread of A + w + B (3 * 2^bits here) decides the key width; too wide a spread falls back to
-# the plain variant.  Launches with fewer than 256 tiles of 128 x 128 use 64 x 64 tiles, whose
-# deeper stages leave one bit less for the cost.
+# the plain variant.  Launches with fewer than 2048 tiles of 128 x 128 use 64 x 64 tiles, whose
+# deeper stages leave one bit less for the cost (so do all launches with Cj >= 512); a spread that
+# needs that bit moves the launch to 128 x 128 tiles if those still fill the chip (>= 512 tiles).
 @pytest.mark.parametrize("bits,expect_keyed", [(22, True), (24, True), (25, False), (29, False)])
 @pytest.mark.parametrize("shape", [(2, 130, 257, 140), (1, 128, 512, 128), (1, 31, 1000, 17)])
 def test_eliminate_node_key_widths_small_tiles(ctx, shape, bits, expect_keyed):
@@ -80,7 +81,7 @@ def test_eliminate_node_key_widths_small_tiles(ctx, shape, bits, expect_keyed):
 
 
 @pytest.mark.parametrize("bits,expect_keyed", [(20, True), (23, True), (24, True), (25, True), (26, False)])
-@pytest.mark.parametrize("shape", [(64, 256, 80, 256), (17, 500, 33, 512)])
+@pytest.mark.parametrize("shape", [(512, 256, 80, 256), (130, 500, 33, 512), (40, 500, 600, 512)])
 def test_eliminate_node_key_widths_large_tiles(ctx, shape, bits, expect_keyed):
     A, w, B = spread_case(shape, bits, bits * 77 + shape[2])
     check_products(ctx, A, w, B, expect_keyed=expect_keyed)
