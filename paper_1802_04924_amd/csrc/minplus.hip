@@ -28,6 +28,10 @@ namespace {
 
 constexpr int NT = kNodeThreads;
 
+using v4i = int __attribute__((ext_vector_type(4)));
+using gv4cptr = const v4i __attribute__((address_space(1)))*;
+using gv4ptr = v4i __attribute__((address_space(1)))*;
+
 __device__ __forceinline__ int wave_min_i32(int v) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v = min(v, __shfl_xor(v, o));
@@ -77,11 +81,16 @@ __global__ __launch_bounds__(NT, KEYED ? 2 : 1) void minplus_kernel(const NodeAr
         d.out += (int64_t)bi * p.sO;
         if (d.arg) d.arg += (int64_t)bi * p.sO;
     }
-    const int32_t* __restrict__ A = d.A;
-    const int32_t* __restrict__ W = d.w;
-    const int32_t* __restrict__ B = d.B;
-    int32_t* __restrict__ O = d.out;
-    int32_t* __restrict__ G = d.arg;
+    // Pointers read from a descriptor are generic to the compiler; say that they are global memory,
+    // otherwise the prefetch loads are issued as flat loads, which also count as LDS traffic and
+    // would be waited for by the first LDS read of the stage they are meant to overlap.
+    using gcptr = const int32_t __attribute__((address_space(1)))*;
+    using gptr = int32_t __attribute__((address_space(1)))*;
+    const gcptr A = (gcptr)(uintptr_t)d.A;
+    const gcptr W = (gcptr)(uintptr_t)d.w;
+    const gcptr B = (gcptr)(uintptr_t)d.B;
+    const gptr O = (gptr)(uintptr_t)d.out;
+    const gptr G = (gptr)(uintptr_t)d.arg;
 
     // ---- key parameters from value ranges (uniform, scalar) ----
     int32_t offA = 0, offB = 0;
@@ -89,8 +98,8 @@ __global__ __launch_bounds__(NT, KEYED ? 2 : 1) void minplus_kernel(const NodeAr
     uint32_t cap = 0xffffffffu;
     if (KEYED) {
         long long loA = d.loA, hiA = d.hiA, loW = d.loW, hiW = d.hiW, loB = d.loB, hiB = d.hiB;
-        if (d.rngA) { loA = max(loA, (long long)d.rngA[0]); hiA = min(hiA, (long long)d.rngA[1]); }
-        if (d.rngB) { loB = max(loB, (long long)d.rngB[0]); hiB = min(hiB, (long long)d.rngB[1]); }
+        if (d.rngA) { const gcptr r = (gcptr)(uintptr_t)d.rngA; loA = max(loA, (long long)r[0]); hiA = min(hiA, (long long)r[1]); }
+        if (d.rngB) { const gcptr r = (gcptr)(uintptr_t)d.rngB; loB = max(loB, (long long)r[0]); hiB = min(hiB, (long long)r[1]); }
         offA = (int32_t)(loA + loW);
         offB = (int32_t)loB;
         const long long a_max = hiA + hiW - (loA + loW);          // largest re-based A + w
@@ -119,15 +128,15 @@ __global__ __launch_bounds__(NT, KEYED ? 2 : 1) void minplus_kernel(const NodeAr
     const int arow = min(a0 + lr, Ci - 1);       // clamped: rows past the end are never stored
     const bool vecA = ((Cj & 3) == 0) && ((((uintptr_t)A) | ((uintptr_t)W)) & 15) == 0;
     const bool vecB = ((Ck & 3) == 0) && ((((uintptr_t)B) & 15) == 0) && (b0 + TN <= Ck);
-    const int32_t* __restrict__ Arow = A + (int64_t)arow * Cj;
+    const gcptr Arow = A + (int64_t)arow * Cj;
 
     int32_t ra[EP], rw[EP], rb[EP];
     auto fetch = [&](int c0) {
         if (vecA && c0 + TK <= Cj) {
 #pragma unroll
             for (int v = 0; v < EP / 4; ++v) {
-                const int4 x = reinterpret_cast<const int4*>(Arow + c0 + lseg)[v];
-                const int4 y = reinterpret_cast<const int4*>(W + c0 + lseg)[v];
+                const v4i x = ((gv4cptr)(Arow + c0 + lseg))[v];
+                const v4i y = ((gv4cptr)(W + c0 + lseg))[v];
                 ra[4 * v] = x.x; ra[4 * v + 1] = x.y; ra[4 * v + 2] = x.z; ra[4 * v + 3] = x.w;
                 rw[4 * v] = y.x; rw[4 * v + 1] = y.y; rw[4 * v + 2] = y.z; rw[4 * v + 3] = y.w;
             }
@@ -141,7 +150,7 @@ __global__ __launch_bounds__(NT, KEYED ? 2 : 1) void minplus_kernel(const NodeAr
         if (vecB && c0 + TK <= Cj) {
 #pragma unroll
             for (int v = 0; v < EP / 4; ++v) {
-                const int4 y = reinterpret_cast<const int4*>(B + (int64_t)(c0 + br) * Ck + b0 + bseg)[v];
+                const v4i y = ((gv4cptr)(B + (int64_t)(c0 + br) * Ck + b0 + bseg))[v];
                 rb[4 * v] = y.x; rb[4 * v + 1] = y.y; rb[4 * v + 2] = y.z; rb[4 * v + 3] = y.w;
             }
         } else {
@@ -264,11 +273,11 @@ __global__ __launch_bounds__(NT, KEYED ? 2 : 1) void minplus_kernel(const NodeAr
 #pragma unroll
         for (int h = 0; h < QUADS; ++h) {
             const int b = b0 + h * 64 + tx * 4;
-            int32_t* orow = O + (int64_t)a * Ck + b;
+            const gptr orow = O + (int64_t)a * Ck + b;
             if (vecO) {
-                *reinterpret_cast<int4*>(orow) = make_int4(val[h * 4], val[h * 4 + 1], val[h * 4 + 2], val[h * 4 + 3]);
-                if (G) *reinterpret_cast<int4*>(G + (int64_t)a * Ck + b) =
-                    make_int4((int32_t)rec[i][h * 4], (int32_t)rec[i][h * 4 + 1], (int32_t)rec[i][h * 4 + 2], (int32_t)rec[i][h * 4 + 3]);
+                *(gv4ptr)(orow) = v4i{val[h * 4], val[h * 4 + 1], val[h * 4 + 2], val[h * 4 + 3]};
+                if (G) *(gv4ptr)(G + (int64_t)a * Ck + b) =
+                    v4i{(int32_t)rec[i][h * 4], (int32_t)rec[i][h * 4 + 1], (int32_t)rec[i][h * 4 + 2], (int32_t)rec[i][h * 4 + 3]};
 #pragma unroll
                 for (int q = 0; q < 4; ++q) { vmin = min(vmin, val[h * 4 + q]); vmax = max(vmax, val[h * 4 + q]); }
             } else {
