@@ -27,6 +27,9 @@ namespace lwp {
 namespace {
 
 constexpr int NT = kNodeThreads;
+#ifndef LWP_TK_SMALL
+#define LWP_TK_SMALL 32
+#endif
 
 using v4i = int __attribute__((ext_vector_type(4)));
 using gv4cptr = const v4i __attribute__((address_space(1)))*;
@@ -130,13 +133,16 @@ __global__ __launch_bounds__(NT, KEYED ? 2 : 1) void minplus_kernel(const NodeAr
     const bool vecB = ((Ck & 3) == 0) && ((((uintptr_t)B) & 15) == 0) && (b0 + TN <= Ck);
     const gcptr Arow = A + (int64_t)arow * Cj;
 
+    // Per-thread source pointers of the staging loads; they advance by one stage per fetch.
+    gcptr pA = Arow + lseg, pW = W + lseg;
+    gcptr pB = B + (int64_t)br * Ck + b0 + bseg;
     int32_t ra[EP], rw[EP], rb[EP];
     auto fetch = [&](int c0) {
         if (vecA && c0 + TK <= Cj) {
 #pragma unroll
             for (int v = 0; v < EP / 4; ++v) {
-                const v4i x = ((gv4cptr)(Arow + c0 + lseg))[v];
-                const v4i y = ((gv4cptr)(W + c0 + lseg))[v];
+                const v4i x = ((gv4cptr)pA)[v];
+                const v4i y = ((gv4cptr)pW)[v];
                 ra[4 * v] = x.x; ra[4 * v + 1] = x.y; ra[4 * v + 2] = x.z; ra[4 * v + 3] = x.w;
                 rw[4 * v] = y.x; rw[4 * v + 1] = y.y; rw[4 * v + 2] = y.z; rw[4 * v + 3] = y.w;
             }
@@ -150,7 +156,7 @@ __global__ __launch_bounds__(NT, KEYED ? 2 : 1) void minplus_kernel(const NodeAr
         if (vecB && c0 + TK <= Cj) {
 #pragma unroll
             for (int v = 0; v < EP / 4; ++v) {
-                const v4i y = ((gv4cptr)(B + (int64_t)(c0 + br) * Ck + b0 + bseg))[v];
+                const v4i y = ((gv4cptr)pB)[v];
                 rb[4 * v] = y.x; rb[4 * v + 1] = y.y; rb[4 * v + 2] = y.z; rb[4 * v + 3] = y.w;
             }
         } else {
@@ -158,26 +164,30 @@ __global__ __launch_bounds__(NT, KEYED ? 2 : 1) void minplus_kernel(const NodeAr
 #pragma unroll
             for (int q = 0; q < EP; ++q) rb[q] = B[(int64_t)c * Ck + min(b0 + bseg + q, Ck - 1)];
         }
+        pA += TK; pW += TK; pB += (int64_t)TK * Ck;
     };
-    // pos0 = position of c0 inside its chunk (keyed): the key's low field is 1 + position
+    // Keys: A side ((A + w - offA, clamped) << tb) + low field - (offB << tb), B side B << tb.  The
+    // re-basing of B rides on the A side (arithmetic is modulo 2^32 and the true sum is in range),
+    // so B costs one shift.  pos0 = position of c0 inside its chunk; the low field is 1 + position.
+    const uint32_t boff = KEYED ? ((uint32_t)offB << tb) : 0u;
     auto stash = [&](int c0, int pos0, int buf) {
-        const bool full = (c0 + TK <= Cj);       // only the last stage can be ragged
-        const uint32_t pos = (uint32_t)(pos0 + lseg + 1);
+        const uint32_t pos = (uint32_t)(pos0 + lseg + 1) - boff;
+        uint32_t ka[EP], kb[EP];
 #pragma unroll
         for (int q = 0; q < EP; ++q) {
-            uint32_t ka;
-            if (KEYED) ka = (min((uint32_t)(ra[q] + rw[q] - offA), cap) << tb) + (pos + q);
-            else ka = (uint32_t)(ra[q] + rw[q]);
-            if (!full && (c0 + lseg + q) >= Cj) ka = padA;
-            As[buf][lseg + q][lr] = ka;
+            if (KEYED) { ka[q] = (min((uint32_t)(ra[q] + rw[q] - offA), cap) << tb) + (pos + q); kb[q] = (uint32_t)rb[q] << tb; }
+            else { ka[q] = (uint32_t)(ra[q] + rw[q]); kb[q] = (uint32_t)rb[q]; }
         }
-        const bool cok = full || (c0 + br) < Cj;
-        uint32_t kb[EP];
+        if (c0 + TK > Cj) {                       // only the last stage can be ragged
+            const bool cok = (c0 + br) < Cj;
 #pragma unroll
-        for (int q = 0; q < EP; ++q) {
-            const uint32_t v = KEYED ? ((uint32_t)(rb[q] - offB) << tb) : (uint32_t)rb[q];
-            kb[q] = cok ? v : 0u;
+            for (int q = 0; q < EP; ++q) {
+                if ((c0 + lseg + q) >= Cj) ka[q] = padA;
+                if (!cok) kb[q] = 0u;
+            }
         }
+#pragma unroll
+        for (int q = 0; q < EP; ++q) As[buf][lseg + q][lr] = ka[q];
 #pragma unroll
         for (int v = 0; v < EP / 4; ++v)
             *reinterpret_cast<uint4*>(&Bs[buf][br][bseg + 4 * v]) = make_uint4(kb[4 * v], kb[4 * v + 1], kb[4 * v + 2], kb[4 * v + 3]);
@@ -310,10 +320,10 @@ hipError_t launch_minplus(const NodeArgs& args, bool keyed, bool small_tiles, hi
     if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     dim3 grid((unsigned)blocks), block(NT);
     if (keyed) {
-        if (small_tiles) hipLaunchKernelGGL((minplus_kernel<true, 4, 32>), grid, block, 0, stream, args);
+        if (small_tiles) hipLaunchKernelGGL((minplus_kernel<true, 4, LWP_TK_SMALL>), grid, block, 0, stream, args);
         else hipLaunchKernelGGL((minplus_kernel<true, 8, 16>), grid, block, 0, stream, args);
     } else {
-        if (small_tiles) hipLaunchKernelGGL((minplus_kernel<false, 4, 32>), grid, block, 0, stream, args);
+        if (small_tiles) hipLaunchKernelGGL((minplus_kernel<false, 4, LWP_TK_SMALL>), grid, block, 0, stream, args);
         else hipLaunchKernelGGL((minplus_kernel<false, 8, 16>), grid, block, 0, stream, args);
     }
     return hipGetLastError();
