@@ -10,6 +10,14 @@ namespace {
 
 constexpr int kThreads = 256;
 
+// Pointers read out of descriptors are generic to the compiler; these casts say "global memory"
+// so that plain global loads/stores are emitted instead of flat ones.
+using gi32c = const int32_t __attribute__((address_space(1)))*;
+using gi32 = int32_t __attribute__((address_space(1)))*;
+using v4i = int __attribute__((ext_vector_type(4)));
+using gv4c = const v4i __attribute__((address_space(1)))*;
+using gv4 = v4i __attribute__((address_space(1)))*;
+
 __device__ __forceinline__ int wave_min(int v) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v = min(v, __shfl_xor(v, o));
@@ -41,23 +49,21 @@ __global__ __launch_bounds__(kThreads) void edge_sum_desc_kernel(const EdgeDesc*
     const int64_t stride = (int64_t)gridDim.x * kThreads;
     const int64_t t0 = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     int lo = 0x7fffffff, hi = (int)0x80000000;
+    const gi32 out = (gi32)(uintptr_t)d.out;
     if (vec) {
         const int64_t n4 = cells >> 2;
         for (int64_t x = t0; x < n4; x += stride) {
-            int4 acc = reinterpret_cast<const int4*>(sp[0])[x];
-            for (int q = 1; q < n; ++q) {
-                const int4 v = reinterpret_cast<const int4*>(sp[q])[x];
-                acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
-            }
-            reinterpret_cast<int4*>(d.out)[x] = acc;
+            v4i acc = ((gv4c)(uintptr_t)sp[0])[x];
+            for (int q = 1; q < n; ++q) acc += ((gv4c)(uintptr_t)sp[q])[x];
+            ((gv4)out)[x] = acc;
             lo = min(min(lo, acc.x), min(acc.y, min(acc.z, acc.w)));
             hi = max(max(hi, acc.x), max(acc.y, max(acc.z, acc.w)));
         }
     } else {
         for (int64_t x = t0; x < cells; x += stride) {
-            int32_t acc = sp[0][x];
-            for (int q = 1; q < n; ++q) acc += sp[q][x];
-            d.out[x] = acc;
+            int32_t acc = ((gi32c)(uintptr_t)sp[0])[x];
+            for (int q = 1; q < n; ++q) acc += ((gi32c)(uintptr_t)sp[q])[x];
+            out[x] = acc;
             lo = min(lo, acc); hi = max(hi, acc);
         }
     }
@@ -176,7 +182,7 @@ __global__ __launch_bounds__(kThreads) void pair_min_kernel(const PairDesc* __re
     unsigned long long best = ~0ull;
     for (int a = blockIdx.x; a < C; a += gridDim.x) {
         const int32_t wa = wi[a];
-        const int32_t* Trow = d.T + (int64_t)a * C;
+        const gi32c Trow = (gi32c)(uintptr_t)d.T + (int64_t)a * C;
         for (int b = threadIdx.x; b < C; b += kThreads) {
             const int32_t s = wa + Trow[b] + wk[b];
             const unsigned long long k = make_key(s, (uint32_t)a * (uint32_t)C + (uint32_t)b);
@@ -232,7 +238,7 @@ __global__ __launch_bounds__(kThreads) void back_substitute_kernel(
         while (lo > 0 && undo[lo - 1].round == r) --lo;
         for (int t = lo + threadIdx.x; t < hi; t += kThreads) {
             const UndoDesc u = undo[t];
-            S[u.j] = u.arg[(int64_t)S[u.i] * C + S[u.k]];
+            S[u.j] = ((gi32c)(uintptr_t)u.arg)[(int64_t)S[u.i] * C + S[u.k]];
         }
         __syncthreads();
         hi = lo;
