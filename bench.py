@@ -80,7 +80,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="cfg4", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4"])
+    ap.add_argument("--workload", default="cfg4", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "resid"])
     ap.add_argument("--layers", type=int, default=64, help="cfg4 only: chain length")
     ap.add_argument("--configs", type=int, default=0, help="override C of the workload")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
@@ -130,6 +130,14 @@ def main():
             p["tc"], p["ts"], p["tx"] = (t.cpu().numpy() for t in tabs)
         elif name == "cfg2":
             p = wl.config2(args.configs or 512)
+        elif name == "resid":
+            # a graph no elimination applies to: one layer feeding three that never rejoin (K = 4);
+            # the whole search is the enumeration of C^4 strategies of the final graph
+            Cr = args.configs or 160
+            e = np.array([[0, 1], [0, 2], [0, 3]], np.int32)
+            tc, ts, tx = wl.random_tables(4, e, Cr, 7, (0, 1 << 20), (0, 1 << 20), (0, 1 << 20))
+            p = {"name": f"resid_star4_C{Cr}", "n_nodes": 4, "edges": e, "C": Cr, "tc": tc, "ts": ts, "tx": tx,
+                 "schedule": wl.SCHEDULE_ROUNDS}
         else:
             p = wl.config0()
         C = p["C"]
@@ -137,6 +145,9 @@ def main():
         n_elim = p["n_nodes"] - 2
         updates = n_elim * C ** 3
         workload = f"{p['name']}: {p['n_nodes']} nodes, {len(p['edges'])} edges, C={C}, {n_elim} node eliminations"
+        if name == "resid":
+            updates = C ** 4      # strategies enumerated, reported in the same field
+            workload = f"{p['name']}: 4 residual nodes, C={C}, {updates:.3g} strategies enumerated per search"
         ctx = Context(0)
         result = {}
 
@@ -144,6 +155,11 @@ def main():
             result["cost"], result["S"] = ctx.search_graph(p["n_nodes"], p["edges"], C, dtc, dts, dtx, p["schedule"])
         if name == "cfg4":
             cpu_payload = ("fold", p)
+        elif name == "resid":
+            # the oracle enumerates at most 2^26 strategies: time it on the first 64 configurations
+            q = dict(p, C=64, tc=np.ascontiguousarray(p["tc"][:, :64]), ts=np.ascontiguousarray(p["ts"][:, :64]),
+                     tx=np.ascontiguousarray(p["tx"][:, :64, :64]), updates=64 ** 4)
+            cpu_payload = ("search", q)
         else:
             p["updates"] = updates
             cpu_payload = ("search", p)

@@ -37,7 +37,7 @@ typedef enum {
     LWP_OK = 0,
     LWP_E_INVAL = -1,          /* null pointer, non-positive size, misaligned pointer        */
     LWP_E_GRAPH = -2,          /* endpoint out of range, self loop, cycle                    */
-    LWP_E_NOT_REDUCIBLE = -3,  /* residual graph is not isolated nodes + single-edge pairs   */
+    LWP_E_NOT_REDUCIBLE = -3,  /* a residual component is too large to enumerate             */
     LWP_E_OVERFLOW = -4,       /* value ranges do not guarantee that every sum fits int32    */
     LWP_E_NOMEM = -5,          /* device or host allocation failed                           */
     LWP_E_HIP = -6             /* a HIP runtime call failed                                  */
@@ -99,7 +99,9 @@ typedef struct { int32_t kind, j, i, k, e1, e2, round; } lwp_step;
  * edges: HOST [n_edges][2] = (src, dst), node ids in [0,n_nodes), parallel edges allowed.
  * steps: HOST, room for max(n_edges,1) entries, may be NULL.  n_steps / n_rounds / n_residual_nodes
  * may be NULL.  Returns LWP_E_GRAPH for a bad endpoint, self loop or cycle and
- * LWP_E_NOT_REDUCIBLE if the residual graph has a node with more than one incident edge. */
+ * LWP_E_NOT_REDUCIBLE if a connected component of the residual graph has more than 12 nodes or
+ * 32 edges (components of one node, of two nodes and one edge, and larger ones that will be
+ * enumerated are all fine). */
 lwp_status lwp_plan_graph(int32_t n_nodes, int32_t n_edges, const int32_t *edges, int32_t schedule,
                           lwp_step *steps, int32_t *n_steps, int32_t *n_rounds,
                           int32_t *n_residual_nodes);
@@ -109,7 +111,11 @@ lwp_status lwp_plan_graph(int32_t n_nodes, int32_t n_edges, const int32_t *edges
  * d_tc, d_ts DEVICE [n_nodes][C]; d_tx DEVICE [n_edges][C][C]; read-only.
  * out_cost HOST int32: t_o of the returned strategy; out_strategy HOST [n_nodes]: configuration
  * index per node.  Among optimal strategies the one produced by the schedule and the
- * lowest-index rule is returned.  Blocking. */
+ * lowest-index rule is returned.  The residual graph (Alg. 1, "enumerating all possible
+ * candidate strategies") is solved per connected component: a node, a pair joined by one edge
+ * (lowest flat index of (source cfg, destination cfg)), or, for K > 2 nodes, enumeration of all
+ * C^K strategies (lexicographically lowest optimum, lower node id more significant), which needs
+ * C^K <= 2^32, else LWP_E_NOT_REDUCIBLE.  Blocking. */
 lwp_status lwp_search_graph(lwp_ctx *ctx, int32_t n_nodes, int32_t n_edges, const int32_t *edges,
                             int32_t C, const int32_t *d_tc, const int32_t *d_ts, const int32_t *d_tx,
                             int32_t schedule, int32_t *out_cost, int32_t *out_strategy);

@@ -17,7 +17,9 @@
  *   - costs are int32 nanoseconds, sums are exact; a sum that leaves int32 is an error;
  *   - every min takes the LOWEST index among equal candidates (strict '<' in ascending order);
  *   - the order of eliminations is the written canonical schedule implemented in orc_search;
- *   - the residual graph may consist of isolated nodes and of node pairs joined by one edge.
+ *   - the residual graph is solved per connected component: one node, a pair joined by one edge
+ *     (lowest flat index of (source cfg, destination cfg)), or outright enumeration of larger
+ *     components (lexicographically lowest optimum, lower node id more significant).
  */
 #include <stdint.h>
 #include <stdlib.h>
@@ -163,9 +165,10 @@ static void sort_ids(int *ids, int n, const live_edge *E)
  *              then eliminate every selected node by Eq. 2 (new edge keeps the
  *              in-edge's id).
  *
- * The residual graph must consist of isolated nodes and pairs joined by one
- * edge; each component is minimised on its own (lowest index / lowest flat
- * index among equals).  The eliminations are then undone in reverse order:
+ * Each connected component of the residual graph is minimised on its own (a
+ * node, a pair joined by one edge, or enumeration of all C^K strategies of a
+ * larger component, K <= 16 and C^K <= 2^26 here).  The eliminations are then
+ * undone in reverse order:
  * S[j] = arg_j[S[i]][S[k]].
  *
  * steps (optional, room for n_edges entries) receives the log; n_steps and
@@ -266,22 +269,63 @@ int orc_search(int n_nodes, int n_edges, const int32_t *edges, int C,
         ++rounds;
     }
 
-    /* ---- residual graph: isolated nodes and pairs joined by one edge ---- */
-    for (int l = 0; l < n_nodes; ++l) { indeg[l] = 0; S[l] = -1; }   /* indeg reused as incident count */
-    for (int e = 0; e < n_edges; ++e) if (E[e].alive) { indeg[E[e].src]++; indeg[E[e].dst]++; }
-    for (int l = 0; l < n_nodes; ++l) if (!dead[l] && indeg[l] > 1) { rc = ORC_E_NOT_REDUCIBLE; goto done; }
+    /* ---- residual graph (Alg. 1: enumerate all strategies of the final graph) ----
+     * Connected components are independent.  One node: min_a w[a].  Two nodes joined by one edge:
+     * orc_final_pair.  Anything larger is enumerated outright, configurations of the lower node id
+     * varying slowest, so that strict '<' keeps the lexicographically lowest optimum. */
     {
+        int *comp = indeg;                       /* reused: component label per node */
         int64_t total = 0;
-        for (int e = 0; e < n_edges; ++e) if (E[e].alive) {
-            int64_t c; int32_t a, b;
-            int r = orc_final_pair(C, w + (size_t)E[e].src * C, E[e].tab, w + (size_t)E[e].dst * C, &c, &a, &b);
-            if (r != ORC_OK) { rc = r; goto done; }
-            total += c; S[E[e].src] = a; S[E[e].dst] = b;
+        for (int l = 0; l < n_nodes; ++l) { comp[l] = dead[l] ? -1 : l; S[l] = -1; }
+        for (int changed = 1; changed;) {        /* label propagation; graphs here are tiny */
+            changed = 0;
+            for (int e = 0; e < n_edges; ++e) if (E[e].alive) {
+                int a = comp[E[e].src], b = comp[E[e].dst];
+                if (a != b) { int m = a < b ? a : b; comp[E[e].src] = comp[E[e].dst] = m; changed = 1; }
+            }
         }
-        for (int l = 0; l < n_nodes; ++l) if (!dead[l] && indeg[l] == 0) {
-            int best = 0;
-            for (int c = 1; c < C; ++c) if (w[(size_t)l * C + c] < w[(size_t)l * C + best]) best = c;
-            total += w[(size_t)l * C + best]; S[l] = best;
+        for (int root = 0; root < n_nodes; ++root) {
+            if (dead[root] || comp[root] != root) continue;
+            int K = 0, ne = 0;
+            for (int l = 0; l < n_nodes; ++l) if (comp[l] == root) ine[K++] = l;      /* ine reused: member nodes, ascending */
+            for (int e = 0; e < n_edges; ++e) if (E[e].alive && comp[E[e].src] == root) oute[ne++] = e;   /* oute reused */
+            int64_t c = 0;
+            if (K == 1) {
+                int l = ine[0], best = 0;
+                for (int q = 1; q < C; ++q) if (w[(size_t)l * C + q] < w[(size_t)l * C + best]) best = q;
+                c = w[(size_t)l * C + best]; S[l] = best;
+            } else if (K == 2 && ne == 1) {
+                int e = oute[0]; int32_t a, b;
+                int r = orc_final_pair(C, w + (size_t)E[e].src * C, E[e].tab, w + (size_t)E[e].dst * C, &c, &a, &b);
+                if (r != ORC_OK) { rc = r; goto done; }
+                S[E[e].src] = a; S[E[e].dst] = b;
+            } else {
+                double n_assign = 1.0;
+                for (int q = 0; q < K; ++q) n_assign *= C;
+                if (n_assign > (double)(1 << 26) || K > 16) { rc = ORC_E_NOT_REDUCIBLE; goto done; }
+                int digit[16], bestd[16], pos_of_src[64], pos_of_dst[64];
+                if (ne > 64) { rc = ORC_E_NOT_REDUCIBLE; goto done; }
+                for (int x = 0; x < ne; ++x)
+                    for (int q = 0; q < K; ++q) {
+                        if (ine[q] == E[oute[x]].src) pos_of_src[x] = q;
+                        if (ine[q] == E[oute[x]].dst) pos_of_dst[x] = q;
+                    }
+                for (int q = 0; q < K; ++q) digit[q] = 0;
+                int have = 0;
+                for (;;) {
+                    int64_t t = 0;
+                    for (int q = 0; q < K; ++q) t += w[(size_t)ine[q] * C + digit[q]];
+                    for (int x = 0; x < ne; ++x)
+                        t += E[oute[x]].tab[(size_t)digit[pos_of_src[x]] * C + digit[pos_of_dst[x]]];
+                    if (!fits_i32(t)) { rc = ORC_E_OVERFLOW; goto done; }
+                    if (!have || t < c) { c = t; have = 1; for (int q = 0; q < K; ++q) bestd[q] = digit[q]; }
+                    int q = K - 1;                               /* odometer: last node fastest */
+                    while (q >= 0 && ++digit[q] == C) digit[q--] = 0;
+                    if (q < 0) break;
+                }
+                for (int q = 0; q < K; ++q) S[ine[q]] = bestd[q];
+            }
+            total += c;
         }
         if (!fits_i32(total)) { rc = ORC_E_OVERFLOW; goto done; }
         *out_cost = total;

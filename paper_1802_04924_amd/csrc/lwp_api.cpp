@@ -98,6 +98,18 @@ bool want_small_tiles(int32_t Ci, int32_t Cj, int32_t Ck, int64_t batch) {
     return large_tiles(Ci, Ck, batch) < 2048 || Cj >= 512;
 }
 
+// A residual component is enumerated outright; its flat strategy index must fit 32 bits.
+bool components_enumerable(const Plan& plan, int32_t C) {
+    for (auto& c : plan.comps) {
+        unsigned long long n = 1;
+        for (size_t q = 0; q < c.nodes.size(); ++q) {
+            n *= (unsigned long long)C;
+            if (n > (1ull << 32)) return false;
+        }
+    }
+    return true;
+}
+
 // Timing of one launch when profiling is on.
 struct ScopedTimer {
     lwp_ctx* ctx; size_t idx = (size_t)-1;
@@ -152,6 +164,7 @@ struct Layout {
     std::vector<std::vector<TableRef>> group_src;
     std::vector<int32_t> group_out_slot;
     std::vector<TableRef> final_table;        // per residual pair
+    std::vector<std::vector<TableRef>> comp_tables;   // per enumerated component, per edge
     int32_t n_slots = 0;
 };
 
@@ -198,6 +211,11 @@ Layout plan_buffers(const Plan& plan, int32_t n_edges) {
         for (int32_t s : release) free_slots.push_back(s);
     }
     for (auto& p : plan.pairs) L.final_table.push_back(cur[p.edge]);
+    for (auto& c : plan.comps) {
+        std::vector<TableRef> t;
+        for (int32_t e : c.edges) t.push_back(cur[e]);
+        L.comp_tables.push_back(t);
+    }
     return L;
 }
 
@@ -208,7 +226,7 @@ Layout plan_buffers(const Plan& plan, int32_t n_edges) {
 struct WsLayout {
     size_t w, head, keys, result, args, slots, total;
     size_t desc, desc_bytes;                                   // descriptor block
-    size_t node_desc, edge_desc, src_ptrs, pair_desc, singles, undo;   // offsets inside the block
+    size_t node_desc, edge_desc, src_ptrs, pair_desc, singles, undo, comps;   // offsets inside the block
     int32_t n_ranges;
 };
 
@@ -222,7 +240,7 @@ WsLayout layout_workspace(const Plan& plan, const Layout& L, int32_t n_nodes, in
     o.n_ranges = n_edges + n_nodes + plan.n_node_steps + (int32_t)L.groups.size();
     o.w = put((size_t)n_nodes * C * sizeof(int32_t));
     o.head = put((2 + 2 * (size_t)o.n_ranges) * sizeof(int32_t));
-    o.keys = put(std::max<size_t>(1, plan.pairs.size() + plan.singles.size()) * sizeof(unsigned long long));
+    o.keys = put(std::max<size_t>(1, plan.pairs.size() + plan.singles.size() + plan.comps.size()) * sizeof(unsigned long long));
     o.result = put((2 + (size_t)n_nodes) * sizeof(int32_t));
     {
         size_t b = 0;
@@ -233,6 +251,7 @@ WsLayout layout_workspace(const Plan& plan, const Layout& L, int32_t n_nodes, in
         o.pair_desc = sub(plan.pairs.size() * sizeof(PairDesc));
         o.singles = sub(plan.singles.size() * sizeof(int32_t));
         o.undo = sub((size_t)plan.n_node_steps * sizeof(UndoDesc));
+        o.comps = sub(plan.comps.size() * sizeof(CompDesc));
         o.desc_bytes = std::max<size_t>(b, 16);
     }
     o.desc = put(o.desc_bytes);
@@ -394,7 +413,11 @@ lwp_status lwp_plan_graph(int32_t n_nodes, int32_t n_edges, const int32_t* edges
     if (n_rounds) *n_rounds = plan.n_rounds;
     if (s != LWP_OK) return s;
     if (steps && !plan.steps.empty()) std::memcpy(steps, plan.steps.data(), plan.steps.size() * sizeof(lwp_step));
-    if (n_residual_nodes) *n_residual_nodes = (int32_t)(2 * plan.pairs.size() + plan.singles.size());
+    if (n_residual_nodes) {
+        size_t k = 2 * plan.pairs.size() + plan.singles.size();
+        for (auto& c : plan.comps) k += c.nodes.size();
+        *n_residual_nodes = (int32_t)k;
+    }
     return LWP_OK;
 }
 
@@ -404,6 +427,7 @@ size_t lwp_search_workspace_bytes(int32_t n_nodes, int32_t n_edges, const int32_
     Plan plan;
     std::string err;
     if (make_plan(n_nodes, n_edges, edges, schedule, plan, err) != LWP_OK) return 0;
+    if (!components_enumerable(plan, C)) return 0;
     Layout L = plan_buffers(plan, n_edges);
     return layout_workspace(plan, L, n_nodes, n_edges, C).total;
 }
@@ -423,6 +447,8 @@ lwp_status lwp_search_graph(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, cons
         lwp_status s = make_plan(n_nodes, n_edges, edges, schedule, plan, err);
         if (s != LWP_OK) return fail(ctx, s, err);
     }
+    if (!components_enumerable(plan, C))
+        return fail(ctx, LWP_E_NOT_REDUCIBLE, "a residual component has more than 2^32 strategies to enumerate");
     const Layout L = plan_buffers(plan, n_edges);
     const WsLayout W = layout_workspace(plan, L, n_nodes, n_edges, C);
     if (lwp_status s = ensure_workspace(ctx, W.total)) return s;
@@ -440,7 +466,7 @@ lwp_status lwp_search_graph(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, cons
     int32_t* d_slots = reinterpret_cast<int32_t*>(ws + W.slots);
     unsigned long long* d_keys = reinterpret_cast<unsigned long long*>(ws + W.keys);
     int32_t* d_result = reinterpret_cast<int32_t*>(ws + W.result);
-    const int32_t n_comp = (int32_t)(plan.pairs.size() + plan.singles.size());
+    const int32_t n_comp = (int32_t)(plan.pairs.size() + plan.singles.size() + plan.comps.size());
     auto table_ptr = [&](const TableRef& r) -> const int32_t* {
         return r.is_slot ? d_slots + (int64_t)r.id * CC : d_tx + (int64_t)r.id * CC;
     };
@@ -466,6 +492,7 @@ lwp_status lwp_search_graph(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, cons
     PairDesc* pd = reinterpret_cast<PairDesc*>(hb + W.pair_desc);
     int32_t* h_singles = reinterpret_cast<int32_t*>(hb + W.singles);
     UndoDesc* ud = reinterpret_cast<UndoDesc*>(hb + W.undo);
+    CompDesc* cd = reinterpret_cast<CompDesc*>(hb + W.comps);
     char* db = ws + W.desc;
     const NodeDesc* d_nd = reinterpret_cast<const NodeDesc*>(db + W.node_desc);
     const EdgeDesc* d_ed = reinterpret_cast<const EdgeDesc*>(db + W.edge_desc);
@@ -473,6 +500,7 @@ lwp_status lwp_search_graph(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, cons
     const PairDesc* d_pd = reinterpret_cast<const PairDesc*>(db + W.pair_desc);
     const int32_t* d_singles = reinterpret_cast<const int32_t*>(db + W.singles);
     const UndoDesc* d_ud = reinterpret_cast<const UndoDesc*>(db + W.undo);
+    const CompDesc* d_cd = reinterpret_cast<const CompDesc*>(db + W.comps);
 
     std::vector<Range> er(n_edges), wr(n_nodes);
     std::vector<int32_t> erng(n_edges);          // range-pair index of the edge's current table
@@ -535,6 +563,26 @@ lwp_status lwp_search_graph(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, cons
         total_lo += wr[v].lo; total_hi += wr[v].lo;
         h_singles[q] = v;
     }
+    for (size_t q = 0; q < plan.comps.size(); ++q) {
+        const auto& c = plan.comps[q];
+        CompDesc d{};
+        d.K = (int32_t)c.nodes.size(); d.n_edges = (int32_t)c.edges.size();
+        int64_t lo = 0, hi = 0;
+        for (int x = 0; x < d.K; ++x) { d.node[x] = c.nodes[x]; lo += wr[c.nodes[x]].lo; hi += wr[c.nodes[x]].hi; }
+        for (int x = 0; x < d.n_edges; ++x) {
+            d.tab[x] = table_ptr(L.comp_tables[q][x]);
+            d.src_pos[x] = (int8_t)(std::find(c.nodes.begin(), c.nodes.end(), c.esrc[x]) - c.nodes.begin());
+            d.dst_pos[x] = (int8_t)(std::find(c.nodes.begin(), c.nodes.end(), c.edst[x]) - c.nodes.begin());
+            lo += er[c.edges[x]].lo; hi += er[c.edges[x]].hi;
+        }
+        // partial sums only add terms of one sign range each; bound both ends with all terms
+        int64_t neg = 0, pos = 0;
+        for (int x = 0; x < d.K; ++x) { neg += std::min<int64_t>(0, wr[c.nodes[x]].lo); pos += std::max<int64_t>(0, wr[c.nodes[x]].hi); }
+        for (int x = 0; x < d.n_edges; ++x) { neg += std::min<int64_t>(0, er[c.edges[x]].lo); pos += std::max<int64_t>(0, er[c.edges[x]].hi); }
+        if (!fits(neg) || !fits(pos)) return fail(ctx, LWP_E_OVERFLOW, "the sum over a residual component may leave int32");
+        total_lo += lo; total_hi += hi;
+        cd[q] = d;
+    }
     if (!fits(total_lo) || !fits(total_hi)) return fail(ctx, LWP_E_OVERFLOW, "the total cost may leave int32");
 
     // 3. descriptors to the device: one copy
@@ -585,8 +633,12 @@ lwp_status lwp_search_graph(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, cons
     // 5. residual graph, undo, results
     LWP_HIP(ctx, launch_pair_min(d_pd, (int32_t)plan.pairs.size(), d_w, C, d_keys, st));
     LWP_HIP(ctx, launch_single_min(d_singles, (int32_t)plan.singles.size(), d_w, C, d_keys + plan.pairs.size(), st));
+    for (size_t q = 0; q < plan.comps.size(); ++q)
+        LWP_HIP(ctx, launch_component_min(d_cd + q, (int32_t)plan.comps[q].nodes.size(), d_w, C,
+                                          d_keys + plan.pairs.size() + plan.singles.size() + q, st));
     LWP_HIP(ctx, launch_back_substitute(d_pd, (int32_t)plan.pairs.size(), d_singles, (int32_t)plan.singles.size(),
-                                        d_keys, d_ud, plan.n_node_steps, C, n_nodes, d_result, st));
+                                        d_cd, (int32_t)plan.comps.size(), d_keys, d_ud, plan.n_node_steps, C, n_nodes,
+                                        d_result, st));
     int32_t* result = reinterpret_cast<int32_t*>(ctx->pin + pin_result);
     LWP_HIP(ctx, hipMemcpyAsync(result, d_result, (2 + (size_t)n_nodes) * sizeof(int32_t), hipMemcpyDeviceToHost, st));
     LWP_HIP(ctx, hipStreamSynchronize(st));

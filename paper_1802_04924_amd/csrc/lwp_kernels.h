@@ -78,6 +78,16 @@ struct PairDesc {       // residual component with two nodes joined by one edge
     const int32_t* T;   // [C][C]
     int32_t src, dst;
 };
+// Residual component with K > 2 nodes: all C^K strategies are enumerated (C^K <= 2^32).  Node
+// q of the component is digit q of the flat strategy index, digit 0 (lowest node id) most
+// significant.  Edge x joins digits src_pos[x] -> dst_pos[x] with table tab[x].
+constexpr int kCompMaxNodes = 12, kCompMaxEdges = 32;
+struct CompDesc {
+    const int32_t* tab[kCompMaxEdges];
+    int32_t node[kCompMaxNodes];
+    int8_t src_pos[kCompMaxEdges], dst_pos[kCompMaxEdges];
+    int32_t K, n_edges;
+};
 struct UndoDesc {       // one node elimination of the log
     const int32_t* arg; // [C][C]
     int32_t j, i, k, round;
@@ -87,10 +97,15 @@ hipError_t launch_pair_min(const PairDesc* d_pairs, int32_t n_pairs, const int32
                            unsigned long long* d_keys, hipStream_t stream);
 hipError_t launch_single_min(const int32_t* d_singles, int32_t n_singles, const int32_t* d_w, int32_t C,
                              unsigned long long* d_keys /* after the pairs */, hipStream_t stream);
-// Decodes the component minima, then walks the undo list backwards (entries of one round are
-// independent).  result[0] = total cost low word, result[1] = high word, result[2..] = strategy.
+// One launch per component; key = d_keys[index of the component].
+hipError_t launch_component_min(const CompDesc* d_comp, int32_t K, const int32_t* d_w, int32_t C,
+                                unsigned long long* d_key, hipStream_t stream);
+// Decodes the component minima (keys: pairs, then singles, then enumerated components), then
+// walks the undo list backwards (entries of one round are independent).
+// result[0] = total cost low word, result[1] = high word, result[2..] = strategy.
 hipError_t launch_back_substitute(const PairDesc* d_pairs, int32_t n_pairs, const int32_t* d_singles,
-                                  int32_t n_singles, const unsigned long long* d_keys,
+                                  int32_t n_singles, const CompDesc* d_comps, int32_t n_comps,
+                                  const unsigned long long* d_keys,
                                   const UndoDesc* d_undo, int32_t n_undo, int32_t C, int32_t n_nodes,
                                   int32_t* d_result, hipStream_t stream);
 

@@ -10,6 +10,7 @@
 //              takes the first eligible node only.  The new edge (i,k) keeps the in-edge's id.
 #include "lwp_plan.h"
 
+#include <algorithm>
 #include <map>
 #include <queue>
 #include <utility>
@@ -93,15 +94,31 @@ lwp_status make_plan(int32_t n_nodes, int32_t n_edges, const int32_t* edges, int
     }
     plan.n_rounds = round;
 
-    std::vector<int32_t> incident(n_nodes, 0);
-    for (int32_t e = 0; e < n_edges; ++e) if (E[e].live) { incident[E[e].src]++; incident[E[e].dst]++; }
-    for (int32_t v = 0; v < n_nodes; ++v)
-        if (!gone[v] && incident[v] > 1) {
-            err = "residual graph is not reducible to isolated nodes and single-edge pairs";
-            return LWP_E_NOT_REDUCIBLE;
+    // residual graph: connected components over the live edges
+    std::vector<int32_t> label(n_nodes);
+    for (int32_t v = 0; v < n_nodes; ++v) label[v] = gone[v] ? -1 : v;
+    for (bool changed = true; changed;) {
+        changed = false;
+        for (int32_t e = 0; e < n_edges; ++e) if (E[e].live) {
+            int32_t a = label[E[e].src], b = label[E[e].dst];
+            if (a != b) { label[E[e].src] = label[E[e].dst] = std::min(a, b); changed = true; }
         }
-    for (int32_t e = 0; e < n_edges; ++e) if (E[e].live) plan.pairs.push_back({e, E[e].src, E[e].dst});
-    for (int32_t v = 0; v < n_nodes; ++v) if (!gone[v] && incident[v] == 0) plan.singles.push_back(v);
+    }
+    for (int32_t root = 0; root < n_nodes; ++root) {
+        if (gone[root] || label[root] != root) continue;
+        ResidualComponent c;
+        for (int32_t v = root; v < n_nodes; ++v) if (label[v] == root) c.nodes.push_back(v);
+        for (int32_t e = 0; e < n_edges; ++e) if (E[e].live && label[E[e].src] == root) {
+            c.edges.push_back(e); c.esrc.push_back(E[e].src); c.edst.push_back(E[e].dst);
+        }
+        if (c.nodes.size() == 1) plan.singles.push_back(root);
+        else if (c.nodes.size() == 2 && c.edges.size() == 1) plan.pairs.push_back({c.edges[0], c.esrc[0], c.edst[0]});
+        else if ((int)c.nodes.size() > kMaxComponentNodes || (int)c.edges.size() > kMaxComponentEdges) {
+            err = "a residual component has more than " + std::to_string(kMaxComponentNodes) + " nodes or " +
+                  std::to_string(kMaxComponentEdges) + " edges";
+            return LWP_E_NOT_REDUCIBLE;
+        } else plan.comps.push_back(std::move(c));
+    }
     return LWP_OK;
 }
 

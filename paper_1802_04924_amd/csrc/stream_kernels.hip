@@ -205,20 +205,63 @@ __global__ __launch_bounds__(kThreads) void single_min_kernel(const int32_t* __r
     block_min_to(best, &keys[blockIdx.y]);
 }
 
+// Enumeration of a residual component (Alg. 1: the final graph's strategies are enumerated).  One
+// thread per assignment of the first K-1 nodes; the last node's configurations are an inner loop.
+// The flat index p*C + c ascends lexicographically (lowest node id most significant), so the 64-bit
+// (cost, index) minimum is the lexicographically lowest optimum.
+__global__ __launch_bounds__(kThreads) void component_min_kernel(const CompDesc* __restrict__ comp,
+                                                                 const int32_t* __restrict__ w, int32_t C,
+                                                                 unsigned long long n_prefix,
+                                                                 unsigned long long* __restrict__ key) {
+    __shared__ CompDesc d;
+    for (int x = threadIdx.x; x < (int)(sizeof(CompDesc) / 4); x += kThreads)
+        reinterpret_cast<int32_t*>(&d)[x] = reinterpret_cast<const int32_t*>(comp)[x];
+    __syncthreads();
+    const int K = d.K, ne = d.n_edges, last = K - 1;
+    unsigned long long best = ~0ull;
+    const unsigned long long stride = (unsigned long long)gridDim.x * kThreads;
+    for (unsigned long long p = (unsigned long long)blockIdx.x * kThreads + threadIdx.x; p < n_prefix; p += stride) {
+        int digit[kCompMaxNodes];
+        unsigned long long r = p;
+        for (int q = last - 1; q >= 0; --q) { digit[q] = (int)(r % (unsigned)C); r /= (unsigned)C; }
+        int32_t base = 0;
+        for (int q = 0; q < last; ++q) base += w[(int64_t)d.node[q] * C + digit[q]];
+        for (int x = 0; x < ne; ++x)
+            if (d.src_pos[x] != last && d.dst_pos[x] != last)
+                base += ((gi32c)(uintptr_t)d.tab[x])[(int64_t)digit[d.src_pos[x]] * C + digit[d.dst_pos[x]]];
+        const int32_t* wl = w + (int64_t)d.node[last] * C;
+        for (int c = 0; c < C; ++c) {
+            int32_t t = base + wl[c];
+            for (int x = 0; x < ne; ++x) {
+                if (d.src_pos[x] == last) t += ((gi32c)(uintptr_t)d.tab[x])[(int64_t)c * C + digit[d.dst_pos[x]]];
+                else if (d.dst_pos[x] == last) t += ((gi32c)(uintptr_t)d.tab[x])[(int64_t)digit[d.src_pos[x]] * C + c];
+            }
+            const unsigned long long k = make_key(t, (uint32_t)(p * (unsigned)C + (unsigned)c));
+            best = k < best ? k : best;
+        }
+    }
+    block_min_to(best, key);
+}
+
 // ---- undo (Alg. 1: S^(i) = S^(i+1) + c_j, c_j the stored argmin of Eq. 2 at (c_i, c_k)) ---------
 __global__ __launch_bounds__(kThreads) void back_substitute_kernel(
     const PairDesc* __restrict__ pairs, int32_t n_pairs, const int32_t* __restrict__ singles, int32_t n_singles,
+    const CompDesc* __restrict__ comps, int32_t n_comps,
     const unsigned long long* __restrict__ keys, const UndoDesc* __restrict__ undo, int32_t n_undo, int32_t C,
     int32_t n_nodes, int32_t* __restrict__ result) {
     __shared__ long long ssum[kThreads / 64];
     int32_t* S = result + 2;
     long long cost = 0;
-    for (int t = threadIdx.x; t < n_pairs + n_singles; t += kThreads) {
+    for (int t = threadIdx.x; t < n_pairs + n_singles + n_comps; t += kThreads) {
         const unsigned long long k = keys[t];
-        const uint32_t flat = (uint32_t)k;
+        uint32_t flat = (uint32_t)k;
         cost += (long long)(int32_t)((uint32_t)(k >> 32) ^ 0x80000000u);
         if (t < n_pairs) { S[pairs[t].src] = (int32_t)(flat / (uint32_t)C); S[pairs[t].dst] = (int32_t)(flat % (uint32_t)C); }
-        else S[singles[t - n_pairs]] = (int32_t)flat;
+        else if (t < n_pairs + n_singles) S[singles[t - n_pairs]] = (int32_t)flat;
+        else {
+            const CompDesc* cd = comps + (t - n_pairs - n_singles);
+            for (int q = cd->K - 1; q >= 0; --q) { S[cd->node[q]] = (int32_t)(flat % (uint32_t)C); flat /= (uint32_t)C; }
+        }
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) cost += __shfl_xor(cost, o);
@@ -325,12 +368,23 @@ hipError_t launch_single_min(const int32_t* d_singles, int32_t n_singles, const 
     return hipGetLastError();
 }
 
+hipError_t launch_component_min(const CompDesc* d_comp, int32_t K, const int32_t* d_w, int32_t C,
+                                unsigned long long* d_key, hipStream_t stream) {
+    unsigned long long n_prefix = 1;
+    for (int q = 0; q + 1 < K; ++q) n_prefix *= (unsigned long long)C;
+    unsigned long long blocks = (n_prefix + kThreads - 1) / kThreads;
+    if (blocks > 65536) blocks = 65536;
+    hipLaunchKernelGGL(component_min_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, d_comp, d_w, C, n_prefix, d_key);
+    return hipGetLastError();
+}
+
 hipError_t launch_back_substitute(const PairDesc* d_pairs, int32_t n_pairs, const int32_t* d_singles,
-                                  int32_t n_singles, const unsigned long long* d_keys,
+                                  int32_t n_singles, const CompDesc* d_comps, int32_t n_comps,
+                                  const unsigned long long* d_keys,
                                   const UndoDesc* d_undo, int32_t n_undo, int32_t C, int32_t n_nodes,
                                   int32_t* d_result, hipStream_t stream) {
     hipLaunchKernelGGL(back_substitute_kernel, dim3(1), dim3(kThreads), 0, stream, d_pairs, n_pairs, d_singles,
-                       n_singles, d_keys, d_undo, n_undo, C, n_nodes, d_result);
+                       n_singles, d_comps, n_comps, d_keys, d_undo, n_undo, C, n_nodes, d_result);
     return hipGetLastError();
 }
 

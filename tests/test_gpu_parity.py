@@ -187,12 +187,37 @@ def test_search_small_irregular_graphs(ctx):
             run_search(ctx, p)
 
 
+IRREDUCIBLE = {
+    "star_out": (4, [(0, 1), (0, 2), (0, 3)]),
+    "star_in": (4, [(1, 0), (2, 0), (3, 0)]),
+    "two_sources": (4, [(0, 2), (1, 2), (2, 3)]),
+    "bipartite": (4, [(0, 2), (0, 3), (1, 2), (1, 3)]),
+    "two_towers": (7, [(0, 1), (1, 4), (2, 3), (3, 4), (4, 5), (5, 6), (4, 6)]),
+    "mixed_components": (8, [(0, 1), (0, 2), (0, 3), (4, 5), (5, 6), (7, 6)]),
+    "triple_in": (9, [(0, 1), (1, 8), (2, 3), (3, 8), (4, 5), (5, 6), (6, 8), (7, 8)]),
+}
+
+
+@pytest.mark.parametrize("name", sorted(IRREDUCIBLE))
+@pytest.mark.parametrize("C,hi", [(1, 7), (2, 1), (5, 3), (23, 1000), (64, 1 << 20)])
+def test_search_enumerates_residual_components(ctx, name, C, hi):
+    from paper_1802_04924_amd import plan_graph
+    n, e = IRREDUCIBLE[name]
+    edges = np.asarray(e, np.int32)
+    if C ** plan_graph(n, edges)["n_residual_nodes"] > (1 << 26):
+        pytest.skip("more strategies than the oracle enumerates")
+    for schedule in (wl.SCHEDULE_ROUNDS, wl.SCHEDULE_LEFT_FOLD):
+        tc, ts, tx = wl.random_tables(n, edges, C, C + hi, (0, hi), (0, hi), (0, hi))
+        p = {"n_nodes": n, "edges": edges, "C": C, "tc": tc, "ts": ts, "tx": tx, "schedule": schedule}
+        run_search(ctx, p)
+
+
 def test_search_errors(ctx):
     from paper_1802_04924_amd import LwpError
     edges = np.array([[0, 1], [0, 2], [0, 3]], np.int32)
-    tc, ts, tx = wl.random_tables(4, edges, 2, 0, (0, 5), (0, 5), (0, 5))
+    tc, ts, tx = wl.random_tables(4, edges, 300, 0, (0, 5), (0, 5), (0, 5))
     with pytest.raises(LwpError) as e:
-        ctx.search_graph(4, edges, 2, dev(tc), dev(ts), dev(tx))
+        ctx.search_graph(4, edges, 300, dev(tc), dev(ts), dev(tx))     # 300^4 > 2^32 strategies
     assert e.value.code == -3
     p = wl.chain_problem(4, 8, 1, tc_range=(1 << 30, (1 << 30) + 5))
     with pytest.raises(LwpError) as e:

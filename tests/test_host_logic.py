@@ -88,9 +88,20 @@ def test_scheduler_rejects_bad_graphs(lib):
     assert code(3, [(0, 3)]) == binding.E_GRAPH              # endpoint out of range
     assert code(3, [(1, 1)]) == binding.E_GRAPH              # self loop
     assert code(3, [(0, 1), (1, 2), (2, 0)]) == binding.E_GRAPH   # cycle
-    assert code(4, [(0, 1), (0, 2), (0, 3)]) == binding.E_NOT_REDUCIBLE
+    assert code(14, [(0, k) for k in range(1, 14)]) == binding.E_NOT_REDUCIBLE     # 14-node residual star
     assert code(0, []) == binding.E_INVAL
     assert code(2, [(0, 1)], schedule=7) == binding.E_INVAL
+
+
+def test_residual_components(lib):
+    star = np.array([(0, 1), (0, 2), (0, 3)], np.int32)
+    plan = binding.plan_graph(4, star, 0)
+    assert len(plan["steps"]) == 0 and plan["n_residual_nodes"] == 4
+    assert binding.search_workspace_bytes(4, star, 256, 0) > 0          # 2^32 strategies: enumerable
+    assert binding.search_workspace_bytes(4, star, 257, 0) == 0         # one more configuration: refused
+    towers = np.array([(0, 1), (1, 4), (2, 3), (3, 4), (4, 5), (5, 6), (4, 6)], np.int32)
+    plan = binding.plan_graph(7, towers, 0)
+    assert plan["n_residual_nodes"] == 4 and [int(s["j"]) for s in plan["steps"] if s["kind"] == 0] == [1, 3, 5]
 
 
 def test_workspace_size(lib):

@@ -277,10 +277,37 @@ def test_forkjoin_full_topology_counts():
     assert r2["cost"] == r["cost"]
 
 
-def test_not_reducible_graph_is_reported():
-    # node 0 feeds three nodes that never rejoin: the residual graph is a star
+IRREDUCIBLE = {
+    "star_out": (4, [(0, 1), (0, 2), (0, 3)]),
+    "star_in": (4, [(1, 0), (2, 0), (3, 0)]),
+    "two_sources": (4, [(0, 2), (1, 2), (2, 3)]),
+    "bipartite": (4, [(0, 2), (0, 3), (1, 2), (1, 3)]),
+    "two_towers": (7, [(0, 1), (1, 4), (2, 3), (3, 4), (4, 5), (5, 6), (4, 6)]),
+    "mixed_components": (8, [(0, 1), (0, 2), (0, 3), (4, 5), (5, 6), (7, 6)]),
+}
+
+
+@pytest.mark.parametrize("name", sorted(IRREDUCIBLE))
+@pytest.mark.parametrize("C,hi", [(2, 1), (3, 5), (4, 100)])
+def test_residual_components_are_enumerated(name, C, hi):
+    # graphs whose final graph keeps K > 2 nodes (Alg. 1 enumerates its strategies)
+    n, e = IRREDUCIBLE[name]
+    e = np.asarray(e, np.int32)
+    for seed in range(3):
+        tc, ts, tx = wl.random_tables(n, e, C, seed, (0, hi), (0, hi), (0, hi))
+        best, S_lex, n_opt = brute.brute_force(n, e, C, tc, ts, tx)
+        r = oracle.search(n, e, C, tc, ts, tx)
+        assert r["cost"] == best
+        assert oracle.strategy_cost(n, e, C, tc, ts, tx, r["strategy"]) == best
+        if n_opt == 1 or (len(r["steps"]) == 0 and name != "mixed_components"):
+            # a single component that is enumerated outright returns the lexicographically lowest optimum
+            assert np.array_equal(r["strategy"], S_lex)
+
+
+def test_too_many_strategies_to_enumerate_is_reported():
+    # node 0 feeds three nodes that never rejoin: K = 4 residual nodes, 600^4 strategies
     edges = np.array([[0, 1], [0, 2], [0, 3]], np.int32)
-    tc, ts, tx = rand_problem(np.random.default_rng(0), 4, edges, 2, 5)
+    tc, ts, tx = rand_problem(np.random.default_rng(0), 4, edges, 600, 5)
     with pytest.raises(oracle.OracleError) as e:
-        oracle.search(4, edges, 2, tc, ts, tx)
+        oracle.search(4, edges, 600, tc, ts, tx)
     assert e.value.code == oracle.E_NOT_REDUCIBLE
