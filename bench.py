@@ -84,6 +84,8 @@ def main():
     ap.add_argument("--layers", type=int, default=64, help="cfg4 only: chain length")
     ap.add_argument("--configs", type=int, default=0, help="override C of the workload")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--no-events", action="store_true",
+                    help="diagnostic: do not bracket the elimination launches with HIP events (no roofline figures)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference dispatch for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
@@ -174,7 +176,7 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    ctx.profile_enable(True)
+    ctx.profile_enable(not args.no_events)
     ctx.profile_reset()
     t0 = time.perf_counter()
     for _ in range(args.steps):

@@ -110,6 +110,15 @@ bool components_enumerable(const Plan& plan, int32_t C) {
     return true;
 }
 
+// Groups of 256 threads per 64 x 64 tile: with fewer workgroups than compute units a tile's c
+// range is shared by 2 or 4 groups (each needs a few stages of 32 candidates to be worth it).
+int choose_ksplit(int64_t workgroups, int32_t Cj, bool small_tiles) {
+    if (!small_tiles) return 1;
+    if (workgroups <= 256 && Cj >= 256) return 4;
+    if (workgroups <= 512 && Cj >= 128) return 2;
+    return 1;
+}
+
 // Timing of one launch when profiling is on.
 struct ScopedTimer {
     lwp_ctx* ctx; size_t idx = (size_t)-1;
@@ -384,7 +393,7 @@ lwp_status lwp_eliminate_node(lwp_ctx* ctx, int32_t batch, int32_t Ci, int32_t C
     a.tilesM = (int32_t)tilesM; a.tilesN = (int32_t)tilesN;
     {
         ScopedTimer tm(ctx, 0, (int64_t)batch * Ci * Cj * Ck, keyed);
-        LWP_HIP(ctx, launch_minplus(a, keyed, small, ctx->stream));
+        LWP_HIP(ctx, launch_minplus(a, keyed, small, choose_ksplit(tilesM * tilesN * batch, Cj, small), ctx->stream));
     }
     return LWP_OK;
 }
@@ -625,7 +634,7 @@ lwp_status lwp_search_graph(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, cons
             na.Ci = na.Cj = na.Ck = C; na.batch = (int32_t)(b - a);
             na.tilesM = na.tilesN = (C + tile - 1) / tile;
             ScopedTimer tm(ctx, 0, (int64_t)(b - a) * CC * C, keyed);
-            LWP_HIP(ctx, launch_minplus(na, keyed, small, st));
+            LWP_HIP(ctx, launch_minplus(na, keyed, small, choose_ksplit((int64_t)na.tilesM * na.tilesN * na.batch, C, small), st));
             a = b;
         }
     }

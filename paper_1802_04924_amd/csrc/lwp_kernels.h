@@ -43,8 +43,9 @@ constexpr int64_t kKeyedMaxSpreadLarge = (1ll << 27) - 2, kKeyedMaxSpreadSmall =
 
 // keyed = true launches the packed-key variant, keyed = false the plain int32 compare/select
 // variant (ranges ignored).  small_tiles selects 64 x 64 output tiles instead of 128 x 128;
-// tilesM / tilesN in args must match.
-hipError_t launch_minplus(const NodeArgs& args, bool keyed, bool small_tiles, hipStream_t stream);
+// tilesM / tilesN in args must match.  ksplit (1, 2 or 4; 64 x 64 tiles only, plain variant at most
+// 2) is the number of 256-thread groups that share one tile, each walking a part of the c range.
+hipError_t launch_minplus(const NodeArgs& args, bool keyed, bool small_tiles, int ksplit, hipStream_t stream);
 
 // ---- edge elimination (Eq. 3) --------------------------------------------------------------
 // out = sum of n_src tables of `cells` elements.  srcs indexes a device array of table pointers.

@@ -5,8 +5,11 @@
 // workgroup (256 threads = 4 wavefronts) owns a square output tile and walks c in stages of 16
 // that are staged through LDS (double-buffered, one barrier per stage); every thread keeps an
 // RB x RB block of running minima in registers (RB = 8: 128 x 128 tiles for throughput; RB = 4:
-// 64 x 64 tiles when a launch would otherwise leave most compute units idle).  w is folded into A
-// while A is staged, so the inner loop is one add and half a three-way min per candidate.
+// 64 x 64 tiles).  w is folded into A while A is staged, so the inner loop is one add and half a
+// three-way min per candidate.  When a launch has fewer tiles than the chip has compute units, KS
+// groups of 256 threads share one tile: each group walks its own contiguous part of the c range
+// with its own LDS buffers, and the groups' (minimum, argmin) blocks are merged through LDS at the
+// end in ascending-c order with a strict '<', which keeps the lowest-index rule.
 //
 // Two arithmetic variants:
 //   keyed   candidates are 32-bit keys (cost << tb) | (1 + position of c in its chunk); a chunk
@@ -46,14 +49,18 @@ __device__ __forceinline__ int wave_max_i32(int v) {
     return v;
 }
 
-template <bool KEYED, int RB, int TK>
-__global__ __launch_bounds__(NT, KEYED ? 2 : 1) void minplus_kernel(const NodeArgs p) {
+template <bool KEYED, int RB, int TK, int KS>
+__global__ __launch_bounds__(NT * KS, (KS > 1) ? KS : (KEYED ? 2 : 1)) void minplus_kernel(const NodeArgs p) {
     constexpr int TM = 16 * RB, TN = 16 * RB;   // output tile
     constexpr int EP = TM * TK / NT;            // elements of A and of B each thread stages per stage
     constexpr int QUADS = RB / 4;
     static_assert(EP % 4 == 0 && TK % EP == 0 && TN % EP == 0 && (TN / EP) * TK == NT, "staging assignment");
-    __shared__ __attribute__((aligned(16))) uint32_t As[2][TK][TM];   // [stage][c][a]  (A transposed)
-    __shared__ __attribute__((aligned(16))) uint32_t Bs[2][TK][TN];   // [stage][c][b]
+    // per group: A tile [stage][c][a] (A transposed) and B tile [stage][c][b], double-buffered
+    __shared__ __attribute__((aligned(16))) uint32_t lds[KS][2][2][TK][TM];
+    static_assert(TM == TN, "square tiles");
+    const int grp = (KS > 1) ? (int)(threadIdx.x / NT) : 0;
+    uint32_t (*As)[TK][TM] = lds[grp][0];
+    uint32_t (*Bs)[TK][TN] = lds[grp][1];
 
     // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Give every XCD a
     // contiguous range of logical ids, and walk the tiles of a product in panels of 8 tile rows,
@@ -121,7 +128,7 @@ __global__ __launch_bounds__(NT, KEYED ? 2 : 1) void minplus_kernel(const NodeAr
     const uint32_t padA = KEYED ? ~fmask : 0x7fffffffu;   // never strictly below any running minimum
     const int spc = KEYED ? (int)(fmask / TK) : 1;        // stages per chunk: TK*spc <= 2^tb - 1
 
-    const int tid = threadIdx.x;
+    const int tid = (KS > 1) ? (int)(threadIdx.x % NT) : (int)threadIdx.x;   // index inside the group
     const int tx = tid & 15, ty = tid >> 4;
     // global -> LDS assignment: A: one row, EP consecutive c;  B: one c, EP consecutive columns
     constexpr int TPR = TK / EP;                 // threads per A row
@@ -201,17 +208,23 @@ __global__ __launch_bounds__(NT, KEYED ? 2 : 1) void minplus_kernel(const NodeAr
 #pragma unroll
         for (int j = 0; j < RB; ++j) { m1[i][j] = padA; rec[i][j] = 0u; }
 
+    // group g of the workgroup walks stages [g*n_g, (g+1)*n_g); stages past the end of c see only
+    // padding (never a winner), so every group runs the same number of barriers
     const int nstages = (Cj + TK - 1) / TK;
-    int sic = 0;        // stage index inside the current chunk
-    int chunk_c0 = 0;   // first c of the current chunk
+    const int n_g = (nstages + KS - 1) / KS;
+    const int s_first = grp * n_g;
+    int sic = 0;                      // stage index inside the current chunk
+    int chunk_c0 = s_first * TK;      // first c of the current chunk
+    if (KS > 1) { pA += (int64_t)s_first * TK; pW += (int64_t)s_first * TK; pB += (int64_t)s_first * TK * Ck; }
 
-    fetch(0);
-    stash(0, 0, 0);
+    fetch(s_first * TK);
+    stash(s_first * TK, 0, 0);
     __syncthreads();
 
-    for (int s = 0; s < nstages; ++s) {
-        const int buf = s & 1;
-        const bool more = (s + 1) < nstages;
+    for (int it = 0; it < n_g; ++it) {
+        const int s = s_first + it;
+        const int buf = it & 1;
+        const bool more = (it + 1) < n_g;
         const bool chunk_end = (sic + 1 == spc);
         if (more) fetch((s + 1) * TK);
 
@@ -248,6 +261,17 @@ __global__ __launch_bounds__(NT, KEYED ? 2 : 1) void minplus_kernel(const NodeAr
                         }
                 }
             }
+            // keep the LDS reads of later iterations behind this iteration's arithmetic (otherwise a
+            // whole stage of operands is loaded first and the register file overflows): the plain
+            // variant's selects get sunk below the reads unless their results are pinned here
+            if (!KEYED) {
+#pragma unroll
+                for (int i = 0; i < RB; ++i)
+#pragma unroll
+                    for (int j = 0; j < RB; j += 4)
+                        asm volatile("" : "+v"(m1[i][j]), "+v"(m1[i][j + 1]), "+v"(m1[i][j + 2]), "+v"(m1[i][j + 3]),
+                                          "+v"(rec[i][j]), "+v"(rec[i][j + 1]), "+v"(rec[i][j + 2]), "+v"(rec[i][j + 3]));
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
 
@@ -269,17 +293,50 @@ __global__ __launch_bounds__(NT, KEYED ? 2 : 1) void minplus_kernel(const NodeAr
         __syncthreads();
     }
 
+    // merge the groups' blocks: groups 1..KS-1 publish (cost, argmin) through LDS, group 0 folds
+    // them in ascending-c order; strict '<' lets the earlier group keep ties
+    if (KS > 1) {
+        int32_t (*xc)[RB * RB][NT] = reinterpret_cast<int32_t (*)[RB * RB][NT]>(&lds[0][0][0][0][0]);
+        uint32_t (*xr)[RB * RB][NT] = reinterpret_cast<uint32_t (*)[RB * RB][NT]>(&lds[0][0][0][0][0] + (KS - 1) * RB * RB * NT);
+        static_assert(2 * (KS - 1) * RB * RB * NT <= KS * 4 * TK * TM, "merge buffers fit the tile buffers");
+        if (grp > 0) {
+#pragma unroll
+            for (int i = 0; i < RB; ++i)
+#pragma unroll
+                for (int j = 0; j < RB; ++j) {
+                    xc[grp - 1][i * RB + j][tid] = KEYED ? (int32_t)(m1[i][j] >> tb) + offA + offB : (int32_t)m1[i][j];
+                    xr[grp - 1][i * RB + j][tid] = rec[i][j];
+                }
+        }
+        __syncthreads();
+        if (grp == 0)
+#pragma unroll
+        for (int i = 0; i < RB; ++i)
+#pragma unroll
+            for (int j = 0; j < RB; ++j) {
+                int32_t best = KEYED ? (int32_t)(m1[i][j] >> tb) + offA + offB : (int32_t)m1[i][j];
+                uint32_t barg = rec[i][j];
+                for (int g = 0; g < KS - 1; ++g) {
+                    const int32_t c2 = xc[g][i * RB + j][tid];
+                    const uint32_t r2 = xr[g][i * RB + j][tid];
+                    if (c2 < best) { best = c2; barg = r2; }
+                }
+                m1[i][j] = (uint32_t)best; rec[i][j] = barg;
+            }
+    }
+    constexpr bool RAW = KEYED && KS == 1;     // m1 still holds keys (otherwise plain costs)
+
     // epilogue: thread rows {h*64 + ty*4 + 0..3}, columns {h*64 + tx*4 + 0..3}, h < QUADS
     const bool vecO = ((Ck & 3) == 0) && ((((uintptr_t)O) | ((uintptr_t)G)) & 15) == 0 && (b0 + TN <= Ck);
     int vmin = 0x7fffffff, vmax = (int)0x80000000;
 #pragma unroll
     for (int i = 0; i < RB; ++i) {
         const int a = a0 + (i >> 2) * 64 + ty * 4 + (i & 3);
-        if (a >= Ci) continue;
+        if (a >= Ci || grp != 0) continue;    // only the first group holds the merged block
         int32_t val[RB];
 #pragma unroll
         for (int j = 0; j < RB; ++j)
-            val[j] = KEYED ? (int32_t)(m1[i][j] >> tb) + offA + offB : (int32_t)m1[i][j];
+            val[j] = RAW ? (int32_t)(m1[i][j] >> tb) + offA + offB : (int32_t)m1[i][j];
 #pragma unroll
         for (int h = 0; h < QUADS; ++h) {
             const int b = b0 + h * 64 + tx * 4;
@@ -303,10 +360,10 @@ __global__ __launch_bounds__(NT, KEYED ? 2 : 1) void minplus_kernel(const NodeAr
     }
     if (d.rngOut) {   // leave the measured range of this table for the launches that consume it
         vmin = wave_min_i32(vmin); vmax = wave_max_i32(vmax);
-        int* red = reinterpret_cast<int*>(&As[0][0][0]);      // all reads of the tiles are done
-        if ((tid & 63) == 0) { red[2 * (tid >> 6)] = vmin; red[2 * (tid >> 6) + 1] = vmax; }
+        __shared__ int red[2 * (NT / 64)];
+        if ((tid & 63) == 0 && grp == 0) { red[2 * (tid >> 6)] = vmin; red[2 * (tid >> 6) + 1] = vmax; }
         __syncthreads();
-        if (tid == 0) {
+        if (tid == 0 && grp == 0) {
             for (int q = 1; q < NT / 64; ++q) { vmin = min(vmin, red[2 * q]); vmax = max(vmax, red[2 * q + 1]); }
             if (vmin <= vmax) { atomicMin(&d.rngOut[0], vmin); atomicMax(&d.rngOut[1], vmax); }
         }
@@ -315,16 +372,20 @@ __global__ __launch_bounds__(NT, KEYED ? 2 : 1) void minplus_kernel(const NodeAr
 
 }  // namespace
 
-hipError_t launch_minplus(const NodeArgs& args, bool keyed, bool small_tiles, hipStream_t stream) {
+hipError_t launch_minplus(const NodeArgs& args, bool keyed, bool small_tiles, int ksplit, hipStream_t stream) {
     const int64_t blocks = (int64_t)args.tilesM * args.tilesN * args.batch;
     if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    dim3 grid((unsigned)blocks), block(NT);
-    if (keyed) {
-        if (small_tiles) hipLaunchKernelGGL((minplus_kernel<true, 4, LWP_TK_SMALL>), grid, block, 0, stream, args);
-        else hipLaunchKernelGGL((minplus_kernel<true, 8, 16>), grid, block, 0, stream, args);
+    dim3 grid((unsigned)blocks);
+    if (!small_tiles) {
+        if (keyed) hipLaunchKernelGGL((minplus_kernel<true, 8, 16, 1>), grid, dim3(NT), 0, stream, args);
+        else hipLaunchKernelGGL((minplus_kernel<false, 8, 16, 1>), grid, dim3(NT), 0, stream, args);
+    } else if (keyed) {
+        if (ksplit >= 4) hipLaunchKernelGGL((minplus_kernel<true, 4, LWP_TK_SMALL, 4>), grid, dim3(4 * NT), 0, stream, args);
+        else if (ksplit >= 2) hipLaunchKernelGGL((minplus_kernel<true, 4, LWP_TK_SMALL, 2>), grid, dim3(2 * NT), 0, stream, args);
+        else hipLaunchKernelGGL((minplus_kernel<true, 4, LWP_TK_SMALL, 1>), grid, dim3(NT), 0, stream, args);
     } else {
-        if (small_tiles) hipLaunchKernelGGL((minplus_kernel<false, 4, LWP_TK_SMALL>), grid, block, 0, stream, args);
-        else hipLaunchKernelGGL((minplus_kernel<false, 8, 16>), grid, block, 0, stream, args);
+        if (ksplit >= 2) hipLaunchKernelGGL((minplus_kernel<false, 4, LWP_TK_SMALL, 2>), grid, dim3(2 * NT), 0, stream, args);
+        else hipLaunchKernelGGL((minplus_kernel<false, 4, LWP_TK_SMALL, 1>), grid, dim3(NT), 0, stream, args);
     }
     return hipGetLastError();
 }
