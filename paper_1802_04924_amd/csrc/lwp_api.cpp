@@ -23,6 +23,7 @@ struct lwp_ctx {
     size_t ws_bytes = 0;
     char* pin = nullptr;       // pinned host staging (descriptor upload, small read-backs)
     size_t pin_bytes = 0;
+    int32_t* split = nullptr;  // scratch + per-tile counters of split tiles (see minplus.hip)
     bool profiling = false;
     struct Timed { hipEvent_t a, b; int kind; int64_t work; bool keyed; };
     std::vector<Timed> timed;
@@ -110,13 +111,33 @@ bool components_enumerable(const Plan& plan, int32_t C) {
     return true;
 }
 
-// Groups of 256 threads per 64 x 64 tile: with fewer workgroups than compute units a tile's c
-// range is shared by 2 or 4 groups (each needs a few stages of 32 candidates to be worth it).
-int choose_ksplit(int64_t workgroups, int32_t Cj, bool small_tiles) {
-    if (!small_tiles) return 1;
-    if (workgroups <= 256 && Cj >= 256) return 4;
-    if (workgroups <= 512 && Cj >= 128) return 2;
-    return 1;
+// Split tiles: a launch with far fewer 64 x 64 tiles than compute units lets several workgroups
+// share a tile, each with a part of the c range of at least two stages of 32 candidates.
+constexpr int kSplitMaxParts = 8, kSplitMaxWorkgroups = 512, kSplitMaxTiles = 128;
+int choose_kparts(int64_t tiles, int32_t Cj, bool small_tiles) {
+    if (!small_tiles || tiles > kSplitMaxTiles) return 1;
+    const int64_t nstages = (Cj + 31) / 32;
+    int64_t k = std::min<int64_t>({kSplitMaxParts, 256 / tiles, nstages / 2});
+    return k < 2 ? 1 : (int)k;
+}
+
+lwp_status ensure_split_buffers(lwp_ctx* ctx) {
+    if (ctx->split) return LWP_OK;
+    const size_t ints = (size_t)kSplitMaxWorkgroups * kSplitScratchIntsPerPart + kSplitMaxTiles;
+    void* p = nullptr;
+    hipError_t e = hipMalloc(&p, ints * sizeof(int32_t));
+    if (e != hipSuccess) { (void)hipGetLastError(); return fail(ctx, LWP_E_NOMEM, std::string("split-tile scratch: ") + hipGetErrorString(e)); }
+    ctx->split = static_cast<int32_t*>(p);
+    // the counters start at zero and every launch leaves them at zero
+    LWP_HIP(ctx, hipMemsetAsync(ctx->split + (size_t)kSplitMaxWorkgroups * kSplitScratchIntsPerPart, 0,
+                                kSplitMaxTiles * sizeof(int32_t), ctx->stream));
+    return LWP_OK;
+}
+
+void set_split(lwp_ctx* ctx, NodeArgs& a, int kparts) {
+    a.kparts = kparts;
+    a.scratch = kparts > 1 ? ctx->split : nullptr;
+    a.counters = kparts > 1 ? ctx->split + (size_t)kSplitMaxWorkgroups * kSplitScratchIntsPerPart : nullptr;
 }
 
 // Timing of one launch when profiling is on.
@@ -315,6 +336,7 @@ void lwp_destroy(lwp_ctx* ctx) {
     for (auto& t : ctx->timed) { hipEventDestroy(t.a); hipEventDestroy(t.b); }
     if (ctx->ws) (void)hipFree(ctx->ws);
     if (ctx->pin) (void)hipHostFree(ctx->pin);
+    if (ctx->split) (void)hipFree(ctx->split);
     delete ctx;
 }
 
@@ -393,7 +415,10 @@ lwp_status lwp_eliminate_node(lwp_ctx* ctx, int32_t batch, int32_t Ci, int32_t C
     a.tilesM = (int32_t)tilesM; a.tilesN = (int32_t)tilesN;
     {
         ScopedTimer tm(ctx, 0, (int64_t)batch * Ci * Cj * Ck, keyed);
-        LWP_HIP(ctx, launch_minplus(a, keyed, small, choose_ksplit(tilesM * tilesN * batch, Cj, small), ctx->stream));
+        const int kparts = choose_kparts(tilesM * tilesN * batch, Cj, small);
+        if (kparts > 1) { if (lwp_status s = ensure_split_buffers(ctx)) return s; }
+        set_split(ctx, a, kparts);
+        LWP_HIP(ctx, launch_minplus(a, keyed, small, ctx->stream));
     }
     return LWP_OK;
 }
@@ -634,7 +659,10 @@ lwp_status lwp_search_graph(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, cons
             na.Ci = na.Cj = na.Ck = C; na.batch = (int32_t)(b - a);
             na.tilesM = na.tilesN = (C + tile - 1) / tile;
             ScopedTimer tm(ctx, 0, (int64_t)(b - a) * CC * C, keyed);
-            LWP_HIP(ctx, launch_minplus(na, keyed, small, choose_ksplit((int64_t)na.tilesM * na.tilesN * na.batch, C, small), st));
+            const int kparts = choose_kparts((int64_t)na.tilesM * na.tilesN * na.batch, C, small);
+            if (kparts > 1) { if (lwp_status s2 = ensure_split_buffers(ctx)) return s2; }
+            set_split(ctx, na, kparts);
+            LWP_HIP(ctx, launch_minplus(na, keyed, small, st));
             a = b;
         }
     }

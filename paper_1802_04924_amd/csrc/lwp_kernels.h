@@ -34,7 +34,13 @@ struct NodeArgs {
     int64_t sA, sw, sB, sO;  // strided addressing: element strides between products
     int32_t Ci, Cj, Ck, batch;
     int32_t tilesM, tilesN;  // output tiles of the chosen tile size per product
+    // Split tiles (64 x 64 tiles only): kparts > 1 workgroups share a tile.  scratch holds
+    // tiles * kparts * 2 * 16 * 256 int32; counters one zeroed int32 per tile (left zeroed).
+    int32_t kparts;
+    int32_t* scratch;
+    int32_t* counters;
 };
+constexpr int64_t kSplitScratchIntsPerPart = 2 * 16 * 256;
 
 constexpr int kTileLarge = 128, kTileSmall = 64, kNodeThreads = 256;
 // largest spread the packed keys can hold: 27 bits with 128 x 128 tiles (16-deep stages), 26 bits
@@ -43,9 +49,8 @@ constexpr int64_t kKeyedMaxSpreadLarge = (1ll << 27) - 2, kKeyedMaxSpreadSmall =
 
 // keyed = true launches the packed-key variant, keyed = false the plain int32 compare/select
 // variant (ranges ignored).  small_tiles selects 64 x 64 output tiles instead of 128 x 128;
-// tilesM / tilesN in args must match.  ksplit (1, 2 or 4; 64 x 64 tiles only, plain variant at most
-// 2) is the number of 256-thread groups that share one tile, each walking a part of the c range.
-hipError_t launch_minplus(const NodeArgs& args, bool keyed, bool small_tiles, int ksplit, hipStream_t stream);
+// tilesM / tilesN in args must match.
+hipError_t launch_minplus(const NodeArgs& args, bool keyed, bool small_tiles, hipStream_t stream);
 
 // ---- edge elimination (Eq. 3) --------------------------------------------------------------
 // out = sum of n_src tables of `cells` elements.  srcs indexes a device array of table pointers.

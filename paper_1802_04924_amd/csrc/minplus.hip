@@ -6,10 +6,10 @@
 // that are staged through LDS (double-buffered, one barrier per stage); every thread keeps an
 // RB x RB block of running minima in registers (RB = 8: 128 x 128 tiles for throughput; RB = 4:
 // 64 x 64 tiles).  w is folded into A while A is staged, so the inner loop is one add and half a
-// three-way min per candidate.  When a launch has fewer tiles than the chip has compute units, KS
-// groups of 256 threads share one tile: each group walks its own contiguous part of the c range
-// with its own LDS buffers, and the groups' (minimum, argmin) blocks are merged through LDS at the
-// end in ascending-c order with a strict '<', which keeps the lowest-index rule.
+// three-way min per candidate.  When a launch has far fewer tiles than the chip has compute units,
+// several workgroups share one tile: each walks its own contiguous part of the c range and
+// publishes its (minimum, argmin) block to global scratch; the workgroup that arrives last merges
+// the parts in ascending-c order with a strict '<', which keeps the lowest-index rule.
 //
 // Two arithmetic variants:
 //   keyed   candidates are 32-bit keys (cost << tb) | (1 + position of c in its chunk); a chunk
@@ -49,18 +49,14 @@ __device__ __forceinline__ int wave_max_i32(int v) {
     return v;
 }
 
-template <bool KEYED, int RB, int TK, int KS>
-__global__ __launch_bounds__(NT * KS, (KS > 1) ? KS : (KEYED ? 2 : 1)) void minplus_kernel(const NodeArgs p) {
+template <bool KEYED, int RB, int TK>
+__global__ __launch_bounds__(NT, KEYED ? 2 : 1) void minplus_kernel(const NodeArgs p) {
     constexpr int TM = 16 * RB, TN = 16 * RB;   // output tile
     constexpr int EP = TM * TK / NT;            // elements of A and of B each thread stages per stage
     constexpr int QUADS = RB / 4;
     static_assert(EP % 4 == 0 && TK % EP == 0 && TN % EP == 0 && (TN / EP) * TK == NT, "staging assignment");
-    // per group: A tile [stage][c][a] (A transposed) and B tile [stage][c][b], double-buffered
-    __shared__ __attribute__((aligned(16))) uint32_t lds[KS][2][2][TK][TM];
-    static_assert(TM == TN, "square tiles");
-    const int grp = (KS > 1) ? (int)(threadIdx.x / NT) : 0;
-    uint32_t (*As)[TK][TM] = lds[grp][0];
-    uint32_t (*Bs)[TK][TN] = lds[grp][1];
+    __shared__ __attribute__((aligned(16))) uint32_t As[2][TK][TM];   // [stage][c][a]  (A transposed)
+    __shared__ __attribute__((aligned(16))) uint32_t Bs[2][TK][TN];   // [stage][c][b]
 
     // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Give every XCD a
     // contiguous range of logical ids, and walk the tiles of a product in panels of 8 tile rows,
@@ -69,6 +65,11 @@ __global__ __launch_bounds__(NT * KS, (KS > 1) ? KS : (KEYED ? 2 : 1)) void minp
     uint32_t bid = blockIdx.x;
     const uint32_t total = gridDim.x;
     if ((total & 7u) == 0u) bid = (bid & 7u) * (total >> 3) + (bid >> 3);
+    // kparts > 1: that many consecutive workgroups share one tile, each with a part of the c range
+    const int kparts = p.kparts;
+    const int part = (kparts > 1) ? (int)(bid % (uint32_t)kparts) : 0;
+    if (kparts > 1) bid /= (uint32_t)kparts;
+    const uint32_t tile_global = bid;
     const int tiles = p.tilesM * p.tilesN;
     const int bi = bid / tiles;
     const int tl = bid - bi * tiles;
@@ -128,7 +129,7 @@ __global__ __launch_bounds__(NT * KS, (KS > 1) ? KS : (KEYED ? 2 : 1)) void minp
     const uint32_t padA = KEYED ? ~fmask : 0x7fffffffu;   // never strictly below any running minimum
     const int spc = KEYED ? (int)(fmask / TK) : 1;        // stages per chunk: TK*spc <= 2^tb - 1
 
-    const int tid = (KS > 1) ? (int)(threadIdx.x % NT) : (int)threadIdx.x;   // index inside the group
+    const int tid = threadIdx.x;
     const int tx = tid & 15, ty = tid >> 4;
     // global -> LDS assignment: A: one row, EP consecutive c;  B: one c, EP consecutive columns
     constexpr int TPR = TK / EP;                 // threads per A row
@@ -208,14 +209,14 @@ __global__ __launch_bounds__(NT * KS, (KS > 1) ? KS : (KEYED ? 2 : 1)) void minp
 #pragma unroll
         for (int j = 0; j < RB; ++j) { m1[i][j] = padA; rec[i][j] = 0u; }
 
-    // group g of the workgroup walks stages [g*n_g, (g+1)*n_g); stages past the end of c see only
-    // padding (never a winner), so every group runs the same number of barriers
+    // part q of a split tile walks stages [q*n_g, (q+1)*n_g); stages past the end of c see only
+    // padding (never a winner)
     const int nstages = (Cj + TK - 1) / TK;
-    const int n_g = (nstages + KS - 1) / KS;
-    const int s_first = grp * n_g;
+    const int n_g = (nstages + kparts - 1) / kparts;
+    const int s_first = part * n_g;
     int sic = 0;                      // stage index inside the current chunk
     int chunk_c0 = s_first * TK;      // first c of the current chunk
-    if (KS > 1) { pA += (int64_t)s_first * TK; pW += (int64_t)s_first * TK; pB += (int64_t)s_first * TK * Ck; }
+    if (kparts > 1) { pA += (int64_t)s_first * TK; pW += (int64_t)s_first * TK; pB += (int64_t)s_first * TK * Ck; }
 
     fetch(s_first * TK);
     stash(s_first * TK, 0, 0);
@@ -293,38 +294,55 @@ __global__ __launch_bounds__(NT * KS, (KS > 1) ? KS : (KEYED ? 2 : 1)) void minp
         __syncthreads();
     }
 
-    // merge the groups' blocks: groups 1..KS-1 publish (cost, argmin) through LDS, group 0 folds
-    // them in ascending-c order; strict '<' lets the earlier group keep ties
-    if (KS > 1) {
-        int32_t (*xc)[RB * RB][NT] = reinterpret_cast<int32_t (*)[RB * RB][NT]>(&lds[0][0][0][0][0]);
-        uint32_t (*xr)[RB * RB][NT] = reinterpret_cast<uint32_t (*)[RB * RB][NT]>(&lds[0][0][0][0][0] + (KS - 1) * RB * RB * NT);
-        static_assert(2 * (KS - 1) * RB * RB * NT <= KS * 4 * TK * TM, "merge buffers fit the tile buffers");
-        if (grp > 0) {
-#pragma unroll
-            for (int i = 0; i < RB; ++i)
-#pragma unroll
-                for (int j = 0; j < RB; ++j) {
-                    xc[grp - 1][i * RB + j][tid] = KEYED ? (int32_t)(m1[i][j] >> tb) + offA + offB : (int32_t)m1[i][j];
-                    xr[grp - 1][i * RB + j][tid] = rec[i][j];
-                }
-        }
-        __syncthreads();
-        if (grp == 0)
+    // Split tile: every part publishes its (cost, argmin) block to global scratch; the part that
+    // arrives last (a counter per tile) folds all parts in ascending-c order -- strict '<' lets the
+    // earlier part keep ties -- and goes on to the epilogue.  The parts run on different compute
+    // units, possibly different XCDs (separate L2s): the blocks are exchanged with device-scope
+    // relaxed atomic stores and loads, which go through to memory, so no cache-wide write-back or
+    // invalidate is needed; a workgroup-scope release makes every thread's stores complete before
+    // the counter is bumped.
+    bool raw = KEYED;                          // m1 still holds keys (otherwise plain costs)
+    if (kparts > 1) {
+        constexpr int CELLS = RB * RB;
+        int32_t* slab = p.scratch + ((int64_t)tile_global * kparts) * (2 * CELLS * NT);
+        int32_t* mine = slab + (int64_t)part * (2 * CELLS * NT);
 #pragma unroll
         for (int i = 0; i < RB; ++i)
 #pragma unroll
             for (int j = 0; j < RB; ++j) {
-                int32_t best = KEYED ? (int32_t)(m1[i][j] >> tb) + offA + offB : (int32_t)m1[i][j];
-                uint32_t barg = rec[i][j];
-                for (int g = 0; g < KS - 1; ++g) {
-                    const int32_t c2 = xc[g][i * RB + j][tid];
-                    const uint32_t r2 = xr[g][i * RB + j][tid];
-                    if (c2 < best) { best = c2; barg = r2; }
-                }
-                m1[i][j] = (uint32_t)best; rec[i][j] = barg;
+                const int32_t cst = KEYED ? (int32_t)(m1[i][j] >> tb) + offA + offB : (int32_t)m1[i][j];
+                __hip_atomic_store(&mine[(i * RB + j) * NT + tid], cst, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(&mine[(CELLS + i * RB + j) * NT + tid], (int32_t)rec[i][j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __syncthreads();
+        __shared__ int arrived;
+        if (tid == 0) arrived = __hip_atomic_fetch_add(&p.counters[tile_global], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        if (arrived != kparts - 1) return;     // uniform for the workgroup
+        if (tid == 0) __hip_atomic_store(&p.counters[tile_global], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
+        // one part at a time, all of its values in flight together
+        for (int q = 0; q < kparts; ++q) {
+            const int32_t* other = slab + (int64_t)q * (2 * CELLS * NT);
+            int32_t c2[RB][RB], r2[RB][RB];
+#pragma unroll
+            for (int i = 0; i < RB; ++i)
+#pragma unroll
+                for (int j = 0; j < RB; ++j) {
+                    c2[i][j] = __hip_atomic_load(&other[(i * RB + j) * NT + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    r2[i][j] = __hip_atomic_load(&other[(CELLS + i * RB + j) * NT + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+#pragma unroll
+            for (int i = 0; i < RB; ++i)
+#pragma unroll
+                for (int j = 0; j < RB; ++j) {
+                    const bool take = (q == 0) || (c2[i][j] < (int32_t)m1[i][j]);
+                    m1[i][j] = take ? (uint32_t)c2[i][j] : m1[i][j];
+                    rec[i][j] = take ? (uint32_t)r2[i][j] : rec[i][j];
+                }
+        }
+        raw = false;
     }
-    constexpr bool RAW = KEYED && KS == 1;     // m1 still holds keys (otherwise plain costs)
 
     // epilogue: thread rows {h*64 + ty*4 + 0..3}, columns {h*64 + tx*4 + 0..3}, h < QUADS
     const bool vecO = ((Ck & 3) == 0) && ((((uintptr_t)O) | ((uintptr_t)G)) & 15) == 0 && (b0 + TN <= Ck);
@@ -332,11 +350,11 @@ __global__ __launch_bounds__(NT * KS, (KS > 1) ? KS : (KEYED ? 2 : 1)) void minp
 #pragma unroll
     for (int i = 0; i < RB; ++i) {
         const int a = a0 + (i >> 2) * 64 + ty * 4 + (i & 3);
-        if (a >= Ci || grp != 0) continue;    // only the first group holds the merged block
+        if (a >= Ci) continue;
         int32_t val[RB];
 #pragma unroll
         for (int j = 0; j < RB; ++j)
-            val[j] = RAW ? (int32_t)(m1[i][j] >> tb) + offA + offB : (int32_t)m1[i][j];
+            val[j] = raw ? (int32_t)(m1[i][j] >> tb) + offA + offB : (int32_t)m1[i][j];
 #pragma unroll
         for (int h = 0; h < QUADS; ++h) {
             const int b = b0 + h * 64 + tx * 4;
@@ -361,9 +379,9 @@ __global__ __launch_bounds__(NT * KS, (KS > 1) ? KS : (KEYED ? 2 : 1)) void minp
     if (d.rngOut) {   // leave the measured range of this table for the launches that consume it
         vmin = wave_min_i32(vmin); vmax = wave_max_i32(vmax);
         __shared__ int red[2 * (NT / 64)];
-        if ((tid & 63) == 0 && grp == 0) { red[2 * (tid >> 6)] = vmin; red[2 * (tid >> 6) + 1] = vmax; }
+        if ((tid & 63) == 0) { red[2 * (tid >> 6)] = vmin; red[2 * (tid >> 6) + 1] = vmax; }
         __syncthreads();
-        if (tid == 0 && grp == 0) {
+        if (tid == 0) {
             for (int q = 1; q < NT / 64; ++q) { vmin = min(vmin, red[2 * q]); vmax = max(vmax, red[2 * q + 1]); }
             if (vmin <= vmax) { atomicMin(&d.rngOut[0], vmin); atomicMax(&d.rngOut[1], vmax); }
         }
@@ -372,20 +390,18 @@ __global__ __launch_bounds__(NT * KS, (KS > 1) ? KS : (KEYED ? 2 : 1)) void minp
 
 }  // namespace
 
-hipError_t launch_minplus(const NodeArgs& args, bool keyed, bool small_tiles, int ksplit, hipStream_t stream) {
-    const int64_t blocks = (int64_t)args.tilesM * args.tilesN * args.batch;
+hipError_t launch_minplus(const NodeArgs& args, bool keyed, bool small_tiles, hipStream_t stream) {
+    const int kparts = args.kparts > 1 ? args.kparts : 1;
+    const int64_t blocks = (int64_t)args.tilesM * args.tilesN * args.batch * kparts;
     if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    dim3 grid((unsigned)blocks);
-    if (!small_tiles) {
-        if (keyed) hipLaunchKernelGGL((minplus_kernel<true, 8, 16, 1>), grid, dim3(NT), 0, stream, args);
-        else hipLaunchKernelGGL((minplus_kernel<false, 8, 16, 1>), grid, dim3(NT), 0, stream, args);
-    } else if (keyed) {
-        if (ksplit >= 4) hipLaunchKernelGGL((minplus_kernel<true, 4, LWP_TK_SMALL, 4>), grid, dim3(4 * NT), 0, stream, args);
-        else if (ksplit >= 2) hipLaunchKernelGGL((minplus_kernel<true, 4, LWP_TK_SMALL, 2>), grid, dim3(2 * NT), 0, stream, args);
-        else hipLaunchKernelGGL((minplus_kernel<true, 4, LWP_TK_SMALL, 1>), grid, dim3(NT), 0, stream, args);
+    if (kparts > 1 && (!small_tiles || !args.scratch || !args.counters)) return hipErrorInvalidValue;
+    dim3 grid((unsigned)blocks), block(NT);
+    if (keyed) {
+        if (small_tiles) hipLaunchKernelGGL((minplus_kernel<true, 4, LWP_TK_SMALL>), grid, block, 0, stream, args);
+        else hipLaunchKernelGGL((minplus_kernel<true, 8, 16>), grid, block, 0, stream, args);
     } else {
-        if (ksplit >= 2) hipLaunchKernelGGL((minplus_kernel<false, 4, LWP_TK_SMALL, 2>), grid, dim3(2 * NT), 0, stream, args);
-        else hipLaunchKernelGGL((minplus_kernel<false, 4, LWP_TK_SMALL, 1>), grid, dim3(NT), 0, stream, args);
+        if (small_tiles) hipLaunchKernelGGL((minplus_kernel<false, 4, LWP_TK_SMALL>), grid, block, 0, stream, args);
+        else hipLaunchKernelGGL((minplus_kernel<false, 8, 16>), grid, block, 0, stream, args);
     }
     return hipGetLastError();
 }
