@@ -494,7 +494,6 @@ lwp_status lwp_search_graph(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, cons
     const int64_t CC = (int64_t)C * C;
     int32_t* d_w = reinterpret_cast<int32_t*>(ws + W.w);
     int32_t* d_head = reinterpret_cast<int32_t*>(ws + W.head);
-    int32_t* d_flag = d_head;
     int32_t* d_stats = d_head + 2;
     int32_t* d_args = reinterpret_cast<int32_t*>(ws + W.args);
     int32_t* d_slots = reinterpret_cast<int32_t*>(ws + W.slots);
@@ -508,14 +507,14 @@ lwp_status lwp_search_graph(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, cons
     const int32_t rng_w0 = n_edges, rng_node0 = n_edges + n_nodes, rng_group0 = rng_node0 + plan.n_node_steps;
 
     // 1. w = t_c + t_s with its ranges, and the range of every input table; one read-back
-    LWP_HIP(ctx, launch_init_workspace(d_stats, W.n_ranges, d_flag, d_keys, n_comp, st));
-    LWP_HIP(ctx, launch_add_vectors(d_tc, d_ts, d_w, n_nodes, C, d_stats + 2 * (int64_t)rng_w0, d_flag, st));
+    LWP_HIP(ctx, launch_prepare_search(d_tc, d_ts, d_w, n_nodes, C, d_stats, W.n_ranges, rng_w0, d_keys, n_comp, st));
     LWP_HIP(ctx, launch_ranges(d_tx, n_edges, CC, d_stats, st));
     int32_t* h_head = reinterpret_cast<int32_t*>(ctx->pin + pin_head);
     LWP_HIP(ctx, hipMemcpyAsync(h_head, d_head, head_in_bytes, hipMemcpyDeviceToHost, st));
     LWP_HIP(ctx, hipStreamSynchronize(st));
-    if (h_head[0]) return fail(ctx, LWP_E_OVERFLOW, "t_c + t_s leaves int32");
     const int32_t* stats = h_head + 2;
+    for (int32_t v = 0; v < n_nodes; ++v)
+        if (stats[2 * (rng_w0 + v)] > stats[2 * (rng_w0 + v) + 1]) return fail(ctx, LWP_E_OVERFLOW, "t_c + t_s leaves int32");
 
     // 2. propagate ranges through the plan: every sum any kernel forms must fit int32.  Descriptors
     //    are written straight into the pinned mirror of the device block.

@@ -74,10 +74,12 @@ hipError_t launch_init_workspace(int32_t* d_stats, int32_t n_tables, int32_t* d_
 // dense one after another), by atomics onto initialised pairs.
 hipError_t launch_ranges(const int32_t* d_tables, int32_t n_tables, int64_t cells, int32_t* d_stats,
                          hipStream_t stream);
-// w[v][c] = tc[v][c] + ts[v][c]; stats[2*v], stats[2*v+1] receive min/max of row v of w;
-// *d_flag is OR-ed with 1 if a sum leaves int32.
-hipError_t launch_add_vectors(const int32_t* tc, const int32_t* ts, int32_t* w, int32_t n_nodes, int32_t C,
-                              int32_t* d_stats, int32_t* d_flag, hipStream_t stream);
+// First launch of a search: w[v][c] = tc[v][c] + ts[v][c]; stats pair w_pair0 + v receives
+// {min, max} of row v of w, or {INT32_MAX, INT32_MIN} if a sum of that row leaves int32; all other
+// of the n_pairs stats pairs are initialised for atomic min/max and keys[0..n_keys) to all ones.
+hipError_t launch_prepare_search(const int32_t* tc, const int32_t* ts, int32_t* w, int32_t n_nodes, int32_t C,
+                                 int32_t* d_stats, int32_t n_pairs, int32_t w_pair0, unsigned long long* d_keys,
+                                 int32_t n_keys, hipStream_t stream);
 
 // ---- residual graph and back-substitution (Alg. 1, enumeration of the final graph and undo) --
 struct PairDesc {       // residual component with two nodes joined by one edge

@@ -133,25 +133,41 @@ __global__ __launch_bounds__(kThreads) void ranges_kernel(const int32_t* __restr
     }
 }
 
-// w = tc + ts, one block row per node (grid.y); also min/max of the node's row of w, and
-// flag[0] is set if a sum leaves int32
-__global__ __launch_bounds__(kThreads) void add_vectors_kernel(const int32_t* __restrict__ tc,
-                                                               const int32_t* __restrict__ ts,
-                                                               int32_t* __restrict__ w, int32_t C,
-                                                               int32_t* __restrict__ stats,
-                                                               int32_t* __restrict__ flag) {
-    const int64_t row = (int64_t)blockIdx.y * C;
-    bool bad = false;
+// First launch of a search.  Blocks [0, n_nodes): w[v] = tc[v] + ts[v] and {min, max} of the row
+// into stats pair w_pair0 + v (written directly: one block owns a row); a sum that leaves int32 is
+// reported as the impossible pair {INT32_MAX, INT32_MIN}.  Further blocks: every other stats pair
+// becomes {INT32_MAX, INT32_MIN} (ready for atomic min/max), every key all ones.
+__global__ __launch_bounds__(kThreads) void prepare_search_kernel(const int32_t* __restrict__ tc,
+                                                                  const int32_t* __restrict__ ts,
+                                                                  int32_t* __restrict__ w, int32_t n_nodes, int32_t C,
+                                                                  int32_t* __restrict__ stats, int32_t n_pairs,
+                                                                  int32_t w_pair0, unsigned long long* __restrict__ keys,
+                                                                  int32_t n_keys) {
+    if ((int)blockIdx.x >= n_nodes) {
+        const int t = ((int)blockIdx.x - n_nodes) * kThreads + threadIdx.x;
+        if (t < n_pairs && (t < w_pair0 || t >= w_pair0 + n_nodes)) { stats[2 * t] = 0x7fffffff; stats[2 * t + 1] = (int32_t)0x80000000; }
+        if (t < n_keys) keys[t] = ~0ull;
+        return;
+    }
+    __shared__ int smin[kThreads / 64], smax[kThreads / 64], sbad[kThreads / 64];
+    const int64_t row = (int64_t)blockIdx.x * C;
+    int bad = 0;
     int lo = 0x7fffffff, hi = (int32_t)0x80000000;
-    for (int x = blockIdx.x * kThreads + threadIdx.x; x < C; x += gridDim.x * kThreads) {
+    for (int x = threadIdx.x; x < C; x += kThreads) {
         const int64_t s = (int64_t)tc[row + x] + (int64_t)ts[row + x];
-        bad = bad || (s != (int64_t)(int32_t)s);
+        bad |= (s != (int64_t)(int32_t)s);
         w[row + x] = (int32_t)s;
         lo = min(lo, (int32_t)s); hi = max(hi, (int32_t)s);
     }
-    lo = wave_min(lo); hi = wave_max(hi);
-    if ((threadIdx.x & 63) == 0 && lo <= hi) { atomicMin(&stats[2 * blockIdx.y], lo); atomicMax(&stats[2 * blockIdx.y + 1], hi); }
-    if (bad) atomicOr(flag, 1);
+    lo = wave_min(lo); hi = wave_max(hi); bad = wave_max(bad);
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) { smin[wave] = lo; smax[wave] = hi; sbad[wave] = bad; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int q = 1; q < kThreads / 64; ++q) { lo = min(lo, smin[q]); hi = max(hi, smax[q]); bad |= sbad[q]; }
+        stats[2 * (w_pair0 + (int)blockIdx.x)] = bad ? 0x7fffffff : lo;
+        stats[2 * (w_pair0 + (int)blockIdx.x) + 1] = bad ? (int32_t)0x80000000 : hi;
+    }
 }
 
 // ---- residual graph ----------------------------------------------------------------------------
@@ -336,14 +352,13 @@ hipError_t launch_ranges(const int32_t* d_tables, int32_t n_tables, int64_t cell
     return hipGetLastError();
 }
 
-hipError_t launch_add_vectors(const int32_t* tc, const int32_t* ts, int32_t* w, int32_t n_nodes, int32_t C,
-                              int32_t* d_stats, int32_t* d_flag, hipStream_t stream) {
-    for (int32_t v0 = 0; v0 < n_nodes; v0 += 65535) {
-        const int32_t n = (n_nodes - v0) < 65535 ? (n_nodes - v0) : 65535;
-        dim3 grid(blocks_for(C, 4, 64), (unsigned)n);
-        hipLaunchKernelGGL(add_vectors_kernel, grid, dim3(kThreads), 0, stream, tc + (int64_t)v0 * C, ts + (int64_t)v0 * C,
-                           w + (int64_t)v0 * C, C, d_stats + 2 * (int64_t)v0, d_flag);
-    }
+hipError_t launch_prepare_search(const int32_t* tc, const int32_t* ts, int32_t* w, int32_t n_nodes, int32_t C,
+                                 int32_t* d_stats, int32_t n_pairs, int32_t w_pair0, unsigned long long* d_keys,
+                                 int32_t n_keys, hipStream_t stream) {
+    const int n_init = n_pairs > n_keys ? n_pairs : n_keys;
+    dim3 grid((unsigned)(n_nodes + (n_init + kThreads - 1) / kThreads));
+    hipLaunchKernelGGL(prepare_search_kernel, grid, dim3(kThreads), 0, stream, tc, ts, w, n_nodes, C, d_stats, n_pairs,
+                       w_pair0, d_keys, n_keys);
     return hipGetLastError();
 }
 
