@@ -111,13 +111,14 @@ bool components_enumerable(const Plan& plan, int32_t C) {
     return true;
 }
 
-// Split tiles: a launch with far fewer 64 x 64 tiles than compute units lets several workgroups
-// share a tile, each with a part of the c range of at least two stages of 32 candidates.
-constexpr int kSplitMaxParts = 8, kSplitMaxWorkgroups = 512, kSplitMaxTiles = 128;
+// Split tiles: a launch with few 64 x 64 tiles lets several workgroups share a tile, each with a
+// part of the c range of at least two stages of 32 candidates.
+// Measured: splitting pays while tiles x parts stays around 1024 workgroups (4 per compute unit).
+constexpr int kSplitMaxParts = 8, kSplitMaxWorkgroups = 1024, kSplitMaxTiles = 512;
 int choose_kparts(int64_t tiles, int32_t Cj, bool small_tiles) {
     if (!small_tiles || tiles > kSplitMaxTiles) return 1;
     const int64_t nstages = (Cj + 31) / 32;
-    int64_t k = std::min<int64_t>({kSplitMaxParts, 256 / tiles, nstages / 2});
+    int64_t k = std::min<int64_t>({kSplitMaxParts, kSplitMaxWorkgroups / tiles, nstages / 2});
     return k < 2 ? 1 : (int)k;
 }
 

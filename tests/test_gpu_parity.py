@@ -87,6 +87,20 @@ def test_eliminate_node_key_widths_large_tiles(ctx, shape, bits, expect_keyed):
     check_products(ctx, A, w, B, expect_keyed=expect_keyed)
 
 
+def test_eliminate_node_split_tiles_repeatedly(ctx):
+    # few tiles: several workgroups share a tile and merge through global scratch; the per-tile
+    # arrival counters must be left ready for the next launch, whatever its shape
+    rng = np.random.default_rng(99)
+    shapes = [(1, 64, 2048, 64), (3, 70, 700, 130), (1, 64, 64, 64), (2, 200, 4096, 100), (1, 512, 512, 512), (9, 33, 257, 65)]
+    for rep in range(3):
+        for batch, Ci, Cj, Ck in shapes:
+            hi = [3, 1 << 20, (1 << 26) - 1][rep]          # heavy ties / keyed / plain variant
+            A = rng.integers(0, hi, size=(batch, Ci, Cj), endpoint=True, dtype=np.int32)
+            w = rng.integers(0, hi, size=(batch, Cj), endpoint=True, dtype=np.int32)
+            B = rng.integers(0, hi, size=(batch, Cj, Ck), endpoint=True, dtype=np.int32)
+            check_products(ctx, A, w, B)
+
+
 def test_eliminate_node_negative_and_offset_values(ctx):
     rng = np.random.default_rng(11)
     A = rng.integers(-(1 << 20), 1 << 10, size=(2, 70, 90, ), dtype=np.int32).reshape(2, 70, 90)
