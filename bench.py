@@ -83,6 +83,8 @@ def main():
     ap.add_argument("--workload", default="cfg4", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "resid"])
     ap.add_argument("--layers", type=int, default=64, help="cfg4 only: chain length")
     ap.add_argument("--configs", type=int, default=0, help="override C of the workload")
+    ap.add_argument("--undo", default="stored", choices=["stored", "recompute"],
+                    help="undo pass: look up stored argmin tables, or recompute the argmin as Alg. 1 does")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-events", action="store_true",
                     help="diagnostic: do not bracket the elimination launches with HIP events (no roofline figures)")
@@ -147,6 +149,8 @@ def main():
         n_elim = p["n_nodes"] - 2
         updates = n_elim * C ** 3
         workload = f"{p['name']}: {p['n_nodes']} nodes, {len(p['edges'])} edges, C={C}, {n_elim} node eliminations"
+        if args.undo == "recompute":
+            workload += ", argmin recomputed in the undo pass"
         if name == "resid":
             updates = C ** 4      # strategies enumerated, reported in the same field
             workload = f"{p['name']}: 4 residual nodes, C={C}, {updates:.3g} strategies enumerated per search"
@@ -154,7 +158,8 @@ def main():
         result = {}
 
         def step():
-            result["cost"], result["S"] = ctx.search_graph(p["n_nodes"], p["edges"], C, dtc, dts, dtx, p["schedule"])
+            result["cost"], result["S"] = ctx.search_graph(p["n_nodes"], p["edges"], C, dtc, dts, dtx, p["schedule"],
+                                                           1 if args.undo == "recompute" else 0)
         if name == "cfg4":
             cpu_payload = ("fold", p)
         elif name == "resid":

@@ -70,8 +70,8 @@ lwp_status lwp_synchronize(lwp_ctx *ctx);
  *   out[b][a][k] = min_c ( A[b][a][c] + w[b][c] + B[b][c][k] ),  argmin[b][a][k] = lowest such c
  * A = table of the in-edge (l_i,l_j), w = t_c(l_j,.) + t_s(l_j,.), B = table of the out-edge.
  * DEVICE, dense, row-major: A [batch][Ci][Cj], w [batch][Cj], B [batch][Cj][Ck],
- * out [batch][Ci][Ck], argmin [batch][Ci][Ck] (may be NULL).  out/argmin must not overlap the
- * inputs.  Sizes: batch, Ci, Cj, Ck >= 1, Cj <= 65536.
+ * out [batch][Ci][Ck], argmin [batch][Ci][Ck] (may be NULL: then only the minimum is computed,
+ * by a variant without argmin bookkeeping).  out/argmin must not overlap the inputs.  Sizes: batch, Ci, Cj, Ck >= 1, Cj <= 65536.
  * The call measures the value ranges of A, w, B on the device (one small synchronising
  * read-back), returns LWP_E_OVERFLOW if max A + max w + max B (or the minima) could leave
  * int32, then enqueues the product kernel and returns. */
@@ -120,10 +120,27 @@ lwp_status lwp_search_graph(lwp_ctx *ctx, int32_t n_nodes, int32_t n_edges, cons
                             int32_t C, const int32_t *d_tc, const int32_t *d_ts, const int32_t *d_tx,
                             int32_t schedule, int32_t *out_cost, int32_t *out_strategy);
 
-/* Host-only: bytes of device workspace lwp_search_graph needs for this graph (0 on a graph it
+/* How the undo pass (Alg. 1, last loop) obtains the configuration c_j of an eliminated node:
+ *   LWP_UNDO_STORED     every node elimination stores its argmin table (one int32 [C][C] each),
+ *                       the undo pass looks c_j up;
+ *   LWP_UNDO_RECOMPUTE  as the paper describes it (Table 2: undoing costs O(EC)): eliminations keep
+ *                       only the minimum, their input tables stay alive, and the undo pass
+ *                       recomputes c_j = argmin_c { A[c_i][c] + w[c] + B[c][c_k] } (lowest c).
+ *                       The elimination kernel then needs no argmin bookkeeping and runs at its
+ *                       full rate for any int32 value range.
+ * Both return the same strategy. */
+typedef enum { LWP_UNDO_STORED = 0, LWP_UNDO_RECOMPUTE = 1 } lwp_undo;
+/* lwp_search_graph with the undo mode chosen by the caller (lwp_search_graph uses STORED). */
+lwp_status lwp_search_graph_ex(lwp_ctx *ctx, int32_t n_nodes, int32_t n_edges, const int32_t *edges,
+                               int32_t C, const int32_t *d_tc, const int32_t *d_ts, const int32_t *d_tx,
+                               int32_t schedule, int32_t undo, int32_t *out_cost, int32_t *out_strategy);
+
+/* Host-only: bytes of device workspace lwp_search_graph(_ex) needs for this graph (0 on a graph it
  * would refuse). */
 size_t lwp_search_workspace_bytes(int32_t n_nodes, int32_t n_edges, const int32_t *edges, int32_t C,
                                   int32_t schedule);
+size_t lwp_search_workspace_bytes_ex(int32_t n_nodes, int32_t n_edges, const int32_t *edges, int32_t C,
+                                     int32_t schedule, int32_t undo);
 
 /* ---- cost tables (Sec. 5.1: t_c, t_s, t_x) ----------------------------------------------- */
 

@@ -5,5 +5,5 @@ seeded synthetic inputs; `build` compiles the HIP sources.  Importing the packag
 the shared library is opened on first use and must have been built.
 """
 from . import workloads  # noqa: F401
-from .binding import (Context, LwpError, SCHEDULE_LEFT_FOLD, SCHEDULE_ROUNDS, plan_graph,  # noqa: F401
-                      search_workspace_bytes)
+from .binding import (Context, LwpError, SCHEDULE_LEFT_FOLD, SCHEDULE_ROUNDS, UNDO_RECOMPUTE,  # noqa: F401
+                      UNDO_STORED, plan_graph, search_workspace_bytes)

@@ -17,11 +17,12 @@ LIB_PATH = os.path.join(_HERE, "liblwp.so")
 
 OK, E_INVAL, E_GRAPH, E_NOT_REDUCIBLE, E_OVERFLOW, E_NOMEM, E_HIP = 0, -1, -2, -3, -4, -5, -6
 SCHEDULE_ROUNDS, SCHEDULE_LEFT_FOLD = 0, 1
+UNDO_STORED, UNDO_RECOMPUTE = 0, 1
 
 EXPORTED = [
     "lwp_create", "lwp_destroy", "lwp_last_error", "lwp_status_string", "lwp_synchronize",
     "lwp_eliminate_node", "lwp_eliminate_edge", "lwp_plan_graph", "lwp_search_graph",
-    "lwp_search_workspace_bytes", "lwp_build_cost_tables",
+    "lwp_search_workspace_bytes", "lwp_search_graph_ex", "lwp_search_workspace_bytes_ex", "lwp_build_cost_tables",
     "lwp_profile_enable", "lwp_profile_reset", "lwp_profile_read",
 ]
 
@@ -73,6 +74,9 @@ def load():
     lib.lwp_search_graph.argtypes = [vp, i32, i32, vp, i32, vp, vp, vp, i32, i32p, vp]
     lib.lwp_search_workspace_bytes.argtypes = [i32, i32, vp, i32, i32]
     lib.lwp_search_workspace_bytes.restype = ctypes.c_size_t
+    lib.lwp_search_graph_ex.argtypes = [vp, i32, i32, vp, i32, vp, vp, vp, i32, i32, i32p, vp]
+    lib.lwp_search_workspace_bytes_ex.argtypes = [i32, i32, vp, i32, i32, i32]
+    lib.lwp_search_workspace_bytes_ex.restype = ctypes.c_size_t
     lib.lwp_build_cost_tables.argtypes = [vp, vp, i32, vp, i32, vp, i32, vp, vp, vp, vp]
     lib.lwp_profile_enable.argtypes = [vp, i32]
     lib.lwp_profile_reset.argtypes = [vp]
@@ -101,10 +105,10 @@ def plan_graph(n_nodes, edges, schedule=SCHEDULE_ROUNDS):
     return {"steps": steps[:ns.value], "n_rounds": nr.value, "n_residual_nodes": nk.value}
 
 
-def search_workspace_bytes(n_nodes, edges, C, schedule=SCHEDULE_ROUNDS) -> int:
+def search_workspace_bytes(n_nodes, edges, C, schedule=SCHEDULE_ROUNDS, undo=UNDO_STORED) -> int:
     lib = load()
     edges = _np_i32(edges, (-1, 2))
-    return int(lib.lwp_search_workspace_bytes(n_nodes, len(edges), edges.ctypes.data, C, int(schedule)))
+    return int(lib.lwp_search_workspace_bytes_ex(n_nodes, len(edges), edges.ctypes.data, C, int(schedule), int(undo)))
 
 
 def _dev(t, what):
@@ -183,7 +187,7 @@ class Context:
         return out
 
     # ---- Alg. 1 ------------------------------------------------------------
-    def search_graph(self, n_nodes, edges, C, tc, ts, tx, schedule=SCHEDULE_ROUNDS):
+    def search_graph(self, n_nodes, edges, C, tc, ts, tx, schedule=SCHEDULE_ROUNDS, undo=UNDO_STORED):
         """Returns (cost, strategy[n_nodes]) with tables resident on the device."""
         edges = _np_i32(edges, (-1, 2))
         E = len(edges)
@@ -193,8 +197,9 @@ class Context:
             raise ValueError("t_x must be [n_edges][C][C]")
         cost = ctypes.c_int32(0)
         S = np.empty(n_nodes, np.int32)
-        rc = self._lib.lwp_search_graph(self._h, n_nodes, E, edges.ctypes.data, C, _dev(tc, "tc"), _dev(ts, "ts"),
-                                        _dev(tx, "tx") if E else None, int(schedule), ctypes.byref(cost), S.ctypes.data)
+        rc = self._lib.lwp_search_graph_ex(self._h, n_nodes, E, edges.ctypes.data, C, _dev(tc, "tc"), _dev(ts, "ts"),
+                                           _dev(tx, "tx") if E else None, int(schedule), int(undo), ctypes.byref(cost),
+                                           S.ctypes.data)
         self._check(rc, "search_graph")
         return cost.value, S
 

@@ -199,7 +199,8 @@ struct Layout {
     int32_t n_slots = 0;
 };
 
-Layout plan_buffers(const Plan& plan, int32_t n_edges) {
+// keep_inputs: tables consumed by node eliminations stay alive (the undo pass re-reads them).
+Layout plan_buffers(const Plan& plan, int32_t n_edges, bool keep_inputs) {
     Layout L;
     std::vector<TableRef> cur(n_edges);
     for (int32_t e = 0; e < n_edges; ++e) cur[e] = {false, e};
@@ -232,8 +233,8 @@ Layout plan_buffers(const Plan& plan, int32_t n_edges) {
         while (t < n && plan.steps[t].round == round && plan.steps[t].kind == 0) {
             const lwp_step& st = plan.steps[t];
             L.node_A.push_back(cur[st.e1]); L.node_B.push_back(cur[st.e2]);
-            if (cur[st.e1].is_slot) release.push_back(cur[st.e1].id);
-            if (cur[st.e2].is_slot) release.push_back(cur[st.e2].id);
+            if (!keep_inputs && cur[st.e1].is_slot) release.push_back(cur[st.e1].id);
+            if (!keep_inputs && cur[st.e2].is_slot) release.push_back(cur[st.e2].id);
             const int32_t out = take();
             L.node_out_slot.push_back(out);
             cur[st.e1] = {true, out};
@@ -261,7 +262,7 @@ struct WsLayout {
     int32_t n_ranges;
 };
 
-WsLayout layout_workspace(const Plan& plan, const Layout& L, int32_t n_nodes, int32_t n_edges, int32_t C) {
+WsLayout layout_workspace(const Plan& plan, const Layout& L, int32_t n_nodes, int32_t n_edges, int32_t C, bool stored_argmin) {
     WsLayout o{};
     size_t off = 0;
     auto put = [&](size_t bytes) { size_t at = off; off = align_up(off + bytes, 256); return at; };
@@ -286,7 +287,7 @@ WsLayout layout_workspace(const Plan& plan, const Layout& L, int32_t n_nodes, in
         o.desc_bytes = std::max<size_t>(b, 16);
     }
     o.desc = put(o.desc_bytes);
-    o.args = put((size_t)plan.n_node_steps * CC);
+    o.args = put(stored_argmin ? (size_t)plan.n_node_steps * CC : 0);
     o.slots = put((size_t)L.n_slots * CC);
     o.total = off;
     return o;
@@ -405,10 +406,12 @@ lwp_status lwp_eliminate_node(lwp_ctx* ctx, int32_t batch, int32_t Ci, int32_t C
     a.base.loA = (int32_t)rA.lo; a.base.hiA = (int32_t)rA.hi; a.base.loW = (int32_t)rw.lo; a.base.hiW = (int32_t)rw.hi;
     a.base.loB = (int32_t)rB.lo; a.base.hiB = (int32_t)rB.hi;
     const int64_t spread = keyed_spread(rA, rw, rB);
-    // one more key bit on large tiles, worth it only if they still fill the chip
-    const bool keyed = spread <= kKeyedMaxSpreadSmall ||
-                       (spread <= kKeyedMaxSpreadLarge && (!prefer_small || large_tiles(Ci, Ck, batch) >= 512));
-    const bool small = prefer_small && (spread <= kKeyedMaxSpreadSmall || !keyed);
+    // one more key bit on large tiles, worth it only if they still fill the chip; without an argmin
+    // output the value-only variant runs, which has no range condition at all
+    const bool value_only = (d_argmin == nullptr);
+    const bool keyed = !value_only && (spread <= kKeyedMaxSpreadSmall ||
+                       (spread <= kKeyedMaxSpreadLarge && (!prefer_small || large_tiles(Ci, Ck, batch) >= 512)));
+    const bool small = prefer_small && (value_only || spread <= kKeyedMaxSpreadSmall || !keyed);
     const int tile = small ? kTileSmall : kTileLarge;
     const int64_t tilesM = (Ci + tile - 1) / tile, tilesN = (Ck + tile - 1) / tile;
     a.sA = (int64_t)Ci * Cj; a.sw = Cj; a.sB = (int64_t)Cj * Ck; a.sO = (int64_t)Ci * Ck;
@@ -419,7 +422,7 @@ lwp_status lwp_eliminate_node(lwp_ctx* ctx, int32_t batch, int32_t Ci, int32_t C
         const int kparts = choose_kparts(tilesM * tilesN * batch, Cj, small);
         if (kparts > 1) { if (lwp_status s = ensure_split_buffers(ctx)) return s; }
         set_split(ctx, a, kparts);
-        LWP_HIP(ctx, launch_minplus(a, keyed, small, ctx->stream));
+        LWP_HIP(ctx, launch_minplus(a, value_only ? kModeValue : (keyed ? kModeKeyed : kModePlain), small, ctx->stream));
     }
     return LWP_OK;
 }
@@ -458,19 +461,33 @@ lwp_status lwp_plan_graph(int32_t n_nodes, int32_t n_edges, const int32_t* edges
 
 size_t lwp_search_workspace_bytes(int32_t n_nodes, int32_t n_edges, const int32_t* edges, int32_t C,
                                   int32_t schedule) {
-    if (C < 1 || C > kMaxConfigs) return 0;
+    return lwp_search_workspace_bytes_ex(n_nodes, n_edges, edges, C, schedule, LWP_UNDO_STORED);
+}
+
+size_t lwp_search_workspace_bytes_ex(int32_t n_nodes, int32_t n_edges, const int32_t* edges, int32_t C,
+                                     int32_t schedule, int32_t undo) {
+    if (C < 1 || C > kMaxConfigs || (undo != LWP_UNDO_STORED && undo != LWP_UNDO_RECOMPUTE)) return 0;
     Plan plan;
     std::string err;
     if (make_plan(n_nodes, n_edges, edges, schedule, plan, err) != LWP_OK) return 0;
     if (!components_enumerable(plan, C)) return 0;
-    Layout L = plan_buffers(plan, n_edges);
-    return layout_workspace(plan, L, n_nodes, n_edges, C).total;
+    Layout L = plan_buffers(plan, n_edges, undo == LWP_UNDO_RECOMPUTE);
+    return layout_workspace(plan, L, n_nodes, n_edges, C, undo == LWP_UNDO_STORED).total;
 }
 
 lwp_status lwp_search_graph(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, const int32_t* edges,
                             int32_t C, const int32_t* d_tc, const int32_t* d_ts, const int32_t* d_tx,
                             int32_t schedule, int32_t* out_cost, int32_t* out_strategy) {
+    return lwp_search_graph_ex(ctx, n_nodes, n_edges, edges, C, d_tc, d_ts, d_tx, schedule, LWP_UNDO_STORED, out_cost,
+                               out_strategy);
+}
+
+lwp_status lwp_search_graph_ex(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, const int32_t* edges,
+                               int32_t C, const int32_t* d_tc, const int32_t* d_ts, const int32_t* d_tx,
+                               int32_t schedule, int32_t undo, int32_t* out_cost, int32_t* out_strategy) {
     if (lwp_status s = check_ctx(ctx)) return s;
+    if (undo != LWP_UNDO_STORED && undo != LWP_UNDO_RECOMPUTE) return fail(ctx, LWP_E_INVAL, "unknown undo mode");
+    const bool stored = (undo == LWP_UNDO_STORED);
     if (C < 1 || C > kMaxConfigs) return fail(ctx, LWP_E_INVAL, "C must be in [1, 65536]");
     if (!d_tc || !d_ts || (n_edges > 0 && !d_tx) || !out_cost || !out_strategy)
         return fail(ctx, LWP_E_INVAL, "null pointer");
@@ -484,8 +501,8 @@ lwp_status lwp_search_graph(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, cons
     }
     if (!components_enumerable(plan, C))
         return fail(ctx, LWP_E_NOT_REDUCIBLE, "a residual component has more than 2^32 strategies to enumerate");
-    const Layout L = plan_buffers(plan, n_edges);
-    const WsLayout W = layout_workspace(plan, L, n_nodes, n_edges, C);
+    const Layout L = plan_buffers(plan, n_edges, !stored);
+    const WsLayout W = layout_workspace(plan, L, n_nodes, n_edges, C, stored);
     if (lwp_status s = ensure_workspace(ctx, W.total)) return s;
     const size_t head_in_bytes = (2 + 2 * (size_t)(n_edges + n_nodes)) * sizeof(int32_t);
     const size_t pin_head = 0, pin_desc = align_up(head_in_bytes, 256), pin_result = pin_desc + align_up(W.desc_bytes, 256);
@@ -568,7 +585,7 @@ lwp_status lwp_search_graph(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, cons
             NodeDesc d{};
             d.A = table_ptr(L.node_A[ni]); d.w = d_w + (int64_t)s.j * C; d.B = table_ptr(L.node_B[ni]);
             d.out = d_slots + (int64_t)L.node_out_slot[ni] * CC;
-            d.arg = d_args + (int64_t)ni * CC;
+            d.arg = stored ? d_args + (int64_t)ni * CC : nullptr;
             d.loA = (int32_t)rA.lo; d.hiA = (int32_t)rA.hi; d.loW = (int32_t)rw.lo; d.hiW = (int32_t)rw.hi;
             d.loB = (int32_t)rB.lo; d.hiB = (int32_t)rB.hi;
             d.rngA = d_stats + 2 * (int64_t)erng[s.e1];
@@ -576,7 +593,7 @@ lwp_status lwp_search_graph(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, cons
             d.rngOut = d_stats + 2 * (int64_t)(rng_node0 + (int32_t)ni);
             nd[ni] = d;
             nd_spread[ni] = keyed_spread(rA, rw, rB);
-            ud[ni] = {d.arg, s.j, s.i, s.k, s.round};
+            ud[ni] = {d.arg, d.A, d.w, d.B, s.j, s.i, s.k, s.round};
             // any fixed c bounds the minimum from above; take the c with the smallest w
             er[s.e1] = {rA.lo + rw.lo + rB.lo, rA.hi + rw.lo + rB.hi};
             erng[s.e1] = rng_node0 + (int32_t)ni;
@@ -644,15 +661,17 @@ lwp_status lwp_search_graph(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, cons
         const bool prefer_small = want_small_tiles(C, C, C, (int64_t)(ni - n0));
         const bool large_fills_chip = large_tiles(C, C, (int64_t)(ni - n0)) >= 512;
         auto variant = [&](size_t q) {
+            if (!stored) return prefer_small ? 4 : 5;     // value-only: no range condition
             if (nd_spread[q] <= (prefer_small ? kKeyedMaxSpreadSmall : kKeyedMaxSpreadLarge)) return prefer_small ? 0 : 1;
             if (nd_spread[q] <= kKeyedMaxSpreadLarge && large_fills_chip) return 1;
             return prefer_small ? 2 : 3;
-        };   // 0 keyed small, 1 keyed large, 2 plain small, 3 plain large
+        };   // 0 keyed small, 1 keyed large, 2 plain small, 3 plain large, 4 value small, 5 value large
         for (size_t a = n0; a < ni;) {
             const int v = variant(a);
             size_t b = a;
             while (b < ni && variant(b) == v) ++b;
-            const bool keyed = v < 2, small = (v == 0 || v == 2);
+            const bool keyed = v < 2, small = (v == 0 || v == 2 || v == 4);
+            const int mode = v >= 4 ? kModeValue : (keyed ? kModeKeyed : kModePlain);
             const int tile = small ? kTileSmall : kTileLarge;
             NodeArgs na{};
             na.descs = d_nd + a;
@@ -662,7 +681,7 @@ lwp_status lwp_search_graph(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, cons
             const int kparts = choose_kparts((int64_t)na.tilesM * na.tilesN * na.batch, C, small);
             if (kparts > 1) { if (lwp_status s2 = ensure_split_buffers(ctx)) return s2; }
             set_split(ctx, na, kparts);
-            LWP_HIP(ctx, launch_minplus(na, keyed, small, st));
+            LWP_HIP(ctx, launch_minplus(na, mode, small, st));
             a = b;
         }
     }

@@ -47,10 +47,11 @@ constexpr int kTileLarge = 128, kTileSmall = 64, kNodeThreads = 256;
 // with 64 x 64 tiles (32-deep stages)
 constexpr int64_t kKeyedMaxSpreadLarge = (1ll << 27) - 2, kKeyedMaxSpreadSmall = (1ll << 26) - 2;
 
-// keyed = true launches the packed-key variant, keyed = false the plain int32 compare/select
-// variant (ranges ignored).  small_tiles selects 64 x 64 output tiles instead of 128 x 128;
-// tilesM / tilesN in args must match.
-hipError_t launch_minplus(const NodeArgs& args, bool keyed, bool small_tiles, hipStream_t stream);
+// mode: packed keys (needs the spread bound above), plain int32 compare/select (any values), or
+// value-only (minimum without argmin, any values; `arg` is ignored).  small_tiles selects 64 x 64
+// output tiles instead of 128 x 128; tilesM / tilesN in args must match.
+constexpr int kModeKeyed = 0, kModePlain = 1, kModeValue = 2;
+hipError_t launch_minplus(const NodeArgs& args, int mode, bool small_tiles, hipStream_t stream);
 
 // ---- edge elimination (Eq. 3) --------------------------------------------------------------
 // out = sum of n_src tables of `cells` elements.  srcs indexes a device array of table pointers.
@@ -97,7 +98,10 @@ struct CompDesc {
     int32_t K, n_edges;
 };
 struct UndoDesc {       // one node elimination of the log
-    const int32_t* arg; // [C][C]
+    const int32_t* arg; // [C][C] stored argmin, or null: recompute from the three tables below
+    const int32_t* A;   // table of the in-edge (i,j) at the time of the elimination
+    const int32_t* w;   // t_c + t_s of node j
+    const int32_t* B;   // table of the out-edge (j,k)
     int32_t j, i, k, round;
 };
 // keys[p] is a 64-bit (cost, flat index) minimum per component, initialised to all ones.

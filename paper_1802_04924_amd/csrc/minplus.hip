@@ -23,6 +23,8 @@
 //           guarantees that from value ranges; the kernel derives tb itself from the ranges it is
 //           given (measured ones where an earlier launch of the same stream left them).
 //   plain   int32 compare/select per candidate (strict '<' in ascending c); no precondition.
+//   value   the minimum only (signed three-way min, no argmin, no precondition), for callers that
+//           recompute the argmin of the few cells they need afterwards, as the paper's undo pass does.
 #include "lwp_kernels.h"
 
 namespace lwp {
@@ -30,9 +32,6 @@ namespace lwp {
 namespace {
 
 constexpr int NT = kNodeThreads;
-#ifndef LWP_TK_SMALL
-#define LWP_TK_SMALL 32
-#endif
 
 using v4i = int __attribute__((ext_vector_type(4)));
 using gv4cptr = const v4i __attribute__((address_space(1)))*;
@@ -49,8 +48,10 @@ __device__ __forceinline__ int wave_max_i32(int v) {
     return v;
 }
 
-template <bool KEYED, int RB, int TK>
-__global__ __launch_bounds__(NT, KEYED ? 2 : 1) void minplus_kernel(const NodeArgs p) {
+template <int MODE, int RB, int TK>
+__global__ __launch_bounds__(NT, MODE == kModePlain ? 1 : 2) void minplus_kernel(const NodeArgs p) {
+    constexpr bool KEYED = (MODE == kModeKeyed);
+    constexpr bool VALUE = (MODE == kModeValue);   // minimum only: no argmin, no keys, any int32
     constexpr int TM = 16 * RB, TN = 16 * RB;   // output tile
     constexpr int EP = TM * TK / NT;            // elements of A and of B each thread stages per stage
     constexpr int QUADS = RB / 4;
@@ -66,7 +67,7 @@ __global__ __launch_bounds__(NT, KEYED ? 2 : 1) void minplus_kernel(const NodeAr
     const uint32_t total = gridDim.x;
     if ((total & 7u) == 0u) bid = (bid & 7u) * (total >> 3) + (bid >> 3);
     // kparts > 1: that many consecutive workgroups share one tile, each with a part of the c range
-    const int kparts = p.kparts;
+    const int kparts = (RB == 4) ? p.kparts : 1;   // only 64 x 64 tiles are ever split
     const int part = (kparts > 1) ? (int)(bid % (uint32_t)kparts) : 0;
     if (kparts > 1) bid /= (uint32_t)kparts;
     const uint32_t tile_global = bid;
@@ -186,7 +187,8 @@ __global__ __launch_bounds__(NT, KEYED ? 2 : 1) void minplus_kernel(const NodeAr
             if (KEYED) { ka[q] = (min((uint32_t)(ra[q] + rw[q] - offA), cap) << tb) + (pos + q); kb[q] = (uint32_t)rb[q] << tb; }
             else { ka[q] = (uint32_t)(ra[q] + rw[q]); kb[q] = (uint32_t)rb[q]; }
         }
-        if (c0 + TK > Cj) {                       // only the last stage can be ragged
+        // value-only mode needs no padding: the clamped loads repeat the last candidate
+        if (!VALUE && c0 + TK > Cj) {             // only the last stage can be ragged
             const bool cok = (c0 + br) < Cj;
 #pragma unroll
             for (int q = 0; q < EP; ++q) {
@@ -247,6 +249,12 @@ __global__ __launch_bounds__(NT, KEYED ? 2 : 1) void minplus_kernel(const NodeAr
 #pragma unroll
                     for (int j = 0; j < RB; ++j)
                         m1[i][j] = min(min(m1[i][j], av[0][i] + bv[0][j]), av[1][i] + bv[1][j]);
+            } else if (VALUE) {
+#pragma unroll
+                for (int i = 0; i < RB; ++i)
+#pragma unroll
+                    for (int j = 0; j < RB; ++j)
+                        m1[i][j] = (uint32_t)min(min((int32_t)m1[i][j], (int32_t)(av[0][i] + bv[0][j])), (int32_t)(av[1][i] + bv[1][j]));
             } else {
 #pragma unroll
                 for (int u = 0; u < 2; ++u) {
@@ -265,13 +273,19 @@ __global__ __launch_bounds__(NT, KEYED ? 2 : 1) void minplus_kernel(const NodeAr
             // keep the LDS reads of later iterations behind this iteration's arithmetic (otherwise a
             // whole stage of operands is loaded first and the register file overflows): the plain
             // variant's selects get sunk below the reads unless their results are pinned here
-            if (!KEYED) {
+            if (MODE == kModePlain) {
 #pragma unroll
                 for (int i = 0; i < RB; ++i)
 #pragma unroll
                     for (int j = 0; j < RB; j += 4)
                         asm volatile("" : "+v"(m1[i][j]), "+v"(m1[i][j + 1]), "+v"(m1[i][j + 2]), "+v"(m1[i][j + 3]),
                                           "+v"(rec[i][j]), "+v"(rec[i][j + 1]), "+v"(rec[i][j + 2]), "+v"(rec[i][j + 3]));
+            } else if (VALUE) {
+#pragma unroll
+                for (int i = 0; i < RB; ++i)
+#pragma unroll
+                    for (int j = 0; j < RB; j += 4)
+                        asm volatile("" : "+v"(m1[i][j]), "+v"(m1[i][j + 1]), "+v"(m1[i][j + 2]), "+v"(m1[i][j + 3]));
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -302,7 +316,7 @@ __global__ __launch_bounds__(NT, KEYED ? 2 : 1) void minplus_kernel(const NodeAr
     // invalidate is needed; a workgroup-scope release makes every thread's stores complete before
     // the counter is bumped.
     bool raw = KEYED;                          // m1 still holds keys (otherwise plain costs)
-    if (kparts > 1) {
+    if (RB == 4 && kparts > 1) {
         constexpr int CELLS = RB * RB;
         int32_t* slab = p.scratch + ((int64_t)tile_global * kparts) * (2 * CELLS * NT);
         int32_t* mine = slab + (int64_t)part * (2 * CELLS * NT);
@@ -312,7 +326,7 @@ __global__ __launch_bounds__(NT, KEYED ? 2 : 1) void minplus_kernel(const NodeAr
             for (int j = 0; j < RB; ++j) {
                 const int32_t cst = KEYED ? (int32_t)(m1[i][j] >> tb) + offA + offB : (int32_t)m1[i][j];
                 __hip_atomic_store(&mine[(i * RB + j) * NT + tid], cst, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                __hip_atomic_store(&mine[(CELLS + i * RB + j) * NT + tid], (int32_t)rec[i][j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (!VALUE) __hip_atomic_store(&mine[(CELLS + i * RB + j) * NT + tid], (int32_t)rec[i][j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         __syncthreads();
@@ -330,7 +344,7 @@ __global__ __launch_bounds__(NT, KEYED ? 2 : 1) void minplus_kernel(const NodeAr
 #pragma unroll
                 for (int j = 0; j < RB; ++j) {
                     c2[i][j] = __hip_atomic_load(&other[(i * RB + j) * NT + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    r2[i][j] = __hip_atomic_load(&other[(CELLS + i * RB + j) * NT + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    r2[i][j] = VALUE ? 0 : __hip_atomic_load(&other[(CELLS + i * RB + j) * NT + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
 #pragma unroll
             for (int i = 0; i < RB; ++i)
@@ -361,7 +375,7 @@ __global__ __launch_bounds__(NT, KEYED ? 2 : 1) void minplus_kernel(const NodeAr
             const gptr orow = O + (int64_t)a * Ck + b;
             if (vecO) {
                 *(gv4ptr)(orow) = v4i{val[h * 4], val[h * 4 + 1], val[h * 4 + 2], val[h * 4 + 3]};
-                if (G) *(gv4ptr)(G + (int64_t)a * Ck + b) =
+                if (!VALUE && G) *(gv4ptr)(G + (int64_t)a * Ck + b) =
                     v4i{(int32_t)rec[i][h * 4], (int32_t)rec[i][h * 4 + 1], (int32_t)rec[i][h * 4 + 2], (int32_t)rec[i][h * 4 + 3]};
 #pragma unroll
                 for (int q = 0; q < 4; ++q) { vmin = min(vmin, val[h * 4 + q]); vmax = max(vmax, val[h * 4 + q]); }
@@ -370,7 +384,7 @@ __global__ __launch_bounds__(NT, KEYED ? 2 : 1) void minplus_kernel(const NodeAr
                 for (int q = 0; q < 4; ++q)
                     if (b + q < Ck) {
                         orow[q] = val[h * 4 + q];
-                        if (G) G[(int64_t)a * Ck + b + q] = (int32_t)rec[i][h * 4 + q];
+                        if (!VALUE && G) G[(int64_t)a * Ck + b + q] = (int32_t)rec[i][h * 4 + q];
                         vmin = min(vmin, val[h * 4 + q]); vmax = max(vmax, val[h * 4 + q]);
                     }
             }
@@ -390,18 +404,20 @@ __global__ __launch_bounds__(NT, KEYED ? 2 : 1) void minplus_kernel(const NodeAr
 
 }  // namespace
 
-hipError_t launch_minplus(const NodeArgs& args, bool keyed, bool small_tiles, hipStream_t stream) {
+hipError_t launch_minplus(const NodeArgs& args, int mode, bool small_tiles, hipStream_t stream) {
     const int kparts = args.kparts > 1 ? args.kparts : 1;
     const int64_t blocks = (int64_t)args.tilesM * args.tilesN * args.batch * kparts;
     if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     if (kparts > 1 && (!small_tiles || !args.scratch || !args.counters)) return hipErrorInvalidValue;
     dim3 grid((unsigned)blocks), block(NT);
-    if (keyed) {
-        if (small_tiles) hipLaunchKernelGGL((minplus_kernel<true, 4, LWP_TK_SMALL>), grid, block, 0, stream, args);
-        else hipLaunchKernelGGL((minplus_kernel<true, 8, 16>), grid, block, 0, stream, args);
+    if (small_tiles) {
+        if (mode == kModeKeyed) hipLaunchKernelGGL((minplus_kernel<kModeKeyed, 4, 32>), grid, block, 0, stream, args);
+        else if (mode == kModeValue) hipLaunchKernelGGL((minplus_kernel<kModeValue, 4, 32>), grid, block, 0, stream, args);
+        else hipLaunchKernelGGL((minplus_kernel<kModePlain, 4, 32>), grid, block, 0, stream, args);
     } else {
-        if (small_tiles) hipLaunchKernelGGL((minplus_kernel<false, 4, LWP_TK_SMALL>), grid, block, 0, stream, args);
-        else hipLaunchKernelGGL((minplus_kernel<false, 8, 16>), grid, block, 0, stream, args);
+        if (mode == kModeKeyed) hipLaunchKernelGGL((minplus_kernel<kModeKeyed, 8, 16>), grid, block, 0, stream, args);
+        else if (mode == kModeValue) hipLaunchKernelGGL((minplus_kernel<kModeValue, 8, 16>), grid, block, 0, stream, args);
+        else hipLaunchKernelGGL((minplus_kernel<kModePlain, 8, 16>), grid, block, 0, stream, args);
     }
     return hipGetLastError();
 }

@@ -260,15 +260,17 @@ __global__ __launch_bounds__(kThreads) void component_min_kernel(const CompDesc*
 }
 
 // ---- undo (Alg. 1: S^(i) = S^(i+1) + c_j, c_j the stored argmin of Eq. 2 at (c_i, c_k)) ---------
-__global__ __launch_bounds__(kThreads) void back_substitute_kernel(
+// One workgroup of 1024 threads: the recomputing form keeps 16 wavefronts busy per round.
+constexpr int kUndoThreads = 1024;
+__global__ __launch_bounds__(kUndoThreads) void back_substitute_kernel(
     const PairDesc* __restrict__ pairs, int32_t n_pairs, const int32_t* __restrict__ singles, int32_t n_singles,
     const CompDesc* __restrict__ comps, int32_t n_comps,
     const unsigned long long* __restrict__ keys, const UndoDesc* __restrict__ undo, int32_t n_undo, int32_t C,
     int32_t n_nodes, int32_t* __restrict__ result) {
-    __shared__ long long ssum[kThreads / 64];
+    __shared__ long long ssum[kUndoThreads / 64];
     int32_t* S = result + 2;
     long long cost = 0;
-    for (int t = threadIdx.x; t < n_pairs + n_singles + n_comps; t += kThreads) {
+    for (int t = threadIdx.x; t < n_pairs + n_singles + n_comps; t += kUndoThreads) {
         const unsigned long long k = keys[t];
         uint32_t flat = (uint32_t)k;
         cost += (long long)(int32_t)((uint32_t)(k >> 32) ^ 0x80000000u);
@@ -285,7 +287,7 @@ __global__ __launch_bounds__(kThreads) void back_substitute_kernel(
     __syncthreads();
     if (threadIdx.x == 0) {
         long long tot = 0;
-        for (int q = 0; q < kThreads / 64; ++q) tot += ssum[q];
+        for (int q = 0; q < kUndoThreads / 64; ++q) tot += ssum[q];
         result[0] = (int32_t)(tot & 0xffffffffll);
         result[1] = (int32_t)(tot >> 32);
     }
@@ -295,9 +297,27 @@ __global__ __launch_bounds__(kThreads) void back_substitute_kernel(
         const int r = undo[hi - 1].round;
         int lo = hi - 1;
         while (lo > 0 && undo[lo - 1].round == r) --lo;
-        for (int t = lo + threadIdx.x; t < hi; t += kThreads) {
-            const UndoDesc u = undo[t];
-            S[u.j] = ((gi32c)(uintptr_t)u.arg)[(int64_t)S[u.i] * C + S[u.k]];
+        if (undo[lo].arg) {
+            for (int t = lo + threadIdx.x; t < hi; t += kUndoThreads) {
+                const UndoDesc u = undo[t];
+                S[u.j] = ((gi32c)(uintptr_t)u.arg)[(int64_t)S[u.i] * C + S[u.k]];
+            }
+        } else {
+            // no stored argmin: c_j = lowest c minimising A[S_i][c] + w[c] + B[c][S_k] (the paper's
+            // own undo step); one wavefront per elimination
+            for (int t = lo + (threadIdx.x >> 6); t < hi; t += kUndoThreads / 64) {
+                const UndoDesc u = undo[t];
+                const gi32c Arow = (gi32c)(uintptr_t)u.A + (int64_t)S[u.i] * C;
+                const gi32c Bcol = (gi32c)(uintptr_t)u.B + S[u.k];
+                const gi32c wj = (gi32c)(uintptr_t)u.w;
+                unsigned long long best = ~0ull;
+                for (int c = threadIdx.x & 63; c < C; c += 64) {
+                    const unsigned long long k = make_key(Arow[c] + wj[c] + Bcol[(int64_t)c * C], (uint32_t)c);
+                    best = k < best ? k : best;
+                }
+                best = wave_min_u64(best);
+                if ((threadIdx.x & 63) == 0) S[u.j] = (int32_t)(uint32_t)best;
+            }
         }
         __syncthreads();
         hi = lo;
@@ -398,7 +418,7 @@ hipError_t launch_back_substitute(const PairDesc* d_pairs, int32_t n_pairs, cons
                                   const unsigned long long* d_keys,
                                   const UndoDesc* d_undo, int32_t n_undo, int32_t C, int32_t n_nodes,
                                   int32_t* d_result, hipStream_t stream) {
-    hipLaunchKernelGGL(back_substitute_kernel, dim3(1), dim3(kThreads), 0, stream, d_pairs, n_pairs, d_singles,
+    hipLaunchKernelGGL(back_substitute_kernel, dim3(1), dim3(kUndoThreads), 0, stream, d_pairs, n_pairs, d_singles,
                        n_singles, d_comps, n_comps, d_keys, d_undo, n_undo, C, n_nodes, d_result);
     return hipGetLastError();
 }

@@ -36,10 +36,13 @@ def viterbi_chain(tc, ts, tx):
 def test_config2_full(ctx):
     p = wl.config2()
     assert p["n_nodes"] == 120 and len(p["edges"]) == 189 and p["C"] == 512
-    cost, S = ctx.search_graph(p["n_nodes"], p["edges"], p["C"], dev(p["tc"]), dev(p["ts"]), dev(p["tx"]), p["schedule"])
+    from paper_1802_04924_amd import UNDO_RECOMPUTE, UNDO_STORED
     ref = oracle.search(p["n_nodes"], p["edges"], p["C"], p["tc"], p["ts"], p["tx"], p["schedule"])
-    assert cost == ref["cost"]
-    assert np.array_equal(S, ref["strategy"])
+    d_tc, d_ts, d_tx = dev(p["tc"]), dev(p["ts"]), dev(p["tx"])
+    for undo in (UNDO_STORED, UNDO_RECOMPUTE):
+        cost, S = ctx.search_graph(p["n_nodes"], p["edges"], p["C"], d_tc, d_ts, d_tx, p["schedule"], undo)
+        assert cost == ref["cost"]
+        assert np.array_equal(S, ref["strategy"])
     assert oracle.strategy_cost(p["n_nodes"], p["edges"], p["C"], p["tc"], p["ts"], p["tx"], S) == cost
 
 
@@ -68,7 +71,10 @@ def test_config4_full(ctx):
     assert (N, C) == (64, 4096)
     tc, ts, tx = p["tc"], p["ts"], p["tx"]
     d_tc, d_ts, d_tx = dev(tc), dev(ts), dev(tx)
+    from paper_1802_04924_amd import UNDO_RECOMPUTE
     cost, S = ctx.search_graph(N, p["edges"], C, d_tc, d_ts, d_tx, wl.SCHEDULE_LEFT_FOLD)
+    cost_r, S_r = ctx.search_graph(N, p["edges"], C, d_tc, d_ts, d_tx, wl.SCHEDULE_LEFT_FOLD, UNDO_RECOMPUTE)
+    assert cost_r == cost and np.array_equal(S_r, S)        # stored and recomputed argmins agree
     # end to end: the optimum of a chain is the layered shortest path; the strategy attains it
     assert cost == viterbi_chain(tc, ts, tx)
     assert oracle.strategy_cost(N, p["edges"], C, tc, ts, tx, S) == cost

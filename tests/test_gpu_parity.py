@@ -126,13 +126,24 @@ def test_eliminate_node_closed_forms(ctx):
     assert (out.cpu().numpy() == 7).all() and (arg.cpu().numpy() == 0).all()
 
 
-def test_eliminate_node_without_argmin_and_overflow(ctx):
-    from paper_1802_04924_amd import LwpError
-    rng = np.random.default_rng(5)
-    A, w, B = wl.batched_products(2, 50, 60, 70, 5)
+@pytest.mark.parametrize("shape", [(2, 50, 60, 70), (1, 64, 2048, 64), (3, 130, 257, 140), (40, 256, 100, 256), (600, 128, 40, 256)])
+@pytest.mark.parametrize("lo,hi", [(0, 3), (0, 1 << 20), (-(1 << 29), 1 << 29)])
+def test_eliminate_node_value_only(ctx, shape, lo, hi):
+    # no argmin requested: the value-only variant (any int32 range) must give the same minima
+    batch, Ci, Cj, Ck = shape
+    rng = np.random.default_rng(abs(hash((shape, lo, hi))) % (1 << 32))
+    A = rng.integers(lo, hi, size=(batch, Ci, Cj), endpoint=True, dtype=np.int32)
+    w = rng.integers(lo // 4, hi // 4 + 1, size=(batch, Cj), endpoint=True, dtype=np.int32)
+    B = rng.integers(lo, hi, size=(batch, Cj, Ck), endpoint=True, dtype=np.int32)
     out, arg = ctx.eliminate_node(dev(A), dev(w), dev(B), want_argmin=False)
     assert arg is None
-    assert np.array_equal(out.cpu().numpy()[1], oracle.minplus_argmin(A[1], w[1], B[1])[0])
+    out = out.cpu().numpy()
+    for b in range(0, batch, max(1, batch // 7)):
+        assert np.array_equal(out[b], oracle.minplus_argmin(A[b], w[b], B[b])[0]), b
+
+
+def test_eliminate_node_overflow(ctx):
+    from paper_1802_04924_amd import LwpError
     big = np.full((1, 4, 4), (1 << 31) - 1, np.int32)
     with pytest.raises(LwpError) as e:
         ctx.eliminate_node(dev(big), dev(np.ones((1, 4), np.int32)), dev(np.zeros((1, 4, 4), np.int32)))
@@ -153,11 +164,16 @@ def test_eliminate_edge(ctx, shape):
 
 
 def run_search(ctx, p, schedule=None):
+    """Both undo modes (stored argmin tables / recomputed argmin, as the paper's Alg. 1 does) must
+    return the oracle's cost and strategy."""
+    from paper_1802_04924_amd import UNDO_RECOMPUTE, UNDO_STORED
     schedule = p["schedule"] if schedule is None else schedule
-    cost, S = ctx.search_graph(p["n_nodes"], p["edges"], p["C"], dev(p["tc"]), dev(p["ts"]), dev(p["tx"]), schedule)
     ref = oracle.search(p["n_nodes"], p["edges"], p["C"], p["tc"], p["ts"], p["tx"], schedule)
-    assert cost == ref["cost"]
-    assert np.array_equal(S, ref["strategy"])
+    d_tc, d_ts, d_tx = dev(p["tc"]), dev(p["ts"]), dev(p["tx"])
+    for undo in (UNDO_STORED, UNDO_RECOMPUTE):
+        cost, S = ctx.search_graph(p["n_nodes"], p["edges"], p["C"], d_tc, d_ts, d_tx, schedule, undo)
+        assert cost == ref["cost"], undo
+        assert np.array_equal(S, ref["strategy"]), undo
     assert oracle.strategy_cost(p["n_nodes"], p["edges"], p["C"], p["tc"], p["ts"], p["tx"], S) == cost
     return cost, S
 

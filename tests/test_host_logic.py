@@ -110,6 +110,9 @@ def test_workspace_size(lib):
     b = binding.search_workspace_bytes(n, wl.chain_edges(n), C, 1)
     assert (62 + 2) * C * C * 4 <= b <= (62 + 2) * C * C * 4 + (1 << 22)
     assert binding.search_workspace_bytes(3, np.array([(0, 1), (1, 2), (2, 0)], np.int32), 8, 0) == 0
+    # recomputed undo: no argmin tables, but every intermediate table stays alive (61 consumed + 1 final)
+    r = binding.search_workspace_bytes(n, wl.chain_edges(n), C, 1, binding.UNDO_RECOMPUTE)
+    assert 62 * C * C * 4 <= r <= 62 * C * C * 4 + (1 << 22)
 
 
 def test_no_gpu_means_loud_failure():

@@ -90,6 +90,20 @@ def test_minplus_uses_w_exactly_once():
     assert (out == 4).all() and (arg == 1).all()
 
 
+def test_stored_argmin_equals_a_fresh_rescan():
+    # Alg. 1 recomputes c_j in the undo pass; the stored argmin must be what a rescan of
+    # A[a][.] + w + B[.][b] finds first
+    rng = np.random.default_rng(12)
+    A = rng.integers(0, 4, size=(20, 50), dtype=np.int32)
+    w = rng.integers(0, 4, size=50, dtype=np.int32)
+    B = rng.integers(0, 4, size=(50, 30), dtype=np.int32)
+    out, arg = oracle.minplus_argmin(A, w, B)
+    for a in range(20):
+        for b in range(30):
+            cand = [int(A[a, c]) + int(w[c]) + int(B[c, b]) for c in range(50)]
+            assert out[a, b] == min(cand) and arg[a, b] == cand.index(min(cand))
+
+
 def test_minplus_negative_and_overflow():
     A = np.array([[-5, 3]], np.int32)
     B = np.array([[2], [-20]], np.int32)
