@@ -106,6 +106,42 @@ def config2(C: int = 512, n_modules: int = 10):
     return forkjoin_problem(n_modules, C, 2, name=f"cfg2_forkjoin{n_modules}_C{C}")
 
 
+def series_parallel_edges(n_ops: int, seed: int, p_parallel: float = 0.3, p_branch: float = 0.15,
+                          max_branches: int = 2):
+    """Random two-terminal DAG grown from one edge by series splits (an edge gets a new node in
+    the middle), parallel duplications (an edge is doubled) and, with probability ``p_branch``,
+    dangling branches (a new sink hanging off an existing node, which makes the residual graph
+    larger than two nodes; at most ``max_branches`` of them).  Node ids are assigned in creation
+    order, so they are NOT topological.
+    """
+    rng = _rng(seed)
+    edges = [(0, 1)]
+    n = 2
+    branches = 0
+    for _ in range(n_ops):
+        r = rng.random()
+        e = int(rng.integers(0, len(edges)))
+        if r < p_branch and branches < max_branches:
+            branches += 1
+            edges.append((edges[e][int(rng.integers(0, 2))], n))
+            n += 1
+        elif r < p_branch + p_parallel:
+            edges.append(edges[e])
+        else:
+            a, b = edges[e]
+            edges[e] = (a, n)
+            edges.append((n, b))
+            n += 1
+    order = rng.permutation(len(edges))
+    return n, np.asarray([edges[i] for i in order], dtype=np.int32).reshape(-1, 2)
+
+
+def series_parallel_problem(n_ops, C, seed, hi=1000, schedule=SCHEDULE_ROUNDS, p_branch=0.0):
+    n_nodes, edges = series_parallel_edges(n_ops, seed, p_branch=p_branch)
+    tc, ts, tx = random_tables(n_nodes, edges, C, seed + 77, (0, hi), (0, hi), (0, hi))
+    return _problem(f"sp{n_ops}_C{C}", n_nodes, edges, C, tc, ts, tx, schedule)
+
+
 def batched_products(batch, Ci, Cj, Ck, seed, hi=1 << 20):
     """Independent (A, w, B) triples for the isolated node-elimination kernel."""
     rng = _rng(seed)

@@ -201,6 +201,56 @@ def test_search_forkjoin(ctx, modules, C, hi, schedule):
     run_search(ctx, p, schedule)
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_search_random_series_parallel(ctx, seed):
+    # random topologies: non-topological node ids, shuffled edges, multi-way parallel edges, and
+    # (odd seeds) dangling branches that leave residual components to enumerate
+    C = [3, 17, 64, 130][seed % 4]
+    p = wl.series_parallel_problem(30 + 7 * seed, C, seed, hi=[2, 1000, 1 << 20][seed % 3], p_branch=0.08 if seed % 2 else 0.0)
+    from paper_1802_04924_amd import plan_graph
+    K = plan_graph(p["n_nodes"], p["edges"])["n_residual_nodes"]
+    if K > 2 and C ** K > (1 << 26):              # more strategies than the oracle enumerates
+        p = wl.series_parallel_problem(30 + 7 * seed, 3, seed, hi=5, p_branch=0.08)
+    for schedule in (wl.SCHEDULE_ROUNDS, wl.SCHEDULE_LEFT_FOLD):
+        run_search(ctx, p, schedule)
+
+
+def test_eliminate_node_maximum_candidate_count(ctx):
+    # Cj at its limit of 65536: one tile, split over workgroups, widest index field
+    rng = np.random.default_rng(65536)
+    Cj = 65536
+    for hi in (3, 1 << 12):
+        A = rng.integers(0, hi, size=(1, 40, Cj), endpoint=True, dtype=np.int32)
+        w = rng.integers(0, hi, size=(1, Cj), endpoint=True, dtype=np.int32)
+        B = rng.integers(0, hi, size=(1, Cj, 70), endpoint=True, dtype=np.int32)
+        check_products(ctx, A, w, B, expect_keyed=True)
+
+
+def test_invalid_arguments_are_refused_before_any_launch(ctx):
+    import ctypes
+    from paper_1802_04924_amd import binding
+    lib, h = binding.load(), ctx._h
+    t = dev(np.zeros((4, 4), np.int32))
+    p = ctypes.c_void_p(t.data_ptr())
+    assert lib.lwp_eliminate_node(h, 1, 4, 4, 4, None, p, p, p, p) == binding.E_INVAL
+    assert lib.lwp_eliminate_node(h, 0, 4, 4, 4, p, p, p, p, p) == binding.E_INVAL
+    assert lib.lwp_eliminate_node(h, 1, 4, 1 << 17, 4, p, p, p, p, p) == binding.E_INVAL
+    assert lib.lwp_eliminate_node(h, 1, 4, 4, 4, ctypes.c_void_p(t.data_ptr() + 2), p, p, p, p) == binding.E_INVAL
+    assert lib.lwp_eliminate_edge(h, 1, 4, 4, p, None, p) == binding.E_INVAL
+    assert lib.lwp_eliminate_edge(h, 1, -1, 4, p, p, p) == binding.E_INVAL
+    cost = ctypes.c_int32(7)
+    S = np.full(2, -5, np.int32)
+    e = np.array([[0, 1]], np.int32)
+    assert lib.lwp_search_graph(h, 2, 1, e.ctypes.data, 0, p, p, p, 0, ctypes.byref(cost), S.ctypes.data) == binding.E_INVAL
+    assert lib.lwp_search_graph(h, 2, 1, e.ctypes.data, 4, p, p, None, 0, ctypes.byref(cost), S.ctypes.data) == binding.E_INVAL
+    assert lib.lwp_search_graph_ex(h, 2, 1, e.ctypes.data, 4, p, p, p, 0, 9, ctypes.byref(cost), S.ctypes.data) == binding.E_INVAL
+    bad = np.array([[0, 2]], np.int32)
+    assert lib.lwp_search_graph(h, 2, 1, bad.ctypes.data, 4, p, p, p, 0, ctypes.byref(cost), S.ctypes.data) == binding.E_GRAPH
+    assert cost.value == 7 and (S == -5).all()              # outputs untouched on error
+    assert b"endpoint" in lib.lwp_last_error(h)
+    assert lib.lwp_eliminate_node(None, 1, 4, 4, 4, p, p, p, p, p) == binding.E_INVAL
+
+
 def test_search_small_irregular_graphs(ctx):
     graphs = {
         "single": (1, []), "two_isolated": (2, []), "parallel3": (2, [(0, 1), (0, 1), (0, 1)]),

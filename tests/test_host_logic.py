@@ -50,6 +50,8 @@ def graphs():
     }
     for m, s in ((1, 5), (3, 7), (10, 2)):
         g[f"forkjoin{m}"] = wl.forkjoin_edges(m, s)
+    for s in range(6):
+        g[f"series_parallel{s}"] = wl.series_parallel_edges(40 + 10 * s, s, p_branch=0.04 if s % 2 else 0.0)
     return g
 
 

@@ -291,6 +291,23 @@ def test_forkjoin_full_topology_counts():
     assert r2["cost"] == r["cost"]
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_random_series_parallel_graphs_equal_brute_force(seed):
+    # random two-terminal DAGs (non-topological ids, shuffled edge order, parallel edges), some
+    # with dangling branches that leave a residual graph of more than two nodes
+    n, e = wl.series_parallel_edges(6 + seed % 4, seed, p_branch=0.2 if seed % 3 == 0 else 0.0)
+    C = 2 if n > 9 else 3
+    for hi in (1, 30):
+        tc, ts, tx = wl.random_tables(n, e, C, seed * 5 + hi, (0, hi), (0, hi), (0, hi))
+        best, S_lex, n_opt = brute.brute_force(n, e, C, tc, ts, tx)
+        for schedule in (oracle.SCHEDULE_ROUNDS, oracle.SCHEDULE_LEFT_FOLD):
+            r = oracle.search(n, e, C, tc, ts, tx, schedule)
+            assert r["cost"] == best
+            assert oracle.strategy_cost(n, e, C, tc, ts, tx, r["strategy"]) == best
+            if n_opt == 1:
+                assert np.array_equal(r["strategy"], S_lex)
+
+
 IRREDUCIBLE = {
     "star_out": (4, [(0, 1), (0, 2), (0, 3)]),
     "star_in": (4, [(1, 0), (2, 0), (3, 0)]),
