@@ -80,7 +80,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="cfg4", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "resid"])
+    ap.add_argument("--workload", default="cfg4", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "resid", "vgg16"])
     ap.add_argument("--layers", type=int, default=64, help="cfg4 only: chain length")
     ap.add_argument("--configs", type=int, default=0, help="override C of the workload")
     ap.add_argument("--undo", default="stored", choices=["stored", "recompute"],
@@ -126,9 +126,9 @@ def main():
     else:
         if name == "cfg4":
             p = wl.config4(args.layers, args.configs or 4096)
-        elif name == "cfg1":
-            # tables of the AlexNet-shaped chain come from the library's own cost-model kernels
-            p = wl.config1()
+        elif name in ("cfg1", "vgg16"):
+            # tables of the AlexNet- / VGG-16-shaped chain come from the library's own cost-model kernels
+            p = wl.config1() if name == "cfg1" else wl.vgg16_problem()
             with Context(0) as c1:
                 tabs = c1.build_cost_tables(p["layers"], p["edges"], p["configs"], p["machine"])
             p["tc"], p["ts"], p["tx"] = (t.cpu().numpy() for t in tabs)

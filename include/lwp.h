@@ -9,7 +9,10 @@
  *
  * Conventions
  *   - All costs are int32 nanoseconds.  Sums are exact; every minimum takes the LOWEST index
- *     among equal candidates.  A sum that could leave int32 is refused (LWP_E_OVERFLOW).
+ *     among equal candidates.  A sum that could leave int32 is refused (LWP_E_OVERFLOW): for a
+ *     node elimination the test is max A + max w + max B (and the minima) over the tables' actual
+ *     value ranges, measured on the device; edge sums and the residual-graph sums are tested
+ *     element by element.  The test is sufficient, not necessary.
  *   - A cost table of an edge e = (l_i, l_j) is row-major [cfg of l_i][cfg of l_j].
  *   - "DEVICE" pointers are HIP device memory on the context's device, owned by the caller;
  *     the library never frees or keeps them.  "HOST" pointers are ordinary host memory.
@@ -38,7 +41,7 @@ typedef enum {
     LWP_E_INVAL = -1,          /* null pointer, non-positive size, misaligned pointer        */
     LWP_E_GRAPH = -2,          /* endpoint out of range, self loop, cycle                    */
     LWP_E_NOT_REDUCIBLE = -3,  /* a residual component is too large to enumerate             */
-    LWP_E_OVERFLOW = -4,       /* value ranges do not guarantee that every sum fits int32    */
+    LWP_E_OVERFLOW = -4,       /* the tables' value ranges do not keep every sum inside int32 */
     LWP_E_NOMEM = -5,          /* device or host allocation failed                           */
     LWP_E_HIP = -6             /* a HIP runtime call failed                                  */
 } lwp_status;

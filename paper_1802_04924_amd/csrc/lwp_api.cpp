@@ -273,7 +273,7 @@ WsLayout layout_workspace(const Plan& plan, const Layout& L, int32_t n_nodes, in
     o.w = put((size_t)n_nodes * C * sizeof(int32_t));
     o.head = put((2 + 2 * (size_t)o.n_ranges) * sizeof(int32_t));
     o.keys = put(std::max<size_t>(1, plan.pairs.size() + plan.singles.size() + plan.comps.size()) * sizeof(unsigned long long));
-    o.result = put((2 + (size_t)n_nodes) * sizeof(int32_t));
+    o.result = put((3 + (size_t)n_nodes) * sizeof(int32_t));
     {
         size_t b = 0;
         auto sub = [&](size_t bytes) { size_t at = b; b = align_up(b + bytes, 16); return at; };
@@ -506,7 +506,7 @@ lwp_status lwp_search_graph_ex(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, c
     if (lwp_status s = ensure_workspace(ctx, W.total)) return s;
     const size_t head_in_bytes = (2 + 2 * (size_t)(n_edges + n_nodes)) * sizeof(int32_t);
     const size_t pin_head = 0, pin_desc = align_up(head_in_bytes, 256), pin_result = pin_desc + align_up(W.desc_bytes, 256);
-    if (lwp_status s = ensure_pinned(ctx, pin_result + (2 + (size_t)n_nodes) * sizeof(int32_t))) return s;
+    if (lwp_status s = ensure_pinned(ctx, pin_result + (3 + (size_t)n_nodes) * sizeof(int32_t))) return s;
     char* ws = ctx->ws;
     hipStream_t st = ctx->stream;
     const int64_t CC = (int64_t)C * C;
@@ -525,7 +525,8 @@ lwp_status lwp_search_graph_ex(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, c
     const int32_t rng_w0 = n_edges, rng_node0 = n_edges + n_nodes, rng_group0 = rng_node0 + plan.n_node_steps;
 
     // 1. w = t_c + t_s with its ranges, and the range of every input table; one read-back
-    LWP_HIP(ctx, launch_prepare_search(d_tc, d_ts, d_w, n_nodes, C, d_stats, W.n_ranges, rng_w0, d_keys, n_comp, st));
+    int32_t* d_flag = d_head;      // set by any kernel that finds a sum outside int32
+    LWP_HIP(ctx, launch_prepare_search(d_tc, d_ts, d_w, n_nodes, C, d_stats, W.n_ranges, rng_w0, d_keys, n_comp, d_flag, st));
     LWP_HIP(ctx, launch_ranges(d_tx, n_edges, CC, d_stats, st));
     int32_t* h_head = reinterpret_cast<int32_t*>(ctx->pin + pin_head);
     LWP_HIP(ctx, hipMemcpyAsync(h_head, d_head, head_in_bytes, hipMemcpyDeviceToHost, st));
@@ -558,6 +559,11 @@ lwp_status lwp_search_graph_ex(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, c
     for (int32_t e = 0; e < n_edges; ++e) { er[e] = {stats[2 * e], stats[2 * e + 1]}; erng[e] = e; }
     for (int32_t v = 0; v < n_nodes; ++v) wr[v] = {stats[2 * (rng_w0 + v)], stats[2 * (rng_w0 + v) + 1]};
     std::vector<int64_t> nd_spread(plan.n_node_steps);
+    // The propagated bounds are worst cases and grow along a chain although the minima do not.
+    // Where they cannot prove that a step stays inside int32 the step is not refused: it runs on a
+    // variant without range conditions and every kernel checks the tables' measured ranges (or
+    // the sums themselves) on the device; the flag they set is read back with the result.
+    auto sat = [](Range r) { return Range{std::max(r.lo, kI32Min), std::min(r.hi, kI32Max)}; };
     {
         size_t ni = 0, gi = 0, nsrc = 0, t = 0;
         const size_t n = plan.steps.size();
@@ -567,11 +573,11 @@ lwp_status lwp_search_graph_ex(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, c
                 const auto& g = L.groups[gi];
                 Range r = er[g.keep];
                 for (int32_t o : g.others) r = {r.lo + er[o].lo, r.hi + er[o].hi};
-                if (!fits(r.lo) || !fits(r.hi)) return fail(ctx, LWP_E_OVERFLOW, "sum of parallel edge tables may leave int32");
-                er[g.keep] = r;
+                er[g.keep] = sat(r);
                 erng[g.keep] = rng_group0 + (int32_t)gi;
                 ed[gi].out = d_slots + (int64_t)L.group_out_slot[gi] * CC;
                 ed[gi].rngOut = d_stats + 2 * (int64_t)erng[g.keep];
+                ed[gi].flag = d_flag;
                 ed[gi].first_src = (int32_t)nsrc;
                 ed[gi].n_src = (int32_t)L.group_src[gi].size();
                 for (auto& r2 : L.group_src[gi]) src_ptrs[nsrc++] = table_ptr(r2);
@@ -580,9 +586,9 @@ lwp_status lwp_search_graph_ex(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, c
                 continue;
             }
             const Range rA = er[s.e1], rw = wr[s.j], rB = er[s.e2];
-            if (!fits(rA.lo + rw.lo) || !fits(rA.hi + rw.hi) || !fits(rA.lo + rw.lo + rB.lo) || !fits(rA.hi + rw.hi + rB.hi))
-                return fail(ctx, LWP_E_OVERFLOW, "a node elimination may leave int32");
+            const bool proven = fits(rA.lo + rw.lo) && fits(rA.hi + rw.hi) && fits(rA.lo + rw.lo + rB.lo) && fits(rA.hi + rw.hi + rB.hi);
             NodeDesc d{};
+            d.flag = d_flag;
             d.A = table_ptr(L.node_A[ni]); d.w = d_w + (int64_t)s.j * C; d.B = table_ptr(L.node_B[ni]);
             d.out = d_slots + (int64_t)L.node_out_slot[ni] * CC;
             d.arg = stored ? d_args + (int64_t)ni * CC : nullptr;
@@ -592,10 +598,10 @@ lwp_status lwp_search_graph_ex(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, c
             d.rngB = d_stats + 2 * (int64_t)erng[s.e2];
             d.rngOut = d_stats + 2 * (int64_t)(rng_node0 + (int32_t)ni);
             nd[ni] = d;
-            nd_spread[ni] = keyed_spread(rA, rw, rB);
+            nd_spread[ni] = proven ? keyed_spread(rA, rw, rB) : (int64_t)1 << 62;   // unproven: no packed keys
             ud[ni] = {d.arg, d.A, d.w, d.B, s.j, s.i, s.k, s.round};
             // any fixed c bounds the minimum from above; take the c with the smallest w
-            er[s.e1] = {rA.lo + rw.lo + rB.lo, rA.hi + rw.lo + rB.hi};
+            er[s.e1] = sat({rA.lo + rw.lo + rB.lo, rA.hi + rw.lo + rB.hi});
             erng[s.e1] = rng_node0 + (int32_t)ni;
             ++ni; ++t;
         }
@@ -604,8 +610,6 @@ lwp_status lwp_search_graph_ex(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, c
     for (size_t q = 0; q < plan.pairs.size(); ++q) {
         const auto& pr = plan.pairs[q];
         const int64_t lo = wr[pr.src].lo + er[pr.edge].lo + wr[pr.dst].lo, hi = wr[pr.src].hi + er[pr.edge].hi + wr[pr.dst].hi;
-        if (!fits(lo) || !fits(hi) || !fits(wr[pr.src].hi + er[pr.edge].hi) || !fits(wr[pr.src].lo + er[pr.edge].lo))
-            return fail(ctx, LWP_E_OVERFLOW, "the residual-graph sum may leave int32");
         total_lo += lo; total_hi += wr[pr.src].lo + er[pr.edge].hi + wr[pr.dst].lo;
         pd[q] = {table_ptr(L.final_table[q]), pr.src, pr.dst};
     }
@@ -626,15 +630,10 @@ lwp_status lwp_search_graph_ex(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, c
             d.dst_pos[x] = (int8_t)(std::find(c.nodes.begin(), c.nodes.end(), c.edst[x]) - c.nodes.begin());
             lo += er[c.edges[x]].lo; hi += er[c.edges[x]].hi;
         }
-        // partial sums only add terms of one sign range each; bound both ends with all terms
-        int64_t neg = 0, pos = 0;
-        for (int x = 0; x < d.K; ++x) { neg += std::min<int64_t>(0, wr[c.nodes[x]].lo); pos += std::max<int64_t>(0, wr[c.nodes[x]].hi); }
-        for (int x = 0; x < d.n_edges; ++x) { neg += std::min<int64_t>(0, er[c.edges[x]].lo); pos += std::max<int64_t>(0, er[c.edges[x]].hi); }
-        if (!fits(neg) || !fits(pos)) return fail(ctx, LWP_E_OVERFLOW, "the sum over a residual component may leave int32");
         total_lo += lo; total_hi += hi;
         cd[q] = d;
     }
-    if (!fits(total_lo) || !fits(total_hi)) return fail(ctx, LWP_E_OVERFLOW, "the total cost may leave int32");
+    (void)total_lo; (void)total_hi;    // the total is formed in 64 bits on the device and checked after the read-back
 
     // 3. descriptors to the device: one copy
     LWP_HIP(ctx, hipMemcpyAsync(db, hb, W.desc_bytes, hipMemcpyHostToDevice, st));
@@ -687,17 +686,18 @@ lwp_status lwp_search_graph_ex(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, c
     }
 
     // 5. residual graph, undo, results
-    LWP_HIP(ctx, launch_pair_min(d_pd, (int32_t)plan.pairs.size(), d_w, C, d_keys, st));
+    LWP_HIP(ctx, launch_pair_min(d_pd, (int32_t)plan.pairs.size(), d_w, C, d_keys, d_flag, st));
     LWP_HIP(ctx, launch_single_min(d_singles, (int32_t)plan.singles.size(), d_w, C, d_keys + plan.pairs.size(), st));
     for (size_t q = 0; q < plan.comps.size(); ++q)
         LWP_HIP(ctx, launch_component_min(d_cd + q, (int32_t)plan.comps[q].nodes.size(), d_w, C,
-                                          d_keys + plan.pairs.size() + plan.singles.size() + q, st));
+                                          d_keys + plan.pairs.size() + plan.singles.size() + q, d_flag, st));
     LWP_HIP(ctx, launch_back_substitute(d_pd, (int32_t)plan.pairs.size(), d_singles, (int32_t)plan.singles.size(),
                                         d_cd, (int32_t)plan.comps.size(), d_keys, d_ud, plan.n_node_steps, C, n_nodes,
-                                        d_result, st));
+                                        d_flag, d_result, st));
     int32_t* result = reinterpret_cast<int32_t*>(ctx->pin + pin_result);
-    LWP_HIP(ctx, hipMemcpyAsync(result, d_result, (2 + (size_t)n_nodes) * sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    LWP_HIP(ctx, hipMemcpyAsync(result, d_result, (3 + (size_t)n_nodes) * sizeof(int32_t), hipMemcpyDeviceToHost, st));
     LWP_HIP(ctx, hipStreamSynchronize(st));
+    if (result[2 + n_nodes]) return fail(ctx, LWP_E_OVERFLOW, "a sum may leave int32 (found on the device from the tables' actual ranges)");
     const int64_t total = (int64_t)(((uint64_t)(uint32_t)result[1] << 32) | (uint32_t)result[0]);
     if (!fits(total)) return fail(ctx, LWP_E_OVERFLOW, "the total cost leaves int32");
     *out_cost = (int32_t)total;

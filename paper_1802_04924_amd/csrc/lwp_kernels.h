@@ -24,7 +24,7 @@ struct NodeDesc {
     const int32_t* rngA;
     const int32_t* rngB;
     int32_t* rngOut;
-    int64_t pad;
+    int32_t* flag;     // optional: OR-ed with 1 if max A + max w + max B (measured) may leave int32
 };
 static_assert(sizeof(NodeDesc) == 96, "descriptor layout");
 
@@ -58,6 +58,7 @@ hipError_t launch_minplus(const NodeArgs& args, int mode, bool small_tiles, hipS
 struct EdgeDesc {
     int32_t* out;
     int32_t* rngOut;     // optional {min, max} of out, by atomics (see NodeDesc)
+    int32_t* flag;       // optional: OR-ed with 1 if a sum leaves int32
     int32_t first_src;   // index into the pointer array
     int32_t n_src;
 };
@@ -78,9 +79,10 @@ hipError_t launch_ranges(const int32_t* d_tables, int32_t n_tables, int64_t cell
 // First launch of a search: w[v][c] = tc[v][c] + ts[v][c]; stats pair w_pair0 + v receives
 // {min, max} of row v of w, or {INT32_MAX, INT32_MIN} if a sum of that row leaves int32; all other
 // of the n_pairs stats pairs are initialised for atomic min/max and keys[0..n_keys) to all ones.
+// *d_flag (optional) is set to 0.
 hipError_t launch_prepare_search(const int32_t* tc, const int32_t* ts, int32_t* w, int32_t n_nodes, int32_t C,
                                  int32_t* d_stats, int32_t n_pairs, int32_t w_pair0, unsigned long long* d_keys,
-                                 int32_t n_keys, hipStream_t stream);
+                                 int32_t n_keys, int32_t* d_flag, hipStream_t stream);
 
 // ---- residual graph and back-substitution (Alg. 1, enumeration of the final graph and undo) --
 struct PairDesc {       // residual component with two nodes joined by one edge
@@ -105,20 +107,22 @@ struct UndoDesc {       // one node elimination of the log
     int32_t j, i, k, round;
 };
 // keys[p] is a 64-bit (cost, flat index) minimum per component, initialised to all ones.
+// d_flag (optional) is OR-ed with 1 if a sum leaves int32.
 hipError_t launch_pair_min(const PairDesc* d_pairs, int32_t n_pairs, const int32_t* d_w, int32_t C,
-                           unsigned long long* d_keys, hipStream_t stream);
+                           unsigned long long* d_keys, int32_t* d_flag, hipStream_t stream);
 hipError_t launch_single_min(const int32_t* d_singles, int32_t n_singles, const int32_t* d_w, int32_t C,
                              unsigned long long* d_keys /* after the pairs */, hipStream_t stream);
 // One launch per component; key = d_keys[index of the component].
 hipError_t launch_component_min(const CompDesc* d_comp, int32_t K, const int32_t* d_w, int32_t C,
-                                unsigned long long* d_key, hipStream_t stream);
+                                unsigned long long* d_key, int32_t* d_flag, hipStream_t stream);
 // Decodes the component minima (keys: pairs, then singles, then enumerated components), then
 // walks the undo list backwards (entries of one round are independent).
-// result[0] = total cost low word, result[1] = high word, result[2..] = strategy.
+// result[0] = total cost low word, result[1] = high word, result[2..2+n_nodes) = strategy,
+// result[2+n_nodes] = *d_flag (0 if d_flag is null).
 hipError_t launch_back_substitute(const PairDesc* d_pairs, int32_t n_pairs, const int32_t* d_singles,
                                   int32_t n_singles, const CompDesc* d_comps, int32_t n_comps,
                                   const unsigned long long* d_keys,
                                   const UndoDesc* d_undo, int32_t n_undo, int32_t C, int32_t n_nodes,
-                                  int32_t* d_result, hipStream_t stream);
+                                  const int32_t* d_flag, int32_t* d_result, hipStream_t stream);
 
 }  // namespace lwp

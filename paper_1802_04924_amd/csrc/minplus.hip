@@ -104,6 +104,17 @@ __global__ __launch_bounds__(NT, MODE == kModePlain ? 1 : 2) void minplus_kernel
     const gptr O = (gptr)(uintptr_t)d.out;
     const gptr G = (gptr)(uintptr_t)d.arg;
 
+    // ---- the sums must fit int32: checked against the measured ranges of the operands ----
+    if (d.flag) {
+        long long loA = d.loA, hiA = d.hiA, loB = d.loB, hiB = d.hiB;
+        if (d.rngA) { const gcptr r = (gcptr)(uintptr_t)d.rngA; loA = max(loA, (long long)r[0]); hiA = min(hiA, (long long)r[1]); }
+        if (d.rngB) { const gcptr r = (gcptr)(uintptr_t)d.rngB; loB = max(loB, (long long)r[0]); hiB = min(hiB, (long long)r[1]); }
+        const long long hi = hiA + d.hiW + hiB, lo = loA + d.loW + loB;
+        const long long hi2 = hiA + d.hiW, lo2 = loA + d.loW;
+        if ((hi > 2147483647ll || lo < -2147483648ll || hi2 > 2147483647ll || lo2 < -2147483648ll) && threadIdx.x == 0)
+            atomicOr(d.flag, 1);
+    }
+
     // ---- key parameters from value ranges (uniform, scalar) ----
     int32_t offA = 0, offB = 0;
     int tb = 0;

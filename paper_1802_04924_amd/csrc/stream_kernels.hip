@@ -49,12 +49,20 @@ __global__ __launch_bounds__(kThreads) void edge_sum_desc_kernel(const EdgeDesc*
     const int64_t stride = (int64_t)gridDim.x * kThreads;
     const int64_t t0 = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     int lo = 0x7fffffff, hi = (int)0x80000000;
+    bool bad = false;
     const gi32 out = (gi32)(uintptr_t)d.out;
     if (vec) {
         const int64_t n4 = cells >> 2;
         for (int64_t x = t0; x < n4; x += stride) {
             v4i acc = ((gv4c)(uintptr_t)sp[0])[x];
-            for (int q = 1; q < n; ++q) acc += ((gv4c)(uintptr_t)sp[q])[x];
+            for (int q = 1; q < n; ++q) {
+                const v4i v = ((gv4c)(uintptr_t)sp[q])[x];
+                // signed overflow of a + v: operands agree in sign, the sum does not
+                const v4i sum = acc + v;
+                const v4i ov = (acc ^ sum) & (v ^ sum);
+                bad |= (ov.x | ov.y | ov.z | ov.w) < 0;
+                acc = sum;
+            }
             ((gv4)out)[x] = acc;
             lo = min(min(lo, acc.x), min(acc.y, min(acc.z, acc.w)));
             hi = max(max(hi, acc.x), max(acc.y, max(acc.z, acc.w)));
@@ -62,11 +70,17 @@ __global__ __launch_bounds__(kThreads) void edge_sum_desc_kernel(const EdgeDesc*
     } else {
         for (int64_t x = t0; x < cells; x += stride) {
             int32_t acc = ((gi32c)(uintptr_t)sp[0])[x];
-            for (int q = 1; q < n; ++q) acc += ((gi32c)(uintptr_t)sp[q])[x];
+            for (int q = 1; q < n; ++q) {
+                const int32_t v = ((gi32c)(uintptr_t)sp[q])[x];
+                const int32_t sum = (int32_t)((uint32_t)acc + (uint32_t)v);
+                bad |= ((acc ^ sum) & (v ^ sum)) < 0;
+                acc = sum;
+            }
             out[x] = acc;
             lo = min(lo, acc); hi = max(hi, acc);
         }
     }
+    if (bad && d.flag) atomicOr(d.flag, 1);
     if (d.rngOut) {
         __shared__ int red[2 * (kThreads / 64)];
         lo = wave_min(lo); hi = wave_max(hi);
@@ -142,9 +156,10 @@ __global__ __launch_bounds__(kThreads) void prepare_search_kernel(const int32_t*
                                                                   int32_t* __restrict__ w, int32_t n_nodes, int32_t C,
                                                                   int32_t* __restrict__ stats, int32_t n_pairs,
                                                                   int32_t w_pair0, unsigned long long* __restrict__ keys,
-                                                                  int32_t n_keys) {
+                                                                  int32_t n_keys, int32_t* __restrict__ flag) {
     if ((int)blockIdx.x >= n_nodes) {
         const int t = ((int)blockIdx.x - n_nodes) * kThreads + threadIdx.x;
+        if (t == 0 && flag) *flag = 0;
         if (t < n_pairs && (t < w_pair0 || t >= w_pair0 + n_nodes)) { stats[2 * t] = 0x7fffffff; stats[2 * t + 1] = (int32_t)0x80000000; }
         if (t < n_keys) keys[t] = ~0ull;
         return;
@@ -191,20 +206,25 @@ __device__ __forceinline__ void block_min_to(unsigned long long v, unsigned long
 // min over (a,b) of w_i[a] + T[a][b] + w_k[b]; grid.y = component
 __global__ __launch_bounds__(kThreads) void pair_min_kernel(const PairDesc* __restrict__ pairs,
                                                             const int32_t* __restrict__ w, int32_t C,
-                                                            unsigned long long* __restrict__ keys) {
+                                                            unsigned long long* __restrict__ keys,
+                                                            int32_t* __restrict__ flag) {
     const PairDesc d = pairs[blockIdx.y];
     const int32_t* wi = w + (int64_t)d.src * C;
     const int32_t* wk = w + (int64_t)d.dst * C;
     unsigned long long best = ~0ull;
+    bool bad = false;
     for (int a = blockIdx.x; a < C; a += gridDim.x) {
         const int32_t wa = wi[a];
         const gi32c Trow = (gi32c)(uintptr_t)d.T + (int64_t)a * C;
         for (int b = threadIdx.x; b < C; b += kThreads) {
-            const int32_t s = wa + Trow[b] + wk[b];
+            const long long s64 = (long long)wa + Trow[b] + wk[b];
+            const int32_t s = (int32_t)s64;
+            bad |= (s64 != (long long)s);
             const unsigned long long k = make_key(s, (uint32_t)a * (uint32_t)C + (uint32_t)b);
             best = k < best ? k : best;
         }
     }
+    if (bad && flag) atomicOr(flag, 1);
     block_min_to(best, &keys[blockIdx.y]);
 }
 
@@ -228,34 +248,38 @@ __global__ __launch_bounds__(kThreads) void single_min_kernel(const int32_t* __r
 __global__ __launch_bounds__(kThreads) void component_min_kernel(const CompDesc* __restrict__ comp,
                                                                  const int32_t* __restrict__ w, int32_t C,
                                                                  unsigned long long n_prefix,
-                                                                 unsigned long long* __restrict__ key) {
+                                                                 unsigned long long* __restrict__ key,
+                                                                 int32_t* __restrict__ flag) {
     __shared__ CompDesc d;
     for (int x = threadIdx.x; x < (int)(sizeof(CompDesc) / 4); x += kThreads)
         reinterpret_cast<int32_t*>(&d)[x] = reinterpret_cast<const int32_t*>(comp)[x];
     __syncthreads();
     const int K = d.K, ne = d.n_edges, last = K - 1;
     unsigned long long best = ~0ull;
+    bool bad = false;
     const unsigned long long stride = (unsigned long long)gridDim.x * kThreads;
     for (unsigned long long p = (unsigned long long)blockIdx.x * kThreads + threadIdx.x; p < n_prefix; p += stride) {
         int digit[kCompMaxNodes];
         unsigned long long r = p;
         for (int q = last - 1; q >= 0; --q) { digit[q] = (int)(r % (unsigned)C); r /= (unsigned)C; }
-        int32_t base = 0;
+        long long base = 0;
         for (int q = 0; q < last; ++q) base += w[(int64_t)d.node[q] * C + digit[q]];
         for (int x = 0; x < ne; ++x)
             if (d.src_pos[x] != last && d.dst_pos[x] != last)
                 base += ((gi32c)(uintptr_t)d.tab[x])[(int64_t)digit[d.src_pos[x]] * C + digit[d.dst_pos[x]]];
         const int32_t* wl = w + (int64_t)d.node[last] * C;
         for (int c = 0; c < C; ++c) {
-            int32_t t = base + wl[c];
+            long long t = base + wl[c];
             for (int x = 0; x < ne; ++x) {
                 if (d.src_pos[x] == last) t += ((gi32c)(uintptr_t)d.tab[x])[(int64_t)c * C + digit[d.dst_pos[x]]];
                 else if (d.dst_pos[x] == last) t += ((gi32c)(uintptr_t)d.tab[x])[(int64_t)digit[d.src_pos[x]] * C + c];
             }
-            const unsigned long long k = make_key(t, (uint32_t)(p * (unsigned)C + (unsigned)c));
+            bad |= (t != (long long)(int32_t)t);
+            const unsigned long long k = make_key((int32_t)t, (uint32_t)(p * (unsigned)C + (unsigned)c));
             best = k < best ? k : best;
         }
     }
+    if (bad && flag) atomicOr(flag, 1);
     block_min_to(best, key);
 }
 
@@ -266,7 +290,7 @@ __global__ __launch_bounds__(kUndoThreads) void back_substitute_kernel(
     const PairDesc* __restrict__ pairs, int32_t n_pairs, const int32_t* __restrict__ singles, int32_t n_singles,
     const CompDesc* __restrict__ comps, int32_t n_comps,
     const unsigned long long* __restrict__ keys, const UndoDesc* __restrict__ undo, int32_t n_undo, int32_t C,
-    int32_t n_nodes, int32_t* __restrict__ result) {
+    int32_t n_nodes, const int32_t* __restrict__ flag, int32_t* __restrict__ result) {
     __shared__ long long ssum[kUndoThreads / 64];
     int32_t* S = result + 2;
     long long cost = 0;
@@ -322,7 +346,7 @@ __global__ __launch_bounds__(kUndoThreads) void back_substitute_kernel(
         __syncthreads();
         hi = lo;
     }
-    (void)n_nodes;
+    if (threadIdx.x == 0) result[2 + n_nodes] = flag ? *flag : 0;
 }
 
 inline unsigned blocks_for(int64_t work_items, int64_t per_thread, unsigned cap) {
@@ -374,21 +398,21 @@ hipError_t launch_ranges(const int32_t* d_tables, int32_t n_tables, int64_t cell
 
 hipError_t launch_prepare_search(const int32_t* tc, const int32_t* ts, int32_t* w, int32_t n_nodes, int32_t C,
                                  int32_t* d_stats, int32_t n_pairs, int32_t w_pair0, unsigned long long* d_keys,
-                                 int32_t n_keys, hipStream_t stream) {
-    const int n_init = n_pairs > n_keys ? n_pairs : n_keys;
+                                 int32_t n_keys, int32_t* d_flag, hipStream_t stream) {
+    const int n_init = (n_pairs > n_keys ? n_pairs : n_keys) + 1;
     dim3 grid((unsigned)(n_nodes + (n_init + kThreads - 1) / kThreads));
     hipLaunchKernelGGL(prepare_search_kernel, grid, dim3(kThreads), 0, stream, tc, ts, w, n_nodes, C, d_stats, n_pairs,
-                       w_pair0, d_keys, n_keys);
+                       w_pair0, d_keys, n_keys, d_flag);
     return hipGetLastError();
 }
 
 hipError_t launch_pair_min(const PairDesc* d_pairs, int32_t n_pairs, const int32_t* d_w, int32_t C,
-                           unsigned long long* d_keys, hipStream_t stream) {
+                           unsigned long long* d_keys, int32_t* d_flag, hipStream_t stream) {
     for (int32_t t0 = 0; t0 < n_pairs; t0 += 65535) {
         const int32_t n = (n_pairs - t0) < 65535 ? (n_pairs - t0) : 65535;
         const unsigned rows = (unsigned)C < 2048u ? (unsigned)C : 2048u;
         dim3 grid(rows, (unsigned)n);
-        hipLaunchKernelGGL(pair_min_kernel, grid, dim3(kThreads), 0, stream, d_pairs + t0, d_w, C, d_keys + t0);
+        hipLaunchKernelGGL(pair_min_kernel, grid, dim3(kThreads), 0, stream, d_pairs + t0, d_w, C, d_keys + t0, d_flag);
     }
     return hipGetLastError();
 }
@@ -404,12 +428,12 @@ hipError_t launch_single_min(const int32_t* d_singles, int32_t n_singles, const 
 }
 
 hipError_t launch_component_min(const CompDesc* d_comp, int32_t K, const int32_t* d_w, int32_t C,
-                                unsigned long long* d_key, hipStream_t stream) {
+                                unsigned long long* d_key, int32_t* d_flag, hipStream_t stream) {
     unsigned long long n_prefix = 1;
     for (int q = 0; q + 1 < K; ++q) n_prefix *= (unsigned long long)C;
     unsigned long long blocks = (n_prefix + kThreads - 1) / kThreads;
     if (blocks > 65536) blocks = 65536;
-    hipLaunchKernelGGL(component_min_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, d_comp, d_w, C, n_prefix, d_key);
+    hipLaunchKernelGGL(component_min_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, d_comp, d_w, C, n_prefix, d_key, d_flag);
     return hipGetLastError();
 }
 
@@ -417,9 +441,9 @@ hipError_t launch_back_substitute(const PairDesc* d_pairs, int32_t n_pairs, cons
                                   int32_t n_singles, const CompDesc* d_comps, int32_t n_comps,
                                   const unsigned long long* d_keys,
                                   const UndoDesc* d_undo, int32_t n_undo, int32_t C, int32_t n_nodes,
-                                  int32_t* d_result, hipStream_t stream) {
+                                  const int32_t* d_flag, int32_t* d_result, hipStream_t stream) {
     hipLaunchKernelGGL(back_substitute_kernel, dim3(1), dim3(kUndoThreads), 0, stream, d_pairs, n_pairs, d_singles,
-                       n_singles, d_comps, n_comps, d_keys, d_undo, n_undo, C, n_nodes, d_result);
+                       n_singles, d_comps, n_comps, d_keys, d_undo, n_undo, C, n_nodes, d_flag, d_result);
     return hipGetLastError();
 }
 

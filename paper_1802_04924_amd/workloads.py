@@ -200,6 +200,37 @@ def alexnet_layers(batch: int = 256) -> np.ndarray:
     return np.asarray(layers, dtype=np.int32)
 
 
+def vgg16_layers(batch: int = 64) -> np.ndarray:
+    """21-layer VGG-16-shaped chain (13 3x3 convolutions, 5 poolings, 3 fully connected layers,
+    224x224 input), the third network of the paper's search-time table."""
+    def conv(cin, hin, cout):
+        return (KIND_CONV, batch, cin, hin, hin, cout, hin, hin, 3, 3, 1, 1, 1, 1)
+
+    def pool(c, hin):
+        return (KIND_POOL, batch, c, hin, hin, c, hin // 2, hin // 2, 2, 2, 2, 2, 0, 0)
+
+    def fc(cin, hin, cout):
+        return (KIND_FC, batch, cin, hin, hin, cout, 1, 1, hin, hin, 1, 1, 0, 0)
+
+    layers, c, h = [], 3, 224
+    for width, reps in ((64, 2), (128, 2), (256, 3), (512, 3), (512, 3)):
+        for _ in range(reps):
+            layers.append(conv(c, h, width))
+            c = width
+        layers.append(pool(c, h))
+        h //= 2
+    layers += [fc(512, 7, 4096), fc(4096, 1, 4096), fc(4096, 1, 1000)]
+    return np.asarray(layers, dtype=np.int32)
+
+
+def vgg16_problem(batch: int = 64):
+    """Descriptors of the VGG-16-shaped chain (tables come from the cost model)."""
+    layers = vgg16_layers(batch)
+    return {"name": "vgg16_C256", "layers": layers, "edges": chain_edges(len(layers)),
+            "configs": config_table(16, 256), "machine": machine(), "C": 256,
+            "n_nodes": len(layers), "schedule": SCHEDULE_ROUNDS}
+
+
 def config_table(n_devices: int = 16, n_rows: int = 256) -> np.ndarray:
     """Configuration enumeration as int32 [n_rows][6] (CONFIG_FIELDS).
 

@@ -292,6 +292,34 @@ def test_search_enumerates_residual_components(ctx, name, C, hi):
         run_search(ctx, p)
 
 
+def test_search_beyond_the_provable_bounds(ctx):
+    # worst-case bounds grow by max t_x per elimination and leave int32 after ~16 steps here, while
+    # the minima stay small: the search must neither refuse nor lose exactness
+    p = wl.chain_problem(40, 48, 3, tc_range=(0, 1 << 20), ts_range=(0, 1 << 20), tx_range=(0, 1 << 27))
+    for schedule in (wl.SCHEDULE_ROUNDS, wl.SCHEDULE_LEFT_FOLD):
+        run_search(ctx, p, schedule)
+    p = wl.forkjoin_problem(3, 40, 4, lo=0, hi=1 << 27)
+    run_search(ctx, p)
+
+
+def test_search_overflow_found_on_the_device(ctx):
+    from paper_1802_04924_amd import LwpError
+    # parallel edges whose sum leaves int32
+    edges = np.array([[0, 1], [0, 1], [0, 1], [1, 2]], np.int32)
+    tc, ts, tx = wl.random_tables(3, edges, 8, 1, (0, 5), (0, 5), (1 << 30, (1 << 30) + 9))
+    with pytest.raises(LwpError) as e:
+        ctx.search_graph(3, edges, 8, dev(tc), dev(ts), dev(tx))
+    assert e.value.code == -4
+    with pytest.raises(oracle.OracleError):
+        oracle.search(3, edges, 8, tc, ts, tx)
+    # residual pair whose sum leaves int32
+    edges = np.array([[0, 1]], np.int32)
+    tc, ts, tx = wl.random_tables(2, edges, 8, 1, (1 << 29, (1 << 29) + 9), (0, 5), (1 << 30, (1 << 30) + 9))
+    with pytest.raises(LwpError) as e:
+        ctx.search_graph(2, edges, 8, dev(tc), dev(ts), dev(tx))
+    assert e.value.code == -4
+
+
 def test_search_errors(ctx):
     from paper_1802_04924_amd import LwpError
     edges = np.array([[0, 1], [0, 2], [0, 3]], np.int32)
@@ -319,6 +347,43 @@ def test_build_cost_tables_alexnet_and_search(ctx):
     ref = oracle.search(p["n_nodes"], p["edges"], p["C"], rtc, rts, rtx, p["schedule"])
     assert cost == ref["cost"] and np.array_equal(S, ref["strategy"])
     assert oracle.strategy_cost(p["n_nodes"], p["edges"], p["C"], rtc, rts, rtx, S) == cost
+
+
+def test_vgg16_tables_and_search(ctx):
+    # second network shape through the cost model: 21-layer chain, tables built on the GPU
+    p = wl.vgg16_problem()
+    assert p["n_nodes"] == 21
+    tc, ts, tx = ctx.build_cost_tables(p["layers"], p["edges"], p["configs"], p["machine"])
+    rtc, rts, rtx = oracle.build_cost_tables(p["layers"], p["edges"], p["configs"], p["machine"])
+    assert np.array_equal(tc.cpu().numpy(), rtc) and np.array_equal(ts.cpu().numpy(), rts)
+    assert np.array_equal(tx.cpu().numpy(), rtx)
+    ref = oracle.search(21, p["edges"], 256, rtc, rts, rtx)
+    for undo in (0, 1):
+        cost, S = ctx.search_graph(21, p["edges"], 256, tc, ts, tx, p["schedule"], undo)
+        assert cost == ref["cost"] and np.array_equal(S, ref["strategy"])
+    # every chosen configuration is one the layer can actually use
+    assert (rtc[np.arange(21), S] < p["machine"]["invalid_cost"]).all()
+
+
+def test_search_on_a_side_stream(ctx):
+    # the context follows the stream it was created with; results must not depend on the default stream
+    import torch
+    from paper_1802_04924_amd import Context
+    p = wl.forkjoin_problem(2, 96, 8)
+    ref = oracle.search(p["n_nodes"], p["edges"], p["C"], p["tc"], p["ts"], p["tx"])
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        d_tc, d_ts, d_tx = dev(p["tc"]), dev(p["ts"]), dev(p["tx"])
+        with Context(0, stream=side) as c2:
+            for _ in range(3):
+                cost, S = c2.search_graph(p["n_nodes"], p["edges"], p["C"], d_tc, d_ts, d_tx)
+                assert cost == ref["cost"] and np.array_equal(S, ref["strategy"])
+            A, w, B = wl.batched_products(2, 100, 300, 90, 4)
+            out, arg = c2.eliminate_node(dev(A), dev(w), dev(B))
+            c2.synchronize()
+            ro, ra = oracle.minplus_argmin(A[1], w[1], B[1])
+            assert np.array_equal(out[1].cpu().numpy(), ro) and np.array_equal(arg[1].cpu().numpy(), ra)
+    side.synchronize()
 
 
 def test_build_cost_tables_odd_shapes(ctx):
