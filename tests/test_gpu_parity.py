@@ -298,7 +298,7 @@ def test_search_beyond_the_provable_bounds(ctx):
     p = wl.chain_problem(40, 48, 3, tc_range=(0, 1 << 20), ts_range=(0, 1 << 20), tx_range=(0, 1 << 27))
     for schedule in (wl.SCHEDULE_ROUNDS, wl.SCHEDULE_LEFT_FOLD):
         run_search(ctx, p, schedule)
-    p = wl.forkjoin_problem(3, 40, 4, lo=0, hi=1 << 27)
+    p = wl.forkjoin_problem(3, 40, 4, lo=0, hi=1 << 25)
     run_search(ctx, p)
 
 
