@@ -528,12 +528,20 @@ lwp_status lwp_search_graph_ex(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, c
     int32_t* d_flag = d_head;      // set by any kernel that finds a sum outside int32
     LWP_HIP(ctx, launch_prepare_search(d_tc, d_ts, d_w, n_nodes, C, d_stats, W.n_ranges, rng_w0, d_keys, n_comp, d_flag, st));
     LWP_HIP(ctx, launch_ranges(d_tx, n_edges, CC, d_stats, st));
+    // Stored argmin tables need a kernel variant chosen from value ranges, so the ranges of the inputs
+    // are read back (the one mid-search synchronisation).  With recomputed undo every elimination is
+    // value-only (no range condition) and overflow is judged on the device from measured ranges, so
+    // nothing is read back and the host assumes full int32 ranges.
     int32_t* h_head = reinterpret_cast<int32_t*>(ctx->pin + pin_head);
-    LWP_HIP(ctx, hipMemcpyAsync(h_head, d_head, head_in_bytes, hipMemcpyDeviceToHost, st));
-    LWP_HIP(ctx, hipStreamSynchronize(st));
-    const int32_t* stats = h_head + 2;
-    for (int32_t v = 0; v < n_nodes; ++v)
-        if (stats[2 * (rng_w0 + v)] > stats[2 * (rng_w0 + v) + 1]) return fail(ctx, LWP_E_OVERFLOW, "t_c + t_s leaves int32");
+    int32_t* stats = h_head + 2;
+    if (stored) {
+        LWP_HIP(ctx, hipMemcpyAsync(h_head, d_head, head_in_bytes, hipMemcpyDeviceToHost, st));
+        LWP_HIP(ctx, hipStreamSynchronize(st));
+        for (int32_t v = 0; v < n_nodes; ++v)
+            if (stats[2 * (rng_w0 + v)] > stats[2 * (rng_w0 + v) + 1]) return fail(ctx, LWP_E_OVERFLOW, "t_c + t_s leaves int32");
+    } else {
+        for (int32_t t2 = 0; t2 < n_edges + n_nodes; ++t2) { stats[2 * t2] = (int32_t)kI32Min; stats[2 * t2 + 1] = (int32_t)kI32Max; }
+    }
 
     // 2. propagate ranges through the plan: every sum any kernel forms must fit int32.  Descriptors
     //    are written straight into the pinned mirror of the device block.
@@ -596,6 +604,7 @@ lwp_status lwp_search_graph_ex(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, c
             d.loB = (int32_t)rB.lo; d.hiB = (int32_t)rB.hi;
             d.rngA = d_stats + 2 * (int64_t)erng[s.e1];
             d.rngB = d_stats + 2 * (int64_t)erng[s.e2];
+            d.rngW = d_stats + 2 * (int64_t)(rng_w0 + s.j);
             d.rngOut = d_stats + 2 * (int64_t)(rng_node0 + (int32_t)ni);
             nd[ni] = d;
             nd_spread[ni] = proven ? keyed_spread(rA, rw, rB) : (int64_t)1 << 62;   // unproven: no packed keys
@@ -693,7 +702,7 @@ lwp_status lwp_search_graph_ex(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, c
                                           d_keys + plan.pairs.size() + plan.singles.size() + q, d_flag, st));
     LWP_HIP(ctx, launch_back_substitute(d_pd, (int32_t)plan.pairs.size(), d_singles, (int32_t)plan.singles.size(),
                                         d_cd, (int32_t)plan.comps.size(), d_keys, d_ud, plan.n_node_steps, C, n_nodes,
-                                        d_flag, d_result, st));
+                                        d_flag, d_stats + 2 * (int64_t)rng_w0, d_result, st));
     int32_t* result = reinterpret_cast<int32_t*>(ctx->pin + pin_result);
     LWP_HIP(ctx, hipMemcpyAsync(result, d_result, (3 + (size_t)n_nodes) * sizeof(int32_t), hipMemcpyDeviceToHost, st));
     LWP_HIP(ctx, hipStreamSynchronize(st));

@@ -11,7 +11,7 @@ namespace lwp {
 // One product of a batched launch.  [loX, hiX] are ranges the caller guarantees for the entries
 // of A, w and B; rngA / rngB optionally point at a measured {min, max} pair in device memory
 // (written by the launch that produced the table, earlier on the same stream) and can only
-// tighten them.  rngOut, if set, receives {min, max} of `out` by atomics and must have been
+// tighten them; rngW likewise for w.  rngOut, if set, receives {min, max} of `out` by atomics and must have been
 // initialised to {INT32_MAX, INT32_MIN}.  The packed-key variant needs
 //   min(hiA + hiW - loA - loW, (hiA - loA) + (hiB - loB) + 1) + (hiB - loB) <= kKeyedMaxSpread*.
 struct NodeDesc {
@@ -23,10 +23,12 @@ struct NodeDesc {
     int32_t loA, hiA, loW, hiW, loB, hiB;
     const int32_t* rngA;
     const int32_t* rngB;
+    const int32_t* rngW;
     int32_t* rngOut;
     int32_t* flag;     // optional: OR-ed with 1 if max A + max w + max B (measured) may leave int32
+    int64_t pad;
 };
-static_assert(sizeof(NodeDesc) == 96, "descriptor layout");
+static_assert(sizeof(NodeDesc) == 112, "descriptor layout");
 
 struct NodeArgs {
     const NodeDesc* descs;   // device array [batch], or null for strided addressing
@@ -118,11 +120,13 @@ hipError_t launch_component_min(const CompDesc* d_comp, int32_t K, const int32_t
 // Decodes the component minima (keys: pairs, then singles, then enumerated components), then
 // walks the undo list backwards (entries of one round are independent).
 // result[0] = total cost low word, result[1] = high word, result[2..2+n_nodes) = strategy,
-// result[2+n_nodes] = *d_flag (0 if d_flag is null).
+// result[2+n_nodes] = *d_flag (0 if d_flag is null), OR 1 if one of the n_nodes stats pairs starting
+// at d_wstats is the impossible {INT32_MAX, INT32_MIN} (a row of t_c + t_s left int32).
 hipError_t launch_back_substitute(const PairDesc* d_pairs, int32_t n_pairs, const int32_t* d_singles,
                                   int32_t n_singles, const CompDesc* d_comps, int32_t n_comps,
                                   const unsigned long long* d_keys,
                                   const UndoDesc* d_undo, int32_t n_undo, int32_t C, int32_t n_nodes,
-                                  const int32_t* d_flag, int32_t* d_result, hipStream_t stream);
+                                  const int32_t* d_flag, const int32_t* d_wstats, int32_t* d_result,
+                                  hipStream_t stream);
 
 }  // namespace lwp

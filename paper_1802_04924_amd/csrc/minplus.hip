@@ -106,11 +106,12 @@ __global__ __launch_bounds__(NT, MODE == kModePlain ? 1 : 2) void minplus_kernel
 
     // ---- the sums must fit int32: checked against the measured ranges of the operands ----
     if (d.flag) {
-        long long loA = d.loA, hiA = d.hiA, loB = d.loB, hiB = d.hiB;
+        long long loA = d.loA, hiA = d.hiA, loB = d.loB, hiB = d.hiB, loW = d.loW, hiW = d.hiW;
         if (d.rngA) { const gcptr r = (gcptr)(uintptr_t)d.rngA; loA = max(loA, (long long)r[0]); hiA = min(hiA, (long long)r[1]); }
         if (d.rngB) { const gcptr r = (gcptr)(uintptr_t)d.rngB; loB = max(loB, (long long)r[0]); hiB = min(hiB, (long long)r[1]); }
-        const long long hi = hiA + d.hiW + hiB, lo = loA + d.loW + loB;
-        const long long hi2 = hiA + d.hiW, lo2 = loA + d.loW;
+        if (d.rngW) { const gcptr r = (gcptr)(uintptr_t)d.rngW; loW = max(loW, (long long)r[0]); hiW = min(hiW, (long long)r[1]); }
+        const long long hi = hiA + hiW + hiB, lo = loA + loW + loB;
+        const long long hi2 = hiA + hiW, lo2 = loA + loW;
         if ((hi > 2147483647ll || lo < -2147483648ll || hi2 > 2147483647ll || lo2 < -2147483648ll) && threadIdx.x == 0)
             atomicOr(d.flag, 1);
     }

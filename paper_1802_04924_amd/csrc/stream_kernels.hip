@@ -290,7 +290,8 @@ __global__ __launch_bounds__(kUndoThreads) void back_substitute_kernel(
     const PairDesc* __restrict__ pairs, int32_t n_pairs, const int32_t* __restrict__ singles, int32_t n_singles,
     const CompDesc* __restrict__ comps, int32_t n_comps,
     const unsigned long long* __restrict__ keys, const UndoDesc* __restrict__ undo, int32_t n_undo, int32_t C,
-    int32_t n_nodes, const int32_t* __restrict__ flag, int32_t* __restrict__ result) {
+    int32_t n_nodes, const int32_t* __restrict__ flag, const int32_t* __restrict__ wstats,
+    int32_t* __restrict__ result) {
     __shared__ long long ssum[kUndoThreads / 64];
     int32_t* S = result + 2;
     long long cost = 0;
@@ -346,7 +347,15 @@ __global__ __launch_bounds__(kUndoThreads) void back_substitute_kernel(
         __syncthreads();
         hi = lo;
     }
-    if (threadIdx.x == 0) result[2 + n_nodes] = flag ? *flag : 0;
+    // a row of t_c + t_s that left int32 was recorded as the impossible range {INT32_MAX, INT32_MIN}
+    __shared__ int wbad;
+    if (threadIdx.x == 0) wbad = 0;
+    __syncthreads();
+    if (wstats)
+        for (int v = threadIdx.x; v < n_nodes; v += kUndoThreads)
+            if (wstats[2 * v] > wstats[2 * v + 1]) wbad = 1;
+    __syncthreads();
+    if (threadIdx.x == 0) result[2 + n_nodes] = (flag ? *flag : 0) | wbad;
 }
 
 inline unsigned blocks_for(int64_t work_items, int64_t per_thread, unsigned cap) {
@@ -441,9 +450,10 @@ hipError_t launch_back_substitute(const PairDesc* d_pairs, int32_t n_pairs, cons
                                   int32_t n_singles, const CompDesc* d_comps, int32_t n_comps,
                                   const unsigned long long* d_keys,
                                   const UndoDesc* d_undo, int32_t n_undo, int32_t C, int32_t n_nodes,
-                                  const int32_t* d_flag, int32_t* d_result, hipStream_t stream) {
+                                  const int32_t* d_flag, const int32_t* d_wstats, int32_t* d_result,
+                                  hipStream_t stream) {
     hipLaunchKernelGGL(back_substitute_kernel, dim3(1), dim3(kUndoThreads), 0, stream, d_pairs, n_pairs, d_singles,
-                       n_singles, d_comps, n_comps, d_keys, d_undo, n_undo, C, n_nodes, d_flag, d_result);
+                       n_singles, d_comps, n_comps, d_keys, d_undo, n_undo, C, n_nodes, d_flag, d_wstats, d_result);
     return hipGetLastError();
 }
 
