@@ -108,7 +108,7 @@ def final_pair(wi, T, wk):
     wi, T, wk = _c(wi), _c(T), _c(wk)
     cost = ctypes.c_int64(0)
     a, b = ctypes.c_int32(0), ctypes.c_int32(0)
-    rc = lib.orc_final_pair(T.shape[0], _p(wi), _p(T), _p(wk), ctypes.byref(cost),
+    rc = lib.orc_final_pair(T.shape[0], T.shape[1], _p(wi), _p(T), _p(wk), ctypes.byref(cost),
                             ctypes.byref(a), ctypes.byref(b))
     if rc:
         raise OracleError(rc, "final_pair")
@@ -136,6 +136,43 @@ def search(n_nodes, edges, C, tc, ts, tx, schedule=SCHEDULE_ROUNDS):
         raise OracleError(rc, "search")
     return {"cost": cost.value, "strategy": S, "steps": steps[:n_steps.value],
             "n_rounds": n_rounds.value}
+
+
+def _ragged_args(n_nodes, edges, Cn, tc, ts, tx):
+    edges, Cn = _c(edges).reshape(-1, 2), _c(Cn).reshape(-1)
+    tc, ts, tx = _c(tc).reshape(-1), _c(ts).reshape(-1), _c(tx).reshape(-1)
+    assert len(Cn) == n_nodes and tc.size == int(Cn.sum()) and ts.size == tc.size
+    assert tx.size == int(sum(int(Cn[i]) * int(Cn[j]) for i, j in edges))
+    return edges, Cn, tc, ts, tx
+
+
+def strategy_cost_ragged(n_nodes, edges, Cn, tc, ts, tx, S) -> int:
+    """Eq. 1 with Cn[l] configurations for node l; tc, ts, tx are the concatenated rows / tables."""
+    lib = _load()
+    edges, Cn, tc, ts, tx = _ragged_args(n_nodes, edges, Cn, tc, ts, tx)
+    S = _c(S)
+    out = ctypes.c_int64(0)
+    rc = lib.orc_strategy_cost_ragged(n_nodes, len(edges), _p(edges), _p(Cn), _p(tc), _p(ts), _p(tx), _p(S), ctypes.byref(out))
+    if rc:
+        raise OracleError(rc, "strategy_cost_ragged")
+    return out.value
+
+
+def search_ragged(n_nodes, edges, Cn, tc, ts, tx, schedule=SCHEDULE_ROUNDS):
+    """Alg. 1 with per-node configuration counts.  Returns dict(cost, strategy, steps, n_rounds)."""
+    lib = _load()
+    edges, Cn, tc, ts, tx = _ragged_args(n_nodes, edges, Cn, tc, ts, tx)
+    E = len(edges)
+    S = np.empty(n_nodes, np.int32)
+    steps = np.zeros(max(E, 1), STEP_DTYPE)
+    cost = ctypes.c_int64(0)
+    n_steps, n_rounds = ctypes.c_int32(0), ctypes.c_int32(0)
+    rc = lib.orc_search_ragged(n_nodes, E, _p(edges), _p(Cn), _p(tc), _p(ts), _p(tx), int(schedule),
+                               ctypes.byref(cost), _p(S), steps.ctypes.data_as(ctypes.c_void_p),
+                               ctypes.byref(n_steps), ctypes.byref(n_rounds))
+    if rc:
+        raise OracleError(rc, "search_ragged")
+    return {"cost": cost.value, "strategy": S, "steps": steps[:n_steps.value], "n_rounds": n_rounds.value}
 
 
 def build_cost_tables(layers, edges, configs, machine):

@@ -37,19 +37,24 @@
 static int fits_i32(int64_t v) { return v >= INT32_MIN && v <= INT32_MAX; }
 
 /* Eq. 1: t_o = sum_l (t_c(l,S_l) + t_s(l,S_l)) + sum_{e=(i,j)} t_x(e,S_i,S_j).
- * tc, ts: [N][C]; tx: [E][C][C] indexed [edge][src cfg][dst cfg]; result in 64 bits. */
-int orc_strategy_cost(int n_nodes, int n_edges, const int32_t *edges, int C,
-                      const int32_t *tc, const int32_t *ts, const int32_t *tx,
-                      const int32_t *S, int64_t *out_cost)
+ * Node l has Cn[l] configurations.  tc, ts: the rows of all nodes one after another; tx: the
+ * tables of all edges one after another, table e is [Cn[src]][Cn[dst]]; result in 64 bits. */
+int orc_strategy_cost_ragged(int n_nodes, int n_edges, const int32_t *edges, const int32_t *Cn,
+                             const int32_t *tc, const int32_t *ts, const int32_t *tx,
+                             const int32_t *S, int64_t *out_cost)
 {
     int64_t t = 0;
+    size_t off = 0;
     for (int l = 0; l < n_nodes; ++l) {
-        if (S[l] < 0 || S[l] >= C) return ORC_E_INVAL;
-        t += (int64_t)tc[(size_t)l * C + S[l]] + (int64_t)ts[(size_t)l * C + S[l]];
+        if (S[l] < 0 || S[l] >= Cn[l]) return ORC_E_INVAL;
+        t += (int64_t)tc[off + S[l]] + (int64_t)ts[off + S[l]];
+        off += (size_t)Cn[l];
     }
+    off = 0;
     for (int e = 0; e < n_edges; ++e) {
         int i = edges[2 * e], j = edges[2 * e + 1];
-        t += tx[((size_t)e * C + S[i]) * C + S[j]];
+        t += tx[off + (size_t)S[i] * Cn[j] + S[j]];
+        off += (size_t)Cn[i] * Cn[j];
     }
     *out_cost = t;
     return ORC_OK;
@@ -98,15 +103,15 @@ int orc_edge_sum(int Ci, int Cj, const int32_t *e1, const int32_t *e2, int32_t *
 }
 
 /* Residual pair (Alg. 1, enumeration of the final graph with K = 2):
- *   min_{a,b} wi[a] + T[a][b] + wk[b], lowest flat index a*C+b among equals. */
-int orc_final_pair(int C, const int32_t *wi, const int32_t *T, const int32_t *wk,
+ *   min_{a,b} wi[a] + T[a][b] + wk[b] over T [Ci][Ck], lowest flat index a*Ck+b among equals. */
+int orc_final_pair(int Ci, int Ck, const int32_t *wi, const int32_t *T, const int32_t *wk,
                    int64_t *out_cost, int32_t *out_a, int32_t *out_b)
 {
     int64_t best = 0;
     int ba = -1, bb = -1, overflow = 0;
-    for (int a = 0; a < C; ++a)
-        for (int b = 0; b < C; ++b) {
-            int64_t s = (int64_t)wi[a] + (int64_t)T[(size_t)a * C + b] + (int64_t)wk[b];
+    for (int a = 0; a < Ci; ++a)
+        for (int b = 0; b < Ck; ++b) {
+            int64_t s = (int64_t)wi[a] + (int64_t)T[(size_t)a * Ck + b] + (int64_t)wk[b];
             if (!fits_i32(s)) overflow = 1;
             if (ba < 0 || s < best) { best = s; ba = a; bb = b; }
         }
@@ -174,14 +179,16 @@ static void sort_ids(int *ids, int n, const live_edge *E)
  * steps (optional, room for n_edges entries) receives the log; n_steps and
  * n_rounds (optional) its length and the number of rounds that did work.
  */
-int orc_search(int n_nodes, int n_edges, const int32_t *edges, int C,
-               const int32_t *tc, const int32_t *ts, const int32_t *tx, int schedule,
-               int64_t *out_cost, int32_t *S, orc_step *steps, int32_t *n_steps, int32_t *n_rounds)
+int orc_search_ragged(int n_nodes, int n_edges, const int32_t *edges, const int32_t *Cn,
+                      const int32_t *tc, const int32_t *ts, const int32_t *tx, int schedule,
+                      int64_t *out_cost, int32_t *S, orc_step *steps, int32_t *n_steps, int32_t *n_rounds)
 {
-    if (n_nodes <= 0 || n_edges < 0 || C <= 0) return ORC_E_INVAL;
+    if (n_nodes <= 0 || n_edges < 0) return ORC_E_INVAL;
     int rc = ORC_OK;
-    size_t CC = (size_t)C * C;
-    int32_t *w = (int32_t *)malloc((size_t)n_nodes * C * sizeof(int32_t));
+    size_t total_w = 0;
+    for (int l = 0; l < n_nodes; ++l) { if (Cn[l] <= 0) return ORC_E_INVAL; total_w += (size_t)Cn[l]; }
+    size_t *woff = (size_t *)malloc(sizeof(size_t) * (size_t)n_nodes);   /* start of node l's row of w */
+    int32_t *w = (int32_t *)malloc(total_w * sizeof(int32_t));
     live_edge *E = (live_edge *)calloc((size_t)(n_edges > 0 ? n_edges : 1), sizeof(live_edge));
     orc_step *log = (orc_step *)calloc((size_t)(n_edges > 0 ? n_edges : 1), sizeof(orc_step));
     int32_t **argtab = (int32_t **)calloc((size_t)(n_edges > 0 ? n_edges : 1), sizeof(int32_t *));
@@ -191,22 +198,27 @@ int orc_search(int n_nodes, int n_edges, const int32_t *edges, int C,
     int *ine = (int *)malloc(sizeof(int) * n_nodes), *oute = (int *)malloc(sizeof(int) * n_nodes);
     int *ids = (int *)malloc(sizeof(int) * (n_edges > 0 ? n_edges : 1));
     int nlog = 0, rounds = 0;
-    if (!w || !E || !log || !argtab || !dead || !sel || !indeg || !outdeg || !ine || !oute || !ids) {
+    if (!woff || !w || !E || !log || !argtab || !dead || !sel || !indeg || !outdeg || !ine || !oute || !ids) {
         rc = ORC_E_NOMEM; goto done;
     }
 
     /* w = t_c + t_s: Eq. 1 and Eq. 2 only ever use the sum. */
-    for (size_t t = 0; t < (size_t)n_nodes * C; ++t) {
+    for (size_t t = 0; t < total_w; ++t) {
         int64_t s = (int64_t)tc[t] + (int64_t)ts[t];
         if (!fits_i32(s)) { rc = ORC_E_OVERFLOW; goto done; }
         w[t] = (int32_t)s;
     }
-    for (int e = 0; e < n_edges; ++e) {
-        E[e].src = edges[2 * e]; E[e].dst = edges[2 * e + 1];
-        if (E[e].src < 0 || E[e].src >= n_nodes || E[e].dst < 0 || E[e].dst >= n_nodes ||
-            E[e].src == E[e].dst) { rc = ORC_E_INVAL; goto done; }
-        E[e].tab = (int32_t *)(tx + (size_t)e * CC);
-        E[e].owned = 0; E[e].alive = 1;
+    { size_t o = 0; for (int l = 0; l < n_nodes; ++l) { woff[l] = o; o += (size_t)Cn[l]; } }
+    {
+        size_t o = 0;       /* table e is [Cn[src]][Cn[dst]], tables one after another */
+        for (int e = 0; e < n_edges; ++e) {
+            E[e].src = edges[2 * e]; E[e].dst = edges[2 * e + 1];
+            if (E[e].src < 0 || E[e].src >= n_nodes || E[e].dst < 0 || E[e].dst >= n_nodes ||
+                E[e].src == E[e].dst) { rc = ORC_E_INVAL; goto done; }
+            E[e].tab = (int32_t *)(tx + o);
+            E[e].owned = 0; E[e].alive = 1;
+            o += (size_t)Cn[E[e].src] * Cn[E[e].dst];
+        }
     }
 
     for (;;) {
@@ -221,9 +233,9 @@ int orc_search(int n_nodes, int n_edges, const int32_t *edges, int C,
             int keep = ids[x];
             for (int z = x + 1; z < y; ++z) {
                 int other = ids[z];
-                int32_t *sum = (int32_t *)malloc(CC * sizeof(int32_t));
+                int32_t *sum = (int32_t *)malloc((size_t)Cn[E[keep].src] * Cn[E[keep].dst] * sizeof(int32_t));
                 if (!sum) { rc = ORC_E_NOMEM; goto done; }
-                int r = orc_edge_sum(C, C, E[keep].tab, E[other].tab, sum);
+                int r = orc_edge_sum(Cn[E[keep].src], Cn[E[keep].dst], E[keep].tab, E[other].tab, sum);
                 if (E[keep].owned) free(E[keep].tab);
                 if (E[other].owned) free(E[other].tab);
                 E[keep].tab = sum; E[keep].owned = 1;
@@ -251,10 +263,10 @@ int orc_search(int n_nodes, int n_edges, const int32_t *edges, int C,
             if (!sel[j]) continue;
             int e1 = ine[j], e2 = oute[j];
             int i = E[e1].src, k = E[e2].dst;
-            int32_t *nt = (int32_t *)malloc(CC * sizeof(int32_t));
-            int32_t *na = (int32_t *)malloc(CC * sizeof(int32_t));
+            int32_t *nt = (int32_t *)malloc((size_t)Cn[i] * Cn[k] * sizeof(int32_t));
+            int32_t *na = (int32_t *)malloc((size_t)Cn[i] * Cn[k] * sizeof(int32_t));
             if (!nt || !na) { free(nt); free(na); rc = ORC_E_NOMEM; goto done; }
-            int r = orc_minplus_argmin(C, C, C, E[e1].tab, w + (size_t)j * C, E[e2].tab, nt, na);
+            int r = orc_minplus_argmin(Cn[i], Cn[j], Cn[k], E[e1].tab, w + woff[j], E[e2].tab, nt, na);
             if (E[e1].owned) free(E[e1].tab);
             if (E[e2].owned) free(E[e2].tab);
             E[e1].tab = nt; E[e1].owned = 1; E[e1].dst = k;
@@ -292,16 +304,16 @@ int orc_search(int n_nodes, int n_edges, const int32_t *edges, int C,
             int64_t c = 0;
             if (K == 1) {
                 int l = ine[0], best = 0;
-                for (int q = 1; q < C; ++q) if (w[(size_t)l * C + q] < w[(size_t)l * C + best]) best = q;
-                c = w[(size_t)l * C + best]; S[l] = best;
+                for (int q = 1; q < Cn[l]; ++q) if (w[woff[l] + q] < w[woff[l] + best]) best = q;
+                c = w[woff[l] + best]; S[l] = best;
             } else if (K == 2 && ne == 1) {
                 int e = oute[0]; int32_t a, b;
-                int r = orc_final_pair(C, w + (size_t)E[e].src * C, E[e].tab, w + (size_t)E[e].dst * C, &c, &a, &b);
+                int r = orc_final_pair(Cn[E[e].src], Cn[E[e].dst], w + woff[E[e].src], E[e].tab, w + woff[E[e].dst], &c, &a, &b);
                 if (r != ORC_OK) { rc = r; goto done; }
                 S[E[e].src] = a; S[E[e].dst] = b;
             } else {
                 double n_assign = 1.0;
-                for (int q = 0; q < K; ++q) n_assign *= C;
+                for (int q = 0; q < K && q < 16; ++q) n_assign *= Cn[ine[q]];
                 if (n_assign > (double)(1 << 26) || K > 16) { rc = ORC_E_NOT_REDUCIBLE; goto done; }
                 int digit[16], bestd[16], pos_of_src[64], pos_of_dst[64];
                 if (ne > 64) { rc = ORC_E_NOT_REDUCIBLE; goto done; }
@@ -314,13 +326,13 @@ int orc_search(int n_nodes, int n_edges, const int32_t *edges, int C,
                 int have = 0;
                 for (;;) {
                     int64_t t = 0;
-                    for (int q = 0; q < K; ++q) t += w[(size_t)ine[q] * C + digit[q]];
+                    for (int q = 0; q < K; ++q) t += w[woff[ine[q]] + digit[q]];
                     for (int x = 0; x < ne; ++x)
-                        t += E[oute[x]].tab[(size_t)digit[pos_of_src[x]] * C + digit[pos_of_dst[x]]];
+                        t += E[oute[x]].tab[(size_t)digit[pos_of_src[x]] * Cn[E[oute[x]].dst] + digit[pos_of_dst[x]]];
                     if (!fits_i32(t)) { rc = ORC_E_OVERFLOW; goto done; }
                     if (!have || t < c) { c = t; have = 1; for (int q = 0; q < K; ++q) bestd[q] = digit[q]; }
                     int q = K - 1;                               /* odometer: last node fastest */
-                    while (q >= 0 && ++digit[q] == C) digit[q--] = 0;
+                    while (q >= 0 && ++digit[q] == Cn[ine[q]]) digit[q--] = 0;
                     if (q < 0) break;
                 }
                 for (int q = 0; q < K; ++q) S[ine[q]] = bestd[q];
@@ -333,7 +345,7 @@ int orc_search(int n_nodes, int n_edges, const int32_t *edges, int C,
     /* ---- undo in reverse order ---- */
     for (int t = nlog - 1; t >= 0; --t) {
         if (log[t].kind != 0) continue;                    /* edge eliminations change nothing */
-        S[log[t].j] = argtab[t][(size_t)S[log[t].i] * C + S[log[t].k]];
+        S[log[t].j] = argtab[t][(size_t)S[log[t].i] * Cn[log[t].k] + S[log[t].k]];
     }
 
 done:
@@ -342,7 +354,34 @@ done:
     if (n_rounds) *n_rounds = rounds;
     if (E) for (int e = 0; e < n_edges; ++e) if (E[e].owned) free(E[e].tab);
     if (argtab) for (int t = 0; t < n_edges; ++t) free(argtab[t]);
-    free(w); free(E); free(log); free(argtab); free(dead); free(sel);
+    free(woff); free(w); free(E); free(log); free(argtab); free(dead); free(sel);
     free(indeg); free(outdeg); free(ine); free(oute); free(ids);
+    return rc;
+}
+
+/* The same with one configuration count C for every node: tc, ts [N][C], tx [E][C][C]. */
+int orc_search(int n_nodes, int n_edges, const int32_t *edges, int C,
+               const int32_t *tc, const int32_t *ts, const int32_t *tx, int schedule,
+               int64_t *out_cost, int32_t *S, orc_step *steps, int32_t *n_steps, int32_t *n_rounds)
+{
+    if (n_nodes <= 0 || C <= 0) return ORC_E_INVAL;
+    int32_t *Cn = (int32_t *)malloc(sizeof(int32_t) * (size_t)n_nodes);
+    if (!Cn) return ORC_E_NOMEM;
+    for (int l = 0; l < n_nodes; ++l) Cn[l] = C;
+    int rc = orc_search_ragged(n_nodes, n_edges, edges, Cn, tc, ts, tx, schedule, out_cost, S, steps, n_steps, n_rounds);
+    free(Cn);
+    return rc;
+}
+
+int orc_strategy_cost(int n_nodes, int n_edges, const int32_t *edges, int C,
+                      const int32_t *tc, const int32_t *ts, const int32_t *tx,
+                      const int32_t *S, int64_t *out_cost)
+{
+    if (n_nodes <= 0 || C <= 0) return ORC_E_INVAL;
+    int32_t *Cn = (int32_t *)malloc(sizeof(int32_t) * (size_t)n_nodes);
+    if (!Cn) return ORC_E_NOMEM;
+    for (int l = 0; l < n_nodes; ++l) Cn[l] = C;
+    int rc = orc_strategy_cost_ragged(n_nodes, n_edges, edges, Cn, tc, ts, tx, S, out_cost);
+    free(Cn);
     return rc;
 }

@@ -45,6 +45,24 @@ def random_tables(n_nodes, edges, C, seed, tc_range, ts_range, tx_range):
     return tc, ts, tx
 
 
+def ragged_tables(n_nodes, edges, Cn, seed, lo=0, hi=1000):
+    """Tables for per-node configuration counts Cn: t_c and t_s are the rows of all nodes one after
+    another, t_x the tables [Cn[src]][Cn[dst]] of all edges one after another (flat int32 arrays)."""
+    rng = _rng(seed)
+    Cn = np.asarray(Cn, dtype=np.int32)
+    total = int(Cn.sum())
+    cells = int(sum(int(Cn[i]) * int(Cn[j]) for i, j in np.asarray(edges).reshape(-1, 2)))
+    tc = rng.integers(lo, hi, size=total, endpoint=True, dtype=np.int32)
+    ts = rng.integers(lo, hi, size=total, endpoint=True, dtype=np.int32)
+    tx = rng.integers(lo, hi, size=cells, endpoint=True, dtype=np.int32)
+    return tc, ts, tx
+
+
+def ragged_counts(n_nodes, seed, c_min, c_max):
+    """Seeded per-node configuration counts in [c_min, c_max]."""
+    return _rng(seed).integers(c_min, c_max, size=n_nodes, endpoint=True, dtype=np.int32)
+
+
 def _problem(name, n_nodes, edges, C, tc, ts, tx, schedule):
     return {"name": name, "n_nodes": int(n_nodes), "edges": np.ascontiguousarray(edges, dtype=np.int32),
             "C": int(C), "tc": tc, "ts": ts, "tx": tx, "schedule": schedule}

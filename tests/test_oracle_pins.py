@@ -342,3 +342,53 @@ def test_too_many_strategies_to_enumerate_is_reported():
     with pytest.raises(oracle.OracleError) as e:
         oracle.search(4, edges, 600, tc, ts, tx)
     assert e.value.code == oracle.E_NOT_REDUCIBLE
+
+
+# ------------------------------------------------------------------ per-node configuration counts
+RAGGED_GRAPHS = {
+    "chain5": (5, [(0, 1), (1, 2), (2, 3), (3, 4)]),
+    "diamond_skip": (4, [(0, 1), (0, 2), (1, 3), (2, 3), (0, 3)]),
+    "star": (4, [(0, 1), (0, 2), (0, 3)]),
+    "backward_ids": (4, [(3, 1), (1, 0), (0, 2)]),
+    "parallel3": (2, [(0, 1), (0, 1), (0, 1)]),
+    "two_towers": (7, [(0, 1), (1, 4), (2, 3), (3, 4), (4, 5), (5, 6), (4, 6)]),
+}
+
+
+@pytest.mark.parametrize("name", sorted(RAGGED_GRAPHS))
+def test_ragged_search_equals_brute_force(name):
+    # layers may have different numbers of configurations (Table 1: a fully connected layer has
+    # fewer parallelizable dimensions than a convolution); tables are then rectangular
+    n, e = RAGGED_GRAPHS[name]
+    e = np.asarray(e, np.int32)
+    for seed in range(5):
+        Cn = wl.ragged_counts(n, seed, 1, 4 if n <= 5 else 3)
+        for hi in (1, 20):
+            tc, ts, tx = wl.ragged_tables(n, e, Cn, seed * 7 + hi, 0, hi)
+            best, S_lex, n_opt = brute.brute_force_ragged(n, e, Cn, tc, ts, tx)
+            for schedule in (oracle.SCHEDULE_ROUNDS, oracle.SCHEDULE_LEFT_FOLD):
+                r = oracle.search_ragged(n, e, Cn, tc, ts, tx, schedule)
+                assert r["cost"] == best
+                assert oracle.strategy_cost_ragged(n, e, Cn, tc, ts, tx, r["strategy"]) == best
+                assert (r["strategy"] < Cn).all()
+                if n_opt == 1:
+                    assert np.array_equal(r["strategy"], S_lex)
+
+
+def test_ragged_with_equal_counts_is_the_uniform_search():
+    p = wl.forkjoin_problem(2, 5, 3, lo=0, hi=9)
+    a = oracle.search(p["n_nodes"], p["edges"], 5, p["tc"], p["ts"], p["tx"])
+    b = oracle.search_ragged(p["n_nodes"], p["edges"], np.full(p["n_nodes"], 5), p["tc"], p["ts"], p["tx"])
+    assert a["cost"] == b["cost"] and np.array_equal(a["strategy"], b["strategy"])
+    assert np.array_equal(a["steps"], b["steps"])
+
+
+def test_ragged_strategy_cost_hand_example():
+    # node 0 has 2 configurations, node 1 has 3; one edge with a 2 x 3 table
+    tc = np.array([1, 2, 10, 20, 30], np.int32)
+    ts = np.array([100, 200, 1000, 2000, 3000], np.int32)
+    tx = np.array([[5, 6, 7], [8, 9, 4]], np.int32) * 10000
+    e = np.array([[0, 1]], np.int32)
+    assert oracle.strategy_cost_ragged(2, e, [2, 3], tc, ts, tx, [1, 2]) == 2 + 200 + 30 + 3000 + 40000
+    best, S, _ = brute.brute_force_ragged(2, e, [2, 3], tc, ts, tx)
+    assert best == 1 + 100 + 10 + 1000 + 50000 and list(S) == [0, 0]
