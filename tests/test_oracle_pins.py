@@ -391,4 +391,7 @@ def test_ragged_strategy_cost_hand_example():
     e = np.array([[0, 1]], np.int32)
     assert oracle.strategy_cost_ragged(2, e, [2, 3], tc, ts, tx, [1, 2]) == 2 + 200 + 30 + 3000 + 40000
     best, S, _ = brute.brute_force_ragged(2, e, [2, 3], tc, ts, tx)
-    assert best == 1 + 100 + 10 + 1000 + 50000 and list(S) == [0, 0]
+    # (0,0) costs 101 + 1010 + 50000 = 51111; (1,2) costs 202 + 3030 + 40000 = 43232 and is the optimum
+    assert best == 43232 and list(S) == [1, 2]
+    r = oracle.search_ragged(2, e, [2, 3], tc, ts, tx)
+    assert r["cost"] == 43232 and list(r["strategy"]) == [1, 2]
