@@ -138,12 +138,27 @@ lwp_status lwp_search_graph_ex(lwp_ctx *ctx, int32_t n_nodes, int32_t n_edges, c
                                int32_t C, const int32_t *d_tc, const int32_t *d_ts, const int32_t *d_tx,
                                int32_t schedule, int32_t undo, int32_t *out_cost, int32_t *out_strategy);
 
+/* The search when the layers' configuration sets differ in size (Sec. 3: each layer l has its own
+ * set of configurations; Sec. 5 enumerates them per layer type, so e.g. a fully-connected layer has
+ * fewer than a convolution).  C_node HOST [n_nodes]: node v has C_node[v] configurations
+ * (1 <= C_node[v] <= 65536).  d_tc, d_ts DEVICE: the nodes' rows concatenated in node order
+ * (row v has C_node[v] entries); d_tx DEVICE: the edges' tables concatenated in edge order, table e
+ * row-major [C_node[src_e]][C_node[dst_e]].  Everything else as lwp_search_graph_ex, with "C^K"
+ * read as the product of the component's C_node.  With all C_node equal it is the same call as
+ * lwp_search_graph_ex (which is implemented by it). */
+lwp_status lwp_search_graph_ragged(lwp_ctx *ctx, int32_t n_nodes, int32_t n_edges, const int32_t *edges,
+                                   const int32_t *C_node, const int32_t *d_tc, const int32_t *d_ts,
+                                   const int32_t *d_tx, int32_t schedule, int32_t undo,
+                                   int32_t *out_cost, int32_t *out_strategy);
+
 /* Host-only: bytes of device workspace lwp_search_graph(_ex) needs for this graph (0 on a graph it
  * would refuse). */
 size_t lwp_search_workspace_bytes(int32_t n_nodes, int32_t n_edges, const int32_t *edges, int32_t C,
                                   int32_t schedule);
 size_t lwp_search_workspace_bytes_ex(int32_t n_nodes, int32_t n_edges, const int32_t *edges, int32_t C,
                                      int32_t schedule, int32_t undo);
+size_t lwp_search_workspace_bytes_ragged(int32_t n_nodes, int32_t n_edges, const int32_t *edges,
+                                         const int32_t *C_node, int32_t schedule, int32_t undo);
 
 /* ---- cost tables (Sec. 5.1: t_c, t_s, t_x) ----------------------------------------------- */
 

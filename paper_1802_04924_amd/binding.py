@@ -22,7 +22,8 @@ UNDO_STORED, UNDO_RECOMPUTE = 0, 1
 EXPORTED = [
     "lwp_create", "lwp_destroy", "lwp_last_error", "lwp_status_string", "lwp_synchronize",
     "lwp_eliminate_node", "lwp_eliminate_edge", "lwp_plan_graph", "lwp_search_graph",
-    "lwp_search_workspace_bytes", "lwp_search_graph_ex", "lwp_search_workspace_bytes_ex", "lwp_build_cost_tables",
+    "lwp_search_workspace_bytes", "lwp_search_graph_ex", "lwp_search_workspace_bytes_ex",
+    "lwp_search_graph_ragged", "lwp_search_workspace_bytes_ragged", "lwp_build_cost_tables",
     "lwp_profile_enable", "lwp_profile_reset", "lwp_profile_read",
 ]
 
@@ -77,6 +78,9 @@ def load():
     lib.lwp_search_graph_ex.argtypes = [vp, i32, i32, vp, i32, vp, vp, vp, i32, i32, i32p, vp]
     lib.lwp_search_workspace_bytes_ex.argtypes = [i32, i32, vp, i32, i32, i32]
     lib.lwp_search_workspace_bytes_ex.restype = ctypes.c_size_t
+    lib.lwp_search_graph_ragged.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, i32, i32, i32p, vp]
+    lib.lwp_search_workspace_bytes_ragged.argtypes = [i32, i32, vp, vp, i32, i32]
+    lib.lwp_search_workspace_bytes_ragged.restype = ctypes.c_size_t
     lib.lwp_build_cost_tables.argtypes = [vp, vp, i32, vp, i32, vp, i32, vp, vp, vp, vp]
     lib.lwp_profile_enable.argtypes = [vp, i32]
     lib.lwp_profile_reset.argtypes = [vp]
@@ -109,6 +113,16 @@ def search_workspace_bytes(n_nodes, edges, C, schedule=SCHEDULE_ROUNDS, undo=UND
     lib = load()
     edges = _np_i32(edges, (-1, 2))
     return int(lib.lwp_search_workspace_bytes_ex(n_nodes, len(edges), edges.ctypes.data, C, int(schedule), int(undo)))
+
+
+def search_workspace_bytes_ragged(n_nodes, edges, C_node, schedule=SCHEDULE_ROUNDS, undo=UNDO_STORED) -> int:
+    lib = load()
+    edges = _np_i32(edges, (-1, 2))
+    C_node = _np_i32(C_node, (-1,))
+    if len(C_node) != n_nodes:
+        raise ValueError("C_node must have one entry per node")
+    return int(lib.lwp_search_workspace_bytes_ragged(n_nodes, len(edges), edges.ctypes.data, C_node.ctypes.data,
+                                                     int(schedule), int(undo)))
 
 
 def _dev(t, what):
@@ -201,6 +215,29 @@ class Context:
                                            _dev(tx, "tx") if E else None, int(schedule), int(undo), ctypes.byref(cost),
                                            S.ctypes.data)
         self._check(rc, "search_graph")
+        return cost.value, S
+
+    def search_graph_ragged(self, n_nodes, edges, C_node, tc, ts, tx, schedule=SCHEDULE_ROUNDS, undo=UNDO_STORED):
+        """Search with C_node[v] configurations for node v; tc, ts, tx are flat concatenations."""
+        edges = _np_i32(edges, (-1, 2))
+        C_node = _np_i32(C_node, (-1,))
+        E = len(edges)
+        if len(C_node) != n_nodes:
+            raise ValueError("C_node must have one entry per node")
+        n_w = int(C_node.astype(np.int64).sum())
+        if tc.dim() != 1 or ts.dim() != 1 or tc.numel() != n_w or ts.numel() != n_w:
+            raise ValueError("t_c / t_s must be flat with sum(C_node) entries")
+        if E:
+            ok = (edges >= 0).all() and (edges < n_nodes).all()
+            n_x = int((C_node[edges[:, 0]].astype(np.int64) * C_node[edges[:, 1]]).sum()) if ok else -1
+            if ok and (tx.dim() != 1 or tx.numel() != n_x):
+                raise ValueError("t_x must be flat with sum(C_src * C_dst) entries")
+        cost = ctypes.c_int32(0)
+        S = np.empty(n_nodes, np.int32)
+        rc = self._lib.lwp_search_graph_ragged(self._h, n_nodes, E, edges.ctypes.data, C_node.ctypes.data,
+                                               _dev(tc, "tc"), _dev(ts, "ts"), _dev(tx, "tx") if E else None,
+                                               int(schedule), int(undo), ctypes.byref(cost), S.ctypes.data)
+        self._check(rc, "search_graph_ragged")
         return cost.value, S
 
     # ---- Sec. 5.1 ----------------------------------------------------------

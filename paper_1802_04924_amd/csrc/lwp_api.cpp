@@ -5,7 +5,9 @@
 #include <algorithm>
 #include <cstdio>
 #include <cstring>
+#include <map>
 #include <string>
+#include <tuple>
 #include <vector>
 
 #include "lwp.h"
@@ -99,18 +101,6 @@ bool want_small_tiles(int32_t Ci, int32_t Cj, int32_t Ck, int64_t batch) {
     return large_tiles(Ci, Ck, batch) < 2048 || Cj >= 512;
 }
 
-// A residual component is enumerated outright; its flat strategy index must fit 32 bits.
-bool components_enumerable(const Plan& plan, int32_t C) {
-    for (auto& c : plan.comps) {
-        unsigned long long n = 1;
-        for (size_t q = 0; q < c.nodes.size(); ++q) {
-            n *= (unsigned long long)C;
-            if (n > (1ull << 32)) return false;
-        }
-    }
-    return true;
-}
-
 // Split tiles: a launch with few 64 x 64 tiles lets several workgroups share a tile, each with a
 // part of the c range of at least two stages of 32 candidates.
 // Measured: splitting pays while tiles x parts stays around 1024 workgroups (4 per compute unit).
@@ -182,39 +172,67 @@ lwp_status check_ctx(lwp_ctx* ctx) {
 }
 
 // ---- buffer planning of a whole search ---------------------------------------------------------
-// Tables produced by eliminations live in equally sized slots; a slot is released once the step
-// that consumed it has been enqueued (launches of one stream run in order).
-struct TableRef { bool is_slot; int32_t id; };   // input edge table id, or slot id
+// Node l has Cn[l] configurations (Sec. 3: every layer has its own configuration set), so the
+// table of an edge (i, j) is Cn[i] x Cn[j] and tables differ in size.  Tables produced by
+// eliminations live in an arena; a region is released once the step that consumed it has been
+// enqueued (launches of one stream run in order) and reused by later tables of the same size.
+struct TableRef {
+    bool is_slot;        // false: element offset into the caller's concatenated t_x; true: into the arena
+    int64_t off;
+    int32_t rows, cols;
+    int64_t cells() const { return (int64_t)rows * cols; }
+};
 
 struct EdgeGroup { int32_t keep; std::vector<int32_t> others; int32_t round; };
 
 struct Layout {
     std::vector<EdgeGroup> groups;            // edge eliminations grouped per (round, kept edge)
-    std::vector<TableRef> node_A, node_B;     // per node step (in plan order)
-    std::vector<int32_t> node_out_slot;
+    std::vector<TableRef> node_A, node_B, node_out;   // per node step (in plan order)
+    std::vector<int64_t> node_arg_off;        // element offset of the step's argmin table
     std::vector<std::vector<TableRef>> group_src;
-    std::vector<int32_t> group_out_slot;
+    std::vector<TableRef> group_out;
     std::vector<TableRef> final_table;        // per residual pair
     std::vector<std::vector<TableRef>> comp_tables;   // per enumerated component, per edge
-    int32_t n_slots = 0;
+    std::vector<int64_t> node_off, tx_off;    // element offsets of w rows / input tables (+ total)
+    int64_t slot_elems = 0, arg_elems = 0;
+    bool uniform = true;                      // every node has the same number of configurations
 };
 
+constexpr int64_t kArenaAlign = 64;           // elements: regions start on 256-byte boundaries
+
 // keep_inputs: tables consumed by node eliminations stay alive (the undo pass re-reads them).
-Layout plan_buffers(const Plan& plan, int32_t n_edges, bool keep_inputs) {
+Layout plan_buffers(const Plan& plan, int32_t n_nodes, int32_t n_edges, const int32_t* edges, const int32_t* Cn,
+                    bool keep_inputs) {
     Layout L;
+    L.node_off.resize((size_t)n_nodes + 1);
+    L.tx_off.resize((size_t)n_edges + 1);
+    L.node_off[0] = 0;
+    for (int32_t v = 0; v < n_nodes; ++v) {
+        L.node_off[v + 1] = L.node_off[v] + Cn[v];
+        if (Cn[v] != Cn[0]) L.uniform = false;
+    }
     std::vector<TableRef> cur(n_edges);
-    for (int32_t e = 0; e < n_edges; ++e) cur[e] = {false, e};
-    std::vector<int32_t> free_slots;
-    auto take = [&]() {
-        if (!free_slots.empty()) { int32_t s = free_slots.back(); free_slots.pop_back(); return s; }
-        return L.n_slots++;
+    L.tx_off[0] = 0;
+    for (int32_t e = 0; e < n_edges; ++e) {
+        cur[e] = {false, L.tx_off[e], Cn[edges[2 * e]], Cn[edges[2 * e + 1]]};
+        L.tx_off[e + 1] = L.tx_off[e] + cur[e].cells();
+    }
+    std::map<int64_t, std::vector<int64_t>> free_regions;    // by size in elements
+    auto take = [&](int32_t rows, int32_t cols) {
+        const int64_t cells = (int64_t)rows * cols;
+        auto& fl = free_regions[cells];
+        int64_t off;
+        if (!fl.empty()) { off = fl.back(); fl.pop_back(); }
+        else { off = L.slot_elems; L.slot_elems += (cells + kArenaAlign - 1) / kArenaAlign * kArenaAlign; }
+        return TableRef{true, off, rows, cols};
     };
+    auto give_back = [&](const std::vector<TableRef>& rs) { for (auto& r : rs) free_regions[r.cells()].push_back(r.off); };
     size_t t = 0;
     const size_t n = plan.steps.size();
     while (t < n) {
         const int32_t round = plan.steps[t].round;
         // E-phase of this round
-        std::vector<int32_t> release;
+        std::vector<TableRef> release;
         while (t < n && plan.steps[t].round == round && plan.steps[t].kind == 1) {
             EdgeGroup g{plan.steps[t].e1, {}, round};
             while (t < n && plan.steps[t].round == round && plan.steps[t].kind == 1 && plan.steps[t].e1 == g.keep) {
@@ -222,31 +240,34 @@ Layout plan_buffers(const Plan& plan, int32_t n_edges, bool keep_inputs) {
                 ++t;
             }
             std::vector<TableRef> src{cur[g.keep]};
-            for (int32_t o : g.others) { src.push_back(cur[o]); if (cur[o].is_slot) release.push_back(cur[o].id); }
-            const int32_t out = cur[g.keep].is_slot ? cur[g.keep].id : take();   // in place when possible
-            cur[g.keep] = {true, out};
-            L.groups.push_back(g); L.group_src.push_back(src); L.group_out_slot.push_back(out);
+            for (int32_t o : g.others) { src.push_back(cur[o]); if (cur[o].is_slot) release.push_back(cur[o]); }
+            const TableRef out = cur[g.keep].is_slot ? cur[g.keep] : take(cur[g.keep].rows, cur[g.keep].cols);   // in place when possible
+            cur[g.keep] = out;
+            L.groups.push_back(g); L.group_src.push_back(src); L.group_out.push_back(out);
         }
-        for (int32_t s : release) free_slots.push_back(s);
+        give_back(release);
         release.clear();
         // N-phase of this round
         while (t < n && plan.steps[t].round == round && plan.steps[t].kind == 0) {
             const lwp_step& st = plan.steps[t];
-            L.node_A.push_back(cur[st.e1]); L.node_B.push_back(cur[st.e2]);
-            if (!keep_inputs && cur[st.e1].is_slot) release.push_back(cur[st.e1].id);
-            if (!keep_inputs && cur[st.e2].is_slot) release.push_back(cur[st.e2].id);
-            const int32_t out = take();
-            L.node_out_slot.push_back(out);
-            cur[st.e1] = {true, out};
+            const TableRef A = cur[st.e1], B = cur[st.e2];
+            L.node_A.push_back(A); L.node_B.push_back(B);
+            if (!keep_inputs && A.is_slot) release.push_back(A);
+            if (!keep_inputs && B.is_slot) release.push_back(B);
+            const TableRef out = take(A.rows, B.cols);
+            L.node_out.push_back(out);
+            L.node_arg_off.push_back(L.arg_elems);
+            L.arg_elems += (out.cells() + kArenaAlign - 1) / kArenaAlign * kArenaAlign;
+            cur[st.e1] = out;
             ++t;
         }
-        for (int32_t s : release) free_slots.push_back(s);
+        give_back(release);
     }
     for (auto& p : plan.pairs) L.final_table.push_back(cur[p.edge]);
     for (auto& c : plan.comps) {
-        std::vector<TableRef> t;
-        for (int32_t e : c.edges) t.push_back(cur[e]);
-        L.comp_tables.push_back(t);
+        std::vector<TableRef> tabs;
+        for (int32_t e : c.edges) tabs.push_back(cur[e]);
+        L.comp_tables.push_back(tabs);
     }
     return L;
 }
@@ -256,24 +277,25 @@ Layout plan_buffers(const Plan& plan, int32_t n_edges, bool keep_inputs) {
 // a single copy.  Tables with a range: input edges, w of every node, output of every node
 // elimination, output of every edge-sum group.
 struct WsLayout {
-    size_t w, head, keys, result, args, slots, total;
+    size_t w, head, keys, result, offs, offs_bytes, args, slots, total;
     size_t desc, desc_bytes;                                   // descriptor block
     size_t node_desc, edge_desc, src_ptrs, pair_desc, singles, undo, comps;   // offsets inside the block
     int32_t n_ranges;
 };
 
-WsLayout layout_workspace(const Plan& plan, const Layout& L, int32_t n_nodes, int32_t n_edges, int32_t C, bool stored_argmin) {
+WsLayout layout_workspace(const Plan& plan, const Layout& L, int32_t n_nodes, int32_t n_edges, bool stored_argmin) {
     WsLayout o{};
     size_t off = 0;
     auto put = [&](size_t bytes) { size_t at = off; off = align_up(off + bytes, 256); return at; };
-    const size_t CC = (size_t)C * C * sizeof(int32_t);
     size_t n_src = 0;
     for (auto& g : L.group_src) n_src += g.size();
     o.n_ranges = n_edges + n_nodes + plan.n_node_steps + (int32_t)L.groups.size();
-    o.w = put((size_t)n_nodes * C * sizeof(int32_t));
+    o.w = put((size_t)L.node_off[n_nodes] * sizeof(int32_t));
     o.head = put((2 + 2 * (size_t)o.n_ranges) * sizeof(int32_t));
     o.keys = put(std::max<size_t>(1, plan.pairs.size() + plan.singles.size() + plan.comps.size()) * sizeof(unsigned long long));
     o.result = put((3 + (size_t)n_nodes) * sizeof(int32_t));
+    o.offs_bytes = L.uniform ? 0 : ((size_t)n_nodes + 1 + (size_t)n_edges + 1) * sizeof(int64_t);
+    o.offs = put(o.offs_bytes);
     {
         size_t b = 0;
         auto sub = [&](size_t bytes) { size_t at = b; b = align_up(b + bytes, 16); return at; };
@@ -281,16 +303,35 @@ WsLayout layout_workspace(const Plan& plan, const Layout& L, int32_t n_nodes, in
         o.edge_desc = sub(L.groups.size() * sizeof(EdgeDesc));
         o.src_ptrs = sub(n_src * sizeof(void*));
         o.pair_desc = sub(plan.pairs.size() * sizeof(PairDesc));
-        o.singles = sub(plan.singles.size() * sizeof(int32_t));
+        o.singles = sub(plan.singles.size() * sizeof(SingleDesc));
         o.undo = sub((size_t)plan.n_node_steps * sizeof(UndoDesc));
         o.comps = sub(plan.comps.size() * sizeof(CompDesc));
         o.desc_bytes = std::max<size_t>(b, 16);
     }
     o.desc = put(o.desc_bytes);
-    o.args = put(stored_argmin ? (size_t)plan.n_node_steps * CC : 0);
-    o.slots = put((size_t)L.n_slots * CC);
+    o.args = put(stored_argmin ? (size_t)L.arg_elems * sizeof(int32_t) : 0);
+    o.slots = put((size_t)L.slot_elems * sizeof(int32_t));
     o.total = off;
     return o;
+}
+
+// A residual component is enumerated outright; its flat strategy index must fit 32 bits.
+bool components_enumerable(const Plan& plan, const int32_t* Cn) {
+    for (auto& c : plan.comps) {
+        unsigned long long n = 1;
+        for (int32_t v : c.nodes) {
+            n *= (unsigned long long)Cn[v];
+            if (n > (1ull << 32)) return false;
+        }
+    }
+    return true;
+}
+
+bool counts_valid(int32_t n_nodes, const int32_t* Cn) {
+    if (!Cn) return false;
+    for (int32_t v = 0; v < n_nodes; ++v)
+        if (Cn[v] < 1 || Cn[v] > kMaxConfigs) return false;
+    return true;
 }
 
 }  // namespace
@@ -466,13 +507,20 @@ size_t lwp_search_workspace_bytes(int32_t n_nodes, int32_t n_edges, const int32_
 
 size_t lwp_search_workspace_bytes_ex(int32_t n_nodes, int32_t n_edges, const int32_t* edges, int32_t C,
                                      int32_t schedule, int32_t undo) {
-    if (C < 1 || C > kMaxConfigs || (undo != LWP_UNDO_STORED && undo != LWP_UNDO_RECOMPUTE)) return 0;
+    if (n_nodes < 1) return 0;
+    const std::vector<int32_t> Cn((size_t)n_nodes, C);
+    return lwp_search_workspace_bytes_ragged(n_nodes, n_edges, edges, Cn.data(), schedule, undo);
+}
+
+size_t lwp_search_workspace_bytes_ragged(int32_t n_nodes, int32_t n_edges, const int32_t* edges,
+                                         const int32_t* C_node, int32_t schedule, int32_t undo) {
+    if (n_nodes < 1 || !counts_valid(n_nodes, C_node) || (undo != LWP_UNDO_STORED && undo != LWP_UNDO_RECOMPUTE)) return 0;
     Plan plan;
     std::string err;
     if (make_plan(n_nodes, n_edges, edges, schedule, plan, err) != LWP_OK) return 0;
-    if (!components_enumerable(plan, C)) return 0;
-    Layout L = plan_buffers(plan, n_edges, undo == LWP_UNDO_RECOMPUTE);
-    return layout_workspace(plan, L, n_nodes, n_edges, C, undo == LWP_UNDO_STORED).total;
+    if (!components_enumerable(plan, C_node)) return 0;
+    Layout L = plan_buffers(plan, n_nodes, n_edges, edges, C_node, undo == LWP_UNDO_RECOMPUTE);
+    return layout_workspace(plan, L, n_nodes, n_edges, undo == LWP_UNDO_STORED).total;
 }
 
 lwp_status lwp_search_graph(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, const int32_t* edges,
@@ -486,9 +534,22 @@ lwp_status lwp_search_graph_ex(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, c
                                int32_t C, const int32_t* d_tc, const int32_t* d_ts, const int32_t* d_tx,
                                int32_t schedule, int32_t undo, int32_t* out_cost, int32_t* out_strategy) {
     if (lwp_status s = check_ctx(ctx)) return s;
+    if (C < 1 || C > kMaxConfigs) return fail(ctx, LWP_E_INVAL, "C must be in [1, 65536]");
+    if (n_nodes < 1) return fail(ctx, LWP_E_GRAPH, "n_nodes must be >= 1");
+    const std::vector<int32_t> Cn((size_t)n_nodes, C);
+    return lwp_search_graph_ragged(ctx, n_nodes, n_edges, edges, Cn.data(), d_tc, d_ts, d_tx, schedule, undo, out_cost,
+                                   out_strategy);
+}
+
+lwp_status lwp_search_graph_ragged(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, const int32_t* edges,
+                                   const int32_t* Cn, const int32_t* d_tc, const int32_t* d_ts,
+                                   const int32_t* d_tx, int32_t schedule, int32_t undo, int32_t* out_cost,
+                                   int32_t* out_strategy) {
+    if (lwp_status s = check_ctx(ctx)) return s;
     if (undo != LWP_UNDO_STORED && undo != LWP_UNDO_RECOMPUTE) return fail(ctx, LWP_E_INVAL, "unknown undo mode");
     const bool stored = (undo == LWP_UNDO_STORED);
-    if (C < 1 || C > kMaxConfigs) return fail(ctx, LWP_E_INVAL, "C must be in [1, 65536]");
+    if (n_nodes < 1) return fail(ctx, LWP_E_GRAPH, "n_nodes must be >= 1");
+    if (!counts_valid(n_nodes, Cn)) return fail(ctx, LWP_E_INVAL, "every configuration count must be in [1, 65536]");
     if (!d_tc || !d_ts || (n_edges > 0 && !d_tx) || !out_cost || !out_strategy)
         return fail(ctx, LWP_E_INVAL, "null pointer");
     if (((uintptr_t)d_tc | (uintptr_t)d_ts | (uintptr_t)d_tx) & 3)
@@ -499,17 +560,17 @@ lwp_status lwp_search_graph_ex(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, c
         lwp_status s = make_plan(n_nodes, n_edges, edges, schedule, plan, err);
         if (s != LWP_OK) return fail(ctx, s, err);
     }
-    if (!components_enumerable(plan, C))
+    if (!components_enumerable(plan, Cn))
         return fail(ctx, LWP_E_NOT_REDUCIBLE, "a residual component has more than 2^32 strategies to enumerate");
-    const Layout L = plan_buffers(plan, n_edges, !stored);
-    const WsLayout W = layout_workspace(plan, L, n_nodes, n_edges, C, stored);
+    const Layout L = plan_buffers(plan, n_nodes, n_edges, edges, Cn, !stored);
+    const WsLayout W = layout_workspace(plan, L, n_nodes, n_edges, stored);
     if (lwp_status s = ensure_workspace(ctx, W.total)) return s;
     const size_t head_in_bytes = (2 + 2 * (size_t)(n_edges + n_nodes)) * sizeof(int32_t);
     const size_t pin_head = 0, pin_desc = align_up(head_in_bytes, 256), pin_result = pin_desc + align_up(W.desc_bytes, 256);
-    if (lwp_status s = ensure_pinned(ctx, pin_result + (3 + (size_t)n_nodes) * sizeof(int32_t))) return s;
+    const size_t pin_offs = pin_result + align_up((3 + (size_t)n_nodes) * sizeof(int32_t), 256);
+    if (lwp_status s = ensure_pinned(ctx, pin_offs + W.offs_bytes)) return s;
     char* ws = ctx->ws;
     hipStream_t st = ctx->stream;
-    const int64_t CC = (int64_t)C * C;
     int32_t* d_w = reinterpret_cast<int32_t*>(ws + W.w);
     int32_t* d_head = reinterpret_cast<int32_t*>(ws + W.head);
     int32_t* d_stats = d_head + 2;
@@ -518,16 +579,29 @@ lwp_status lwp_search_graph_ex(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, c
     unsigned long long* d_keys = reinterpret_cast<unsigned long long*>(ws + W.keys);
     int32_t* d_result = reinterpret_cast<int32_t*>(ws + W.result);
     const int32_t n_comp = (int32_t)(plan.pairs.size() + plan.singles.size() + plan.comps.size());
-    auto table_ptr = [&](const TableRef& r) -> const int32_t* {
-        return r.is_slot ? d_slots + (int64_t)r.id * CC : d_tx + (int64_t)r.id * CC;
-    };
+    auto table_ptr = [&](const TableRef& r) -> const int32_t* { return (r.is_slot ? d_slots : d_tx) + r.off; };
+    auto slot_ptr = [&](const TableRef& r) -> int32_t* { return d_slots + r.off; };
+    auto w_ptr = [&](int32_t v) -> const int32_t* { return d_w + L.node_off[v]; };
     // index of the range pair of: input edge e | w of node v | output of node step | output of group
     const int32_t rng_w0 = n_edges, rng_node0 = n_edges + n_nodes, rng_group0 = rng_node0 + plan.n_node_steps;
 
-    // 1. w = t_c + t_s with its ranges, and the range of every input table; one read-back
+    // 1. w = t_c + t_s with its ranges, and the range of every input table
     int32_t* d_flag = d_head;      // set by any kernel that finds a sum outside int32
-    LWP_HIP(ctx, launch_prepare_search(d_tc, d_ts, d_w, n_nodes, C, d_stats, W.n_ranges, rng_w0, d_keys, n_comp, d_flag, st));
-    LWP_HIP(ctx, launch_ranges(d_tx, n_edges, CC, d_stats, st));
+    if (L.uniform) {
+        LWP_HIP(ctx, launch_prepare_search(d_tc, d_ts, d_w, n_nodes, Cn[0], nullptr, d_stats, W.n_ranges, rng_w0, d_keys, n_comp, d_flag, st));
+        LWP_HIP(ctx, launch_ranges(d_tx, n_edges, (int64_t)Cn[0] * Cn[0], d_stats, st));
+    } else {
+        // rows and tables of different sizes: their offsets go to the device first
+        int64_t* h_offs = reinterpret_cast<int64_t*>(ctx->pin + pin_offs);
+        std::memcpy(h_offs, L.node_off.data(), ((size_t)n_nodes + 1) * sizeof(int64_t));
+        std::memcpy(h_offs + n_nodes + 1, L.tx_off.data(), ((size_t)n_edges + 1) * sizeof(int64_t));
+        int64_t* d_offs = reinterpret_cast<int64_t*>(ws + W.offs);
+        LWP_HIP(ctx, hipMemcpyAsync(d_offs, h_offs, W.offs_bytes, hipMemcpyHostToDevice, st));
+        int64_t max_cells = 1;
+        for (int32_t e = 0; e < n_edges; ++e) max_cells = std::max(max_cells, L.tx_off[e + 1] - L.tx_off[e]);
+        LWP_HIP(ctx, launch_prepare_search(d_tc, d_ts, d_w, n_nodes, 0, d_offs, d_stats, W.n_ranges, rng_w0, d_keys, n_comp, d_flag, st));
+        LWP_HIP(ctx, launch_ranges_var(d_tx, d_offs + n_nodes + 1, n_edges, max_cells, d_stats, st));
+    }
     // Stored argmin tables need a kernel variant chosen from value ranges, so the ranges of the inputs
     // are read back (the one mid-search synchronisation).  With recomputed undo every elimination is
     // value-only (no range condition) and overflow is judged on the device from measured ranges, so
@@ -550,7 +624,7 @@ lwp_status lwp_search_graph_ex(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, c
     EdgeDesc* ed = reinterpret_cast<EdgeDesc*>(hb + W.edge_desc);
     const int32_t** src_ptrs = reinterpret_cast<const int32_t**>(hb + W.src_ptrs);
     PairDesc* pd = reinterpret_cast<PairDesc*>(hb + W.pair_desc);
-    int32_t* h_singles = reinterpret_cast<int32_t*>(hb + W.singles);
+    SingleDesc* sd = reinterpret_cast<SingleDesc*>(hb + W.singles);
     UndoDesc* ud = reinterpret_cast<UndoDesc*>(hb + W.undo);
     CompDesc* cd = reinterpret_cast<CompDesc*>(hb + W.comps);
     char* db = ws + W.desc;
@@ -558,7 +632,7 @@ lwp_status lwp_search_graph_ex(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, c
     const EdgeDesc* d_ed = reinterpret_cast<const EdgeDesc*>(db + W.edge_desc);
     const int32_t* const* d_src = reinterpret_cast<const int32_t* const*>(db + W.src_ptrs);
     const PairDesc* d_pd = reinterpret_cast<const PairDesc*>(db + W.pair_desc);
-    const int32_t* d_singles = reinterpret_cast<const int32_t*>(db + W.singles);
+    const SingleDesc* d_sd = reinterpret_cast<const SingleDesc*>(db + W.singles);
     const UndoDesc* d_ud = reinterpret_cast<const UndoDesc*>(db + W.undo);
     const CompDesc* d_cd = reinterpret_cast<const CompDesc*>(db + W.comps);
 
@@ -566,7 +640,12 @@ lwp_status lwp_search_graph_ex(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, c
     std::vector<int32_t> erng(n_edges);          // range-pair index of the edge's current table
     for (int32_t e = 0; e < n_edges; ++e) { er[e] = {stats[2 * e], stats[2 * e + 1]}; erng[e] = e; }
     for (int32_t v = 0; v < n_nodes; ++v) wr[v] = {stats[2 * (rng_w0 + v)], stats[2 * (rng_w0 + v) + 1]};
-    std::vector<int64_t> nd_spread(plan.n_node_steps);
+    // Node eliminations of one round are independent; those of equal shape (Ci, Cj, Ck) and kernel
+    // variant share a launch, so the descriptors of a round are ordered by (shape, variant).
+    struct NodeWork { NodeDesc d; int64_t spread; int32_t Ci, Cj, Ck; int variant; };
+    struct NodeLaunch { size_t first, count; int32_t Ci, Cj, Ck; int variant; };
+    struct RoundWork { size_t g0, g1; int64_t edge_cells, edge_max_cells; std::vector<NodeLaunch> launches; };
+    std::vector<RoundWork> rounds;
     // The propagated bounds are worst cases and grow along a chain although the minima do not.
     // Where they cannot prove that a step stays inside int32 the step is not refused: it runs on a
     // variant without range conditions and every kernel checks the tables' measured ranges (or
@@ -575,133 +654,160 @@ lwp_status lwp_search_graph_ex(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, c
     {
         size_t ni = 0, gi = 0, nsrc = 0, t = 0;
         const size_t n = plan.steps.size();
+        std::vector<NodeWork> work;
+        std::vector<size_t> order;
         while (t < n) {
-            const lwp_step& s = plan.steps[t];
-            if (s.kind == 1) {                  // one group = all steps adding into the same kept edge
+            const int32_t round = plan.steps[t].round;
+            RoundWork rw_{gi, gi, 0, 1, {}};
+            while (t < n && plan.steps[t].round == round && plan.steps[t].kind == 1) {
+                // one group = all steps adding into the same kept edge
                 const auto& g = L.groups[gi];
                 Range r = er[g.keep];
                 for (int32_t o : g.others) r = {r.lo + er[o].lo, r.hi + er[o].hi};
                 er[g.keep] = sat(r);
                 erng[g.keep] = rng_group0 + (int32_t)gi;
-                ed[gi].out = d_slots + (int64_t)L.group_out_slot[gi] * CC;
+                ed[gi].out = slot_ptr(L.group_out[gi]);
                 ed[gi].rngOut = d_stats + 2 * (int64_t)erng[g.keep];
                 ed[gi].flag = d_flag;
+                ed[gi].cells = L.group_out[gi].cells();
                 ed[gi].first_src = (int32_t)nsrc;
                 ed[gi].n_src = (int32_t)L.group_src[gi].size();
                 for (auto& r2 : L.group_src[gi]) src_ptrs[nsrc++] = table_ptr(r2);
+                rw_.edge_cells += ed[gi].cells;
+                rw_.edge_max_cells = std::max(rw_.edge_max_cells, ed[gi].cells);
                 t += g.others.size();
                 ++gi;
-                continue;
             }
-            const Range rA = er[s.e1], rw = wr[s.j], rB = er[s.e2];
-            const bool proven = fits(rA.lo + rw.lo) && fits(rA.hi + rw.hi) && fits(rA.lo + rw.lo + rB.lo) && fits(rA.hi + rw.hi + rB.hi);
-            NodeDesc d{};
-            d.flag = d_flag;
-            d.A = table_ptr(L.node_A[ni]); d.w = d_w + (int64_t)s.j * C; d.B = table_ptr(L.node_B[ni]);
-            d.out = d_slots + (int64_t)L.node_out_slot[ni] * CC;
-            d.arg = stored ? d_args + (int64_t)ni * CC : nullptr;
-            d.loA = (int32_t)rA.lo; d.hiA = (int32_t)rA.hi; d.loW = (int32_t)rw.lo; d.hiW = (int32_t)rw.hi;
-            d.loB = (int32_t)rB.lo; d.hiB = (int32_t)rB.hi;
-            d.rngA = d_stats + 2 * (int64_t)erng[s.e1];
-            d.rngB = d_stats + 2 * (int64_t)erng[s.e2];
-            d.rngW = d_stats + 2 * (int64_t)(rng_w0 + s.j);
-            d.rngOut = d_stats + 2 * (int64_t)(rng_node0 + (int32_t)ni);
-            nd[ni] = d;
-            nd_spread[ni] = proven ? keyed_spread(rA, rw, rB) : (int64_t)1 << 62;   // unproven: no packed keys
-            ud[ni] = {d.arg, d.A, d.w, d.B, s.j, s.i, s.k, s.round};
-            // any fixed c bounds the minimum from above; take the c with the smallest w
-            er[s.e1] = sat({rA.lo + rw.lo + rB.lo, rA.hi + rw.lo + rB.hi});
-            erng[s.e1] = rng_node0 + (int32_t)ni;
-            ++ni; ++t;
+            rw_.g1 = gi;
+            const size_t n0 = ni;
+            work.clear();
+            while (t < n && plan.steps[t].round == round && plan.steps[t].kind == 0) {
+                const lwp_step& s = plan.steps[t];
+                const Range rA = er[s.e1], rw = wr[s.j], rB = er[s.e2];
+                const bool proven = fits(rA.lo + rw.lo) && fits(rA.hi + rw.hi) && fits(rA.lo + rw.lo + rB.lo) && fits(rA.hi + rw.hi + rB.hi);
+                const TableRef &tA = L.node_A[ni], &tB = L.node_B[ni], &tO = L.node_out[ni];
+                NodeWork nw{};
+                NodeDesc& d = nw.d;
+                d.flag = d_flag;
+                d.A = table_ptr(tA); d.w = w_ptr(s.j); d.B = table_ptr(tB);
+                d.out = slot_ptr(tO);
+                d.arg = stored ? d_args + L.node_arg_off[ni] : nullptr;
+                d.loA = (int32_t)rA.lo; d.hiA = (int32_t)rA.hi; d.loW = (int32_t)rw.lo; d.hiW = (int32_t)rw.hi;
+                d.loB = (int32_t)rB.lo; d.hiB = (int32_t)rB.hi;
+                d.rngA = d_stats + 2 * (int64_t)erng[s.e1];
+                d.rngB = d_stats + 2 * (int64_t)erng[s.e2];
+                d.rngW = d_stats + 2 * (int64_t)(rng_w0 + s.j);
+                d.rngOut = d_stats + 2 * (int64_t)(rng_node0 + (int32_t)ni);
+                nw.spread = proven ? keyed_spread(rA, rw, rB) : (int64_t)1 << 62;   // unproven: no packed keys
+                nw.Ci = tA.rows; nw.Cj = tA.cols; nw.Ck = tB.cols;
+                work.push_back(nw);
+                ud[ni] = {d.arg, d.A, d.w, d.B, s.j, s.i, s.k, s.round, nw.Cj, nw.Ck};
+                // any fixed c bounds the minimum from above; take the c with the smallest w
+                er[s.e1] = sat({rA.lo + rw.lo + rB.lo, rA.hi + rw.lo + rB.hi});
+                erng[s.e1] = rng_node0 + (int32_t)ni;
+                ++ni; ++t;
+            }
+            // kernel variant per product: packed keys on the preferred tile size if the spread
+            // allows, else packed keys on 128 x 128 tiles (one more bit), else the plain variant;
+            // 0 keyed small, 1 keyed large, 2 plain small, 3 plain large, 4 value small, 5 value large
+            auto shape_less = [&](const NodeWork& a, const NodeWork& b) {
+                return std::tie(a.Ci, a.Cj, a.Ck) < std::tie(b.Ci, b.Cj, b.Ck);
+            };
+            order.resize(work.size());
+            for (size_t q = 0; q < order.size(); ++q) order[q] = q;
+            if (!L.uniform)
+                std::stable_sort(order.begin(), order.end(), [&](size_t a, size_t b) { return shape_less(work[a], work[b]); });
+            for (size_t a = 0; a < order.size();) {
+                size_t b = a;
+                while (b < order.size() && !shape_less(work[order[a]], work[order[b]])) ++b;
+                const NodeWork& w0 = work[order[a]];
+                const bool prefer_small = want_small_tiles(w0.Ci, w0.Cj, w0.Ck, (int64_t)(b - a));
+                const bool large_fills_chip = large_tiles(w0.Ci, w0.Ck, (int64_t)(b - a)) >= 512;
+                for (size_t q = a; q < b; ++q) {
+                    NodeWork& x = work[order[q]];
+                    if (!stored) x.variant = prefer_small ? 4 : 5;     // value-only: no range condition
+                    else if (x.spread <= (prefer_small ? kKeyedMaxSpreadSmall : kKeyedMaxSpreadLarge)) x.variant = prefer_small ? 0 : 1;
+                    else if (x.spread <= kKeyedMaxSpreadLarge && large_fills_chip) x.variant = 1;
+                    else x.variant = prefer_small ? 2 : 3;
+                }
+                std::stable_sort(order.begin() + a, order.begin() + b, [&](size_t p, size_t q) { return work[p].variant < work[q].variant; });
+                for (size_t q = a; q < b;) {
+                    size_t e = q;
+                    while (e < b && work[order[e]].variant == work[order[q]].variant) ++e;
+                    rw_.launches.push_back({n0 + q, e - q, w0.Ci, w0.Cj, w0.Ck, work[order[q]].variant});
+                    q = e;
+                }
+                a = b;
+            }
+            for (size_t q = 0; q < order.size(); ++q) nd[n0 + q] = work[order[q]].d;
+            rounds.push_back(std::move(rw_));
         }
     }
-    int64_t total_hi = 0, total_lo = 0;
+    int32_t pair_max_rows = 1, single_max_c = 1;
     for (size_t q = 0; q < plan.pairs.size(); ++q) {
         const auto& pr = plan.pairs[q];
-        const int64_t lo = wr[pr.src].lo + er[pr.edge].lo + wr[pr.dst].lo, hi = wr[pr.src].hi + er[pr.edge].hi + wr[pr.dst].hi;
-        total_lo += lo; total_hi += wr[pr.src].lo + er[pr.edge].hi + wr[pr.dst].lo;
-        pd[q] = {table_ptr(L.final_table[q]), pr.src, pr.dst};
+        pd[q] = {table_ptr(L.final_table[q]), w_ptr(pr.src), w_ptr(pr.dst), pr.src, pr.dst, Cn[pr.src], Cn[pr.dst]};
+        pair_max_rows = std::max(pair_max_rows, Cn[pr.src]);
     }
     for (size_t q = 0; q < plan.singles.size(); ++q) {
         const int32_t v = plan.singles[q];
-        total_lo += wr[v].lo; total_hi += wr[v].lo;
-        h_singles[q] = v;
+        sd[q] = {w_ptr(v), v, Cn[v]};
+        single_max_c = std::max(single_max_c, Cn[v]);
     }
+    std::vector<unsigned long long> comp_prefix(plan.comps.size());
     for (size_t q = 0; q < plan.comps.size(); ++q) {
         const auto& c = plan.comps[q];
         CompDesc d{};
         d.K = (int32_t)c.nodes.size(); d.n_edges = (int32_t)c.edges.size();
-        int64_t lo = 0, hi = 0;
-        for (int x = 0; x < d.K; ++x) { d.node[x] = c.nodes[x]; lo += wr[c.nodes[x]].lo; hi += wr[c.nodes[x]].hi; }
+        unsigned long long prefix = 1;
+        for (int x = 0; x < d.K; ++x) {
+            d.node[x] = c.nodes[x]; d.Cn[x] = Cn[c.nodes[x]]; d.w[x] = w_ptr(c.nodes[x]);
+            if (x + 1 < d.K) prefix *= (unsigned long long)d.Cn[x];
+        }
+        comp_prefix[q] = prefix;
         for (int x = 0; x < d.n_edges; ++x) {
             d.tab[x] = table_ptr(L.comp_tables[q][x]);
             d.src_pos[x] = (int8_t)(std::find(c.nodes.begin(), c.nodes.end(), c.esrc[x]) - c.nodes.begin());
             d.dst_pos[x] = (int8_t)(std::find(c.nodes.begin(), c.nodes.end(), c.edst[x]) - c.nodes.begin());
-            lo += er[c.edges[x]].lo; hi += er[c.edges[x]].hi;
         }
-        total_lo += lo; total_hi += hi;
         cd[q] = d;
     }
-    (void)total_lo; (void)total_hi;    // the total is formed in 64 bits on the device and checked after the read-back
 
     // 3. descriptors to the device: one copy
     LWP_HIP(ctx, hipMemcpyAsync(db, hb, W.desc_bytes, hipMemcpyHostToDevice, st));
 
     // 4. eliminations, round by round
-    size_t gi = 0, ni = 0, t = 0;
-    const size_t n = plan.steps.size();
-    while (t < n) {
-        const int32_t round = plan.steps[t].round;
-        size_t g0 = gi;
-        while (t < n && plan.steps[t].round == round && plan.steps[t].kind == 1) {
-            t += L.groups[gi].others.size();
-            ++gi;
+    for (const RoundWork& r : rounds) {
+        if (r.g1 > r.g0) {
+            ScopedTimer tm(ctx, 1, r.edge_cells, false);
+            LWP_HIP(ctx, launch_edge_sum_desc(d_ed + r.g0, d_src, (int32_t)(r.g1 - r.g0), r.edge_max_cells, st));
         }
-        if (gi > g0) {
-            ScopedTimer tm(ctx, 1, (int64_t)(gi - g0) * CC, false);
-            LWP_HIP(ctx, launch_edge_sum_desc(d_ed + g0, d_src, (int32_t)(gi - g0), CC, st));
-        }
-        size_t n0 = ni;
-        while (t < n && plan.steps[t].round == round && plan.steps[t].kind == 0) { ++t; ++ni; }
-        // products of one round run in one launch per variant (contiguous runs): packed keys on
-        // the preferred tile size if the spread allows, else packed keys on 128 x 128 tiles (one
-        // more bit), else the plain variant
-        const bool prefer_small = want_small_tiles(C, C, C, (int64_t)(ni - n0));
-        const bool large_fills_chip = large_tiles(C, C, (int64_t)(ni - n0)) >= 512;
-        auto variant = [&](size_t q) {
-            if (!stored) return prefer_small ? 4 : 5;     // value-only: no range condition
-            if (nd_spread[q] <= (prefer_small ? kKeyedMaxSpreadSmall : kKeyedMaxSpreadLarge)) return prefer_small ? 0 : 1;
-            if (nd_spread[q] <= kKeyedMaxSpreadLarge && large_fills_chip) return 1;
-            return prefer_small ? 2 : 3;
-        };   // 0 keyed small, 1 keyed large, 2 plain small, 3 plain large, 4 value small, 5 value large
-        for (size_t a = n0; a < ni;) {
-            const int v = variant(a);
-            size_t b = a;
-            while (b < ni && variant(b) == v) ++b;
+        for (const NodeLaunch& nl : r.launches) {
+            const int v = nl.variant;
             const bool keyed = v < 2, small = (v == 0 || v == 2 || v == 4);
             const int mode = v >= 4 ? kModeValue : (keyed ? kModeKeyed : kModePlain);
             const int tile = small ? kTileSmall : kTileLarge;
             NodeArgs na{};
-            na.descs = d_nd + a;
-            na.Ci = na.Cj = na.Ck = C; na.batch = (int32_t)(b - a);
-            na.tilesM = na.tilesN = (C + tile - 1) / tile;
-            ScopedTimer tm(ctx, 0, (int64_t)(b - a) * CC * C, keyed);
-            const int kparts = choose_kparts((int64_t)na.tilesM * na.tilesN * na.batch, C, small);
+            na.descs = d_nd + nl.first;
+            na.Ci = nl.Ci; na.Cj = nl.Cj; na.Ck = nl.Ck; na.batch = (int32_t)nl.count;
+            na.tilesM = (nl.Ci + tile - 1) / tile;
+            na.tilesN = (nl.Ck + tile - 1) / tile;
+            ScopedTimer tm(ctx, 0, (int64_t)nl.count * nl.Ci * nl.Cj * nl.Ck, keyed);
+            const int kparts = choose_kparts((int64_t)na.tilesM * na.tilesN * na.batch, nl.Cj, small);
             if (kparts > 1) { if (lwp_status s2 = ensure_split_buffers(ctx)) return s2; }
             set_split(ctx, na, kparts);
             LWP_HIP(ctx, launch_minplus(na, mode, small, st));
-            a = b;
         }
     }
 
     // 5. residual graph, undo, results
-    LWP_HIP(ctx, launch_pair_min(d_pd, (int32_t)plan.pairs.size(), d_w, C, d_keys, d_flag, st));
-    LWP_HIP(ctx, launch_single_min(d_singles, (int32_t)plan.singles.size(), d_w, C, d_keys + plan.pairs.size(), st));
+    LWP_HIP(ctx, launch_pair_min(d_pd, (int32_t)plan.pairs.size(), pair_max_rows, d_keys, d_flag, st));
+    LWP_HIP(ctx, launch_single_min(d_sd, (int32_t)plan.singles.size(), single_max_c, d_keys + plan.pairs.size(), st));
     for (size_t q = 0; q < plan.comps.size(); ++q)
-        LWP_HIP(ctx, launch_component_min(d_cd + q, (int32_t)plan.comps[q].nodes.size(), d_w, C,
+        LWP_HIP(ctx, launch_component_min(d_cd + q, comp_prefix[q],
                                           d_keys + plan.pairs.size() + plan.singles.size() + q, d_flag, st));
-    LWP_HIP(ctx, launch_back_substitute(d_pd, (int32_t)plan.pairs.size(), d_singles, (int32_t)plan.singles.size(),
-                                        d_cd, (int32_t)plan.comps.size(), d_keys, d_ud, plan.n_node_steps, C, n_nodes,
+    LWP_HIP(ctx, launch_back_substitute(d_pd, (int32_t)plan.pairs.size(), d_sd, (int32_t)plan.singles.size(),
+                                        d_cd, (int32_t)plan.comps.size(), d_keys, d_ud, plan.n_node_steps, n_nodes,
                                         d_flag, d_stats + 2 * (int64_t)rng_w0, d_result, st));
     int32_t* result = reinterpret_cast<int32_t*>(ctx->pin + pin_result);
     LWP_HIP(ctx, hipMemcpyAsync(result, d_result, (3 + (size_t)n_nodes) * sizeof(int32_t), hipMemcpyDeviceToHost, st));

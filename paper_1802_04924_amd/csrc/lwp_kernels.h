@@ -61,11 +61,13 @@ struct EdgeDesc {
     int32_t* out;
     int32_t* rngOut;     // optional {min, max} of out, by atomics (see NodeDesc)
     int32_t* flag;       // optional: OR-ed with 1 if a sum leaves int32
+    int64_t cells;       // elements of every table of this group
     int32_t first_src;   // index into the pointer array
     int32_t n_src;
 };
+// max_cells: the largest `cells` among the descriptors (sizes the grid).
 hipError_t launch_edge_sum_desc(const EdgeDesc* d_descs, const int32_t* const* d_src_ptrs, int32_t n_desc,
-                                int64_t cells, hipStream_t stream);
+                                int64_t max_cells, hipStream_t stream);
 hipError_t launch_edge_sum_pair(const int32_t* e1, const int32_t* e2, int32_t* out, int64_t cells,
                                 hipStream_t stream);
 
@@ -78,54 +80,69 @@ hipError_t launch_init_workspace(int32_t* d_stats, int32_t n_tables, int32_t* d_
 // dense one after another), by atomics onto initialised pairs.
 hipError_t launch_ranges(const int32_t* d_tables, int32_t n_tables, int64_t cells, int32_t* d_stats,
                          hipStream_t stream);
-// First launch of a search: w[v][c] = tc[v][c] + ts[v][c]; stats pair w_pair0 + v receives
-// {min, max} of row v of w, or {INT32_MAX, INT32_MIN} if a sum of that row leaves int32; all other
-// of the n_pairs stats pairs are initialised for atomic min/max and keys[0..n_keys) to all ones.
-// *d_flag (optional) is set to 0.
+// The same for tables of different sizes: table t is elements [d_off[t], d_off[t+1]) of d_tables
+// (d_off: device array of n_tables + 1 offsets); max_cells sizes the grid.
+hipError_t launch_ranges_var(const int32_t* d_tables, const int64_t* d_off, int32_t n_tables, int64_t max_cells,
+                             int32_t* d_stats, hipStream_t stream);
+// First launch of a search: w = tc + ts, row by row; row v is elements [v*C, (v+1)*C), or
+// [d_node_off[v], d_node_off[v+1]) if d_node_off (device, n_nodes + 1 offsets) is given.  Stats pair
+// w_pair0 + v receives {min, max} of row v of w, or {INT32_MAX, INT32_MIN} if a sum of that row
+// leaves int32; all other of the n_pairs stats pairs are initialised for atomic min/max and
+// keys[0..n_keys) to all ones.  *d_flag (optional) is set to 0.
 hipError_t launch_prepare_search(const int32_t* tc, const int32_t* ts, int32_t* w, int32_t n_nodes, int32_t C,
-                                 int32_t* d_stats, int32_t n_pairs, int32_t w_pair0, unsigned long long* d_keys,
-                                 int32_t n_keys, int32_t* d_flag, hipStream_t stream);
+                                 const int64_t* d_node_off, int32_t* d_stats, int32_t n_pairs, int32_t w_pair0,
+                                 unsigned long long* d_keys, int32_t n_keys, int32_t* d_flag, hipStream_t stream);
 
 // ---- residual graph and back-substitution (Alg. 1, enumeration of the final graph and undo) --
 struct PairDesc {       // residual component with two nodes joined by one edge
-    const int32_t* T;   // [C][C]
-    int32_t src, dst;
+    const int32_t* T;   // [Ci][Ck]
+    const int32_t* wi;  // t_c + t_s of the source node [Ci]
+    const int32_t* wk;  // of the destination node [Ck]
+    int32_t src, dst, Ci, Ck;
 };
-// Residual component with K > 2 nodes: all C^K strategies are enumerated (C^K <= 2^32).  Node
-// q of the component is digit q of the flat strategy index, digit 0 (lowest node id) most
-// significant.  Edge x joins digits src_pos[x] -> dst_pos[x] with table tab[x].
+struct SingleDesc {     // residual isolated node
+    const int32_t* w;   // [C]
+    int32_t node, C;
+};
+// Residual component with K > 2 nodes: all strategies are enumerated (their number <= 2^32).  Node
+// q of the component is digit q of the flat strategy index (radix Cn[q]), digit 0 (lowest node id)
+// most significant.  Edge x joins digits src_pos[x] -> dst_pos[x] with table tab[x]
+// [Cn[src_pos[x]]][Cn[dst_pos[x]]].
 constexpr int kCompMaxNodes = 12, kCompMaxEdges = 32;
 struct CompDesc {
     const int32_t* tab[kCompMaxEdges];
+    const int32_t* w[kCompMaxNodes];
     int32_t node[kCompMaxNodes];
+    int32_t Cn[kCompMaxNodes];
     int8_t src_pos[kCompMaxEdges], dst_pos[kCompMaxEdges];
     int32_t K, n_edges;
 };
 struct UndoDesc {       // one node elimination of the log
-    const int32_t* arg; // [C][C] stored argmin, or null: recompute from the three tables below
-    const int32_t* A;   // table of the in-edge (i,j) at the time of the elimination
-    const int32_t* w;   // t_c + t_s of node j
-    const int32_t* B;   // table of the out-edge (j,k)
+    const int32_t* arg; // [Ci][Ck] stored argmin, or null: recompute from the three tables below
+    const int32_t* A;   // table of the in-edge (i,j) at the time of the elimination [Ci][Cj]
+    const int32_t* w;   // t_c + t_s of node j [Cj]
+    const int32_t* B;   // table of the out-edge (j,k) [Cj][Ck]
     int32_t j, i, k, round;
+    int32_t Cj, Ck;
 };
 // keys[p] is a 64-bit (cost, flat index) minimum per component, initialised to all ones.
-// d_flag (optional) is OR-ed with 1 if a sum leaves int32.
-hipError_t launch_pair_min(const PairDesc* d_pairs, int32_t n_pairs, const int32_t* d_w, int32_t C,
+// d_flag (optional) is OR-ed with 1 if a sum leaves int32.  max_rows / max_c size the grids.
+hipError_t launch_pair_min(const PairDesc* d_pairs, int32_t n_pairs, int32_t max_rows,
                            unsigned long long* d_keys, int32_t* d_flag, hipStream_t stream);
-hipError_t launch_single_min(const int32_t* d_singles, int32_t n_singles, const int32_t* d_w, int32_t C,
+hipError_t launch_single_min(const SingleDesc* d_singles, int32_t n_singles, int32_t max_c,
                              unsigned long long* d_keys /* after the pairs */, hipStream_t stream);
-// One launch per component; key = d_keys[index of the component].
-hipError_t launch_component_min(const CompDesc* d_comp, int32_t K, const int32_t* d_w, int32_t C,
+// One launch per component; n_prefix = product of Cn[0..K-2]; key = d_keys[index of the component].
+hipError_t launch_component_min(const CompDesc* d_comp, unsigned long long n_prefix,
                                 unsigned long long* d_key, int32_t* d_flag, hipStream_t stream);
 // Decodes the component minima (keys: pairs, then singles, then enumerated components), then
 // walks the undo list backwards (entries of one round are independent).
 // result[0] = total cost low word, result[1] = high word, result[2..2+n_nodes) = strategy,
 // result[2+n_nodes] = *d_flag (0 if d_flag is null), OR 1 if one of the n_nodes stats pairs starting
 // at d_wstats is the impossible {INT32_MAX, INT32_MIN} (a row of t_c + t_s left int32).
-hipError_t launch_back_substitute(const PairDesc* d_pairs, int32_t n_pairs, const int32_t* d_singles,
+hipError_t launch_back_substitute(const PairDesc* d_pairs, int32_t n_pairs, const SingleDesc* d_singles,
                                   int32_t n_singles, const CompDesc* d_comps, int32_t n_comps,
                                   const unsigned long long* d_keys,
-                                  const UndoDesc* d_undo, int32_t n_undo, int32_t C, int32_t n_nodes,
+                                  const UndoDesc* d_undo, int32_t n_undo, int32_t n_nodes,
                                   const int32_t* d_flag, const int32_t* d_wstats, int32_t* d_result,
                                   hipStream_t stream);
 

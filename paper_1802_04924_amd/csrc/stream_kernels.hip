@@ -39,9 +39,9 @@ __device__ __forceinline__ unsigned long long wave_min_u64(unsigned long long v)
 
 // ---- Eq. 3 -----------------------------------------------------------------------------------
 __global__ __launch_bounds__(kThreads) void edge_sum_desc_kernel(const EdgeDesc* __restrict__ descs,
-                                                                 const int32_t* const* __restrict__ srcs,
-                                                                 int64_t cells) {
+                                                                 const int32_t* const* __restrict__ srcs) {
     const EdgeDesc d = descs[blockIdx.y];
+    const int64_t cells = d.cells;
     const int32_t* const* sp = srcs + d.first_src;
     const int n = d.n_src;
     bool vec = ((cells & 3) == 0) && ((((uintptr_t)d.out) & 15) == 0);
@@ -119,10 +119,13 @@ __global__ void init_workspace_kernel(int32_t* stats, int32_t n_tables, int32_t*
     if (flag && t == 0) *flag = 0;
 }
 
+// Table blockIdx.y is elements [y*cells, (y+1)*cells), or [off[y], off[y+1]) if off is given.
 __global__ __launch_bounds__(kThreads) void ranges_kernel(const int32_t* __restrict__ tables, int64_t cells,
+                                                          const int64_t* __restrict__ off,
                                                           int32_t* __restrict__ stats) {
     __shared__ int smin[kThreads / 64], smax[kThreads / 64];
-    const int32_t* T = tables + (int64_t)blockIdx.y * cells;
+    const int32_t* T = tables + (off ? off[blockIdx.y] : (int64_t)blockIdx.y * cells);
+    if (off) cells = off[blockIdx.y + 1] - off[blockIdx.y];
     int lo = 0x7fffffff, hi = (int32_t)0x80000000;
     const int64_t stride = (int64_t)gridDim.x * kThreads;
     const int64_t t0 = (int64_t)blockIdx.x * kThreads + threadIdx.x;
@@ -154,6 +157,7 @@ __global__ __launch_bounds__(kThreads) void ranges_kernel(const int32_t* __restr
 __global__ __launch_bounds__(kThreads) void prepare_search_kernel(const int32_t* __restrict__ tc,
                                                                   const int32_t* __restrict__ ts,
                                                                   int32_t* __restrict__ w, int32_t n_nodes, int32_t C,
+                                                                  const int64_t* __restrict__ node_off,
                                                                   int32_t* __restrict__ stats, int32_t n_pairs,
                                                                   int32_t w_pair0, unsigned long long* __restrict__ keys,
                                                                   int32_t n_keys, int32_t* __restrict__ flag) {
@@ -165,7 +169,8 @@ __global__ __launch_bounds__(kThreads) void prepare_search_kernel(const int32_t*
         return;
     }
     __shared__ int smin[kThreads / 64], smax[kThreads / 64], sbad[kThreads / 64];
-    const int64_t row = (int64_t)blockIdx.x * C;
+    const int64_t row = node_off ? node_off[blockIdx.x] : (int64_t)blockIdx.x * C;
+    if (node_off) C = (int32_t)(node_off[blockIdx.x + 1] - row);
     int bad = 0;
     int lo = 0x7fffffff, hi = (int32_t)0x80000000;
     for (int x = threadIdx.x; x < C; x += kThreads) {
@@ -205,22 +210,22 @@ __device__ __forceinline__ void block_min_to(unsigned long long v, unsigned long
 
 // min over (a,b) of w_i[a] + T[a][b] + w_k[b]; grid.y = component
 __global__ __launch_bounds__(kThreads) void pair_min_kernel(const PairDesc* __restrict__ pairs,
-                                                            const int32_t* __restrict__ w, int32_t C,
                                                             unsigned long long* __restrict__ keys,
                                                             int32_t* __restrict__ flag) {
     const PairDesc d = pairs[blockIdx.y];
-    const int32_t* wi = w + (int64_t)d.src * C;
-    const int32_t* wk = w + (int64_t)d.dst * C;
+    const gi32c wi = (gi32c)(uintptr_t)d.wi;
+    const gi32c wk = (gi32c)(uintptr_t)d.wk;
+    const int Ci = d.Ci, Ck = d.Ck;
     unsigned long long best = ~0ull;
     bool bad = false;
-    for (int a = blockIdx.x; a < C; a += gridDim.x) {
+    for (int a = blockIdx.x; a < Ci; a += gridDim.x) {
         const int32_t wa = wi[a];
-        const gi32c Trow = (gi32c)(uintptr_t)d.T + (int64_t)a * C;
-        for (int b = threadIdx.x; b < C; b += kThreads) {
+        const gi32c Trow = (gi32c)(uintptr_t)d.T + (int64_t)a * Ck;
+        for (int b = threadIdx.x; b < Ck; b += kThreads) {
             const long long s64 = (long long)wa + Trow[b] + wk[b];
             const int32_t s = (int32_t)s64;
             bad |= (s64 != (long long)s);
-            const unsigned long long k = make_key(s, (uint32_t)a * (uint32_t)C + (uint32_t)b);
+            const unsigned long long k = make_key(s, (uint32_t)a * (uint32_t)Ck + (uint32_t)b);
             best = k < best ? k : best;
         }
     }
@@ -229,10 +234,10 @@ __global__ __launch_bounds__(kThreads) void pair_min_kernel(const PairDesc* __re
 }
 
 // min over a of w[a]; grid.y = isolated node
-__global__ __launch_bounds__(kThreads) void single_min_kernel(const int32_t* __restrict__ singles,
-                                                              const int32_t* __restrict__ w, int32_t C,
+__global__ __launch_bounds__(kThreads) void single_min_kernel(const SingleDesc* __restrict__ singles,
                                                               unsigned long long* __restrict__ keys) {
-    const int32_t* wl = w + (int64_t)singles[blockIdx.y] * C;
+    const gi32c wl = (gi32c)(uintptr_t)singles[blockIdx.y].w;
+    const int C = singles[blockIdx.y].C;
     unsigned long long best = ~0ull;
     for (int x = blockIdx.x * kThreads + threadIdx.x; x < C; x += gridDim.x * kThreads) {
         const unsigned long long k = make_key(wl[x], (uint32_t)x);
@@ -243,10 +248,9 @@ __global__ __launch_bounds__(kThreads) void single_min_kernel(const int32_t* __r
 
 // Enumeration of a residual component (Alg. 1: the final graph's strategies are enumerated).  One
 // thread per assignment of the first K-1 nodes; the last node's configurations are an inner loop.
-// The flat index p*C + c ascends lexicographically (lowest node id most significant), so the 64-bit
-// (cost, index) minimum is the lexicographically lowest optimum.
+// The flat (mixed-radix) index ascends lexicographically (lowest node id most significant), so the
+// 64-bit (cost, index) minimum is the lexicographically lowest optimum.
 __global__ __launch_bounds__(kThreads) void component_min_kernel(const CompDesc* __restrict__ comp,
-                                                                 const int32_t* __restrict__ w, int32_t C,
                                                                  unsigned long long n_prefix,
                                                                  unsigned long long* __restrict__ key,
                                                                  int32_t* __restrict__ flag) {
@@ -261,17 +265,18 @@ __global__ __launch_bounds__(kThreads) void component_min_kernel(const CompDesc*
     for (unsigned long long p = (unsigned long long)blockIdx.x * kThreads + threadIdx.x; p < n_prefix; p += stride) {
         int digit[kCompMaxNodes];
         unsigned long long r = p;
-        for (int q = last - 1; q >= 0; --q) { digit[q] = (int)(r % (unsigned)C); r /= (unsigned)C; }
+        for (int q = last - 1; q >= 0; --q) { digit[q] = (int)(r % (unsigned)d.Cn[q]); r /= (unsigned)d.Cn[q]; }
         long long base = 0;
-        for (int q = 0; q < last; ++q) base += w[(int64_t)d.node[q] * C + digit[q]];
+        for (int q = 0; q < last; ++q) base += ((gi32c)(uintptr_t)d.w[q])[digit[q]];
         for (int x = 0; x < ne; ++x)
             if (d.src_pos[x] != last && d.dst_pos[x] != last)
-                base += ((gi32c)(uintptr_t)d.tab[x])[(int64_t)digit[d.src_pos[x]] * C + digit[d.dst_pos[x]]];
-        const int32_t* wl = w + (int64_t)d.node[last] * C;
+                base += ((gi32c)(uintptr_t)d.tab[x])[(int64_t)digit[d.src_pos[x]] * d.Cn[d.dst_pos[x]] + digit[d.dst_pos[x]]];
+        const gi32c wl = (gi32c)(uintptr_t)d.w[last];
+        const int C = d.Cn[last];
         for (int c = 0; c < C; ++c) {
             long long t = base + wl[c];
             for (int x = 0; x < ne; ++x) {
-                if (d.src_pos[x] == last) t += ((gi32c)(uintptr_t)d.tab[x])[(int64_t)c * C + digit[d.dst_pos[x]]];
+                if (d.src_pos[x] == last) t += ((gi32c)(uintptr_t)d.tab[x])[(int64_t)c * d.Cn[d.dst_pos[x]] + digit[d.dst_pos[x]]];
                 else if (d.dst_pos[x] == last) t += ((gi32c)(uintptr_t)d.tab[x])[(int64_t)digit[d.src_pos[x]] * C + c];
             }
             bad |= (t != (long long)(int32_t)t);
@@ -287,9 +292,9 @@ __global__ __launch_bounds__(kThreads) void component_min_kernel(const CompDesc*
 // One workgroup of 1024 threads: the recomputing form keeps 16 wavefronts busy per round.
 constexpr int kUndoThreads = 1024;
 __global__ __launch_bounds__(kUndoThreads) void back_substitute_kernel(
-    const PairDesc* __restrict__ pairs, int32_t n_pairs, const int32_t* __restrict__ singles, int32_t n_singles,
+    const PairDesc* __restrict__ pairs, int32_t n_pairs, const SingleDesc* __restrict__ singles, int32_t n_singles,
     const CompDesc* __restrict__ comps, int32_t n_comps,
-    const unsigned long long* __restrict__ keys, const UndoDesc* __restrict__ undo, int32_t n_undo, int32_t C,
+    const unsigned long long* __restrict__ keys, const UndoDesc* __restrict__ undo, int32_t n_undo,
     int32_t n_nodes, const int32_t* __restrict__ flag, const int32_t* __restrict__ wstats,
     int32_t* __restrict__ result) {
     __shared__ long long ssum[kUndoThreads / 64];
@@ -299,11 +304,13 @@ __global__ __launch_bounds__(kUndoThreads) void back_substitute_kernel(
         const unsigned long long k = keys[t];
         uint32_t flat = (uint32_t)k;
         cost += (long long)(int32_t)((uint32_t)(k >> 32) ^ 0x80000000u);
-        if (t < n_pairs) { S[pairs[t].src] = (int32_t)(flat / (uint32_t)C); S[pairs[t].dst] = (int32_t)(flat % (uint32_t)C); }
-        else if (t < n_pairs + n_singles) S[singles[t - n_pairs]] = (int32_t)flat;
+        if (t < n_pairs) {
+            const uint32_t Ck = (uint32_t)pairs[t].Ck;
+            S[pairs[t].src] = (int32_t)(flat / Ck); S[pairs[t].dst] = (int32_t)(flat % Ck);
+        } else if (t < n_pairs + n_singles) S[singles[t - n_pairs].node] = (int32_t)flat;
         else {
             const CompDesc* cd = comps + (t - n_pairs - n_singles);
-            for (int q = cd->K - 1; q >= 0; --q) { S[cd->node[q]] = (int32_t)(flat % (uint32_t)C); flat /= (uint32_t)C; }
+            for (int q = cd->K - 1; q >= 0; --q) { S[cd->node[q]] = (int32_t)(flat % (uint32_t)cd->Cn[q]); flat /= (uint32_t)cd->Cn[q]; }
         }
     }
 #pragma unroll
@@ -325,19 +332,19 @@ __global__ __launch_bounds__(kUndoThreads) void back_substitute_kernel(
         if (undo[lo].arg) {
             for (int t = lo + threadIdx.x; t < hi; t += kUndoThreads) {
                 const UndoDesc u = undo[t];
-                S[u.j] = ((gi32c)(uintptr_t)u.arg)[(int64_t)S[u.i] * C + S[u.k]];
+                S[u.j] = ((gi32c)(uintptr_t)u.arg)[(int64_t)S[u.i] * u.Ck + S[u.k]];
             }
         } else {
             // no stored argmin: c_j = lowest c minimising A[S_i][c] + w[c] + B[c][S_k] (the paper's
             // own undo step); one wavefront per elimination
             for (int t = lo + (threadIdx.x >> 6); t < hi; t += kUndoThreads / 64) {
                 const UndoDesc u = undo[t];
-                const gi32c Arow = (gi32c)(uintptr_t)u.A + (int64_t)S[u.i] * C;
+                const gi32c Arow = (gi32c)(uintptr_t)u.A + (int64_t)S[u.i] * u.Cj;
                 const gi32c Bcol = (gi32c)(uintptr_t)u.B + S[u.k];
                 const gi32c wj = (gi32c)(uintptr_t)u.w;
                 unsigned long long best = ~0ull;
-                for (int c = threadIdx.x & 63; c < C; c += 64) {
-                    const unsigned long long k = make_key(Arow[c] + wj[c] + Bcol[(int64_t)c * C], (uint32_t)c);
+                for (int c = threadIdx.x & 63; c < u.Cj; c += 64) {
+                    const unsigned long long k = make_key(Arow[c] + wj[c] + Bcol[(int64_t)c * u.Ck], (uint32_t)c);
                     best = k < best ? k : best;
                 }
                 best = wave_min_u64(best);
@@ -368,11 +375,11 @@ inline unsigned blocks_for(int64_t work_items, int64_t per_thread, unsigned cap)
 }  // namespace
 
 hipError_t launch_edge_sum_desc(const EdgeDesc* d_descs, const int32_t* const* d_src_ptrs, int32_t n_desc,
-                                int64_t cells, hipStream_t stream) {
+                                int64_t max_cells, hipStream_t stream) {
     for (int32_t t0 = 0; t0 < n_desc; t0 += 65535) {
         const int32_t n = (n_desc - t0) < 65535 ? (n_desc - t0) : 65535;
-        dim3 grid(blocks_for(cells, 16, 2048), (unsigned)n);
-        hipLaunchKernelGGL(edge_sum_desc_kernel, grid, dim3(kThreads), 0, stream, d_descs + t0, d_src_ptrs, cells);
+        dim3 grid(blocks_for(max_cells, 16, 2048), (unsigned)n);
+        hipLaunchKernelGGL(edge_sum_desc_kernel, grid, dim3(kThreads), 0, stream, d_descs + t0, d_src_ptrs);
     }
     return hipGetLastError();
 }
@@ -400,60 +407,71 @@ hipError_t launch_ranges(const int32_t* d_tables, int32_t n_tables, int64_t cell
         const int32_t n = (n_tables - t0) < 65535 ? (n_tables - t0) : 65535;
         dim3 grid(blocks_for(cells, 16, cap), (unsigned)n);
         hipLaunchKernelGGL(ranges_kernel, grid, dim3(kThreads), 0, stream, d_tables + (int64_t)t0 * cells, cells,
+                           (const int64_t*)nullptr, d_stats + 2 * (int64_t)t0);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_ranges_var(const int32_t* d_tables, const int64_t* d_off, int32_t n_tables, int64_t max_cells,
+                             int32_t* d_stats, hipStream_t stream) {
+    if (n_tables <= 0) return hipSuccess;
+    unsigned cap = n_tables >= 64 ? 64u : (n_tables >= 8 ? 512u : 4096u);
+    for (int32_t t0 = 0; t0 < n_tables; t0 += 65535) {
+        const int32_t n = (n_tables - t0) < 65535 ? (n_tables - t0) : 65535;
+        dim3 grid(blocks_for(max_cells, 16, cap), (unsigned)n);
+        hipLaunchKernelGGL(ranges_kernel, grid, dim3(kThreads), 0, stream, d_tables, (int64_t)0, d_off + t0,
                            d_stats + 2 * (int64_t)t0);
     }
     return hipGetLastError();
 }
 
 hipError_t launch_prepare_search(const int32_t* tc, const int32_t* ts, int32_t* w, int32_t n_nodes, int32_t C,
-                                 int32_t* d_stats, int32_t n_pairs, int32_t w_pair0, unsigned long long* d_keys,
-                                 int32_t n_keys, int32_t* d_flag, hipStream_t stream) {
+                                 const int64_t* d_node_off, int32_t* d_stats, int32_t n_pairs, int32_t w_pair0,
+                                 unsigned long long* d_keys, int32_t n_keys, int32_t* d_flag, hipStream_t stream) {
     const int n_init = (n_pairs > n_keys ? n_pairs : n_keys) + 1;
     dim3 grid((unsigned)(n_nodes + (n_init + kThreads - 1) / kThreads));
-    hipLaunchKernelGGL(prepare_search_kernel, grid, dim3(kThreads), 0, stream, tc, ts, w, n_nodes, C, d_stats, n_pairs,
-                       w_pair0, d_keys, n_keys, d_flag);
+    hipLaunchKernelGGL(prepare_search_kernel, grid, dim3(kThreads), 0, stream, tc, ts, w, n_nodes, C, d_node_off, d_stats,
+                       n_pairs, w_pair0, d_keys, n_keys, d_flag);
     return hipGetLastError();
 }
 
-hipError_t launch_pair_min(const PairDesc* d_pairs, int32_t n_pairs, const int32_t* d_w, int32_t C,
+hipError_t launch_pair_min(const PairDesc* d_pairs, int32_t n_pairs, int32_t max_rows,
                            unsigned long long* d_keys, int32_t* d_flag, hipStream_t stream) {
     for (int32_t t0 = 0; t0 < n_pairs; t0 += 65535) {
         const int32_t n = (n_pairs - t0) < 65535 ? (n_pairs - t0) : 65535;
-        const unsigned rows = (unsigned)C < 2048u ? (unsigned)C : 2048u;
+        const unsigned rows = (unsigned)max_rows < 2048u ? (unsigned)(max_rows < 1 ? 1 : max_rows) : 2048u;
         dim3 grid(rows, (unsigned)n);
-        hipLaunchKernelGGL(pair_min_kernel, grid, dim3(kThreads), 0, stream, d_pairs + t0, d_w, C, d_keys + t0, d_flag);
+        hipLaunchKernelGGL(pair_min_kernel, grid, dim3(kThreads), 0, stream, d_pairs + t0, d_keys + t0, d_flag);
     }
     return hipGetLastError();
 }
 
-hipError_t launch_single_min(const int32_t* d_singles, int32_t n_singles, const int32_t* d_w, int32_t C,
+hipError_t launch_single_min(const SingleDesc* d_singles, int32_t n_singles, int32_t max_c,
                              unsigned long long* d_keys, hipStream_t stream) {
     for (int32_t t0 = 0; t0 < n_singles; t0 += 65535) {
         const int32_t n = (n_singles - t0) < 65535 ? (n_singles - t0) : 65535;
-        dim3 grid(blocks_for(C, 4, 64), (unsigned)n);
-        hipLaunchKernelGGL(single_min_kernel, grid, dim3(kThreads), 0, stream, d_singles + t0, d_w, C, d_keys + t0);
+        dim3 grid(blocks_for(max_c, 4, 64), (unsigned)n);
+        hipLaunchKernelGGL(single_min_kernel, grid, dim3(kThreads), 0, stream, d_singles + t0, d_keys + t0);
     }
     return hipGetLastError();
 }
 
-hipError_t launch_component_min(const CompDesc* d_comp, int32_t K, const int32_t* d_w, int32_t C,
+hipError_t launch_component_min(const CompDesc* d_comp, unsigned long long n_prefix,
                                 unsigned long long* d_key, int32_t* d_flag, hipStream_t stream) {
-    unsigned long long n_prefix = 1;
-    for (int q = 0; q + 1 < K; ++q) n_prefix *= (unsigned long long)C;
     unsigned long long blocks = (n_prefix + kThreads - 1) / kThreads;
     if (blocks > 65536) blocks = 65536;
-    hipLaunchKernelGGL(component_min_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, d_comp, d_w, C, n_prefix, d_key, d_flag);
+    hipLaunchKernelGGL(component_min_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, d_comp, n_prefix, d_key, d_flag);
     return hipGetLastError();
 }
 
-hipError_t launch_back_substitute(const PairDesc* d_pairs, int32_t n_pairs, const int32_t* d_singles,
+hipError_t launch_back_substitute(const PairDesc* d_pairs, int32_t n_pairs, const SingleDesc* d_singles,
                                   int32_t n_singles, const CompDesc* d_comps, int32_t n_comps,
                                   const unsigned long long* d_keys,
-                                  const UndoDesc* d_undo, int32_t n_undo, int32_t C, int32_t n_nodes,
+                                  const UndoDesc* d_undo, int32_t n_undo, int32_t n_nodes,
                                   const int32_t* d_flag, const int32_t* d_wstats, int32_t* d_result,
                                   hipStream_t stream) {
     hipLaunchKernelGGL(back_substitute_kernel, dim3(1), dim3(kUndoThreads), 0, stream, d_pairs, n_pairs, d_singles,
-                       n_singles, d_comps, n_comps, d_keys, d_undo, n_undo, C, n_nodes, d_flag, d_wstats, d_result);
+                       n_singles, d_comps, n_comps, d_keys, d_undo, n_undo, n_nodes, d_flag, d_wstats, d_result);
     return hipGetLastError();
 }
 
