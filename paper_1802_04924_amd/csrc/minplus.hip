@@ -49,7 +49,7 @@ __device__ __forceinline__ int wave_max_i32(int v) {
 }
 
 template <int MODE, int RB, int TK>
-__global__ __launch_bounds__(NT, MODE == kModePlain ? 1 : 2) void minplus_kernel(const NodeArgs p) {
+__global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) void minplus_kernel(const NodeArgs p) {
     constexpr bool KEYED = (MODE == kModeKeyed);
     constexpr bool VALUE = (MODE == kModeValue);   // minimum only: no argmin, no keys, any int32
     constexpr int TM = 16 * RB, TN = 16 * RB;   // output tile
@@ -187,17 +187,22 @@ __global__ __launch_bounds__(NT, MODE == kModePlain ? 1 : 2) void minplus_kernel
         }
         pA += TK; pW += TK; pB += (int64_t)TK * Ck;
     };
-    // Keys: A side ((A + w - offA, clamped) << tb) + low field - (offB << tb), B side B << tb.  The
-    // re-basing of B rides on the A side (arithmetic is modulo 2^32 and the true sum is in range),
-    // so B costs one shift.  pos0 = position of c0 inside its chunk; the low field is 1 + position.
-    const uint32_t boff = KEYED ? ((uint32_t)offB << tb) : 0u;
+    // Keys: A side ((A + w - offA, clamped) << tb) - (offB << tb), B side (B << tb) + low field.
+    // The re-basing of B rides on the A side (arithmetic is modulo 2^32 and the true sum is in
+    // range); the low field, 1 + position of c inside its chunk, rides on the B side, where all
+    // elements a thread stages share one c.  That makes three operations per A element (a
+    // three-operand add, the clamp, shift-and-add) and one per B element (shift-and-add).
+    const uint32_t nboff = KEYED ? 0u - ((uint32_t)offB << tb) : 0u;
+    const uint32_t noffA = 0u - (uint32_t)offA;
     auto stash = [&](int c0, int pos0, int buf) {
-        const uint32_t pos = (uint32_t)(pos0 + lseg + 1) - boff;
+        const uint32_t pos = (uint32_t)(pos0 + br + 1);
         uint32_t ka[EP], kb[EP];
 #pragma unroll
         for (int q = 0; q < EP; ++q) {
-            if (KEYED) { ka[q] = (min((uint32_t)(ra[q] + rw[q] - offA), cap) << tb) + (pos + q); kb[q] = (uint32_t)rb[q] << tb; }
-            else { ka[q] = (uint32_t)(ra[q] + rw[q]); kb[q] = (uint32_t)rb[q]; }
+            if (KEYED) {
+                ka[q] = (min((uint32_t)ra[q] + (uint32_t)rw[q] + noffA, cap) << tb) + nboff;
+                kb[q] = ((uint32_t)rb[q] << tb) + pos;
+            } else { ka[q] = (uint32_t)(ra[q] + rw[q]); kb[q] = (uint32_t)rb[q]; }
         }
         // value-only mode needs no padding: the clamped loads repeat the last candidate
         if (!VALUE && c0 + TK > Cj) {             // only the last stage can be ragged
