@@ -175,6 +175,43 @@ def search_ragged(n_nodes, edges, Cn, tc, ts, tx, schedule=SCHEDULE_ROUNDS):
     return {"cost": cost.value, "strategy": S, "steps": steps[:n_steps.value], "n_rounds": n_rounds.value}
 
 
+def _machine(machine):
+    return np.array([machine["n_devices"], machine["flop_per_ns"], machine["byte_per_ns"],
+                     machine["invalid_cost"]], np.int32)
+
+
+def enumerate_configs(layer, n_devices):
+    """Configurations of one layer (Sec. 4 / Table 1, reading in cost_model_oracle.c): int32 [C][6]."""
+    lib = _load()
+    layer = _c(layer).reshape(14)
+    n = lib.orc_enumerate_configs(_p(layer), int(n_devices), None, 0)
+    out = np.zeros((n, 6), np.int32)
+    assert lib.orc_enumerate_configs(_p(layer), int(n_devices), _p(out), n) == n
+    return out
+
+
+def build_cost_tables_ragged(layers, edges, configs, Cn, machine):
+    """Cost tables with a configuration list per layer (lists concatenated in ``configs``).
+
+    Returns flat (tc, ts, tx) in the layout search_ragged takes."""
+    lib = _load()
+    layers = _c(layers).reshape(-1, 14)
+    edges = _c(edges).reshape(-1, 2)
+    configs = _c(configs).reshape(-1, 6)
+    Cn = _c(Cn).reshape(-1)
+    if len(Cn) != len(layers) or int(Cn.sum()) != len(configs):
+        raise ValueError("Cn must have one entry per layer and sum to the number of rows")
+    m = _machine(machine)
+    total = int(Cn.astype(np.int64).sum())
+    cells = int(sum(int(Cn[i]) * int(Cn[j]) for i, j in edges))
+    tc, ts, tx = np.empty(total, np.int32), np.empty(total, np.int32), np.empty(cells, np.int32)
+    rc = lib.orc_build_cost_tables_ragged(_p(layers), len(layers), _p(edges), len(edges), _p(configs), _p(Cn),
+                                          _p(m), _p(tc), _p(ts), _p(tx))
+    if rc:
+        raise OracleError(rc, "build_cost_tables_ragged")
+    return tc, ts, tx
+
+
 def build_cost_tables(layers, edges, configs, machine):
     """Analytic cost model of Sec. 5.1 (readings in cost_model_oracle.c): returns (tc, ts, tx)."""
     lib = _load()

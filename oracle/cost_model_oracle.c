@@ -70,14 +70,21 @@ static int64_t overlap(int64_t a0, int64_t a1, int64_t b0, int64_t b1)
     return imax(0, imin(a1, b1) - imax(a0, b0));
 }
 
-int orc_build_cost_tables(const orc_layer *layers, int n_layers, const int32_t *edges, int n_edges,
-                          const orc_config *cfgs, int C, const orc_machine *m,
-                          int32_t *tc, int32_t *ts, int32_t *tx)
+/* The three tables when layer l has its own list of configurations: rows
+ * cfgs[cfg_off[l] .. cfg_off[l] + Cn[l]).  t_c and t_s are the layers' rows one after another
+ * (row l starts at node_off[l]); t_x holds the edges' tables [Cn[src]][Cn[dst]] one after another
+ * (table e starts at tx_off[e]). */
+static int build_tables(const orc_layer *layers, int n_layers, const int32_t *edges, int n_edges,
+                        const orc_config *cfgs, const int64_t *cfg_off, const int32_t *Cn,
+                        const int64_t *node_off, const int64_t *tx_off, const orc_machine *m,
+                        int32_t *tc, int32_t *ts, int32_t *tx)
 {
-    if (n_layers <= 0 || C <= 0 || m->flop_per_ns <= 0 || m->byte_per_ns <= 0) return ORC_E_INVAL;
+    if (n_layers <= 0 || m->flop_per_ns <= 0 || m->byte_per_ns <= 0) return ORC_E_INVAL;
+    for (int l = 0; l < n_layers; ++l) if (Cn[l] <= 0) return ORC_E_INVAL;
     int overflow = 0;
     for (int l = 0; l < n_layers; ++l) {
         const orc_layer *L = &layers[l];
+        const int C = Cn[l];
         int64_t F, P;
         if (L->kind == KIND_CONV) {
             F = 3 * 2 * (int64_t)L->N * L->Cout * L->Hout * L->Wout * L->Cin * L->kh * L->kw;
@@ -90,7 +97,7 @@ int orc_build_cost_tables(const orc_layer *layers, int n_layers, const int32_t *
             P = 0;
         } else return ORC_E_INVAL;
         for (int r = 0; r < C; ++r) {
-            const orc_config *c = &cfgs[r];
+            const orc_config *c = &cfgs[cfg_off[l] + r];
             int64_t vc = m->invalid_cost, vs = 0;
             if (config_valid(L, c, m)) {
                 int64_t d = (int64_t)c->n * c->h * c->w * c->c;
@@ -99,8 +106,8 @@ int orc_build_cost_tables(const orc_layer *layers, int n_layers, const int32_t *
                 vs = round_div(P * (rep - 1), rep * m->byte_per_ns);
             }
             if (vc > INT32_MAX || vs > INT32_MAX) overflow = 1;
-            tc[(size_t)l * C + r] = (int32_t)vc;
-            ts[(size_t)l * C + r] = (int32_t)vs;
+            tc[node_off[l] + r] = (int32_t)vc;
+            ts[node_off[l] + r] = (int32_t)vs;
         }
     }
     for (int e = 0; e < n_edges; ++e) {
@@ -109,11 +116,12 @@ int orc_build_cost_tables(const orc_layer *layers, int n_layers, const int32_t *
         const orc_layer *Pl = &layers[pi], *Cl = &layers[ci];
         /* the tensor on the edge: the producer's output is the consumer's input */
         if (Pl->N != Cl->N || Pl->Cout != Cl->Cin || Pl->Hout != Cl->Hin || Pl->Wout != Cl->Win) return ORC_E_INVAL;
+        const int Ca = Cn[pi], Cb = Cn[ci];
 #pragma omp parallel for schedule(dynamic, 4) reduction(| : overflow)
-        for (int a = 0; a < C; ++a) {
-            const orc_config *ca = &cfgs[a];
-            for (int b = 0; b < C; ++b) {
-                const orc_config *cb = &cfgs[b];
+        for (int a = 0; a < Ca; ++a) {
+            const orc_config *ca = &cfgs[cfg_off[pi] + a];
+            for (int b = 0; b < Cb; ++b) {
+                const orc_config *cb = &cfgs[cfg_off[ci] + b];
                 int64_t cells = 0;
                 if (config_valid(Pl, ca, m) && config_valid(Cl, cb, m)) {
                     for (int pn = 0; pn < ca->n; ++pn) for (int ph = 0; ph < ca->h; ++ph)
@@ -147,9 +155,72 @@ int orc_build_cost_tables(const orc_layer *layers, int n_layers, const int32_t *
                 }
                 int64_t v = round_div(4 * cells, m->byte_per_ns);
                 if (v > INT32_MAX) overflow = 1;
-                tx[((size_t)e * C + a) * C + b] = (int32_t)v;
+                tx[tx_off[e] + (int64_t)a * Cb + b] = (int32_t)v;
             }
         }
     }
     return overflow ? ORC_E_OVERFLOW : ORC_OK;
+}
+
+/* One list of C configurations shared by all layers: t_c, t_s [n_layers][C], t_x [n_edges][C][C]. */
+int orc_build_cost_tables(const orc_layer *layers, int n_layers, const int32_t *edges, int n_edges,
+                          const orc_config *cfgs, int C, const orc_machine *m,
+                          int32_t *tc, int32_t *ts, int32_t *tx)
+{
+    if (n_layers <= 0 || C <= 0 || n_edges < 0) return ORC_E_INVAL;
+    int64_t *cfg_off = calloc((size_t)n_layers, sizeof(int64_t));
+    int64_t *node_off = malloc((size_t)n_layers * sizeof(int64_t));
+    int64_t *tx_off = malloc((size_t)(n_edges + 1) * sizeof(int64_t));
+    int32_t *Cn = malloc((size_t)n_layers * sizeof(int32_t));
+    for (int l = 0; l < n_layers; ++l) { node_off[l] = (int64_t)l * C; Cn[l] = C; }
+    for (int e = 0; e < n_edges; ++e) tx_off[e] = (int64_t)e * C * C;
+    int rc = build_tables(layers, n_layers, edges, n_edges, cfgs, cfg_off, Cn, node_off, tx_off, m, tc, ts, tx);
+    free(cfg_off); free(node_off); free(tx_off); free(Cn);
+    return rc;
+}
+
+/* Per-layer lists, concatenated in layer order in cfgs; Cn[l] rows for layer l. */
+int orc_build_cost_tables_ragged(const orc_layer *layers, int n_layers, const int32_t *edges, int n_edges,
+                                 const orc_config *cfgs, const int32_t *Cn, const orc_machine *m,
+                                 int32_t *tc, int32_t *ts, int32_t *tx)
+{
+    if (n_layers <= 0 || n_edges < 0) return ORC_E_INVAL;
+    for (int e = 0; e < n_edges; ++e)
+        if (edges[2 * e] < 0 || edges[2 * e] >= n_layers || edges[2 * e + 1] < 0 || edges[2 * e + 1] >= n_layers)
+            return ORC_E_INVAL;
+    int64_t *cfg_off = malloc((size_t)(n_layers + 1) * sizeof(int64_t));
+    int64_t *tx_off = malloc((size_t)(n_edges + 1) * sizeof(int64_t));
+    cfg_off[0] = 0;
+    for (int l = 0; l < n_layers; ++l) cfg_off[l + 1] = cfg_off[l] + Cn[l];
+    tx_off[0] = 0;
+    for (int e = 0; e < n_edges; ++e) tx_off[e + 1] = tx_off[e] + (int64_t)Cn[edges[2 * e]] * Cn[edges[2 * e + 1]];
+    int rc = build_tables(layers, n_layers, edges, n_edges, cfgs, cfg_off, Cn, cfg_off, tx_off, m, tc, ts, tx);
+    free(cfg_off); free(tx_off);
+    return rc;
+}
+
+/* The configurations of one layer (Sec. 4: a degree of parallelism per parallelizable dimension,
+ * Table 1; equal partitioning): all (n, h, w, c) of powers of two whose product d does not exceed
+ * the number of devices and whose degrees do not exceed the layer's extents (a fully connected
+ * layer splits only sample and channel), each with every device block [offset, offset + d) whose
+ * offset is a multiple of d.  Order: ascending (n, h, w, c, offset).
+ * Returns the count; writes at most cap rows. */
+int orc_enumerate_configs(const orc_layer *L, int n_devices, orc_config *out, int cap)
+{
+    int count = 0;
+    for (int n = 1; n <= n_devices && n <= L->N; n *= 2)
+        for (int h = 1; n * h <= n_devices && h <= L->Hout; h *= 2)
+            for (int w = 1; n * h * w <= n_devices && w <= L->Wout; w *= 2)
+                for (int c = 1; n * h * w * c <= n_devices && c <= L->Cout; c *= 2) {
+                    if (L->kind == KIND_FC && (h != 1 || w != 1)) continue;
+                    const int d = n * h * w * c;
+                    for (int off = 0; off + d <= n_devices; off += d) {
+                        if (count < cap) {
+                            orc_config r = { n, h, w, c, off, 0 };
+                            out[count] = r;
+                        }
+                        ++count;
+                    }
+                }
+    return count;
 }

@@ -171,3 +171,71 @@ def test_search_on_the_alexnet_tables_beats_the_uniform_strategies():
     data_par = [rows[(16, 1, 1, 1, 0)]] * 11
     assert r["cost"] <= oracle.strategy_cost(11, p["edges"], 256, tc, ts, tx, data_par)
     assert (tc[np.arange(11), r["strategy"]] < p["machine"]["invalid_cost"]).all()
+
+
+# ---- configuration sets per layer (Sec. 4, Table 1) and tables built from them ------------------
+def test_enumeration_counts_follow_the_closed_form():
+    # power-of-two degrees over D parallelizable dimensions with product 2^k: binom(k+D-1, D-1)
+    # tuples, each with n_devices / 2^k aligned device blocks
+    from math import comb
+    big_conv = conv(64, 64, 64, 64, 3, 1, 1)          # no degree exceeds an extent
+    big_fc = fc(64, 64, 1, 64)
+    for n_dev in (1, 2, 4, 8, 16, 32):
+        K = n_dev.bit_length() - 1
+        assert len(oracle.enumerate_configs(big_conv, n_dev)) == sum(comb(k + 3, 3) * (n_dev >> k) for k in range(K + 1))
+        assert len(oracle.enumerate_configs(big_fc, n_dev)) == sum((k + 1) * (n_dev >> k) for k in range(K + 1))
+    assert len(oracle.enumerate_configs(big_conv, 16)) == 163
+    assert len(oracle.enumerate_configs(big_fc, 16)) == 57
+    # a machine that is not a power of two: blocks [0,d), [d,2d), ... that fit
+    rows = oracle.enumerate_configs(big_fc, 6)
+    assert sorted(map(tuple, rows[:, [0, 3, 4]])) == sorted(
+        [(1, 1, o) for o in range(6)] + [(1, 2, o) for o in (0, 2, 4)] + [(2, 1, o) for o in (0, 2, 4)] +
+        [(1, 4, 0), (2, 2, 0), (4, 1, 0)])
+
+
+def test_enumeration_is_the_valid_part_of_the_full_table():
+    # independent generator of the full table (no layer limits) + validity as the cost model sees it
+    full = wl.config_table(16, 163)
+    for layer in list(wl.alexnet_layers(256)) + [conv(2, 3, 5, 3, 3, 1, 1), fc(1, 8, 1, 2), pool(8, 2, 4, 2, 2)]:
+        tc, _, _ = oracle.build_cost_tables(np.asarray([layer], np.int32), np.zeros((0, 2), np.int32), full, M)
+        valid = full[tc[0] != M["invalid_cost"]]
+        rows = oracle.enumerate_configs(layer, 16)
+        assert np.array_equal(rows, valid)
+        assert (np.diff([tuple(r) for r in rows[:, :5]], axis=0) != 0).any(axis=1).all()    # no duplicates
+    assert np.array_equal(oracle.enumerate_configs(conv(64, 64, 64, 64, 3, 1, 1), 16), full)
+
+
+def ragged_alexnet(batch=256):
+    layers = wl.alexnet_layers(batch)
+    lists = [oracle.enumerate_configs(l, 16) for l in layers]
+    Cn = np.array([len(x) for x in lists], np.int32)
+    return layers, wl.chain_edges(len(layers)), lists, Cn
+
+
+def test_ragged_tables_are_subtables_of_the_uniform_ones():
+    layers, edges, lists, Cn = ragged_alexnet()
+    full = wl.config_table(16, 256)
+    tc, ts, tx = oracle.build_cost_tables(layers, edges, full, M)
+    rtc, rts, rtx = oracle.build_cost_tables_ragged(layers, edges, np.concatenate(lists), Cn, M)
+    key = {tuple(r[:5]): i for i, r in enumerate(full[:163])}
+    idx = [np.array([key[tuple(r[:5])] for r in rows]) for rows in lists]
+    assert Cn.max() == 163 and Cn.min() < 60 and len(set(Cn.tolist())) > 2
+    assert np.array_equal(rtc, np.concatenate([tc[l][idx[l]] for l in range(len(layers))]))
+    assert np.array_equal(rts, np.concatenate([ts[l][idx[l]] for l in range(len(layers))]))
+    assert np.array_equal(rtx, np.concatenate([tx[e][np.ix_(idx[i], idx[j])].reshape(-1) for e, (i, j) in enumerate(edges)]))
+    assert (rtc != M["invalid_cost"]).all()
+
+
+def test_search_on_ragged_tables_finds_the_same_strategy():
+    # rows that are invalid for a layer can never win, and dropping them keeps the order of the
+    # rest, so the lowest-index rule picks the same configurations
+    layers, edges, lists, Cn = ragged_alexnet()
+    full = wl.config_table(16, 256)
+    tc, ts, tx = oracle.build_cost_tables(layers, edges, full, M)
+    rtc, rts, rtx = oracle.build_cost_tables_ragged(layers, edges, np.concatenate(lists), Cn, M)
+    for schedule in (wl.SCHEDULE_ROUNDS, wl.SCHEDULE_LEFT_FOLD):
+        u = oracle.search(len(layers), edges, 256, tc, ts, tx, schedule)
+        r = oracle.search_ragged(len(layers), edges, Cn, rtc, rts, rtx, schedule)
+        assert u["cost"] == r["cost"]
+        for l in range(len(layers)):
+            assert tuple(full[u["strategy"][l]][:5]) == tuple(lists[l][r["strategy"][l]][:5])
