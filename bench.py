@@ -44,6 +44,13 @@ def cpu_baseline(kind, payload):
         dt = time.perf_counter() - t0
         return {"value": p["updates"] / dt / 1e9, "unit": "G cell-updates/s", "cores": threads, "kind": "oracle",
                 "sample": f"the whole search once ({dt * 1e3:.1f} ms)", "search_ms": dt * 1e3}
+    if kind == "search_ragged":
+        p = payload
+        t0 = time.perf_counter()
+        oracle.search_ragged(p["n_nodes"], p["edges"], p["Cn"], p["tc"], p["ts"], p["tx"], p["schedule"])
+        dt = time.perf_counter() - t0
+        return {"value": p["updates"] / dt / 1e9, "unit": "G cell-updates/s", "cores": threads, "kind": "oracle",
+                "sample": f"the whole search once ({dt * 1e3:.1f} ms)", "search_ms": dt * 1e3}
     if kind == "fold":
         # the first eliminations of the left fold T <- T (x) B_j, as many as fit roughly 12 s
         p = payload
@@ -80,7 +87,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="cfg4", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "resid", "vgg16"])
+    ap.add_argument("--workload", default="cfg4", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "resid", "vgg16", "cfg1-lists", "vgg16-lists"],
+                    help="cfg4 is the headline; *-lists: the AlexNet- / VGG-16-shaped chain with one configuration "
+                         "list per layer (Sec. 4, Table 1) instead of one padded list of 256 rows")
     ap.add_argument("--layers", type=int, default=64, help="cfg4 only: chain length")
     ap.add_argument("--configs", type=int, default=0, help="override C of the workload")
     ap.add_argument("--undo", default="stored", choices=["stored", "recompute"],
@@ -123,6 +132,29 @@ def main():
             ctx.synchronize()
         # rows of many A tables against one (w, B): the same loop nest as whole products, sized to ~12 s
         cpu_payload = ("minplus", (A.reshape(batch * C, C), w[0], B[0], "rows of the A tables against (w[0], B[0])"))
+    elif name.endswith("-lists"):
+        from paper_1802_04924_amd import enumerate_configs, plan_graph
+        p = wl.config1() if name == "cfg1-lists" else wl.vgg16_problem()
+        lists = [enumerate_configs(l, p["machine"]["n_devices"]) for l in p["layers"]]
+        Cn = np.array([len(x) for x in lists], np.int32)
+        with Context(0) as c1:
+            dtc, dts, dtx = c1.build_cost_tables_ragged(p["layers"], p["edges"], np.concatenate(lists), Cn, p["machine"])
+        steps = plan_graph(p["n_nodes"], p["edges"], p["schedule"])["steps"]
+        updates = int(sum(int(Cn[s["i"]]) * int(Cn[s["j"]]) * int(Cn[s["k"]]) for s in steps if s["kind"] == 0))
+        workload = (f"{p['name'].rsplit('_', 1)[0]}_lists: {p['n_nodes']} nodes, {len(p['edges'])} edges, "
+                    f"{int(Cn.min())}..{int(Cn.max())} configurations per layer, {p['n_nodes'] - 2} node eliminations")
+        if args.undo == "recompute":
+            workload += ", argmin recomputed in the undo pass"
+        ctx = Context(0)
+        result = {}
+
+        def step():
+            result["cost"], result["S"] = ctx.search_graph_ragged(p["n_nodes"], p["edges"], Cn, dtc, dts, dtx, p["schedule"],
+                                                                  1 if args.undo == "recompute" else 0)
+        q = {"n_nodes": p["n_nodes"], "edges": p["edges"], "Cn": Cn, "tc": dtc.cpu().numpy(), "ts": dts.cpu().numpy(),
+             "tx": dtx.cpu().numpy(), "schedule": p["schedule"], "updates": updates}
+        cpu_payload = ("search_ragged", q)
+        C = int(Cn.max())
     else:
         if name == "cfg4":
             p = wl.config4(args.layers, args.configs or 4096)

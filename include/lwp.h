@@ -194,6 +194,25 @@ lwp_status lwp_build_cost_tables(lwp_ctx *ctx, const lwp_layer *layers, int32_t 
                                  int32_t C, const lwp_machine *machine,
                                  int32_t *d_tc, int32_t *d_ts, int32_t *d_tx);
 
+/* The same with a configuration list per layer (Sec. 4: the configurations of a layer depend on
+ * its parallelizable dimensions, Table 1).  C_node HOST [n_layers]; cfgs HOST: the layers' lists
+ * one after another (layer l has C_node[l] rows, 1..65535).  Outputs DEVICE in the layout
+ * lwp_search_graph_ragged takes: d_tc, d_ts the layers' rows concatenated, d_tx the edges' tables
+ * [C_node[src]][C_node[dst]] concatenated. */
+lwp_status lwp_build_cost_tables_ragged(lwp_ctx *ctx, const lwp_layer *layers, int32_t n_layers,
+                                        const int32_t *edges, int32_t n_edges, const lwp_config *cfgs,
+                                        const int32_t *C_node, const lwp_machine *machine,
+                                        int32_t *d_tc, int32_t *d_ts, int32_t *d_tx);
+
+/* Host-only: the configurations of one layer on a machine of n_devices (Sec. 4, Table 1; equal
+ * partitioning): every (n, h, w, c) of power-of-two degrees with n*h*w*c = d <= n_devices, no degree
+ * above the extent it splits (N, Hout, Wout, Cout), h = w = 1 for a fully connected layer, once
+ * per device block [k*d, (k+1)*d) inside the machine.  Ascending (n, h, w, c, dev_offset).
+ * *count receives the number of configurations; at most `capacity` rows are written to out
+ * (out may be NULL if capacity is 0). */
+lwp_status lwp_enumerate_configs(const lwp_layer *layer, int32_t n_devices, lwp_config *out,
+                                 int32_t capacity, int32_t *count);
+
 /* ---- measurement ------------------------------------------------------------------------- */
 
 /* Accumulated since the last lwp_profile_reset while profiling is on: every node-elimination

@@ -6,4 +6,5 @@ the shared library is opened on first use and must have been built.
 """
 from . import workloads  # noqa: F401
 from .binding import (Context, LwpError, SCHEDULE_LEFT_FOLD, SCHEDULE_ROUNDS, UNDO_RECOMPUTE,  # noqa: F401
-                      UNDO_STORED, plan_graph, search_workspace_bytes, search_workspace_bytes_ragged)
+                      UNDO_STORED, enumerate_configs, plan_graph, search_workspace_bytes,
+                      search_workspace_bytes_ragged)

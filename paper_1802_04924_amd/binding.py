@@ -24,6 +24,7 @@ EXPORTED = [
     "lwp_eliminate_node", "lwp_eliminate_edge", "lwp_plan_graph", "lwp_search_graph",
     "lwp_search_workspace_bytes", "lwp_search_graph_ex", "lwp_search_workspace_bytes_ex",
     "lwp_search_graph_ragged", "lwp_search_workspace_bytes_ragged", "lwp_build_cost_tables",
+    "lwp_build_cost_tables_ragged", "lwp_enumerate_configs",
     "lwp_profile_enable", "lwp_profile_reset", "lwp_profile_read",
 ]
 
@@ -82,6 +83,8 @@ def load():
     lib.lwp_search_workspace_bytes_ragged.argtypes = [i32, i32, vp, vp, i32, i32]
     lib.lwp_search_workspace_bytes_ragged.restype = ctypes.c_size_t
     lib.lwp_build_cost_tables.argtypes = [vp, vp, i32, vp, i32, vp, i32, vp, vp, vp, vp]
+    lib.lwp_build_cost_tables_ragged.argtypes = [vp, vp, i32, vp, i32, vp, vp, vp, vp, vp, vp]
+    lib.lwp_enumerate_configs.argtypes = [vp, i32, vp, i32, i32p]
     lib.lwp_profile_enable.argtypes = [vp, i32]
     lib.lwp_profile_reset.argtypes = [vp]
     lib.lwp_profile_read.argtypes = [vp, ctypes.POINTER(Profile)]
@@ -113,6 +116,21 @@ def search_workspace_bytes(n_nodes, edges, C, schedule=SCHEDULE_ROUNDS, undo=UND
     lib = load()
     edges = _np_i32(edges, (-1, 2))
     return int(lib.lwp_search_workspace_bytes_ex(n_nodes, len(edges), edges.ctypes.data, C, int(schedule), int(undo)))
+
+
+def enumerate_configs(layer, n_devices) -> np.ndarray:
+    """Host-only: configurations of one layer (int32 [C][6]) on a machine of n_devices."""
+    lib = load()
+    layer = _np_i32(layer, (14,))
+    n = ctypes.c_int32(0)
+    rc = lib.lwp_enumerate_configs(layer.ctypes.data, int(n_devices), None, 0, ctypes.byref(n))
+    if rc:
+        raise LwpError(rc, "enumerate_configs", lib.lwp_status_string(rc).decode())
+    out = np.zeros((n.value, 6), np.int32)
+    rc = lib.lwp_enumerate_configs(layer.ctypes.data, int(n_devices), out.ctypes.data, n.value, ctypes.byref(n))
+    if rc:
+        raise LwpError(rc, "enumerate_configs", lib.lwp_status_string(rc).decode())
+    return out
 
 
 def search_workspace_bytes_ragged(n_nodes, edges, C_node, schedule=SCHEDULE_ROUNDS, undo=UNDO_STORED) -> int:
@@ -256,6 +274,32 @@ class Context:
         rc = self._lib.lwp_build_cost_tables(self._h, layers.ctypes.data, L, edges.ctypes.data, E, configs.ctypes.data, C,
                                              m.ctypes.data, _dev(tc, "tc"), _dev(ts, "ts"), _dev(tx, "tx") if E else None)
         self._check(rc, "build_cost_tables")
+        return tc, ts, tx
+
+    def build_cost_tables_ragged(self, layers, edges, configs, C_node, machine):
+        """Per-layer configuration lists (concatenated in ``configs``, C_node[l] rows for layer l)
+        -> flat (tc, ts, tx) on the device, in the layout search_graph_ragged takes."""
+        import torch
+        layers = _np_i32(layers, (-1, 14))
+        edges = _np_i32(edges, (-1, 2))
+        configs = _np_i32(configs, (-1, 6))
+        C_node = _np_i32(C_node, (-1,))
+        L, E = len(layers), len(edges)
+        if len(C_node) != L or (C_node < 1).any() or int(C_node.astype(np.int64).sum()) != len(configs):
+            raise ValueError("C_node must have one positive entry per layer and sum to the number of rows")
+        if E and ((edges < 0).any() or (edges >= L).any()):
+            raise ValueError("edge endpoint out of range")
+        m = np.array([machine["n_devices"], machine["flop_per_ns"], machine["byte_per_ns"], machine["invalid_cost"]], np.int32)
+        rows = int(C_node.astype(np.int64).sum())
+        cells = int((C_node[edges[:, 0]].astype(np.int64) * C_node[edges[:, 1]]).sum()) if E else 0
+        dev = torch.device("cuda", self.device)
+        tc = torch.empty(rows, dtype=torch.int32, device=dev)
+        ts = torch.empty(rows, dtype=torch.int32, device=dev)
+        tx = torch.empty(max(cells, 1), dtype=torch.int32, device=dev)[:cells]
+        rc = self._lib.lwp_build_cost_tables_ragged(self._h, layers.ctypes.data, L, edges.ctypes.data, E,
+                                                    configs.ctypes.data, C_node.ctypes.data, m.ctypes.data,
+                                                    _dev(tc, "tc"), _dev(ts, "ts"), _dev(tx, "tx") if E else None)
+        self._check(rc, "build_cost_tables_ragged")
         return tc, ts, tx
 
     # ---- measurement -------------------------------------------------------

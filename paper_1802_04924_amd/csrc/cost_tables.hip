@@ -48,13 +48,20 @@ __device__ inline Span spatial_need(const lwp_layer& L, bool height, int t, int 
                   : window(split(t, g, L.Wout), L.sw, L.pw, L.kw, L.Win);
 }
 
-__global__ void node_costs_kernel(const lwp_layer* __restrict__ layers, int n_layers,
-                                  const lwp_config* __restrict__ cfgs, int C, lwp_machine m,
+// Where layer l finds its configurations and its rows: configurations cfgs[cfg_off .. + C),
+// outputs t_c, t_s at element out_off.  One shared list: cfg_off = 0 for every layer.
+struct LayerSlice { int64_t cfg_off, out_off; int32_t C, pad; };
+
+// grid: x over the configurations of a layer, y = layer
+__global__ void node_costs_kernel(const lwp_layer* __restrict__ layers, const LayerSlice* __restrict__ slices,
+                                  const lwp_config* __restrict__ cfgs, lwp_machine m,
                                   int32_t* __restrict__ tc, int32_t* __restrict__ ts, int32_t* __restrict__ flag) {
-    const int x = blockIdx.x * blockDim.x + threadIdx.x;
-    if (x >= n_layers * C) return;
-    const lwp_layer L = layers[x / C];
-    const lwp_config c = cfgs[x % C];
+    const LayerSlice sl = slices[blockIdx.y];
+    const int r = blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= sl.C) return;
+    const int64_t x = sl.out_off + r;
+    const lwp_layer L = layers[blockIdx.y];
+    const lwp_config c = cfgs[sl.cfg_off + r];
     long long work, params;
     if (L.kind == KIND_CONV) {
         work = 6ll * L.N * L.Cout * L.Hout * L.Wout * L.Cin * L.kh * L.kw;
@@ -79,16 +86,20 @@ __global__ void node_costs_kernel(const lwp_layer* __restrict__ layers, int n_la
     ts[x] = (int32_t)vs;
 }
 
-__global__ void edge_costs_kernel(const lwp_layer* __restrict__ layers, const int32_t* __restrict__ edges,
-                                  const lwp_config* __restrict__ cfgs, int C, lwp_machine m,
+// grid: x over consumer configurations, y over producer configurations (both sized for the
+// largest list), z = edge; table e starts at element tx_off[e]
+__global__ void edge_costs_kernel(const lwp_layer* __restrict__ layers, const LayerSlice* __restrict__ slices,
+                                  const int32_t* __restrict__ edges, const int64_t* __restrict__ tx_off,
+                                  const lwp_config* __restrict__ cfgs, lwp_machine m,
                                   int32_t* __restrict__ tx, int32_t* __restrict__ flag) {
     const int e = blockIdx.z;
     const int b = blockIdx.x * blockDim.x + threadIdx.x;     // consumer configuration
     const int a = blockIdx.y;                                // producer configuration
-    if (b >= C) return;
+    const LayerSlice sa = slices[edges[2 * e]], sb = slices[edges[2 * e + 1]];
+    if (a >= sa.C || b >= sb.C) return;
     const lwp_layer P = layers[edges[2 * e]];
     const lwp_layer Q = layers[edges[2 * e + 1]];
-    const lwp_config ca = cfgs[a], cb = cfgs[b];
+    const lwp_config ca = cfgs[sa.cfg_off + a], cb = cfgs[sb.cfg_off + b];
     long long cells = 0;
     if (row_valid(P, ca, m.n_devices) && row_valid(Q, cb, m.n_devices)) {
         // volume read by all consumer parts, wherever it lives
@@ -121,7 +132,91 @@ __global__ void edge_costs_kernel(const lwp_layer* __restrict__ layers, const in
     }
     const long long v = div_round(4 * cells, m.byte_per_ns);
     if (v > 2147483647ll) atomicOr(flag, 1);
-    tx[((size_t)e * C + a) * C + b] = (int32_t)v;
+    tx[tx_off[e] + (int64_t)a * sb.C + b] = (int32_t)v;
+}
+
+}  // namespace
+
+namespace {
+
+// cfg_rows: total rows in cfgs.  shared: every layer uses rows [0, Cn[0]).
+lwp_status build_tables(lwp_ctx* ctx, const lwp_layer* layers, int32_t n_layers, const int32_t* edges,
+                        int32_t n_edges, const lwp_config* cfgs, const int32_t* Cn, bool shared,
+                        const lwp_machine* machine, int32_t* d_tc, int32_t* d_ts, int32_t* d_tx) {
+    if (machine->n_devices < 1 || machine->flop_per_ns < 1 || machine->byte_per_ns < 1 || machine->invalid_cost < 0)
+        return lwp::ctx_fail(ctx, LWP_E_INVAL, "machine constants must be positive");
+    for (int32_t l = 0; l < n_layers; ++l) {
+        const lwp_layer& L = layers[l];
+        if (L.kind < KIND_CONV || L.kind > KIND_FC) return lwp::ctx_fail(ctx, LWP_E_INVAL, "unknown layer kind");
+        if (L.N < 1 || L.Cin < 1 || L.Hin < 1 || L.Win < 1 || L.Cout < 1 || L.Hout < 1 || L.Wout < 1 || L.kh < 1 ||
+            L.kw < 1 || L.sh < 1 || L.sw < 1 || L.ph < 0 || L.pw < 0)
+            return lwp::ctx_fail(ctx, LWP_E_INVAL, "layer extents must be positive");
+        if (Cn[l] < 1 || Cn[l] > 65535) return lwp::ctx_fail(ctx, LWP_E_INVAL, "a layer needs 1..65535 configurations");
+    }
+    for (int32_t e = 0; e < n_edges; ++e) {
+        const int32_t p = edges[2 * e], q = edges[2 * e + 1];
+        if (p < 0 || p >= n_layers || q < 0 || q >= n_layers || p == q)
+            return lwp::ctx_fail(ctx, LWP_E_GRAPH, "edge endpoint out of range");
+        const lwp_layer &P = layers[p], &Q = layers[q];
+        if (P.N != Q.N || P.Cout != Q.Cin || P.Hout != Q.Hin || P.Wout != Q.Win)
+            return lwp::ctx_fail(ctx, LWP_E_INVAL, "producer output and consumer input shapes differ");
+    }
+    std::vector<LayerSlice> slices((size_t)n_layers);
+    std::vector<int64_t> tx_off((size_t)(n_edges > 0 ? n_edges : 1));
+    int64_t rows = 0, cfg_rows = 0;
+    int32_t c_max = 1;
+    for (int32_t l = 0; l < n_layers; ++l) {
+        slices[l] = {shared ? 0 : rows, rows, Cn[l], 0};
+        rows += Cn[l];
+        c_max = Cn[l] > c_max ? Cn[l] : c_max;
+    }
+    cfg_rows = shared ? Cn[0] : rows;
+    int64_t cells = 0;
+    for (int32_t e = 0; e < n_edges; ++e) { tx_off[e] = cells; cells += (int64_t)Cn[edges[2 * e]] * Cn[edges[2 * e + 1]]; }
+
+    hipStream_t st = lwp::ctx_stream(ctx);
+    const size_t bl = (size_t)n_layers * sizeof(lwp_layer), bs = (size_t)n_layers * sizeof(LayerSlice),
+                 bc = (size_t)cfg_rows * sizeof(lwp_config), be = (size_t)(n_edges > 0 ? n_edges : 1) * 2 * sizeof(int32_t),
+                 bo = tx_off.size() * sizeof(int64_t);
+    auto up = [](size_t v) { return (v + 255) / 256 * 256; };
+    const size_t off_s = up(bl), off_c = off_s + up(bs), off_e = off_c + up(bc), off_o = off_e + up(be), off_f = off_o + up(bo);
+    char* d = nullptr;
+    if (hipMalloc(&d, off_f + 256) != hipSuccess) { (void)hipGetLastError(); return lwp::ctx_fail(ctx, LWP_E_NOMEM, "descriptor upload buffer"); }
+    lwp_status result = LWP_OK;
+    int32_t flag = 0;
+    hipError_t herr = hipSuccess;
+    auto ok = [&](hipError_t e) { if (e != hipSuccess && herr == hipSuccess) herr = e; return e == hipSuccess; };
+    if (ok(hipMemcpyAsync(d, layers, bl, hipMemcpyHostToDevice, st)) &&
+        ok(hipMemcpyAsync(d + off_s, slices.data(), bs, hipMemcpyHostToDevice, st)) &&
+        ok(hipMemcpyAsync(d + off_c, cfgs, bc, hipMemcpyHostToDevice, st)) &&
+        (n_edges == 0 || ok(hipMemcpyAsync(d + off_e, edges, (size_t)n_edges * 2 * sizeof(int32_t), hipMemcpyHostToDevice, st))) &&
+        (n_edges == 0 || ok(hipMemcpyAsync(d + off_o, tx_off.data(), (size_t)n_edges * sizeof(int64_t), hipMemcpyHostToDevice, st))) &&
+        ok(hipMemsetAsync(d + off_f, 0, sizeof(int32_t), st))) {
+        const lwp_layer* dl = reinterpret_cast<const lwp_layer*>(d);
+        const LayerSlice* ds = reinterpret_cast<const LayerSlice*>(d + off_s);
+        const lwp_config* dc = reinterpret_cast<const lwp_config*>(d + off_c);
+        const int32_t* de = reinterpret_cast<const int32_t*>(d + off_e);
+        const int64_t* dof = reinterpret_cast<const int64_t*>(d + off_o);
+        int32_t* df = reinterpret_cast<int32_t*>(d + off_f);
+        for (int32_t l0 = 0; l0 < n_layers && herr == hipSuccess; l0 += 65535) {
+            const int32_t nl = (n_layers - l0) < 65535 ? (n_layers - l0) : 65535;
+            hipLaunchKernelGGL(node_costs_kernel, dim3((c_max + 255) / 256, nl), dim3(256), 0, st, dl + l0, ds + l0, dc,
+                               *machine, d_tc, d_ts, df);
+            ok(hipGetLastError());
+        }
+        for (int32_t e0 = 0; e0 < n_edges && herr == hipSuccess; e0 += 65535) {
+            const int32_t ne = (n_edges - e0) < 65535 ? (n_edges - e0) : 65535;
+            hipLaunchKernelGGL(edge_costs_kernel, dim3((c_max + 255) / 256, c_max, ne), dim3(256), 0, st, dl, ds,
+                               de + 2 * (size_t)e0, dof + e0, dc, *machine, d_tx, df);
+            ok(hipGetLastError());
+        }
+        ok(hipMemcpyAsync(&flag, df, sizeof(int32_t), hipMemcpyDeviceToHost, st));
+    }
+    ok(hipStreamSynchronize(st));
+    (void)hipFree(d);
+    if (herr != hipSuccess) return lwp::ctx_fail(ctx, LWP_E_HIP, hipGetErrorString(herr));
+    if (flag) result = lwp::ctx_fail(ctx, LWP_E_OVERFLOW, "a cost does not fit int32 nanoseconds");
+    return result;
 }
 
 }  // namespace
@@ -136,57 +231,44 @@ extern "C" lwp_status lwp_build_cost_tables(lwp_ctx* ctx, const lwp_layer* layer
         return lwp::ctx_fail(ctx, LWP_E_INVAL, "null pointer");
     if (n_layers < 1 || n_edges < 0 || C < 1 || C > 65535)
         return lwp::ctx_fail(ctx, LWP_E_INVAL, "bad sizes");
-    if (machine->n_devices < 1 || machine->flop_per_ns < 1 || machine->byte_per_ns < 1 || machine->invalid_cost < 0)
-        return lwp::ctx_fail(ctx, LWP_E_INVAL, "machine constants must be positive");
-    for (int32_t l = 0; l < n_layers; ++l) {
-        const lwp_layer& L = layers[l];
-        if (L.kind < KIND_CONV || L.kind > KIND_FC) return lwp::ctx_fail(ctx, LWP_E_INVAL, "unknown layer kind");
-        if (L.N < 1 || L.Cin < 1 || L.Hin < 1 || L.Win < 1 || L.Cout < 1 || L.Hout < 1 || L.Wout < 1 || L.kh < 1 ||
-            L.kw < 1 || L.sh < 1 || L.sw < 1 || L.ph < 0 || L.pw < 0)
-            return lwp::ctx_fail(ctx, LWP_E_INVAL, "layer extents must be positive");
-    }
-    for (int32_t e = 0; e < n_edges; ++e) {
-        const int32_t p = edges[2 * e], q = edges[2 * e + 1];
-        if (p < 0 || p >= n_layers || q < 0 || q >= n_layers || p == q)
-            return lwp::ctx_fail(ctx, LWP_E_GRAPH, "edge endpoint out of range");
-        const lwp_layer &P = layers[p], &Q = layers[q];
-        if (P.N != Q.N || P.Cout != Q.Cin || P.Hout != Q.Hin || P.Wout != Q.Win)
-            return lwp::ctx_fail(ctx, LWP_E_INVAL, "producer output and consumer input shapes differ");
-    }
-    hipStream_t st = lwp::ctx_stream(ctx);
-    const size_t bl = (size_t)n_layers * sizeof(lwp_layer), bc = (size_t)C * sizeof(lwp_config),
-                 be = (size_t)(n_edges > 0 ? n_edges : 1) * 2 * sizeof(int32_t);
-    char* d = nullptr;
-    const size_t off_c = (bl + 255) / 256 * 256, off_e = off_c + (bc + 255) / 256 * 256,
-                 off_f = off_e + (be + 255) / 256 * 256;
-    if (hipMalloc(&d, off_f + 256) != hipSuccess) { (void)hipGetLastError(); return lwp::ctx_fail(ctx, LWP_E_NOMEM, "descriptor upload buffer"); }
-    lwp_status result = LWP_OK;
-    int32_t flag = 0;
-    hipError_t herr = hipSuccess;
-    auto ok = [&](hipError_t e) { if (e != hipSuccess && herr == hipSuccess) herr = e; return e == hipSuccess; };
-    if (ok(hipMemcpyAsync(d, layers, bl, hipMemcpyHostToDevice, st)) &&
-        ok(hipMemcpyAsync(d + off_c, cfgs, bc, hipMemcpyHostToDevice, st)) &&
-        (n_edges == 0 || ok(hipMemcpyAsync(d + off_e, edges, (size_t)n_edges * 2 * sizeof(int32_t), hipMemcpyHostToDevice, st))) &&
-        ok(hipMemsetAsync(d + off_f, 0, sizeof(int32_t), st))) {
-        const lwp_layer* dl = reinterpret_cast<const lwp_layer*>(d);
-        const lwp_config* dc = reinterpret_cast<const lwp_config*>(d + off_c);
-        const int32_t* de = reinterpret_cast<const int32_t*>(d + off_e);
-        int32_t* df = reinterpret_cast<int32_t*>(d + off_f);
-        const int total = n_layers * C;
-        hipLaunchKernelGGL(node_costs_kernel, dim3((total + 255) / 256), dim3(256), 0, st, dl, n_layers, dc, C, *machine,
-                           d_tc, d_ts, df);
-        ok(hipGetLastError());
-        for (int32_t e0 = 0; e0 < n_edges && herr == hipSuccess; e0 += 65535) {
-            const int32_t ne = (n_edges - e0) < 65535 ? (n_edges - e0) : 65535;
-            hipLaunchKernelGGL(edge_costs_kernel, dim3((C + 255) / 256, C, ne), dim3(256), 0, st, dl, de + 2 * (size_t)e0, dc,
-                               C, *machine, d_tx + (size_t)e0 * C * C, df);
-            ok(hipGetLastError());
-        }
-        ok(hipMemcpyAsync(&flag, df, sizeof(int32_t), hipMemcpyDeviceToHost, st));
-    }
-    ok(hipStreamSynchronize(st));
-    (void)hipFree(d);
-    if (herr != hipSuccess) return lwp::ctx_fail(ctx, LWP_E_HIP, hipGetErrorString(herr));
-    if (flag) result = lwp::ctx_fail(ctx, LWP_E_OVERFLOW, "a cost does not fit int32 nanoseconds");
-    return result;
+    const std::vector<int32_t> Cn((size_t)n_layers, C);
+    return build_tables(ctx, layers, n_layers, edges, n_edges, cfgs, Cn.data(), true, machine, d_tc, d_ts, d_tx);
+}
+
+extern "C" lwp_status lwp_build_cost_tables_ragged(lwp_ctx* ctx, const lwp_layer* layers, int32_t n_layers,
+                                                   const int32_t* edges, int32_t n_edges, const lwp_config* cfgs,
+                                                   const int32_t* C_node, const lwp_machine* machine,
+                                                   int32_t* d_tc, int32_t* d_ts, int32_t* d_tx) {
+    if (!ctx) return LWP_E_INVAL;
+    if (lwp_status rc = lwp::ctx_enter(ctx)) return rc;
+    if (!layers || !cfgs || !C_node || !machine || !d_tc || !d_ts || (n_edges > 0 && (!edges || !d_tx)))
+        return lwp::ctx_fail(ctx, LWP_E_INVAL, "null pointer");
+    if (n_layers < 1 || n_edges < 0) return lwp::ctx_fail(ctx, LWP_E_INVAL, "bad sizes");
+    return build_tables(ctx, layers, n_layers, edges, n_edges, cfgs, C_node, false, machine, d_tc, d_ts, d_tx);
+}
+
+// Sec. 4 / Table 1: a configuration gives a degree of parallelism to every parallelizable
+// dimension of the layer's output (sample, height, width, channel; a fully connected layer has
+// only sample and channel), partitions being equal.  Enumerated here: power-of-two degrees whose
+// product d fits the machine and that do not exceed the layer's extents, on every device block
+// [k*d, (k+1)*d).  Ascending (n, h, w, c, offset).
+extern "C" lwp_status lwp_enumerate_configs(const lwp_layer* layer, int32_t n_devices, lwp_config* out,
+                                            int32_t capacity, int32_t* count) {
+    if (!layer || !count || n_devices < 1 || capacity < 0 || (capacity > 0 && !out)) return LWP_E_INVAL;
+    if (layer->kind < KIND_CONV || layer->kind > KIND_FC || layer->N < 1 || layer->Cout < 1 || layer->Hout < 1 ||
+        layer->Wout < 1)
+        return LWP_E_INVAL;
+    const bool fc = layer->kind == KIND_FC;
+    int64_t found = 0;
+    for (int64_t n = 1; n <= n_devices && n <= layer->N; n <<= 1)
+        for (int64_t h = 1; n * h <= n_devices && h <= (fc ? 1 : layer->Hout); h <<= 1)
+            for (int64_t w = 1; n * h * w <= n_devices && w <= (fc ? 1 : layer->Wout); w <<= 1)
+                for (int64_t c = 1; n * h * w * c <= n_devices && c <= layer->Cout; c <<= 1) {
+                    const int64_t degree = n * h * w * c;
+                    for (int64_t block = 0; (block + 1) * degree <= n_devices; ++block, ++found)
+                        if (found < capacity) out[found] = {(int32_t)n, (int32_t)h, (int32_t)w, (int32_t)c, (int32_t)(block * degree), 0};
+                }
+    if (found > 2147483647ll) return LWP_E_INVAL;
+    *count = (int32_t)found;
+    return LWP_OK;
 }

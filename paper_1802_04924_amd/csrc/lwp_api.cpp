@@ -279,7 +279,7 @@ Layout plan_buffers(const Plan& plan, int32_t n_nodes, int32_t n_edges, const in
 struct WsLayout {
     size_t w, head, keys, result, offs, offs_bytes, args, slots, total;
     size_t desc, desc_bytes;                                   // descriptor block
-    size_t node_desc, edge_desc, src_ptrs, pair_desc, singles, undo, comps;   // offsets inside the block
+    size_t node_desc, edge_desc, src_ptrs, pair_desc, singles, undo, comps, tile_begin;   // offsets inside the block
     int32_t n_ranges;
 };
 
@@ -306,6 +306,7 @@ WsLayout layout_workspace(const Plan& plan, const Layout& L, int32_t n_nodes, in
         o.singles = sub(plan.singles.size() * sizeof(SingleDesc));
         o.undo = sub((size_t)plan.n_node_steps * sizeof(UndoDesc));
         o.comps = sub(plan.comps.size() * sizeof(CompDesc));
+        o.tile_begin = sub((2 * (size_t)plan.n_node_steps + 2) * sizeof(int32_t));   // launches of mixed shapes
         o.desc_bytes = std::max<size_t>(b, 16);
     }
     o.desc = put(o.desc_bytes);
@@ -627,6 +628,8 @@ lwp_status lwp_search_graph_ragged(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edge
     SingleDesc* sd = reinterpret_cast<SingleDesc*>(hb + W.singles);
     UndoDesc* ud = reinterpret_cast<UndoDesc*>(hb + W.undo);
     CompDesc* cd = reinterpret_cast<CompDesc*>(hb + W.comps);
+    int32_t* tbeg = reinterpret_cast<int32_t*>(hb + W.tile_begin);
+    size_t n_tbeg = 0;
     char* db = ws + W.desc;
     const NodeDesc* d_nd = reinterpret_cast<const NodeDesc*>(db + W.node_desc);
     const EdgeDesc* d_ed = reinterpret_cast<const EdgeDesc*>(db + W.edge_desc);
@@ -635,15 +638,21 @@ lwp_status lwp_search_graph_ragged(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edge
     const SingleDesc* d_sd = reinterpret_cast<const SingleDesc*>(db + W.singles);
     const UndoDesc* d_ud = reinterpret_cast<const UndoDesc*>(db + W.undo);
     const CompDesc* d_cd = reinterpret_cast<const CompDesc*>(db + W.comps);
+    const int32_t* d_tbeg = reinterpret_cast<const int32_t*>(db + W.tile_begin);
 
     std::vector<Range> er(n_edges), wr(n_nodes);
     std::vector<int32_t> erng(n_edges);          // range-pair index of the edge's current table
     for (int32_t e = 0; e < n_edges; ++e) { er[e] = {stats[2 * e], stats[2 * e + 1]}; erng[e] = e; }
     for (int32_t v = 0; v < n_nodes; ++v) wr[v] = {stats[2 * (rng_w0 + v)], stats[2 * (rng_w0 + v) + 1]};
-    // Node eliminations of one round are independent; those of equal shape (Ci, Cj, Ck) and kernel
-    // variant share a launch, so the descriptors of a round are ordered by (shape, variant).
+    // Node eliminations of one round are independent; those of equal kernel variant share a
+    // launch if they agree in shape (Ci, Cj, Ck) or run on 64 x 64 tiles (a launch of mixed shapes),
+    // so the descriptors of a round are ordered by (variant, shape).
     struct NodeWork { NodeDesc d; int64_t spread; int32_t Ci, Cj, Ck; int variant; };
-    struct NodeLaunch { size_t first, count; int32_t Ci, Cj, Ck; int variant; };
+    struct NodeLaunch {
+        size_t first, count; int32_t Ci, Cj, Ck; int variant;
+        int64_t tile_begin;      // index into the tile_begin block for mixed shapes, else -1
+        int32_t total_tiles, min_Cj; int64_t updates;
+    };
     struct RoundWork { size_t g0, g1; int64_t edge_cells, edge_max_cells; std::vector<NodeLaunch> launches; };
     std::vector<RoundWork> rounds;
     // The propagated bounds are worst cases and grow along a chain although the minima do not.
@@ -700,6 +709,7 @@ lwp_status lwp_search_graph_ragged(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edge
                 d.rngOut = d_stats + 2 * (int64_t)(rng_node0 + (int32_t)ni);
                 nw.spread = proven ? keyed_spread(rA, rw, rB) : (int64_t)1 << 62;   // unproven: no packed keys
                 nw.Ci = tA.rows; nw.Cj = tA.cols; nw.Ck = tB.cols;
+                d.Ci = nw.Ci; d.Cj = nw.Cj; d.Ck = nw.Ck;
                 work.push_back(nw);
                 ud[ni] = {d.arg, d.A, d.w, d.B, s.j, s.i, s.k, s.round, nw.Cj, nw.Ck};
                 // any fixed c bounds the minimum from above; take the c with the smallest w
@@ -710,32 +720,53 @@ lwp_status lwp_search_graph_ragged(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edge
             // kernel variant per product: packed keys on the preferred tile size if the spread
             // allows, else packed keys on 128 x 128 tiles (one more bit), else the plain variant;
             // 0 keyed small, 1 keyed large, 2 plain small, 3 plain large, 4 value small, 5 value large
-            auto shape_less = [&](const NodeWork& a, const NodeWork& b) {
-                return std::tie(a.Ci, a.Cj, a.Ck) < std::tie(b.Ci, b.Cj, b.Ck);
-            };
+            auto shape_of = [](const NodeWork& a) { return std::make_tuple(a.Ci, a.Cj, a.Ck); };
+            std::map<std::tuple<int32_t, int32_t, int32_t>, int64_t> shape_count;
+            for (const NodeWork& x : work) ++shape_count[shape_of(x)];
+            for (NodeWork& x : work) {
+                const int64_t same = shape_count[shape_of(x)];
+                const bool prefer_small = want_small_tiles(x.Ci, x.Cj, x.Ck, same);
+                const bool large_fills_chip = large_tiles(x.Ci, x.Ck, same) >= 512;
+                if (!stored) x.variant = prefer_small ? 4 : 5;     // value-only: no range condition
+                else if (x.spread <= (prefer_small ? kKeyedMaxSpreadSmall : kKeyedMaxSpreadLarge)) x.variant = prefer_small ? 0 : 1;
+                else if (x.spread <= kKeyedMaxSpreadLarge && large_fills_chip) x.variant = 1;
+                else x.variant = prefer_small ? 2 : 3;
+            }
             order.resize(work.size());
             for (size_t q = 0; q < order.size(); ++q) order[q] = q;
-            if (!L.uniform)
-                std::stable_sort(order.begin(), order.end(), [&](size_t a, size_t b) { return shape_less(work[a], work[b]); });
+            std::stable_sort(order.begin(), order.end(), [&](size_t a, size_t b) {
+                return std::make_pair(work[a].variant, shape_of(work[a])) < std::make_pair(work[b].variant, shape_of(work[b]));
+            });
             for (size_t a = 0; a < order.size();) {
+                const int v = work[order[a]].variant;
                 size_t b = a;
-                while (b < order.size() && !shape_less(work[order[a]], work[order[b]])) ++b;
-                const NodeWork& w0 = work[order[a]];
-                const bool prefer_small = want_small_tiles(w0.Ci, w0.Cj, w0.Ck, (int64_t)(b - a));
-                const bool large_fills_chip = large_tiles(w0.Ci, w0.Ck, (int64_t)(b - a)) >= 512;
-                for (size_t q = a; q < b; ++q) {
-                    NodeWork& x = work[order[q]];
-                    if (!stored) x.variant = prefer_small ? 4 : 5;     // value-only: no range condition
-                    else if (x.spread <= (prefer_small ? kKeyedMaxSpreadSmall : kKeyedMaxSpreadLarge)) x.variant = prefer_small ? 0 : 1;
-                    else if (x.spread <= kKeyedMaxSpreadLarge && large_fills_chip) x.variant = 1;
-                    else x.variant = prefer_small ? 2 : 3;
-                }
-                std::stable_sort(order.begin() + a, order.begin() + b, [&](size_t p, size_t q) { return work[p].variant < work[q].variant; });
-                for (size_t q = a; q < b;) {
-                    size_t e = q;
-                    while (e < b && work[order[e]].variant == work[order[q]].variant) ++e;
-                    rw_.launches.push_back({n0 + q, e - q, w0.Ci, w0.Cj, w0.Ck, work[order[q]].variant});
-                    q = e;
+                while (b < order.size() && work[order[b]].variant == v) ++b;
+                const bool small = (v == 0 || v == 2 || v == 4);
+                const bool one_shape = shape_of(work[order[a]]) == shape_of(work[order[b - 1]]);
+                if (small && !one_shape) {
+                    // one launch over all shapes: product q owns tiles [tile_begin[q], tile_begin[q+1])
+                    NodeLaunch nl{n0 + a, b - a, 0, 0, 0, v, (int64_t)n_tbeg, 0, INT32_MAX, 0};
+                    int64_t tiles = 0;
+                    for (size_t q = a; q < b; ++q) {
+                        NodeWork& x = work[order[q]];
+                        tbeg[n_tbeg++] = (int32_t)tiles;
+                        tiles += (int64_t)((x.Ci + kTileSmall - 1) / kTileSmall) * ((x.Ck + kTileSmall - 1) / kTileSmall);
+                        nl.min_Cj = std::min(nl.min_Cj, x.Cj);
+                        nl.updates += (int64_t)x.Ci * x.Cj * x.Ck;
+                    }
+                    tbeg[n_tbeg++] = (int32_t)tiles;
+                    if (tiles > INT32_MAX) return fail(ctx, LWP_E_INVAL, "too many tiles in one round");
+                    nl.total_tiles = (int32_t)tiles;
+                    rw_.launches.push_back(nl);
+                } else {
+                    for (size_t q = a; q < b;) {
+                        size_t e = q;
+                        while (e < b && shape_of(work[order[e]]) == shape_of(work[order[q]])) ++e;
+                        const NodeWork& x = work[order[q]];
+                        rw_.launches.push_back({n0 + q, e - q, x.Ci, x.Cj, x.Ck, v, -1, 0, x.Cj,
+                                                (int64_t)(e - q) * x.Ci * x.Cj * x.Ck});
+                        q = e;
+                    }
                 }
                 a = b;
             }
@@ -792,8 +823,12 @@ lwp_status lwp_search_graph_ragged(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edge
             na.Ci = nl.Ci; na.Cj = nl.Cj; na.Ck = nl.Ck; na.batch = (int32_t)nl.count;
             na.tilesM = (nl.Ci + tile - 1) / tile;
             na.tilesN = (nl.Ck + tile - 1) / tile;
-            ScopedTimer tm(ctx, 0, (int64_t)nl.count * nl.Ci * nl.Cj * nl.Ck, keyed);
-            const int kparts = choose_kparts((int64_t)na.tilesM * na.tilesN * na.batch, nl.Cj, small);
+            const bool mixed = nl.tile_begin >= 0;
+            if (mixed) { na.tile_begin = d_tbeg + nl.tile_begin; na.total_tiles = nl.total_tiles; }
+            ScopedTimer tm(ctx, 0, nl.updates, keyed);
+            // a launch of mixed shapes splits by its shortest product (parts beyond a product's
+            // stages see only padding)
+            const int kparts = choose_kparts(mixed ? nl.total_tiles : (int64_t)na.tilesM * na.tilesN * na.batch, nl.min_Cj, small);
             if (kparts > 1) { if (lwp_status s2 = ensure_split_buffers(ctx)) return s2; }
             set_split(ctx, na, kparts);
             LWP_HIP(ctx, launch_minplus(na, mode, small, st));

@@ -26,9 +26,10 @@ struct NodeDesc {
     const int32_t* rngW;
     int32_t* rngOut;
     int32_t* flag;     // optional: OR-ed with 1 if max A + max w + max B (measured) may leave int32
-    int64_t pad;
+    int32_t Ci, Cj, Ck;   // shape of this product; read only by launches of mixed shapes
+    int32_t pad[3];
 };
-static_assert(sizeof(NodeDesc) == 112, "descriptor layout");
+static_assert(sizeof(NodeDesc) == 128, "descriptor layout");
 
 struct NodeArgs {
     const NodeDesc* descs;   // device array [batch], or null for strided addressing
@@ -36,6 +37,12 @@ struct NodeArgs {
     int64_t sA, sw, sB, sO;  // strided addressing: element strides between products
     int32_t Ci, Cj, Ck, batch;
     int32_t tilesM, tilesN;  // output tiles of the chosen tile size per product
+    // Mixed shapes (64 x 64 tiles, descriptor addressing only): product q has its own shape in
+    // descs[q] and owns tiles [tile_begin[q], tile_begin[q+1]) of the launch; tile_begin is a
+    // device array of batch + 1 ascending entries and total_tiles = tile_begin[batch].  Ci, Cj, Ck,
+    // tilesM and tilesN above are then ignored.
+    const int32_t* tile_begin;
+    int32_t total_tiles;
     // Split tiles (64 x 64 tiles only): kparts > 1 workgroups share a tile.  scratch holds
     // tiles * kparts * 2 * 16 * 256 int32; counters one zeroed int32 per tile (left zeroed).
     int32_t kparts;

@@ -48,8 +48,9 @@ __device__ __forceinline__ int wave_max_i32(int v) {
     return v;
 }
 
-template <int MODE, int RB, int TK>
+template <int MODE, int RB, int TK, bool MIXED = false>
 __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) void minplus_kernel(const NodeArgs p) {
+    static_assert(!MIXED || RB == 4, "launches of mixed shapes use 64 x 64 tiles");
     constexpr bool KEYED = (MODE == kModeKeyed);
     constexpr bool VALUE = (MODE == kModeValue);   // minimum only: no argmin, no keys, any int32
     constexpr int TM = 16 * RB, TN = 16 * RB;   // output tile
@@ -71,21 +72,25 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
     const int part = (kparts > 1) ? (int)(bid % (uint32_t)kparts) : 0;
     if (kparts > 1) bid /= (uint32_t)kparts;
     const uint32_t tile_global = bid;
-    const int tiles = p.tilesM * p.tilesN;
-    const int bi = bid / tiles;
-    const int tl = bid - bi * tiles;
-    constexpr int PANEL = 8;
-    const int panel = tl / (PANEL * p.tilesN);
-    const int prow0 = panel * PANEL;
-    const int prows = min(PANEL, p.tilesM - prow0);
-    const int within = tl - panel * PANEL * p.tilesN;
-    const int tni = within / prows;
-    const int tmi = prow0 + (within - tni * prows);
-    const int a0 = tmi * TM, b0 = tni * TN;
-    const int Ci = p.Ci, Cj = p.Cj, Ck = p.Ck;
+    int bi, tl;
+    if (MIXED) {
+        // products of different shapes: find the one that owns this tile (uniform binary search)
+        const int32_t __attribute__((address_space(1)))* tb0 = (const int32_t __attribute__((address_space(1)))*)(uintptr_t)p.tile_begin;
+        int lo = 0, hi = p.batch;
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if ((uint32_t)tb0[mid] <= bid) lo = mid; else hi = mid;
+        }
+        bi = lo;
+        tl = (int)bid - tb0[lo];
+    } else {
+        const int tiles = p.tilesM * p.tilesN;
+        bi = bid / tiles;
+        tl = bid - bi * tiles;
+    }
 
     NodeDesc d;
-    if (p.descs) {
+    if (MIXED || p.descs) {
         d = p.descs[bi];
     } else {
         d = p.base;
@@ -93,6 +98,17 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
         d.out += (int64_t)bi * p.sO;
         if (d.arg) d.arg += (int64_t)bi * p.sO;
     }
+    const int Ci = MIXED ? d.Ci : p.Ci, Cj = MIXED ? d.Cj : p.Cj, Ck = MIXED ? d.Ck : p.Ck;
+    const int tilesM = MIXED ? (Ci + TM - 1) / TM : p.tilesM, tilesN = MIXED ? (Ck + TN - 1) / TN : p.tilesN;
+    constexpr int PANEL = 8;
+    const int panel = tl / (PANEL * tilesN);
+    const int prow0 = panel * PANEL;
+    const int prows = min(PANEL, tilesM - prow0);
+    const int within = tl - panel * PANEL * tilesN;
+    const int tni = within / prows;
+    const int tmi = prow0 + (within - tni * prows);
+    const int a0 = tmi * TM, b0 = tni * TN;
+
     // Pointers read from a descriptor are generic to the compiler; say that they are global memory,
     // otherwise the prefetch loads are issued as flat loads, which also count as LDS traffic and
     // would be waited for by the first LDS read of the stage they are meant to overlap.
@@ -423,11 +439,17 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
 
 hipError_t launch_minplus(const NodeArgs& args, int mode, bool small_tiles, hipStream_t stream) {
     const int kparts = args.kparts > 1 ? args.kparts : 1;
-    const int64_t blocks = (int64_t)args.tilesM * args.tilesN * args.batch * kparts;
-    if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    const bool mixed = args.tile_begin != nullptr;
+    const int64_t blocks = (mixed ? (int64_t)args.total_tiles : (int64_t)args.tilesM * args.tilesN * args.batch) * kparts;
+    if (blocks <= 0 || blocks > 0x7fffffffLL || args.batch < 1) return hipErrorInvalidValue;
     if (kparts > 1 && (!small_tiles || !args.scratch || !args.counters)) return hipErrorInvalidValue;
+    if (mixed && (!small_tiles || !args.descs)) return hipErrorInvalidValue;
     dim3 grid((unsigned)blocks), block(NT);
-    if (small_tiles) {
+    if (mixed) {
+        if (mode == kModeKeyed) hipLaunchKernelGGL((minplus_kernel<kModeKeyed, 4, 32, true>), grid, block, 0, stream, args);
+        else if (mode == kModeValue) hipLaunchKernelGGL((minplus_kernel<kModeValue, 4, 32, true>), grid, block, 0, stream, args);
+        else hipLaunchKernelGGL((minplus_kernel<kModePlain, 4, 32, true>), grid, block, 0, stream, args);
+    } else if (small_tiles) {
         if (mode == kModeKeyed) hipLaunchKernelGGL((minplus_kernel<kModeKeyed, 4, 32>), grid, block, 0, stream, args);
         else if (mode == kModeValue) hipLaunchKernelGGL((minplus_kernel<kModeValue, 4, 32>), grid, block, 0, stream, args);
         else hipLaunchKernelGGL((minplus_kernel<kModePlain, 4, 32>), grid, block, 0, stream, args);

@@ -119,6 +119,46 @@ def forkjoin_problem(n_modules, C, seed, lo=1, hi=100000, schedule=SCHEDULE_ROUN
     return _problem(name, n_nodes, edges, C, tc, ts, tx, schedule)
 
 
+def resnet_edges(blocks_per_stage=(3, 4, 6, 3), bottleneck: bool = False):
+    """ResNet-shaped DAG: a stem (convolution, pooling), stages of residual blocks, pooling and a
+    fully connected layer.  A block is 2 (``bottleneck``: 3) convolutions followed by an element-wise
+    addition that also receives the block's input; the first block of every stage after the first
+    has a projection convolution on the skip path.  Node ids are topological.  The default is
+    ResNet-34's block counts (55 nodes); (3, 4, 6, 3) with bottlenecks is ResNet-50-shaped."""
+    edges = []
+    nid = 2
+    edges.append((0, 1))                 # stem convolution -> pooling
+    prev = 1
+    for stage, n_blocks in enumerate(blocks_per_stage):
+        for b in range(n_blocks):
+            x = prev
+            for _ in range(3 if bottleneck else 2):
+                edges.append((prev, nid))
+                prev = nid
+                nid += 1
+            if b == 0 and stage > 0:     # projection on the skip path
+                edges.append((x, nid))
+                skip = nid
+                nid += 1
+            else:
+                skip = x
+            add = nid
+            nid += 1
+            edges.append((prev, add))
+            edges.append((skip, add))
+            prev = add
+    edges.append((prev, nid))            # global pooling
+    edges.append((nid, nid + 1))         # fully connected
+    return nid + 2, np.asarray(edges, dtype=np.int32).reshape(-1, 2)
+
+
+def resnet_problem(C, seed, blocks_per_stage=(3, 4, 6, 3), bottleneck=False, lo=1, hi=100000,
+                   schedule=SCHEDULE_ROUNDS):
+    n_nodes, edges = resnet_edges(blocks_per_stage, bottleneck)
+    tc, ts, tx = random_tables(n_nodes, edges, C, seed, (lo, hi), (lo, hi), (lo, hi))
+    return _problem(f"resnet{n_nodes}_C{C}", n_nodes, edges, C, tc, ts, tx, schedule)
+
+
 def config2(C: int = 512, n_modules: int = 10):
     """Inception-shaped DAG, 120 nodes / 189 edges at the default size."""
     return forkjoin_problem(n_modules, C, 2, name=f"cfg2_forkjoin{n_modules}_C{C}")

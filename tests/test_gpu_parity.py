@@ -431,3 +431,10 @@ def test_build_cost_tables_errors(ctx):
     with pytest.raises(LwpError) as e:
         ctx.build_cost_tables(p["layers"], p["edges"], p["configs"], slow)
     assert e.value.code == -4
+
+
+@pytest.mark.parametrize("C,hi,bottleneck", [(3, 2, False), (40, 1000, False), (96, 1 << 20, True), (130, 100000, True)])
+def test_search_resnet_shaped(ctx, C, hi, bottleneck):
+    p = wl.resnet_problem(C, seed=C, bottleneck=bottleneck, lo=0, hi=hi)
+    for schedule in (wl.SCHEDULE_ROUNDS, wl.SCHEDULE_LEFT_FOLD):
+        run_search(ctx, p, schedule)

@@ -123,3 +123,22 @@ def test_no_gpu_means_loud_failure():
         pytest.skip("GPU present")
     with pytest.raises(RuntimeError):
         binding.Context(0)
+
+
+def test_configuration_enumeration_matches_the_oracle(lib):
+    import ctypes
+    from paper_1802_04924_amd import enumerate_configs
+    odd = [(wl.KIND_CONV, 6, 3, 23, 31, 10, 12, 16, 3, 3, 2, 2, 1, 1), (wl.KIND_FC, 3, 7, 4, 6, 9, 1, 1, 4, 6, 1, 1, 0, 0),
+           (wl.KIND_POOL, 1, 7, 6, 8, 7, 1, 3, 3, 3, 1, 1, 0, 0)]
+    for layer in list(wl.alexnet_layers(256)) + list(wl.vgg16_layers(64)) + [np.asarray(x, np.int32) for x in odd]:
+        for n_dev in (1, 2, 3, 6, 16, 32, 64):
+            assert np.array_equal(enumerate_configs(layer, n_dev), oracle.enumerate_configs(layer, n_dev))
+    # capacity smaller than the count: the count is still reported, only `capacity` rows are written
+    layer = np.ascontiguousarray(wl.alexnet_layers(256)[0])
+    out = np.full((5, 6), -1, np.int32)
+    n = ctypes.c_int32(0)
+    assert lib.lwp_enumerate_configs(layer.ctypes.data, 16, out[:4].ctypes.data, 4, ctypes.byref(n)) == binding.OK
+    assert n.value == 163 and (out[4] == -1).all() and np.array_equal(out[:4], oracle.enumerate_configs(layer, 16)[:4])
+    assert lib.lwp_enumerate_configs(layer.ctypes.data, 0, None, 0, ctypes.byref(n)) == binding.E_INVAL
+    assert lib.lwp_enumerate_configs(None, 16, None, 0, ctypes.byref(n)) == binding.E_INVAL
+    assert lib.lwp_enumerate_configs(layer.ctypes.data, 16, None, 4, ctypes.byref(n)) == binding.E_INVAL

@@ -395,3 +395,25 @@ def test_ragged_strategy_cost_hand_example():
     assert best == 43232 and list(S) == [1, 2]
     r = oracle.search_ragged(2, e, [2, 3], tc, ts, tx)
     assert r["cost"] == 43232 and list(r["strategy"]) == [1, 2]
+
+
+def test_resnet_shaped_graph_reduces_to_two_nodes_and_matches_enumeration():
+    # residual blocks: a chain of convolutions in parallel with a skip edge (Sec. 5.2: such graphs
+    # reduce to K = 2); one block per stage keeps the enumeration of all C^N strategies small
+    from oracle import brute
+    n, edges = wl.resnet_edges((1, 1))
+    for C, hi, seed in ((2, 1, 0), (3, 50, 1), (3, 2, 2)):
+        tc, ts, tx = wl.random_tables(n, edges, C, seed, (0, hi), (0, hi), (0, hi))
+        best, S0, n_opt = brute.brute_force(n, edges, C, tc, ts, tx)
+        for schedule in (wl.SCHEDULE_ROUNDS, wl.SCHEDULE_LEFT_FOLD):
+            r = oracle.search(n, edges, C, tc, ts, tx, schedule)
+            assert r["cost"] == best
+            assert oracle.strategy_cost(n, edges, C, tc, ts, tx, r["strategy"]) == best
+            if n_opt == 1:
+                assert np.array_equal(r["strategy"], S0)
+    for bottleneck in (False, True):
+        n, edges = wl.resnet_edges(bottleneck=bottleneck)
+        tc, ts, tx = wl.random_tables(n, edges, 4, 9, (0, 9), (0, 9), (0, 9))
+        r = oracle.search(n, edges, 4, tc, ts, tx)
+        live = {int(s["j"]) for s in r["steps"] if s["kind"] == 0}
+        assert len(live) == n - 2                      # every node but two was eliminated
