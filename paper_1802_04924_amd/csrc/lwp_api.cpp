@@ -104,7 +104,6 @@ bool want_small_tiles(int32_t Ci, int32_t Cj, int32_t Ck, int64_t batch) {
 // Split tiles: a launch with few 64 x 64 tiles lets several workgroups share a tile, each with a
 // part of the c range of at least two stages of 32 candidates.
 // Measured: splitting pays while tiles x parts stays around 1024 workgroups (4 per compute unit).
-constexpr int kSplitMaxParts = 8, kSplitMaxWorkgroups = 1024, kSplitMaxTiles = 512;
 int choose_kparts(int64_t tiles, int32_t Cj, bool small_tiles) {
     if (!small_tiles || tiles > kSplitMaxTiles) return 1;
     const int64_t nstages = (Cj + 31) / 32;
@@ -711,7 +710,7 @@ lwp_status lwp_search_graph_ragged(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edge
                 nw.Ci = tA.rows; nw.Cj = tA.cols; nw.Ck = tB.cols;
                 d.Ci = nw.Ci; d.Cj = nw.Cj; d.Ck = nw.Ck;
                 work.push_back(nw);
-                ud[ni] = {d.arg, d.A, d.w, d.B, s.j, s.i, s.k, s.round, nw.Cj, nw.Ck};
+                ud[ni] = {d.arg, d.A, d.w, d.B, s.j, s.i, s.k, s.round, nw.Cj, nw.Ck, (int32_t)n0, 0};
                 // any fixed c bounds the minimum from above; take the c with the smallest w
                 er[s.e1] = sat({rA.lo + rw.lo + rB.lo, rA.hi + rw.lo + rB.hi});
                 erng[s.e1] = rng_node0 + (int32_t)ni;

@@ -50,6 +50,10 @@ struct NodeArgs {
     int32_t* counters;
 };
 constexpr int64_t kSplitScratchIntsPerPart = 2 * 16 * 256;
+// Capacity of the split-tile buffers every caller of launch_minplus provides: scratch for
+// kSplitMaxWorkgroups parts, one counter for each of kSplitMaxTiles tiles.  A split launch must
+// stay within both (the launcher refuses one that does not).
+constexpr int kSplitMaxParts = 8, kSplitMaxWorkgroups = 1024, kSplitMaxTiles = 512;
 
 constexpr int kTileLarge = 128, kTileSmall = 64, kNodeThreads = 256;
 // largest spread the packed keys can hold: 27 bits with 128 x 128 tiles (16-deep stages), 26 bits
@@ -131,7 +135,10 @@ struct UndoDesc {       // one node elimination of the log
     const int32_t* B;   // table of the out-edge (j,k) [Cj][Ck]
     int32_t j, i, k, round;
     int32_t Cj, Ck;
+    int32_t first;      // index of the first entry of this entry's round (entries are ordered by round)
+    int32_t pad;
 };
+static_assert(sizeof(UndoDesc) == 64, "descriptor layout");
 // keys[p] is a 64-bit (cost, flat index) minimum per component, initialised to all ones.
 // d_flag (optional) is OR-ed with 1 if a sum leaves int32.  max_rows / max_c size the grids.
 hipError_t launch_pair_min(const PairDesc* d_pairs, int32_t n_pairs, int32_t max_rows,

@@ -120,44 +120,6 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
     const gptr O = (gptr)(uintptr_t)d.out;
     const gptr G = (gptr)(uintptr_t)d.arg;
 
-    // ---- the sums must fit int32: checked against the measured ranges of the operands ----
-    if (d.flag) {
-        long long loA = d.loA, hiA = d.hiA, loB = d.loB, hiB = d.hiB, loW = d.loW, hiW = d.hiW;
-        if (d.rngA) { const gcptr r = (gcptr)(uintptr_t)d.rngA; loA = max(loA, (long long)r[0]); hiA = min(hiA, (long long)r[1]); }
-        if (d.rngB) { const gcptr r = (gcptr)(uintptr_t)d.rngB; loB = max(loB, (long long)r[0]); hiB = min(hiB, (long long)r[1]); }
-        if (d.rngW) { const gcptr r = (gcptr)(uintptr_t)d.rngW; loW = max(loW, (long long)r[0]); hiW = min(hiW, (long long)r[1]); }
-        const long long hi = hiA + hiW + hiB, lo = loA + loW + loB;
-        const long long hi2 = hiA + hiW, lo2 = loA + loW;
-        if ((hi > 2147483647ll || lo < -2147483648ll || hi2 > 2147483647ll || lo2 < -2147483648ll) && threadIdx.x == 0)
-            atomicOr(d.flag, 1);
-    }
-
-    // ---- key parameters from value ranges (uniform, scalar) ----
-    int32_t offA = 0, offB = 0;
-    int tb = 0;
-    uint32_t cap = 0xffffffffu;
-    if (KEYED) {
-        long long loA = d.loA, hiA = d.hiA, loW = d.loW, hiW = d.hiW, loB = d.loB, hiB = d.hiB;
-        if (d.rngA) { const gcptr r = (gcptr)(uintptr_t)d.rngA; loA = max(loA, (long long)r[0]); hiA = min(hiA, (long long)r[1]); }
-        if (d.rngB) { const gcptr r = (gcptr)(uintptr_t)d.rngB; loB = max(loB, (long long)r[0]); hiB = min(hiB, (long long)r[1]); }
-        offA = (int32_t)(loA + loW);
-        offB = (int32_t)loB;
-        const long long a_max = hiA + hiW - (loA + loW);          // largest re-based A + w
-        const long long out_max = (hiA - loA) + (hiB - loB);      // largest re-based result
-        const long long capl = min(a_max, out_max + 1);
-        const long long spread = capl + (hiB - loB);
-        cap = (uint32_t)capl;
-        constexpr int TB_MIN = (TK <= 16) ? 5 : 6;               // a chunk holds at least one stage
-        tb = TB_MIN;
-        for (int t = 17; t > TB_MIN; --t)
-            if (spread <= (1ll << (32 - t)) - 2) { tb = t; break; }
-        for (int t = TB_MIN; t < tb; ++t)
-            if (((1 << t) - 1) / TK * TK >= Cj) { tb = t; break; }   // one chunk already covers all c
-    }
-    const uint32_t fmask = KEYED ? ((1u << tb) - 1u) : 0u;
-    const uint32_t padA = KEYED ? ~fmask : 0x7fffffffu;   // never strictly below any running minimum
-    const int spc = KEYED ? (int)(fmask / TK) : 1;        // stages per chunk: TK*spc <= 2^tb - 1
-
     const int tid = threadIdx.x;
     const int tx = tid & 15, ty = tid >> 4;
     // global -> LDS assignment: A: one row, EP consecutive c;  B: one c, EP consecutive columns
@@ -203,6 +165,53 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
         }
         pA += TK; pW += TK; pB += (int64_t)TK * Ck;
     };
+    // part q of a split tile walks stages [q*n_g, (q+1)*n_g); stages past the end of c see only
+    // padding (never a winner)
+    const int nstages = (Cj + TK - 1) / TK;
+    const int n_g = (nstages + kparts - 1) / kparts;
+    const int s_first = part * n_g;
+    if (kparts > 1) { pA += (int64_t)s_first * TK; pW += (int64_t)s_first * TK; pB += (int64_t)s_first * TK * Ck; }
+    // The first stage's loads need only the descriptor's pointers: they are issued before the value
+    // ranges are read, so that the two memory round trips overlap.
+    fetch(s_first * TK);
+
+    // ---- value ranges of the operands: the caller's bounds, tightened by the measured ranges (read
+    //      once: every read is a round trip to memory on the critical path of a small launch) ----
+    long long loA = d.loA, hiA = d.hiA, loB = d.loB, hiB = d.hiB, loW = d.loW, hiW = d.hiW;
+    if (d.rngA) { const gcptr r = (gcptr)(uintptr_t)d.rngA; loA = max(loA, (long long)r[0]); hiA = min(hiA, (long long)r[1]); }
+    if (d.rngB) { const gcptr r = (gcptr)(uintptr_t)d.rngB; loB = max(loB, (long long)r[0]); hiB = min(hiB, (long long)r[1]); }
+    if (d.rngW) { const gcptr r = (gcptr)(uintptr_t)d.rngW; loW = max(loW, (long long)r[0]); hiW = min(hiW, (long long)r[1]); }
+    // the sums must fit int32
+    if (d.flag) {
+        const long long hi = hiA + hiW + hiB, lo = loA + loW + loB;
+        const long long hi2 = hiA + hiW, lo2 = loA + loW;
+        if ((hi > 2147483647ll || lo < -2147483648ll || hi2 > 2147483647ll || lo2 < -2147483648ll) && threadIdx.x == 0)
+            atomicOr(d.flag, 1);
+    }
+
+    // ---- key parameters from value ranges (uniform, scalar) ----
+    int32_t offA = 0, offB = 0;
+    int tb = 0;
+    uint32_t cap = 0xffffffffu;
+    if (KEYED) {
+        offA = (int32_t)(loA + loW);
+        offB = (int32_t)loB;
+        const long long a_max = hiA + hiW - (loA + loW);          // largest re-based A + w
+        const long long out_max = (hiA - loA) + (hiB - loB);      // largest re-based result
+        const long long capl = min(a_max, out_max + 1);
+        const long long spread = capl + (hiB - loB);
+        cap = (uint32_t)capl;
+        constexpr int TB_MIN = (TK <= 16) ? 5 : 6;               // a chunk holds at least one stage
+        tb = TB_MIN;
+        for (int t = 17; t > TB_MIN; --t)
+            if (spread <= (1ll << (32 - t)) - 2) { tb = t; break; }
+        for (int t = TB_MIN; t < tb; ++t)
+            if (((1 << t) - 1) / TK * TK >= Cj) { tb = t; break; }   // one chunk already covers all c
+    }
+    const uint32_t fmask = KEYED ? ((1u << tb) - 1u) : 0u;
+    const uint32_t padA = KEYED ? ~fmask : 0x7fffffffu;   // never strictly below any running minimum
+    const int spc = KEYED ? (int)(fmask / TK) : 1;        // stages per chunk: TK*spc <= 2^tb - 1
+
     // Keys: A side ((A + w - offA, clamped) << tb) - (offB << tb), B side (B << tb) + low field.
     // The re-basing of B rides on the A side (arithmetic is modulo 2^32 and the true sum is in
     // range); the low field, 1 + position of c inside its chunk, rides on the B side, where all
@@ -244,16 +253,8 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
 #pragma unroll
         for (int j = 0; j < RB; ++j) { m1[i][j] = padA; rec[i][j] = 0u; }
 
-    // part q of a split tile walks stages [q*n_g, (q+1)*n_g); stages past the end of c see only
-    // padding (never a winner)
-    const int nstages = (Cj + TK - 1) / TK;
-    const int n_g = (nstages + kparts - 1) / kparts;
-    const int s_first = part * n_g;
     int sic = 0;                      // stage index inside the current chunk
     int chunk_c0 = s_first * TK;      // first c of the current chunk
-    if (kparts > 1) { pA += (int64_t)s_first * TK; pW += (int64_t)s_first * TK; pB += (int64_t)s_first * TK * Ck; }
-
-    fetch(s_first * TK);
     stash(s_first * TK, 0, 0);
     __syncthreads();
 
@@ -368,25 +369,33 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
         __syncthreads();
         if (arrived != kparts - 1) return;     // uniform for the workgroup
         if (tid == 0) __hip_atomic_store(&p.counters[tile_global], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
-        // one part at a time, all of its values in flight together
-        for (int q = 0; q < kparts; ++q) {
-            const int32_t* other = slab + (int64_t)q * (2 * CELLS * NT);
-            int32_t c2[RB][RB], r2[RB][RB];
+        // two parts at a time, all of their values in flight together (one round trip to the
+        // memory side per pair); folded in ascending part order
+        for (int q = 0; q < kparts; q += 2) {
+            const int q1 = min(q + 1, kparts - 1);      // odd part count: the last part is read twice
+            const int32_t* other0 = slab + (int64_t)q * (2 * CELLS * NT);
+            const int32_t* other1 = slab + (int64_t)q1 * (2 * CELLS * NT);
+            int32_t c2[2][RB][RB], r2[2][RB][RB];
 #pragma unroll
             for (int i = 0; i < RB; ++i)
 #pragma unroll
                 for (int j = 0; j < RB; ++j) {
-                    c2[i][j] = __hip_atomic_load(&other[(i * RB + j) * NT + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    r2[i][j] = VALUE ? 0 : __hip_atomic_load(&other[(CELLS + i * RB + j) * NT + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    c2[0][i][j] = __hip_atomic_load(&other0[(i * RB + j) * NT + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    c2[1][i][j] = __hip_atomic_load(&other1[(i * RB + j) * NT + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    r2[0][i][j] = VALUE ? 0 : __hip_atomic_load(&other0[(CELLS + i * RB + j) * NT + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    r2[1][i][j] = VALUE ? 0 : __hip_atomic_load(&other1[(CELLS + i * RB + j) * NT + tid], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
 #pragma unroll
-            for (int i = 0; i < RB; ++i)
+            for (int u = 0; u < 2; ++u)
 #pragma unroll
-                for (int j = 0; j < RB; ++j) {
-                    const bool take = (q == 0) || (c2[i][j] < (int32_t)m1[i][j]);
-                    m1[i][j] = take ? (uint32_t)c2[i][j] : m1[i][j];
-                    rec[i][j] = take ? (uint32_t)r2[i][j] : rec[i][j];
-                }
+                for (int i = 0; i < RB; ++i)
+#pragma unroll
+                    for (int j = 0; j < RB; ++j) {
+                        // strict '<': a repeated part changes nothing
+                        const bool take = (q + u == 0) || (c2[u][i][j] < (int32_t)m1[i][j]);
+                        m1[i][j] = take ? (uint32_t)c2[u][i][j] : m1[i][j];
+                        rec[i][j] = take ? (uint32_t)r2[u][i][j] : rec[i][j];
+                    }
         }
         raw = false;
     }
@@ -443,6 +452,8 @@ hipError_t launch_minplus(const NodeArgs& args, int mode, bool small_tiles, hipS
     const int64_t blocks = (mixed ? (int64_t)args.total_tiles : (int64_t)args.tilesM * args.tilesN * args.batch) * kparts;
     if (blocks <= 0 || blocks > 0x7fffffffLL || args.batch < 1) return hipErrorInvalidValue;
     if (kparts > 1 && (!small_tiles || !args.scratch || !args.counters)) return hipErrorInvalidValue;
+    if (kparts > 1 && (kparts > kSplitMaxParts || blocks / kparts > kSplitMaxTiles || blocks > kSplitMaxWorkgroups))
+        return hipErrorInvalidValue;   // beyond the capacity of the split-tile buffers
     if (mixed && (!small_tiles || !args.descs)) return hipErrorInvalidValue;
     dim3 grid((unsigned)blocks), block(NT);
     if (mixed) {

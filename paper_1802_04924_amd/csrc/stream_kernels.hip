@@ -119,6 +119,7 @@ __global__ void init_workspace_kernel(int32_t* stats, int32_t n_tables, int32_t*
     if (flag && t == 0) *flag = 0;
 }
 
+constexpr int kRangeLoads = 8;      // 16-byte loads a thread keeps in flight
 // Table blockIdx.y is elements [y*cells, (y+1)*cells), or [off[y], off[y+1]) if off is given.
 __global__ __launch_bounds__(kThreads) void ranges_kernel(const int32_t* __restrict__ tables, int64_t cells,
                                                           const int64_t* __restrict__ off,
@@ -131,10 +132,19 @@ __global__ __launch_bounds__(kThreads) void ranges_kernel(const int32_t* __restr
     const int64_t t0 = (int64_t)blockIdx.x * kThreads + threadIdx.x;
     if (((cells & 3) == 0) && ((((uintptr_t)T) & 15) == 0)) {
         const int64_t n4 = cells >> 2;
-        for (int64_t x = t0; x < n4; x += stride) {
-            const int4 v = reinterpret_cast<const int4*>(T)[x];
-            lo = min(min(lo, v.x), min(v.y, min(v.z, v.w)));
-            hi = max(max(hi, v.x), max(v.y, max(v.z, v.w)));
+        const gv4c T4 = (gv4c)(uintptr_t)T;
+        for (int64_t x = t0; x < n4; x += kRangeLoads * stride) {       // independent loads in flight
+            v4i v[kRangeLoads];
+#pragma unroll
+            for (int q = 0; q < kRangeLoads; ++q) {
+                const int64_t y = x + q * stride;
+                v[q] = T4[y < n4 ? y : x];                     // past the end: repeat an element already counted
+            }
+#pragma unroll
+            for (int q = 0; q < kRangeLoads; ++q) {
+                lo = min(min(lo, v[q].x), min(v[q].y, min(v[q].z, v[q].w)));
+                hi = max(max(hi, v[q].x), max(v[q].y, max(v[q].z, v[q].w)));
+            }
         }
     } else {
         for (int64_t x = t0; x < cells; x += stride) { const int v = T[x]; lo = min(lo, v); hi = max(hi, v); }
@@ -326,9 +336,7 @@ __global__ __launch_bounds__(kUndoThreads) void back_substitute_kernel(
     // walk the rounds backwards; node eliminations of one round never depend on each other
     int hi = n_undo;
     while (hi > 0) {
-        const int r = undo[hi - 1].round;
-        int lo = hi - 1;
-        while (lo > 0 && undo[lo - 1].round == r) --lo;
+        const int lo = undo[hi - 1].first;
         if (undo[lo].arg) {
             for (int t = lo + threadIdx.x; t < hi; t += kUndoThreads) {
                 const UndoDesc u = undo[t];
@@ -405,7 +413,7 @@ hipError_t launch_ranges(const int32_t* d_tables, int32_t n_tables, int64_t cell
     unsigned cap = n_tables >= 64 ? 64u : (n_tables >= 8 ? 512u : 4096u);
     for (int32_t t0 = 0; t0 < n_tables; t0 += 65535) {
         const int32_t n = (n_tables - t0) < 65535 ? (n_tables - t0) : 65535;
-        dim3 grid(blocks_for(cells, 16, cap), (unsigned)n);
+        dim3 grid(blocks_for(cells, 4 * kRangeLoads, cap), (unsigned)n);
         hipLaunchKernelGGL(ranges_kernel, grid, dim3(kThreads), 0, stream, d_tables + (int64_t)t0 * cells, cells,
                            (const int64_t*)nullptr, d_stats + 2 * (int64_t)t0);
     }
@@ -418,7 +426,7 @@ hipError_t launch_ranges_var(const int32_t* d_tables, const int64_t* d_off, int3
     unsigned cap = n_tables >= 64 ? 64u : (n_tables >= 8 ? 512u : 4096u);
     for (int32_t t0 = 0; t0 < n_tables; t0 += 65535) {
         const int32_t n = (n_tables - t0) < 65535 ? (n_tables - t0) : 65535;
-        dim3 grid(blocks_for(max_cells, 16, cap), (unsigned)n);
+        dim3 grid(blocks_for(max_cells, 4 * kRangeLoads, cap), (unsigned)n);
         hipLaunchKernelGGL(ranges_kernel, grid, dim3(kThreads), 0, stream, d_tables, (int64_t)0, d_off + t0,
                            d_stats + 2 * (int64_t)t0);
     }
