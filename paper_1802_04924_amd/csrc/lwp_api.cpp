@@ -276,8 +276,9 @@ Layout plan_buffers(const Plan& plan, int32_t n_nodes, int32_t n_edges, const in
 // a single copy.  Tables with a range: input edges, w of every node, output of every node
 // elimination, output of every edge-sum group.
 struct WsLayout {
-    size_t w, head, keys, result, offs, offs_bytes, args, slots, total;
+    size_t w, head, keys, result, args, slots, total;
     size_t desc, desc_bytes;                                   // descriptor block
+    size_t offs, offs_bytes;                                   // row / table offsets, at the start of the block
     size_t node_desc, edge_desc, src_ptrs, pair_desc, singles, undo, comps, tile_begin;   // offsets inside the block
     int32_t n_ranges;
 };
@@ -294,10 +295,10 @@ WsLayout layout_workspace(const Plan& plan, const Layout& L, int32_t n_nodes, in
     o.keys = put(std::max<size_t>(1, plan.pairs.size() + plan.singles.size() + plan.comps.size()) * sizeof(unsigned long long));
     o.result = put((3 + (size_t)n_nodes) * sizeof(int32_t));
     o.offs_bytes = L.uniform ? 0 : ((size_t)n_nodes + 1 + (size_t)n_edges + 1) * sizeof(int64_t);
-    o.offs = put(o.offs_bytes);
     {
         size_t b = 0;
         auto sub = [&](size_t bytes) { size_t at = b; b = align_up(b + bytes, 16); return at; };
+        o.offs = sub(o.offs_bytes);      // first, so that it can be uploaded ahead of the rest
         o.node_desc = sub((size_t)plan.n_node_steps * sizeof(NodeDesc));
         o.edge_desc = sub(L.groups.size() * sizeof(EdgeDesc));
         o.src_ptrs = sub(n_src * sizeof(void*));
@@ -567,8 +568,7 @@ lwp_status lwp_search_graph_ragged(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edge
     if (lwp_status s = ensure_workspace(ctx, W.total)) return s;
     const size_t head_in_bytes = (2 + 2 * (size_t)(n_edges + n_nodes)) * sizeof(int32_t);
     const size_t pin_head = 0, pin_desc = align_up(head_in_bytes, 256), pin_result = pin_desc + align_up(W.desc_bytes, 256);
-    const size_t pin_offs = pin_result + align_up((3 + (size_t)n_nodes) * sizeof(int32_t), 256);
-    if (lwp_status s = ensure_pinned(ctx, pin_offs + W.offs_bytes)) return s;
+    if (lwp_status s = ensure_pinned(ctx, pin_result + (3 + (size_t)n_nodes) * sizeof(int32_t))) return s;
     char* ws = ctx->ws;
     hipStream_t st = ctx->stream;
     int32_t* d_w = reinterpret_cast<int32_t*>(ws + W.w);
@@ -587,28 +587,36 @@ lwp_status lwp_search_graph_ragged(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edge
 
     // 1. w = t_c + t_s with its ranges, and the range of every input table
     int32_t* d_flag = d_head;      // set by any kernel that finds a sum outside int32
-    if (L.uniform) {
-        LWP_HIP(ctx, launch_prepare_search(d_tc, d_ts, d_w, n_nodes, Cn[0], nullptr, d_stats, W.n_ranges, rng_w0, d_keys, n_comp, d_flag, st));
-        LWP_HIP(ctx, launch_ranges(d_tx, n_edges, (int64_t)Cn[0] * Cn[0], d_stats, st));
-    } else {
-        // rows and tables of different sizes: their offsets go to the device first
-        int64_t* h_offs = reinterpret_cast<int64_t*>(ctx->pin + pin_offs);
+    char* hb = ctx->pin + pin_desc;
+    char* db = ws + W.desc;
+    if (!L.uniform) {              // rows and tables of different sizes: the kernels need their offsets
+        int64_t* h_offs = reinterpret_cast<int64_t*>(hb + W.offs);
         std::memcpy(h_offs, L.node_off.data(), ((size_t)n_nodes + 1) * sizeof(int64_t));
         std::memcpy(h_offs + n_nodes + 1, L.tx_off.data(), ((size_t)n_edges + 1) * sizeof(int64_t));
-        int64_t* d_offs = reinterpret_cast<int64_t*>(ws + W.offs);
-        LWP_HIP(ctx, hipMemcpyAsync(d_offs, h_offs, W.offs_bytes, hipMemcpyHostToDevice, st));
-        int64_t max_cells = 1;
-        for (int32_t e = 0; e < n_edges; ++e) max_cells = std::max(max_cells, L.tx_off[e + 1] - L.tx_off[e]);
-        LWP_HIP(ctx, launch_prepare_search(d_tc, d_ts, d_w, n_nodes, 0, d_offs, d_stats, W.n_ranges, rng_w0, d_keys, n_comp, d_flag, st));
-        LWP_HIP(ctx, launch_ranges_var(d_tx, d_offs + n_nodes + 1, n_edges, max_cells, d_stats, st));
     }
+    auto measure_inputs = [&]() -> lwp_status {
+        if (L.uniform) {
+            LWP_HIP(ctx, launch_prepare_search(d_tc, d_ts, d_w, n_nodes, Cn[0], nullptr, d_stats, W.n_ranges, rng_w0, d_keys, n_comp, d_flag, st));
+            LWP_HIP(ctx, launch_ranges(d_tx, n_edges, (int64_t)Cn[0] * Cn[0], d_stats, st));
+        } else {
+            const int64_t* d_offs = reinterpret_cast<const int64_t*>(db + W.offs);
+            int64_t max_cells = 1;
+            for (int32_t e = 0; e < n_edges; ++e) max_cells = std::max(max_cells, L.tx_off[e + 1] - L.tx_off[e]);
+            LWP_HIP(ctx, launch_prepare_search(d_tc, d_ts, d_w, n_nodes, 0, d_offs, d_stats, W.n_ranges, rng_w0, d_keys, n_comp, d_flag, st));
+            LWP_HIP(ctx, launch_ranges_var(d_tx, d_offs + n_nodes + 1, n_edges, max_cells, d_stats, st));
+        }
+        return LWP_OK;
+    };
     // Stored argmin tables need a kernel variant chosen from value ranges, so the ranges of the inputs
-    // are read back (the one mid-search synchronisation).  With recomputed undo every elimination is
-    // value-only (no range condition) and overflow is judged on the device from measured ranges, so
-    // nothing is read back and the host assumes full int32 ranges.
+    // are read back (the one mid-search synchronisation) before the descriptors are written.  With
+    // recomputed undo every elimination is value-only (no range condition) and overflow is judged on
+    // the device from measured ranges: nothing is read back, the host assumes full int32 ranges,
+    // writes the descriptors first and uploads them together with the offsets in one copy.
     int32_t* h_head = reinterpret_cast<int32_t*>(ctx->pin + pin_head);
     int32_t* stats = h_head + 2;
     if (stored) {
+        if (!L.uniform) LWP_HIP(ctx, hipMemcpyAsync(db + W.offs, hb + W.offs, W.offs_bytes, hipMemcpyHostToDevice, st));
+        if (lwp_status s = measure_inputs()) return s;
         LWP_HIP(ctx, hipMemcpyAsync(h_head, d_head, head_in_bytes, hipMemcpyDeviceToHost, st));
         LWP_HIP(ctx, hipStreamSynchronize(st));
         for (int32_t v = 0; v < n_nodes; ++v)
@@ -619,7 +627,6 @@ lwp_status lwp_search_graph_ragged(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edge
 
     // 2. propagate ranges through the plan: every sum any kernel forms must fit int32.  Descriptors
     //    are written straight into the pinned mirror of the device block.
-    char* hb = ctx->pin + pin_desc;
     NodeDesc* nd = reinterpret_cast<NodeDesc*>(hb + W.node_desc);
     EdgeDesc* ed = reinterpret_cast<EdgeDesc*>(hb + W.edge_desc);
     const int32_t** src_ptrs = reinterpret_cast<const int32_t**>(hb + W.src_ptrs);
@@ -629,7 +636,6 @@ lwp_status lwp_search_graph_ragged(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edge
     CompDesc* cd = reinterpret_cast<CompDesc*>(hb + W.comps);
     int32_t* tbeg = reinterpret_cast<int32_t*>(hb + W.tile_begin);
     size_t n_tbeg = 0;
-    char* db = ws + W.desc;
     const NodeDesc* d_nd = reinterpret_cast<const NodeDesc*>(db + W.node_desc);
     const EdgeDesc* d_ed = reinterpret_cast<const EdgeDesc*>(db + W.edge_desc);
     const int32_t* const* d_src = reinterpret_cast<const int32_t* const*>(db + W.src_ptrs);
@@ -650,7 +656,7 @@ lwp_status lwp_search_graph_ragged(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edge
     struct NodeLaunch {
         size_t first, count; int32_t Ci, Cj, Ck; int variant;
         int64_t tile_begin;      // index into the tile_begin block for mixed shapes, else -1
-        int32_t total_tiles, min_Cj; int64_t updates;
+        int32_t total_tiles, split_Cj; int64_t updates;   // split_Cj: the Cj that decides how tiles are split
     };
     struct RoundWork { size_t g0, g1; int64_t edge_cells, edge_max_cells; std::vector<NodeLaunch> launches; };
     std::vector<RoundWork> rounds;
@@ -744,13 +750,13 @@ lwp_status lwp_search_graph_ragged(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edge
                 const bool one_shape = shape_of(work[order[a]]) == shape_of(work[order[b - 1]]);
                 if (small && !one_shape) {
                     // one launch over all shapes: product q owns tiles [tile_begin[q], tile_begin[q+1])
-                    NodeLaunch nl{n0 + a, b - a, 0, 0, 0, v, (int64_t)n_tbeg, 0, INT32_MAX, 0};
+                    NodeLaunch nl{n0 + a, b - a, 0, 0, 0, v, (int64_t)n_tbeg, 0, 0, 0};
                     int64_t tiles = 0;
                     for (size_t q = a; q < b; ++q) {
                         NodeWork& x = work[order[q]];
                         tbeg[n_tbeg++] = (int32_t)tiles;
                         tiles += (int64_t)((x.Ci + kTileSmall - 1) / kTileSmall) * ((x.Ck + kTileSmall - 1) / kTileSmall);
-                        nl.min_Cj = std::min(nl.min_Cj, x.Cj);
+                        nl.split_Cj = std::max(nl.split_Cj, x.Cj);
                         nl.updates += (int64_t)x.Ci * x.Cj * x.Ck;
                     }
                     tbeg[n_tbeg++] = (int32_t)tiles;
@@ -805,6 +811,7 @@ lwp_status lwp_search_graph_ragged(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edge
 
     // 3. descriptors to the device: one copy
     LWP_HIP(ctx, hipMemcpyAsync(db, hb, W.desc_bytes, hipMemcpyHostToDevice, st));
+    if (!stored) { if (lwp_status s = measure_inputs()) return s; }
 
     // 4. eliminations, round by round
     for (const RoundWork& r : rounds) {
@@ -825,9 +832,9 @@ lwp_status lwp_search_graph_ragged(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edge
             const bool mixed = nl.tile_begin >= 0;
             if (mixed) { na.tile_begin = d_tbeg + nl.tile_begin; na.total_tiles = nl.total_tiles; }
             ScopedTimer tm(ctx, 0, nl.updates, keyed);
-            // a launch of mixed shapes splits by its shortest product (parts beyond a product's
-            // stages see only padding)
-            const int kparts = choose_kparts(mixed ? nl.total_tiles : (int64_t)na.tilesM * na.tilesN * na.batch, nl.min_Cj, small);
+            // a launch of mixed shapes splits by its longest product: every product divides its own
+            // stages among the parts, and parts beyond a short product's stages see only padding
+            const int kparts = choose_kparts(mixed ? nl.total_tiles : (int64_t)na.tilesM * na.tilesN * na.batch, nl.split_Cj, small);
             if (kparts > 1) { if (lwp_status s2 = ensure_split_buffers(ctx)) return s2; }
             set_split(ctx, na, kparts);
             LWP_HIP(ctx, launch_minplus(na, mode, small, st));

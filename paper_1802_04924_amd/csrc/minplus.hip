@@ -358,7 +358,10 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
         for (int i = 0; i < RB; ++i)
 #pragma unroll
             for (int j = 0; j < RB; ++j) {
-                const int32_t cst = KEYED ? (int32_t)(m1[i][j] >> tb) + offA + offB : (int32_t)m1[i][j];
+                // a part whose stages all lie beyond Cj still holds the padding key: its cost field plus
+                // the offsets may pass INT32_MAX, so the sum is formed in 64 bits and saturated (real
+                // costs never exceed INT32_MAX, and such a part is the last, so it cannot win a tie)
+                const int32_t cst = KEYED ? (int32_t)min((long long)(m1[i][j] >> tb) + offA + offB, 2147483647ll) : (int32_t)m1[i][j];
                 __hip_atomic_store(&mine[(i * RB + j) * NT + tid], cst, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 if (!VALUE) __hip_atomic_store(&mine[(CELLS + i * RB + j) * NT + tid], (int32_t)rec[i][j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }

@@ -101,6 +101,27 @@ def test_eliminate_node_split_tiles_repeatedly(ctx):
             check_products(ctx, A, w, B)
 
 
+def test_split_tiles_with_an_empty_part_and_costs_next_to_int32_max(ctx):
+    # Cj = 257 is 9 stages of 32; split four ways (3 stages each) the last part has no candidates at
+    # all and holds only padding.  With all costs just below INT32_MAX the padding must still lose.
+    rng = np.random.default_rng(257)
+    for Cj in (257, 260, 288):
+        base = 1 << 30
+        A = rng.integers(base, base + 1000, size=(1, 130, Cj), endpoint=True, dtype=np.int32)
+        w = rng.integers(0, 1000, size=(1, Cj), endpoint=True, dtype=np.int32)
+        B = rng.integers(base - 5000, base - 4000, size=(1, Cj, 140), endpoint=True, dtype=np.int32)
+        check_products(ctx, A, w, B, expect_keyed=True)
+        # the same through a search whose round mixes shapes (parts are sized for the longest product)
+    Cn = np.array([70, 257, 40, 33, 64, 288, 50], np.int32)
+    edges = wl.chain_edges(len(Cn))
+    tc, ts, tx = wl.ragged_tables(len(Cn), edges, Cn, 5, 0, 1000)
+    tx = (tx.astype(np.int64) + (1 << 28)).astype(np.int32)          # 6 edges: totals stay below 2^31
+    ref = oracle.search_ragged(len(Cn), edges, Cn, tc, ts, tx)
+    for undo in (0, 1):
+        cost, S = ctx.search_graph_ragged(len(Cn), edges, Cn, dev(tc), dev(ts), dev(tx), 0, undo)
+        assert cost == ref["cost"] and np.array_equal(S, ref["strategy"])
+
+
 def test_eliminate_node_negative_and_offset_values(ctx):
     rng = np.random.default_rng(11)
     A = rng.integers(-(1 << 20), 1 << 10, size=(2, 70, 90, ), dtype=np.int32).reshape(2, 70, 90)
