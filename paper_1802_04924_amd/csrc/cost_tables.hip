@@ -15,7 +15,7 @@
 #include <vector>
 
 #include "lwp.h"
-#include "lwp_internal.h"
+#include "lwp_context.h"
 
 namespace {
 
@@ -144,22 +144,22 @@ lwp_status build_tables(lwp_ctx* ctx, const lwp_layer* layers, int32_t n_layers,
                         int32_t n_edges, const lwp_config* cfgs, const int32_t* Cn, bool shared,
                         const lwp_machine* machine, int32_t* d_tc, int32_t* d_ts, int32_t* d_tx) {
     if (machine->n_devices < 1 || machine->flop_per_ns < 1 || machine->byte_per_ns < 1 || machine->invalid_cost < 0)
-        return lwp::ctx_fail(ctx, LWP_E_INVAL, "machine constants must be positive");
+        return lwp::fail(ctx, LWP_E_INVAL, "machine constants must be positive");
     for (int32_t l = 0; l < n_layers; ++l) {
         const lwp_layer& L = layers[l];
-        if (L.kind < KIND_CONV || L.kind > KIND_FC) return lwp::ctx_fail(ctx, LWP_E_INVAL, "unknown layer kind");
+        if (L.kind < KIND_CONV || L.kind > KIND_FC) return lwp::fail(ctx, LWP_E_INVAL, "unknown layer kind");
         if (L.N < 1 || L.Cin < 1 || L.Hin < 1 || L.Win < 1 || L.Cout < 1 || L.Hout < 1 || L.Wout < 1 || L.kh < 1 ||
             L.kw < 1 || L.sh < 1 || L.sw < 1 || L.ph < 0 || L.pw < 0)
-            return lwp::ctx_fail(ctx, LWP_E_INVAL, "layer extents must be positive");
-        if (Cn[l] < 1 || Cn[l] > 65535) return lwp::ctx_fail(ctx, LWP_E_INVAL, "a layer needs 1..65535 configurations");
+            return lwp::fail(ctx, LWP_E_INVAL, "layer extents must be positive");
+        if (Cn[l] < 1 || Cn[l] > 65535) return lwp::fail(ctx, LWP_E_INVAL, "a layer needs 1..65535 configurations");
     }
     for (int32_t e = 0; e < n_edges; ++e) {
         const int32_t p = edges[2 * e], q = edges[2 * e + 1];
         if (p < 0 || p >= n_layers || q < 0 || q >= n_layers || p == q)
-            return lwp::ctx_fail(ctx, LWP_E_GRAPH, "edge endpoint out of range");
+            return lwp::fail(ctx, LWP_E_GRAPH, "edge endpoint out of range");
         const lwp_layer &P = layers[p], &Q = layers[q];
         if (P.N != Q.N || P.Cout != Q.Cin || P.Hout != Q.Hin || P.Wout != Q.Win)
-            return lwp::ctx_fail(ctx, LWP_E_INVAL, "producer output and consumer input shapes differ");
+            return lwp::fail(ctx, LWP_E_INVAL, "producer output and consumer input shapes differ");
     }
     std::vector<LayerSlice> slices((size_t)n_layers);
     std::vector<int64_t> tx_off((size_t)(n_edges > 0 ? n_edges : 1));
@@ -174,14 +174,14 @@ lwp_status build_tables(lwp_ctx* ctx, const lwp_layer* layers, int32_t n_layers,
     int64_t cells = 0;
     for (int32_t e = 0; e < n_edges; ++e) { tx_off[e] = cells; cells += (int64_t)Cn[edges[2 * e]] * Cn[edges[2 * e + 1]]; }
 
-    hipStream_t st = lwp::ctx_stream(ctx);
+    hipStream_t st = ctx->stream;
     const size_t bl = (size_t)n_layers * sizeof(lwp_layer), bs = (size_t)n_layers * sizeof(LayerSlice),
                  bc = (size_t)cfg_rows * sizeof(lwp_config), be = (size_t)(n_edges > 0 ? n_edges : 1) * 2 * sizeof(int32_t),
                  bo = tx_off.size() * sizeof(int64_t);
     auto up = [](size_t v) { return (v + 255) / 256 * 256; };
     const size_t off_s = up(bl), off_c = off_s + up(bs), off_e = off_c + up(bc), off_o = off_e + up(be), off_f = off_o + up(bo);
     char* d = nullptr;
-    if (hipMalloc(&d, off_f + 256) != hipSuccess) { (void)hipGetLastError(); return lwp::ctx_fail(ctx, LWP_E_NOMEM, "descriptor upload buffer"); }
+    if (hipMalloc(&d, off_f + 256) != hipSuccess) { (void)hipGetLastError(); return lwp::fail(ctx, LWP_E_NOMEM, "descriptor upload buffer"); }
     lwp_status result = LWP_OK;
     int32_t flag = 0;
     hipError_t herr = hipSuccess;
@@ -214,8 +214,8 @@ lwp_status build_tables(lwp_ctx* ctx, const lwp_layer* layers, int32_t n_layers,
     }
     ok(hipStreamSynchronize(st));
     (void)hipFree(d);
-    if (herr != hipSuccess) return lwp::ctx_fail(ctx, LWP_E_HIP, hipGetErrorString(herr));
-    if (flag) result = lwp::ctx_fail(ctx, LWP_E_OVERFLOW, "a cost does not fit int32 nanoseconds");
+    if (herr != hipSuccess) return lwp::fail(ctx, LWP_E_HIP, hipGetErrorString(herr));
+    if (flag) result = lwp::fail(ctx, LWP_E_OVERFLOW, "a cost does not fit int32 nanoseconds");
     return result;
 }
 
@@ -226,11 +226,11 @@ extern "C" lwp_status lwp_build_cost_tables(lwp_ctx* ctx, const lwp_layer* layer
                                             int32_t C, const lwp_machine* machine,
                                             int32_t* d_tc, int32_t* d_ts, int32_t* d_tx) {
     if (!ctx) return LWP_E_INVAL;
-    if (lwp_status rc = lwp::ctx_enter(ctx)) return rc;
+    if (lwp_status rc = lwp::check_ctx(ctx)) return rc;
     if (!layers || !cfgs || !machine || !d_tc || !d_ts || (n_edges > 0 && (!edges || !d_tx)))
-        return lwp::ctx_fail(ctx, LWP_E_INVAL, "null pointer");
+        return lwp::fail(ctx, LWP_E_INVAL, "null pointer");
     if (n_layers < 1 || n_edges < 0 || C < 1 || C > 65535)
-        return lwp::ctx_fail(ctx, LWP_E_INVAL, "bad sizes");
+        return lwp::fail(ctx, LWP_E_INVAL, "bad sizes");
     const std::vector<int32_t> Cn((size_t)n_layers, C);
     return build_tables(ctx, layers, n_layers, edges, n_edges, cfgs, Cn.data(), true, machine, d_tc, d_ts, d_tx);
 }
@@ -240,10 +240,10 @@ extern "C" lwp_status lwp_build_cost_tables_ragged(lwp_ctx* ctx, const lwp_layer
                                                    const int32_t* C_node, const lwp_machine* machine,
                                                    int32_t* d_tc, int32_t* d_ts, int32_t* d_tx) {
     if (!ctx) return LWP_E_INVAL;
-    if (lwp_status rc = lwp::ctx_enter(ctx)) return rc;
+    if (lwp_status rc = lwp::check_ctx(ctx)) return rc;
     if (!layers || !cfgs || !C_node || !machine || !d_tc || !d_ts || (n_edges > 0 && (!edges || !d_tx)))
-        return lwp::ctx_fail(ctx, LWP_E_INVAL, "null pointer");
-    if (n_layers < 1 || n_edges < 0) return lwp::ctx_fail(ctx, LWP_E_INVAL, "bad sizes");
+        return lwp::fail(ctx, LWP_E_INVAL, "null pointer");
+    if (n_layers < 1 || n_edges < 0) return lwp::fail(ctx, LWP_E_INVAL, "bad sizes");
     return build_tables(ctx, layers, n_layers, edges, n_edges, cfgs, C_node, false, machine, d_tc, d_ts, d_tx);
 }
 

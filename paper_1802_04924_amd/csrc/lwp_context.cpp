@@ -1,0 +1,169 @@
+// Context life cycle, its buffers, launch timing (C ABI: lwp_create ... lwp_profile_read).
+#include "lwp_context.h"
+
+#include <new>
+
+namespace lwp {
+
+lwp_status fail(lwp_ctx* ctx, lwp_status s, const std::string& why) {
+    if (ctx) ctx->err = why;
+    return s;
+}
+
+lwp_status check_ctx(lwp_ctx* ctx) {
+    if (!ctx) return LWP_E_INVAL;
+    ctx->err.clear();
+    hipError_t e = hipSetDevice(ctx->device);
+    if (e != hipSuccess) return fail(ctx, LWP_E_HIP, std::string("hipSetDevice: ") + hipGetErrorString(e));
+    return LWP_OK;
+}
+
+lwp_status ensure_workspace(lwp_ctx* ctx, size_t bytes) {
+    if (bytes <= ctx->ws_bytes) return LWP_OK;
+    LWP_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    if (ctx->ws) { LWP_HIP(ctx, hipFree(ctx->ws)); ctx->ws = nullptr; ctx->ws_bytes = 0; }
+    void* p = nullptr;
+    hipError_t e = hipMalloc(&p, bytes);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(ctx, LWP_E_NOMEM, "device workspace of " + std::to_string(bytes) + " bytes: " + hipGetErrorString(e));
+    }
+    ctx->ws = static_cast<char*>(p);
+    ctx->ws_bytes = bytes;
+    return LWP_OK;
+}
+
+lwp_status ensure_pinned(lwp_ctx* ctx, size_t bytes) {
+    if (bytes <= ctx->pin_bytes) return LWP_OK;
+    LWP_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    if (ctx->pin) { LWP_HIP(ctx, hipHostFree(ctx->pin)); ctx->pin = nullptr; ctx->pin_bytes = 0; }
+    void* p = nullptr;
+    bytes = align_up(bytes, 1 << 16);
+    hipError_t e = hipHostMalloc(&p, bytes, hipHostMallocDefault);
+    if (e != hipSuccess) { (void)hipGetLastError(); return fail(ctx, LWP_E_NOMEM, std::string("pinned host buffer: ") + hipGetErrorString(e)); }
+    ctx->pin = static_cast<char*>(p);
+    ctx->pin_bytes = bytes;
+    return LWP_OK;
+}
+
+lwp_status ensure_split_buffers(lwp_ctx* ctx) {
+    if (ctx->split) return LWP_OK;
+    const size_t ints = (size_t)kSplitMaxWorkgroups * kSplitScratchIntsPerPart + kSplitMaxTiles;
+    void* p = nullptr;
+    hipError_t e = hipMalloc(&p, ints * sizeof(int32_t));
+    if (e != hipSuccess) { (void)hipGetLastError(); return fail(ctx, LWP_E_NOMEM, std::string("split-tile scratch: ") + hipGetErrorString(e)); }
+    ctx->split = static_cast<int32_t*>(p);
+    // the counters start at zero and every launch leaves them at zero
+    LWP_HIP(ctx, hipMemsetAsync(ctx->split + (size_t)kSplitMaxWorkgroups * kSplitScratchIntsPerPart, 0,
+                                kSplitMaxTiles * sizeof(int32_t), ctx->stream));
+    return LWP_OK;
+}
+
+void set_split(lwp_ctx* ctx, NodeArgs& a, int kparts) {
+    a.kparts = kparts;
+    a.scratch = kparts > 1 ? ctx->split : nullptr;
+    a.counters = kparts > 1 ? ctx->split + (size_t)kSplitMaxWorkgroups * kSplitScratchIntsPerPart : nullptr;
+}
+
+ScopedTimer::ScopedTimer(lwp_ctx* c, int kind, int64_t work, bool keyed) : ctx(c) {
+    if (!c->profiling) return;
+    lwp_ctx::Timed t{nullptr, nullptr, kind, work, keyed};
+    if (hipEventCreate(&t.a) != hipSuccess || hipEventCreate(&t.b) != hipSuccess) return;
+    hipEventRecord(t.a, c->stream);
+    c->timed.push_back(t);
+    idx = c->timed.size() - 1;
+}
+ScopedTimer::~ScopedTimer() { if (idx != (size_t)-1) hipEventRecord(ctx->timed[idx].b, ctx->stream); }
+
+lwp_status drain_profile(lwp_ctx* ctx) {
+    LWP_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    for (auto& t : ctx->timed) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, t.a, t.b) == hipSuccess) {
+            if (t.kind == 0) {
+                ctx->prof.node_launches++; ctx->prof.node_cell_updates += t.work; ctx->prof.node_ms += ms;
+                if (t.keyed) ctx->prof.keyed_launches++;
+            } else {
+                ctx->prof.edge_launches++; ctx->prof.edge_cells += t.work; ctx->prof.edge_ms += ms;
+            }
+        }
+        hipEventDestroy(t.a); hipEventDestroy(t.b);
+    }
+    ctx->timed.clear();
+    return LWP_OK;
+}
+
+}  // namespace lwp
+
+using namespace lwp;
+
+extern "C" {
+
+const char* lwp_status_string(lwp_status s) {
+    switch (s) {
+        case LWP_OK: return "ok";
+        case LWP_E_INVAL: return "invalid argument";
+        case LWP_E_GRAPH: return "invalid graph";
+        case LWP_E_NOT_REDUCIBLE: return "graph not reducible";
+        case LWP_E_OVERFLOW: return "int32 overflow possible";
+        case LWP_E_NOMEM: return "out of memory";
+        case LWP_E_HIP: return "HIP error";
+    }
+    return "unknown status";
+}
+
+lwp_status lwp_create(lwp_ctx** out, int device, void* hip_stream) {
+    if (!out) return LWP_E_INVAL;
+    *out = nullptr;
+    int n = 0;
+    if (hipGetDeviceCount(&n) != hipSuccess || device < 0 || device >= n) return LWP_E_HIP;
+    if (hipSetDevice(device) != hipSuccess) return LWP_E_HIP;
+    lwp_ctx* c = new (std::nothrow) lwp_ctx();
+    if (!c) return LWP_E_NOMEM;
+    c->device = device;
+    c->stream = static_cast<hipStream_t>(hip_stream);
+    *out = c;
+    return LWP_OK;
+}
+
+void lwp_destroy(lwp_ctx* ctx) {
+    if (!ctx) return;
+    (void)hipSetDevice(ctx->device);
+    (void)hipStreamSynchronize(ctx->stream);
+    for (auto& t : ctx->timed) { hipEventDestroy(t.a); hipEventDestroy(t.b); }
+    if (ctx->ws) (void)hipFree(ctx->ws);
+    if (ctx->pin) (void)hipHostFree(ctx->pin);
+    if (ctx->split) (void)hipFree(ctx->split);
+    delete ctx;
+}
+
+const char* lwp_last_error(const lwp_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+lwp_status lwp_synchronize(lwp_ctx* ctx) {
+    if (lwp_status s = check_ctx(ctx)) return s;
+    LWP_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    return LWP_OK;
+}
+
+lwp_status lwp_profile_enable(lwp_ctx* ctx, int32_t on) {
+    if (lwp_status s = check_ctx(ctx)) return s;
+    ctx->profiling = on != 0;
+    return LWP_OK;
+}
+
+lwp_status lwp_profile_reset(lwp_ctx* ctx) {
+    if (lwp_status s = check_ctx(ctx)) return s;
+    if (lwp_status s = drain_profile(ctx)) return s;
+    ctx->prof = lwp_profile{};
+    return LWP_OK;
+}
+
+lwp_status lwp_profile_read(lwp_ctx* ctx, lwp_profile* out) {
+    if (lwp_status s = check_ctx(ctx)) return s;
+    if (!out) return fail(ctx, LWP_E_INVAL, "null output");
+    if (lwp_status s = drain_profile(ctx)) return s;
+    *out = ctx->prof;
+    return LWP_OK;
+}
+
+}  // extern "C"

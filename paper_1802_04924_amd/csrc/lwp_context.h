@@ -1,0 +1,101 @@
+// The library's context and the helpers every translation unit behind the C ABI shares: error
+// recording, the context's growing device workspace and pinned staging buffer, the split-tile
+// buffers, launch timing, and the policy that picks a min-plus kernel variant.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "lwp.h"
+#include "lwp_kernels.h"
+
+struct lwp_ctx {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    std::string err;
+    char* ws = nullptr;        // device workspace
+    size_t ws_bytes = 0;
+    char* pin = nullptr;       // pinned host staging (descriptor upload, small read-backs)
+    size_t pin_bytes = 0;
+    int32_t* split = nullptr;  // scratch + per-tile counters of split tiles (see minplus.hip)
+    bool profiling = false;
+    struct Timed { hipEvent_t a, b; int kind; int64_t work; bool keyed; };
+    std::vector<Timed> timed;
+    lwp_profile prof{};
+};
+
+namespace lwp {
+
+constexpr int64_t kI32Max = 2147483647LL, kI32Min = -2147483648LL;
+constexpr int kMaxConfigs = 65536;
+
+// Records `why` as the context's last error and returns `s`.
+lwp_status fail(lwp_ctx* ctx, lwp_status s, const std::string& why);
+
+#define LWP_HIP(ctx, call)                                                                     \
+    do {                                                                                       \
+        hipError_t e_ = (call);                                                                \
+        if (e_ != hipSuccess)                                                                  \
+            return ::lwp::fail(ctx, e_ == hipErrorOutOfMemory ? LWP_E_NOMEM : LWP_E_HIP,       \
+                               std::string(#call) + ": " + hipGetErrorString(e_));             \
+    } while (0)
+
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Clears the last error and makes the context's device current.
+lwp_status check_ctx(lwp_ctx* ctx);
+// Grow-only buffers of the context (a growth synchronises the stream and reallocates).
+lwp_status ensure_workspace(lwp_ctx* ctx, size_t bytes);
+lwp_status ensure_pinned(lwp_ctx* ctx, size_t bytes);
+// Scratch and arrival counters of split tiles, allocated on first use; set_split points a
+// launch at them.
+lwp_status ensure_split_buffers(lwp_ctx* ctx);
+void set_split(lwp_ctx* ctx, NodeArgs& a, int kparts);
+
+// Brackets one launch with HIP events while profiling is on (kind 0: node elimination with
+// `work` cell updates, kind 1: edge elimination with `work` cells).
+struct ScopedTimer {
+    lwp_ctx* ctx;
+    size_t idx = (size_t)-1;
+    ScopedTimer(lwp_ctx* c, int kind, int64_t work, bool keyed);
+    ~ScopedTimer();
+};
+// Synchronises and folds the recorded events into ctx->prof.
+lwp_status drain_profile(lwp_ctx* ctx);
+
+// ---- choice of the min-plus kernel variant -----------------------------------------------------
+struct Range { int64_t lo, hi; };
+inline bool fits(int64_t v) { return v >= kI32Min && v <= kI32Max; }
+
+// Spread the packed-key arithmetic must represent for one product (see minplus.hip): re-based
+// A + w, clamped just above the largest possible result where that is tighter, plus re-based B.
+inline int64_t keyed_spread(Range rA, Range rw, Range rB) {
+    const int64_t a_max = rA.hi + rw.hi - (rA.lo + rw.lo);
+    const int64_t out_max = (rA.hi - rA.lo) + (rB.hi - rB.lo);
+    return std::min(a_max, out_max + 1) + (rB.hi - rB.lo);
+}
+
+// Tile choice.  Measured on MI355X the 64 x 64 variant (4 waves per SIMD, 32-deep stages) matches or
+// beats the 128 x 128 variant except for very large batches of short products (Cj < 512), where
+// its four times as many workgroup start-ups show; it also quantises a launch four times finer.
+inline int64_t large_tiles(int32_t Ci, int32_t Ck, int64_t batch) {
+    return (int64_t)((Ci + kTileLarge - 1) / kTileLarge) * ((Ck + kTileLarge - 1) / kTileLarge) * batch;
+}
+inline bool want_small_tiles(int32_t Ci, int32_t Cj, int32_t Ck, int64_t batch) {
+    return large_tiles(Ci, Ck, batch) < 2048 || Cj >= 512;
+}
+
+// Split tiles: a launch with few 64 x 64 tiles lets several workgroups share a tile, each with a
+// part of the c range of at least two stages of 32 candidates.
+// Measured: splitting pays while tiles x parts stays around 1024 workgroups (4 per compute unit).
+inline int choose_kparts(int64_t tiles, int32_t Cj, bool small_tiles) {
+    if (!small_tiles || tiles > kSplitMaxTiles) return 1;
+    const int64_t nstages = (Cj + 31) / 32;
+    int64_t k = std::min<int64_t>({kSplitMaxParts, kSplitMaxWorkgroups / tiles, nstages / 2});
+    return k < 2 ? 1 : (int)k;
+}
+
+}  // namespace lwp

@@ -1,0 +1,672 @@
+// Alg. 1 behind the C ABI: buffer planning, value-range analysis, descriptors and the launch
+// sequence of a whole search (eliminate -> solve the residual graph -> undo).
+#include <cstring>
+#include <map>
+#include <tuple>
+
+#include "lwp_context.h"
+#include "lwp_plan.h"
+
+using namespace lwp;
+
+namespace {
+
+// ---- buffer planning of a whole search ---------------------------------------------------------
+// Node l has Cn[l] configurations (Sec. 3: every layer has its own configuration set), so the
+// table of an edge (i, j) is Cn[i] x Cn[j] and tables differ in size.  Tables produced by
+// eliminations live in an arena; a region is released once the step that consumed it has been
+// enqueued (launches of one stream run in order) and reused by later tables of the same size.
+struct TableRef {
+    bool is_slot;        // false: element offset into the caller's concatenated t_x; true: into the arena
+    int64_t off;
+    int32_t rows, cols;
+    int64_t cells() const { return (int64_t)rows * cols; }
+};
+
+struct EdgeGroup { int32_t keep; std::vector<int32_t> others; int32_t round; };
+
+struct Layout {
+    std::vector<EdgeGroup> groups;            // edge eliminations grouped per (round, kept edge)
+    std::vector<TableRef> node_A, node_B, node_out;   // per node step (in plan order)
+    std::vector<int64_t> node_arg_off;        // element offset of the step's argmin table
+    std::vector<std::vector<TableRef>> group_src;
+    std::vector<TableRef> group_out;
+    std::vector<TableRef> final_table;        // per residual pair
+    std::vector<std::vector<TableRef>> comp_tables;   // per enumerated component, per edge
+    std::vector<int64_t> node_off, tx_off;    // element offsets of w rows / input tables (+ total)
+    int64_t slot_elems = 0, arg_elems = 0;
+    bool uniform = true;                      // every node has the same number of configurations
+};
+
+constexpr int64_t kArenaAlign = 64;           // elements: regions start on 256-byte boundaries
+
+// keep_inputs: tables consumed by node eliminations stay alive (the undo pass re-reads them).
+Layout plan_buffers(const Plan& plan, int32_t n_nodes, int32_t n_edges, const int32_t* edges, const int32_t* Cn,
+                    bool keep_inputs) {
+    Layout L;
+    L.node_off.resize((size_t)n_nodes + 1);
+    L.tx_off.resize((size_t)n_edges + 1);
+    L.node_off[0] = 0;
+    for (int32_t v = 0; v < n_nodes; ++v) {
+        L.node_off[v + 1] = L.node_off[v] + Cn[v];
+        if (Cn[v] != Cn[0]) L.uniform = false;
+    }
+    std::vector<TableRef> cur(n_edges);
+    L.tx_off[0] = 0;
+    for (int32_t e = 0; e < n_edges; ++e) {
+        cur[e] = {false, L.tx_off[e], Cn[edges[2 * e]], Cn[edges[2 * e + 1]]};
+        L.tx_off[e + 1] = L.tx_off[e] + cur[e].cells();
+    }
+    std::map<int64_t, std::vector<int64_t>> free_regions;    // by size in elements
+    auto take = [&](int32_t rows, int32_t cols) {
+        const int64_t cells = (int64_t)rows * cols;
+        auto& fl = free_regions[cells];
+        int64_t off;
+        if (!fl.empty()) { off = fl.back(); fl.pop_back(); }
+        else { off = L.slot_elems; L.slot_elems += (cells + kArenaAlign - 1) / kArenaAlign * kArenaAlign; }
+        return TableRef{true, off, rows, cols};
+    };
+    auto give_back = [&](const std::vector<TableRef>& rs) { for (auto& r : rs) free_regions[r.cells()].push_back(r.off); };
+    size_t t = 0;
+    const size_t n = plan.steps.size();
+    while (t < n) {
+        const int32_t round = plan.steps[t].round;
+        // E-phase of this round
+        std::vector<TableRef> release;
+        while (t < n && plan.steps[t].round == round && plan.steps[t].kind == 1) {
+            EdgeGroup g{plan.steps[t].e1, {}, round};
+            while (t < n && plan.steps[t].round == round && plan.steps[t].kind == 1 && plan.steps[t].e1 == g.keep) {
+                g.others.push_back(plan.steps[t].e2);
+                ++t;
+            }
+            std::vector<TableRef> src{cur[g.keep]};
+            for (int32_t o : g.others) { src.push_back(cur[o]); if (cur[o].is_slot) release.push_back(cur[o]); }
+            const TableRef out = cur[g.keep].is_slot ? cur[g.keep] : take(cur[g.keep].rows, cur[g.keep].cols);   // in place when possible
+            cur[g.keep] = out;
+            L.groups.push_back(g); L.group_src.push_back(src); L.group_out.push_back(out);
+        }
+        give_back(release);
+        release.clear();
+        // N-phase of this round
+        while (t < n && plan.steps[t].round == round && plan.steps[t].kind == 0) {
+            const lwp_step& st = plan.steps[t];
+            const TableRef A = cur[st.e1], B = cur[st.e2];
+            L.node_A.push_back(A); L.node_B.push_back(B);
+            if (!keep_inputs && A.is_slot) release.push_back(A);
+            if (!keep_inputs && B.is_slot) release.push_back(B);
+            const TableRef out = take(A.rows, B.cols);
+            L.node_out.push_back(out);
+            L.node_arg_off.push_back(L.arg_elems);
+            L.arg_elems += (out.cells() + kArenaAlign - 1) / kArenaAlign * kArenaAlign;
+            cur[st.e1] = out;
+            ++t;
+        }
+        give_back(release);
+    }
+    for (auto& p : plan.pairs) L.final_table.push_back(cur[p.edge]);
+    for (auto& c : plan.comps) {
+        std::vector<TableRef> tabs;
+        for (int32_t e : c.edges) tabs.push_back(cur[e]);
+        L.comp_tables.push_back(tabs);
+    }
+    return L;
+}
+
+// Device workspace of one search.  The descriptor block is mirrored in pinned host memory and
+// uploaded with a single copy; `head` = {overflow flag, pad, [min,max] per table} is read back with
+// a single copy.  Tables with a range: input edges, w of every node, output of every node
+// elimination, output of every edge-sum group.
+struct WsLayout {
+    size_t w, head, keys, result, args, slots, total;
+    size_t desc, desc_bytes;                                   // descriptor block
+    size_t offs, offs_bytes;                                   // row / table offsets, at the start of the block
+    size_t node_desc, edge_desc, src_ptrs, pair_desc, singles, undo, comps, tile_begin;   // offsets inside the block
+    int32_t n_ranges;
+};
+
+WsLayout layout_workspace(const Plan& plan, const Layout& L, int32_t n_nodes, int32_t n_edges, bool stored_argmin) {
+    WsLayout o{};
+    size_t off = 0;
+    auto put = [&](size_t bytes) { size_t at = off; off = align_up(off + bytes, 256); return at; };
+    size_t n_src = 0;
+    for (auto& g : L.group_src) n_src += g.size();
+    o.n_ranges = n_edges + n_nodes + plan.n_node_steps + (int32_t)L.groups.size();
+    o.w = put((size_t)L.node_off[n_nodes] * sizeof(int32_t));
+    o.head = put((2 + 2 * (size_t)o.n_ranges) * sizeof(int32_t));
+    o.keys = put(std::max<size_t>(1, plan.pairs.size() + plan.singles.size() + plan.comps.size()) * sizeof(unsigned long long));
+    o.result = put((3 + (size_t)n_nodes) * sizeof(int32_t));
+    o.offs_bytes = L.uniform ? 0 : ((size_t)n_nodes + 1 + (size_t)n_edges + 1) * sizeof(int64_t);
+    {
+        size_t b = 0;
+        auto sub = [&](size_t bytes) { size_t at = b; b = align_up(b + bytes, 16); return at; };
+        o.offs = sub(o.offs_bytes);      // first, so that it can be uploaded ahead of the rest
+        o.node_desc = sub((size_t)plan.n_node_steps * sizeof(NodeDesc));
+        o.edge_desc = sub(L.groups.size() * sizeof(EdgeDesc));
+        o.src_ptrs = sub(n_src * sizeof(void*));
+        o.pair_desc = sub(plan.pairs.size() * sizeof(PairDesc));
+        o.singles = sub(plan.singles.size() * sizeof(SingleDesc));
+        o.undo = sub((size_t)plan.n_node_steps * sizeof(UndoDesc));
+        o.comps = sub(plan.comps.size() * sizeof(CompDesc));
+        o.tile_begin = sub((2 * (size_t)plan.n_node_steps + 2) * sizeof(int32_t));   // launches of mixed shapes
+        o.desc_bytes = std::max<size_t>(b, 16);
+    }
+    o.desc = put(o.desc_bytes);
+    o.args = put(stored_argmin ? (size_t)L.arg_elems * sizeof(int32_t) : 0);
+    o.slots = put((size_t)L.slot_elems * sizeof(int32_t));
+    o.total = off;
+    return o;
+}
+
+// A residual component is enumerated outright; its flat strategy index must fit 32 bits.
+bool components_enumerable(const Plan& plan, const int32_t* Cn) {
+    for (auto& c : plan.comps) {
+        unsigned long long n = 1;
+        for (int32_t v : c.nodes) {
+            n *= (unsigned long long)Cn[v];
+            if (n > (1ull << 32)) return false;
+        }
+    }
+    return true;
+}
+
+bool counts_valid(int32_t n_nodes, const int32_t* Cn) {
+    if (!Cn) return false;
+    for (int32_t v = 0; v < n_nodes; ++v)
+        if (Cn[v] < 1 || Cn[v] > kMaxConfigs) return false;
+    return true;
+}
+
+
+// One search: what the host decides (plan, buffers, descriptors, launches) and the order in which
+// it is put on the stream.  The device workspace and the pinned mirror are handed in by the caller.
+class Search {
+public:
+    Search(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, const int32_t* edges, const int32_t* Cn,
+           const int32_t* d_tc, const int32_t* d_ts, const int32_t* d_tx, int32_t schedule, bool stored)
+        : ctx_(ctx), n_nodes_(n_nodes), n_edges_(n_edges), edges_(edges), Cn_(Cn), d_tc_(d_tc), d_ts_(d_ts),
+          d_tx_(d_tx), schedule_(schedule), stored_(stored) {}
+
+    // Validates the graph, fixes the schedule and lays out the buffers (host only).
+    lwp_status plan();
+    size_t workspace_bytes() const { return W_.total; }
+    size_t pinned_bytes() const { return pin_result_ + (3 + (size_t)n_nodes_) * sizeof(int32_t); }
+    void bind(char* ws, char* pin);
+
+    // Stored argmin tables need a kernel variant chosen from value ranges, so the ranges of the inputs
+    // are read back (the one mid-search synchronisation) before the descriptors are written.  With
+    // recomputed undo every elimination is value-only (no range condition) and overflow is judged on
+    // the device from measured ranges: nothing is read back, the host assumes full int32 ranges,
+    // writes the descriptors first and uploads them together with the offsets in one copy.
+    lwp_status run(int32_t* out_cost, int32_t* out_strategy);
+
+private:
+    lwp_status upload_offsets();
+    lwp_status measure_inputs();                 // w = t_c + t_s, ranges of w and of every input table
+    lwp_status read_input_ranges();              // stored undo only; synchronises
+    void assume_full_ranges();
+    lwp_status write_descriptors();              // range propagation, descriptors, launch list
+    lwp_status upload_descriptors();
+    lwp_status enqueue_eliminations();
+    lwp_status enqueue_residual_and_undo();
+    lwp_status fetch_result(int32_t* out_cost, int32_t* out_strategy);   // synchronises
+
+    const int32_t* table_ptr(const TableRef& r) const { return (r.is_slot ? d_slots_ : d_tx_) + r.off; }
+    int32_t* slot_ptr(const TableRef& r) const { return d_slots_ + r.off; }
+    const int32_t* w_ptr(int32_t v) const { return d_w_ + L_.node_off[v]; }
+
+    struct NodeLaunch {
+        size_t first, count; int32_t Ci, Cj, Ck; int variant;
+        int64_t tile_begin;      // index into the tile_begin block for mixed shapes, else -1
+        int32_t total_tiles, split_Cj; int64_t updates;   // split_Cj: the Cj that decides how tiles are split
+    };
+    struct RoundWork { size_t g0, g1; int64_t edge_cells, edge_max_cells; std::vector<NodeLaunch> launches; };
+
+    lwp_ctx* ctx_;
+    int32_t n_nodes_, n_edges_;
+    const int32_t* edges_;
+    const int32_t* Cn_;
+    const int32_t *d_tc_, *d_ts_, *d_tx_;
+    int32_t schedule_;
+    bool stored_;
+
+    Plan plan_;
+    Layout L_;
+    WsLayout W_{};
+    size_t head_in_bytes_ = 0, pin_head_ = 0, pin_desc_ = 0, pin_result_ = 0;
+    int32_t n_comp_ = 0, rng_w0_ = 0, rng_node0_ = 0, rng_group0_ = 0;
+    // device
+    char* ws_ = nullptr;
+    int32_t *d_w_ = nullptr, *d_head_ = nullptr, *d_stats_ = nullptr, *d_flag_ = nullptr, *d_args_ = nullptr,
+            *d_slots_ = nullptr, *d_result_ = nullptr;
+    unsigned long long* d_keys_ = nullptr;
+    char* db_ = nullptr;         // descriptor block on the device
+    // pinned host
+    char* hb_ = nullptr;         // mirror of the descriptor block
+    int32_t* h_stats_ = nullptr;
+    int32_t* h_result_ = nullptr;
+    // launches
+    std::vector<RoundWork> rounds_;
+    std::vector<unsigned long long> comp_prefix_;
+    int32_t pair_max_rows_ = 1, single_max_c_ = 1;
+};
+
+lwp_status Search::plan() {
+    {
+        std::string err;
+        lwp_status s = make_plan(n_nodes_, n_edges_, edges_, schedule_, plan_, err);
+        if (s != LWP_OK) return fail(ctx_, s, err);
+    }
+    if (!components_enumerable(plan_, Cn_))
+        return fail(ctx_, LWP_E_NOT_REDUCIBLE, "a residual component has more than 2^32 strategies to enumerate");
+    L_ = plan_buffers(plan_, n_nodes_, n_edges_, edges_, Cn_, !stored_);
+    W_ = layout_workspace(plan_, L_, n_nodes_, n_edges_, stored_);
+    head_in_bytes_ = (2 + 2 * (size_t)(n_edges_ + n_nodes_)) * sizeof(int32_t);
+    pin_head_ = 0;
+    pin_desc_ = align_up(head_in_bytes_, 256);
+    pin_result_ = pin_desc_ + align_up(W_.desc_bytes, 256);
+    n_comp_ = (int32_t)(plan_.pairs.size() + plan_.singles.size() + plan_.comps.size());
+    // index of the range pair of: input edge e | w of node v | output of node step | output of group
+    rng_w0_ = n_edges_;
+    rng_node0_ = n_edges_ + n_nodes_;
+    rng_group0_ = rng_node0_ + plan_.n_node_steps;
+    return LWP_OK;
+}
+
+void Search::bind(char* ws, char* pin) {
+    ws_ = ws;
+    d_w_ = reinterpret_cast<int32_t*>(ws + W_.w);
+    d_head_ = reinterpret_cast<int32_t*>(ws + W_.head);
+    d_flag_ = d_head_;           // set by any kernel that finds a sum outside int32
+    d_stats_ = d_head_ + 2;
+    d_args_ = reinterpret_cast<int32_t*>(ws + W_.args);
+    d_slots_ = reinterpret_cast<int32_t*>(ws + W_.slots);
+    d_keys_ = reinterpret_cast<unsigned long long*>(ws + W_.keys);
+    d_result_ = reinterpret_cast<int32_t*>(ws + W_.result);
+    db_ = ws + W_.desc;
+    hb_ = pin + pin_desc_;
+    h_stats_ = reinterpret_cast<int32_t*>(pin + pin_head_) + 2;
+    h_result_ = reinterpret_cast<int32_t*>(pin + pin_result_);
+    if (!L_.uniform) {           // rows and tables of different sizes: the kernels need their offsets
+        int64_t* h_offs = reinterpret_cast<int64_t*>(hb_ + W_.offs);
+        std::memcpy(h_offs, L_.node_off.data(), ((size_t)n_nodes_ + 1) * sizeof(int64_t));
+        std::memcpy(h_offs + n_nodes_ + 1, L_.tx_off.data(), ((size_t)n_edges_ + 1) * sizeof(int64_t));
+    }
+}
+
+lwp_status Search::run(int32_t* out_cost, int32_t* out_strategy) {
+    if (stored_) {
+        if (lwp_status s = upload_offsets()) return s;
+        if (lwp_status s = measure_inputs()) return s;
+        if (lwp_status s = read_input_ranges()) return s;
+        if (lwp_status s = write_descriptors()) return s;
+        if (lwp_status s = upload_descriptors()) return s;
+    } else {
+        assume_full_ranges();
+        if (lwp_status s = write_descriptors()) return s;
+        if (lwp_status s = upload_descriptors()) return s;      // the offsets travel with the block
+        if (lwp_status s = measure_inputs()) return s;
+    }
+    if (lwp_status s = enqueue_eliminations()) return s;
+    if (lwp_status s = enqueue_residual_and_undo()) return s;
+    return fetch_result(out_cost, out_strategy);
+}
+
+lwp_status Search::upload_offsets() {
+    if (L_.uniform) return LWP_OK;
+    LWP_HIP(ctx_, hipMemcpyAsync(db_ + W_.offs, hb_ + W_.offs, W_.offs_bytes, hipMemcpyHostToDevice, ctx_->stream));
+    return LWP_OK;
+}
+
+lwp_status Search::measure_inputs() {
+    hipStream_t st = ctx_->stream;
+    if (L_.uniform) {
+        LWP_HIP(ctx_, launch_prepare_search(d_tc_, d_ts_, d_w_, n_nodes_, Cn_[0], nullptr, d_stats_, W_.n_ranges, rng_w0_,
+                                            d_keys_, n_comp_, d_flag_, st));
+        LWP_HIP(ctx_, launch_ranges(d_tx_, n_edges_, (int64_t)Cn_[0] * Cn_[0], d_stats_, st));
+    } else {
+        const int64_t* d_offs = reinterpret_cast<const int64_t*>(db_ + W_.offs);
+        int64_t max_cells = 1;
+        for (int32_t e = 0; e < n_edges_; ++e) max_cells = std::max(max_cells, L_.tx_off[e + 1] - L_.tx_off[e]);
+        LWP_HIP(ctx_, launch_prepare_search(d_tc_, d_ts_, d_w_, n_nodes_, 0, d_offs, d_stats_, W_.n_ranges, rng_w0_,
+                                            d_keys_, n_comp_, d_flag_, st));
+        LWP_HIP(ctx_, launch_ranges_var(d_tx_, d_offs + n_nodes_ + 1, n_edges_, max_cells, d_stats_, st));
+    }
+    return LWP_OK;
+}
+
+lwp_status Search::read_input_ranges() {
+    LWP_HIP(ctx_, hipMemcpyAsync(h_stats_ - 2, d_head_, head_in_bytes_, hipMemcpyDeviceToHost, ctx_->stream));
+    LWP_HIP(ctx_, hipStreamSynchronize(ctx_->stream));
+    for (int32_t v = 0; v < n_nodes_; ++v)
+        if (h_stats_[2 * (rng_w0_ + v)] > h_stats_[2 * (rng_w0_ + v) + 1]) return fail(ctx_, LWP_E_OVERFLOW, "t_c + t_s leaves int32");
+    return LWP_OK;
+}
+
+void Search::assume_full_ranges() {
+    for (int32_t t = 0; t < n_edges_ + n_nodes_; ++t) { h_stats_[2 * t] = (int32_t)kI32Min; h_stats_[2 * t + 1] = (int32_t)kI32Max; }
+}
+
+// Propagates value ranges through the plan (every sum any kernel forms must fit int32) and writes
+// the descriptors straight into the pinned mirror of the device block.
+lwp_status Search::write_descriptors() {
+    const Plan& plan = plan_;
+    const Layout& L = L_;
+    const bool stored = stored_;
+    const int32_t* stats = h_stats_;
+    NodeDesc* nd = reinterpret_cast<NodeDesc*>(hb_ + W_.node_desc);
+    EdgeDesc* ed = reinterpret_cast<EdgeDesc*>(hb_ + W_.edge_desc);
+    const int32_t** src_ptrs = reinterpret_cast<const int32_t**>(hb_ + W_.src_ptrs);
+    PairDesc* pd = reinterpret_cast<PairDesc*>(hb_ + W_.pair_desc);
+    SingleDesc* sd = reinterpret_cast<SingleDesc*>(hb_ + W_.singles);
+    UndoDesc* ud = reinterpret_cast<UndoDesc*>(hb_ + W_.undo);
+    CompDesc* cd = reinterpret_cast<CompDesc*>(hb_ + W_.comps);
+    int32_t* tbeg = reinterpret_cast<int32_t*>(hb_ + W_.tile_begin);
+    size_t n_tbeg = 0;
+    rounds_.clear();
+
+    std::vector<Range> er(n_edges_), wr(n_nodes_);
+    std::vector<int32_t> erng(n_edges_);          // range-pair index of the edge's current table
+    for (int32_t e = 0; e < n_edges_; ++e) { er[e] = {stats[2 * e], stats[2 * e + 1]}; erng[e] = e; }
+    for (int32_t v = 0; v < n_nodes_; ++v) wr[v] = {stats[2 * (rng_w0_ + v)], stats[2 * (rng_w0_ + v) + 1]};
+    // Node eliminations of one round are independent; those of equal kernel variant share a
+    // launch if they agree in shape (Ci, Cj, Ck) or run on 64 x 64 tiles (a launch of mixed shapes),
+    // so the descriptors of a round are ordered by (variant, shape).
+    struct NodeWork { NodeDesc d; int64_t spread; int32_t Ci, Cj, Ck; int variant; };
+    // The propagated bounds are worst cases and grow along a chain although the minima do not.
+    // Where they cannot prove that a step stays inside int32 the step is not refused: it runs on a
+    // variant without range conditions and every kernel checks the tables' measured ranges (or
+    // the sums themselves) on the device; the flag they set is read back with the result.
+    auto sat = [](Range r) { return Range{std::max(r.lo, kI32Min), std::min(r.hi, kI32Max)}; };
+    size_t ni = 0, gi = 0, nsrc = 0, t = 0;
+    const size_t n = plan.steps.size();
+    std::vector<NodeWork> work;
+    std::vector<size_t> order;
+    while (t < n) {
+        const int32_t round = plan.steps[t].round;
+        RoundWork rw_{gi, gi, 0, 1, {}};
+        while (t < n && plan.steps[t].round == round && plan.steps[t].kind == 1) {
+            // one group = all steps adding into the same kept edge
+            const auto& g = L.groups[gi];
+            Range r = er[g.keep];
+            for (int32_t o : g.others) r = {r.lo + er[o].lo, r.hi + er[o].hi};
+            er[g.keep] = sat(r);
+            erng[g.keep] = rng_group0_ + (int32_t)gi;
+            ed[gi].out = slot_ptr(L.group_out[gi]);
+            ed[gi].rngOut = d_stats_ + 2 * (int64_t)erng[g.keep];
+            ed[gi].flag = d_flag_;
+            ed[gi].cells = L.group_out[gi].cells();
+            ed[gi].first_src = (int32_t)nsrc;
+            ed[gi].n_src = (int32_t)L.group_src[gi].size();
+            for (auto& r2 : L.group_src[gi]) src_ptrs[nsrc++] = table_ptr(r2);
+            rw_.edge_cells += ed[gi].cells;
+            rw_.edge_max_cells = std::max(rw_.edge_max_cells, ed[gi].cells);
+            t += g.others.size();
+            ++gi;
+        }
+        rw_.g1 = gi;
+        const size_t n0 = ni;
+        work.clear();
+        while (t < n && plan.steps[t].round == round && plan.steps[t].kind == 0) {
+            const lwp_step& s = plan.steps[t];
+            const Range rA = er[s.e1], rw = wr[s.j], rB = er[s.e2];
+            const bool proven = fits(rA.lo + rw.lo) && fits(rA.hi + rw.hi) && fits(rA.lo + rw.lo + rB.lo) && fits(rA.hi + rw.hi + rB.hi);
+            const TableRef &tA = L.node_A[ni], &tB = L.node_B[ni], &tO = L.node_out[ni];
+            NodeWork nw{};
+            NodeDesc& d = nw.d;
+            d.flag = d_flag_;
+            d.A = table_ptr(tA); d.w = w_ptr(s.j); d.B = table_ptr(tB);
+            d.out = slot_ptr(tO);
+            d.arg = stored ? d_args_ + L.node_arg_off[ni] : nullptr;
+            d.loA = (int32_t)rA.lo; d.hiA = (int32_t)rA.hi; d.loW = (int32_t)rw.lo; d.hiW = (int32_t)rw.hi;
+            d.loB = (int32_t)rB.lo; d.hiB = (int32_t)rB.hi;
+            d.rngA = d_stats_ + 2 * (int64_t)erng[s.e1];
+            d.rngB = d_stats_ + 2 * (int64_t)erng[s.e2];
+            d.rngW = d_stats_ + 2 * (int64_t)(rng_w0_ + s.j);
+            d.rngOut = d_stats_ + 2 * (int64_t)(rng_node0_ + (int32_t)ni);
+            nw.spread = proven ? keyed_spread(rA, rw, rB) : (int64_t)1 << 62;   // unproven: no packed keys
+            nw.Ci = tA.rows; nw.Cj = tA.cols; nw.Ck = tB.cols;
+            d.Ci = nw.Ci; d.Cj = nw.Cj; d.Ck = nw.Ck;
+            work.push_back(nw);
+            ud[ni] = {d.arg, d.A, d.w, d.B, s.j, s.i, s.k, s.round, nw.Cj, nw.Ck, (int32_t)n0, 0};
+            // any fixed c bounds the minimum from above; take the c with the smallest w
+            er[s.e1] = sat({rA.lo + rw.lo + rB.lo, rA.hi + rw.lo + rB.hi});
+            erng[s.e1] = rng_node0_ + (int32_t)ni;
+            ++ni; ++t;
+        }
+        // kernel variant per product: packed keys on the preferred tile size if the spread
+        // allows, else packed keys on 128 x 128 tiles (one more bit), else the plain variant;
+        // 0 keyed small, 1 keyed large, 2 plain small, 3 plain large, 4 value small, 5 value large
+        auto shape_of = [](const NodeWork& a) { return std::make_tuple(a.Ci, a.Cj, a.Ck); };
+        std::map<std::tuple<int32_t, int32_t, int32_t>, int64_t> shape_count;
+        for (const NodeWork& x : work) ++shape_count[shape_of(x)];
+        for (NodeWork& x : work) {
+            const int64_t same = shape_count[shape_of(x)];
+            const bool prefer_small = want_small_tiles(x.Ci, x.Cj, x.Ck, same);
+            const bool large_fills_chip = large_tiles(x.Ci, x.Ck, same) >= 512;
+            if (!stored) x.variant = prefer_small ? 4 : 5;     // value-only: no range condition
+            else if (x.spread <= (prefer_small ? kKeyedMaxSpreadSmall : kKeyedMaxSpreadLarge)) x.variant = prefer_small ? 0 : 1;
+            else if (x.spread <= kKeyedMaxSpreadLarge && large_fills_chip) x.variant = 1;
+            else x.variant = prefer_small ? 2 : 3;
+        }
+        order.resize(work.size());
+        for (size_t q = 0; q < order.size(); ++q) order[q] = q;
+        std::stable_sort(order.begin(), order.end(), [&](size_t a, size_t b) {
+            return std::make_pair(work[a].variant, shape_of(work[a])) < std::make_pair(work[b].variant, shape_of(work[b]));
+        });
+        for (size_t a = 0; a < order.size();) {
+            const int v = work[order[a]].variant;
+            size_t b = a;
+            while (b < order.size() && work[order[b]].variant == v) ++b;
+            const bool small = (v == 0 || v == 2 || v == 4);
+            const bool one_shape = shape_of(work[order[a]]) == shape_of(work[order[b - 1]]);
+            if (small && !one_shape) {
+                // one launch over all shapes: product q owns tiles [tile_begin[q], tile_begin[q+1])
+                NodeLaunch nl{n0 + a, b - a, 0, 0, 0, v, (int64_t)n_tbeg, 0, 0, 0};
+                int64_t tiles = 0;
+                for (size_t q = a; q < b; ++q) {
+                    NodeWork& x = work[order[q]];
+                    tbeg[n_tbeg++] = (int32_t)tiles;
+                    tiles += (int64_t)((x.Ci + kTileSmall - 1) / kTileSmall) * ((x.Ck + kTileSmall - 1) / kTileSmall);
+                    nl.split_Cj = std::max(nl.split_Cj, x.Cj);
+                    nl.updates += (int64_t)x.Ci * x.Cj * x.Ck;
+                }
+                tbeg[n_tbeg++] = (int32_t)tiles;
+                if (tiles > INT32_MAX) return fail(ctx_, LWP_E_INVAL, "too many tiles in one round");
+                nl.total_tiles = (int32_t)tiles;
+                rw_.launches.push_back(nl);
+            } else {
+                for (size_t q = a; q < b;) {
+                    size_t e = q;
+                    while (e < b && shape_of(work[order[e]]) == shape_of(work[order[q]])) ++e;
+                    const NodeWork& x = work[order[q]];
+                    rw_.launches.push_back({n0 + q, e - q, x.Ci, x.Cj, x.Ck, v, -1, 0, x.Cj,
+                                            (int64_t)(e - q) * x.Ci * x.Cj * x.Ck});
+                    q = e;
+                }
+            }
+            a = b;
+        }
+        for (size_t q = 0; q < order.size(); ++q) nd[n0 + q] = work[order[q]].d;
+        rounds_.push_back(std::move(rw_));
+    }
+
+    pair_max_rows_ = 1; single_max_c_ = 1;
+    for (size_t q = 0; q < plan.pairs.size(); ++q) {
+        const auto& pr = plan.pairs[q];
+        pd[q] = {table_ptr(L.final_table[q]), w_ptr(pr.src), w_ptr(pr.dst), pr.src, pr.dst, Cn_[pr.src], Cn_[pr.dst]};
+        pair_max_rows_ = std::max(pair_max_rows_, Cn_[pr.src]);
+    }
+    for (size_t q = 0; q < plan.singles.size(); ++q) {
+        const int32_t v = plan.singles[q];
+        sd[q] = {w_ptr(v), v, Cn_[v]};
+        single_max_c_ = std::max(single_max_c_, Cn_[v]);
+    }
+    comp_prefix_.assign(plan.comps.size(), 1);
+    for (size_t q = 0; q < plan.comps.size(); ++q) {
+        const auto& c = plan.comps[q];
+        CompDesc d{};
+        d.K = (int32_t)c.nodes.size(); d.n_edges = (int32_t)c.edges.size();
+        unsigned long long prefix = 1;
+        for (int x = 0; x < d.K; ++x) {
+            d.node[x] = c.nodes[x]; d.Cn[x] = Cn_[c.nodes[x]]; d.w[x] = w_ptr(c.nodes[x]);
+            if (x + 1 < d.K) prefix *= (unsigned long long)d.Cn[x];
+        }
+        comp_prefix_[q] = prefix;
+        for (int x = 0; x < d.n_edges; ++x) {
+            d.tab[x] = table_ptr(L.comp_tables[q][x]);
+            d.src_pos[x] = (int8_t)(std::find(c.nodes.begin(), c.nodes.end(), c.esrc[x]) - c.nodes.begin());
+            d.dst_pos[x] = (int8_t)(std::find(c.nodes.begin(), c.nodes.end(), c.edst[x]) - c.nodes.begin());
+        }
+        cd[q] = d;
+    }
+    return LWP_OK;
+}
+
+lwp_status Search::upload_descriptors() {
+    LWP_HIP(ctx_, hipMemcpyAsync(db_, hb_, W_.desc_bytes, hipMemcpyHostToDevice, ctx_->stream));
+    return LWP_OK;
+}
+
+lwp_status Search::enqueue_eliminations() {
+    hipStream_t st = ctx_->stream;
+    const NodeDesc* d_nd = reinterpret_cast<const NodeDesc*>(db_ + W_.node_desc);
+    const EdgeDesc* d_ed = reinterpret_cast<const EdgeDesc*>(db_ + W_.edge_desc);
+    const int32_t* const* d_src = reinterpret_cast<const int32_t* const*>(db_ + W_.src_ptrs);
+    const int32_t* d_tbeg = reinterpret_cast<const int32_t*>(db_ + W_.tile_begin);
+    for (const RoundWork& r : rounds_) {
+        if (r.g1 > r.g0) {
+            ScopedTimer tm(ctx_, 1, r.edge_cells, false);
+            LWP_HIP(ctx_, launch_edge_sum_desc(d_ed + r.g0, d_src, (int32_t)(r.g1 - r.g0), r.edge_max_cells, st));
+        }
+        for (const NodeLaunch& nl : r.launches) {
+            const int v = nl.variant;
+            const bool keyed = v < 2, small = (v == 0 || v == 2 || v == 4);
+            const int mode = v >= 4 ? kModeValue : (keyed ? kModeKeyed : kModePlain);
+            const int tile = small ? kTileSmall : kTileLarge;
+            NodeArgs na{};
+            na.descs = d_nd + nl.first;
+            na.Ci = nl.Ci; na.Cj = nl.Cj; na.Ck = nl.Ck; na.batch = (int32_t)nl.count;
+            na.tilesM = (nl.Ci + tile - 1) / tile;
+            na.tilesN = (nl.Ck + tile - 1) / tile;
+            const bool mixed = nl.tile_begin >= 0;
+            if (mixed) { na.tile_begin = d_tbeg + nl.tile_begin; na.total_tiles = nl.total_tiles; }
+            ScopedTimer tm(ctx_, 0, nl.updates, keyed);
+            // a launch of mixed shapes splits by its longest product: every product divides its own
+            // stages among the parts, and parts beyond a short product's stages see only padding
+            const int kparts = choose_kparts(mixed ? nl.total_tiles : (int64_t)na.tilesM * na.tilesN * na.batch, nl.split_Cj, small);
+            if (kparts > 1) { if (lwp_status s2 = ensure_split_buffers(ctx_)) return s2; }
+            set_split(ctx_, na, kparts);
+            LWP_HIP(ctx_, launch_minplus(na, mode, small, st));
+        }
+    }
+    return LWP_OK;
+}
+
+lwp_status Search::enqueue_residual_and_undo() {
+    hipStream_t st = ctx_->stream;
+    const PairDesc* d_pd = reinterpret_cast<const PairDesc*>(db_ + W_.pair_desc);
+    const SingleDesc* d_sd = reinterpret_cast<const SingleDesc*>(db_ + W_.singles);
+    const UndoDesc* d_ud = reinterpret_cast<const UndoDesc*>(db_ + W_.undo);
+    const CompDesc* d_cd = reinterpret_cast<const CompDesc*>(db_ + W_.comps);
+    const size_t np = plan_.pairs.size(), ns = plan_.singles.size(), nc = plan_.comps.size();
+    LWP_HIP(ctx_, launch_pair_min(d_pd, (int32_t)np, pair_max_rows_, d_keys_, d_flag_, st));
+    LWP_HIP(ctx_, launch_single_min(d_sd, (int32_t)ns, single_max_c_, d_keys_ + np, st));
+    for (size_t q = 0; q < nc; ++q)
+        LWP_HIP(ctx_, launch_component_min(d_cd + q, comp_prefix_[q], d_keys_ + np + ns + q, d_flag_, st));
+    LWP_HIP(ctx_, launch_back_substitute(d_pd, (int32_t)np, d_sd, (int32_t)ns, d_cd, (int32_t)nc, d_keys_, d_ud,
+                                         plan_.n_node_steps, n_nodes_, d_flag_, d_stats_ + 2 * (int64_t)rng_w0_, d_result_, st));
+    return LWP_OK;
+}
+
+lwp_status Search::fetch_result(int32_t* out_cost, int32_t* out_strategy) {
+    LWP_HIP(ctx_, hipMemcpyAsync(h_result_, d_result_, (3 + (size_t)n_nodes_) * sizeof(int32_t), hipMemcpyDeviceToHost, ctx_->stream));
+    LWP_HIP(ctx_, hipStreamSynchronize(ctx_->stream));
+    if (h_result_[2 + n_nodes_]) return fail(ctx_, LWP_E_OVERFLOW, "a sum may leave int32 (found on the device from the tables' actual ranges)");
+    // the total is formed in 64 bits on the device
+    const int64_t total = (int64_t)(((uint64_t)(uint32_t)h_result_[1] << 32) | (uint32_t)h_result_[0]);
+    if (!fits(total)) return fail(ctx_, LWP_E_OVERFLOW, "the total cost leaves int32");
+    *out_cost = (int32_t)total;
+    std::memcpy(out_strategy, h_result_ + 2, (size_t)n_nodes_ * sizeof(int32_t));
+    return LWP_OK;
+}
+
+}  // namespace
+
+// ================================================================================================
+extern "C" {
+
+lwp_status lwp_plan_graph(int32_t n_nodes, int32_t n_edges, const int32_t* edges, int32_t schedule,
+                          lwp_step* steps, int32_t* n_steps, int32_t* n_rounds, int32_t* n_residual_nodes) {
+    Plan plan;
+    std::string err;
+    lwp_status s = make_plan(n_nodes, n_edges, edges, schedule, plan, err);
+    if (n_steps) *n_steps = (int32_t)plan.steps.size();
+    if (n_rounds) *n_rounds = plan.n_rounds;
+    if (s != LWP_OK) return s;
+    if (steps && !plan.steps.empty()) std::memcpy(steps, plan.steps.data(), plan.steps.size() * sizeof(lwp_step));
+    if (n_residual_nodes) {
+        size_t k = 2 * plan.pairs.size() + plan.singles.size();
+        for (auto& c : plan.comps) k += c.nodes.size();
+        *n_residual_nodes = (int32_t)k;
+    }
+    return LWP_OK;
+}
+
+size_t lwp_search_workspace_bytes(int32_t n_nodes, int32_t n_edges, const int32_t* edges, int32_t C,
+                                  int32_t schedule) {
+    return lwp_search_workspace_bytes_ex(n_nodes, n_edges, edges, C, schedule, LWP_UNDO_STORED);
+}
+
+size_t lwp_search_workspace_bytes_ex(int32_t n_nodes, int32_t n_edges, const int32_t* edges, int32_t C,
+                                     int32_t schedule, int32_t undo) {
+    if (n_nodes < 1) return 0;
+    const std::vector<int32_t> Cn((size_t)n_nodes, C);
+    return lwp_search_workspace_bytes_ragged(n_nodes, n_edges, edges, Cn.data(), schedule, undo);
+}
+
+size_t lwp_search_workspace_bytes_ragged(int32_t n_nodes, int32_t n_edges, const int32_t* edges,
+                                         const int32_t* C_node, int32_t schedule, int32_t undo) {
+    if (n_nodes < 1 || !counts_valid(n_nodes, C_node) || (undo != LWP_UNDO_STORED && undo != LWP_UNDO_RECOMPUTE)) return 0;
+    Search search(nullptr, n_nodes, n_edges, edges, C_node, nullptr, nullptr, nullptr, schedule, undo == LWP_UNDO_STORED);
+    return search.plan() == LWP_OK ? search.workspace_bytes() : 0;
+}
+
+lwp_status lwp_search_graph(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, const int32_t* edges,
+                            int32_t C, const int32_t* d_tc, const int32_t* d_ts, const int32_t* d_tx,
+                            int32_t schedule, int32_t* out_cost, int32_t* out_strategy) {
+    return lwp_search_graph_ex(ctx, n_nodes, n_edges, edges, C, d_tc, d_ts, d_tx, schedule, LWP_UNDO_STORED, out_cost,
+                               out_strategy);
+}
+
+lwp_status lwp_search_graph_ex(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, const int32_t* edges,
+                               int32_t C, const int32_t* d_tc, const int32_t* d_ts, const int32_t* d_tx,
+                               int32_t schedule, int32_t undo, int32_t* out_cost, int32_t* out_strategy) {
+    if (lwp_status s = check_ctx(ctx)) return s;
+    if (C < 1 || C > kMaxConfigs) return fail(ctx, LWP_E_INVAL, "C must be in [1, 65536]");
+    if (n_nodes < 1) return fail(ctx, LWP_E_GRAPH, "n_nodes must be >= 1");
+    const std::vector<int32_t> Cn((size_t)n_nodes, C);
+    return lwp_search_graph_ragged(ctx, n_nodes, n_edges, edges, Cn.data(), d_tc, d_ts, d_tx, schedule, undo, out_cost,
+                                   out_strategy);
+}
+
+lwp_status lwp_search_graph_ragged(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, const int32_t* edges,
+                                   const int32_t* Cn, const int32_t* d_tc, const int32_t* d_ts,
+                                   const int32_t* d_tx, int32_t schedule, int32_t undo, int32_t* out_cost,
+                                   int32_t* out_strategy) {
+    if (lwp_status s = check_ctx(ctx)) return s;
+    if (undo != LWP_UNDO_STORED && undo != LWP_UNDO_RECOMPUTE) return fail(ctx, LWP_E_INVAL, "unknown undo mode");
+    if (n_nodes < 1) return fail(ctx, LWP_E_GRAPH, "n_nodes must be >= 1");
+    if (!counts_valid(n_nodes, Cn)) return fail(ctx, LWP_E_INVAL, "every configuration count must be in [1, 65536]");
+    if (!d_tc || !d_ts || (n_edges > 0 && !d_tx) || !out_cost || !out_strategy)
+        return fail(ctx, LWP_E_INVAL, "null pointer");
+    if (((uintptr_t)d_tc | (uintptr_t)d_ts | (uintptr_t)d_tx) & 3)
+        return fail(ctx, LWP_E_INVAL, "table pointer not 4-byte aligned");
+    Search search(ctx, n_nodes, n_edges, edges, Cn, d_tc, d_ts, d_tx, schedule, undo == LWP_UNDO_STORED);
+    if (lwp_status s = search.plan()) return s;
+    if (lwp_status s = ensure_workspace(ctx, search.workspace_bytes())) return s;
+    if (lwp_status s = ensure_pinned(ctx, search.pinned_bytes())) return s;
+    search.bind(ctx->ws, ctx->pin);
+    return search.run(out_cost, out_strategy);
+}
+
+}  // extern "C"
