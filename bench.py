@@ -97,6 +97,9 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-events", action="store_true",
                     help="diagnostic: do not bracket the elimination launches with HIP events (no roofline figures)")
+    ap.add_argument("--replay", action="store_true",
+                    help="prepare the search once (schedule, buffers, descriptors; recomputed undo) and time runs of "
+                         "the prepared plan")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference dispatch for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
@@ -151,6 +154,7 @@ def main():
         def step():
             result["cost"], result["S"] = ctx.search_graph_ragged(p["n_nodes"], p["edges"], Cn, dtc, dts, dtx, p["schedule"],
                                                                   1 if args.undo == "recompute" else 0)
+        plan_args = (p["n_nodes"], p["edges"], Cn, dtc.reshape(-1), dts.reshape(-1), dtx.reshape(-1), p["schedule"])
         q = {"n_nodes": p["n_nodes"], "edges": p["edges"], "Cn": Cn, "tc": dtc.cpu().numpy(), "ts": dts.cpu().numpy(),
              "tx": dtx.cpu().numpy(), "schedule": p["schedule"], "updates": updates}
         cpu_payload = ("search_ragged", q)
@@ -192,6 +196,7 @@ def main():
         def step():
             result["cost"], result["S"] = ctx.search_graph(p["n_nodes"], p["edges"], C, dtc, dts, dtx, p["schedule"],
                                                            1 if args.undo == "recompute" else 0)
+        plan_args = (p["n_nodes"], p["edges"], C, dtc, dts, dtx, p["schedule"])
         if name == "cfg4":
             cpu_payload = ("fold", p)
         elif name == "resid":
@@ -202,6 +207,15 @@ def main():
         else:
             p["updates"] = updates
             cpu_payload = ("search", p)
+    if args.replay:
+        if name == "cfg3":
+            log("bench.py: --replay applies to the search workloads")
+            sys.exit(2)
+        plan = ctx.search_plan(*plan_args)
+        workload += ", host-side work done once (argmin recomputed in the undo pass)"
+
+        def step():  # noqa: F811
+            result["cost"], result["S"] = plan.run()
     log(f"[bench] inputs ready in {time.perf_counter() - t_gen:.1f} s: {workload}")
 
     if args.calibrate_copy:
@@ -246,6 +260,8 @@ def main():
         log("[bench] timing the CPU oracle on a bounded sample ...")
         line["cpu_baseline"] = cpu_baseline(*cpu_payload)
     print(json.dumps(line), flush=True)
+    if args.replay:
+        plan.close()
     ctx.close()
 
 

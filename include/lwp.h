@@ -151,6 +151,23 @@ lwp_status lwp_search_graph_ragged(lwp_ctx *ctx, int32_t n_nodes, int32_t n_edge
                                    const int32_t *d_tx, int32_t schedule, int32_t undo,
                                    int32_t *out_cost, int32_t *out_strategy);
 
+/* A search prepared once and run many times on tables that change in place (the cost tables are
+ * re-measured or rebuilt for another batch size or machine while the graph stays; Sec. 5.1, 5.2).
+ * lwp_search_plan_create fixes graph, configuration counts (as lwp_search_graph_ragged), table
+ * ADDRESSES and schedule, allocates the plan's own workspace and does all host-side work --
+ * schedule, buffer plan, descriptors, their upload -- once.  That is possible with recomputed
+ * undo (LWP_UNDO_RECOMPUTE): value-only eliminations and device-side overflow checks leave
+ * nothing for the host to decide from the tables' values.  lwp_search_plan_run enqueues the
+ * launch sequence on the context's stream, waits for it and returns what lwp_search_graph_ragged
+ * would return for the tables' present contents.  Blocking.  A plan belongs to its context:
+ * destroy it before the context. */
+typedef struct lwp_search_plan lwp_search_plan;
+lwp_status lwp_search_plan_create(lwp_ctx *ctx, int32_t n_nodes, int32_t n_edges, const int32_t *edges,
+                                  const int32_t *C_node, const int32_t *d_tc, const int32_t *d_ts,
+                                  const int32_t *d_tx, int32_t schedule, lwp_search_plan **out);
+lwp_status lwp_search_plan_run(lwp_search_plan *plan, int32_t *out_cost, int32_t *out_strategy);
+void lwp_search_plan_destroy(lwp_search_plan *plan);
+
 /* Host-only: bytes of device workspace lwp_search_graph(_ex) needs for this graph (0 on a graph it
  * would refuse). */
 size_t lwp_search_workspace_bytes(int32_t n_nodes, int32_t n_edges, const int32_t *edges, int32_t C,

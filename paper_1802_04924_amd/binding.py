@@ -25,6 +25,7 @@ EXPORTED = [
     "lwp_search_workspace_bytes", "lwp_search_graph_ex", "lwp_search_workspace_bytes_ex",
     "lwp_search_graph_ragged", "lwp_search_workspace_bytes_ragged", "lwp_build_cost_tables",
     "lwp_build_cost_tables_ragged", "lwp_enumerate_configs",
+    "lwp_search_plan_create", "lwp_search_plan_run", "lwp_search_plan_destroy",
     "lwp_profile_enable", "lwp_profile_reset", "lwp_profile_read",
 ]
 
@@ -85,6 +86,10 @@ def load():
     lib.lwp_build_cost_tables.argtypes = [vp, vp, i32, vp, i32, vp, i32, vp, vp, vp, vp]
     lib.lwp_build_cost_tables_ragged.argtypes = [vp, vp, i32, vp, i32, vp, vp, vp, vp, vp, vp]
     lib.lwp_enumerate_configs.argtypes = [vp, i32, vp, i32, i32p]
+    lib.lwp_search_plan_create.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, i32, ctypes.POINTER(vp)]
+    lib.lwp_search_plan_run.argtypes = [vp, i32p, vp]
+    lib.lwp_search_plan_destroy.argtypes = [vp]
+    lib.lwp_search_plan_destroy.restype = None
     lib.lwp_profile_enable.argtypes = [vp, i32]
     lib.lwp_profile_reset.argtypes = [vp]
     lib.lwp_profile_read.argtypes = [vp, ctypes.POINTER(Profile)]
@@ -148,6 +153,51 @@ def _dev(t, what):
     if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.int32 and t.is_contiguous()):
         raise TypeError(f"{what} must be a contiguous int32 CUDA tensor")
     return t.data_ptr()
+
+
+class SearchPlan:
+    """Owns one lwp_search_plan (see Context.search_plan).  Close it before its context."""
+
+    def __init__(self, ctx, n_nodes, edges, C_node, tc, ts, tx, schedule):
+        edges = _np_i32(edges, (-1, 2))
+        C_node = np.full(n_nodes, int(C_node), np.int32) if np.ndim(C_node) == 0 else _np_i32(C_node, (-1,))
+        if len(C_node) != n_nodes:
+            raise ValueError("C_node must have one entry per node")
+        E = len(edges)
+        n_w = int(C_node.astype(np.int64).sum())
+        if tc.numel() != n_w or ts.numel() != n_w:
+            raise ValueError("t_c / t_s must hold sum(C_node) entries")
+        if E and (edges >= 0).all() and (edges < n_nodes).all():
+            if tx.numel() != int((C_node[edges[:, 0]].astype(np.int64) * C_node[edges[:, 1]]).sum()):
+                raise ValueError("t_x must hold sum(C_src * C_dst) entries")
+        self._ctx, self._lib, self.n_nodes = ctx, ctx._lib, n_nodes
+        self._tables = (tc, ts, tx)
+        h = ctypes.c_void_p()
+        rc = self._lib.lwp_search_plan_create(ctx._h, n_nodes, E, edges.ctypes.data, C_node.ctypes.data, _dev(tc, "tc"),
+                                              _dev(ts, "ts"), _dev(tx, "tx") if E else None, int(schedule), ctypes.byref(h))
+        ctx._check(rc, "search_plan_create")
+        self._h = h
+
+    def run(self):
+        """Returns (cost, strategy[n_nodes]) for what the tables hold now."""
+        cost = ctypes.c_int32(0)
+        S = np.empty(self.n_nodes, np.int32)
+        rc = self._lib.lwp_search_plan_run(self._h, ctypes.byref(cost), S.ctypes.data)
+        self._ctx._check(rc, "search_plan_run")
+        return cost.value, S
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self._lib.lwp_search_plan_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
 
 
 class Context:
@@ -257,6 +307,13 @@ class Context:
                                                int(schedule), int(undo), ctypes.byref(cost), S.ctypes.data)
         self._check(rc, "search_graph_ragged")
         return cost.value, S
+
+    def search_plan(self, n_nodes, edges, C_node, tc, ts, tx, schedule=SCHEDULE_ROUNDS):
+        """A search prepared once and run many times: SearchPlan.run() searches the tables' present contents.
+
+        C_node: one count for all nodes or one per node; tc, ts, tx as search_graph / search_graph_ragged
+        take them.  The plan keeps the three tensors alive; change their contents in place between runs."""
+        return SearchPlan(self, n_nodes, edges, C_node, tc, ts, tx, schedule)
 
     # ---- Sec. 5.1 ----------------------------------------------------------
     def build_cost_tables(self, layers, edges, configs, machine):

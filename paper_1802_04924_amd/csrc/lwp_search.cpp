@@ -2,6 +2,7 @@
 // sequence of a whole search (eliminate -> solve the residual graph -> undo).
 #include <cstring>
 #include <map>
+#include <new>
 #include <tuple>
 
 #include "lwp_context.h"
@@ -184,7 +185,7 @@ public:
     Search(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, const int32_t* edges, const int32_t* Cn,
            const int32_t* d_tc, const int32_t* d_ts, const int32_t* d_tx, int32_t schedule, bool stored)
         : ctx_(ctx), n_nodes_(n_nodes), n_edges_(n_edges), edges_(edges), Cn_(Cn), d_tc_(d_tc), d_ts_(d_ts),
-          d_tx_(d_tx), schedule_(schedule), stored_(stored) {}
+          d_tx_(d_tx), schedule_(schedule), stored_(stored), stream_(ctx ? ctx->stream : nullptr) {}
 
     // Validates the graph, fixes the schedule and lays out the buffers (host only).
     lwp_status plan();
@@ -199,6 +200,12 @@ public:
     // writes the descriptors first and uploads them together with the offsets in one copy.
     lwp_status run(int32_t* out_cost, int32_t* out_strategy);
 
+    // The pieces of run() for a caller that prepares once and runs many times (recomputed undo
+    // only: nothing the host decides then depends on the tables' values).
+    lwp_status prepare_replay();                 // descriptors for any int32 input, uploaded; synchronises
+    lwp_status enqueue_all();                    // everything between the tables and the result copy
+    lwp_status finish(int32_t* out_cost, int32_t* out_strategy) const;   // after the stream has drained
+
 private:
     lwp_status upload_offsets();
     lwp_status measure_inputs();                 // w = t_c + t_s, ranges of w and of every input table
@@ -208,7 +215,7 @@ private:
     lwp_status upload_descriptors();
     lwp_status enqueue_eliminations();
     lwp_status enqueue_residual_and_undo();
-    lwp_status fetch_result(int32_t* out_cost, int32_t* out_strategy);   // synchronises
+    lwp_status enqueue_result_copy();
 
     const int32_t* table_ptr(const TableRef& r) const { return (r.is_slot ? d_slots_ : d_tx_) + r.off; }
     int32_t* slot_ptr(const TableRef& r) const { return d_slots_ + r.off; }
@@ -228,6 +235,7 @@ private:
     const int32_t *d_tc_, *d_ts_, *d_tx_;
     int32_t schedule_;
     bool stored_;
+    hipStream_t stream_;
 
     Plan plan_;
     Layout L_;
@@ -308,17 +316,35 @@ lwp_status Search::run(int32_t* out_cost, int32_t* out_strategy) {
     }
     if (lwp_status s = enqueue_eliminations()) return s;
     if (lwp_status s = enqueue_residual_and_undo()) return s;
-    return fetch_result(out_cost, out_strategy);
+    if (lwp_status s = enqueue_result_copy()) return s;
+    LWP_HIP(ctx_, hipStreamSynchronize(stream_));
+    return finish(out_cost, out_strategy);
+}
+
+lwp_status Search::prepare_replay() {
+    if (stored_) return fail(ctx_, LWP_E_INVAL, "a replayed search recomputes the argmin in the undo pass");
+    assume_full_ranges();
+    if (lwp_status s = write_descriptors()) return s;
+    if (lwp_status s = upload_descriptors()) return s;
+    LWP_HIP(ctx_, hipStreamSynchronize(stream_));
+    return LWP_OK;
+}
+
+lwp_status Search::enqueue_all() {
+    if (lwp_status s = measure_inputs()) return s;
+    if (lwp_status s = enqueue_eliminations()) return s;
+    if (lwp_status s = enqueue_residual_and_undo()) return s;
+    return enqueue_result_copy();
 }
 
 lwp_status Search::upload_offsets() {
     if (L_.uniform) return LWP_OK;
-    LWP_HIP(ctx_, hipMemcpyAsync(db_ + W_.offs, hb_ + W_.offs, W_.offs_bytes, hipMemcpyHostToDevice, ctx_->stream));
+    LWP_HIP(ctx_, hipMemcpyAsync(db_ + W_.offs, hb_ + W_.offs, W_.offs_bytes, hipMemcpyHostToDevice, stream_));
     return LWP_OK;
 }
 
 lwp_status Search::measure_inputs() {
-    hipStream_t st = ctx_->stream;
+    hipStream_t st = stream_;
     if (L_.uniform) {
         LWP_HIP(ctx_, launch_prepare_search(d_tc_, d_ts_, d_w_, n_nodes_, Cn_[0], nullptr, d_stats_, W_.n_ranges, rng_w0_,
                                             d_keys_, n_comp_, d_flag_, st));
@@ -335,8 +361,8 @@ lwp_status Search::measure_inputs() {
 }
 
 lwp_status Search::read_input_ranges() {
-    LWP_HIP(ctx_, hipMemcpyAsync(h_stats_ - 2, d_head_, head_in_bytes_, hipMemcpyDeviceToHost, ctx_->stream));
-    LWP_HIP(ctx_, hipStreamSynchronize(ctx_->stream));
+    LWP_HIP(ctx_, hipMemcpyAsync(h_stats_ - 2, d_head_, head_in_bytes_, hipMemcpyDeviceToHost, stream_));
+    LWP_HIP(ctx_, hipStreamSynchronize(stream_));
     for (int32_t v = 0; v < n_nodes_; ++v)
         if (h_stats_[2 * (rng_w0_ + v)] > h_stats_[2 * (rng_w0_ + v) + 1]) return fail(ctx_, LWP_E_OVERFLOW, "t_c + t_s leaves int32");
     return LWP_OK;
@@ -523,12 +549,12 @@ lwp_status Search::write_descriptors() {
 }
 
 lwp_status Search::upload_descriptors() {
-    LWP_HIP(ctx_, hipMemcpyAsync(db_, hb_, W_.desc_bytes, hipMemcpyHostToDevice, ctx_->stream));
+    LWP_HIP(ctx_, hipMemcpyAsync(db_, hb_, W_.desc_bytes, hipMemcpyHostToDevice, stream_));
     return LWP_OK;
 }
 
 lwp_status Search::enqueue_eliminations() {
-    hipStream_t st = ctx_->stream;
+    hipStream_t st = stream_;
     const NodeDesc* d_nd = reinterpret_cast<const NodeDesc*>(db_ + W_.node_desc);
     const EdgeDesc* d_ed = reinterpret_cast<const EdgeDesc*>(db_ + W_.edge_desc);
     const int32_t* const* d_src = reinterpret_cast<const int32_t* const*>(db_ + W_.src_ptrs);
@@ -563,7 +589,7 @@ lwp_status Search::enqueue_eliminations() {
 }
 
 lwp_status Search::enqueue_residual_and_undo() {
-    hipStream_t st = ctx_->stream;
+    hipStream_t st = stream_;
     const PairDesc* d_pd = reinterpret_cast<const PairDesc*>(db_ + W_.pair_desc);
     const SingleDesc* d_sd = reinterpret_cast<const SingleDesc*>(db_ + W_.singles);
     const UndoDesc* d_ud = reinterpret_cast<const UndoDesc*>(db_ + W_.undo);
@@ -578,9 +604,12 @@ lwp_status Search::enqueue_residual_and_undo() {
     return LWP_OK;
 }
 
-lwp_status Search::fetch_result(int32_t* out_cost, int32_t* out_strategy) {
-    LWP_HIP(ctx_, hipMemcpyAsync(h_result_, d_result_, (3 + (size_t)n_nodes_) * sizeof(int32_t), hipMemcpyDeviceToHost, ctx_->stream));
-    LWP_HIP(ctx_, hipStreamSynchronize(ctx_->stream));
+lwp_status Search::enqueue_result_copy() {
+    LWP_HIP(ctx_, hipMemcpyAsync(h_result_, d_result_, (3 + (size_t)n_nodes_) * sizeof(int32_t), hipMemcpyDeviceToHost, stream_));
+    return LWP_OK;
+}
+
+lwp_status Search::finish(int32_t* out_cost, int32_t* out_strategy) const {
     if (h_result_[2 + n_nodes_]) return fail(ctx_, LWP_E_OVERFLOW, "a sum may leave int32 (found on the device from the tables' actual ranges)");
     // the total is formed in 64 bits on the device
     const int64_t total = (int64_t)(((uint64_t)(uint32_t)h_result_[1] << 32) | (uint32_t)h_result_[0]);
@@ -592,8 +621,74 @@ lwp_status Search::fetch_result(int32_t* out_cost, int32_t* out_strategy) {
 
 }  // namespace
 
+// A search whose host-side work (schedule, buffers, descriptors) was done once.  It owns its
+// workspace and pinned buffers; a run only re-enqueues the launch sequence.
+struct lwp_search_plan {
+    lwp_ctx* ctx = nullptr;
+    std::vector<int32_t> edges, Cn;
+    Search* search = nullptr;
+    char* ws = nullptr;
+    char* pin = nullptr;
+};
+
 // ================================================================================================
 extern "C" {
+
+void lwp_search_plan_destroy(lwp_search_plan* plan) {
+    if (!plan) return;
+    if (plan->ctx) { (void)hipSetDevice(plan->ctx->device); (void)hipStreamSynchronize(plan->ctx->stream); }
+    if (plan->ws) (void)hipFree(plan->ws);
+    if (plan->pin) (void)hipHostFree(plan->pin);
+    delete plan->search;
+    delete plan;
+}
+
+lwp_status lwp_search_plan_create(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges, const int32_t* edges,
+                                  const int32_t* C_node, const int32_t* d_tc, const int32_t* d_ts,
+                                  const int32_t* d_tx, int32_t schedule, lwp_search_plan** out) {
+    if (lwp_status s = check_ctx(ctx)) return s;
+    if (!out) return fail(ctx, LWP_E_INVAL, "null output");
+    *out = nullptr;
+    if (n_nodes < 1) return fail(ctx, LWP_E_GRAPH, "n_nodes must be >= 1");
+    if (n_edges < 0 || (n_edges > 0 && !edges)) return fail(ctx, LWP_E_GRAPH, "edge list missing");
+    if (!counts_valid(n_nodes, C_node)) return fail(ctx, LWP_E_INVAL, "every configuration count must be in [1, 65536]");
+    if (!d_tc || !d_ts || (n_edges > 0 && !d_tx)) return fail(ctx, LWP_E_INVAL, "null pointer");
+    if (((uintptr_t)d_tc | (uintptr_t)d_ts | (uintptr_t)d_tx) & 3)
+        return fail(ctx, LWP_E_INVAL, "table pointer not 4-byte aligned");
+    lwp_search_plan* plan = new (std::nothrow) lwp_search_plan();
+    if (!plan) return fail(ctx, LWP_E_NOMEM, "plan object");
+    plan->ctx = ctx;
+    auto bail = [&](lwp_status s) { const std::string why = ctx->err; lwp_search_plan_destroy(plan); ctx->err = why; return s; };
+    plan->edges.assign(edges, edges + 2 * (size_t)n_edges);
+    plan->Cn.assign(C_node, C_node + n_nodes);
+    plan->search = new (std::nothrow) Search(ctx, n_nodes, n_edges, plan->edges.data(), plan->Cn.data(), d_tc, d_ts, d_tx,
+                                             schedule, /*stored=*/false);
+    if (!plan->search) return bail(fail(ctx, LWP_E_NOMEM, "plan object"));
+    Search& search = *plan->search;
+    if (lwp_status s = search.plan()) return bail(s);
+    void* p = nullptr;
+    hipError_t e = hipMalloc(&p, std::max<size_t>(search.workspace_bytes(), 256));
+    if (e != hipSuccess) { (void)hipGetLastError(); return bail(fail(ctx, LWP_E_NOMEM, std::string("plan workspace: ") + hipGetErrorString(e))); }
+    plan->ws = static_cast<char*>(p);
+    e = hipHostMalloc(&p, search.pinned_bytes(), hipHostMallocDefault);
+    if (e != hipSuccess) { (void)hipGetLastError(); return bail(fail(ctx, LWP_E_NOMEM, std::string("plan pinned buffer: ") + hipGetErrorString(e))); }
+    plan->pin = static_cast<char*>(p);
+    if (lwp_status s = ensure_split_buffers(ctx)) return bail(s);
+    search.bind(plan->ws, plan->pin);
+    if (lwp_status s = search.prepare_replay()) return bail(s);
+    *out = plan;
+    return LWP_OK;
+}
+
+lwp_status lwp_search_plan_run(lwp_search_plan* plan, int32_t* out_cost, int32_t* out_strategy) {
+    if (!plan) return LWP_E_INVAL;
+    lwp_ctx* ctx = plan->ctx;
+    if (lwp_status s = check_ctx(ctx)) return s;
+    if (!out_cost || !out_strategy) return fail(ctx, LWP_E_INVAL, "null pointer");
+    if (lwp_status s = plan->search->enqueue_all()) return s;
+    LWP_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    return plan->search->finish(out_cost, out_strategy);
+}
 
 lwp_status lwp_plan_graph(int32_t n_nodes, int32_t n_edges, const int32_t* edges, int32_t schedule,
                           lwp_step* steps, int32_t* n_steps, int32_t* n_rounds, int32_t* n_residual_nodes) {
