@@ -32,6 +32,10 @@ namespace lwp {
 namespace {
 
 constexpr int NT = kNodeThreads;
+#ifndef LWP_PIPE
+#define LWP_PIPE 1
+#endif
+constexpr bool kPipeLdsReads = LWP_PIPE != 0;
 
 using v4i = int __attribute__((ext_vector_type(4)));
 using gv4cptr = const v4i __attribute__((address_space(1)))*;
@@ -53,6 +57,7 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
     static_assert(!MIXED || RB == 4, "launches of mixed shapes use 64 x 64 tiles");
     constexpr bool KEYED = (MODE == kModeKeyed);
     constexpr bool VALUE = (MODE == kModeValue);   // minimum only: no argmin, no keys, any int32
+    constexpr bool PIPE = kPipeLdsReads && RB == 4;
     constexpr int TM = 16 * RB, TN = 16 * RB;   // output tile
     constexpr int EP = TM * TK / NT;            // elements of A and of B each thread stages per stage
     constexpr int QUADS = RB / 4;
@@ -265,9 +270,11 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
         const bool chunk_end = (sic + 1 == spc);
         if (more) fetch((s + 1) * TK);
 
-#pragma unroll
-        for (int cc = 0; cc < TK; cc += 2) {
-            uint32_t av[2][RB], bv[2][RB];
+        // Operands of two candidates (cc, cc+1) per step.  With PIPE the reads of the next step are
+        // issued before the arithmetic of the current one, so one wavefront alone hides the LDS
+        // latency (launches too small to fill every SIMD with several wavefronts).
+        uint32_t avp[PIPE ? 2 : 1][2][RB], bvp[PIPE ? 2 : 1][2][RB];
+        auto lds_read = [&](int cc, uint32_t (&av)[2][RB], uint32_t (&bv)[2][RB]) {
 #pragma unroll
             for (int u = 0; u < 2; ++u)
 #pragma unroll
@@ -277,6 +284,17 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
                     av[u][4 * h] = a4.x; av[u][4 * h + 1] = a4.y; av[u][4 * h + 2] = a4.z; av[u][4 * h + 3] = a4.w;
                     bv[u][4 * h] = b4.x; bv[u][4 * h + 1] = b4.y; bv[u][4 * h + 2] = b4.z; bv[u][4 * h + 3] = b4.w;
                 }
+        };
+        if (PIPE) lds_read(0, avp[0], bvp[0]);
+#pragma unroll
+        for (int cc = 0; cc < TK; cc += 2) {
+            const int pb = PIPE ? ((cc >> 1) & 1) : 0;
+            if (PIPE) {
+                if (cc + 2 < TK) lds_read(cc + 2, avp[pb ^ 1], bvp[pb ^ 1]);
+                __builtin_amdgcn_sched_barrier(0);      // the reads go out before this step's arithmetic
+            } else lds_read(cc, avp[0], bvp[0]);
+            uint32_t (&av)[2][RB] = avp[pb];
+            uint32_t (&bv)[2][RB] = bvp[pb];
             if (KEYED) {
 #pragma unroll
                 for (int i = 0; i < RB; ++i)
