@@ -2,18 +2,19 @@
 //   out[a][b] = min_c ( A[a][c] + w[c] + B[c][b] ),  arg[a][b] = lowest c attaining the minimum.
 //
 // (min,+) is not a ring the matrix cores implement, so this runs on the integer VALU.  One
-// workgroup (256 threads = 4 wavefronts) owns a square output tile and walks c in stages of 16
-// that are staged through LDS (double-buffered, one barrier per stage); every thread keeps an
-// RB x RB block of running minima in registers (RB = 8: 128 x 128 tiles for throughput; RB = 4:
-// 64 x 64 tiles).  w is folded into A while A is staged, so the inner loop is one add and half a
-// three-way min per candidate.  When a launch has far fewer tiles than the chip has compute units,
-// several workgroups share one tile: each walks its own contiguous part of the c range and
+// workgroup (256 threads = 4 wavefronts) owns a square output tile and walks c in stages of TK
+// candidates that are staged through LDS (double-buffered, one barrier per stage, the next stage's
+// global loads in flight meanwhile); every thread keeps an RB x RB block of running minima in
+// registers (RB = 4: 64 x 64 tiles, TK = 32, 4 wavefronts per SIMD; RB = 8: 128 x 128 tiles,
+// TK = 16, 2 per SIMD).  w is folded into A while A is staged, so the inner loop is one add and
+// half a three-way min per candidate.  When a launch has far fewer tiles than the chip has compute
+// units, several workgroups share one tile: each walks its own contiguous part of the c range and
 // publishes its (minimum, argmin) block to global scratch; the workgroup that arrives last merges
 // the parts in ascending-c order with a strict '<', which keeps the lowest-index rule.
 //
-// Two arithmetic variants:
+// Three arithmetic variants:
 //   keyed   candidates are 32-bit keys (cost << tb) | (1 + position of c in its chunk); a chunk
-//           is `spc` stages (16*spc <= 2^tb - 1 consecutive c).  An unsigned min over keys
+//           is `spc` stages (TK*spc <= 2^tb - 1 consecutive c).  An unsigned min over keys
 //           carries the lowest c of equal costs inside a chunk for free.  At every chunk end a
 //           non-zero low field says the minimum changed in this chunk: (chunk, position) is
 //           recorded and the field is cleared, so a later chunk can only win with a strictly
@@ -25,6 +26,8 @@
 //   plain   int32 compare/select per candidate (strict '<' in ascending c); no precondition.
 //   value   the minimum only (signed three-way min, no argmin, no precondition), for callers that
 //           recompute the argmin of the few cells they need afterwards, as the paper's undo pass does.
+// A launch may mix products of different shapes (MIXED, 64 x 64 tiles): a prefix array of tile
+// counts tells a workgroup which product its tile belongs to.
 #include "lwp_kernels.h"
 
 namespace lwp {
