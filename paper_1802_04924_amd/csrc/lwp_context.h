@@ -79,13 +79,15 @@ inline int64_t keyed_spread(Range rA, Range rw, Range rB) {
 }
 
 // Tile choice.  Measured on MI355X the 64 x 64 variant (4 waves per SIMD, 32-deep stages) matches or
-// beats the 128 x 128 variant except for very large batches of short products (Cj < 512), where
-// its four times as many workgroup start-ups show; it also quantises a launch four times finer.
+// beats the 128 x 128 variant except for launches of very many tiles (batches of thousands of
+// products), where its four times as many workgroup start-ups cost about 1 %; it also quantises a
+// launch four times finer, which matters when a launch is only a few waves of workgroups.
 inline int64_t large_tiles(int32_t Ci, int32_t Ck, int64_t batch) {
     return (int64_t)((Ci + kTileLarge - 1) / kTileLarge) * ((Ck + kTileLarge - 1) / kTileLarge) * batch;
 }
 inline bool want_small_tiles(int32_t Ci, int32_t Cj, int32_t Ck, int64_t batch) {
-    return large_tiles(Ci, Ck, batch) < 2048 || Cj >= 512;
+    (void)Cj;
+    return large_tiles(Ci, Ck, batch) < 2048;
 }
 
 // Split tiles: a launch with few 64 x 64 tiles lets several workgroups share a tile, each with a
