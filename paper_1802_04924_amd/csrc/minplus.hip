@@ -225,8 +225,12 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
     // range); the low field, 1 + position of c inside its chunk, rides on the B side, where all
     // elements a thread stages share one c.  That makes three operations per A element (a
     // three-operand add, the clamp, shift-and-add) and one per B element (shift-and-add).
-    const uint32_t nboff = KEYED ? 0u - ((uint32_t)offB << tb) : 0u;
-    const uint32_t noffA = 0u - (uint32_t)offA;
+    uint32_t nboff = KEYED ? 0u - ((uint32_t)offB << tb) : 0u;
+    uint32_t noffA = 0u - (uint32_t)offA;
+    // opaque to the optimiser, which would otherwise rewrite the two fused forms below
+    // (add3; shift-and-add) into subtract, add, subtract, shift
+    noffA = __builtin_amdgcn_readfirstlane(noffA);      // uniform: a scalar register
+    asm volatile("" : "+v"(nboff), "+s"(noffA));
     auto stash = [&](int c0, int pos0, int buf) {
         const uint32_t pos = (uint32_t)(pos0 + br + 1);
         uint32_t ka[EP], kb[EP];
