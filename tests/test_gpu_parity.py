@@ -459,3 +459,19 @@ def test_search_resnet_shaped(ctx, C, hi, bottleneck):
     p = wl.resnet_problem(C, seed=C, bottleneck=bottleneck, lo=0, hi=hi)
     for schedule in (wl.SCHEDULE_ROUNDS, wl.SCHEDULE_LEFT_FOLD):
         run_search(ctx, p, schedule)
+
+
+def test_search_long_chains(ctx):
+    # thousands of layers: thousands of rounds under LEFT_FOLD, batches of thousands of tiny
+    # products under ROUNDS
+    p = wl.chain_problem(3000, 3, seed=30, tc_range=(0, 9), ts_range=(0, 9), tx_range=(0, 9))
+    run_search(ctx, p, wl.SCHEDULE_ROUNDS)
+    p = wl.chain_problem(1200, 5, seed=31, tc_range=(0, 1000), ts_range=(0, 1000), tx_range=(0, 1000))
+    run_search(ctx, p, wl.SCHEDULE_LEFT_FOLD)
+    Cn = wl.ragged_counts(2500, 32, 1, 6)
+    edges = wl.chain_edges(2500)
+    tc, ts, tx = wl.ragged_tables(2500, edges, Cn, 33, 0, 50)
+    ref = oracle.search_ragged(2500, edges, Cn, tc, ts, tx)
+    for undo in (0, 1):
+        cost, S = ctx.search_graph_ragged(2500, edges, Cn, dev(tc), dev(ts), dev(tx), 0, undo)
+        assert cost == ref["cost"] and np.array_equal(S, ref["strategy"])
