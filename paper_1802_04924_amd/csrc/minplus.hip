@@ -72,6 +72,12 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
     // contiguous range of logical ids, and walk the tiles of a product in panels of 8 tile rows,
     // column by column: 64 consecutive ids (the tiles resident on one XCD at a time) then form an
     // 8 x 8 block that shares 8 row strips of A and 8 column strips of B.
+    // A workgroup that starts while older ones are in their arithmetic loops would get issue slots
+    // only when those stall, and its start-up -- a chain of dependent loads with some scalar
+    // arithmetic between them -- would take many times longer than on an idle compute unit.  Its
+    // wavefronts therefore run at raised priority until their first stage is in LDS, and again
+    // while they store their results.
+    __builtin_amdgcn_s_setprio(3);
     uint32_t bid = blockIdx.x;
     const uint32_t total = gridDim.x;
     if ((total & 7u) == 0u) bid = (bid & 7u) * (total >> 3) + (bid >> 3);
@@ -269,6 +275,7 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
     int chunk_c0 = s_first * TK;      // first c of the current chunk
     stash(s_first * TK, 0, 0);
     __syncthreads();
+    __builtin_amdgcn_s_setprio(0);
 
     for (int it = 0; it < n_g; ++it) {
         const int s = s_first + it;
@@ -374,6 +381,7 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
     // relaxed atomic stores and loads, which go through to memory, so no cache-wide write-back or
     // invalidate is needed; a workgroup-scope release makes every thread's stores complete before
     // the counter is bumped.
+    __builtin_amdgcn_s_setprio(3);
     bool raw = KEYED;                          // m1 still holds keys (otherwise plain costs)
     if (RB == 4 && kparts > 1) {
         constexpr int CELLS = RB * RB;
