@@ -85,9 +85,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="cfg4", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "resid", "vgg16", "cfg1-lists", "vgg16-lists"],
+    ap.add_argument("--workload", default="cfg4", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "resid", "vgg16", "cfg1-lists", "vgg16-lists", "wide"],
                     help="cfg4 is the headline; *-lists: the AlexNet- / VGG-16-shaped chain with one configuration "
-                         "list per layer (Sec. 4, Table 1) instead of one padded list of 256 rows")
+                         "list per layer (Sec. 4, Table 1) instead of one padded list of 256 rows; wide: a chain "
+                         "with node costs from microseconds to half a second (no global offset fits packed keys)")
     ap.add_argument("--layers", type=int, default=64, help="cfg4 only: chain length")
     ap.add_argument("--configs", type=int, default=0, help="override C of the workload")
     ap.add_argument("--undo", default="stored", choices=["stored", "recompute"],
@@ -168,6 +169,10 @@ def main():
             p["tc"], p["ts"], p["tx"] = (t.cpu().numpy() for t in tabs)
         elif name == "cfg2":
             p = wl.config2(args.configs or 512)
+        elif name == "wide":
+            Cw = args.configs or 2048
+            p = wl.chain_problem(min(args.layers, 10), Cw, 6, tc_range=(1000, 1 << 29), ts_range=(0, 1 << 20),
+                                 tx_range=(0, 1 << 22), schedule=wl.SCHEDULE_LEFT_FOLD, name=f"wide_chain_C{Cw}")
         elif name == "resid":
             # a graph no elimination applies to: one layer feeding three that never rejoin (K = 4);
             # the whole search is the enumeration of C^4 strategies of the final graph

@@ -78,6 +78,15 @@ inline int64_t keyed_spread(Range rA, Range rw, Range rB) {
     return std::min(a_max, out_max + 1) + (rB.hi - rB.lo);
 }
 
+// The same for keys re-based per output row: the row's minimum re-bases to 0 and everything more
+// than B's spread above it is clamped, so only B's spread counts.
+inline int64_t keyed_row_spread(Range rB) { return 2 * (rB.hi - rB.lo) + 1; }
+// Their extra pass over A pays once a launch is bound by arithmetic rather than by latency
+// (measured: no gain for launches of a few 163^3 products, 2.3x for 2048^3).
+inline bool keyed_row_pays(int32_t Ci, int32_t Cj, int32_t Ck, int64_t batch) {
+    return (int64_t)Ci * Cj * Ck * batch >= ((int64_t)1 << 28);
+}
+
 // Tile choice.  Measured on MI355X the 64 x 64 variant (4 waves per SIMD, 32-deep stages) matches or
 // beats the 128 x 128 variant except for launches of very many tiles (batches of thousands of
 // products), where its four times as many workgroup start-ups cost about 1 %; it also quantises a

@@ -45,18 +45,21 @@ lwp_status lwp_eliminate_node(lwp_ctx* ctx, int32_t batch, int32_t Ci, int32_t C
     const bool value_only = (d_argmin == nullptr);
     const bool keyed = !value_only && (spread <= kKeyedMaxSpreadSmall ||
                        (spread <= kKeyedMaxSpreadLarge && (!prefer_small || large_tiles(Ci, Ck, batch) >= 512)));
-    const bool small = prefer_small && (value_only || spread <= kKeyedMaxSpreadSmall || !keyed);
+    // keys re-based per row (64 x 64 tiles) where global offsets do not fit: only B's spread counts
+    const bool keyed_row = !value_only && !keyed && keyed_row_spread(rB) <= kKeyedMaxSpreadSmall &&
+                           keyed_row_pays(Ci, Cj, Ck, batch);
+    const bool small = keyed_row || (prefer_small && (value_only || spread <= kKeyedMaxSpreadSmall || !keyed));
     const int tile = small ? kTileSmall : kTileLarge;
     const int64_t tilesM = (Ci + tile - 1) / tile, tilesN = (Ck + tile - 1) / tile;
     a.sA = (int64_t)Ci * Cj; a.sw = Cj; a.sB = (int64_t)Cj * Ck; a.sO = (int64_t)Ci * Ck;
     a.Ci = Ci; a.Cj = Cj; a.Ck = Ck; a.batch = batch;
     a.tilesM = (int32_t)tilesM; a.tilesN = (int32_t)tilesN;
     {
-        ScopedTimer tm(ctx, 0, (int64_t)batch * Ci * Cj * Ck, keyed);
+        ScopedTimer tm(ctx, 0, (int64_t)batch * Ci * Cj * Ck, keyed || keyed_row);
         const int kparts = choose_kparts(tilesM * tilesN * batch, Cj, small);
         if (kparts > 1) { if (lwp_status s = ensure_split_buffers(ctx)) return s; }
         set_split(ctx, a, kparts);
-        LWP_HIP(ctx, launch_minplus(a, value_only ? kModeValue : (keyed ? kModeKeyed : kModePlain), small, ctx->stream));
+        LWP_HIP(ctx, launch_minplus(a, value_only ? kModeValue : (keyed ? kModeKeyed : (keyed_row ? kModeKeyedRow : kModePlain)), small, ctx->stream));
     }
     return LWP_OK;
 }

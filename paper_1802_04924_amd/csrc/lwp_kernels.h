@@ -63,7 +63,9 @@ constexpr int64_t kKeyedMaxSpreadLarge = (1ll << 27) - 2, kKeyedMaxSpreadSmall =
 // mode: packed keys (needs the spread bound above), plain int32 compare/select (any values), or
 // value-only (minimum without argmin, any values; `arg` is ignored).  small_tiles selects 64 x 64
 // output tiles instead of 128 x 128; tilesM / tilesN in args must match.
-constexpr int kModeKeyed = 0, kModePlain = 1, kModeValue = 2;
+// kModeKeyedRow: packed keys whose A side is re-based per output row (64 x 64 tiles only): needs
+//   2 * (hiB - loB) + 1 <= kKeyedMaxSpreadSmall and nothing of A or w beyond A + w fitting int32.
+constexpr int kModeKeyed = 0, kModePlain = 1, kModeValue = 2, kModeKeyedRow = 3;
 hipError_t launch_minplus(const NodeArgs& args, int mode, bool small_tiles, hipStream_t stream);
 
 // ---- edge elimination (Eq. 3) --------------------------------------------------------------

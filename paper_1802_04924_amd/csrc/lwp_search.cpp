@@ -397,7 +397,7 @@ lwp_status Search::write_descriptors() {
     // Node eliminations of one round are independent; those of equal kernel variant share a
     // launch if they agree in shape (Ci, Cj, Ck) or run on 64 x 64 tiles (a launch of mixed shapes),
     // so the descriptors of a round are ordered by (variant, shape).
-    struct NodeWork { NodeDesc d; int64_t spread; int32_t Ci, Cj, Ck; int variant; };
+    struct NodeWork { NodeDesc d; int64_t spread, spread_row; int32_t Ci, Cj, Ck; int variant; };
     // The propagated bounds are worst cases and grow along a chain although the minima do not.
     // Where they cannot prove that a step stays inside int32 the step is not refused: it runs on a
     // variant without range conditions and every kernel checks the tables' measured ranges (or
@@ -449,7 +449,8 @@ lwp_status Search::write_descriptors() {
             d.rngB = d_stats_ + 2 * (int64_t)erng[s.e2];
             d.rngW = d_stats_ + 2 * (int64_t)(rng_w0_ + s.j);
             d.rngOut = d_stats_ + 2 * (int64_t)(rng_node0_ + (int32_t)ni);
-            nw.spread = proven ? keyed_spread(rA, rw, rB) : (int64_t)1 << 62;   // unproven: no packed keys
+            nw.spread = proven ? keyed_spread(rA, rw, rB) : (int64_t)1 << 62;   // unproven: no keys on global offsets
+            nw.spread_row = keyed_row_spread(rB);       // keys re-based per row need a bound on B only
             nw.Ci = tA.rows; nw.Cj = tA.cols; nw.Ck = tB.cols;
             d.Ci = nw.Ci; d.Cj = nw.Cj; d.Ck = nw.Ck;
             work.push_back(nw);
@@ -460,8 +461,10 @@ lwp_status Search::write_descriptors() {
             ++ni; ++t;
         }
         // kernel variant per product: packed keys on the preferred tile size if the spread
-        // allows, else packed keys on 128 x 128 tiles (one more bit), else the plain variant;
-        // 0 keyed small, 1 keyed large, 2 plain small, 3 plain large, 4 value small, 5 value large
+        // allows, else packed keys on 128 x 128 tiles (one more bit), else keys re-based per row
+        // (64 x 64 tiles; one more pass over A, but only B's spread counts), else the plain variant;
+        // 0 keyed small, 1 keyed large, 2 plain small, 3 plain large, 4 value small, 5 value large,
+        // 6 keyed per row (small)
         auto shape_of = [](const NodeWork& a) { return std::make_tuple(a.Ci, a.Cj, a.Ck); };
         std::map<std::tuple<int32_t, int32_t, int32_t>, int64_t> shape_count;
         for (const NodeWork& x : work) ++shape_count[shape_of(x)];
@@ -472,6 +475,7 @@ lwp_status Search::write_descriptors() {
             if (!stored) x.variant = prefer_small ? 4 : 5;     // value-only: no range condition
             else if (x.spread <= (prefer_small ? kKeyedMaxSpreadSmall : kKeyedMaxSpreadLarge)) x.variant = prefer_small ? 0 : 1;
             else if (x.spread <= kKeyedMaxSpreadLarge && large_fills_chip) x.variant = 1;
+            else if (x.spread_row <= kKeyedMaxSpreadSmall && keyed_row_pays(x.Ci, x.Cj, x.Ck, same)) x.variant = 6;
             else x.variant = prefer_small ? 2 : 3;
         }
         order.resize(work.size());
@@ -483,7 +487,7 @@ lwp_status Search::write_descriptors() {
             const int v = work[order[a]].variant;
             size_t b = a;
             while (b < order.size() && work[order[b]].variant == v) ++b;
-            const bool small = (v == 0 || v == 2 || v == 4);
+            const bool small = (v == 0 || v == 2 || v == 4 || v == 6);
             const bool one_shape = shape_of(work[order[a]]) == shape_of(work[order[b - 1]]);
             if (small && !one_shape) {
                 // one launch over all shapes: product q owns tiles [tile_begin[q], tile_begin[q+1])
@@ -566,8 +570,8 @@ lwp_status Search::enqueue_eliminations() {
         }
         for (const NodeLaunch& nl : r.launches) {
             const int v = nl.variant;
-            const bool keyed = v < 2, small = (v == 0 || v == 2 || v == 4);
-            const int mode = v >= 4 ? kModeValue : (keyed ? kModeKeyed : kModePlain);
+            const bool keyed = v < 2 || v == 6, small = (v == 0 || v == 2 || v == 4 || v == 6);
+            const int mode = v == 6 ? kModeKeyedRow : (v >= 4 ? kModeValue : (keyed ? kModeKeyed : kModePlain));
             const int tile = small ? kTileSmall : kTileLarge;
             NodeArgs na{};
             na.descs = d_nd + nl.first;

@@ -12,7 +12,7 @@
 // publishes its (minimum, argmin) block to global scratch; the workgroup that arrives last merges
 // the parts in ascending-c order with a strict '<', which keeps the lowest-index rule.
 //
-// Three arithmetic variants:
+// Four arithmetic variants:
 //   keyed   candidates are 32-bit keys (cost << tb) | (1 + position of c in its chunk); a chunk
 //           is `spc` stages (TK*spc <= 2^tb - 1 consecutive c).  An unsigned min over keys
 //           carries the lowest c of equal costs inside a chunk for free.  At every chunk end a
@@ -23,6 +23,11 @@
 //           the minimum nor tie with it); they must then fit 32-tb bits.  The launcher's caller
 //           guarantees that from value ranges; the kernel derives tb itself from the ranges it is
 //           given (measured ones where an earlier launch of the same stream left them).
+//   keyed, re-based per row   as keyed, but A + w is re-based to the minimum of its own row (over
+//           the c range the workgroup walks) and clamped just above the spread of B: a candidate
+//           further above its row's minimum than B's spread can never win.  Key width then depends
+//           on the spread of B alone, however wide the values of A and w range (cost tables mix
+//           nanosecond-scale and second-scale entries).  Costs one extra pass over the A rows.
 //   plain   int32 compare/select per candidate (strict '<' in ascending c); no precondition.
 //   value   the minimum only (signed three-way min, no argmin, no precondition), for callers that
 //           recompute the argmin of the few cells they need afterwards, as the paper's undo pass does.
@@ -58,7 +63,9 @@ __device__ __forceinline__ int wave_max_i32(int v) {
 template <int MODE, int RB, int TK, bool MIXED = false>
 __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) void minplus_kernel(const NodeArgs p) {
     static_assert(!MIXED || RB == 4, "launches of mixed shapes use 64 x 64 tiles");
-    constexpr bool KEYED = (MODE == kModeKeyed);
+    constexpr bool ROW = (MODE == kModeKeyedRow);  // keys re-based per output row
+    constexpr bool KEYED = (MODE == kModeKeyed) || ROW;
+    static_assert(!ROW || RB == 4, "row-rebased keys use 64 x 64 tiles");
     constexpr bool VALUE = (MODE == kModeValue);   // minimum only: no argmin, no keys, any int32
     constexpr bool PIPE = kPipeLdsReads && RB == 4;
     constexpr int TM = 16 * RB, TN = 16 * RB;   // output tile
@@ -72,12 +79,6 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
     // contiguous range of logical ids, and walk the tiles of a product in panels of 8 tile rows,
     // column by column: 64 consecutive ids (the tiles resident on one XCD at a time) then form an
     // 8 x 8 block that shares 8 row strips of A and 8 column strips of B.
-    // A workgroup that starts while older ones are in their arithmetic loops would get issue slots
-    // only when those stall, and its start-up -- a chain of dependent loads with some scalar
-    // arithmetic between them -- would take many times longer than on an idle compute unit.  Its
-    // wavefronts therefore run at raised priority until their first stage is in LDS, and again
-    // while they store their results.
-    __builtin_amdgcn_s_setprio(3);
     uint32_t bid = blockIdx.x;
     const uint32_t total = gridDim.x;
     if ((total & 7u) == 0u) bid = (bid & 7u) * (total >> 3) + (bid >> 3);
@@ -112,6 +113,14 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
         d.out += (int64_t)bi * p.sO;
         if (d.arg) d.arg += (int64_t)bi * p.sO;
     }
+    // A workgroup that starts while older ones are in their arithmetic loops would get issue slots
+    // only when those stall, and its start-up -- a chain of dependent loads with some scalar
+    // arithmetic between them -- would take many times longer than on an idle compute unit.  Its
+    // wavefronts therefore run at raised priority until their first stage is in LDS, and again
+    // while they store their results.
+    // (Raised only after the descriptor has been read: ahead of that read the priority change keeps
+    // the compiler from using scalar loads for it.)
+    __builtin_amdgcn_s_setprio(3);
     const int Ci = MIXED ? d.Ci : p.Ci, Cj = MIXED ? d.Cj : p.Cj, Ck = MIXED ? d.Ck : p.Ck;
     const int tilesM = MIXED ? (Ci + TM - 1) / TM : p.tilesM, tilesN = MIXED ? (Ck + TN - 1) / TN : p.tilesN;
     constexpr int PANEL = 8;
@@ -203,6 +212,33 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
             atomicOr(d.flag, 1);
     }
 
+    // ---- row-rebased keys: minimum of A + w over this workgroup's c range, per tile row ----
+    __shared__ int32_t rmin[ROW ? TM : 1];
+    if (ROW) {
+        int32_t mn = 0x7fffffff;
+        const int c_end = min(Cj, (s_first + n_g) * TK);
+        for (int c0 = s_first * TK; c0 < c_end; c0 += TK) {
+            if (vecA && c0 + TK <= Cj) {
+#pragma unroll
+                for (int v = 0; v < EP / 4; ++v) {
+                    const v4i x = ((gv4cptr)(Arow + c0 + lseg))[v];
+                    const v4i y = ((gv4cptr)(W + c0 + lseg))[v];
+                    mn = min(min(mn, x.x + y.x), min(x.y + y.y, min(x.z + y.z, x.w + y.w)));
+                }
+            } else {
+#pragma unroll
+                for (int q = 0; q < EP; ++q) {
+                    const int c = c0 + lseg + q;
+                    if (c < Cj) mn = min(mn, Arow[c] + W[c]);
+                }
+            }
+        }
+#pragma unroll
+        for (int o = TPR / 2; o > 0; o >>= 1) mn = min(mn, __shfl_xor(mn, o));   // the TPR threads of a row are adjacent lanes
+        if ((tid % TPR) == 0) rmin[lr] = mn;
+        __syncthreads();
+    }
+
     // ---- key parameters from value ranges (uniform, scalar) ----
     int32_t offA = 0, offB = 0;
     int tb = 0;
@@ -212,7 +248,9 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
         offB = (int32_t)loB;
         const long long a_max = hiA + hiW - (loA + loW);          // largest re-based A + w
         const long long out_max = (hiA - loA) + (hiB - loB);      // largest re-based result
-        const long long capl = min(a_max, out_max + 1);
+        // per row: the row's minimum re-bases to 0 and pairs with a B of at most the spread of B, so
+        // anything more than that spread above the row's minimum loses
+        const long long capl = ROW ? (hiB - loB) + 1 : min(a_max, out_max + 1);
         const long long spread = capl + (hiB - loB);
         cap = (uint32_t)capl;
         constexpr int TB_MIN = (TK <= 16) ? 5 : 6;               // a chunk holds at least one stage
@@ -232,11 +270,15 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
     // elements a thread stages share one c.  That makes three operations per A element (a
     // three-operand add, the clamp, shift-and-add) and one per B element (shift-and-add).
     uint32_t nboff = KEYED ? 0u - ((uint32_t)offB << tb) : 0u;
-    uint32_t noffA = 0u - (uint32_t)offA;
+    uint32_t noffA = 0u - (uint32_t)(ROW ? rmin[lr] : offA);
     // opaque to the optimiser, which would otherwise rewrite the two fused forms below
     // (add3; shift-and-add) into subtract, add, subtract, shift
-    noffA = __builtin_amdgcn_readfirstlane(noffA);      // uniform: a scalar register
-    asm volatile("" : "+v"(nboff), "+s"(noffA));
+    if (ROW) {
+        asm volatile("" : "+v"(nboff), "+v"(noffA));
+    } else {
+        noffA = __builtin_amdgcn_readfirstlane(noffA);  // uniform: a scalar register
+        asm volatile("" : "+v"(nboff), "+s"(noffA));
+    }
     auto stash = [&](int c0, int pos0, int buf) {
         const uint32_t pos = (uint32_t)(pos0 + br + 1);
         uint32_t ka[EP], kb[EP];
@@ -394,7 +436,8 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
                 // a part whose stages all lie beyond Cj still holds the padding key: its cost field plus
                 // the offsets may pass INT32_MAX, so the sum is formed in 64 bits and saturated (real
                 // costs never exceed INT32_MAX, and such a part is the last, so it cannot win a tie)
-                const int32_t cst = KEYED ? (int32_t)min((long long)(m1[i][j] >> tb) + offA + offB, 2147483647ll) : (int32_t)m1[i][j];
+                const long long base = ROW ? (long long)rmin[ty * 4 + (i & 3)] + offB : (long long)offA + offB;
+                const int32_t cst = KEYED ? (int32_t)min((long long)(m1[i][j] >> tb) + base, 2147483647ll) : (int32_t)m1[i][j];
                 __hip_atomic_store(&mine[(i * RB + j) * NT + tid], cst, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 if (!VALUE) __hip_atomic_store(&mine[(CELLS + i * RB + j) * NT + tid], (int32_t)rec[i][j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
@@ -446,7 +489,7 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
         int32_t val[RB];
 #pragma unroll
         for (int j = 0; j < RB; ++j)
-            val[j] = raw ? (int32_t)(m1[i][j] >> tb) + offA + offB : (int32_t)m1[i][j];
+            val[j] = raw ? (int32_t)(m1[i][j] >> tb) + (ROW ? rmin[ty * 4 + (i & 3)] : offA) + offB : (int32_t)m1[i][j];
 #pragma unroll
         for (int h = 0; h < QUADS; ++h) {
             const int b = b0 + h * 64 + tx * 4;
@@ -492,12 +535,15 @@ hipError_t launch_minplus(const NodeArgs& args, int mode, bool small_tiles, hipS
         return hipErrorInvalidValue;   // beyond the capacity of the split-tile buffers
     if (mixed && (!small_tiles || !args.descs)) return hipErrorInvalidValue;
     dim3 grid((unsigned)blocks), block(NT);
+    if (mode == kModeKeyedRow && !small_tiles) return hipErrorInvalidValue;
     if (mixed) {
         if (mode == kModeKeyed) hipLaunchKernelGGL((minplus_kernel<kModeKeyed, 4, 32, true>), grid, block, 0, stream, args);
+        else if (mode == kModeKeyedRow) hipLaunchKernelGGL((minplus_kernel<kModeKeyedRow, 4, 32, true>), grid, block, 0, stream, args);
         else if (mode == kModeValue) hipLaunchKernelGGL((minplus_kernel<kModeValue, 4, 32, true>), grid, block, 0, stream, args);
         else hipLaunchKernelGGL((minplus_kernel<kModePlain, 4, 32, true>), grid, block, 0, stream, args);
     } else if (small_tiles) {
         if (mode == kModeKeyed) hipLaunchKernelGGL((minplus_kernel<kModeKeyed, 4, 32>), grid, block, 0, stream, args);
+        else if (mode == kModeKeyedRow) hipLaunchKernelGGL((minplus_kernel<kModeKeyedRow, 4, 32>), grid, block, 0, stream, args);
         else if (mode == kModeValue) hipLaunchKernelGGL((minplus_kernel<kModeValue, 4, 32>), grid, block, 0, stream, args);
         else hipLaunchKernelGGL((minplus_kernel<kModePlain, 4, 32>), grid, block, 0, stream, args);
     } else {

@@ -69,11 +69,12 @@ def spread_case(shape, bits, seed):
     return A, w, B
 
 
-# The spread of A + w + B (3 * 2^bits here) decides the key width; too wide a spread falls back to
-# the plain variant.  Launches with fewer than 2048 tiles of 128 x 128 use 64 x 64 tiles, whose
-# deeper stages leave one bit less for the cost (so do all launches with Cj >= 512); a spread that
-# needs that bit moves the launch to 128 x 128 tiles if those still fill the chip (>= 512 tiles).
-@pytest.mark.parametrize("bits,expect_keyed", [(22, True), (24, True), (25, False), (29, False)])
+# The spread of A + w + B (3 * 2^bits here) decides the key width.  Launches with fewer than 2048
+# tiles of 128 x 128 use 64 x 64 tiles, whose deeper stages leave one bit less for the cost; a spread
+# that needs that bit moves the launch to 128 x 128 tiles if those still fill the chip (>= 512
+# tiles).  Beyond that the plain variant runs (keys re-based per row are for launches of at least
+# 2^28 cell updates, tested further down).
+@pytest.mark.parametrize("bits,expect_keyed", [(22, True), (24, True), (25, False), (26, False), (29, False)])
 @pytest.mark.parametrize("shape", [(2, 130, 257, 140), (1, 128, 512, 128), (1, 31, 1000, 17)])
 def test_eliminate_node_key_widths_small_tiles(ctx, shape, bits, expect_keyed):
     A, w, B = spread_case(shape, bits, bits * 1000 + shape[2])
@@ -120,6 +121,51 @@ def test_split_tiles_with_an_empty_part_and_costs_next_to_int32_max(ctx):
     for undo in (0, 1):
         cost, S = ctx.search_graph_ragged(len(Cn), edges, Cn, dev(tc), dev(ts), dev(tx), 0, undo)
         assert cost == ref["cost"] and np.array_equal(S, ref["strategy"])
+
+
+# shapes of at least 2^28 cell updates (smaller launches are bound by latency and stay on the plain
+# variant): ragged in every dimension, fewer rows than a tile, the longest c range, a batch, split tiles
+@pytest.mark.parametrize("shape", [(1, 333, 1000, 900), (2, 130, 2570, 500), (40, 100, 330, 290), (1, 3, 65536, 1400),
+                                   (1, 512, 1024, 512), (9, 257, 513, 257)])
+@pytest.mark.parametrize("b_bits", [1, 12, 24])
+def test_eliminate_node_keys_rebased_per_row(ctx, shape, b_bits):
+    # A and w range over 2^29 (no global offset brings A + w + B into 26 bits) while B is narrow:
+    # every row of A + w is re-based to its own minimum and the packed keys still apply
+    batch, Ci, Cj, Ck = shape
+    rng = np.random.default_rng(Cj * 31 + b_bits)
+    A = rng.integers(-(1 << 28), 1 << 28, size=(batch, Ci, Cj), dtype=np.int32)
+    w = rng.integers(-(1 << 28), 1 << 28, size=(batch, Cj), dtype=np.int32)
+    B = rng.integers(1000, 1000 + (1 << b_bits) - 1, size=(batch, Cj, Ck), endpoint=True, dtype=np.int32)
+    # ties: repeat candidates exactly, and rows whose minimum is attained many times
+    A[:, :, Cj // 2:] = A[:, :, :Cj - Cj // 2]
+    w[:, Cj // 2:] = w[:, :Cj - Cj // 2]
+    B[:, Cj // 2:, :] = B[:, :Cj - Cj // 2, :]
+    if Ci > 2:
+        A[:, 1, :] = -w                                   # a whole row of A + w equal to 0
+    check_products(ctx, A, w, B, expect_keyed=True)
+    if b_bits == 1:                                       # the same launch below the size threshold: plain
+        check_products(ctx, A[:1, :, :64], w[:1, :64], B[:1, :64, :], expect_keyed=False)
+
+
+def test_search_with_wide_node_costs_uses_keys_rebased_per_row(ctx):
+    # node costs from microseconds to half a second, transfers up to a few milliseconds: the shape
+    # of real cost tables (Sec. 5.1), at a size where arithmetic dominates
+    p = wl.chain_problem(6, 700, 3, tc_range=(1000, 1 << 29), ts_range=(0, 1 << 20), tx_range=(0, 1 << 22))
+    ctx.profile_enable(True)
+    ctx.profile_reset()
+    for schedule in (wl.SCHEDULE_ROUNDS, wl.SCHEDULE_LEFT_FOLD):
+        run_search(ctx, p, schedule)
+    prof = ctx.profile_read()
+    ctx.profile_enable(False)
+    # run_search runs every search twice: stored argmin (all launches on keys) and recomputed (value-only)
+    assert prof["keyed_launches"] * 2 == prof["node_launches"] > 0
+    Cn = np.array([700, 650, 701, 300, 900, 640], np.int32)      # the same with per-node counts
+    edges = wl.chain_edges(6)
+    tc, ts, tx = wl.ragged_tables(6, edges, Cn, 8, 0, 1 << 22)
+    tc = (tc.astype(np.int64) * 100).astype(np.int32)
+    ref = oracle.search_ragged(6, edges, Cn, tc, ts, tx)
+    cost, S = ctx.search_graph_ragged(6, edges, Cn, dev(tc), dev(ts), dev(tx))
+    assert cost == ref["cost"] and np.array_equal(S, ref["strategy"])
 
 
 def test_eliminate_node_negative_and_offset_values(ctx):
