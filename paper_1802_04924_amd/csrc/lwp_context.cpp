@@ -69,11 +69,11 @@ ScopedTimer::ScopedTimer(lwp_ctx* c, int kind, int64_t work, bool keyed) : ctx(c
     if (!c->profiling) return;
     lwp_ctx::Timed t{nullptr, nullptr, kind, work, keyed};
     if (hipEventCreate(&t.a) != hipSuccess || hipEventCreate(&t.b) != hipSuccess) return;
-    hipEventRecord(t.a, c->stream);
+    (void)hipEventRecord(t.a, c->stream);
     c->timed.push_back(t);
     idx = c->timed.size() - 1;
 }
-ScopedTimer::~ScopedTimer() { if (idx != (size_t)-1) hipEventRecord(ctx->timed[idx].b, ctx->stream); }
+ScopedTimer::~ScopedTimer() { if (idx != (size_t)-1) (void)hipEventRecord(ctx->timed[idx].b, ctx->stream); }
 
 lwp_status drain_profile(lwp_ctx* ctx) {
     LWP_HIP(ctx, hipStreamSynchronize(ctx->stream));
@@ -87,7 +87,7 @@ lwp_status drain_profile(lwp_ctx* ctx) {
                 ctx->prof.edge_launches++; ctx->prof.edge_cells += t.work; ctx->prof.edge_ms += ms;
             }
         }
-        hipEventDestroy(t.a); hipEventDestroy(t.b);
+        (void)hipEventDestroy(t.a); (void)hipEventDestroy(t.b);
     }
     ctx->timed.clear();
     return LWP_OK;
@@ -130,7 +130,7 @@ void lwp_destroy(lwp_ctx* ctx) {
     if (!ctx) return;
     (void)hipSetDevice(ctx->device);
     (void)hipStreamSynchronize(ctx->stream);
-    for (auto& t : ctx->timed) { hipEventDestroy(t.a); hipEventDestroy(t.b); }
+    for (auto& t : ctx->timed) { (void)hipEventDestroy(t.a); (void)hipEventDestroy(t.b); }
     if (ctx->ws) (void)hipFree(ctx->ws);
     if (ctx->pin) (void)hipHostFree(ctx->pin);
     if (ctx->split) (void)hipFree(ctx->split);
