@@ -11,8 +11,6 @@
 #include "lwp_plan.h"
 
 #include <algorithm>
-#include <map>
-#include <queue>
 #include <utility>
 
 namespace lwp {
@@ -33,36 +31,47 @@ lwp_status make_plan(int32_t n_nodes, int32_t n_edges, const int32_t* edges, int
         if (s == d) { err = "self loop"; return LWP_E_GRAPH; }
         E[e] = {s, d, true};
     }
-    {   // acyclicity (Kahn)
-        std::vector<int32_t> indeg(n_nodes, 0);
-        std::vector<std::vector<int32_t>> succ(n_nodes);
-        for (auto& e : E) { indeg[e.dst]++; succ[e.src].push_back(e.dst); }
-        std::queue<int32_t> q;
-        for (int32_t v = 0; v < n_nodes; ++v) if (!indeg[v]) q.push(v);
-        int32_t seen = 0;
-        while (!q.empty()) {
-            int32_t v = q.front(); q.pop(); ++seen;
-            for (int32_t u : succ[v]) if (--indeg[u] == 0) q.push(u);
+    {   // acyclicity (Kahn), successors in compressed rows
+        std::vector<int32_t> indeg(n_nodes, 0), first(n_nodes + 1, 0), succ(n_edges), order;
+        for (auto& e : E) { indeg[e.dst]++; first[e.src + 1]++; }
+        for (int32_t v = 0; v < n_nodes; ++v) first[v + 1] += first[v];
+        std::vector<int32_t> fill(first.begin(), first.end() - 1);
+        for (auto& e : E) succ[fill[e.src]++] = e.dst;
+        order.reserve(n_nodes);
+        for (int32_t v = 0; v < n_nodes; ++v) if (!indeg[v]) order.push_back(v);
+        for (size_t head = 0; head < order.size(); ++head) {
+            const int32_t v = order[head];
+            for (int32_t x = first[v]; x < first[v + 1]; ++x) if (--indeg[succ[x]] == 0) order.push_back(succ[x]);
         }
-        if (seen != n_nodes) { err = "graph has a cycle"; return LWP_E_GRAPH; }
+        if ((int32_t)order.size() != n_nodes) { err = "graph has a cycle"; return LWP_E_GRAPH; }
     }
 
     std::vector<char> gone(n_nodes, 0), taken(n_nodes, 0);
     std::vector<int32_t> n_in(n_nodes), n_out(n_nodes), e_in(n_nodes), e_out(n_nodes);
     int32_t round = 0;
+    plan.steps.reserve(n_edges);
+    struct Key { int32_t src, dst, id; };
+    std::vector<Key> keys;
+    keys.reserve(n_edges);
+    std::vector<int32_t> chosen;
     for (;;) {
         bool worked = false;
-        // E-phase
-        std::map<std::pair<int32_t, int32_t>, std::vector<int32_t>> groups;
-        for (int32_t e = 0; e < n_edges; ++e) if (E[e].live) groups[{E[e].src, E[e].dst}].push_back(e);
-        for (auto& g : groups) {
-            const std::vector<int32_t>& ids = g.second;       // ascending by construction
-            for (size_t z = 1; z < ids.size(); ++z) {
-                plan.steps.push_back({1, -1, g.first.first, g.first.second, ids[0], ids[z], round});
-                E[ids[z]].live = false;
+        // E-phase: live edges ordered by (src, dst, id); equal (src, dst) form a group
+        keys.clear();
+        for (int32_t e = 0; e < n_edges; ++e) if (E[e].live) keys.push_back({E[e].src, E[e].dst, e});
+        std::sort(keys.begin(), keys.end(), [](const Key& a, const Key& b) {
+            return a.src != b.src ? a.src < b.src : (a.dst != b.dst ? a.dst < b.dst : a.id < b.id);
+        });
+        for (size_t g0 = 0; g0 < keys.size();) {
+            size_t g1 = g0 + 1;
+            while (g1 < keys.size() && keys[g1].src == keys[g0].src && keys[g1].dst == keys[g0].dst) ++g1;
+            for (size_t z = g0 + 1; z < g1; ++z) {
+                plan.steps.push_back({1, -1, keys[g0].src, keys[g0].dst, keys[g0].id, keys[z].id, round});
+                E[keys[z].id].live = false;
                 ++plan.n_edge_steps;
                 worked = true;
             }
+            g0 = g1;
         }
         // N-phase
         for (int32_t v = 0; v < n_nodes; ++v) { n_in[v] = n_out[v] = 0; taken[v] = 0; }
@@ -70,7 +79,7 @@ lwp_status make_plan(int32_t n_nodes, int32_t n_edges, const int32_t* edges, int
             n_out[E[e].src]++; e_out[E[e].src] = e;
             n_in[E[e].dst]++;  e_in[E[e].dst] = e;
         }
-        std::vector<int32_t> chosen;
+        chosen.clear();
         for (int32_t j = 0; j < n_nodes; ++j) {
             if (gone[j] || n_in[j] != 1 || n_out[j] != 1) continue;
             int32_t i = E[e_in[j]].src, k = E[e_out[j]].dst;
