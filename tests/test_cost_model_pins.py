@@ -239,3 +239,39 @@ def test_search_on_ragged_tables_finds_the_same_strategy():
         assert u["cost"] == r["cost"]
         for l in range(len(layers)):
             assert tuple(full[u["strategy"][l]][:5]) == tuple(lists[l][r["strategy"][l]][:5])
+
+
+# ---- facts the paper prints (tests/golden/) ------------------------------------------------------
+def read_golden(name):
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", name)
+    return [l.split() for l in open(path).read().splitlines() if l.strip() and not l.startswith("#")]
+
+
+def test_enumeration_respects_the_papers_parallelizable_dimensions():
+    dims = {row[0].rstrip(":"): set(row[1:]) for row in read_golden("parallelizable_dimensions.txt")}
+    column = {"sample": 0, "height": 1, "width": 2, "channel": 3}
+    layers = {"fully_connected": fc(64, 64, 8, 64), "conv2d": conv(64, 64, 64, 64, 3, 1, 1), "pool2d": pool(64, 64, 64, 2, 2)}
+    for kind, layer in layers.items():
+        rows = oracle.enumerate_configs(layer, 16)
+        for name, col in column.items():
+            split = bool((rows[:, col] > 1).any())
+            assert split == (name in dims[kind]), (kind, name)
+
+
+def test_vgg16_strategy_agrees_with_the_papers_where_the_analytic_model_can():
+    groups = {row[0]: tuple(int(x) for x in row[1:]) for row in read_golden("vgg16_strategy_4gpus.txt")}
+    layers = wl.vgg16_layers(64)
+    m = wl.machine(n_devices=4)
+    lists = [oracle.enumerate_configs(l, 4) for l in layers]
+    Cn = np.array([len(x) for x in lists], np.int32)
+    edges = wl.chain_edges(len(layers))
+    tc, ts, tx = oracle.build_cost_tables_ragged(layers, edges, np.concatenate(lists), Cn, m)
+    S = oracle.search_ragged(len(layers), edges, Cn, tc, ts, tx)["strategy"]
+    chosen = [tuple(int(x) for x in lists[l][S[l]][:4]) for l in range(len(layers))]
+    blocks = {"conv_block_1": range(0, 3), "conv_block_2": range(3, 6), "conv_block_3": range(6, 10), "conv_block_4": range(10, 14)}
+    for name, ls in blocks.items():
+        assert all(chosen[l] == groups[name] for l in ls), name          # data parallelism on all 4 devices
+    for l, name in zip(range(18, 21), ("fc_1", "fc_2", "fc_3")):
+        n, h, w, c = chosen[l]
+        assert (n, h, w) == groups[name][:3] and 1 < c <= groups[name][3]   # channel split, no sample split

@@ -417,3 +417,25 @@ def test_resnet_shaped_graph_reduces_to_two_nodes_and_matches_enumeration():
         r = oracle.search(n, edges, 4, tc, ts, tx)
         live = {int(s["j"]) for s in r["steps"] if s["kind"] == 0}
         assert len(live) == n - 2                      # every node but two was eliminated
+
+
+def test_final_graph_sizes_the_paper_states():
+    import os
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "final_graph_sizes.txt")
+    rows = [l.split() for l in open(path).read().splitlines() if l.strip() and not l.startswith("#")]
+    graphs = {
+        "lenet5": (6, wl.chain_edges(6)), "alexnet": (len(wl.alexnet_layers(8)), wl.chain_edges(11)),
+        "vgg16": (len(wl.vgg16_layers(8)), wl.chain_edges(21)), "inception_v3": wl.forkjoin_edges(10, 2),
+        "resnet": wl.resnet_edges(bottleneck=True),
+    }
+    for name, n_layers, K in rows:
+        n, edges = graphs[name]
+        if n_layers != "-":
+            assert n == int(n_layers)
+        tc, ts, tx = wl.random_tables(n, edges, 2, 1, (0, 9), (0, 9), (0, 9))
+        for schedule in (wl.SCHEDULE_ROUNDS, wl.SCHEDULE_LEFT_FOLD):
+            steps = oracle.search(n, edges, 2, tc, ts, tx, schedule)["steps"]
+            eliminated = {int(s["j"]) for s in steps if s["kind"] == 0}
+            assert n - len(eliminated) == int(K)
+            # every elimination removes one edge and the final graph keeps one (Sec. 5.2, time complexity)
+            assert len(steps) == len(edges) - 1
