@@ -257,7 +257,9 @@ __global__ __launch_bounds__(kThreads) void single_min_kernel(const SingleDesc* 
 }
 
 // Enumeration of a residual component (Alg. 1: the final graph's strategies are enumerated).  One
-// thread per assignment of the first K-1 nodes; the last node's configurations are an inner loop.
+// thread per assignment of the first K-1 nodes (a "prefix", which fixes every term but those of the
+// last node); the last node's configurations are an inner loop.  Consecutive threads differ in the
+// later digits, so most of a wavefront reads the same table rows.
 // The flat (mixed-radix) index ascends lexicographically (lowest node id most significant), so the
 // 64-bit (cost, index) minimum is the lexicographically lowest optimum.
 __global__ __launch_bounds__(kThreads) void component_min_kernel(const CompDesc* __restrict__ comp,
@@ -265,10 +267,24 @@ __global__ __launch_bounds__(kThreads) void component_min_kernel(const CompDesc*
                                                                  unsigned long long* __restrict__ key,
                                                                  int32_t* __restrict__ flag) {
     __shared__ CompDesc d;
+    // edges sorted out once: those between earlier nodes, and those that touch the last node
+    __shared__ int n_inner, n_touch;
+    __shared__ int8_t inner[kCompMaxEdges], touch[kCompMaxEdges];
     for (int x = threadIdx.x; x < (int)(sizeof(CompDesc) / 4); x += kThreads)
         reinterpret_cast<int32_t*>(&d)[x] = reinterpret_cast<const int32_t*>(comp)[x];
     __syncthreads();
-    const int K = d.K, ne = d.n_edges, last = K - 1;
+    const int K = d.K, last = K - 1;
+    if (threadIdx.x == 0) {
+        int ni = 0, nt = 0;
+        for (int x = 0; x < d.n_edges; ++x) {
+            if (d.src_pos[x] == last || d.dst_pos[x] == last) touch[nt++] = (int8_t)x; else inner[ni++] = (int8_t)x;
+        }
+        n_inner = ni; n_touch = nt;
+    }
+    __syncthreads();
+    const int ni = n_inner, nt = n_touch;
+    const gi32c wl = (gi32c)(uintptr_t)d.w[last];
+    const int C = d.Cn[last];
     unsigned long long best = ~0ull;
     bool bad = false;
     const unsigned long long stride = (unsigned long long)gridDim.x * kThreads;
@@ -278,16 +294,30 @@ __global__ __launch_bounds__(kThreads) void component_min_kernel(const CompDesc*
         for (int q = last - 1; q >= 0; --q) { digit[q] = (int)(r % (unsigned)d.Cn[q]); r /= (unsigned)d.Cn[q]; }
         long long base = 0;
         for (int q = 0; q < last; ++q) base += ((gi32c)(uintptr_t)d.w[q])[digit[q]];
-        for (int x = 0; x < ne; ++x)
-            if (d.src_pos[x] != last && d.dst_pos[x] != last)
-                base += ((gi32c)(uintptr_t)d.tab[x])[(int64_t)digit[d.src_pos[x]] * d.Cn[d.dst_pos[x]] + digit[d.dst_pos[x]]];
-        const gi32c wl = (gi32c)(uintptr_t)d.w[last];
-        const int C = d.Cn[last];
+        for (int z = 0; z < ni; ++z) {
+            const int x = inner[z];
+            base += ((gi32c)(uintptr_t)d.tab[x])[(int64_t)digit[d.src_pos[x]] * d.Cn[d.dst_pos[x]] + digit[d.dst_pos[x]]];
+        }
+        // an edge that touches the last node contributes T[first + c * step]
+        constexpr int kFast = 4;
+        gi32c tp[kFast];
+        int64_t ts[kFast];
+        for (int z = 0; z < kFast; ++z) {
+            const int x = touch[z < nt ? z : 0];
+            const bool out_edge = d.src_pos[x] == last;      // the last node is the edge's source
+            tp[z] = (gi32c)(uintptr_t)d.tab[x] + (out_edge ? (int64_t)digit[d.dst_pos[x]] : (int64_t)digit[d.src_pos[x]] * C);
+            ts[z] = out_edge ? d.Cn[d.dst_pos[x]] : 1;
+        }
         for (int c = 0; c < C; ++c) {
             long long t = base + wl[c];
-            for (int x = 0; x < ne; ++x) {
-                if (d.src_pos[x] == last) t += ((gi32c)(uintptr_t)d.tab[x])[(int64_t)c * d.Cn[d.dst_pos[x]] + digit[d.dst_pos[x]]];
-                else if (d.dst_pos[x] == last) t += ((gi32c)(uintptr_t)d.tab[x])[(int64_t)digit[d.src_pos[x]] * C + c];
+#pragma unroll
+            for (int z = 0; z < kFast; ++z)
+                if (z < nt) t += tp[z][c * ts[z]];
+            for (int z = kFast; z < nt; ++z) {
+                const int x = touch[z];
+                const gi32c T = (gi32c)(uintptr_t)d.tab[x];
+                t += (d.src_pos[x] == last) ? T[(int64_t)c * d.Cn[d.dst_pos[x]] + digit[d.dst_pos[x]]]
+                                            : T[(int64_t)digit[d.src_pos[x]] * C + c];
             }
             bad |= (t != (long long)(int32_t)t);
             const unsigned long long k = make_key((int32_t)t, (uint32_t)(p * (unsigned)C + (unsigned)c));
