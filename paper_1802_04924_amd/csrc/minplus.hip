@@ -421,8 +421,8 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
     // earlier part keep ties -- and goes on to the epilogue.  The parts run on different compute
     // units, possibly different XCDs (separate L2s): the blocks are exchanged with device-scope
     // relaxed atomic stores and loads, which go through to memory, so no cache-wide write-back or
-    // invalidate is needed; a workgroup-scope release makes every thread's stores complete before
-    // the counter is bumped.
+    // invalidate is needed; every wavefront waits for its stores to complete before the barrier
+    // that precedes the bump of the counter.
     __builtin_amdgcn_s_setprio(3);
     bool raw = KEYED;                          // m1 still holds keys (otherwise plain costs)
     if (RB == 4 && kparts > 1) {
@@ -441,6 +441,11 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
                 __hip_atomic_store(&mine[(i * RB + j) * NT + tid], cst, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 if (!VALUE) __hip_atomic_store(&mine[(CELLS + i * RB + j) * NT + tid], (int32_t)rec[i][j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
+        // Every wavefront waits until its own stores have completed -- they are write-through to
+        // device scope, so completed means visible to every compute unit -- before the barrier
+        // after which the arrival is counted.  (A workgroup-scope release is not enough: it
+        // orders the stores for this compute unit only and need not wait for them.)
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         __syncthreads();
         __shared__ int arrived;

@@ -102,6 +102,22 @@ def test_eliminate_node_split_tiles_repeatedly(ctx):
             check_products(ctx, A, w, B)
 
 
+def test_split_tiles_never_read_a_previous_launchs_partials(ctx):
+    # the parts of a tile meet in scratch memory that every launch reuses: with fresh data per launch
+    # a part published too late (or read too early) would show as a result of the launch before
+    rng = np.random.default_rng(4242)
+    for rep in range(40):
+        for batch, Ci, Cj, Ck in ((1, 64, 2048, 64), (1, 512, 512, 512), (3, 100, 700, 90)):
+            A = rng.integers(0, 1 << 20, size=(batch, Ci, Cj), dtype=np.int32)
+            w = rng.integers(0, 1 << 20, size=(batch, Cj), dtype=np.int32)
+            B = rng.integers(0, 1 << 20, size=(batch, Cj, Ck), dtype=np.int32)
+            out, arg = ctx.eliminate_node(dev(A), dev(w), dev(B))
+            out, arg = out.cpu().numpy(), arg.cpu().numpy()
+            for b in range(batch):
+                ro, ra = oracle.minplus_argmin(A[b], w[b], B[b])
+                assert np.array_equal(out[b], ro) and np.array_equal(arg[b], ra), (rep, batch, Ci, Cj, Ck)
+
+
 def test_split_tiles_with_an_empty_part_and_costs_next_to_int32_max(ctx):
     # Cj = 257 is 9 stages of 32; split four ways (3 stages each) the last part has no candidates at
     # all and holds only padding.  With all costs just below INT32_MAX the padding must still lose.
