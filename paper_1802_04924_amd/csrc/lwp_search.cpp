@@ -302,7 +302,13 @@ void Search::bind(char* ws, char* pin) {
 }
 
 lwp_status Search::run(int32_t* out_cost, int32_t* out_strategy) {
-    if (stored_) {
+    // A small search is bound by latency, not arithmetic: reading the ranges back to pick the
+    // faster kernel variant costs more than the plain variant loses, so it is skipped and every
+    // elimination runs on the variant that needs no range (overflow is still found on the device).
+    int64_t updates = 0;
+    for (size_t q = 0; q < L_.node_A.size(); ++q) updates += (int64_t)L_.node_A[q].rows * L_.node_A[q].cols * L_.node_B[q].cols;
+    constexpr int64_t kReadBackPaysFrom = (int64_t)1 << 29;
+    if (stored_ && updates >= kReadBackPaysFrom) {
         if (lwp_status s = upload_offsets()) return s;
         if (lwp_status s = measure_inputs()) return s;
         if (lwp_status s = read_input_ranges()) return s;

@@ -383,6 +383,26 @@ def test_search_beyond_the_provable_bounds(ctx):
         run_search(ctx, p, schedule)
     p = wl.forkjoin_problem(3, 40, 4, lo=0, hi=1 << 25)
     run_search(ctx, p)
+    # the same above the size (2^29 cell updates) from which a search reads the value ranges back and
+    # picks packed-key variants: unprovable bounds then meet keys whose width comes from measured ranges
+    p = wl.chain_problem(40, 256, 5, tc_range=(0, 1 << 20), ts_range=(0, 1 << 20), tx_range=(0, 1 << 27))
+    for schedule in (wl.SCHEDULE_ROUNDS, wl.SCHEDULE_LEFT_FOLD):
+        run_search(ctx, p, schedule)
+
+
+def test_search_sizes_around_the_read_back_threshold(ctx):
+    # below 2^29 cell updates a search with stored argmin skips the read-back of value ranges and
+    # runs every elimination on the plain variant; from there on it reads them back and uses keys
+    for n_layers, C, expect_keys in ((5, 512, False), (6, 512, True)):       # 3 * 2^27 and 4 * 2^27 updates
+        p = wl.chain_problem(n_layers, C, n_layers, tc_range=(0, 1000), ts_range=(0, 1000), tx_range=(0, 1000))
+        ref = oracle.search(p["n_nodes"], p["edges"], C, p["tc"], p["ts"], p["tx"])
+        ctx.profile_enable(True)
+        ctx.profile_reset()
+        cost, S = ctx.search_graph(p["n_nodes"], p["edges"], C, dev(p["tc"]), dev(p["ts"]), dev(p["tx"]))
+        prof = ctx.profile_read()
+        ctx.profile_enable(False)
+        assert cost == ref["cost"] and np.array_equal(S, ref["strategy"])
+        assert (prof["keyed_launches"] == prof["node_launches"]) == expect_keys and (prof["keyed_launches"] > 0) == expect_keys
 
 
 def test_search_overflow_found_on_the_device(ctx):

@@ -45,6 +45,7 @@ def run_ragged(ctx, n_nodes, edges, Cn, seed, hi, schedules=(wl.SCHEDULE_ROUNDS,
     (40, 1, 3, 7),
 ])
 def test_ragged_chains(ctx, n_layers, c_min, c_max, hi):
+    # (searches below 2^29 cell updates: no read-back of value ranges, plain and value-only variants)
     Cn = wl.ragged_counts(n_layers, n_layers + c_max, c_min, c_max)
     run_ragged(ctx, n_layers, wl.chain_edges(n_layers), Cn, seed=n_layers, hi=hi)
 
@@ -239,3 +240,26 @@ def test_ragged_cost_tables_errors(ctx):
 def test_ragged_resnet_shaped(ctx, c_max, hi):
     n, edges = wl.resnet_edges(bottleneck=True)
     run_ragged(ctx, n, edges, wl.ragged_counts(n, c_max, 1, c_max), seed=c_max, hi=hi)
+
+
+@pytest.mark.parametrize("hi,t_c_scale", [(1000, 1), (1 << 20, 1), (1 << 20, 400)])
+def test_ragged_searches_large_enough_for_packed_keys(ctx, hi, t_c_scale):
+    # above 2^29 cell updates a search reads the value ranges back and launches of mixed shapes run
+    # on packed keys (global offsets, or re-based per row when node costs range widely)
+    Cn = wl.ragged_counts(10, 77, 350, 620)
+    edges = wl.chain_edges(10)
+    tc, ts, tx = wl.ragged_tables(10, edges, Cn, hi % 97, 0, hi)
+    tc = (tc.astype(np.int64) * t_c_scale).astype(np.int32)
+    from paper_1802_04924_amd import UNDO_STORED
+    for schedule in (wl.SCHEDULE_ROUNDS, wl.SCHEDULE_LEFT_FOLD):
+        ref = oracle.search_ragged(10, edges, Cn, tc, ts, tx, schedule)
+        ctx.profile_enable(True)
+        ctx.profile_reset()
+        cost, S = ctx.search_graph_ragged(10, edges, Cn, dev(tc), dev(ts), dev(tx), schedule, UNDO_STORED)
+        prof = ctx.profile_read()
+        ctx.profile_enable(False)
+        assert cost == ref["cost"] and np.array_equal(S, ref["strategy"])
+        assert prof["keyed_launches"] > 0
+    n, fj = wl.forkjoin_edges(2, 3)
+    Cn = wl.ragged_counts(n, 78, 250, 400)
+    run_ragged(ctx, n, fj, Cn, seed=3, hi=hi, schedules=(wl.SCHEDULE_ROUNDS,))
