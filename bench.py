@@ -242,6 +242,8 @@ def main():
     ms_per_step = dt / args.steps * 1e3
     value = updates / (dt / args.steps) / 1e9
 
+    # the int32 VALU rate the device sustains on the kernel's own two instructions, register-only
+    valu = ctx.measure_valu_rate()
     node_ms = prof["node_ms"] / max(prof["node_launches"], 1)
     upd_per_launch = prof["node_cell_updates"] / max(prof["node_launches"], 1)
     achieved = OPS_PER_UPDATE * upd_per_launch / (node_ms * 1e-3) / 1e12 if node_ms > 0 else 0.0
@@ -250,7 +252,10 @@ def main():
                 "traffic": PMC_TRAFFIC_BYTES_C4096 if (name == "cfg4" and C == 4096) else None,
                 "launches": prof["node_launches"], "avg_launch_ms": node_ms,
                 "cell_updates_per_launch": upd_per_launch, "keyed_launches": prof["keyed_launches"],
-                "kernel_cell_updates_per_s_G": upd_per_launch / (node_ms * 1e-3) / 1e9 if node_ms > 0 else 0.0}
+                "kernel_cell_updates_per_s_G": upd_per_launch / (node_ms * 1e-3) / 1e9 if node_ms > 0 else 0.0,
+                "measured_valu_lane_TOPs": valu["lane_ops_per_s"] / 1e12,
+                "measured_add_min3_cell_updates_per_s_G": valu["cell_updates_per_s"] / 1e9,
+                "frac_of_measured_add_min3": (upd_per_launch / (node_ms * 1e-3)) / valu["cell_updates_per_s"] if node_ms > 0 else 0.0}
 
     line = {"metric": "min-plus cell-updates/s over the whole strategy search", "value": value, "unit": "G cell-updates/s",
             "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,

@@ -25,7 +25,7 @@ EXPORTED = [
     "lwp_search_workspace_bytes", "lwp_search_graph_ex", "lwp_search_workspace_bytes_ex",
     "lwp_search_graph_ragged", "lwp_search_workspace_bytes_ragged", "lwp_build_cost_tables",
     "lwp_build_cost_tables_ragged", "lwp_enumerate_configs",
-    "lwp_search_plan_create", "lwp_search_plan_run", "lwp_search_plan_destroy",
+    "lwp_search_plan_create", "lwp_search_plan_run", "lwp_search_plan_destroy", "lwp_measure_valu_rate",
     "lwp_profile_enable", "lwp_profile_reset", "lwp_profile_read",
 ]
 
@@ -90,6 +90,7 @@ def load():
     lib.lwp_search_plan_run.argtypes = [vp, i32p, vp]
     lib.lwp_search_plan_destroy.argtypes = [vp]
     lib.lwp_search_plan_destroy.restype = None
+    lib.lwp_measure_valu_rate.argtypes = [vp, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
     lib.lwp_profile_enable.argtypes = [vp, i32]
     lib.lwp_profile_reset.argtypes = [vp]
     lib.lwp_profile_read.argtypes = [vp, ctypes.POINTER(Profile)]
@@ -360,6 +361,12 @@ class Context:
         return tc, ts, tx
 
     # ---- measurement -------------------------------------------------------
+    def measure_valu_rate(self):
+        """Register-only add + three-way-min loop: dict(lane_ops_per_s, cell_updates_per_s) the device sustains."""
+        lane, upd = ctypes.c_double(0), ctypes.c_double(0)
+        self._check(self._lib.lwp_measure_valu_rate(self._h, ctypes.byref(lane), ctypes.byref(upd)), "measure_valu_rate")
+        return {"lane_ops_per_s": lane.value, "cell_updates_per_s": upd.value}
+
     def profile_enable(self, on=True):
         self._check(self._lib.lwp_profile_enable(self._h, 1 if on else 0), "profile_enable")
 

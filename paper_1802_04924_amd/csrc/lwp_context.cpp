@@ -145,6 +145,38 @@ lwp_status lwp_synchronize(lwp_ctx* ctx) {
     return LWP_OK;
 }
 
+lwp_status lwp_measure_valu_rate(lwp_ctx* ctx, double* lane_ops_per_s, double* cell_updates_per_s) {
+    if (lwp_status s = check_ctx(ctx)) return s;
+    if (!lane_ops_per_s || !cell_updates_per_s) return fail(ctx, LWP_E_INVAL, "null output");
+    if (lwp_status s = ensure_workspace(ctx, 4096)) return s;
+    hipDeviceProp_t prop;
+    LWP_HIP(ctx, hipGetDeviceProperties(&prop, ctx->device));
+    const int blocks = prop.multiProcessorCount * 8;        // 8 wavefronts per SIMD
+    const int iters = 4000;
+    uint32_t* d_out = reinterpret_cast<uint32_t*>(ctx->ws);
+    hipEvent_t a = nullptr, b = nullptr;
+    LWP_HIP(ctx, hipEventCreate(&a));
+    hipError_t e = hipEventCreate(&b);
+    if (e != hipSuccess) { (void)hipEventDestroy(a); return fail(ctx, LWP_E_HIP, std::string("hipEventCreate: ") + hipGetErrorString(e)); }
+    float best_ms = 0.f;
+    hipError_t err = hipSuccess;
+    for (int rep = 0; rep < 3 && err == hipSuccess; ++rep) {     // first pass warms up; keep the fastest
+        err = hipEventRecord(a, ctx->stream);
+        if (err == hipSuccess) err = launch_alu_probe(d_out, blocks, iters, ctx->stream);
+        if (err == hipSuccess) err = hipEventRecord(b, ctx->stream);
+        if (err == hipSuccess) err = hipEventSynchronize(b);
+        float ms = 0.f;
+        if (err == hipSuccess) err = hipEventElapsedTime(&ms, a, b);
+        if (err == hipSuccess && rep > 0 && (best_ms == 0.f || ms < best_ms)) best_ms = ms;
+    }
+    (void)hipEventDestroy(a); (void)hipEventDestroy(b);
+    if (err != hipSuccess) { (void)hipGetLastError(); return fail(ctx, LWP_E_HIP, std::string("VALU probe: ") + hipGetErrorString(err)); }
+    const double threads = (double)blocks * kNodeThreads, sec = best_ms * 1e-3;
+    *lane_ops_per_s = threads * iters * alu_probe_instr_per_iter() / sec;
+    *cell_updates_per_s = threads * iters * alu_probe_updates_per_iter() / sec;
+    return LWP_OK;
+}
+
 lwp_status lwp_profile_enable(lwp_ctx* ctx, int32_t on) {
     if (lwp_status s = check_ctx(ctx)) return s;
     ctx->profiling = on != 0;

@@ -162,4 +162,13 @@ hipError_t launch_back_substitute(const PairDesc* d_pairs, int32_t n_pairs, cons
                                   const int32_t* d_flag, const int32_t* d_wstats, int32_t* d_result,
                                   hipStream_t stream);
 
+// ---- VALU issue-rate probe ---------------------------------------------------------------------
+// `blocks` workgroups of 256 threads each run `iters` iterations of a register-only add + three-way
+// min loop; per iteration and thread alu_probe_instr_per_iter() VALU instructions that perform the
+// arithmetic of alu_probe_updates_per_iter() cell updates.  d_out: one uint32 (never written in
+// practice).
+hipError_t launch_alu_probe(uint32_t* d_out, int blocks, int iters, hipStream_t stream);
+int alu_probe_instr_per_iter();
+int alu_probe_updates_per_iter();
+
 }  // namespace lwp

@@ -403,6 +403,37 @@ __global__ __launch_bounds__(kUndoThreads) void back_substitute_kernel(
     if (threadIdx.x == 0) result[2 + n_nodes] = (flag ? *flag : 0) | wbad;
 }
 
+// ---- VALU issue-rate probe ----------------------------------------------------------------------
+// Register-only chains of the inner loop's two instructions (32-bit add, three-way unsigned min) on
+// 32 independent accumulators per thread: measures the int32 VALU rate the chip sustains, against
+// which the min-plus kernel's rate is read.  Per loop iteration and thread: 64 adds (all 8 x 8 sums
+// of two operand sets) + 32 min3 -- the arithmetic of 64 cell updates -- + the few instructions
+// that keep the operands changing.
+constexpr int kProbeInstrPerIter = 64 + 32 + 7;   // as compiled: the operand updates reuse 8 of the sums, 7 moves remain
+constexpr int kProbeUpdatesPerIter = 64;
+__global__ __launch_bounds__(kThreads) void alu_probe_kernel(uint32_t* __restrict__ out, int iters, uint32_t seed) {
+    uint32_t m[32], a[8], b[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) { a[q] = seed + threadIdx.x * 7u + q; b[q] = seed * 3u + blockIdx.x + 11u * q; }
+#pragma unroll
+    for (int j = 0; j < 32; ++j) m[j] = 0xffffffffu;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < 32; ++j) {
+            const int p0 = 2 * j, p1 = 2 * j + 1;            // two of the 64 (a, b) pairs
+            m[j] = min(min(m[j], a[p0 & 7] + b[p0 >> 3]), a[p1 & 7] + b[p1 >> 3]);
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) a[q] += b[q];
+#pragma unroll
+        for (int j = 0; j < 32; j += 4) asm volatile("" : "+v"(m[j]), "+v"(m[j + 1]), "+v"(m[j + 2]), "+v"(m[j + 3]));
+    }
+    uint32_t r = 0;
+#pragma unroll
+    for (int j = 0; j < 32; ++j) r ^= m[j];
+    if (r == 0x12345u) out[0] = r;        // never true in practice; keeps the chains alive
+}
+
 inline unsigned blocks_for(int64_t work_items, int64_t per_thread, unsigned cap) {
     int64_t b = (work_items + (int64_t)kThreads * per_thread - 1) / ((int64_t)kThreads * per_thread);
     if (b < 1) b = 1;
@@ -501,6 +532,13 @@ hipError_t launch_component_min(const CompDesc* d_comp, unsigned long long n_pre
     hipLaunchKernelGGL(component_min_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, d_comp, n_prefix, d_key, d_flag);
     return hipGetLastError();
 }
+
+hipError_t launch_alu_probe(uint32_t* d_out, int blocks, int iters, hipStream_t stream) {
+    hipLaunchKernelGGL(alu_probe_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, d_out, iters, 12345u);
+    return hipGetLastError();
+}
+int alu_probe_instr_per_iter() { return kProbeInstrPerIter; }
+int alu_probe_updates_per_iter() { return kProbeUpdatesPerIter; }
 
 hipError_t launch_back_substitute(const PairDesc* d_pairs, int32_t n_pairs, const SingleDesc* d_singles,
                                   int32_t n_singles, const CompDesc* d_comps, int32_t n_comps,
