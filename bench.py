@@ -26,7 +26,7 @@ PEAK_INT32_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 OPS_PER_UPDATE = 2
 # L2<->fabric bytes of one 4096^3 min-plus launch from the rocprofv3 --pmc passes (FETCH_SIZE and
 # WRITE_SIZE, each scaled by a 1 GiB reference copy): profiles/minplus_kernel_C4096_pmc.txt.
-PMC_TRAFFIC_BYTES_C4096 = 1_775_344_642
+PMC_TRAFFIC_BYTES_C4096 = 1_775_358_427
 
 
 def log(*a):
