@@ -172,7 +172,7 @@ static void sort_ids(int *ids, int n, const live_edge *E)
  *
  * Each connected component of the residual graph is minimised on its own (a
  * node, a pair joined by one edge, or enumeration of all C^K strategies of a
- * larger component, K <= 16 and C^K <= 2^26 here).  The eliminations are then
+ * larger component, K <= 16 and at most 2^32 strategies here).  The eliminations are then
  * undone in reverse order:
  * S[j] = arg_j[S[i]][S[k]].
  *
@@ -312,29 +312,58 @@ int orc_search_ragged(int n_nodes, int n_edges, const int32_t *edges, const int3
                 if (r != ORC_OK) { rc = r; goto done; }
                 S[E[e].src] = a; S[E[e].dst] = b;
             } else {
-                double n_assign = 1.0;
-                for (int q = 0; q < K && q < 16; ++q) n_assign *= Cn[ine[q]];
-                if (n_assign > (double)(1 << 26) || K > 16) { rc = ORC_E_NOT_REDUCIBLE; goto done; }
-                int digit[16], bestd[16], pos_of_src[64], pos_of_dst[64];
-                if (ne > 64) { rc = ORC_E_NOT_REDUCIBLE; goto done; }
+                /* number of strategies of the component, counted in 64 bits */
+                uint64_t n_assign = 1;
+                if (K > 16 || ne > 64) { rc = ORC_E_NOT_REDUCIBLE; goto done; }
+                for (int q = 0; q < K; ++q) {
+                    n_assign *= (uint64_t)Cn[ine[q]];
+                    if (n_assign > ((uint64_t)1 << 32)) { rc = ORC_E_NOT_REDUCIBLE; goto done; }
+                }
+                int bestd[16], pos_of_src[64], pos_of_dst[64];
                 for (int x = 0; x < ne; ++x)
                     for (int q = 0; q < K; ++q) {
                         if (ine[q] == E[oute[x]].src) pos_of_src[x] = q;
                         if (ine[q] == E[oute[x]].dst) pos_of_dst[x] = q;
                     }
-                for (int q = 0; q < K; ++q) digit[q] = 0;
-                int have = 0;
-                for (;;) {
-                    int64_t t = 0;
-                    for (int q = 0; q < K; ++q) t += w[woff[ine[q]] + digit[q]];
-                    for (int x = 0; x < ne; ++x)
-                        t += E[oute[x]].tab[(size_t)digit[pos_of_src[x]] * Cn[E[oute[x]].dst] + digit[pos_of_dst[x]]];
-                    if (!fits_i32(t)) { rc = ORC_E_OVERFLOW; goto done; }
-                    if (!have || t < c) { c = t; have = 1; for (int q = 0; q < K; ++q) bestd[q] = digit[q]; }
-                    int q = K - 1;                               /* odometer: last node fastest */
-                    while (q >= 0 && ++digit[q] == Cn[ine[q]]) digit[q--] = 0;
-                    if (q < 0) break;
+                /* The configurations of the component's first node are independent slices of the
+                 * enumeration: each slice keeps its own first optimum (threads share the slices),
+                 * and the slices are then compared in ascending order with strict '<', which is
+                 * the order one odometer over all K digits would visit them in. */
+                int C0 = Cn[ine[0]];
+                int64_t *slice_cost = (int64_t *)malloc(sizeof(int64_t) * (size_t)C0);
+                int32_t *slice_digits = (int32_t *)malloc(sizeof(int32_t) * 16 * (size_t)C0);
+                if (!slice_cost || !slice_digits) { free(slice_cost); free(slice_digits); rc = ORC_E_NOMEM; goto done; }
+                int overflow = 0;
+#pragma omp parallel for schedule(dynamic) reduction(| : overflow)
+                for (int d0 = 0; d0 < C0; ++d0) {
+                    int digit[16];
+                    int64_t bc = 0;
+                    int have = 0;
+                    digit[0] = d0;
+                    for (int q = 1; q < K; ++q) digit[q] = 0;
+                    for (;;) {
+                        int64_t t = 0;
+                        for (int q = 0; q < K; ++q) t += w[woff[ine[q]] + digit[q]];
+                        for (int x = 0; x < ne; ++x)
+                            t += E[oute[x]].tab[(size_t)digit[pos_of_src[x]] * Cn[E[oute[x]].dst] + digit[pos_of_dst[x]]];
+                        if (!fits_i32(t)) overflow = 1;
+                        if (!have || t < bc) {
+                            bc = t; have = 1;
+                            for (int q = 0; q < K; ++q) slice_digits[(size_t)d0 * 16 + q] = digit[q];
+                        }
+                        int q = K - 1;                           /* odometer: last node fastest */
+                        while (q >= 1 && ++digit[q] == Cn[ine[q]]) digit[q--] = 0;
+                        if (q < 1) break;
+                    }
+                    slice_cost[d0] = bc;
                 }
+                for (int d0 = 0; d0 < C0; ++d0)
+                    if (d0 == 0 || slice_cost[d0] < c) {
+                        c = slice_cost[d0];
+                        for (int q = 0; q < K; ++q) bestd[q] = slice_digits[(size_t)d0 * 16 + q];
+                    }
+                free(slice_cost); free(slice_digits);
+                if (overflow) { rc = ORC_E_OVERFLOW; goto done; }
                 for (int q = 0; q < K; ++q) S[ine[q]] = bestd[q];
             }
             total += c;

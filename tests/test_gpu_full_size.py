@@ -84,7 +84,7 @@ def test_config4_full(ctx):
     w_all = (tc + ts).astype(np.int32)
     d_w = dev(w_all)
     T = d_tx[0]
-    args = []
+    args, lefts = [], []
     for j in range(1, N - 1):
         Bj = d_tx[j]
         out, arg = ctx.eliminate_node(T[None], d_w[j][None], Bj[None])
@@ -100,12 +100,19 @@ def test_config4_full(ctx):
             ro, ra = oracle.minplus_argmin(T.cpu().numpy(), w_all[j], Bj.cpu().numpy())
             assert np.array_equal(out.cpu().numpy(), ro) and np.array_equal(arg.cpu().numpy(), ra)
         args.append(arg)
+        lefts.append(T)                                              # table of the edge (0, j) when node j went
         T = out
-    # residual pair (0, N-1) and the undo pass on the host, from the GPU's tables
+    # residual pair (0, N-1) and the undo pass on the host: the configuration of node j is recomputed
+    # from the VALUE tables as the lowest minimiser of Eq. 2 at the already fixed (c_0, c_{j+1}) -- the
+    # argmin tables of the GPU are not consulted, only compared at the 62 cells the undo pass reads
     c2, a, b = oracle.final_pair(w_all[0], T.cpu().numpy(), w_all[N - 1])
     assert c2 == cost
     S2 = np.zeros(N, np.int32)
     S2[0], S2[N - 1] = a, b
     for j in range(N - 2, 0, -1):                                    # reverse order; node j sat between 0 and j+1
-        S2[j] = int(args[j - 1][int(S2[0]), int(S2[j + 1])])
+        left = lefts[j - 1][int(S2[0])].cpu().numpy().astype(np.int64)             # t_x'(0, j)[c_0][.]
+        right = d_tx[j][:, int(S2[j + 1])].cpu().numpy().astype(np.int64)          # t_x(j, j+1)[.][c_{j+1}]
+        S2[j] = int(np.argmin(left + w_all[j].astype(np.int64) + right))           # first occurrence = lowest index
+        assert int(args[j - 1][int(S2[0]), int(S2[j + 1])]) == S2[j], f"stored argmin of node {j} at the cell the undo pass reads"
     assert np.array_equal(S, S2)
+    assert np.array_equal(S_r, S2)

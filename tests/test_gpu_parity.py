@@ -292,7 +292,7 @@ def test_search_random_series_parallel(ctx, seed):
     p = wl.series_parallel_problem(30 + 7 * seed, C, seed, hi=[2, 1000, 1 << 20][seed % 3], p_branch=0.08 if seed % 2 else 0.0)
     from paper_1802_04924_amd import plan_graph
     K = plan_graph(p["n_nodes"], p["edges"])["n_residual_nodes"]
-    if K > 2 and C ** K > (1 << 26):              # more strategies than the oracle enumerates
+    if K > 2 and C ** K > (1 << 32):              # possibly more strategies than either side enumerates
         p = wl.series_parallel_problem(30 + 7 * seed, 3, seed, hi=5, p_branch=0.08)
     for schedule in (wl.SCHEDULE_ROUNDS, wl.SCHEDULE_LEFT_FOLD):
         run_search(ctx, p, schedule)
@@ -364,15 +364,36 @@ IRREDUCIBLE = {
 @pytest.mark.parametrize("name", sorted(IRREDUCIBLE))
 @pytest.mark.parametrize("C,hi", [(1, 7), (2, 1), (5, 3), (23, 1000), (64, 1 << 20)])
 def test_search_enumerates_residual_components(ctx, name, C, hi):
-    from paper_1802_04924_amd import plan_graph
+    # the largest component here has 5 nodes: at most 64^5 = 2^30 strategies, which both sides enumerate
     n, e = IRREDUCIBLE[name]
     edges = np.asarray(e, np.int32)
-    if C ** plan_graph(n, edges)["n_residual_nodes"] > (1 << 26):
-        pytest.skip("more strategies than the oracle enumerates")
     for schedule in (wl.SCHEDULE_ROUNDS, wl.SCHEDULE_LEFT_FOLD):
         tc, ts, tx = wl.random_tables(n, edges, C, C + hi, (0, hi), (0, hi), (0, hi))
         p = {"n_nodes": n, "edges": edges, "C": C, "tc": tc, "ts": ts, "tx": tx, "schedule": schedule}
         run_search(ctx, p)
+
+
+@pytest.mark.parametrize("C,hi", [(160, 1 << 20), (250, 1 << 20), (256, 3)])
+def test_search_enumerates_up_to_2_pow_32_strategies(ctx, C, hi):
+    # a layer feeding three layers that never rejoin: nothing can be eliminated and all C^4 strategies
+    # of the final graph are enumerated (Alg. 1).  160^4 = 6.6e8 is the size the benchmark's residual
+    # workload times, 250^4 = 3.9e9 lies just under the limit of 2^32, 256^4 is the limit itself (the
+    # flat strategy index then uses all 32 bits; small costs make ties that only the index resolves)
+    edges = np.array([[0, 1], [0, 2], [0, 3]], np.int32)
+    tc, ts, tx = wl.random_tables(4, edges, C, 7, (0, hi), (0, hi), (0, hi))
+    run_search(ctx, {"n_nodes": 4, "edges": edges, "C": C, "tc": tc, "ts": ts, "tx": tx, "schedule": wl.SCHEDULE_ROUNDS})
+
+
+def test_search_refuses_more_than_2_pow_32_strategies(ctx):
+    from paper_1802_04924_amd import LwpError
+    edges = np.array([[0, 1], [0, 2], [0, 3]], np.int32)
+    tc, ts, tx = wl.random_tables(4, edges, 257, 7, (0, 9), (0, 9), (0, 9))
+    with pytest.raises(LwpError) as e:
+        ctx.search_graph(4, edges, 257, dev(tc), dev(ts), dev(tx))
+    assert e.value.code == -3
+    with pytest.raises(oracle.OracleError) as e2:
+        oracle.search(4, edges, 257, tc, ts, tx)
+    assert e2.value.code == oracle.E_NOT_REDUCIBLE
 
 
 def test_search_beyond_the_provable_bounds(ctx):
