@@ -16,10 +16,12 @@
  *   - A cost table of an edge e = (l_i, l_j) is row-major [cfg of l_i][cfg of l_j].
  *   - "DEVICE" pointers are HIP device memory on the context's device, owned by the caller;
  *     the library never frees or keeps them.  "HOST" pointers are ordinary host memory.
- *   - Every kernel is enqueued on the context's stream.  lwp_eliminate_edge only enqueues;
- *     lwp_eliminate_node synchronises once (it reads back value ranges before it picks a
- *     kernel variant) and then enqueues; lwp_search_graph and lwp_build_cost_tables return
- *     after the stream has drained.
+ *   - Every kernel is enqueued on the context's stream.  lwp_eliminate_node, _node_bounded and
+ *     lwp_eliminate_edge only enqueue and return (the first call of a size may grow a buffer of
+ *     the context, which waits for the stream once); what their kernels find on the device -- a
+ *     sum that may leave int32, a value outside promised ranges -- is reported by the next
+ *     lwp_synchronize.  lwp_search_graph and lwp_build_cost_tables return after the stream has
+ *     drained.
  *   - Errors are return codes; on error the outputs are untouched unless stated.  Argument
  *     and graph validation happen before any GPU work.  lwp_last_error gives the reason.
  *   - A context must not be used from two threads at once.
@@ -64,7 +66,11 @@ void lwp_destroy(lwp_ctx *ctx);
 /* Human-readable reason of the last failure on ctx; valid until the next call on ctx. */
 const char *lwp_last_error(const lwp_ctx *ctx);
 const char *lwp_status_string(lwp_status s);
-/* Blocks until the context's stream has drained. */
+/* Blocks until the context's stream has drained, then reports what the kernels of
+ * lwp_eliminate_node, lwp_eliminate_node_bounded and lwp_eliminate_edge enqueued since the last
+ * lwp_synchronize found: LWP_E_OVERFLOW if a sum of one of them may have left int32,
+ * LWP_E_INVAL if one met a value outside the ranges its caller promised; the outputs of such
+ * an elimination are invalid.  The record is cleared by the call. */
 lwp_status lwp_synchronize(lwp_ctx *ctx);
 
 /* ---- node elimination (Sec. 5.2, Eq. 2; argmin of Thm. 3 in the appendix) ---------------- */
@@ -75,17 +81,29 @@ lwp_status lwp_synchronize(lwp_ctx *ctx);
  * DEVICE, dense, row-major: A [batch][Ci][Cj], w [batch][Cj], B [batch][Cj][Ck],
  * out [batch][Ci][Ck], argmin [batch][Ci][Ck] (may be NULL: then only the minimum is computed,
  * by a variant without argmin bookkeeping).  out/argmin must not overlap the inputs.  Sizes: batch, Ci, Cj, Ck >= 1, Cj <= 65536.
- * The call measures the value ranges of A, w, B on the device (one small synchronising
- * read-back), returns LWP_E_OVERFLOW if max A + max w + max B (or the minima) could leave
- * int32, then enqueues the product kernel and returns. */
+ * Enqueues and returns.  Nothing is assumed about the values: one pass measures the value ranges
+ * of A, w and B of every product on the device, and the product kernels pick their arithmetic
+ * variant per product from those ranges, also on the device.  If max A + max w + max B (or the
+ * minima) of a product could leave int32 the next lwp_synchronize returns LWP_E_OVERFLOW. */
 lwp_status lwp_eliminate_node(lwp_ctx *ctx, int32_t batch, int32_t Ci, int32_t Cj, int32_t Ck,
                               const int32_t *d_A, const int32_t *d_w, const int32_t *d_B,
                               int32_t *d_out, int32_t *d_argmin);
 
+/* The same for a caller that knows ranges of the values (cost tables come out of a cost model with
+ * known bounds, Sec. 5.1): bounds HOST [6] = {lo A, hi A, lo w, hi w, lo B, hi B}, inclusive, valid
+ * for every product.  The measuring pass is skipped and the host picks the kernel variant, so the
+ * call costs one launch.  Returns LWP_E_OVERFLOW at once if hi A + hi w + hi B (or the minima)
+ * leaves int32.  The kernel checks every element it reads against the promise; a violation makes
+ * the outputs invalid and the next lwp_synchronize return LWP_E_INVAL. */
+lwp_status lwp_eliminate_node_bounded(lwp_ctx *ctx, int32_t batch, int32_t Ci, int32_t Cj, int32_t Ck,
+                                      const int32_t *d_A, const int32_t *d_w, const int32_t *d_B,
+                                      int32_t *d_out, int32_t *d_argmin, const int32_t *bounds);
+
 /* ---- edge elimination (Sec. 5.2, Eq. 3) -------------------------------------------------- */
 
-/* out[b][i][j] = e1[b][i][j] + e2[b][i][j] (wrapping int32 add; the caller guarantees the
- * range).  DEVICE, dense [batch][Ci][Cj]; out may alias e1 or e2.  Enqueues and returns. */
+/* out[b][i][j] = e1[b][i][j] + e2[b][i][j].  DEVICE, dense [batch][Ci][Cj]; out may alias e1 or
+ * e2.  Enqueues and returns; if a sum leaves int32 (the wrapped value is stored) the next
+ * lwp_synchronize returns LWP_E_OVERFLOW. */
 lwp_status lwp_eliminate_edge(lwp_ctx *ctx, int32_t batch, int32_t Ci, int32_t Cj,
                               const int32_t *d_e1, const int32_t *d_e2, int32_t *d_out);
 
@@ -241,7 +259,12 @@ typedef struct {
     int64_t edge_launches;
     int64_t edge_cells;
     double edge_ms;
-    int64_t keyed_launches;    /* node launches that used the packed-key variant   */
+    int64_t keyed_launches;    /* node launches that used the packed-key variant (whole searches and
+                                  lwp_eliminate_node_bounded, where the host picks the variant)      */
+    /* products of lwp_eliminate_node(_bounded) per kernel variant since the last reset (the variant
+     * of lwp_eliminate_node is picked on the device, per product): packed keys on global offsets,
+     * packed keys re-based per row, compare/select, minimum only */
+    int64_t products_keyed, products_keyed_row, products_plain, products_value;
 } lwp_profile;
 /* Runs a register-only loop of the min-plus kernel's two inner instructions (32-bit add, three-way
  * unsigned min; no memory traffic) on every compute unit and reports the rate the device

@@ -21,7 +21,7 @@ UNDO_STORED, UNDO_RECOMPUTE = 0, 1
 
 EXPORTED = [
     "lwp_create", "lwp_destroy", "lwp_last_error", "lwp_status_string", "lwp_synchronize",
-    "lwp_eliminate_node", "lwp_eliminate_edge", "lwp_plan_graph", "lwp_search_graph",
+    "lwp_eliminate_node", "lwp_eliminate_node_bounded", "lwp_eliminate_edge", "lwp_plan_graph", "lwp_search_graph",
     "lwp_search_workspace_bytes", "lwp_search_graph_ex", "lwp_search_workspace_bytes_ex",
     "lwp_search_graph_ragged", "lwp_search_workspace_bytes_ragged", "lwp_build_cost_tables",
     "lwp_build_cost_tables_ragged", "lwp_enumerate_configs",
@@ -41,7 +41,9 @@ class Profile(ctypes.Structure):
     _fields_ = [("node_launches", ctypes.c_int64), ("node_cell_updates", ctypes.c_int64),
                 ("node_ms", ctypes.c_double), ("edge_launches", ctypes.c_int64),
                 ("edge_cells", ctypes.c_int64), ("edge_ms", ctypes.c_double),
-                ("keyed_launches", ctypes.c_int64)]
+                ("keyed_launches", ctypes.c_int64), ("products_keyed", ctypes.c_int64),
+                ("products_keyed_row", ctypes.c_int64), ("products_plain", ctypes.c_int64),
+                ("products_value", ctypes.c_int64)]
 
 
 class LwpError(RuntimeError):
@@ -72,6 +74,7 @@ def load():
     lib.lwp_status_string.restype = ctypes.c_char_p
     lib.lwp_synchronize.argtypes = [vp]
     lib.lwp_eliminate_node.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp, vp]
+    lib.lwp_eliminate_node_bounded.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp]
     lib.lwp_eliminate_edge.argtypes = [vp, i32, i32, i32, vp, vp, vp]
     lib.lwp_plan_graph.argtypes = [i32, i32, vp, i32, vp, i32p, i32p, i32p]
     lib.lwp_search_graph.argtypes = [vp, i32, i32, vp, i32, vp, vp, vp, i32, i32p, vp]
@@ -239,8 +242,11 @@ class Context:
         self._check(self._lib.lwp_synchronize(self._h), "synchronize")
 
     # ---- Eq. 2 -------------------------------------------------------------
-    def eliminate_node(self, A, w, B, out=None, argmin=None, want_argmin=True):
-        """A [batch][Ci][Cj], w [batch][Cj], B [batch][Cj][Ck] -> (out, argmin) [batch][Ci][Ck]."""
+    def eliminate_node(self, A, w, B, out=None, argmin=None, want_argmin=True, bounds=None):
+        """A [batch][Ci][Cj], w [batch][Cj], B [batch][Cj][Ck] -> (out, argmin) [batch][Ci][Ck].
+
+        Only enqueues; synchronize() reports what the kernels found (overflow, broken promise).
+        bounds: optional (lo A, hi A, lo w, hi w, lo B, hi B) the caller promises for the values."""
         import torch
         if A.dim() == 2:
             A, w, B = A[None], w[None], B[None]
@@ -252,8 +258,14 @@ class Context:
             out = torch.empty((batch, Ci, Ck), dtype=torch.int32, device=A.device)
         if argmin is None and want_argmin:
             argmin = torch.empty((batch, Ci, Ck), dtype=torch.int32, device=A.device)
-        rc = self._lib.lwp_eliminate_node(self._h, batch, Ci, Cj, Ck, _dev(A, "A"), _dev(w, "w"), _dev(B, "B"),
-                                          _dev(out, "out"), _dev(argmin, "argmin") if argmin is not None else None)
+        if bounds is None:
+            rc = self._lib.lwp_eliminate_node(self._h, batch, Ci, Cj, Ck, _dev(A, "A"), _dev(w, "w"), _dev(B, "B"),
+                                              _dev(out, "out"), _dev(argmin, "argmin") if argmin is not None else None)
+        else:
+            b = _np_i32(bounds, (6,))
+            rc = self._lib.lwp_eliminate_node_bounded(self._h, batch, Ci, Cj, Ck, _dev(A, "A"), _dev(w, "w"), _dev(B, "B"),
+                                                      _dev(out, "out"), _dev(argmin, "argmin") if argmin is not None else None,
+                                                      b.ctypes.data)
         self._check(rc, "eliminate_node")
         return out, argmin
 

@@ -59,6 +59,16 @@ lwp_status ensure_split_buffers(lwp_ctx* ctx) {
     return LWP_OK;
 }
 
+lwp_status ensure_state(lwp_ctx* ctx) {
+    if (ctx->dstate) return LWP_OK;
+    void* p = nullptr;
+    hipError_t e = hipMalloc(&p, 256);
+    if (e != hipSuccess) { (void)hipGetLastError(); return fail(ctx, LWP_E_NOMEM, std::string("device state words: ") + hipGetErrorString(e)); }
+    ctx->dstate = static_cast<int32_t*>(p);
+    LWP_HIP(ctx, hipMemsetAsync(ctx->dstate, 0, 256, ctx->stream));
+    return ensure_pinned(ctx, 4096);       // lwp_synchronize reads the error bits back through it
+}
+
 void set_split(lwp_ctx* ctx, NodeArgs& a, int kparts) {
     a.kparts = kparts;
     a.scratch = kparts > 1 ? ctx->split : nullptr;
@@ -134,6 +144,7 @@ void lwp_destroy(lwp_ctx* ctx) {
     if (ctx->ws) (void)hipFree(ctx->ws);
     if (ctx->pin) (void)hipHostFree(ctx->pin);
     if (ctx->split) (void)hipFree(ctx->split);
+    if (ctx->dstate) (void)hipFree(ctx->dstate);
     delete ctx;
 }
 
@@ -141,8 +152,21 @@ const char* lwp_last_error(const lwp_ctx* ctx) { return ctx ? ctx->err.c_str() :
 
 lwp_status lwp_synchronize(lwp_ctx* ctx) {
     if (lwp_status s = check_ctx(ctx)) return s;
+    if (!ctx->dstate) {
+        LWP_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        return LWP_OK;
+    }
+    // what the kernels of lwp_eliminate_node / _edge found since the last call: the word is copied
+    // behind them on the stream into pinned memory, so one wait covers both
+    int32_t* bits_p = reinterpret_cast<int32_t*>(ctx->pin);
+    LWP_HIP(ctx, hipMemcpyAsync(bits_p, ctx->dstate, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
     LWP_HIP(ctx, hipStreamSynchronize(ctx->stream));
-    return LWP_OK;
+    const int32_t bits = *bits_p;
+    if (!bits) return LWP_OK;
+    LWP_HIP(ctx, hipMemsetAsync(ctx->dstate, 0, sizeof(int32_t), ctx->stream));
+    LWP_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    if (bits & 2) return fail(ctx, LWP_E_INVAL, "an elimination met values outside the ranges its caller promised; its results are invalid");
+    return fail(ctx, LWP_E_OVERFLOW, "a sum of an elimination enqueued since the last lwp_synchronize may leave int32; its results are invalid");
 }
 
 lwp_status lwp_measure_valu_rate(lwp_ctx* ctx, double* lane_ops_per_s, double* cell_updates_per_s) {
@@ -187,6 +211,10 @@ lwp_status lwp_profile_reset(lwp_ctx* ctx) {
     if (lwp_status s = check_ctx(ctx)) return s;
     if (lwp_status s = drain_profile(ctx)) return s;
     ctx->prof = lwp_profile{};
+    if (ctx->dstate) {
+        LWP_HIP(ctx, hipMemsetAsync(ctx->dstate + 1, 0, (kStateInts - 1) * sizeof(int32_t), ctx->stream));
+        LWP_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    }
     return LWP_OK;
 }
 
@@ -195,6 +223,15 @@ lwp_status lwp_profile_read(lwp_ctx* ctx, lwp_profile* out) {
     if (!out) return fail(ctx, LWP_E_INVAL, "null output");
     if (lwp_status s = drain_profile(ctx)) return s;
     *out = ctx->prof;
+    if (ctx->dstate) {
+        int32_t st[kStateInts] = {};
+        LWP_HIP(ctx, hipMemcpyAsync(st, ctx->dstate, sizeof(st), hipMemcpyDeviceToHost, ctx->stream));
+        LWP_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        out->products_keyed = st[1 + kModeKeyed];
+        out->products_plain = st[1 + kModePlain];
+        out->products_value = st[1 + kModeValue];
+        out->products_keyed_row = st[1 + kModeKeyedRow];
+    }
     return LWP_OK;
 }
 

@@ -21,6 +21,10 @@ struct lwp_ctx {
     char* pin = nullptr;       // pinned host staging (descriptor upload, small read-backs)
     size_t pin_bytes = 0;
     int32_t* split = nullptr;  // scratch + per-tile counters of split tiles (see minplus.hip)
+    // device words of the single-step entry points, which only enqueue: [0] error bits set by their
+    // kernels (1: a sum may leave int32, 2: an element outside the ranges the caller promised),
+    // reported and cleared by lwp_synchronize; [1 + mode] products that ran on each kernel variant
+    int32_t* dstate = nullptr;
     bool profiling = false;
     struct Timed { hipEvent_t a, b; int kind; int64_t work; bool keyed; };
     std::vector<Timed> timed;
@@ -53,6 +57,8 @@ lwp_status ensure_pinned(lwp_ctx* ctx, size_t bytes);
 // Scratch and arrival counters of split tiles, allocated on first use; set_split points a
 // launch at them.
 lwp_status ensure_split_buffers(lwp_ctx* ctx);
+constexpr int kStateInts = 8;
+lwp_status ensure_state(lwp_ctx* ctx);
 void set_split(lwp_ctx* ctx, NodeArgs& a, int kparts);
 
 // Brackets one launch with HIP events while profiling is on (kind 0: node elimination with

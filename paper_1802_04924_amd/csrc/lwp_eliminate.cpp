@@ -1,7 +1,91 @@
-// Single eliminations behind the C ABI: Eq. 2 (lwp_eliminate_node) and Eq. 3 (lwp_eliminate_edge).
+// Single eliminations behind the C ABI: Eq. 2 (lwp_eliminate_node, lwp_eliminate_node_bounded) and
+// Eq. 3 (lwp_eliminate_edge).  All three only enqueue; what their kernels find on the device (a sum
+// that may leave int32, a value outside promised ranges) is reported by lwp_synchronize.
 #include "lwp_context.h"
 
 using namespace lwp;
+
+namespace {
+
+// Device memory one node elimination needs beyond its operands.
+struct NodeScratch {
+    int32_t* stats;       // measured ranges: [3][batch][2] = {min, max} of A, w, B per product
+    int32_t* split;       // split-tile scratch (kSplitMaxWorkgroups parts) or null: tiles are not split
+    int32_t* counters;    // split-tile arrival counters (kSplitMaxTiles, zero between launches)
+    int32_t* flag;        // error bits (see lwp_ctx::dstate)
+    int32_t* mode_count;  // optional: products per kernel variant
+};
+
+struct NodeCall {
+    int32_t batch, Ci, Cj, Ck;
+    const int32_t *A, *w, *B;
+    int32_t *out, *arg;
+};
+
+void fill_common(NodeArgs& a, const NodeCall& c, const NodeScratch& sc, bool small) {
+    const int tile = small ? kTileSmall : kTileLarge;
+    a.descs = nullptr;
+    a.base.A = c.A; a.base.w = c.w; a.base.B = c.B; a.base.out = c.out; a.base.arg = c.arg;
+    a.base.flag = sc.flag;
+    a.sA = (int64_t)c.Ci * c.Cj; a.sw = c.Cj; a.sB = (int64_t)c.Cj * c.Ck; a.sO = (int64_t)c.Ci * c.Ck;
+    a.Ci = c.Ci; a.Cj = c.Cj; a.Ck = c.Ck; a.batch = c.batch;
+    a.tilesM = (c.Ci + tile - 1) / tile; a.tilesN = (c.Ck + tile - 1) / tile;
+    a.mode_count = sc.mode_count;
+    const int kparts = sc.split ? choose_kparts((int64_t)a.tilesM * a.tilesN * c.batch, c.Cj, small) : 1;
+    a.kparts = kparts;
+    a.scratch = kparts > 1 ? sc.split : nullptr;
+    a.counters = kparts > 1 ? sc.counters : nullptr;
+}
+
+// Eq. 2 with nothing known about the values: one pass measures {min, max} of A, w and B of every
+// product on the device; the product kernels read them there.  With an argmin output the kernel
+// variant depends on the ranges, so one launch per candidate variant is enqueued and every workgroup
+// first decides, from its product's ranges, whether the product is for its launch (exactly one of
+// the launches takes each product; the others' workgroups exit after one small read).  Nothing
+// comes back to the host.
+hipError_t enqueue_node_measured(const NodeCall& c, const NodeScratch& sc, hipStream_t st) {
+    int32_t *sA = sc.stats, *sW = sc.stats + 2 * (int64_t)c.batch, *sB = sc.stats + 4 * (int64_t)c.batch;
+    hipError_t e = launch_init_workspace(sc.stats, 3 * c.batch, nullptr, nullptr, 0, st);
+    if (e == hipSuccess) e = launch_ranges(c.A, c.batch, (int64_t)c.Ci * c.Cj, sA, st);
+    if (e == hipSuccess) e = launch_ranges(c.w, c.batch, c.Cj, sW, st);
+    if (e == hipSuccess) e = launch_ranges(c.B, c.batch, (int64_t)c.Cj * c.Ck, sB, st);
+    if (e != hipSuccess) return e;
+    const bool small = want_small_tiles(c.Ci, c.Cj, c.Ck, c.batch);
+    NodeArgs a{};
+    a.base.loA = a.base.loW = a.base.loB = (int32_t)kI32Min;
+    a.base.hiA = a.base.hiW = a.base.hiB = (int32_t)kI32Max;
+    a.base.rngA = sA; a.base.rngW = sW; a.base.rngB = sB;
+    a.sR = 2;
+    if (!c.arg) {       // minimum only: one variant, the ranges serve the overflow test
+        fill_common(a, c, sc, small);
+        return launch_minplus(a, kModeValue, small, st);
+    }
+    const bool row = keyed_row_pays(c.Ci, c.Cj, c.Ck, c.batch);
+    a.guard = 1; a.guard_row = row ? 1 : 0;
+    a.guard_limit = small ? kKeyedMaxSpreadSmall : kKeyedMaxSpreadLarge;
+    fill_common(a, c, sc, small);
+    e = launch_minplus(a, kModeKeyed, small, st);
+    if (e == hipSuccess && row) {
+        NodeArgs r = a;
+        fill_common(r, c, sc, true);
+        e = launch_minplus(r, kModeKeyedRow, true, st);
+    }
+    if (e == hipSuccess) e = launch_minplus(a, kModePlain, small, st);
+    return e;
+}
+
+lwp_status check_node_call(lwp_ctx* ctx, const NodeCall& c) {
+    if (c.batch < 1 || c.Ci < 1 || c.Cj < 1 || c.Ck < 1) return fail(ctx, LWP_E_INVAL, "sizes must be positive");
+    if (c.Cj > kMaxConfigs) return fail(ctx, LWP_E_INVAL, "Cj exceeds 65536");
+    if (!c.A || !c.w || !c.B || !c.out) return fail(ctx, LWP_E_INVAL, "null table pointer");
+    if (((uintptr_t)c.A | (uintptr_t)c.w | (uintptr_t)c.B | (uintptr_t)c.out | (uintptr_t)c.arg) & 3)
+        return fail(ctx, LWP_E_INVAL, "table pointer not 4-byte aligned");
+    if ((int64_t)((c.Ci + kTileSmall - 1) / kTileSmall) * ((c.Ck + kTileSmall - 1) / kTileSmall) * c.batch > 0x7fffffffLL)
+        return fail(ctx, LWP_E_INVAL, "too many output tiles");
+    return LWP_OK;
+}
+
+}  // namespace
 
 extern "C" {
 
@@ -10,57 +94,51 @@ lwp_status lwp_eliminate_node(lwp_ctx* ctx, int32_t batch, int32_t Ci, int32_t C
                               const int32_t* d_A, const int32_t* d_w, const int32_t* d_B,
                               int32_t* d_out, int32_t* d_argmin) {
     if (lwp_status s = check_ctx(ctx)) return s;
-    if (batch < 1 || Ci < 1 || Cj < 1 || Ck < 1) return fail(ctx, LWP_E_INVAL, "sizes must be positive");
-    if (Cj > kMaxConfigs) return fail(ctx, LWP_E_INVAL, "Cj exceeds 65536");
-    if (!d_A || !d_w || !d_B || !d_out) return fail(ctx, LWP_E_INVAL, "null table pointer");
-    if (((uintptr_t)d_A | (uintptr_t)d_w | (uintptr_t)d_B | (uintptr_t)d_out | (uintptr_t)d_argmin) & 3)
-        return fail(ctx, LWP_E_INVAL, "table pointer not 4-byte aligned");
-    const bool prefer_small = want_small_tiles(Ci, Cj, Ck, batch);
-    if ((int64_t)((Ci + kTileSmall - 1) / kTileSmall) * ((Ck + kTileSmall - 1) / kTileSmall) * batch > 0x7fffffffLL)
-        return fail(ctx, LWP_E_INVAL, "too many output tiles");
+    const NodeCall c{batch, Ci, Cj, Ck, d_A, d_w, d_B, d_out, d_argmin};
+    if (lwp_status s = check_node_call(ctx, c)) return s;
+    if (lwp_status s = ensure_workspace(ctx, 6 * (size_t)batch * sizeof(int32_t))) return s;
+    if (lwp_status s = ensure_state(ctx)) return s;
+    if (lwp_status s = ensure_split_buffers(ctx)) return s;
+    const NodeScratch sc{reinterpret_cast<int32_t*>(ctx->ws), ctx->split,
+                         ctx->split + (size_t)kSplitMaxWorkgroups * kSplitScratchIntsPerPart, ctx->dstate, ctx->dstate + 1};
+    ScopedTimer tm(ctx, 0, (int64_t)batch * Ci * Cj * Ck, false);
+    LWP_HIP(ctx, enqueue_node_measured(c, sc, ctx->stream));
+    return LWP_OK;
+}
 
-    // value ranges of A, w, B over the whole batch
-    if (lwp_status s = ensure_workspace(ctx, 4096)) return s;
-    if (lwp_status s = ensure_pinned(ctx, 4096)) return s;
-    int32_t* d_stats = reinterpret_cast<int32_t*>(ctx->ws);
-    LWP_HIP(ctx, launch_init_workspace(d_stats, 3, nullptr, nullptr, 0, ctx->stream));
-    LWP_HIP(ctx, launch_ranges(d_A, 1, (int64_t)batch * Ci * Cj, d_stats, ctx->stream));
-    LWP_HIP(ctx, launch_ranges(d_w, 1, (int64_t)batch * Cj, d_stats + 2, ctx->stream));
-    LWP_HIP(ctx, launch_ranges(d_B, 1, (int64_t)batch * Cj * Ck, d_stats + 4, ctx->stream));
-    int32_t* st = reinterpret_cast<int32_t*>(ctx->pin);
-    LWP_HIP(ctx, hipMemcpyAsync(st, d_stats, 6 * sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
-    LWP_HIP(ctx, hipStreamSynchronize(ctx->stream));
-    const Range rA{st[0], st[1]}, rw{st[2], st[3]}, rB{st[4], st[5]};
+lwp_status lwp_eliminate_node_bounded(lwp_ctx* ctx, int32_t batch, int32_t Ci, int32_t Cj, int32_t Ck,
+                                      const int32_t* d_A, const int32_t* d_w, const int32_t* d_B,
+                                      int32_t* d_out, int32_t* d_argmin, const int32_t* bounds) {
+    if (lwp_status s = check_ctx(ctx)) return s;
+    const NodeCall c{batch, Ci, Cj, Ck, d_A, d_w, d_B, d_out, d_argmin};
+    if (lwp_status s = check_node_call(ctx, c)) return s;
+    if (!bounds) return fail(ctx, LWP_E_INVAL, "null bounds");
+    const Range rA{bounds[0], bounds[1]}, rw{bounds[2], bounds[3]}, rB{bounds[4], bounds[5]};
+    if (rA.lo > rA.hi || rw.lo > rw.hi || rB.lo > rB.hi) return fail(ctx, LWP_E_INVAL, "a promised range is empty");
     if (!fits(rA.lo + rw.lo + rB.lo) || !fits(rA.hi + rw.hi + rB.hi) || !fits(rA.lo + rw.lo) || !fits(rA.hi + rw.hi))
-        return fail(ctx, LWP_E_OVERFLOW, "A + w + B may leave int32");
-
-    NodeArgs a{};
-    a.descs = nullptr;
-    a.base.A = d_A; a.base.w = d_w; a.base.B = d_B; a.base.out = d_out; a.base.arg = d_argmin;
-    a.base.loA = (int32_t)rA.lo; a.base.hiA = (int32_t)rA.hi; a.base.loW = (int32_t)rw.lo; a.base.hiW = (int32_t)rw.hi;
-    a.base.loB = (int32_t)rB.lo; a.base.hiB = (int32_t)rB.hi;
-    const int64_t spread = keyed_spread(rA, rw, rB);
-    // one more key bit on large tiles, worth it only if they still fill the chip; without an argmin
-    // output the value-only variant runs, which has no range condition at all
+        return fail(ctx, LWP_E_OVERFLOW, "A + w + B may leave int32 within the promised ranges");
+    if (lwp_status s = ensure_state(ctx)) return s;
+    if (lwp_status s = ensure_split_buffers(ctx)) return s;
+    const NodeScratch sc{nullptr, ctx->split, ctx->split + (size_t)kSplitMaxWorkgroups * kSplitScratchIntsPerPart,
+                         ctx->dstate, ctx->dstate + 1};
+    // the host knows the ranges, so it picks the variant: packed keys on the preferred tile size if
+    // the spread allows, else on 128 x 128 tiles (one more bit) if those still fill the chip, else
+    // keys re-based per row, else compare/select; without an argmin output the minimum-only variant
+    const bool prefer_small = want_small_tiles(Ci, Cj, Ck, batch);
     const bool value_only = (d_argmin == nullptr);
+    const int64_t spread = (rA.hi + rw.hi - rA.lo - rw.lo) + (rB.hi - rB.lo);   // promised ranges need not be attained
     const bool keyed = !value_only && (spread <= kKeyedMaxSpreadSmall ||
                        (spread <= kKeyedMaxSpreadLarge && (!prefer_small || large_tiles(Ci, Ck, batch) >= 512)));
-    // keys re-based per row (64 x 64 tiles) where global offsets do not fit: only B's spread counts
     const bool keyed_row = !value_only && !keyed && keyed_row_spread(rB) <= kKeyedMaxSpreadSmall &&
                            keyed_row_pays(Ci, Cj, Ck, batch);
     const bool small = keyed_row || (prefer_small && (value_only || spread <= kKeyedMaxSpreadSmall || !keyed));
-    const int tile = small ? kTileSmall : kTileLarge;
-    const int64_t tilesM = (Ci + tile - 1) / tile, tilesN = (Ck + tile - 1) / tile;
-    a.sA = (int64_t)Ci * Cj; a.sw = Cj; a.sB = (int64_t)Cj * Ck; a.sO = (int64_t)Ci * Ck;
-    a.Ci = Ci; a.Cj = Cj; a.Ck = Ck; a.batch = batch;
-    a.tilesM = (int32_t)tilesM; a.tilesN = (int32_t)tilesN;
-    {
-        ScopedTimer tm(ctx, 0, (int64_t)batch * Ci * Cj * Ck, keyed || keyed_row);
-        const int kparts = choose_kparts(tilesM * tilesN * batch, Cj, small);
-        if (kparts > 1) { if (lwp_status s = ensure_split_buffers(ctx)) return s; }
-        set_split(ctx, a, kparts);
-        LWP_HIP(ctx, launch_minplus(a, value_only ? kModeValue : (keyed ? kModeKeyed : (keyed_row ? kModeKeyedRow : kModePlain)), small, ctx->stream));
-    }
+    NodeArgs a{};
+    a.base.loA = (int32_t)rA.lo; a.base.hiA = (int32_t)rA.hi; a.base.loW = (int32_t)rw.lo; a.base.hiW = (int32_t)rw.hi;
+    a.base.loB = (int32_t)rB.lo; a.base.hiB = (int32_t)rB.hi;
+    fill_common(a, c, sc, small);
+    const int mode = value_only ? kModeValue : (keyed ? kModeKeyed : (keyed_row ? kModeKeyedRow : kModePlain));
+    ScopedTimer tm(ctx, 0, (int64_t)batch * Ci * Cj * Ck, keyed || keyed_row);
+    LWP_HIP(ctx, launch_minplus(a, mode, small, ctx->stream, /*verify=*/true));
     return LWP_OK;
 }
 
@@ -72,9 +150,10 @@ lwp_status lwp_eliminate_edge(lwp_ctx* ctx, int32_t batch, int32_t Ci, int32_t C
     if (!d_e1 || !d_e2 || !d_out) return fail(ctx, LWP_E_INVAL, "null table pointer");
     if (((uintptr_t)d_e1 | (uintptr_t)d_e2 | (uintptr_t)d_out) & 3)
         return fail(ctx, LWP_E_INVAL, "table pointer not 4-byte aligned");
+    if (lwp_status s = ensure_state(ctx)) return s;
     const int64_t cells = (int64_t)batch * Ci * Cj;
     ScopedTimer tm(ctx, 1, cells, false);
-    LWP_HIP(ctx, launch_edge_sum_pair(d_e1, d_e2, d_out, cells, ctx->stream));
+    LWP_HIP(ctx, launch_edge_sum_pair(d_e1, d_e2, d_out, cells, ctx->dstate, ctx->stream));
     return LWP_OK;
 }
 

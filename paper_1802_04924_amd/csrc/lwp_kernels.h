@@ -35,6 +35,8 @@ struct NodeArgs {
     const NodeDesc* descs;   // device array [batch], or null for strided addressing
     NodeDesc base;           // strided addressing: product 0
     int64_t sA, sw, sB, sO;  // strided addressing: element strides between products
+    int64_t sR;              // strided addressing: int32 elements between the products' measured range pairs
+                             // (base.rngA / rngW / rngB point at product 0's pairs; 0 = one pair for all)
     int32_t Ci, Cj, Ck, batch;
     int32_t tilesM, tilesN;  // output tiles of the chosen tile size per product
     // Mixed shapes (64 x 64 tiles, descriptor addressing only): product q has its own shape in
@@ -48,6 +50,15 @@ struct NodeArgs {
     int32_t kparts;
     int32_t* scratch;
     int32_t* counters;
+    // Guarded launch: the variant is decided on the device, per product, from the measured ranges
+    // (see auto_variant in minplus.hip); a workgroup whose product is not for this launch's variant
+    // exits at once.  guard = 0: no guard.  guard_limit: largest spread packed keys on global
+    // offsets may have at this launch's tile size; guard_row: keys re-based per row are among the
+    // candidates (some launch of the group runs them).
+    int32_t guard, guard_row;
+    int64_t guard_limit;
+    // optional: element `mode` is incremented once per product that this launch works on
+    int32_t* mode_count;
 };
 constexpr int64_t kSplitScratchIntsPerPart = 2 * 16 * 256;
 // Capacity of the split-tile buffers every caller of launch_minplus provides: scratch for
@@ -66,7 +77,13 @@ constexpr int64_t kKeyedMaxSpreadLarge = (1ll << 27) - 2, kKeyedMaxSpreadSmall =
 // kModeKeyedRow: packed keys whose A side is re-based per output row (64 x 64 tiles only): needs
 //   2 * (hiB - loB) + 1 <= kKeyedMaxSpreadSmall and nothing of A or w beyond A + w fitting int32.
 constexpr int kModeKeyed = 0, kModePlain = 1, kModeValue = 2, kModeKeyedRow = 3;
-hipError_t launch_minplus(const NodeArgs& args, int mode, bool small_tiles, hipStream_t stream);
+// verify: the ranges in the descriptors are promises of the caller, not measurements (they need not
+// be attained, and rngA / rngW / rngB must be null).  The kernel then checks every element of A, w
+// and B it stages against them and ORs 2 into `flag` on a violation (results are then meaningless
+// but every access stays in bounds); the keyed variant needs
+//   (hiA + hiW - loA - loW) + (hiB - loB) <= kKeyedMaxSpread*.
+// Strided addressing only, not with mixed shapes.
+hipError_t launch_minplus(const NodeArgs& args, int mode, bool small_tiles, hipStream_t stream, bool verify = false);
 
 // ---- edge elimination (Eq. 3) --------------------------------------------------------------
 // out = sum of n_src tables of `cells` elements.  srcs indexes a device array of table pointers.
@@ -81,8 +98,12 @@ struct EdgeDesc {
 // max_cells: the largest `cells` among the descriptors (sizes the grid).
 hipError_t launch_edge_sum_desc(const EdgeDesc* d_descs, const int32_t* const* d_src_ptrs, int32_t n_desc,
                                 int64_t max_cells, hipStream_t stream);
-hipError_t launch_edge_sum_pair(const int32_t* e1, const int32_t* e2, int32_t* out, int64_t cells,
+// flag (optional) is OR-ed with 1 if a sum leaves int32 (the wrapped sum is stored).
+hipError_t launch_edge_sum_pair(const int32_t* e1, const int32_t* e2, int32_t* out, int64_t cells, int32_t* flag,
                                 hipStream_t stream);
+
+// p[0..n) = value (a fill kernel: also safe inside a captured graph, unlike a memset node).
+hipError_t launch_fill_i32(int32_t* d_p, int64_t n, int32_t value, hipStream_t stream);
 
 // ---- value ranges ----------------------------------------------------------------------------
 // One launch that prepares a search: stats[2*t] = INT32_MAX, stats[2*t+1] = INT32_MIN for

@@ -40,10 +40,6 @@ namespace lwp {
 namespace {
 
 constexpr int NT = kNodeThreads;
-#ifndef LWP_PIPE
-#define LWP_PIPE 1
-#endif
-constexpr bool kPipeLdsReads = LWP_PIPE != 0;
 
 using v4i = int __attribute__((ext_vector_type(4)));
 using gv4cptr = const v4i __attribute__((address_space(1)))*;
@@ -60,14 +56,29 @@ __device__ __forceinline__ int wave_max_i32(int v) {
     return v;
 }
 
-template <int MODE, int RB, int TK, bool MIXED = false>
+// Which variant a product runs on when the choice is made on the device (guarded launches), from the
+// measured ranges of its operands: packed keys on global offsets if their spread fits `limit`, else
+// keys re-based per row if allowed and the spread of B fits them, else the plain variant.  A product
+// whose sums may leave int32 is flagged by the kernels and runs on the plain variant.
+__device__ __forceinline__ int auto_variant(long long loA, long long hiA, long long loW, long long hiW, long long loB,
+                                            long long hiB, long long limit, bool row_ok) {
+    const long long hi = hiA + hiW + hiB, lo = loA + loW + loB, hi2 = hiA + hiW, lo2 = loA + loW;
+    if (hi > 2147483647ll || lo < -2147483648ll || hi2 > 2147483647ll || lo2 < -2147483648ll) return kModePlain;
+    const long long a_max = hiA + hiW - (loA + loW), out_max = (hiA - loA) + (hiB - loB);
+    if (min(a_max, out_max + 1) + (hiB - loB) <= limit) return kModeKeyed;
+    if (row_ok && 2 * (hiB - loB) + 1 <= kKeyedMaxSpreadSmall) return kModeKeyedRow;
+    return kModePlain;
+}
+
+template <int MODE, int RB, int TK, bool MIXED = false, bool VERIFY = false>
 __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) void minplus_kernel(const NodeArgs p) {
     static_assert(!MIXED || RB == 4, "launches of mixed shapes use 64 x 64 tiles");
+    static_assert(!(MIXED && VERIFY), "promised ranges come with strided addressing");
     constexpr bool ROW = (MODE == kModeKeyedRow);  // keys re-based per output row
     constexpr bool KEYED = (MODE == kModeKeyed) || ROW;
     static_assert(!ROW || RB == 4, "row-rebased keys use 64 x 64 tiles");
     constexpr bool VALUE = (MODE == kModeValue);   // minimum only: no argmin, no keys, any int32
-    constexpr bool PIPE = kPipeLdsReads && RB == 4;
+    constexpr bool PIPE = RB == 4;   // LDS reads issued one step ahead of the arithmetic
     constexpr int TM = 16 * RB, TN = 16 * RB;   // output tile
     constexpr int EP = TM * TK / NT;            // elements of A and of B each thread stages per stage
     constexpr int QUADS = RB / 4;
@@ -112,7 +123,20 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
         d.A += (int64_t)bi * p.sA; d.w += (int64_t)bi * p.sw; d.B += (int64_t)bi * p.sB;
         d.out += (int64_t)bi * p.sO;
         if (d.arg) d.arg += (int64_t)bi * p.sO;
+        if (d.rngA) d.rngA += (int64_t)bi * p.sR;
+        if (d.rngW) d.rngW += (int64_t)bi * p.sR;
+        if (d.rngB) d.rngB += (int64_t)bi * p.sR;
     }
+    // Guarded launch: is this product for this launch's variant?  Decided before anything else is
+    // loaded, so that a workgroup that is not needed costs one small read.
+    if (!MIXED && !VERIFY && p.guard) {
+        const int32_t __attribute__((address_space(1)))* ra_ = (const int32_t __attribute__((address_space(1)))*)(uintptr_t)d.rngA;
+        const int32_t __attribute__((address_space(1)))* rw_ = (const int32_t __attribute__((address_space(1)))*)(uintptr_t)d.rngW;
+        const int32_t __attribute__((address_space(1)))* rb_ = (const int32_t __attribute__((address_space(1)))*)(uintptr_t)d.rngB;
+        const int want = auto_variant(ra_[0], ra_[1], rw_[0], rw_[1], rb_[0], rb_[1], p.guard_limit, p.guard_row != 0);
+        if (want != MODE) return;          // uniform for the workgroup
+    }
+    if (p.mode_count && tl == 0 && part == 0 && threadIdx.x == 0) atomicAdd(&p.mode_count[MODE], 1);
     // A workgroup that starts while older ones are in their arithmetic loops would get issue slots
     // only when those stall, and its start-up -- a chain of dependent loads with some scalar
     // arithmetic between them -- would take many times longer than on an idle compute unit.  Its
@@ -250,7 +274,8 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
         const long long out_max = (hiA - loA) + (hiB - loB);      // largest re-based result
         // per row: the row's minimum re-bases to 0 and pairs with a B of at most the spread of B, so
         // anything more than that spread above the row's minimum loses
-        const long long capl = ROW ? (hiB - loB) + 1 : min(a_max, out_max + 1);
+        // (promised ranges need not be attained, so the bound on the result does not hold for them)
+        const long long capl = ROW ? (hiB - loB) + 1 : (VERIFY ? a_max : min(a_max, out_max + 1));
         const long long spread = capl + (hiB - loB);
         cap = (uint32_t)capl;
         constexpr int TB_MIN = (TK <= 16) ? 5 : 6;               // a chunk holds at least one stage
@@ -279,9 +304,24 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
         noffA = __builtin_amdgcn_readfirstlane(noffA);  // uniform: a scalar register
         asm volatile("" : "+v"(nboff), "+s"(noffA));
     }
+    // Promised ranges (VERIFY): every element of A and B is checked when it is staged -- the A strip
+    // by the workgroups of the first tile column, the B strip by those of the first tile row, so
+    // every element is checked once per pass over it and most workgroups check nothing.
+    const bool chkA = VERIFY && tni == 0, chkB = VERIFY && tmi == 0;
+    int32_t vloA = 0x7fffffff, vhiA = (int32_t)0x80000000, vloB = 0x7fffffff, vhiB = (int32_t)0x80000000;
     auto stash = [&](int c0, int pos0, int buf) {
         const uint32_t pos = (uint32_t)(pos0 + br + 1);
         uint32_t ka[EP], kb[EP];
+        if (VERIFY) {       // the loads are clamped to valid elements, so everything seen here is data
+            if (chkA) {
+#pragma unroll
+                for (int q = 0; q < EP; q += 2) { vloA = min(min(vloA, ra[q]), ra[q + 1]); vhiA = max(max(vhiA, ra[q]), ra[q + 1]); }
+            }
+            if (chkB) {
+#pragma unroll
+                for (int q = 0; q < EP; q += 2) { vloB = min(min(vloB, rb[q]), rb[q + 1]); vhiB = max(max(vhiB, rb[q]), rb[q + 1]); }
+            }
+        }
 #pragma unroll
         for (int q = 0; q < EP; ++q) {
             if (KEYED) {
@@ -416,6 +456,13 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
         __syncthreads();
     }
 
+    if (VERIFY) {
+        bool bad = (chkA && (vloA < d.loA || vhiA > d.hiA)) || (chkB && (vloB < d.loB || vhiB > d.hiB));
+        if (chkA && chkB && part == 0)      // one workgroup per product checks w
+            for (int c = tid; c < Cj; c += NT) { const int32_t x = W[c]; bad |= (x < d.loW || x > d.hiW); }
+        if (bad && d.flag) atomicOr(d.flag, 2);
+    }
+
     // Split tile: every part publishes its (cost, argmin) block to global scratch; the part that
     // arrives last (a counter per tile) folds all parts in ascending-c order -- strict '<' lets the
     // earlier part keep ties -- and goes on to the epilogue.  The parts run on different compute
@@ -530,7 +577,7 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
 
 }  // namespace
 
-hipError_t launch_minplus(const NodeArgs& args, int mode, bool small_tiles, hipStream_t stream) {
+hipError_t launch_minplus(const NodeArgs& args, int mode, bool small_tiles, hipStream_t stream, bool verify) {
     const int kparts = args.kparts > 1 ? args.kparts : 1;
     const bool mixed = args.tile_begin != nullptr;
     const int64_t blocks = (mixed ? (int64_t)args.total_tiles : (int64_t)args.tilesM * args.tilesN * args.batch) * kparts;
@@ -539,23 +586,40 @@ hipError_t launch_minplus(const NodeArgs& args, int mode, bool small_tiles, hipS
     if (kparts > 1 && (kparts > kSplitMaxParts || blocks / kparts > kSplitMaxTiles || blocks > kSplitMaxWorkgroups))
         return hipErrorInvalidValue;   // beyond the capacity of the split-tile buffers
     if (mixed && (!small_tiles || !args.descs)) return hipErrorInvalidValue;
-    dim3 grid((unsigned)blocks), block(NT);
     if (mode == kModeKeyedRow && !small_tiles) return hipErrorInvalidValue;
+    if (verify && (mixed || args.descs || args.guard || args.base.rngA || args.base.rngW || args.base.rngB)) return hipErrorInvalidValue;
+    if (args.guard && (mixed || args.descs || mode == kModeValue || !args.base.rngA || !args.base.rngW || !args.base.rngB))
+        return hipErrorInvalidValue;
+    dim3 grid((unsigned)blocks), block(NT);
+#define LWP_LAUNCH(MODE, RB, TK, MIXED, VERIFY) \
+    hipLaunchKernelGGL((minplus_kernel<MODE, RB, TK, MIXED, VERIFY>), grid, block, 0, stream, args)
     if (mixed) {
-        if (mode == kModeKeyed) hipLaunchKernelGGL((minplus_kernel<kModeKeyed, 4, 32, true>), grid, block, 0, stream, args);
-        else if (mode == kModeKeyedRow) hipLaunchKernelGGL((minplus_kernel<kModeKeyedRow, 4, 32, true>), grid, block, 0, stream, args);
-        else if (mode == kModeValue) hipLaunchKernelGGL((minplus_kernel<kModeValue, 4, 32, true>), grid, block, 0, stream, args);
-        else hipLaunchKernelGGL((minplus_kernel<kModePlain, 4, 32, true>), grid, block, 0, stream, args);
+        if (mode == kModeKeyed) LWP_LAUNCH(kModeKeyed, 4, 32, true, false);
+        else if (mode == kModeKeyedRow) LWP_LAUNCH(kModeKeyedRow, 4, 32, true, false);
+        else if (mode == kModeValue) LWP_LAUNCH(kModeValue, 4, 32, true, false);
+        else LWP_LAUNCH(kModePlain, 4, 32, true, false);
+    } else if (verify) {
+        if (small_tiles) {
+            if (mode == kModeKeyed) LWP_LAUNCH(kModeKeyed, 4, 32, false, true);
+            else if (mode == kModeKeyedRow) LWP_LAUNCH(kModeKeyedRow, 4, 32, false, true);
+            else if (mode == kModeValue) LWP_LAUNCH(kModeValue, 4, 32, false, true);
+            else LWP_LAUNCH(kModePlain, 4, 32, false, true);
+        } else {
+            if (mode == kModeKeyed) LWP_LAUNCH(kModeKeyed, 8, 16, false, true);
+            else if (mode == kModeValue) LWP_LAUNCH(kModeValue, 8, 16, false, true);
+            else LWP_LAUNCH(kModePlain, 8, 16, false, true);
+        }
     } else if (small_tiles) {
-        if (mode == kModeKeyed) hipLaunchKernelGGL((minplus_kernel<kModeKeyed, 4, 32>), grid, block, 0, stream, args);
-        else if (mode == kModeKeyedRow) hipLaunchKernelGGL((minplus_kernel<kModeKeyedRow, 4, 32>), grid, block, 0, stream, args);
-        else if (mode == kModeValue) hipLaunchKernelGGL((minplus_kernel<kModeValue, 4, 32>), grid, block, 0, stream, args);
-        else hipLaunchKernelGGL((minplus_kernel<kModePlain, 4, 32>), grid, block, 0, stream, args);
+        if (mode == kModeKeyed) LWP_LAUNCH(kModeKeyed, 4, 32, false, false);
+        else if (mode == kModeKeyedRow) LWP_LAUNCH(kModeKeyedRow, 4, 32, false, false);
+        else if (mode == kModeValue) LWP_LAUNCH(kModeValue, 4, 32, false, false);
+        else LWP_LAUNCH(kModePlain, 4, 32, false, false);
     } else {
-        if (mode == kModeKeyed) hipLaunchKernelGGL((minplus_kernel<kModeKeyed, 8, 16>), grid, block, 0, stream, args);
-        else if (mode == kModeValue) hipLaunchKernelGGL((minplus_kernel<kModeValue, 8, 16>), grid, block, 0, stream, args);
-        else hipLaunchKernelGGL((minplus_kernel<kModePlain, 8, 16>), grid, block, 0, stream, args);
+        if (mode == kModeKeyed) LWP_LAUNCH(kModeKeyed, 8, 16, false, false);
+        else if (mode == kModeValue) LWP_LAUNCH(kModeValue, 8, 16, false, false);
+        else LWP_LAUNCH(kModePlain, 8, 16, false, false);
     }
+#undef LWP_LAUNCH
     return hipGetLastError();
 }
 

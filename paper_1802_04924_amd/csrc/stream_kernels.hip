@@ -94,20 +94,30 @@ __global__ __launch_bounds__(kThreads) void edge_sum_desc_kernel(const EdgeDesc*
 }
 
 __global__ __launch_bounds__(kThreads) void edge_sum_pair_kernel(const int32_t* e1, const int32_t* e2,
-                                                                 int32_t* out, int64_t cells) {
+                                                                 int32_t* out, int64_t cells, int32_t* flag) {
     const bool vec = ((cells & 3) == 0) && (((((uintptr_t)e1) | ((uintptr_t)e2) | ((uintptr_t)out)) & 15) == 0);
     const int64_t stride = (int64_t)gridDim.x * kThreads;
     const int64_t t0 = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    bool bad = false;
     if (vec) {
         const int64_t n4 = cells >> 2;
         for (int64_t x = t0; x < n4; x += stride) {
-            const int4 a = reinterpret_cast<const int4*>(e1)[x];
-            const int4 b = reinterpret_cast<const int4*>(e2)[x];
-            reinterpret_cast<int4*>(out)[x] = make_int4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w);
+            const v4i a = ((gv4c)(uintptr_t)e1)[x];
+            const v4i b = ((gv4c)(uintptr_t)e2)[x];
+            const v4i sum = a + b;
+            const v4i ov = (a ^ sum) & (b ^ sum);     // operands agree in sign, the sum does not
+            bad |= (ov.x | ov.y | ov.z | ov.w) < 0;
+            ((gv4)(uintptr_t)out)[x] = sum;
         }
     } else {
-        for (int64_t x = t0; x < cells; x += stride) out[x] = e1[x] + e2[x];
+        for (int64_t x = t0; x < cells; x += stride) {
+            const int32_t a = e1[x], b = e2[x];
+            const int32_t sum = (int32_t)((uint32_t)a + (uint32_t)b);
+            bad |= ((a ^ sum) & (b ^ sum)) < 0;
+            out[x] = sum;
+        }
     }
+    if (bad && flag) atomicOr(flag, 1);
 }
 
 // ---- value ranges ------------------------------------------------------------------------------
@@ -117,6 +127,11 @@ __global__ void init_workspace_kernel(int32_t* stats, int32_t n_tables, int32_t*
     if (t < n_tables) { stats[2 * t] = 0x7fffffff; stats[2 * t + 1] = (int32_t)0x80000000; }
     if (keys && t < n_keys) keys[t] = ~0ull;
     if (flag && t == 0) *flag = 0;
+}
+
+__global__ void fill_i32_kernel(int32_t* p, int64_t n, int32_t value) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < n) p[t] = value;
 }
 
 constexpr int kRangeLoads = 8;      // 16-byte loads a thread keeps in flight
@@ -453,10 +468,10 @@ hipError_t launch_edge_sum_desc(const EdgeDesc* d_descs, const int32_t* const* d
     return hipGetLastError();
 }
 
-hipError_t launch_edge_sum_pair(const int32_t* e1, const int32_t* e2, int32_t* out, int64_t cells,
+hipError_t launch_edge_sum_pair(const int32_t* e1, const int32_t* e2, int32_t* out, int64_t cells, int32_t* flag,
                                 hipStream_t stream) {
     dim3 grid(blocks_for(cells, 16, 8192));
-    hipLaunchKernelGGL(edge_sum_pair_kernel, grid, dim3(kThreads), 0, stream, e1, e2, out, cells);
+    hipLaunchKernelGGL(edge_sum_pair_kernel, grid, dim3(kThreads), 0, stream, e1, e2, out, cells, flag);
     return hipGetLastError();
 }
 
@@ -465,6 +480,12 @@ hipError_t launch_init_workspace(int32_t* d_stats, int32_t n_tables, int32_t* d_
     const int n = n_tables > n_keys ? n_tables : n_keys;
     hipLaunchKernelGGL(init_workspace_kernel, dim3((n + 256) / 256), dim3(256), 0, stream, d_stats, n_tables, d_flag,
                        d_keys, n_keys);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_i32(int32_t* d_p, int64_t n, int32_t value, hipStream_t stream) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, d_p, n, value);
     return hipGetLastError();
 }
 
