@@ -45,7 +45,8 @@ typedef enum {
     LWP_E_NOT_REDUCIBLE = -3,  /* a residual component is too large to enumerate             */
     LWP_E_OVERFLOW = -4,       /* the tables' value ranges do not keep every sum inside int32 */
     LWP_E_NOMEM = -5,          /* device or host allocation failed                           */
-    LWP_E_HIP = -6             /* a HIP runtime call failed                                  */
+    LWP_E_HIP = -6,            /* a HIP runtime call failed                                  */
+    LWP_E_TOO_LARGE = -7       /* a size exceeds the fixed capacity of lwp_eliminate_node_noalloc */
 } lwp_status;
 
 /* Order of eliminations (the paper leaves the choice open, Alg. 2 "if there exists ...").
@@ -98,6 +99,23 @@ lwp_status lwp_eliminate_node(lwp_ctx *ctx, int32_t batch, int32_t Ci, int32_t C
 lwp_status lwp_eliminate_node_bounded(lwp_ctx *ctx, int32_t batch, int32_t Ci, int32_t Cj, int32_t Ck,
                                       const int32_t *d_A, const int32_t *d_w, const int32_t *d_B,
                                       int32_t *d_out, int32_t *d_argmin, const int32_t *bounds);
+
+/* lwp_eliminate_node for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  No context: the kernels are enqueued on
+ * hip_stream (a hipStream_t, NULL = the default stream) of the CURRENT device, and the device memory
+ * they need beyond the operands -- measured ranges, arrival counters and partial results of split
+ * tiles -- is a fixed array inside the library's device code (about 32.1 MiB per GPU, held from the
+ * first use of the library on that GPU until the process ends).  The call itself allocates and
+ * frees nothing; the array's address is looked up once per device, by lwp_create or by the first
+ * call on that device.  Limits: batch <= LWP_NOALLOC_MAX_BATCH, else LWP_E_TOO_LARGE (Ci, Cj, Ck as
+ * for lwp_eliminate_node).  Same results as lwp_eliminate_node, bit for bit.  Enqueues and returns.
+ * d_status: DEVICE int32 owned by the caller, or NULL; bit 0 is OR-ed in if a sum of some product
+ * may leave int32 (the call never clears it).  All calls on one GPU share the array: calls that
+ * overlap in time on one GPU (different streams, or threads) race and give wrong results. */
+#define LWP_NOALLOC_MAX_BATCH 4096
+lwp_status lwp_eliminate_node_noalloc(void *hip_stream, int32_t batch, int32_t Ci, int32_t Cj, int32_t Ck,
+                                      const int32_t *d_A, const int32_t *d_w, const int32_t *d_B,
+                                      int32_t *d_out, int32_t *d_argmin, int32_t *d_status);
 
 /* ---- edge elimination (Sec. 5.2, Eq. 3) -------------------------------------------------- */
 

@@ -15,13 +15,14 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "liblwp.so")
 
-OK, E_INVAL, E_GRAPH, E_NOT_REDUCIBLE, E_OVERFLOW, E_NOMEM, E_HIP = 0, -1, -2, -3, -4, -5, -6
+OK, E_INVAL, E_GRAPH, E_NOT_REDUCIBLE, E_OVERFLOW, E_NOMEM, E_HIP, E_TOO_LARGE = 0, -1, -2, -3, -4, -5, -6, -7
+NOALLOC_MAX_BATCH = 4096
 SCHEDULE_ROUNDS, SCHEDULE_LEFT_FOLD = 0, 1
 UNDO_STORED, UNDO_RECOMPUTE = 0, 1
 
 EXPORTED = [
     "lwp_create", "lwp_destroy", "lwp_last_error", "lwp_status_string", "lwp_synchronize",
-    "lwp_eliminate_node", "lwp_eliminate_node_bounded", "lwp_eliminate_edge", "lwp_plan_graph", "lwp_search_graph",
+    "lwp_eliminate_node", "lwp_eliminate_node_bounded", "lwp_eliminate_node_noalloc", "lwp_eliminate_edge", "lwp_plan_graph", "lwp_search_graph",
     "lwp_search_workspace_bytes", "lwp_search_graph_ex", "lwp_search_workspace_bytes_ex",
     "lwp_search_graph_ragged", "lwp_search_workspace_bytes_ragged", "lwp_build_cost_tables",
     "lwp_build_cost_tables_ragged", "lwp_enumerate_configs",
@@ -75,6 +76,7 @@ def load():
     lib.lwp_synchronize.argtypes = [vp]
     lib.lwp_eliminate_node.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp, vp]
     lib.lwp_eliminate_node_bounded.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp]
+    lib.lwp_eliminate_node_noalloc.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp]
     lib.lwp_eliminate_edge.argtypes = [vp, i32, i32, i32, vp, vp, vp]
     lib.lwp_plan_graph.argtypes = [i32, i32, vp, i32, vp, i32p, i32p, i32p]
     lib.lwp_search_graph.argtypes = [vp, i32, i32, vp, i32, vp, vp, vp, i32, i32p, vp]
@@ -157,6 +159,28 @@ def _dev(t, what):
     if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.int32 and t.is_contiguous()):
         raise TypeError(f"{what} must be a contiguous int32 CUDA tensor")
     return t.data_ptr()
+
+
+def eliminate_node_noalloc(A, w, B, out, argmin=None, status=None, stream=None):
+    """lwp_eliminate_node_noalloc on the current device: every buffer is the caller's, nothing is allocated.
+
+    A [batch][Ci][Cj], w [batch][Cj], B [batch][Cj][Ck], out (and argmin, optional) [batch][Ci][Ck]:
+    contiguous int32 CUDA tensors; status: optional int32 CUDA tensor of one element that receives
+    error bits; stream: a torch stream (default: the current one).  Only enqueues."""
+    import torch
+    lib = load()
+    batch, Ci, Cj = A.shape
+    Ck = B.shape[2]
+    if tuple(B.shape) != (batch, Cj, Ck) or tuple(w.shape) != (batch, Cj) or tuple(out.shape) != (batch, Ci, Ck):
+        raise ValueError("shape mismatch between A, w, B and out")
+    if argmin is not None and tuple(argmin.shape) != (batch, Ci, Ck):
+        raise ValueError("argmin must have the shape of out")
+    st = stream if stream is not None else torch.cuda.current_stream()
+    rc = lib.lwp_eliminate_node_noalloc(ctypes.c_void_p(st.cuda_stream), batch, Ci, Cj, Ck, _dev(A, "A"), _dev(w, "w"),
+                                        _dev(B, "B"), _dev(out, "out"), _dev(argmin, "argmin") if argmin is not None else None,
+                                        _dev(status, "status") if status is not None else None)
+    if rc:
+        raise LwpError(rc, "eliminate_node_noalloc", lib.lwp_status_string(rc).decode())
 
 
 class SearchPlan:

@@ -118,6 +118,7 @@ const char* lwp_status_string(lwp_status s) {
         case LWP_E_OVERFLOW: return "int32 overflow possible";
         case LWP_E_NOMEM: return "out of memory";
         case LWP_E_HIP: return "HIP error";
+        case LWP_E_TOO_LARGE: return "size beyond the fixed capacity of an entry point that does not allocate";
     }
     return "unknown status";
 }
@@ -132,6 +133,8 @@ lwp_status lwp_create(lwp_ctx** out, int device, void* hip_stream) {
     if (!c) return LWP_E_NOMEM;
     c->device = device;
     c->stream = static_cast<hipStream_t>(hip_stream);
+    (void)prepare_noalloc_scratch(device);     // set-up for lwp_eliminate_node_noalloc; it retries if this failed
+    (void)hipGetLastError();
     *out = c;
     return LWP_OK;
 }

@@ -57,6 +57,9 @@ lwp_status ensure_pinned(lwp_ctx* ctx, size_t bytes);
 // Scratch and arrival counters of split tiles, allocated on first use; set_split points a
 // launch at them.
 lwp_status ensure_split_buffers(lwp_ctx* ctx);
+// Looks up, once per device, the scratch array of the entry point that allocates nothing
+// (lwp_eliminate.cpp); `device` must be current.
+hipError_t prepare_noalloc_scratch(int device);
 constexpr int kStateInts = 8;
 lwp_status ensure_state(lwp_ctx* ctx);
 void set_split(lwp_ctx* ctx, NodeArgs& a, int kparts);

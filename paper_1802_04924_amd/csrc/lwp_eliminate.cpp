@@ -1,6 +1,8 @@
 // Single eliminations behind the C ABI: Eq. 2 (lwp_eliminate_node, lwp_eliminate_node_bounded) and
 // Eq. 3 (lwp_eliminate_edge).  All three only enqueue; what their kernels find on the device (a sum
 // that may leave int32, a value outside promised ranges) is reported by lwp_synchronize.
+#include <mutex>
+
 #include "lwp_context.h"
 
 using namespace lwp;
@@ -85,9 +87,67 @@ lwp_status check_node_call(lwp_ctx* ctx, const NodeCall& c) {
     return LWP_OK;
 }
 
+// ---- scratch of the entry point that allocates nothing -------------------------------------------
+// One array per GPU, held from the moment the library's code is loaded on it until the process ends:
+//   [0, 6 * kNoAllocMaxBatch)   measured ranges of A, w, B per product
+//   then kSplitMaxTiles         arrival counters of split tiles
+//   then                        split-tile scratch for kSplitMaxWorkgroups parts
+constexpr int64_t kNoAllocStatsInts = 6 * (int64_t)LWP_NOALLOC_MAX_BATCH;
+constexpr int64_t kNoAllocInts = kNoAllocStatsInts + kSplitMaxTiles + (int64_t)kSplitMaxWorkgroups * kSplitScratchIntsPerPart;
+static __device__ __align__(256) int32_t scratch[kNoAllocInts];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+int32_t* g_scratch_ptr[kMaxDevices] = {};      // device address of `scratch` on each GPU, once known
+
+// Device address of this GPU's copy of `scratch` (the array's name is only a host-side handle).
+// `device` must be the current device.
+hipError_t scratch_on_device(int device, int32_t** out) {
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void* ptr = nullptr;
+        hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        g_scratch_ptr[device] = static_cast<int32_t*>(ptr);
+    }
+    *out = g_scratch_ptr[device];
+    return hipSuccess;
+}
+
 }  // namespace
 
+namespace lwp {
+// Set-up hook for lwp_create: looks the scratch array up on the context's device, so that a later
+// lwp_eliminate_node_noalloc on that device finds everything ready.
+hipError_t prepare_noalloc_scratch(int device) {
+    int32_t* p = nullptr;
+    return scratch_on_device(device, &p);
+}
+}  // namespace lwp
+
 extern "C" {
+
+lwp_status lwp_eliminate_node_noalloc(void* hip_stream, int32_t batch, int32_t Ci, int32_t Cj, int32_t Ck,
+                                      const int32_t* d_A, const int32_t* d_w, const int32_t* d_B,
+                                      int32_t* d_out, int32_t* d_argmin, int32_t* d_status) {
+    const NodeCall c{batch, Ci, Cj, Ck, d_A, d_w, d_B, d_out, d_argmin};
+    if (lwp_status s = check_node_call(nullptr, c)) return s;
+    if (((uintptr_t)d_status) & 3) return LWP_E_INVAL;
+    if (batch > LWP_NOALLOC_MAX_BATCH) return LWP_E_TOO_LARGE;
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess) return LWP_E_HIP;
+    int32_t* base = nullptr;
+    if (scratch_on_device(device, &base) != hipSuccess) { (void)hipGetLastError(); return LWP_E_HIP; }
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    int32_t* counters = base + kNoAllocStatsInts;
+    // the array keeps what the last call left: the ranges are initialised by the measuring pass; the
+    // counters are zero after every complete launch, and are cleared here in case one was cut short
+    if (launch_fill_i32(counters, kSplitMaxTiles, 0, st) != hipSuccess) { (void)hipGetLastError(); return LWP_E_HIP; }
+    const NodeScratch sc{base, counters + kSplitMaxTiles, counters, d_status, nullptr};
+    if (enqueue_node_measured(c, sc, st) != hipSuccess) { (void)hipGetLastError(); return LWP_E_HIP; }
+    return LWP_OK;
+}
 
 // ---- Eq. 2 -------------------------------------------------------------------------------------
 lwp_status lwp_eliminate_node(lwp_ctx* ctx, int32_t batch, int32_t Ci, int32_t Cj, int32_t Ck,
