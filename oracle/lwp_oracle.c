@@ -195,7 +195,10 @@ int orc_search_ragged(int n_nodes, int n_edges, const int32_t *edges, const int3
     char *dead = (char *)calloc((size_t)n_nodes, 1);
     char *sel = (char *)malloc((size_t)n_nodes);
     int *indeg = (int *)malloc(sizeof(int) * n_nodes), *outdeg = (int *)malloc(sizeof(int) * n_nodes);
-    int *ine = (int *)malloc(sizeof(int) * n_nodes), *oute = (int *)malloc(sizeof(int) * n_nodes);
+    /* per node during the elimination phase; reused per residual component for its member nodes
+     * (ine) and its live edges (oute), of which there can be more than nodes */
+    size_t n_slots = (size_t)(n_nodes > n_edges ? n_nodes : n_edges);
+    int *ine = (int *)malloc(sizeof(int) * n_nodes), *oute = (int *)malloc(sizeof(int) * n_slots);
     int *ids = (int *)malloc(sizeof(int) * (n_edges > 0 ? n_edges : 1));
     int nlog = 0, rounds = 0;
     if (!woff || !w || !E || !log || !argtab || !dead || !sel || !indeg || !outdeg || !ine || !oute || !ids) {
