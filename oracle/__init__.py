@@ -18,7 +18,7 @@ _LIB_PATH = os.path.join(_HERE, "liblwp_oracle.so")
 _lib = None
 
 OK, E_INVAL, E_NOT_REDUCIBLE, E_OVERFLOW, E_NOMEM = 0, -1, -3, -4, -5
-SCHEDULE_ROUNDS, SCHEDULE_LEFT_FOLD = 0, 1
+SCHEDULE_ROUNDS, SCHEDULE_LEFT_FOLD, SCHEDULE_NONE = 0, 1, 2
 
 _i32p = ctypes.POINTER(ctypes.c_int32)
 _i64p = ctypes.POINTER(ctypes.c_int64)
@@ -228,3 +228,32 @@ def build_cost_tables(layers, edges, configs, machine):
     if rc:
         raise OracleError(rc, "build_cost_tables")
     return tc, ts, tx
+
+
+def build_cost_tables_graph(layers, edges, configs, Cn, n_devices, flop_per_ns, invalid_cost, bandwidth, measured_tc=None):
+    """Cost tables on a device graph (Sec. 4: bandwidth[u][v] = b(d_u, d_v) in bytes per ns) with per-layer
+    configuration lists; measured_tc (optional, layout of tc) replaces the analytic t_c (Sec. 5.1).
+
+    Returns flat (tc, ts, tx) in the layout search_ragged takes."""
+    lib = _load()
+    layers = _c(layers).reshape(-1, 14)
+    edges = _c(edges).reshape(-1, 2)
+    configs = _c(configs).reshape(-1, 6)
+    Cn = _c(Cn).reshape(-1)
+    bandwidth = _c(bandwidth).reshape(n_devices, n_devices)
+    if len(Cn) != len(layers) or int(Cn.sum()) != len(configs):
+        raise ValueError("Cn must have one entry per layer and sum to the number of rows")
+    total = int(Cn.astype(np.int64).sum())
+    cells = int(sum(int(Cn[i]) * int(Cn[j]) for i, j in edges))
+    tc, ts, tx = np.empty(total, np.int32), np.empty(total, np.int32), np.empty(max(cells, 1), np.int32)
+    mt = None
+    if measured_tc is not None:
+        mt = _c(measured_tc).reshape(-1)
+        if mt.size != total:
+            raise ValueError("measured_tc must have one entry per configuration row")
+    rc = lib.orc_build_cost_tables_graph(_p(layers), len(layers), _p(edges), len(edges), _p(configs), _p(Cn),
+                                         int(n_devices), int(flop_per_ns), int(invalid_cost), _p(bandwidth),
+                                         _p(mt) if mt is not None else None, _p(tc), _p(ts), _p(tx))
+    if rc:
+        raise OracleError(rc, "build_cost_tables_graph")
+    return tc, ts, tx[:cells]

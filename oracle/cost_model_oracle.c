@@ -22,6 +22,21 @@
  *     the window-expanded, clipped spatial range (fully connected: everything).
  *   Rounding is half-up in integers: (num + den/2) / den.  Invalid rows/columns of t_x are 0.
  *
+ * With a device graph (Sec. 4: every connection (d_i, d_j) has its own bandwidth b(d_i, d_j); Sec. 5.1,
+ * assumption 2: moving s bytes over it takes s / b) -- orc_build_cost_tables_graph:
+ *   t_x = round( sum over (producer part p on device u, consumer part q on device v != u) of
+ *         4 * |T(p) ^ R(q)| / b(u, v) ): the transfers of one tensor are added up, each over its own
+ *         connection (with one bandwidth for all pairs this is the formula above);
+ *   t_s = max over the devices u that hold parameters of round( sum over the other devices v holding a
+ *         replica of the same parameters of (P / r) / b(u, v) ): every replica sends an r-th of its
+ *         gradients to each of the others (each serves an r-th of the parameters, in the paper's
+ *         words a parameter server for it); devices work at the same time, the slowest finishes last
+ *         (with one bandwidth: P * (r-1) / (r * b), the formula above);
+ *   t_c = a table of measured times handed in by the caller (Sec. 5.1: "processing the layer under
+ *         that configuration multiple times on the device and measuring"), or the analytic value.
+ *   Sums of fractions with different denominators are exact: with L the least common multiple of
+ *   all bandwidths, s / b = s * (L / b) / L, and one division by L (half-up) ends the sum.
+ *
  * Absolute values are PARITY UNPINNED against the paper (its t_c are device measurements); the
  * tests pin this file through closed forms and conservation properties instead.
  */
@@ -223,4 +238,145 @@ int orc_enumerate_configs(const orc_layer *L, int n_devices, orc_config *out, in
                     }
                 }
     return count;
+}
+
+
+/* ---- device graph and measured t_c ------------------------------------------------------------ */
+
+static int64_t gcd64(int64_t a, int64_t b) { while (b) { int64_t t = a % b; a = b; b = t; } return a; }
+
+static int in_config(const orc_config *c, int dev, int *in_, int *ih, int *iw, int *ic)
+{
+    int64_t d = (int64_t)c->n * c->h * c->w * c->c;
+    int p = dev - c->dev_offset;
+    if (p < 0 || p >= d) return 0;
+    *ic = p % c->c; p /= c->c;
+    *iw = p % c->w; p /= c->w;
+    *ih = p % c->h; *in_ = p / c->h;
+    return 1;
+}
+
+/* Per-layer configuration lists as orc_build_cost_tables_ragged takes them; bw [n_devices][n_devices]
+ * holds b(u, v) in bytes per ns for the connection from device u (row) to device v (column), the
+ * diagonal is ignored; measured_tc (may be NULL) has the layout of tc and replaces the analytic t_c
+ * of every configuration its layer can use. */
+int orc_build_cost_tables_graph(const orc_layer *layers, int n_layers, const int32_t *edges, int n_edges,
+                                const orc_config *cfgs, const int32_t *Cn, int n_devices, int flop_per_ns,
+                                int invalid_cost, const int32_t *bw, const int32_t *measured_tc,
+                                int32_t *tc, int32_t *ts, int32_t *tx)
+{
+    if (n_layers <= 0 || n_edges < 0 || n_devices <= 0 || flop_per_ns <= 0) return ORC_E_INVAL;
+    int64_t L = 1;                                 /* least common multiple of the bandwidths */
+    for (int u = 0; u < n_devices; ++u)
+        for (int v = 0; v < n_devices; ++v) {
+            if (u == v) continue;
+            int64_t b = bw[u * n_devices + v];
+            if (b <= 0) return ORC_E_INVAL;
+            L = L / gcd64(L, b) * b;
+            if (L > (1 << 20)) return ORC_E_INVAL;
+        }
+    for (int e = 0; e < n_edges; ++e)
+        if (edges[2 * e] < 0 || edges[2 * e] >= n_layers || edges[2 * e + 1] < 0 || edges[2 * e + 1] >= n_layers)
+            return ORC_E_INVAL;
+    const orc_machine m = { n_devices, flop_per_ns, 1, invalid_cost };    /* for config_valid */
+    int overflow = 0;
+    int64_t off = 0;
+    for (int l = 0; l < n_layers; ++l) {
+        const orc_layer *Ly = &layers[l];
+        int64_t F, P;
+        if (Ly->kind == KIND_CONV) {
+            F = 3 * 2 * (int64_t)Ly->N * Ly->Cout * Ly->Hout * Ly->Wout * Ly->Cin * Ly->kh * Ly->kw;
+            P = 4 * ((int64_t)Ly->Cout * Ly->Cin * Ly->kh * Ly->kw + Ly->Cout);
+        } else if (Ly->kind == KIND_FC) {
+            F = 3 * 2 * (int64_t)Ly->N * ((int64_t)Ly->Cin * Ly->Hin * Ly->Win) * Ly->Cout;
+            P = 4 * ((int64_t)Ly->Cout * Ly->Cin * Ly->Hin * Ly->Win + Ly->Cout);
+        } else if (Ly->kind == KIND_POOL) {
+            F = 2 * (int64_t)Ly->N * Ly->Cout * Ly->Hout * Ly->Wout * Ly->kh * Ly->kw;
+            P = 0;
+        } else return ORC_E_INVAL;
+        if (Cn[l] <= 0) return ORC_E_INVAL;
+        for (int r = 0; r < Cn[l]; ++r) {
+            const orc_config *c = &cfgs[off + r];
+            int64_t vc = invalid_cost, vs = 0;
+            if (config_valid(Ly, c, &m)) {
+                int64_t d = (int64_t)c->n * c->h * c->w * c->c;
+                int64_t rep = (int64_t)c->n * c->h * c->w;
+                if (measured_tc) {
+                    vc = measured_tc[off + r];
+                    if (vc < 0) return ORC_E_INVAL;
+                } else vc = round_div(F, d * flop_per_ns);
+                /* every device u of the configuration against the other holders of its parameters:
+                 * the parts that differ from u's only in the sample, height or width index */
+                for (int u = c->dev_offset; u < c->dev_offset + d; ++u) {
+                    int un = 0, uh = 0, uw = 0, uc = 0, vn = 0, vh = 0, vw = 0, vcx = 0;
+                    in_config(c, u, &un, &uh, &uw, &uc);
+                    int64_t inv = 0;                        /* sum of L / b(u, v) */
+                    for (int v = c->dev_offset; v < c->dev_offset + d; ++v) {
+                        in_config(c, v, &vn, &vh, &vw, &vcx);
+                        if (v == u || vcx != uc) continue;
+                        inv += L / bw[u * n_devices + v];
+                    }
+                    int64_t t = round_div(P * inv, rep * L);
+                    vs = imax(vs, t);
+                }
+            }
+            if (vc > INT32_MAX || vs > INT32_MAX) overflow = 1;
+            tc[off + r] = (int32_t)vc;
+            ts[off + r] = (int32_t)vs;
+        }
+        off += Cn[l];
+    }
+    int64_t *cfg_off = malloc((size_t)(n_layers + 1) * sizeof(int64_t));
+    cfg_off[0] = 0;
+    for (int l = 0; l < n_layers; ++l) cfg_off[l + 1] = cfg_off[l] + Cn[l];
+    int64_t tx_off = 0;
+    for (int e = 0; e < n_edges; ++e) {
+        int pi = edges[2 * e], ci = edges[2 * e + 1];
+        const orc_layer *Pl = &layers[pi], *Cl = &layers[ci];
+        if (Pl->N != Cl->N || Pl->Cout != Cl->Cin || Pl->Hout != Cl->Hin || Pl->Wout != Cl->Win) { free(cfg_off); return ORC_E_INVAL; }
+        const int Ca = Cn[pi], Cb = Cn[ci];
+        for (int a = 0; a < Ca; ++a) {
+            const orc_config *ca = &cfgs[cfg_off[pi] + a];
+            for (int b = 0; b < Cb; ++b) {
+                const orc_config *cb = &cfgs[cfg_off[ci] + b];
+                int64_t scaled = 0;                         /* sum of 4 * cells * L / b(u, v) */
+                if (config_valid(Pl, ca, &m) && config_valid(Cl, cb, &m)) {
+                    int64_t da = (int64_t)ca->n * ca->h * ca->w * ca->c, db = (int64_t)cb->n * cb->h * cb->w * cb->c;
+                    for (int u = ca->dev_offset; u < ca->dev_offset + da; ++u)
+                        for (int v = cb->dev_offset; v < cb->dev_offset + db; ++v) {
+                            if (u == v) continue;                /* already local */
+                            int pn = 0, ph = 0, pw = 0, pc = 0, qn = 0, qh = 0, qw = 0, qc = 0;
+                            in_config(ca, u, &pn, &ph, &pw, &pc);
+                            in_config(cb, v, &qn, &qh, &qw, &qc);
+                            int64_t tn0, tn1, th0, th1, tw0, tw1, tc0, tc1;
+                            part(pn, ca->n, Pl->N, &tn0, &tn1);
+                            part(ph, ca->h, Pl->Hout, &th0, &th1);
+                            part(pw, ca->w, Pl->Wout, &tw0, &tw1);
+                            part(pc, ca->c, Pl->Cout, &tc0, &tc1);
+                            int64_t rn0, rn1, rh0, rh1, rw0, rw1, rc0, rc1, o0, o1;
+                            part(qn, cb->n, Cl->N, &rn0, &rn1);
+                            if (Cl->kind == KIND_FC) {
+                                rc0 = 0; rc1 = Cl->Cin; rh0 = 0; rh1 = Cl->Hin; rw0 = 0; rw1 = Cl->Win;
+                            } else {
+                                if (Cl->kind == KIND_POOL) part(qc, cb->c, Cl->Cout, &rc0, &rc1);
+                                else { rc0 = 0; rc1 = Cl->Cin; }
+                                part(qh, cb->h, Cl->Hout, &o0, &o1);
+                                window(o0, o1, Cl->sh, Cl->ph, Cl->kh, Cl->Hin, &rh0, &rh1);
+                                part(qw, cb->w, Cl->Wout, &o0, &o1);
+                                window(o0, o1, Cl->sw, Cl->pw, Cl->kw, Cl->Win, &rw0, &rw1);
+                            }
+                            int64_t cells = overlap(tn0, tn1, rn0, rn1) * overlap(tc0, tc1, rc0, rc1) *
+                                            overlap(th0, th1, rh0, rh1) * overlap(tw0, tw1, rw0, rw1);
+                            scaled += 4 * cells * (L / bw[u * n_devices + v]);
+                        }
+                }
+                int64_t t = round_div(scaled, L);
+                if (t > INT32_MAX) overflow = 1;
+                tx[tx_off + (int64_t)a * Cb + b] = (int32_t)t;
+            }
+        }
+        tx_off += (int64_t)Ca * Cb;
+    }
+    free(cfg_off);
+    return overflow ? ORC_E_OVERFLOW : ORC_OK;
 }

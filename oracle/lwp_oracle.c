@@ -33,6 +33,7 @@
 
 #define ORC_SCHEDULE_ROUNDS 0
 #define ORC_SCHEDULE_LEFT_FOLD 1
+#define ORC_SCHEDULE_NONE 2          /* no elimination at all: the baseline of Sec. 5.2 / Table 3 */
 
 static int fits_i32(int64_t v) { return v >= INT32_MIN && v <= INT32_MAX; }
 
@@ -226,6 +227,9 @@ int orc_search_ragged(int n_nodes, int n_edges, const int32_t *edges, const int3
 
     for (;;) {
         int changed = 0;
+        /* The baseline the paper compares with (Sec. 5.2, last paragraph; Table 3) searches the
+         * original graph: nothing is eliminated and every strategy of it is enumerated below. */
+        if (schedule == ORC_SCHEDULE_NONE) break;
         /* ---- E-phase: merge parallel edges (Eq. 3) ---- */
         int nl = 0;
         for (int e = 0; e < n_edges; ++e) if (E[e].alive) ids[nl++] = e;

@@ -16,6 +16,7 @@ import numpy as np
 # Schedules understood by both the oracle and the GPU library.
 SCHEDULE_ROUNDS = 0      # batched rounds of independent eliminations
 SCHEDULE_LEFT_FOLD = 1   # one node elimination per round, lowest eligible id
+SCHEDULE_NONE = 2        # no elimination: every strategy of the original graph is enumerated (the paper's baseline)
 
 # Layer kinds for the analytic cost model inputs.
 KIND_CONV, KIND_POOL, KIND_FC = 0, 1, 2

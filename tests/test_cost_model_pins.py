@@ -275,3 +275,129 @@ def test_vgg16_strategy_agrees_with_the_papers_where_the_analytic_model_can():
     for l, name in zip(range(18, 21), ("fc_1", "fc_2", "fc_3")):
         n, h, w, c = chosen[l]
         assert (n, h, w) == groups[name][:3] and 1 < c <= groups[name][3]   # channel split, no sample split
+
+
+# ---- device graph (Sec. 4) and measured t_c (Sec. 5.1) -------------------------------------------
+
+def graph_tables(layers, lists, bw, edges=None, measured_tc=None, flop_per_ns=10_000, invalid=1 << 28):
+    layers = np.asarray(layers, np.int32)
+    if edges is None:
+        edges = wl.chain_edges(len(layers))
+    Cn = np.array([len(x) for x in lists], np.int32)
+    bw = np.asarray(bw, np.int32)
+    return oracle.build_cost_tables_graph(layers, edges, np.concatenate(lists), Cn, len(bw), flop_per_ns, invalid, bw,
+                                          measured_tc)
+
+
+def two_islands(fast=100, slow=10, n=4):
+    """Devices {0,1} and {2,3} (and so on) joined by fast links inside an island, slow ones between."""
+    bw = np.full((n, n), slow, np.int32)
+    for u in range(n):
+        for v in range(n):
+            if u // 2 == v // 2:
+                bw[u, v] = fast
+    return bw
+
+
+def test_device_graph_with_one_bandwidth_is_the_plain_cost_model():
+    # every connection at the machine's one bandwidth: the tables of the AlexNet-shaped chain, built from
+    # per-layer configuration lists on 16 devices, must come out bit for bit as before
+    p = wl.config1()
+    lists = [oracle.enumerate_configs(l, 16) for l in p["layers"]]
+    Cn = np.array([len(x) for x in lists], np.int32)
+    ref = oracle.build_cost_tables_ragged(p["layers"], p["edges"], np.concatenate(lists), Cn, p["machine"])
+    bw = np.full((16, 16), p["machine"]["byte_per_ns"], np.int32)
+    np.fill_diagonal(bw, 0)                                   # the diagonal is never read
+    got = oracle.build_cost_tables_graph(p["layers"], p["edges"], np.concatenate(lists), Cn, 16,
+                                         p["machine"]["flop_per_ns"], p["machine"]["invalid_cost"], bw)
+    for a, b in zip(ref, got):
+        assert np.array_equal(a, b)
+
+
+def test_device_graph_transfers_by_hand():
+    # fully connected -> fully connected, N = 8 samples, 6 features between them (24 B per sample).
+    # islands {0,1} and {2,3}: 100 B/ns inside, 10 B/ns between.
+    layers = [fc(8, 5, 1, 6), fc(8, 6, 1, 7)]
+    lists = [cfg((2, 1, 1, 1, 0), (4, 1, 1, 1, 0), (1, 1, 1, 1, 3)),            # producer: samples over {0,1}; over {0..3}; all on 3
+             cfg((1, 1, 1, 2, 2), (1, 1, 1, 2, 0), (1, 1, 1, 4, 0), (1, 1, 1, 1, 0))]   # consumer: channels over {2,3}; {0,1}; {0..3}; all on 0
+    tc, ts, tx = graph_tables(layers, lists, two_islands())
+    tx = tx.reshape(3, 4)
+    # a consumer part of a fully connected layer reads every feature of every sample.
+    # producer parts on 0,1 hold 4 samples each (96 B); consumer parts on 2,3: four transfers of 96 B
+    # between the islands: 4 * 96 / 10 = 38.4 -> 38
+    assert tx[0, 0] == 38
+    # consumer parts on 0,1: 0->1 and 1->0 inside the island, the rest is local: 2 * 96 / 100 = 1.92 -> 2
+    assert tx[0, 1] == 2
+    # producer parts of 2 samples (48 B) on 0..3, consumer parts on 0..3: each part goes to the three
+    # other devices, one inside its island, two outside: 4 * 48/100 + 8 * 48/10 = 1.92 + 38.4 = 40.32 -> 40
+    assert tx[1, 2] == 40
+    # everything on device 3, consumer on device 0: 192 B between the islands -> 19.2 -> 19
+    assert tx[2, 3] == 19
+    # one bandwidth of 10 for all: the last but one case is 12 * 48 / 10 = 57.6 -> 58
+    assert graph_tables(layers, lists, np.full((4, 4), 10))[2].reshape(3, 4)[1, 2] == 58
+
+
+def test_device_graph_direction_of_a_connection():
+    # b(u, v) is the bandwidth from u (row, the sender) to v (column): an asymmetric pair tells the two apart
+    layers = [fc(8, 5, 1, 6), fc(8, 6, 1, 7)]
+    lists = [cfg((1, 1, 1, 1, 0), (1, 1, 1, 1, 1)), cfg((1, 1, 1, 1, 0), (1, 1, 1, 1, 1))]
+    bw = np.array([[0, 4], [16, 0]], np.int32)                # 0 -> 1 at 4 B/ns, 1 -> 0 at 16 B/ns
+    tx = graph_tables(layers, lists, bw)[2].reshape(2, 2)
+    assert tx[0, 1] == 48                                     # producer on 0, consumer on 1: 192 B / 4
+    assert tx[1, 0] == 12                                     # producer on 1, consumer on 0: 192 B / 16
+    assert tx[0, 0] == 0 and tx[1, 1] == 0
+
+
+def test_device_graph_parameter_synchronisation_by_hand():
+    # fully connected 5 -> 6: P = 4 * (30 + 6) = 144 B.  Four replicas on devices 0..3 (sample split):
+    # every replica sends a quarter (36 B) to each of the others: one inside its island, two outside:
+    # 36/100 + 2 * 36/10 = 7.56 -> 8.
+    layers = [fc(8, 5, 1, 6)]
+    lists = [cfg((4, 1, 1, 1, 0), (2, 1, 1, 1, 0), (2, 1, 1, 1, 2), (2, 1, 1, 2, 0), (1, 1, 1, 4, 0), (1, 1, 1, 1, 2))]
+    tc, ts, tx = graph_tables(layers, lists, two_islands(), edges=np.zeros((0, 2), np.int32))
+    assert ts[0] == 8
+    assert ts[1] == 1 and ts[2] == 1                           # two replicas inside an island: 72 / 100 = 0.72 -> 1
+    # samples over 2, channels over 2 on devices 0..3: part (i_n, i_c) on device 2 i_n + i_c, so the
+    # replicas of one channel half sit on {0, 2} and {1, 3}: 72 B between the islands = 7.2 -> 7
+    assert ts[3] == 7
+    assert ts[4] == 0 and ts[5] == 0                           # no replicas: nothing to synchronise
+    # the slowest device decides: device 0 sends to 1 slowly, everything else is fast
+    bw = np.full((2, 2), 1000, np.int32)
+    bw[0, 1] = 3
+    ts2 = graph_tables(layers, [cfg((2, 1, 1, 1, 0))], bw, edges=np.zeros((0, 2), np.int32))[1]
+    assert ts2[0] == 24                                        # 72 / 3, not 72 / 1000
+
+
+def test_measured_compute_times_replace_the_analytic_ones():
+    layers = [conv(4, 3, 8, 6, 3, 1, 1), fc(4, 6, 8, 5)]
+    lists = [oracle.enumerate_configs(np.asarray(l, np.int32), 4) for l in layers]
+    n = sum(len(x) for x in lists)
+    measured = (np.arange(n, dtype=np.int32) * 37 + 11) % 1009      # distinct, unrelated to any formula
+    bw = two_islands()
+    tc, ts, tx = graph_tables(layers, lists, bw, measured_tc=measured)
+    assert np.array_equal(tc, measured)
+    tc0, ts0, tx0 = graph_tables(layers, lists, bw)
+    assert np.array_equal(ts, ts0) and np.array_equal(tx, tx0)      # t_s and t_x do not depend on t_c
+    assert not np.array_equal(tc0, measured)
+    with pytest.raises(oracle.OracleError):
+        graph_tables(layers, lists, bw, measured_tc=-measured - 1)   # a negative time
+
+
+def test_device_graph_scaling_and_refusals():
+    p = wl.config1()
+    layers = p["layers"][:4]
+    lists = [oracle.enumerate_configs(l, 4) for l in layers]
+    bw = two_islands(fast=60, slow=12)
+    tc, ts, tx = graph_tables(layers, lists, bw)
+    tc2, ts2, tx2 = graph_tables(layers, lists, 2 * bw)
+    # twice the bandwidth everywhere: half the time, up to the rounding of each entry
+    assert np.all(np.abs(2 * tx2.astype(np.int64) - tx) <= 1) and np.all(np.abs(2 * ts2.astype(np.int64) - ts) <= 1)
+    assert np.array_equal(tc, tc2)
+    # slower links between the islands can only cost time
+    tx3 = graph_tables(layers, lists, two_islands(fast=60, slow=6))[2]
+    assert np.all(tx3 >= tx) and np.any(tx3 > tx)
+    with pytest.raises(oracle.OracleError):
+        graph_tables(layers, lists, np.zeros((4, 4), np.int32))      # a connection without bandwidth
+    primes = np.array([[0, 1009, 1013, 1019], [1021, 0, 1031, 1033], [1039, 1049, 0, 1051], [1061, 1063, 1069, 0]], np.int32)
+    with pytest.raises(oracle.OracleError):
+        graph_tables(layers, lists, primes)                           # no common time unit below 2^20

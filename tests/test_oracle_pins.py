@@ -191,6 +191,37 @@ def small_graphs():
 
 @pytest.mark.parametrize("name", sorted(small_graphs()))
 @pytest.mark.parametrize("hi", [1, 50])
+def test_baseline_without_eliminations_equals_the_definition(name, hi):
+    # Sec. 5.2 / Table 3: the baseline searches the original graph by enumerating every strategy.  Its
+    # result is the definition itself: the minimum of Eq. 1, and among equal minima the
+    # lexicographically lowest strategy (lower node id more significant) -- also under heavy ties
+    n_nodes, edges = small_graphs()[name]
+    edges = np.asarray(edges, np.int32).reshape(-1, 2)
+    C = 2 if n_nodes > 8 else 3
+    for seed in range(4):
+        rng = np.random.default_rng(77 * seed + hi)
+        tc, ts, tx = rand_problem(rng, n_nodes, edges, C, hi)
+        best, S_lex, n_opt = brute.brute_force(n_nodes, edges, C, tc, ts, tx)
+        r = oracle.search(n_nodes, edges, C, tc, ts, tx, oracle.SCHEDULE_NONE)
+        assert r["cost"] == best and len(r["steps"]) == 0 and r["n_rounds"] == 0
+        assert np.array_equal(r["strategy"], S_lex)
+        # and Alg. 1 finds the same optimum (Thm. 1 and 2)
+        assert oracle.search(n_nodes, edges, C, tc, ts, tx, oracle.SCHEDULE_ROUNDS)["cost"] == best
+
+
+def test_baseline_refuses_graphs_too_large_to_enumerate():
+    p = wl.chain_problem(17, 2, 1)
+    with pytest.raises(oracle.OracleError) as e:
+        oracle.search(17, p["edges"], 2, p["tc"], p["ts"], p["tx"], oracle.SCHEDULE_NONE)
+    assert e.value.code == oracle.E_NOT_REDUCIBLE
+    p = wl.chain_problem(6, 64, 1)                                   # 2^36 strategies
+    with pytest.raises(oracle.OracleError) as e:
+        oracle.search(6, p["edges"], 64, p["tc"], p["ts"], p["tx"], oracle.SCHEDULE_NONE)
+    assert e.value.code == oracle.E_NOT_REDUCIBLE
+
+
+@pytest.mark.parametrize("name", sorted(small_graphs()))
+@pytest.mark.parametrize("hi", [1, 50])
 @pytest.mark.parametrize("schedule", [oracle.SCHEDULE_ROUNDS, oracle.SCHEDULE_LEFT_FOLD])
 def test_search_equals_brute_force_on_tiny_graphs(name, hi, schedule):
     n_nodes, edges = small_graphs()[name]
