@@ -54,8 +54,14 @@ typedef enum {
  *   LWP_SCHEDULE_ROUNDS     scan nodes in ascending id, take every eligible node none of whose
  *                           two neighbours was taken in this round; all taken nodes are
  *                           eliminated by one batched launch;
- *   LWP_SCHEDULE_LEFT_FOLD  take only the lowest-id eligible node per round. */
-typedef enum { LWP_SCHEDULE_ROUNDS = 0, LWP_SCHEDULE_LEFT_FOLD = 1 } lwp_schedule;
+ *   LWP_SCHEDULE_LEFT_FOLD  take only the lowest-id eligible node per round;
+ *   LWP_SCHEDULE_NONE       eliminate nothing: the baseline the paper compares its algorithm with
+ *                           (Sec. 5.2, last paragraph; Table 3), which finds the optimum of the
+ *                           ORIGINAL graph by enumerating every strategy.  Each connected component
+ *                           is enumerated on the device like a residual component (same limits:
+ *                           12 nodes, 32 edges, 2^32 strategies); among equal optima the
+ *                           lexicographically lowest strategy, lower node id more significant. */
+typedef enum { LWP_SCHEDULE_ROUNDS = 0, LWP_SCHEDULE_LEFT_FOLD = 1, LWP_SCHEDULE_NONE = 2 } lwp_schedule;
 
 /* ---- context --------------------------------------------------------------------------- */
 
@@ -256,6 +262,33 @@ lwp_status lwp_build_cost_tables_ragged(lwp_ctx *ctx, const lwp_layer *layers, i
                                         const int32_t *edges, int32_t n_edges, const lwp_config *cfgs,
                                         const int32_t *C_node, const lwp_machine *machine,
                                         int32_t *d_tc, int32_t *d_ts, int32_t *d_tx);
+
+/* The cost model on a device graph (Sec. 4: each connection (d_i, d_j) has a bandwidth b(d_i, d_j);
+ * Sec. 5.1, assumption 2: moving s bytes over it takes s / b) and with measured compute times
+ * (Sec. 5.1: t_c is the measured time of the layer under the configuration).
+ * bandwidth HOST [n_devices][n_devices]: b(u, v) in byte per ns from device u (row, the sender) to
+ * device v (column), positive for u != v, the diagonal is ignored; all entries must have a common
+ * multiple of at most 2^20 (the sums below are exact). */
+typedef struct {
+    int32_t n_devices;
+    int32_t flop_per_ns;    /* per-device compute rate of the analytic t_c; unused with measured t_c */
+    int32_t invalid_cost;   /* t_c of a configuration a layer cannot use                            */
+    int32_t pad;
+    const int32_t *bandwidth;
+} lwp_device_graph;
+/* Arguments and table layout as lwp_build_cost_tables_ragged.  measured_tc HOST, laid out like d_tc,
+ * or NULL: if given, t_c of every configuration its layer can use is copied from it (entries must be
+ * >= 0) instead of the analytic value.
+ *   t_x = round( sum over (producer part on device u, consumer part on device v != u) of
+ *         4 * elements the consumer part reads from the producer part / b(u, v) );
+ *   t_s = max over the devices u holding parameters of round( sum over the other r - 1 devices v that
+ *         hold a replica of the same parameters of (4 * parameters / r) / b(u, v) );
+ * with one bandwidth for all connections both are the formulas of lwp_build_cost_tables.  Blocking. */
+lwp_status lwp_build_cost_tables_graph(lwp_ctx *ctx, const lwp_layer *layers, int32_t n_layers,
+                                       const int32_t *edges, int32_t n_edges, const lwp_config *cfgs,
+                                       const int32_t *C_node, const lwp_device_graph *graph,
+                                       const int32_t *measured_tc,
+                                       int32_t *d_tc, int32_t *d_ts, int32_t *d_tx);
 
 /* Host-only: the configurations of one layer on a machine of n_devices (Sec. 4, Table 1; equal
  * partitioning): every (n, h, w, c) of power-of-two degrees with n*h*w*c = d <= n_devices, no degree

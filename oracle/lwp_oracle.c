@@ -313,7 +313,7 @@ int orc_search_ragged(int n_nodes, int n_edges, const int32_t *edges, const int3
                 int l = ine[0], best = 0;
                 for (int q = 1; q < Cn[l]; ++q) if (w[woff[l] + q] < w[woff[l] + best]) best = q;
                 c = w[woff[l] + best]; S[l] = best;
-            } else if (K == 2 && ne == 1) {
+            } else if (K == 2 && ne == 1 && schedule != ORC_SCHEDULE_NONE) {   /* the baseline enumerates in node order */
                 int e = oute[0]; int32_t a, b;
                 int r = orc_final_pair(Cn[E[e].src], Cn[E[e].dst], w + woff[E[e].src], E[e].tab, w + woff[E[e].dst], &c, &a, &b);
                 if (r != ORC_OK) { rc = r; goto done; }

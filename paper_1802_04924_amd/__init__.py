@@ -5,6 +5,6 @@ seeded synthetic inputs; `build` compiles the HIP sources.  Importing the packag
 the shared library is opened on first use and must have been built.
 """
 from . import workloads  # noqa: F401
-from .binding import (Context, LwpError, SCHEDULE_LEFT_FOLD, SCHEDULE_ROUNDS, UNDO_RECOMPUTE,  # noqa: F401
+from .binding import (Context, LwpError, SCHEDULE_LEFT_FOLD, SCHEDULE_NONE, SCHEDULE_ROUNDS, UNDO_RECOMPUTE,  # noqa: F401
                       UNDO_STORED, enumerate_configs, plan_graph, search_workspace_bytes,
                       search_workspace_bytes_ragged)

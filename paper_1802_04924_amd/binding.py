@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "liblwp.so")
 
 OK, E_INVAL, E_GRAPH, E_NOT_REDUCIBLE, E_OVERFLOW, E_NOMEM, E_HIP, E_TOO_LARGE = 0, -1, -2, -3, -4, -5, -6, -7
 NOALLOC_MAX_BATCH = 4096
-SCHEDULE_ROUNDS, SCHEDULE_LEFT_FOLD = 0, 1
+SCHEDULE_ROUNDS, SCHEDULE_LEFT_FOLD, SCHEDULE_NONE = 0, 1, 2
 UNDO_STORED, UNDO_RECOMPUTE = 0, 1
 
 EXPORTED = [
@@ -25,7 +25,7 @@ EXPORTED = [
     "lwp_eliminate_node", "lwp_eliminate_node_bounded", "lwp_eliminate_node_noalloc", "lwp_eliminate_edge", "lwp_plan_graph", "lwp_search_graph",
     "lwp_search_workspace_bytes", "lwp_search_graph_ex", "lwp_search_workspace_bytes_ex",
     "lwp_search_graph_ragged", "lwp_search_workspace_bytes_ragged", "lwp_build_cost_tables",
-    "lwp_build_cost_tables_ragged", "lwp_enumerate_configs",
+    "lwp_build_cost_tables_ragged", "lwp_build_cost_tables_graph", "lwp_enumerate_configs",
     "lwp_search_plan_create", "lwp_search_plan_run", "lwp_search_plan_destroy", "lwp_measure_valu_rate",
     "lwp_profile_enable", "lwp_profile_reset", "lwp_profile_read",
 ]
@@ -45,6 +45,11 @@ class Profile(ctypes.Structure):
                 ("keyed_launches", ctypes.c_int64), ("products_keyed", ctypes.c_int64),
                 ("products_keyed_row", ctypes.c_int64), ("products_plain", ctypes.c_int64),
                 ("products_value", ctypes.c_int64)]
+
+
+class DeviceGraph(ctypes.Structure):
+    _fields_ = [("n_devices", ctypes.c_int32), ("flop_per_ns", ctypes.c_int32), ("invalid_cost", ctypes.c_int32),
+                ("pad", ctypes.c_int32), ("bandwidth", ctypes.c_void_p)]
 
 
 class LwpError(RuntimeError):
@@ -90,6 +95,7 @@ def load():
     lib.lwp_search_workspace_bytes_ragged.restype = ctypes.c_size_t
     lib.lwp_build_cost_tables.argtypes = [vp, vp, i32, vp, i32, vp, i32, vp, vp, vp, vp]
     lib.lwp_build_cost_tables_ragged.argtypes = [vp, vp, i32, vp, i32, vp, vp, vp, vp, vp, vp]
+    lib.lwp_build_cost_tables_graph.argtypes = [vp, vp, i32, vp, i32, vp, vp, ctypes.POINTER(DeviceGraph), vp, vp, vp, vp]
     lib.lwp_enumerate_configs.argtypes = [vp, i32, vp, i32, i32p]
     lib.lwp_search_plan_create.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, i32, ctypes.POINTER(vp)]
     lib.lwp_search_plan_run.argtypes = [vp, i32p, vp]
@@ -394,6 +400,40 @@ class Context:
                                                     configs.ctypes.data, C_node.ctypes.data, m.ctypes.data,
                                                     _dev(tc, "tc"), _dev(ts, "ts"), _dev(tx, "tx") if E else None)
         self._check(rc, "build_cost_tables_ragged")
+        return tc, ts, tx
+
+    def build_cost_tables_graph(self, layers, edges, configs, C_node, n_devices, flop_per_ns, invalid_cost, bandwidth,
+                                measured_tc=None):
+        """As build_cost_tables_ragged on a device graph: bandwidth int32 [n_devices][n_devices] (byte per ns
+        from row device to column device); measured_tc (optional, host int32, one entry per configuration
+        row) replaces the analytic t_c."""
+        import torch
+        layers = _np_i32(layers, (-1, 14))
+        edges = _np_i32(edges, (-1, 2))
+        configs = _np_i32(configs, (-1, 6))
+        C_node = _np_i32(C_node, (-1,))
+        bandwidth = _np_i32(bandwidth, (int(n_devices), int(n_devices)))
+        L, E = len(layers), len(edges)
+        if len(C_node) != L or (C_node < 1).any() or int(C_node.astype(np.int64).sum()) != len(configs):
+            raise ValueError("C_node must have one positive entry per layer and sum to the number of rows")
+        if E and ((edges < 0).any() or (edges >= L).any()):
+            raise ValueError("edge endpoint out of range")
+        rows = int(C_node.astype(np.int64).sum())
+        cells = int((C_node[edges[:, 0]].astype(np.int64) * C_node[edges[:, 1]]).sum()) if E else 0
+        mt = None
+        if measured_tc is not None:
+            mt = _np_i32(measured_tc, (-1,))
+            if mt.size != rows:
+                raise ValueError("measured_tc must have one entry per configuration row")
+        g = DeviceGraph(int(n_devices), int(flop_per_ns), int(invalid_cost), 0, bandwidth.ctypes.data)
+        dev = torch.device("cuda", self.device)
+        tc = torch.empty(rows, dtype=torch.int32, device=dev)
+        ts = torch.empty(rows, dtype=torch.int32, device=dev)
+        tx = torch.empty(max(cells, 1), dtype=torch.int32, device=dev)[:cells]
+        rc = self._lib.lwp_build_cost_tables_graph(self._h, layers.ctypes.data, L, edges.ctypes.data, E, configs.ctypes.data,
+                                                   C_node.ctypes.data, ctypes.byref(g), mt.ctypes.data if mt is not None else None,
+                                                   _dev(tc, "tc"), _dev(ts, "ts"), _dev(tx, "tx") if E else None)
+        self._check(rc, "build_cost_tables_graph")
         return tc, ts, tx
 
     # ---- measurement -------------------------------------------------------

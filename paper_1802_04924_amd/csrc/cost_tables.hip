@@ -9,6 +9,12 @@
 // producer's parts partition its output tensor, the volume read by all consumer parts is a
 // product of per-dimension sums; what stays on the same device is subtracted part by part
 // (a producer part shares a device with at most one consumer part).
+//
+// With a device graph (Sec. 4: every connection (d_i, d_j) has its own bandwidth; lwp_build_cost_tables_graph)
+// a transfer's time depends on both of its ends, so the volume between every pair of parts is
+// weighted by L / b(u, v), L the least common multiple of the bandwidths (the sum of fractions stays
+// an exact integer until one final division): the consumer's parts are walked dimension by dimension
+// and whole subtrees without overlap are skipped.  t_c may then come from the caller's measurements.
 #include <hip/hip_runtime.h>
 
 #include <string>
@@ -135,14 +141,119 @@ __global__ void edge_costs_kernel(const lwp_layer* __restrict__ layers, const La
     tx[tx_off[e] + (int64_t)a * sb.C + b] = (int32_t)v;
 }
 
+// ---- device graph ----------------------------------------------------------------------------
+// wgt [n_devices][n_devices] = L / b(u, v) (0 on the diagonal); measured (optional) replaces the
+// analytic t_c of usable configurations.
+struct GraphArgs { const int32_t* wgt; const int32_t* measured; int64_t L; int32_t n_devices, flop_per_ns, invalid_cost, pad; };
+
+__device__ inline void part_index(const lwp_config& c, int p, int& in, int& ih, int& iw, int& ic) {
+    ic = p % c.c; p /= c.c;
+    iw = p % c.w; p /= c.w;
+    ih = p % c.h; in = p / c.h;
+}
+
+__global__ void node_costs_graph_kernel(const lwp_layer* __restrict__ layers, const LayerSlice* __restrict__ slices,
+                                        const lwp_config* __restrict__ cfgs, GraphArgs g,
+                                        int32_t* __restrict__ tc, int32_t* __restrict__ ts, int32_t* __restrict__ flag) {
+    const LayerSlice sl = slices[blockIdx.y];
+    const int r = blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= sl.C) return;
+    const int64_t x = sl.out_off + r;
+    const lwp_layer L = layers[blockIdx.y];
+    const lwp_config c = cfgs[sl.cfg_off + r];
+    long long work, params;
+    if (L.kind == KIND_CONV) {
+        work = 6ll * L.N * L.Cout * L.Hout * L.Wout * L.Cin * L.kh * L.kw;
+        params = 4ll * ((long long)L.Cout * L.Cin * L.kh * L.kw + L.Cout);
+    } else if (L.kind == KIND_FC) {
+        const long long fan_in = (long long)L.Cin * L.Hin * L.Win;
+        work = 6ll * L.N * fan_in * L.Cout;
+        params = 4ll * (fan_in * L.Cout + L.Cout);
+    } else {
+        work = 2ll * L.N * L.Cout * L.Hout * L.Wout * L.kh * L.kw;
+        params = 0;
+    }
+    long long vc = g.invalid_cost, vs = 0;
+    if (row_valid(L, c, g.n_devices)) {
+        const int replicas = c.n * c.h * c.w;
+        if (g.measured) {
+            vc = g.measured[x];
+            if (vc < 0) atomicOr(flag, 2);
+        } else vc = div_round(work, (long long)replicas * c.c * g.flop_per_ns);
+        // the holders of one channel part's parameters sit c devices apart; every one of them sends an
+        // r-th of its gradients to each of the others, and the slowest sender finishes last
+        for (int ic = 0; ic < c.c; ++ic)
+            for (int s = 0; s < replicas; ++s) {
+                const int u = c.dev_offset + s * c.c + ic;
+                long long inv = 0;
+                for (int t = 0; t < replicas; ++t)
+                    if (t != s) inv += g.wgt[(int64_t)u * g.n_devices + c.dev_offset + t * c.c + ic];
+                const long long v = div_round(params * inv, (long long)replicas * g.L);
+                vs = v > vs ? v : vs;
+            }
+    }
+    if (vc > 2147483647ll || vs > 2147483647ll) atomicOr(flag, 1);
+    tc[x] = (int32_t)vc;
+    ts[x] = (int32_t)vs;
+}
+
+__global__ void edge_costs_graph_kernel(const lwp_layer* __restrict__ layers, const LayerSlice* __restrict__ slices,
+                                        const int32_t* __restrict__ edges, const int64_t* __restrict__ tx_off,
+                                        const lwp_config* __restrict__ cfgs, GraphArgs g,
+                                        int32_t* __restrict__ tx, int32_t* __restrict__ flag) {
+    const int e = blockIdx.z;
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;     // consumer configuration
+    const int a = blockIdx.y;                                // producer configuration
+    const LayerSlice sa = slices[edges[2 * e]], sb = slices[edges[2 * e + 1]];
+    if (a >= sa.C || b >= sb.C) return;
+    const lwp_layer P = layers[edges[2 * e]];
+    const lwp_layer Q = layers[edges[2 * e + 1]];
+    const lwp_config ca = cfgs[sa.cfg_off + a], cb = cfgs[sb.cfg_off + b];
+    long long scaled = 0;                                    // sum of elements * L / b(u, v)
+    if (row_valid(P, ca, g.n_devices) && row_valid(Q, cb, g.n_devices)) {
+        const int da = ca.n * ca.h * ca.w * ca.c;
+        for (int p = 0; p < da; ++p) {
+            int pn, ph, pw, pc;
+            part_index(ca, p, pn, ph, pw, pc);
+            const Span tn = split(pn, ca.n, P.N), th = split(ph, ca.h, P.Hout), tw = split(pw, ca.w, P.Wout),
+                       tcs = split(pc, ca.c, P.Cout);
+            const int32_t* wrow = g.wgt + (int64_t)(ca.dev_offset + p) * g.n_devices + cb.dev_offset;
+            for (int qn = 0; qn < cb.n; ++qn) {
+                const long long on = common(tn, split(qn, cb.n, Q.N));
+                if (!on) continue;
+                for (int qh = 0; qh < cb.h; ++qh) {
+                    const long long oh = on * common(th, spatial_need(Q, true, qh, cb.h));
+                    if (!oh) continue;
+                    for (int qw = 0; qw < cb.w; ++qw) {
+                        const long long ow = oh * common(tw, spatial_need(Q, false, qw, cb.w));
+                        if (!ow) continue;
+                        for (int qc = 0; qc < cb.c; ++qc) {
+                            const Span need_c = (Q.kind == KIND_POOL) ? split(qc, cb.c, Q.Cout) : Span{0, Q.Cin};
+                            // the weight of a device with itself is 0: what is local costs nothing
+                            scaled += ow * common(tcs, need_c) * wrow[((qn * cb.h + qh) * cb.w + qw) * cb.c + qc];
+                        }
+                    }
+                }
+            }
+        }
+    }
+    const long long v = div_round(4 * scaled, g.L);
+    if (v > 2147483647ll) atomicOr(flag, 1);
+    tx[tx_off[e] + (int64_t)a * sb.C + b] = (int32_t)v;
+}
+
 }  // namespace
 
 namespace {
 
-// cfg_rows: total rows in cfgs.  shared: every layer uses rows [0, Cn[0]).
+struct GraphHost { std::vector<int32_t> wgt; int64_t L; const int32_t* measured; int64_t rows; };
+
+// cfg_rows: total rows in cfgs.  shared: every layer uses rows [0, Cn[0]).  graph (optional): weights
+// of a device graph and measured t_c; machine->byte_per_ns is then unused.
 lwp_status build_tables(lwp_ctx* ctx, const lwp_layer* layers, int32_t n_layers, const int32_t* edges,
                         int32_t n_edges, const lwp_config* cfgs, const int32_t* Cn, bool shared,
-                        const lwp_machine* machine, int32_t* d_tc, int32_t* d_ts, int32_t* d_tx) {
+                        const lwp_machine* machine, int32_t* d_tc, int32_t* d_ts, int32_t* d_tx,
+                        const GraphHost* graph = nullptr) {
     if (machine->n_devices < 1 || machine->flop_per_ns < 1 || machine->byte_per_ns < 1 || machine->invalid_cost < 0)
         return lwp::fail(ctx, LWP_E_INVAL, "machine constants must be positive");
     for (int32_t l = 0; l < n_layers; ++l) {
@@ -180,8 +291,11 @@ lwp_status build_tables(lwp_ctx* ctx, const lwp_layer* layers, int32_t n_layers,
                  bo = tx_off.size() * sizeof(int64_t);
     auto up = [](size_t v) { return (v + 255) / 256 * 256; };
     const size_t off_s = up(bl), off_c = off_s + up(bs), off_e = off_c + up(bc), off_o = off_e + up(be), off_f = off_o + up(bo);
+    const size_t bw_bytes = graph ? graph->wgt.size() * sizeof(int32_t) : 0;
+    const size_t bm_bytes = (graph && graph->measured) ? (size_t)rows * sizeof(int32_t) : 0;
+    const size_t off_w = off_f + 256, off_m = off_w + up(bw_bytes);
     char* d = nullptr;
-    if (hipMalloc(&d, off_f + 256) != hipSuccess) { (void)hipGetLastError(); return lwp::fail(ctx, LWP_E_NOMEM, "descriptor upload buffer"); }
+    if (hipMalloc(&d, off_m + up(bm_bytes) + 256) != hipSuccess) { (void)hipGetLastError(); return lwp::fail(ctx, LWP_E_NOMEM, "descriptor upload buffer"); }
     lwp_status result = LWP_OK;
     int32_t flag = 0;
     hipError_t herr = hipSuccess;
@@ -191,6 +305,8 @@ lwp_status build_tables(lwp_ctx* ctx, const lwp_layer* layers, int32_t n_layers,
         ok(hipMemcpyAsync(d + off_c, cfgs, bc, hipMemcpyHostToDevice, st)) &&
         (n_edges == 0 || ok(hipMemcpyAsync(d + off_e, edges, (size_t)n_edges * 2 * sizeof(int32_t), hipMemcpyHostToDevice, st))) &&
         (n_edges == 0 || ok(hipMemcpyAsync(d + off_o, tx_off.data(), (size_t)n_edges * sizeof(int64_t), hipMemcpyHostToDevice, st))) &&
+        (bw_bytes == 0 || ok(hipMemcpyAsync(d + off_w, graph->wgt.data(), bw_bytes, hipMemcpyHostToDevice, st))) &&
+        (bm_bytes == 0 || ok(hipMemcpyAsync(d + off_m, graph->measured, bm_bytes, hipMemcpyHostToDevice, st))) &&
         ok(hipMemsetAsync(d + off_f, 0, sizeof(int32_t), st))) {
         const lwp_layer* dl = reinterpret_cast<const lwp_layer*>(d);
         const LayerSlice* ds = reinterpret_cast<const LayerSlice*>(d + off_s);
@@ -198,16 +314,28 @@ lwp_status build_tables(lwp_ctx* ctx, const lwp_layer* layers, int32_t n_layers,
         const int32_t* de = reinterpret_cast<const int32_t*>(d + off_e);
         const int64_t* dof = reinterpret_cast<const int64_t*>(d + off_o);
         int32_t* df = reinterpret_cast<int32_t*>(d + off_f);
+        GraphArgs ga{};
+        if (graph)
+            ga = {reinterpret_cast<const int32_t*>(d + off_w), bm_bytes ? reinterpret_cast<const int32_t*>(d + off_m) : nullptr,
+                  graph->L, machine->n_devices, machine->flop_per_ns, machine->invalid_cost, 0};
         for (int32_t l0 = 0; l0 < n_layers && herr == hipSuccess; l0 += 65535) {
             const int32_t nl = (n_layers - l0) < 65535 ? (n_layers - l0) : 65535;
-            hipLaunchKernelGGL(node_costs_kernel, dim3((c_max + 255) / 256, nl), dim3(256), 0, st, dl + l0, ds + l0, dc,
-                               *machine, d_tc, d_ts, df);
+            if (graph)
+                hipLaunchKernelGGL(node_costs_graph_kernel, dim3((c_max + 255) / 256, nl), dim3(256), 0, st, dl + l0, ds + l0,
+                                   dc, ga, d_tc, d_ts, df);
+            else
+                hipLaunchKernelGGL(node_costs_kernel, dim3((c_max + 255) / 256, nl), dim3(256), 0, st, dl + l0, ds + l0, dc,
+                                   *machine, d_tc, d_ts, df);
             ok(hipGetLastError());
         }
         for (int32_t e0 = 0; e0 < n_edges && herr == hipSuccess; e0 += 65535) {
             const int32_t ne = (n_edges - e0) < 65535 ? (n_edges - e0) : 65535;
-            hipLaunchKernelGGL(edge_costs_kernel, dim3((c_max + 255) / 256, c_max, ne), dim3(256), 0, st, dl, ds,
-                               de + 2 * (size_t)e0, dof + e0, dc, *machine, d_tx, df);
+            if (graph)
+                hipLaunchKernelGGL(edge_costs_graph_kernel, dim3((c_max + 63) / 64, c_max, ne), dim3(64), 0, st, dl, ds,
+                                   de + 2 * (size_t)e0, dof + e0, dc, ga, d_tx, df);
+            else
+                hipLaunchKernelGGL(edge_costs_kernel, dim3((c_max + 255) / 256, c_max, ne), dim3(256), 0, st, dl, ds,
+                                   de + 2 * (size_t)e0, dof + e0, dc, *machine, d_tx, df);
             ok(hipGetLastError());
         }
         ok(hipMemcpyAsync(&flag, df, sizeof(int32_t), hipMemcpyDeviceToHost, st));
@@ -215,7 +343,8 @@ lwp_status build_tables(lwp_ctx* ctx, const lwp_layer* layers, int32_t n_layers,
     ok(hipStreamSynchronize(st));
     (void)hipFree(d);
     if (herr != hipSuccess) return lwp::fail(ctx, LWP_E_HIP, hipGetErrorString(herr));
-    if (flag) result = lwp::fail(ctx, LWP_E_OVERFLOW, "a cost does not fit int32 nanoseconds");
+    if (flag & 2) result = lwp::fail(ctx, LWP_E_INVAL, "a measured t_c is negative");
+    else if (flag) result = lwp::fail(ctx, LWP_E_OVERFLOW, "a cost does not fit int32 nanoseconds");
     return result;
 }
 
@@ -245,6 +374,41 @@ extern "C" lwp_status lwp_build_cost_tables_ragged(lwp_ctx* ctx, const lwp_layer
         return lwp::fail(ctx, LWP_E_INVAL, "null pointer");
     if (n_layers < 1 || n_edges < 0) return lwp::fail(ctx, LWP_E_INVAL, "bad sizes");
     return build_tables(ctx, layers, n_layers, edges, n_edges, cfgs, C_node, false, machine, d_tc, d_ts, d_tx);
+}
+
+// Sec. 4: the device graph gives every connection (d_i, d_j) its own bandwidth; Sec. 5.1: t_c is
+// measured on the device.  See the header for the readings.
+extern "C" lwp_status lwp_build_cost_tables_graph(lwp_ctx* ctx, const lwp_layer* layers, int32_t n_layers,
+                                                  const int32_t* edges, int32_t n_edges, const lwp_config* cfgs,
+                                                  const int32_t* C_node, const lwp_device_graph* dg,
+                                                  const int32_t* measured_tc,
+                                                  int32_t* d_tc, int32_t* d_ts, int32_t* d_tx) {
+    if (!ctx) return LWP_E_INVAL;
+    if (lwp_status rc = lwp::check_ctx(ctx)) return rc;
+    if (!layers || !cfgs || !C_node || !dg || !dg->bandwidth || !d_tc || !d_ts || (n_edges > 0 && (!edges || !d_tx)))
+        return lwp::fail(ctx, LWP_E_INVAL, "null pointer");
+    if (n_layers < 1 || n_edges < 0) return lwp::fail(ctx, LWP_E_INVAL, "bad sizes");
+    if (dg->n_devices < 1 || dg->n_devices > 4096) return lwp::fail(ctx, LWP_E_INVAL, "a device graph has 1..4096 devices");
+    const int32_t D = dg->n_devices;
+    GraphHost gh;
+    gh.L = 1;
+    auto gcd = [](int64_t a, int64_t b) { while (b) { const int64_t t = a % b; a = b; b = t; } return a; };
+    for (int32_t u = 0; u < D; ++u)
+        for (int32_t v = 0; v < D; ++v) {
+            if (u == v) continue;
+            const int64_t b = dg->bandwidth[(size_t)u * D + v];
+            if (b < 1) return lwp::fail(ctx, LWP_E_INVAL, "every connection of the device graph needs a positive bandwidth");
+            gh.L = gh.L / gcd(gh.L, b) * b;
+            if (gh.L > (1 << 20))
+                return lwp::fail(ctx, LWP_E_INVAL, "the bandwidths have no common multiple below 2^20 (exact sums of transfer times need one)");
+        }
+    gh.wgt.assign((size_t)D * D, 0);
+    for (int32_t u = 0; u < D; ++u)
+        for (int32_t v = 0; v < D; ++v)
+            if (u != v) gh.wgt[(size_t)u * D + v] = (int32_t)(gh.L / dg->bandwidth[(size_t)u * D + v]);
+    gh.measured = measured_tc;
+    const lwp_machine m{dg->n_devices, dg->flop_per_ns, 1, dg->invalid_cost};
+    return build_tables(ctx, layers, n_layers, edges, n_edges, cfgs, C_node, false, &m, d_tc, d_ts, d_tx, &gh);
 }
 
 // Sec. 4 / Table 1: a configuration gives a degree of parallelism to every parallelizable

@@ -23,7 +23,10 @@ lwp_status make_plan(int32_t n_nodes, int32_t n_edges, const int32_t* edges, int
                      Plan& plan, std::string& err) {
     plan = Plan();
     if (n_nodes <= 0 || n_edges < 0 || (n_edges > 0 && !edges)) { err = "bad graph sizes"; return LWP_E_INVAL; }
-    if (schedule != LWP_SCHEDULE_ROUNDS && schedule != LWP_SCHEDULE_LEFT_FOLD) { err = "unknown schedule"; return LWP_E_INVAL; }
+    if (schedule != LWP_SCHEDULE_ROUNDS && schedule != LWP_SCHEDULE_LEFT_FOLD && schedule != LWP_SCHEDULE_NONE) {
+        err = "unknown schedule";
+        return LWP_E_INVAL;
+    }
     std::vector<Edge> E(n_edges);
     for (int32_t e = 0; e < n_edges; ++e) {
         int32_t s = edges[2 * e], d = edges[2 * e + 1];
@@ -55,6 +58,8 @@ lwp_status make_plan(int32_t n_nodes, int32_t n_edges, const int32_t* edges, int
     keys.reserve(n_edges);
     std::vector<int32_t> chosen;
     for (;;) {
+        // the exhaustive baseline (Sec. 5.2, Table 3) searches the original graph: no eliminations
+        if (schedule == LWP_SCHEDULE_NONE) break;
         bool worked = false;
         // E-phase: live edges ordered by (src, dst, id); equal (src, dst) form a group
         keys.clear();
@@ -121,7 +126,8 @@ lwp_status make_plan(int32_t n_nodes, int32_t n_edges, const int32_t* edges, int
             c.edges.push_back(e); c.esrc.push_back(E[e].src); c.edst.push_back(E[e].dst);
         }
         if (c.nodes.size() == 1) plan.singles.push_back(root);
-        else if (c.nodes.size() == 2 && c.edges.size() == 1) plan.pairs.push_back({c.edges[0], c.esrc[0], c.edst[0]});
+        else if (c.nodes.size() == 2 && c.edges.size() == 1 && schedule != LWP_SCHEDULE_NONE)   // (the baseline enumerates in node order)
+            plan.pairs.push_back({c.edges[0], c.esrc[0], c.edst[0]});
         else if ((int)c.nodes.size() > kMaxComponentNodes || (int)c.edges.size() > kMaxComponentEdges) {
             err = "a residual component has more than " + std::to_string(kMaxComponentNodes) + " nodes or " +
                   std::to_string(kMaxComponentEdges) + " edges";

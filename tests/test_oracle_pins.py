@@ -175,6 +175,7 @@ def test_config0_equals_brute_force_over_all_16_pow_6():
 def small_graphs():
     g = {}
     g["chain2"] = (2, [(0, 1)])
+    g["backward_pair"] = (2, [(1, 0)])
     g["chain5"] = (5, [(0, 1), (1, 2), (2, 3), (3, 4)])
     g["single"] = (1, [])
     g["two_isolated"] = (2, [])
