@@ -394,7 +394,7 @@ def main():
                 "traffic": pmc_traffic_bytes() if (headline == "cfg4" and wk.C == 4096 and args.undo == "stored") else None,
                 "algorithmic_bytes": (4 * (2 * wk.C * wk.C + wk.C) + 8 * wk.C * wk.C) if headline == "cfg4" else None,
                 "launches": prof["node_launches"], "avg_launch_ms": node_ms,
-                "cell_updates_per_launch": upd_per_launch, "keyed_launches": prof["keyed_launches"],
+                "cell_updates_per_launch": upd_per_launch, "products_by_variant": {k: prof[k] for k in ("products_keyed", "products_keyed_row", "products_plain", "products_value")},
                 "kernel_cell_updates_per_s_G": upd_per_s / 1e9,
                 "measured_valu_lane_TOPs": valu["lane_ops_per_s"] / 1e12,
                 "measured_add_min3_cell_updates_per_s_G": valu["cell_updates_per_s"] / 1e9,

@@ -69,8 +69,10 @@ lwp_status ensure_state(lwp_ctx* ctx) {
     return ensure_pinned(ctx, 4096);       // lwp_synchronize reads the error bits back through it
 }
 
-void set_split(lwp_ctx* ctx, NodeArgs& a, int kparts) {
+void set_split(lwp_ctx* ctx, NodeArgs& a, Split split) {
+    const int kparts = split.kparts;
     a.kparts = kparts;
+    a.n_whole = (int32_t)split.n_whole;
     a.scratch = kparts > 1 ? ctx->split : nullptr;
     a.counters = kparts > 1 ? ctx->split + (size_t)kSplitMaxWorkgroups * kSplitScratchIntsPerPart : nullptr;
 }

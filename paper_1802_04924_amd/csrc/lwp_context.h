@@ -25,6 +25,9 @@ struct lwp_ctx {
     // kernels (1: a sum may leave int32, 2: an element outside the ranges the caller promised),
     // reported and cleared by lwp_synchronize; [1 + mode] products that ran on each kernel variant
     int32_t* dstate = nullptr;
+    // a search on this context met tables too wide for packed keys on global offsets: later searches
+    // do not try those first (see Search::run)
+    bool keys_failed = false;
     bool profiling = false;
     struct Timed { hipEvent_t a, b; int kind; int64_t work; bool keyed; };
     std::vector<Timed> timed;
@@ -56,13 +59,15 @@ lwp_status ensure_workspace(lwp_ctx* ctx, size_t bytes);
 lwp_status ensure_pinned(lwp_ctx* ctx, size_t bytes);
 // Scratch and arrival counters of split tiles, allocated on first use; set_split points a
 // launch at them.
+// How a launch's tiles are split: the first n_whole tiles have one workgroup each, the others kparts.
+struct Split { int kparts; int64_t n_whole; };
 lwp_status ensure_split_buffers(lwp_ctx* ctx);
 // Looks up, once per device, the scratch array of the entry point that allocates nothing
 // (lwp_eliminate.cpp); `device` must be current.
 hipError_t prepare_noalloc_scratch(int device);
 constexpr int kStateInts = 8;
 lwp_status ensure_state(lwp_ctx* ctx);
-void set_split(lwp_ctx* ctx, NodeArgs& a, int kparts);
+void set_split(lwp_ctx* ctx, NodeArgs& a, Split split);
 
 // Brackets one launch with HIP events while profiling is on (kind 0: node elimination with
 // `work` cell updates, kind 1: edge elimination with `work` cells).
@@ -111,11 +116,18 @@ inline bool want_small_tiles(int32_t Ci, int32_t Cj, int32_t Ck, int64_t batch) 
 // Split tiles: a launch with few 64 x 64 tiles lets several workgroups share a tile, each with a
 // part of the c range of at least two stages of 32 candidates.
 // Measured: splitting pays while tiles x parts stays around 1024 workgroups (4 per compute unit).
-inline int choose_kparts(int64_t tiles, int32_t Cj, bool small_tiles) {
-    if (!small_tiles || tiles > kSplitMaxTiles) return 1;
+// A launch of more tiles runs in rounds of kWorkgroupSlots workgroups; if its last round is less than
+// half full, the tiles of that round are shared instead, so that the round ends sooner (a launch of
+// 4160 tiles would otherwise take five rounds for the work of 4.06).
+constexpr int64_t kWorkgroupSlots = 1024;      // 256 compute units x 4 resident workgroups of 64 x 64 tiles
+inline Split choose_split(int64_t tiles, int32_t Cj, bool small_tiles) {
+    if (!small_tiles) return {1, tiles};
     const int64_t nstages = (Cj + 31) / 32;
-    int64_t k = std::min<int64_t>({kSplitMaxParts, kSplitMaxWorkgroups / tiles, nstages / 2});
-    return k < 2 ? 1 : (int)k;
+    const int64_t shared = tiles <= kSplitMaxTiles ? tiles : tiles % kWorkgroupSlots;
+    if (shared == 0 || shared > kSplitMaxTiles) return {1, tiles};
+    const int64_t k = std::min<int64_t>({kSplitMaxParts, kSplitMaxWorkgroups / shared, nstages / 2});
+    if (k < 2) return {1, tiles};
+    return {(int)k, tiles - shared};
 }
 
 }  // namespace lwp

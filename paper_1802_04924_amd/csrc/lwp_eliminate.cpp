@@ -33,18 +33,18 @@ void fill_common(NodeArgs& a, const NodeCall& c, const NodeScratch& sc, bool sma
     a.Ci = c.Ci; a.Cj = c.Cj; a.Ck = c.Ck; a.batch = c.batch;
     a.tilesM = (c.Ci + tile - 1) / tile; a.tilesN = (c.Ck + tile - 1) / tile;
     a.mode_count = sc.mode_count;
-    const int kparts = sc.split ? choose_kparts((int64_t)a.tilesM * a.tilesN * c.batch, c.Cj, small) : 1;
-    a.kparts = kparts;
-    a.scratch = kparts > 1 ? sc.split : nullptr;
-    a.counters = kparts > 1 ? sc.counters : nullptr;
+    const int64_t tiles = (int64_t)a.tilesM * a.tilesN * c.batch;
+    const Split split = sc.split ? choose_split(tiles, c.Cj, small) : Split{1, tiles};
+    a.kparts = split.kparts;
+    a.n_whole = (int32_t)split.n_whole;
+    a.scratch = split.kparts > 1 ? sc.split : nullptr;
+    a.counters = split.kparts > 1 ? sc.counters : nullptr;
 }
 
 // Eq. 2 with nothing known about the values: one pass measures {min, max} of A, w and B of every
-// product on the device; the product kernels read them there.  With an argmin output the kernel
-// variant depends on the ranges, so one launch per candidate variant is enqueued and every workgroup
-// first decides, from its product's ranges, whether the product is for its launch (exactly one of
-// the launches takes each product; the others' workgroups exit after one small read).  Nothing
-// comes back to the host.
+// product on the device; the product kernel reads them there.  With an argmin output the arithmetic
+// variant depends on the ranges: every workgroup picks it from its product's ranges and runs the
+// matching body of the kernel.  Nothing comes back to the host.
 hipError_t enqueue_node_measured(const NodeCall& c, const NodeScratch& sc, hipStream_t st) {
     int32_t *sA = sc.stats, *sW = sc.stats + 2 * (int64_t)c.batch, *sB = sc.stats + 4 * (int64_t)c.batch;
     hipError_t e = launch_init_workspace(sc.stats, 3 * c.batch, nullptr, nullptr, 0, st);
@@ -62,18 +62,10 @@ hipError_t enqueue_node_measured(const NodeCall& c, const NodeScratch& sc, hipSt
         fill_common(a, c, sc, small);
         return launch_minplus(a, kModeValue, small, st);
     }
-    const bool row = keyed_row_pays(c.Ci, c.Cj, c.Ck, c.batch);
-    a.guard = 1; a.guard_row = row ? 1 : 0;
-    a.guard_limit = small ? kKeyedMaxSpreadSmall : kKeyedMaxSpreadLarge;
+    a.auto_row = keyed_row_pays(c.Ci, c.Cj, c.Ck, c.batch) ? 1 : 0;
+    a.auto_limit = small ? kKeyedMaxSpreadSmall : kKeyedMaxSpreadLarge;
     fill_common(a, c, sc, small);
-    e = launch_minplus(a, kModeKeyed, small, st);
-    if (e == hipSuccess && row) {
-        NodeArgs r = a;
-        fill_common(r, c, sc, true);
-        e = launch_minplus(r, kModeKeyedRow, true, st);
-    }
-    if (e == hipSuccess) e = launch_minplus(a, kModePlain, small, st);
-    return e;
+    return launch_minplus(a, kModeAuto, small, st);
 }
 
 lwp_status check_node_call(lwp_ctx* ctx, const NodeCall& c) {

@@ -26,6 +26,7 @@ struct NodeDesc {
     const int32_t* rngW;
     int32_t* rngOut;
     int32_t* flag;     // optional: OR-ed with 1 if max A + max w + max B (measured) may leave int32
+                       // (2: a promised range broken, 4: skipped by a speculative launch; see NodeArgs)
     int32_t Ci, Cj, Ck;   // shape of this product; read only by launches of mixed shapes
     int32_t pad[3];
 };
@@ -45,18 +46,20 @@ struct NodeArgs {
     // tilesM and tilesN above are then ignored.
     const int32_t* tile_begin;
     int32_t total_tiles;
-    // Split tiles (64 x 64 tiles only): kparts > 1 workgroups share a tile.  scratch holds
-    // tiles * kparts * 2 * 16 * 256 int32; counters one zeroed int32 per tile (left zeroed).
-    int32_t kparts;
+    // Split tiles (64 x 64 tiles only): with kparts > 1 the launch's first n_whole tiles have one
+    // workgroup each and every later ("shared") tile has kparts workgroups.  scratch holds
+    // shared tiles * kparts * 2 * 16 * 256 int32; counters one zeroed int32 per shared tile (left zeroed).
+    int32_t kparts, n_whole;
     int32_t* scratch;
     int32_t* counters;
-    // Guarded launch: the variant is decided on the device, per product, from the measured ranges
-    // (see auto_variant in minplus.hip); a workgroup whose product is not for this launch's variant
-    // exits at once.  guard = 0: no guard.  guard_limit: largest spread packed keys on global
-    // offsets may have at this launch's tile size; guard_row: keys re-based per row are among the
-    // candidates (some launch of the group runs them).
-    int32_t guard, guard_row;
-    int64_t guard_limit;
+    // kModeAuto: the variant is decided on the device, per product, from the measured ranges (see
+    // auto_variant in minplus.hip).  auto_limit: largest spread packed keys on global offsets may
+    // have at this launch's tile size; auto_row: keys re-based per row are among the candidates.
+    int32_t auto_row;
+    // kModeKeyed launched without knowing the ranges: a product whose measured ranges do not allow
+    // packed keys is skipped -- its outputs are NOT written -- and 4 is OR-ed into its `flag`
+    int32_t speculative;
+    int64_t auto_limit;
     // optional: element `mode` is incremented once per product that this launch works on
     int32_t* mode_count;
 };
@@ -76,7 +79,9 @@ constexpr int64_t kKeyedMaxSpreadLarge = (1ll << 27) - 2, kKeyedMaxSpreadSmall =
 // output tiles instead of 128 x 128; tilesM / tilesN in args must match.
 // kModeKeyedRow: packed keys whose A side is re-based per output row (64 x 64 tiles only): needs
 //   2 * (hiB - loB) + 1 <= kKeyedMaxSpreadSmall and nothing of A or w beyond A + w fitting int32.
-constexpr int kModeKeyed = 0, kModePlain = 1, kModeValue = 2, kModeKeyedRow = 3;
+// kModeAuto: keyed, keyed per row or plain, picked per product on the device from the ranges the
+//   descriptors point at (args.auto_limit, args.auto_row); mode_count then counts by picked variant.
+constexpr int kModeKeyed = 0, kModePlain = 1, kModeValue = 2, kModeKeyedRow = 3, kModeAuto = 4;
 // verify: the ranges in the descriptors are promises of the caller, not measurements (they need not
 // be attained, and rngA / rngW / rngB must be null).  The kernel then checks every element of A, w
 // and B it stages against them and ORs 2 into `flag` on a violation (results are then meaningless

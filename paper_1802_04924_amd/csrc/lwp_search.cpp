@@ -26,6 +26,19 @@ struct TableRef {
 
 struct EdgeGroup { int32_t keep; std::vector<int32_t> others; int32_t round; };
 
+// kernel variants of a node-elimination launch: arithmetic picked on the device (stored argmin
+// tables) or value-only (recomputed undo), on 64 x 64 or 128 x 128 tiles
+// (tile size = variant & 1; the arithmetic = variant / 2)
+enum { kVarAutoSmall = 0, kVarAutoLarge = 1, kVarValueSmall = 2, kVarValueLarge = 3,
+       kVarKeyedSmall = 4, kVarKeyedLarge = 5, kVarPlainSmall = 6, kVarPlainLarge = 7 };
+// How a search with stored argmin tables picks the arithmetic of its node eliminations:
+//   kArithPlain  compare/select everywhere: for searches so small that launches are bound by latency;
+//   kArithKeyed  packed keys on global offsets everywhere, launched speculatively: the fastest
+//                kernel, and the right one unless a table's values range widely; a product whose
+//                measured ranges do not allow the keys is skipped and flagged, and the search runs again with
+//   kArithAuto   the kernel that picks keys, keys re-based per row or compare/select per product.
+enum { kArithAuto = 0, kArithValue = 1, kArithKeyed = 2, kArithPlain = 3 };
+
 struct Layout {
     std::vector<EdgeGroup> groups;            // edge eliminations grouped per (round, kept edge)
     std::vector<TableRef> node_A, node_B, node_out;   // per node step (in plan order)
@@ -193,25 +206,22 @@ public:
     size_t pinned_bytes() const { return pin_result_ + (3 + (size_t)n_nodes_) * sizeof(int32_t); }
     void bind(char* ws, char* pin);
 
-    // Stored argmin tables need a kernel variant chosen from value ranges, so the ranges of the inputs
-    // are read back (the one mid-search synchronisation) before the descriptors are written.  With
-    // recomputed undo every elimination is value-only (no range condition) and overflow is judged on
-    // the device from measured ranges: nothing is read back, the host assumes full int32 ranges,
-    // writes the descriptors first and uploads them together with the offsets in one copy.
+    // Nothing the host decides depends on the tables' values: with stored argmin tables the
+    // elimination kernel picks its arithmetic variant per product on the device, from the ranges the
+    // producing launches measured; with recomputed undo every elimination is value-only; overflow is
+    // judged on the device in both.  So the descriptors are written first, uploaded with one copy,
+    // and everything is enqueued without a read-back; the one synchronisation is at the end.
     lwp_status run(int32_t* out_cost, int32_t* out_strategy);
 
-    // The pieces of run() for a caller that prepares once and runs many times (recomputed undo
-    // only: nothing the host decides then depends on the tables' values).
+    // The pieces of run() for a caller that prepares once and runs many times.
     lwp_status prepare_replay();                 // descriptors for any int32 input, uploaded; synchronises
     lwp_status enqueue_all();                    // everything between the tables and the result copy
     lwp_status finish(int32_t* out_cost, int32_t* out_strategy) const;   // after the stream has drained
 
 private:
-    lwp_status upload_offsets();
     lwp_status measure_inputs();                 // w = t_c + t_s, ranges of w and of every input table
-    lwp_status read_input_ranges();              // stored undo only; synchronises
-    void assume_full_ranges();
-    lwp_status write_descriptors();              // range propagation, descriptors, launch list
+    lwp_status write_descriptors(int arith);     // descriptors, launch list; arith: see kArith*
+    lwp_status attempt(int arith, bool replay_prepare);
     lwp_status upload_descriptors();
     lwp_status enqueue_eliminations();
     lwp_status enqueue_residual_and_undo();
@@ -240,7 +250,7 @@ private:
     Plan plan_;
     Layout L_;
     WsLayout W_{};
-    size_t head_in_bytes_ = 0, pin_head_ = 0, pin_desc_ = 0, pin_result_ = 0;
+    size_t pin_desc_ = 0, pin_result_ = 0;
     int32_t n_comp_ = 0, rng_w0_ = 0, rng_node0_ = 0, rng_group0_ = 0;
     // device
     char* ws_ = nullptr;
@@ -250,7 +260,6 @@ private:
     char* db_ = nullptr;         // descriptor block on the device
     // pinned host
     char* hb_ = nullptr;         // mirror of the descriptor block
-    int32_t* h_stats_ = nullptr;
     int32_t* h_result_ = nullptr;
     // launches
     std::vector<RoundWork> rounds_;
@@ -268,9 +277,7 @@ lwp_status Search::plan() {
         return fail(ctx_, LWP_E_NOT_REDUCIBLE, "a residual component has more than 2^32 strategies to enumerate");
     L_ = plan_buffers(plan_, n_nodes_, n_edges_, edges_, Cn_, !stored_);
     W_ = layout_workspace(plan_, L_, n_nodes_, n_edges_, stored_);
-    head_in_bytes_ = (2 + 2 * (size_t)(n_edges_ + n_nodes_)) * sizeof(int32_t);
-    pin_head_ = 0;
-    pin_desc_ = align_up(head_in_bytes_, 256);
+    pin_desc_ = 0;
     pin_result_ = pin_desc_ + align_up(W_.desc_bytes, 256);
     n_comp_ = (int32_t)(plan_.pairs.size() + plan_.singles.size() + plan_.comps.size());
     // index of the range pair of: input edge e | w of node v | output of node step | output of group
@@ -292,7 +299,6 @@ void Search::bind(char* ws, char* pin) {
     d_result_ = reinterpret_cast<int32_t*>(ws + W_.result);
     db_ = ws + W_.desc;
     hb_ = pin + pin_desc_;
-    h_stats_ = reinterpret_cast<int32_t*>(pin + pin_head_) + 2;
     h_result_ = reinterpret_cast<int32_t*>(pin + pin_result_);
     if (!L_.uniform) {           // rows and tables of different sizes: the kernels need their offsets
         int64_t* h_offs = reinterpret_cast<int64_t*>(hb_ + W_.offs);
@@ -302,35 +308,33 @@ void Search::bind(char* ws, char* pin) {
 }
 
 lwp_status Search::run(int32_t* out_cost, int32_t* out_strategy) {
-    // A small search is bound by latency, not arithmetic: reading the ranges back to pick the
-    // faster kernel variant costs more than the plain variant loses, so it is skipped and every
-    // elimination runs on the variant that needs no range (overflow is still found on the device).
     int64_t updates = 0;
     for (size_t q = 0; q < L_.node_A.size(); ++q) updates += (int64_t)L_.node_A[q].rows * L_.node_A[q].cols * L_.node_B[q].cols;
-    constexpr int64_t kReadBackPaysFrom = (int64_t)1 << 29;
-    if (stored_ && updates >= kReadBackPaysFrom) {
-        if (lwp_status s = upload_offsets()) return s;
-        if (lwp_status s = measure_inputs()) return s;
-        if (lwp_status s = read_input_ranges()) return s;
-        if (lwp_status s = write_descriptors()) return s;
-        if (lwp_status s = upload_descriptors()) return s;
-    } else {
-        assume_full_ranges();
-        if (lwp_status s = write_descriptors()) return s;
+    // Below this size launches are bound by latency, not arithmetic, and the kernel with the least
+    // start-up work wins (measured: AlexNet- and VGG-16-shaped searches with 256 configurations).
+    constexpr int64_t kKeysPayFrom = (int64_t)1 << 29;
+    int arith = !stored_ ? kArithValue : (updates < kKeysPayFrom ? kArithPlain : (ctx_->keys_failed ? kArithAuto : kArithKeyed));
+    for (;;) {
+        if (lwp_status s = write_descriptors(arith)) return s;
         if (lwp_status s = upload_descriptors()) return s;      // the offsets travel with the block
         if (lwp_status s = measure_inputs()) return s;
+        if (lwp_status s = enqueue_eliminations()) return s;
+        if (lwp_status s = enqueue_residual_and_undo()) return s;
+        if (lwp_status s = enqueue_result_copy()) return s;
+        LWP_HIP(ctx_, hipStreamSynchronize(stream_));
+        if (arith == kArithKeyed && (h_result_[2 + n_nodes_] & 4)) {
+            // some table's values range too widely for packed keys on global offsets: once more with
+            // the kernel that picks per product; later searches of this context start there
+            ctx_->keys_failed = true;
+            arith = kArithAuto;
+            continue;
+        }
+        return finish(out_cost, out_strategy);
     }
-    if (lwp_status s = enqueue_eliminations()) return s;
-    if (lwp_status s = enqueue_residual_and_undo()) return s;
-    if (lwp_status s = enqueue_result_copy()) return s;
-    LWP_HIP(ctx_, hipStreamSynchronize(stream_));
-    return finish(out_cost, out_strategy);
 }
 
 lwp_status Search::prepare_replay() {
-    if (stored_) return fail(ctx_, LWP_E_INVAL, "a replayed search recomputes the argmin in the undo pass");
-    assume_full_ranges();
-    if (lwp_status s = write_descriptors()) return s;
+    if (lwp_status s = write_descriptors(stored_ ? kArithAuto : kArithValue)) return s;
     if (lwp_status s = upload_descriptors()) return s;
     LWP_HIP(ctx_, hipStreamSynchronize(stream_));
     return LWP_OK;
@@ -341,12 +345,6 @@ lwp_status Search::enqueue_all() {
     if (lwp_status s = enqueue_eliminations()) return s;
     if (lwp_status s = enqueue_residual_and_undo()) return s;
     return enqueue_result_copy();
-}
-
-lwp_status Search::upload_offsets() {
-    if (L_.uniform) return LWP_OK;
-    LWP_HIP(ctx_, hipMemcpyAsync(db_ + W_.offs, hb_ + W_.offs, W_.offs_bytes, hipMemcpyHostToDevice, stream_));
-    return LWP_OK;
 }
 
 lwp_status Search::measure_inputs() {
@@ -366,25 +364,14 @@ lwp_status Search::measure_inputs() {
     return LWP_OK;
 }
 
-lwp_status Search::read_input_ranges() {
-    LWP_HIP(ctx_, hipMemcpyAsync(h_stats_ - 2, d_head_, head_in_bytes_, hipMemcpyDeviceToHost, stream_));
-    LWP_HIP(ctx_, hipStreamSynchronize(stream_));
-    for (int32_t v = 0; v < n_nodes_; ++v)
-        if (h_stats_[2 * (rng_w0_ + v)] > h_stats_[2 * (rng_w0_ + v) + 1]) return fail(ctx_, LWP_E_OVERFLOW, "t_c + t_s leaves int32");
-    return LWP_OK;
-}
-
-void Search::assume_full_ranges() {
-    for (int32_t t = 0; t < n_edges_ + n_nodes_; ++t) { h_stats_[2 * t] = (int32_t)kI32Min; h_stats_[2 * t + 1] = (int32_t)kI32Max; }
-}
-
-// Propagates value ranges through the plan (every sum any kernel forms must fit int32) and writes
-// the descriptors straight into the pinned mirror of the device block.
-lwp_status Search::write_descriptors() {
+// Writes the descriptors straight into the pinned mirror of the device block and fixes the launch
+// list.  The descriptors promise nothing about the values (full int32 ranges): every kernel reads
+// the ranges its producers measured (rngA / rngB / rngW) and tests on the device what it needs --
+// key widths, and that no sum leaves int32; the flag those tests set comes back with the result.
+lwp_status Search::write_descriptors(int arith) {
     const Plan& plan = plan_;
     const Layout& L = L_;
     const bool stored = stored_;
-    const int32_t* stats = h_stats_;
     NodeDesc* nd = reinterpret_cast<NodeDesc*>(hb_ + W_.node_desc);
     EdgeDesc* ed = reinterpret_cast<EdgeDesc*>(hb_ + W_.edge_desc);
     const int32_t** src_ptrs = reinterpret_cast<const int32_t**>(hb_ + W_.src_ptrs);
@@ -396,19 +383,12 @@ lwp_status Search::write_descriptors() {
     size_t n_tbeg = 0;
     rounds_.clear();
 
-    std::vector<Range> er(n_edges_), wr(n_nodes_);
     std::vector<int32_t> erng(n_edges_);          // range-pair index of the edge's current table
-    for (int32_t e = 0; e < n_edges_; ++e) { er[e] = {stats[2 * e], stats[2 * e + 1]}; erng[e] = e; }
-    for (int32_t v = 0; v < n_nodes_; ++v) wr[v] = {stats[2 * (rng_w0_ + v)], stats[2 * (rng_w0_ + v) + 1]};
+    for (int32_t e = 0; e < n_edges_; ++e) erng[e] = e;
     // Node eliminations of one round are independent; those of equal kernel variant share a
     // launch if they agree in shape (Ci, Cj, Ck) or run on 64 x 64 tiles (a launch of mixed shapes),
     // so the descriptors of a round are ordered by (variant, shape).
-    struct NodeWork { NodeDesc d; int64_t spread, spread_row; int32_t Ci, Cj, Ck; int variant; };
-    // The propagated bounds are worst cases and grow along a chain although the minima do not.
-    // Where they cannot prove that a step stays inside int32 the step is not refused: it runs on a
-    // variant without range conditions and every kernel checks the tables' measured ranges (or
-    // the sums themselves) on the device; the flag they set is read back with the result.
-    auto sat = [](Range r) { return Range{std::max(r.lo, kI32Min), std::min(r.hi, kI32Max)}; };
+    struct NodeWork { NodeDesc d; int32_t Ci, Cj, Ck; int variant; };
     size_t ni = 0, gi = 0, nsrc = 0, t = 0;
     const size_t n = plan.steps.size();
     std::vector<NodeWork> work;
@@ -419,9 +399,6 @@ lwp_status Search::write_descriptors() {
         while (t < n && plan.steps[t].round == round && plan.steps[t].kind == 1) {
             // one group = all steps adding into the same kept edge
             const auto& g = L.groups[gi];
-            Range r = er[g.keep];
-            for (int32_t o : g.others) r = {r.lo + er[o].lo, r.hi + er[o].hi};
-            er[g.keep] = sat(r);
             erng[g.keep] = rng_group0_ + (int32_t)gi;
             ed[gi].out = slot_ptr(L.group_out[gi]);
             ed[gi].rngOut = d_stats_ + 2 * (int64_t)erng[g.keep];
@@ -440,8 +417,6 @@ lwp_status Search::write_descriptors() {
         work.clear();
         while (t < n && plan.steps[t].round == round && plan.steps[t].kind == 0) {
             const lwp_step& s = plan.steps[t];
-            const Range rA = er[s.e1], rw = wr[s.j], rB = er[s.e2];
-            const bool proven = fits(rA.lo + rw.lo) && fits(rA.hi + rw.hi) && fits(rA.lo + rw.lo + rB.lo) && fits(rA.hi + rw.hi + rB.hi);
             const TableRef &tA = L.node_A[ni], &tB = L.node_B[ni], &tO = L.node_out[ni];
             NodeWork nw{};
             NodeDesc& d = nw.d;
@@ -449,40 +424,27 @@ lwp_status Search::write_descriptors() {
             d.A = table_ptr(tA); d.w = w_ptr(s.j); d.B = table_ptr(tB);
             d.out = slot_ptr(tO);
             d.arg = stored ? d_args_ + L.node_arg_off[ni] : nullptr;
-            d.loA = (int32_t)rA.lo; d.hiA = (int32_t)rA.hi; d.loW = (int32_t)rw.lo; d.hiW = (int32_t)rw.hi;
-            d.loB = (int32_t)rB.lo; d.hiB = (int32_t)rB.hi;
+            d.loA = d.loW = d.loB = (int32_t)kI32Min;
+            d.hiA = d.hiW = d.hiB = (int32_t)kI32Max;
             d.rngA = d_stats_ + 2 * (int64_t)erng[s.e1];
             d.rngB = d_stats_ + 2 * (int64_t)erng[s.e2];
             d.rngW = d_stats_ + 2 * (int64_t)(rng_w0_ + s.j);
             d.rngOut = d_stats_ + 2 * (int64_t)(rng_node0_ + (int32_t)ni);
-            nw.spread = proven ? keyed_spread(rA, rw, rB) : (int64_t)1 << 62;   // unproven: no keys on global offsets
-            nw.spread_row = keyed_row_spread(rB);       // keys re-based per row need a bound on B only
             nw.Ci = tA.rows; nw.Cj = tA.cols; nw.Ck = tB.cols;
             d.Ci = nw.Ci; d.Cj = nw.Cj; d.Ck = nw.Ck;
             work.push_back(nw);
             ud[ni] = {d.arg, d.A, d.w, d.B, s.j, s.i, s.k, s.round, nw.Cj, nw.Ck, (int32_t)n0, 0};
-            // any fixed c bounds the minimum from above; take the c with the smallest w
-            er[s.e1] = sat({rA.lo + rw.lo + rB.lo, rA.hi + rw.lo + rB.hi});
             erng[s.e1] = rng_node0_ + (int32_t)ni;
             ++ni; ++t;
         }
-        // kernel variant per product: packed keys on the preferred tile size if the spread
-        // allows, else packed keys on 128 x 128 tiles (one more bit), else keys re-based per row
-        // (64 x 64 tiles; one more pass over A, but only B's spread counts), else the plain variant;
-        // 0 keyed small, 1 keyed large, 2 plain small, 3 plain large, 4 value small, 5 value large,
-        // 6 keyed per row (small)
+        // kernel variant per product: the search's arithmetic, and the tile size from the number of
+        // tiles the products of that shape make
         auto shape_of = [](const NodeWork& a) { return std::make_tuple(a.Ci, a.Cj, a.Ck); };
         std::map<std::tuple<int32_t, int32_t, int32_t>, int64_t> shape_count;
         for (const NodeWork& x : work) ++shape_count[shape_of(x)];
         for (NodeWork& x : work) {
-            const int64_t same = shape_count[shape_of(x)];
-            const bool prefer_small = want_small_tiles(x.Ci, x.Cj, x.Ck, same);
-            const bool large_fills_chip = large_tiles(x.Ci, x.Ck, same) >= 512;
-            if (!stored) x.variant = prefer_small ? 4 : 5;     // value-only: no range condition
-            else if (x.spread <= (prefer_small ? kKeyedMaxSpreadSmall : kKeyedMaxSpreadLarge)) x.variant = prefer_small ? 0 : 1;
-            else if (x.spread <= kKeyedMaxSpreadLarge && large_fills_chip) x.variant = 1;
-            else if (x.spread_row <= kKeyedMaxSpreadSmall && keyed_row_pays(x.Ci, x.Cj, x.Ck, same)) x.variant = 6;
-            else x.variant = prefer_small ? 2 : 3;
+            const bool prefer_small = want_small_tiles(x.Ci, x.Cj, x.Ck, shape_count[shape_of(x)]);
+            x.variant = 2 * arith + (prefer_small ? 0 : 1);
         }
         order.resize(work.size());
         for (size_t q = 0; q < order.size(); ++q) order[q] = q;
@@ -493,7 +455,7 @@ lwp_status Search::write_descriptors() {
             const int v = work[order[a]].variant;
             size_t b = a;
             while (b < order.size() && work[order[b]].variant == v) ++b;
-            const bool small = (v == 0 || v == 2 || v == 4 || v == 6);
+            const bool small = (v & 1) == 0;
             const bool one_shape = shape_of(work[order[a]]) == shape_of(work[order[b - 1]]);
             if (small && !one_shape) {
                 // one launch over all shapes: product q owns tiles [tile_begin[q], tile_begin[q+1])
@@ -576,8 +538,9 @@ lwp_status Search::enqueue_eliminations() {
         }
         for (const NodeLaunch& nl : r.launches) {
             const int v = nl.variant;
-            const bool keyed = v < 2 || v == 6, small = (v == 0 || v == 2 || v == 4 || v == 6);
-            const int mode = v == 6 ? kModeKeyedRow : (v >= 4 ? kModeValue : (keyed ? kModeKeyed : kModePlain));
+            const bool small = (v & 1) == 0;
+            const int arith = v / 2;
+            const int mode = arith == kArithAuto ? kModeAuto : (arith == kArithValue ? kModeValue : (arith == kArithKeyed ? kModeKeyed : kModePlain));
             const int tile = small ? kTileSmall : kTileLarge;
             NodeArgs na{};
             na.descs = d_nd + nl.first;
@@ -586,12 +549,19 @@ lwp_status Search::enqueue_eliminations() {
             na.tilesN = (nl.Ck + tile - 1) / tile;
             const bool mixed = nl.tile_begin >= 0;
             if (mixed) { na.tile_begin = d_tbeg + nl.tile_begin; na.total_tiles = nl.total_tiles; }
-            ScopedTimer tm(ctx_, 0, nl.updates, keyed);
+            if (mode == kModeAuto) {
+                na.auto_limit = small ? kKeyedMaxSpreadSmall : kKeyedMaxSpreadLarge;
+                // a launch of mixed shapes is judged by its products' common size class
+                na.auto_row = keyed_row_pays(mixed ? 1 : nl.Ci, mixed ? 1 : nl.Cj, mixed ? 1 : nl.Ck, mixed ? nl.updates : (int64_t)nl.count) ? 1 : 0;
+            }
+            na.speculative = arith == kArithKeyed ? 1 : 0;
+            na.mode_count = ctx_->dstate ? ctx_->dstate + 1 : nullptr;
+            ScopedTimer tm(ctx_, 0, nl.updates, arith == kArithKeyed);
             // a launch of mixed shapes splits by its longest product: every product divides its own
             // stages among the parts, and parts beyond a short product's stages see only padding
-            const int kparts = choose_kparts(mixed ? nl.total_tiles : (int64_t)na.tilesM * na.tilesN * na.batch, nl.split_Cj, small);
-            if (kparts > 1) { if (lwp_status s2 = ensure_split_buffers(ctx_)) return s2; }
-            set_split(ctx_, na, kparts);
+            const Split split = choose_split(mixed ? nl.total_tiles : (int64_t)na.tilesM * na.tilesN * na.batch, nl.split_Cj, small);
+            if (split.kparts > 1) { if (lwp_status s2 = ensure_split_buffers(ctx_)) return s2; }
+            set_split(ctx_, na, split);
             LWP_HIP(ctx_, launch_minplus(na, mode, small, st));
         }
     }
@@ -620,7 +590,7 @@ lwp_status Search::enqueue_result_copy() {
 }
 
 lwp_status Search::finish(int32_t* out_cost, int32_t* out_strategy) const {
-    if (h_result_[2 + n_nodes_]) return fail(ctx_, LWP_E_OVERFLOW, "a sum may leave int32 (found on the device from the tables' actual ranges)");
+    if (h_result_[2 + n_nodes_] & 3) return fail(ctx_, LWP_E_OVERFLOW, "a sum may leave int32 (found on the device from the tables' actual ranges)");
     // the total is formed in 64 bits on the device
     const int64_t total = (int64_t)(((uint64_t)(uint32_t)h_result_[1] << 32) | (uint32_t)h_result_[0]);
     if (!fits(total)) return fail(ctx_, LWP_E_OVERFLOW, "the total cost leaves int32");
@@ -684,6 +654,7 @@ lwp_status lwp_search_plan_create(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edges
     if (e != hipSuccess) { (void)hipGetLastError(); return bail(fail(ctx, LWP_E_NOMEM, std::string("plan pinned buffer: ") + hipGetErrorString(e))); }
     plan->pin = static_cast<char*>(p);
     if (lwp_status s = ensure_split_buffers(ctx)) return bail(s);
+    if (lwp_status s = ensure_state(ctx)) return bail(s);
     search.bind(plan->ws, plan->pin);
     if (lwp_status s = search.prepare_replay()) return bail(s);
     *out = plan;
@@ -770,6 +741,7 @@ lwp_status lwp_search_graph_ragged(lwp_ctx* ctx, int32_t n_nodes, int32_t n_edge
     if (lwp_status s = search.plan()) return s;
     if (lwp_status s = ensure_workspace(ctx, search.workspace_bytes())) return s;
     if (lwp_status s = ensure_pinned(ctx, search.pinned_bytes())) return s;
+    if (lwp_status s = ensure_state(ctx)) return s;
     search.bind(ctx->ws, ctx->pin);
     return search.run(out_cost, out_strategy);
 }

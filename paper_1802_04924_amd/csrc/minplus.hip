@@ -70,35 +70,40 @@ __device__ __forceinline__ int auto_variant(long long loA, long long hiA, long l
     return kModePlain;
 }
 
-template <int MODE, int RB, int TK, bool MIXED = false, bool VERIFY = false>
-__global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) void minplus_kernel(const NodeArgs p) {
-    static_assert(!MIXED || RB == 4, "launches of mixed shapes use 64 x 64 tiles");
-    static_assert(!(MIXED && VERIFY), "promised ranges come with strided addressing");
-    constexpr bool ROW = (MODE == kModeKeyedRow);  // keys re-based per output row
-    constexpr bool KEYED = (MODE == kModeKeyed) || ROW;
-    static_assert(!ROW || RB == 4, "row-rebased keys use 64 x 64 tiles");
-    constexpr bool VALUE = (MODE == kModeValue);   // minimum only: no argmin, no keys, any int32
-    constexpr bool PIPE = RB == 4;   // LDS reads issued one step ahead of the arithmetic
-    constexpr int TM = 16 * RB, TN = 16 * RB;   // output tile
-    constexpr int EP = TM * TK / NT;            // elements of A and of B each thread stages per stage
-    constexpr int QUADS = RB / 4;
-    static_assert(EP % 4 == 0 && TK % EP == 0 && TN % EP == 0 && (TN / EP) * TK == NT, "staging assignment");
-    __shared__ __attribute__((aligned(16))) uint32_t As[2][TK][TM];   // [stage][c][a]  (A transposed)
-    __shared__ __attribute__((aligned(16))) uint32_t Bs[2][TK][TN];   // [stage][c][b]
+// What one workgroup works on: the product's descriptor, its tile of that product, and -- for a tile
+// shared by several workgroups -- its part of the c range.
+struct TileWork {
+    NodeDesc d;
+    int tl;                 // tile index inside the product
+    int part, kparts;       // this workgroup's part of the c range (kparts == 1: the whole range)
+    uint32_t split_idx;     // index of a shared tile among the launch's shared tiles
+};
 
-    // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Give every XCD a
-    // contiguous range of logical ids, and walk the tiles of a product in panels of 8 tile rows,
-    // column by column: 64 consecutive ids (the tiles resident on one XCD at a time) then form an
-    // 8 x 8 block that shares 8 row strips of A and 8 column strips of B.
+// Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Give every XCD a
+// contiguous range of logical ids, and walk the tiles of a product in panels of 8 tile rows,
+// column by column: 64 consecutive ids (the tiles resident on one XCD at a time) then form an
+// 8 x 8 block that shares 8 row strips of A and 8 column strips of B.
+// Split tiles (64 x 64 tiles only): the launch's first n_whole tiles have one workgroup each;
+// every later tile is shared by kparts consecutive workgroups, each with a part of the c range.
+// The shared tiles come last in dispatch order, so that the short workgroups fill the launch's
+// last, partly empty round of workgroup slots.
+template <int RB, bool MIXED>
+__device__ __forceinline__ void decode_work(const NodeArgs& p, TileWork& w) {
     uint32_t bid = blockIdx.x;
-    const uint32_t total = gridDim.x;
-    if ((total & 7u) == 0u) bid = (bid & 7u) * (total >> 3) + (bid >> 3);
-    // kparts > 1: that many consecutive workgroups share one tile, each with a part of the c range
-    const int kparts = (RB == 4) ? p.kparts : 1;   // only 64 x 64 tiles are ever split
-    const int part = (kparts > 1) ? (int)(bid % (uint32_t)kparts) : 0;
-    if (kparts > 1) bid /= (uint32_t)kparts;
-    const uint32_t tile_global = bid;
-    int bi, tl;
+    const uint32_t n_whole = (RB == 4 && p.kparts > 1) ? (uint32_t)p.n_whole : gridDim.x;
+    w.kparts = 1; w.part = 0; w.split_idx = 0;
+    if (bid < n_whole) {
+        if ((n_whole & 7u) == 0u) bid = (bid & 7u) * (n_whole >> 3) + (bid >> 3);
+    } else {
+        uint32_t x = bid - n_whole;
+        const uint32_t rest = gridDim.x - n_whole;
+        if ((rest & 7u) == 0u) x = (x & 7u) * (rest >> 3) + (x >> 3);
+        w.kparts = p.kparts;
+        w.part = (int)(x % (uint32_t)w.kparts);
+        w.split_idx = x / (uint32_t)w.kparts;
+        bid = n_whole + w.split_idx;
+    }
+    int bi;
     if (MIXED) {
         // products of different shapes: find the one that owns this tile (uniform binary search)
         const int32_t __attribute__((address_space(1)))* tb0 = (const int32_t __attribute__((address_space(1)))*)(uintptr_t)p.tile_begin;
@@ -108,14 +113,13 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
             if ((uint32_t)tb0[mid] <= bid) lo = mid; else hi = mid;
         }
         bi = lo;
-        tl = (int)bid - tb0[lo];
+        w.tl = (int)bid - tb0[lo];
     } else {
         const int tiles = p.tilesM * p.tilesN;
         bi = bid / tiles;
-        tl = bid - bi * tiles;
+        w.tl = bid - bi * tiles;
     }
-
-    NodeDesc d;
+    NodeDesc& d = w.d;
     if (MIXED || p.descs) {
         d = p.descs[bi];
     } else {
@@ -127,16 +131,29 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
         if (d.rngW) d.rngW += (int64_t)bi * p.sR;
         if (d.rngB) d.rngB += (int64_t)bi * p.sR;
     }
-    // Guarded launch: is this product for this launch's variant?  Decided before anything else is
-    // loaded, so that a workgroup that is not needed costs one small read.
-    if (!MIXED && !VERIFY && p.guard) {
-        const int32_t __attribute__((address_space(1)))* ra_ = (const int32_t __attribute__((address_space(1)))*)(uintptr_t)d.rngA;
-        const int32_t __attribute__((address_space(1)))* rw_ = (const int32_t __attribute__((address_space(1)))*)(uintptr_t)d.rngW;
-        const int32_t __attribute__((address_space(1)))* rb_ = (const int32_t __attribute__((address_space(1)))*)(uintptr_t)d.rngB;
-        const int want = auto_variant(ra_[0], ra_[1], rw_[0], rw_[1], rb_[0], rb_[1], p.guard_limit, p.guard_row != 0);
-        if (want != MODE) return;          // uniform for the workgroup
-    }
-    if (p.mode_count && tl == 0 && part == 0 && threadIdx.x == 0) atomicAdd(&p.mode_count[MODE], 1);
+}
+
+// One workgroup's tile (or part of a shared tile).  smA / smB: the double-buffered LDS stages
+// (2 * TK * 16 RB words each), smRow: 16 RB words (row-rebased keys only), smMisc: 16 words.
+template <int MODE, int RB, int TK, bool MIXED, bool VERIFY>
+__device__ __forceinline__ void minplus_tile(const NodeArgs& p, const TileWork& work, uint32_t* smA, uint32_t* smB,
+                                             int32_t* smRow, int* smMisc) {
+    static_assert(!MIXED || RB == 4, "launches of mixed shapes use 64 x 64 tiles");
+    static_assert(!(MIXED && VERIFY), "promised ranges come with strided addressing");
+    constexpr bool ROW = (MODE == kModeKeyedRow);  // keys re-based per output row
+    constexpr bool KEYED = (MODE == kModeKeyed) || ROW;
+    static_assert(!ROW || RB == 4, "row-rebased keys use 64 x 64 tiles");
+    constexpr bool VALUE = (MODE == kModeValue);   // minimum only: no argmin, no keys, any int32
+    constexpr bool PIPE = RB == 4;   // LDS reads issued one step ahead of the arithmetic
+    constexpr int TM = 16 * RB, TN = 16 * RB;   // output tile
+    constexpr int EP = TM * TK / NT;            // elements of A and of B each thread stages per stage
+    constexpr int QUADS = RB / 4;
+    static_assert(EP % 4 == 0 && TK % EP == 0 && TN % EP == 0 && (TN / EP) * TK == NT, "staging assignment");
+    uint32_t (*As)[TK][TM] = reinterpret_cast<uint32_t (*)[TK][TM]>(smA);   // [stage][c][a]  (A transposed)
+    uint32_t (*Bs)[TK][TN] = reinterpret_cast<uint32_t (*)[TK][TN]>(smB);   // [stage][c][b]
+    const NodeDesc& d = work.d;
+    const int tl = work.tl, part = work.part, kparts = work.kparts;
+    const uint32_t split_idx = work.split_idx;
     // A workgroup that starts while older ones are in their arithmetic loops would get issue slots
     // only when those stall, and its start-up -- a chain of dependent loads with some scalar
     // arithmetic between them -- would take many times longer than on an idle compute unit.  Its
@@ -207,8 +224,13 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
             }
         } else {
             const int c = min(c0 + br, Cj - 1);
+            const gcptr Brow = B + (int64_t)c * Ck;
+            // opaque per stage: otherwise the clamped column offsets are hoisted out of the stage loop
+            // and sit in sixteen registers that the common (vector) path never uses
+            int col0 = b0 + bseg;
+            asm volatile("" : "+v"(col0));
 #pragma unroll
-            for (int q = 0; q < EP; ++q) rb[q] = B[(int64_t)c * Ck + min(b0 + bseg + q, Ck - 1)];
+            for (int q = 0; q < EP; ++q) rb[q] = Brow[min(col0 + q, Ck - 1)];
         }
         pA += TK; pW += TK; pB += (int64_t)TK * Ck;
     };
@@ -237,7 +259,7 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
     }
 
     // ---- row-rebased keys: minimum of A + w over this workgroup's c range, per tile row ----
-    __shared__ int32_t rmin[ROW ? TM : 1];
+    int32_t* rmin = smRow;
     if (ROW) {
         int32_t mn = 0x7fffffff;
         const int c_end = min(Cj, (s_first + n_g) * TK);
@@ -279,6 +301,13 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
         const long long spread = capl + (hiB - loB);
         cap = (uint32_t)capl;
         constexpr int TB_MIN = (TK <= 16) ? 5 : 6;               // a chunk holds at least one stage
+        // A launch made on the assumption that packed keys will do: where a product's ranges do not
+        // allow them, say so and leave the product alone (the caller then runs it another way).
+        // Nothing has been stored and no barrier passed yet; uniform for the workgroup.
+        if (!ROW && !VERIFY && p.speculative && spread > (1ll << (32 - TB_MIN)) - 2) {
+            if (d.flag && threadIdx.x == 0) atomicOr(d.flag, 4);
+            return;
+        }
         tb = TB_MIN;
         for (int t = 17; t > TB_MIN; --t)
             if (spread <= (1ll << (32 - t)) - 2) { tb = t; break; }
@@ -474,7 +503,7 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
     bool raw = KEYED;                          // m1 still holds keys (otherwise plain costs)
     if (RB == 4 && kparts > 1) {
         constexpr int CELLS = RB * RB;
-        int32_t* slab = p.scratch + ((int64_t)tile_global * kparts) * (2 * CELLS * NT);
+        int32_t* slab = p.scratch + ((int64_t)split_idx * kparts) * (2 * CELLS * NT);
         int32_t* mine = slab + (int64_t)part * (2 * CELLS * NT);
 #pragma unroll
         for (int i = 0; i < RB; ++i)
@@ -495,11 +524,11 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
         __syncthreads();
-        __shared__ int arrived;
-        if (tid == 0) arrived = __hip_atomic_fetch_add(&p.counters[tile_global], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        int& arrived = smMisc[0];
+        if (tid == 0) arrived = __hip_atomic_fetch_add(&p.counters[split_idx], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __syncthreads();
         if (arrived != kparts - 1) return;     // uniform for the workgroup
-        if (tid == 0) __hip_atomic_store(&p.counters[tile_global], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
+        if (tid == 0) __hip_atomic_store(&p.counters[split_idx], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
         // two parts at a time, all of their values in flight together (one round trip to the
         // memory side per pair); folded in ascending part order
         for (int q = 0; q < kparts; q += 2) {
@@ -563,9 +592,12 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
             }
         }
     }
+    // one workgroup per tile gets here (of a shared tile: the one that merged the parts); count the
+    // product once, off the start-up path
+    if (p.mode_count && tl == 0 && tid == 0) atomicAdd(&p.mode_count[MODE], 1);
     if (d.rngOut) {   // leave the measured range of this table for the launches that consume it
         vmin = wave_min_i32(vmin); vmax = wave_max_i32(vmax);
-        __shared__ int red[2 * (NT / 64)];
+        int* red = smMisc + 1;
         if ((tid & 63) == 0) { red[2 * (tid >> 6)] = vmin; red[2 * (tid >> 6) + 1] = vmax; }
         __syncthreads();
         if (tid == 0) {
@@ -575,25 +607,67 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
     }
 }
 
+template <int MODE, int RB, int TK, bool MIXED = false, bool VERIFY = false>
+__global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) void minplus_kernel(const NodeArgs p) {
+    __shared__ __attribute__((aligned(16))) uint32_t smA[2 * TK * 16 * RB];
+    __shared__ __attribute__((aligned(16))) uint32_t smB[2 * TK * 16 * RB];
+    __shared__ int32_t smRow[MODE == kModeKeyedRow ? 16 * RB : 1];
+    __shared__ int smMisc[16];
+    TileWork work;
+    decode_work<RB, MIXED>(p, work);
+    minplus_tile<MODE, RB, TK, MIXED, VERIFY>(p, work, smA, smB, smRow, smMisc);
+}
+
+// The variant is picked here, per product, from the measured ranges of its operands: the host
+// then needs to know nothing about the tables' values and no value has to travel back to it.
+// auto_limit: largest spread packed keys on global offsets may have at this tile size; auto_row:
+// keys re-based per row are a candidate (64 x 64 tiles, launches large enough for their extra pass).
+template <int RB, int TK, bool MIXED = false>
+__global__ __launch_bounds__(NT, RB == 4 ? 4 : 2) void minplus_auto_kernel(const NodeArgs p) {
+    __shared__ __attribute__((aligned(16))) uint32_t smA[2 * TK * 16 * RB];
+    __shared__ __attribute__((aligned(16))) uint32_t smB[2 * TK * 16 * RB];
+    __shared__ int32_t smRow[RB == 4 ? 16 * RB : 1];
+    __shared__ int smMisc[16];
+    TileWork work;
+    decode_work<RB, MIXED>(p, work);
+    using gcptr = const int32_t __attribute__((address_space(1)))*;
+    const NodeDesc& d = work.d;
+    long long loA = d.loA, hiA = d.hiA, loB = d.loB, hiB = d.hiB, loW = d.loW, hiW = d.hiW;
+    if (d.rngA) { const gcptr r = (gcptr)(uintptr_t)d.rngA; loA = max(loA, (long long)r[0]); hiA = min(hiA, (long long)r[1]); }
+    if (d.rngB) { const gcptr r = (gcptr)(uintptr_t)d.rngB; loB = max(loB, (long long)r[0]); hiB = min(hiB, (long long)r[1]); }
+    if (d.rngW) { const gcptr r = (gcptr)(uintptr_t)d.rngW; loW = max(loW, (long long)r[0]); hiW = min(hiW, (long long)r[1]); }
+    int want = auto_variant(loA, hiA, loW, hiW, loB, hiB, p.auto_limit, RB == 4 && p.auto_row != 0);
+    want = __builtin_amdgcn_readfirstlane(want);         // the same for the whole workgroup: a scalar branch
+    if (want == kModeKeyed) minplus_tile<kModeKeyed, RB, TK, MIXED, false>(p, work, smA, smB, smRow, smMisc);
+    else if (RB == 4 && want == kModeKeyedRow) minplus_tile<kModeKeyedRow, 4, 32, MIXED, false>(p, work, smA, smB, smRow, smMisc);
+    else minplus_tile<kModePlain, RB, TK, MIXED, false>(p, work, smA, smB, smRow, smMisc);
+}
+
 }  // namespace
 
 hipError_t launch_minplus(const NodeArgs& args, int mode, bool small_tiles, hipStream_t stream, bool verify) {
     const int kparts = args.kparts > 1 ? args.kparts : 1;
     const bool mixed = args.tile_begin != nullptr;
-    const int64_t blocks = (mixed ? (int64_t)args.total_tiles : (int64_t)args.tilesM * args.tilesN * args.batch) * kparts;
-    if (blocks <= 0 || blocks > 0x7fffffffLL || args.batch < 1) return hipErrorInvalidValue;
+    const int64_t tiles = mixed ? (int64_t)args.total_tiles : (int64_t)args.tilesM * args.tilesN * args.batch;
+    const int64_t n_whole = kparts > 1 ? (int64_t)args.n_whole : tiles;
+    if (tiles <= 0 || args.batch < 1 || n_whole < 0 || n_whole > tiles) return hipErrorInvalidValue;
+    const int64_t n_shared = tiles - n_whole;
+    const int64_t blocks = n_whole + n_shared * kparts;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     if (kparts > 1 && (!small_tiles || !args.scratch || !args.counters)) return hipErrorInvalidValue;
-    if (kparts > 1 && (kparts > kSplitMaxParts || blocks / kparts > kSplitMaxTiles || blocks > kSplitMaxWorkgroups))
+    if (kparts > 1 && (kparts > kSplitMaxParts || n_shared > kSplitMaxTiles || n_shared * kparts > kSplitMaxWorkgroups))
         return hipErrorInvalidValue;   // beyond the capacity of the split-tile buffers
     if (mixed && (!small_tiles || !args.descs)) return hipErrorInvalidValue;
     if (mode == kModeKeyedRow && !small_tiles) return hipErrorInvalidValue;
-    if (verify && (mixed || args.descs || args.guard || args.base.rngA || args.base.rngW || args.base.rngB)) return hipErrorInvalidValue;
-    if (args.guard && (mixed || args.descs || mode == kModeValue || !args.base.rngA || !args.base.rngW || !args.base.rngB))
-        return hipErrorInvalidValue;
+    if (verify && (mixed || args.descs || mode == kModeAuto || args.base.rngA || args.base.rngW || args.base.rngB)) return hipErrorInvalidValue;
     dim3 grid((unsigned)blocks), block(NT);
 #define LWP_LAUNCH(MODE, RB, TK, MIXED, VERIFY) \
     hipLaunchKernelGGL((minplus_kernel<MODE, RB, TK, MIXED, VERIFY>), grid, block, 0, stream, args)
-    if (mixed) {
+    if (mode == kModeAuto) {
+        if (mixed) hipLaunchKernelGGL((minplus_auto_kernel<4, 32, true>), grid, block, 0, stream, args);
+        else if (small_tiles) hipLaunchKernelGGL((minplus_auto_kernel<4, 32, false>), grid, block, 0, stream, args);
+        else hipLaunchKernelGGL((minplus_auto_kernel<8, 16, false>), grid, block, 0, stream, args);
+    } else if (mixed) {
         if (mode == kModeKeyed) LWP_LAUNCH(kModeKeyed, 4, 32, true, false);
         else if (mode == kModeKeyedRow) LWP_LAUNCH(kModeKeyedRow, 4, 32, true, false);
         else if (mode == kModeValue) LWP_LAUNCH(kModeValue, 4, 32, true, false);

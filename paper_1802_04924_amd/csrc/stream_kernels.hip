@@ -378,6 +378,13 @@ __global__ __launch_bounds__(kUndoThreads) void back_substitute_kernel(
         result[0] = (int32_t)(tot & 0xffffffffll);
         result[1] = (int32_t)(tot >> 32);
     }
+    // An elimination that a speculative launch skipped left its tables unwritten: argmin entries
+    // would then be arbitrary numbers, not configurations, so nothing is looked up through them.
+    // (The flag is final: every launch that can set it has completed before this kernel starts.)
+    if (flag && (*flag & 4)) {
+        if (threadIdx.x == 0) result[2 + n_nodes] = *flag;
+        return;
+    }
     // walk the rounds backwards; node eliminations of one round never depend on each other
     int hi = n_undo;
     while (hi > 0) {

@@ -127,6 +127,26 @@ def test_eliminate_node_split_tiles_repeatedly(ctx):
             check_products(ctx, A, w, B)
 
 
+@pytest.mark.parametrize("shape", [(17, 512, 100, 512), (1, 2100, 300, 2100), (3, 1200, 2050, 1230), (65, 256, 512, 256)])
+@pytest.mark.parametrize("hi", [3, 1 << 20, (1 << 28) - 1])
+def test_eliminate_node_last_round_of_workgroups_shares_its_tiles(ctx, shape, hi):
+    # launches of a few more tiles than a multiple of 1024 workgroup slots: the tiles beyond the last full
+    # round are shared by several workgroups each (one launch with whole and shared tiles side by side);
+    # heavy ties / packed keys / compare-select, ragged edges, a batch whose last product is cut in two
+    batch, Ci, Cj, Ck = shape
+    tiles = batch * (-(-Ci // 64)) * (-(-Ck // 64))
+    assert tiles > 1024 and 0 < tiles % 1024 <= 512
+    rng = np.random.default_rng(tiles + hi % 1000)
+    A = rng.integers(0, hi, size=(batch, Ci, Cj), endpoint=True, dtype=np.int32)
+    w = rng.integers(0, hi, size=(batch, Cj), endpoint=True, dtype=np.int32)
+    B = rng.integers(0, hi, size=(batch, Cj, Ck), endpoint=True, dtype=np.int32)
+    check_products(ctx, A, w, B)
+    out, _ = ctx.eliminate_node(dev(A), dev(w), dev(B), want_argmin=False)
+    ctx.synchronize()
+    for b in range(0, batch, max(1, batch // 4)):
+        assert np.array_equal(out[b].cpu().numpy(), oracle.minplus_argmin(A[b], w[b], B[b])[0])
+
+
 def test_split_tiles_never_read_a_previous_launchs_partials(ctx):
     # the parts of a tile meet in scratch memory that every launch reuses: with fresh data per launch
     # a part published too late (or read too early) would show as a result of the launch before
@@ -188,7 +208,7 @@ def test_eliminate_node_keys_rebased_per_row(ctx, shape, b_bits):
         check_products(ctx, A[:1, :, :64], w[:1, :64], B[:1, :64, :], expect_keyed=False)
 
 
-def test_search_with_wide_node_costs_uses_keys_rebased_per_row(ctx):
+def test_search_with_wide_node_costs_stays_on_packed_keys(ctx):
     # node costs from microseconds to half a second, transfers up to a few milliseconds: the shape
     # of real cost tables (Sec. 5.1), at a size where arithmetic dominates
     p = wl.chain_problem(6, 700, 3, tc_range=(1000, 1 << 29), ts_range=(0, 1 << 20), tx_range=(0, 1 << 22))
@@ -198,8 +218,12 @@ def test_search_with_wide_node_costs_uses_keys_rebased_per_row(ctx):
         run_search(ctx, p, schedule)
     prof = ctx.profile_read()
     ctx.profile_enable(False)
-    # run_search runs every search twice: stored argmin (all launches on keys) and recomputed (value-only)
-    assert prof["keyed_launches"] * 2 == prof["node_launches"] > 0
+    # run_search runs every search twice: with stored argmin (every product on packed keys: on global
+    # offsets where clamping at the largest possible result absorbs the width of the node costs, else
+    # re-based per row) and with recomputed argmin (value-only)
+    n_products = 2 * (p["n_nodes"] - 2)
+    assert prof["products_keyed"] + prof["products_keyed_row"] == n_products and prof["products_value"] == n_products
+    assert prof["products_plain"] == 0
     Cn = np.array([700, 650, 701, 300, 900, 640], np.int32)      # the same with per-node counts
     edges = wl.chain_edges(6)
     tc, ts, tx = wl.ragged_tables(6, edges, Cn, 8, 0, 1 << 22)
@@ -538,19 +562,48 @@ def test_search_beyond_the_provable_bounds(ctx):
         run_search(ctx, p, schedule)
 
 
-def test_search_sizes_around_the_read_back_threshold(ctx):
-    # below 2^29 cell updates a search with stored argmin skips the read-back of value ranges and
-    # runs every elimination on the plain variant; from there on it reads them back and uses keys
-    for n_layers, C, expect_keys in ((5, 512, False), (6, 512, True)):       # 3 * 2^27 and 4 * 2^27 updates
-        p = wl.chain_problem(n_layers, C, n_layers, tc_range=(0, 1000), ts_range=(0, 1000), tx_range=(0, 1000))
-        ref = oracle.search(p["n_nodes"], p["edges"], C, p["tc"], p["ts"], p["tx"])
-        ctx.profile_enable(True)
-        ctx.profile_reset()
-        cost, S = ctx.search_graph(p["n_nodes"], p["edges"], C, dev(p["tc"]), dev(p["ts"]), dev(p["tx"]))
-        prof = ctx.profile_read()
-        ctx.profile_enable(False)
+def test_search_picks_its_arithmetic_without_reading_values_back():
+    # A search with stored argmin never reads value ranges back.  Small searches (bound by latency) run
+    # on compare/select.  Larger ones are launched on packed keys speculatively; a product whose measured
+    # ranges do not allow them is skipped and flagged on the device, and the search runs again on the
+    # kernel that picks keys, keys per row or compare/select per product -- which later searches of the
+    # same context then start with.
+    from paper_1802_04924_amd import Context
+    with Context(0) as c:
+        c.profile_enable(True)
+        for n_layers, C, expect in ((4, 96, "plain"), (5, 512, "plain"), (6, 512, "keyed")):   # 3 * 2^27 and 4 * 2^27 updates
+            p = wl.chain_problem(n_layers, C, n_layers, tc_range=(0, 1000), ts_range=(0, 1000), tx_range=(0, 1000))
+            ref = oracle.search(p["n_nodes"], p["edges"], C, p["tc"], p["ts"], p["tx"])
+            c.profile_reset()
+            cost, S = c.search_graph(p["n_nodes"], p["edges"], C, dev(p["tc"]), dev(p["ts"]), dev(p["tx"]))
+            prof = c.profile_read()
+            assert cost == ref["cost"] and np.array_equal(S, ref["strategy"])
+            assert prof["products_" + expect] == n_layers - 2
+            assert prof["products_keyed"] + prof["products_plain"] + prof["products_keyed_row"] == n_layers - 2
+        # one table with values over 2^28: no global offset brings its products into the key range
+        p = wl.chain_problem(6, 700, 9, tc_range=(0, 1000), ts_range=(0, 1000), tx_range=(0, 1000))
+        p["tx"][2] = np.random.default_rng(5).integers(-(1 << 27), 1 << 27, size=(700, 700), dtype=np.int32)
+        d = dev(p["tc"]), dev(p["ts"]), dev(p["tx"])
+        for schedule in (wl.SCHEDULE_LEFT_FOLD, wl.SCHEDULE_ROUNDS):
+            ref = oracle.search(6, p["edges"], 700, p["tc"], p["ts"], p["tx"], schedule)
+            for rep in range(2):
+                c.profile_reset()
+                cost, S = c.search_graph(6, p["edges"], 700, *d, schedule)
+                prof = c.profile_read()
+                assert cost == ref["cost"] and np.array_equal(S, ref["strategy"])
+                total = prof["products_keyed"] + prof["products_plain"] + prof["products_keyed_row"]
+                first = schedule == wl.SCHEDULE_LEFT_FOLD and rep == 0
+                # the first search of the context ran twice (products skipped by the first run are not counted)
+                assert (4 < total <= 8) if first else total == 4
+                # in the left fold the wide table is the B side of one product (compare/select); in rounds
+                # it is an A side first (keys re-based per row) and its minima are narrow again
+                assert prof["products_keyed"] >= 1
+                assert prof["products_plain" if schedule == wl.SCHEDULE_LEFT_FOLD else "products_keyed_row"] >= 1
+        # narrow tables again: the context stays on the picking kernel, results unchanged
+        p = wl.chain_problem(6, 512, 6, tc_range=(0, 1000), ts_range=(0, 1000), tx_range=(0, 1000))
+        ref = oracle.search(6, p["edges"], 512, p["tc"], p["ts"], p["tx"])
+        cost, S = c.search_graph(6, p["edges"], 512, dev(p["tc"]), dev(p["ts"]), dev(p["tx"]))
         assert cost == ref["cost"] and np.array_equal(S, ref["strategy"])
-        assert (prof["keyed_launches"] == prof["node_launches"]) == expect_keys and (prof["keyed_launches"] > 0) == expect_keys
 
 
 def test_search_overflow_found_on_the_device(ctx):

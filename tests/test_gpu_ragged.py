@@ -244,8 +244,8 @@ def test_ragged_resnet_shaped(ctx, c_max, hi):
 
 @pytest.mark.parametrize("hi,t_c_scale", [(1000, 1), (1 << 20, 1), (1 << 20, 400)])
 def test_ragged_searches_large_enough_for_packed_keys(ctx, hi, t_c_scale):
-    # above 2^29 cell updates a search reads the value ranges back and launches of mixed shapes run
-    # on packed keys (global offsets, or re-based per row when node costs range widely)
+    # launches of mixed shapes pick packed keys on the device (global offsets, or re-based per row when
+    # node costs range widely)
     Cn = wl.ragged_counts(10, 77, 350, 620)
     edges = wl.chain_edges(10)
     tc, ts, tx = wl.ragged_tables(10, edges, Cn, hi % 97, 0, hi)
@@ -259,7 +259,7 @@ def test_ragged_searches_large_enough_for_packed_keys(ctx, hi, t_c_scale):
         prof = ctx.profile_read()
         ctx.profile_enable(False)
         assert cost == ref["cost"] and np.array_equal(S, ref["strategy"])
-        assert prof["keyed_launches"] > 0
+        assert prof["products_keyed"] + prof["products_keyed_row"] == 8 and prof["products_plain"] == 0
     n, fj = wl.forkjoin_edges(2, 3)
     Cn = wl.ragged_counts(n, 78, 250, 400)
     run_ragged(ctx, n, fj, Cn, seed=3, hi=hi, schedules=(wl.SCHEDULE_ROUNDS,))
