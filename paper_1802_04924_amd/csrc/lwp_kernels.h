@@ -181,12 +181,14 @@ hipError_t launch_component_min(const CompDesc* d_comp, unsigned long long n_pre
 // result[0] = total cost low word, result[1] = high word, result[2..2+n_nodes) = strategy,
 // result[2+n_nodes] = *d_flag (0 if d_flag is null), OR 1 if one of the n_nodes stats pairs starting
 // at d_wstats is the impossible {INT32_MAX, INT32_MIN} (a row of t_c + t_s left int32).
+// h_result (optional): pinned host memory the device can write; receives a copy of the 3 + n_nodes
+// result words before the kernel ends.
 hipError_t launch_back_substitute(const PairDesc* d_pairs, int32_t n_pairs, const SingleDesc* d_singles,
                                   int32_t n_singles, const CompDesc* d_comps, int32_t n_comps,
                                   const unsigned long long* d_keys,
                                   const UndoDesc* d_undo, int32_t n_undo, int32_t n_nodes,
                                   const int32_t* d_flag, const int32_t* d_wstats, int32_t* d_result,
-                                  hipStream_t stream);
+                                  int32_t* h_result, hipStream_t stream);
 
 // ---- VALU issue-rate probe ---------------------------------------------------------------------
 // `blocks` workgroups of 256 threads each run `iters` iterations of a register-only add + three-way

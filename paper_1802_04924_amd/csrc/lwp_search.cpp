@@ -219,6 +219,7 @@ public:
     lwp_status finish(int32_t* out_cost, int32_t* out_strategy) const;   // after the stream has drained
 
 private:
+    lwp_status upload_offsets();                 // per-node counts only: row / table offsets, ahead of the descriptors
     lwp_status measure_inputs();                 // w = t_c + t_s, ranges of w and of every input table
     lwp_status write_descriptors(int arith);     // descriptors, launch list; arith: see kArith*
     lwp_status attempt(int arith, bool replay_prepare);
@@ -315,9 +316,12 @@ lwp_status Search::run(int32_t* out_cost, int32_t* out_strategy) {
     constexpr int64_t kKeysPayFrom = (int64_t)1 << 29;
     int arith = !stored_ ? kArithValue : (updates < kKeysPayFrom ? kArithPlain : (ctx_->keys_failed ? kArithAuto : kArithKeyed));
     for (;;) {
-        if (lwp_status s = write_descriptors(arith)) return s;
-        if (lwp_status s = upload_descriptors()) return s;      // the offsets travel with the block
+        // the measuring pass needs no descriptor (only, with per-node counts, the offsets, which go
+        // ahead): it runs on the device while the host writes the descriptors
+        if (lwp_status s = upload_offsets()) return s;
         if (lwp_status s = measure_inputs()) return s;
+        if (lwp_status s = write_descriptors(arith)) return s;
+        if (lwp_status s = upload_descriptors()) return s;
         if (lwp_status s = enqueue_eliminations()) return s;
         if (lwp_status s = enqueue_residual_and_undo()) return s;
         if (lwp_status s = enqueue_result_copy()) return s;
@@ -345,6 +349,12 @@ lwp_status Search::enqueue_all() {
     if (lwp_status s = enqueue_eliminations()) return s;
     if (lwp_status s = enqueue_residual_and_undo()) return s;
     return enqueue_result_copy();
+}
+
+lwp_status Search::upload_offsets() {
+    if (L_.uniform) return LWP_OK;
+    LWP_HIP(ctx_, hipMemcpyAsync(db_ + W_.offs, hb_ + W_.offs, W_.offs_bytes, hipMemcpyHostToDevice, stream_));
+    return LWP_OK;
 }
 
 lwp_status Search::measure_inputs() {
@@ -580,13 +590,13 @@ lwp_status Search::enqueue_residual_and_undo() {
     for (size_t q = 0; q < nc; ++q)
         LWP_HIP(ctx_, launch_component_min(d_cd + q, comp_prefix_[q], d_keys_ + np + ns + q, d_flag_, st));
     LWP_HIP(ctx_, launch_back_substitute(d_pd, (int32_t)np, d_sd, (int32_t)ns, d_cd, (int32_t)nc, d_keys_, d_ud,
-                                         plan_.n_node_steps, n_nodes_, d_flag_, d_stats_ + 2 * (int64_t)rng_w0_, d_result_, st));
+                                         plan_.n_node_steps, n_nodes_, d_flag_, d_stats_ + 2 * (int64_t)rng_w0_, d_result_,
+                                         h_result_, st));
     return LWP_OK;
 }
 
 lwp_status Search::enqueue_result_copy() {
-    LWP_HIP(ctx_, hipMemcpyAsync(h_result_, d_result_, (3 + (size_t)n_nodes_) * sizeof(int32_t), hipMemcpyDeviceToHost, stream_));
-    return LWP_OK;
+    return LWP_OK;       // the undo kernel writes the result into the pinned host buffer itself
 }
 
 lwp_status Search::finish(int32_t* out_cost, int32_t* out_strategy) const {

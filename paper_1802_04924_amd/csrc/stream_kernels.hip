@@ -351,7 +351,7 @@ __global__ __launch_bounds__(kUndoThreads) void back_substitute_kernel(
     const CompDesc* __restrict__ comps, int32_t n_comps,
     const unsigned long long* __restrict__ keys, const UndoDesc* __restrict__ undo, int32_t n_undo,
     int32_t n_nodes, const int32_t* __restrict__ flag, const int32_t* __restrict__ wstats,
-    int32_t* __restrict__ result) {
+    int32_t* __restrict__ result, int32_t* __restrict__ host_result) {
     __shared__ long long ssum[kUndoThreads / 64];
     int32_t* S = result + 2;
     long long cost = 0;
@@ -382,7 +382,10 @@ __global__ __launch_bounds__(kUndoThreads) void back_substitute_kernel(
     // would then be arbitrary numbers, not configurations, so nothing is looked up through them.
     // (The flag is final: every launch that can set it has completed before this kernel starts.)
     if (flag && (*flag & 4)) {
-        if (threadIdx.x == 0) result[2 + n_nodes] = *flag;
+        if (threadIdx.x == 0) {
+            result[2 + n_nodes] = *flag;
+            if (host_result) host_result[2 + n_nodes] = *flag;
+        }
         return;
     }
     // walk the rounds backwards; node eliminations of one round never depend on each other
@@ -423,6 +426,12 @@ __global__ __launch_bounds__(kUndoThreads) void back_substitute_kernel(
             if (wstats[2 * v] > wstats[2 * v + 1]) wbad = 1;
     __syncthreads();
     if (threadIdx.x == 0) result[2 + n_nodes] = (flag ? *flag : 0) | wbad;
+    // the result goes straight to the caller's pinned host buffer (posted writes over the host
+    // link, complete when the kernel is): one dependent copy fewer at the end of every search
+    if (host_result) {
+        __syncthreads();
+        for (int t = threadIdx.x; t < 3 + n_nodes; t += kUndoThreads) host_result[t] = result[t];
+    }
 }
 
 // ---- VALU issue-rate probe ----------------------------------------------------------------------
@@ -573,9 +582,9 @@ hipError_t launch_back_substitute(const PairDesc* d_pairs, int32_t n_pairs, cons
                                   const unsigned long long* d_keys,
                                   const UndoDesc* d_undo, int32_t n_undo, int32_t n_nodes,
                                   const int32_t* d_flag, const int32_t* d_wstats, int32_t* d_result,
-                                  hipStream_t stream) {
+                                  int32_t* h_result, hipStream_t stream) {
     hipLaunchKernelGGL(back_substitute_kernel, dim3(1), dim3(kUndoThreads), 0, stream, d_pairs, n_pairs, d_singles,
-                       n_singles, d_comps, n_comps, d_keys, d_undo, n_undo, n_nodes, d_flag, d_wstats, d_result);
+                       n_singles, d_comps, n_comps, d_keys, d_undo, n_undo, n_nodes, d_flag, d_wstats, d_result, h_result);
     return hipGetLastError();
 }
 
