@@ -320,8 +320,8 @@ typedef struct {
 /* Runs a register-only loop of the min-plus kernel's two inner instructions (32-bit add, three-way
  * unsigned min; no memory traffic) on every compute unit and reports the rate the device
  * sustains: VALU lane-operations per second (instructions x 64 lanes) and the cell updates per
- * second those instructions amount to (1.5 instructions per update, plus ~7 % loop upkeep).  The
- * measured counterpart of the datasheet-derived peak the roofline fraction is quoted against.
+ * second those instructions amount to (1.5 instructions per update).  The measured counterpart
+ * of the datasheet-derived peak the roofline fraction is quoted against.
  * Blocking (a few milliseconds). */
 lwp_status lwp_measure_valu_rate(lwp_ctx *ctx, double *lane_ops_per_s, double *cell_updates_per_s);
 lwp_status lwp_profile_enable(lwp_ctx *ctx, int32_t on);

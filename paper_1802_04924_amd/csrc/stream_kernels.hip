@@ -438,9 +438,11 @@ __global__ __launch_bounds__(kUndoThreads) void back_substitute_kernel(
 // Register-only chains of the inner loop's two instructions (32-bit add, three-way unsigned min) on
 // 32 independent accumulators per thread: measures the int32 VALU rate the chip sustains, against
 // which the min-plus kernel's rate is read.  Per loop iteration and thread: 64 adds (all 8 x 8 sums
-// of two operand sets) + 32 min3 -- the arithmetic of 64 cell updates -- + the few instructions
-// that keep the operands changing.
-constexpr int kProbeInstrPerIter = 64 + 32 + 7;   // as compiled: the operand updates reuse 8 of the sums, 7 moves remain
+// of two operand sets) + 32 min3 -- the arithmetic of 64 cell updates.  As compiled the loop also
+// holds 7 register moves (the operand updates reuse 8 of the sums); the hardware counters show that
+// they cost no issue slot -- an iteration takes 96 x 4 cycles per wavefront, not 103 x 4 -- so they
+// are not counted as work.
+constexpr int kProbeInstrPerIter = 64 + 32;
 constexpr int kProbeUpdatesPerIter = 64;
 __global__ __launch_bounds__(kThreads) void alu_probe_kernel(uint32_t* __restrict__ out, int iters, uint32_t seed) {
     uint32_t m[32], a[8], b[8];
