@@ -149,6 +149,7 @@ class Workload:
         if name.endswith("-lists"):
             from paper_1802_04924_amd import enumerate_configs, plan_graph
             p = wl.config1() if name == "cfg1-lists" else wl.vgg16_problem()
+            p["machine"] = dict(p["machine"], n_devices=args.devices)
             lists = [enumerate_configs(l, p["machine"]["n_devices"]) for l in p["layers"]]
             Cn = np.array([len(x) for x in lists], np.int32)
             with Context(0) as c1:
@@ -156,7 +157,8 @@ class Workload:
             steps = plan_graph(p["n_nodes"], p["edges"], p["schedule"])["steps"]
             self.updates = int(sum(int(Cn[s["i"]]) * int(Cn[s["j"]]) * int(Cn[s["k"]]) for s in steps if s["kind"] == 0))
             self.workload = (f"{p['name'].rsplit('_', 1)[0]}_lists: {p['n_nodes']} nodes, {len(p['edges'])} edges, "
-                             f"{int(Cn.min())}..{int(Cn.max())} configurations per layer, {p['n_nodes'] - 2} node eliminations")
+                             f"{args.devices} devices, {int(Cn.min())}..{int(Cn.max())} configurations per layer, "
+                             f"{p['n_nodes'] - 2} node eliminations")
 
             def step():
                 self.result["cost"], self.result["S"] = self.ctx.search_graph_ragged(p["n_nodes"], p["edges"], Cn, dtc, dts, dtx,
@@ -309,6 +311,9 @@ def main():
                          "packed keys); baseline: the exhaustive search the paper compares with (Sec. 5.2, Table 3) on a 6-layer chain "
                          "with 40 configurations, every one of the 4.1e9 strategies enumerated")
     ap.add_argument("--layers", type=int, default=64, help="cfg4 only: chain length")
+    ap.add_argument("--devices", type=int, default=16,
+                    help="*-lists only: devices of the machine the configurations are enumerated for (the paper's Table 3 "
+                         "searches are for 4 GPUs)")
     ap.add_argument("--configs", type=int, default=0, help="override C of the workload")
     ap.add_argument("--undo", default="stored", choices=["stored", "recompute"],
                     help="undo pass: look up stored argmin tables, or recompute the argmin as Alg. 1 does")

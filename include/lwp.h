@@ -80,6 +80,13 @@ const char *lwp_status_string(lwp_status s);
  * an elimination are invalid.  The record is cleared by the call. */
 lwp_status lwp_synchronize(lwp_ctx *ctx);
 
+/* Options of a context.  LWP_OPT_SINGLE_LAUNCH (default 1): a search whose whole work is a few
+ * million operations (the sizes the paper itself searches: a handful of devices, tens of
+ * configurations per layer) runs as one launch of one workgroup instead of a dozen dependent
+ * launches; 0 sends every search down the general path.  Results are identical. */
+typedef enum { LWP_OPT_SINGLE_LAUNCH = 0 } lwp_option;
+lwp_status lwp_set_option(lwp_ctx *ctx, int32_t option, int32_t value);
+
 /* ---- node elimination (Sec. 5.2, Eq. 2; argmin of Thm. 3 in the appendix) ---------------- */
 
 /* For every b in [0,batch):

@@ -21,7 +21,7 @@ SCHEDULE_ROUNDS, SCHEDULE_LEFT_FOLD, SCHEDULE_NONE = 0, 1, 2
 UNDO_STORED, UNDO_RECOMPUTE = 0, 1
 
 EXPORTED = [
-    "lwp_create", "lwp_destroy", "lwp_last_error", "lwp_status_string", "lwp_synchronize",
+    "lwp_create", "lwp_destroy", "lwp_last_error", "lwp_status_string", "lwp_synchronize", "lwp_set_option",
     "lwp_eliminate_node", "lwp_eliminate_node_bounded", "lwp_eliminate_node_noalloc", "lwp_eliminate_edge", "lwp_plan_graph", "lwp_search_graph",
     "lwp_search_workspace_bytes", "lwp_search_graph_ex", "lwp_search_workspace_bytes_ex",
     "lwp_search_graph_ragged", "lwp_search_workspace_bytes_ragged", "lwp_build_cost_tables",
@@ -79,6 +79,7 @@ def load():
     lib.lwp_status_string.argtypes = [ctypes.c_int]
     lib.lwp_status_string.restype = ctypes.c_char_p
     lib.lwp_synchronize.argtypes = [vp]
+    lib.lwp_set_option.argtypes = [vp, i32, i32]
     lib.lwp_eliminate_node.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp, vp]
     lib.lwp_eliminate_node_bounded.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp]
     lib.lwp_eliminate_node_noalloc.argtypes = [vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp]
@@ -267,6 +268,10 @@ class Context:
     def _check(self, rc, what):
         if rc:
             raise LwpError(rc, what, self._lib.lwp_last_error(self._h).decode())
+
+    def set_single_launch(self, on=True):
+        """Whether very small searches run as one launch of one workgroup (default) or down the general path."""
+        self._check(self._lib.lwp_set_option(self._h, 0, 1 if on else 0), "set_option")
 
     def synchronize(self):
         self._check(self._lib.lwp_synchronize(self._h), "synchronize")

@@ -155,6 +155,13 @@ void lwp_destroy(lwp_ctx* ctx) {
 
 const char* lwp_last_error(const lwp_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
 
+lwp_status lwp_set_option(lwp_ctx* ctx, int32_t option, int32_t value) {
+    if (lwp_status s = check_ctx(ctx)) return s;
+    if (option != LWP_OPT_SINGLE_LAUNCH) return fail(ctx, LWP_E_INVAL, "unknown option");
+    ctx->single_launch = value != 0;
+    return LWP_OK;
+}
+
 lwp_status lwp_synchronize(lwp_ctx* ctx) {
     if (lwp_status s = check_ctx(ctx)) return s;
     if (!ctx->dstate) {

@@ -28,6 +28,7 @@ struct lwp_ctx {
     // a search on this context met tables too wide for packed keys on global offsets: later searches
     // do not try those first (see Search::run)
     bool keys_failed = false;
+    bool single_launch = true;     // LWP_OPT_SINGLE_LAUNCH
     bool profiling = false;
     struct Timed { hipEvent_t a, b; int kind; int64_t work; bool keyed; };
     std::vector<Timed> timed;

@@ -190,6 +190,36 @@ hipError_t launch_back_substitute(const PairDesc* d_pairs, int32_t n_pairs, cons
                                   const int32_t* d_flag, const int32_t* d_wstats, int32_t* d_result,
                                   int32_t* h_result, hipStream_t stream);
 
+// ---- a whole small search in one launch (one workgroup) -------------------------------------------
+// The descriptors are those of the general path; rounds[r] names the edge-sum groups and the node
+// eliminations of round r (ranges into `edges` / `nodes`).  NodeDesc.Ci/Cj/Ck must be set; ranges,
+// rngOut and per-descriptor flags are ignored (overflow is found exactly and OR-ed into *flag, which
+// the kernel first clears).  w receives t_c + t_s for all n_w entries.  keys: one per component.
+// result / host_result as launch_back_substitute.
+struct TinyRound { int32_t g0, g1, n0, n1; };
+struct TinyArgs {
+    const int32_t* tc;
+    const int32_t* ts;
+    int32_t* w;
+    int64_t n_w;
+    const TinyRound* rounds;
+    int32_t n_rounds;
+    const NodeDesc* nodes;
+    const EdgeDesc* edges;
+    const int32_t* const* srcs;
+    const PairDesc* pairs;
+    const SingleDesc* singles;
+    const CompDesc* comps;
+    int32_t n_pairs, n_singles, n_comps;
+    unsigned long long* keys;
+    const UndoDesc* undo;
+    int32_t n_undo, n_nodes;
+    int32_t* flag;
+    int32_t* result;
+    int32_t* host_result;
+};
+hipError_t launch_tiny_search(const TinyArgs& args, hipStream_t stream);
+
 // ---- VALU issue-rate probe ---------------------------------------------------------------------
 // `blocks` workgroups of 256 threads each run `iters` iterations of a register-only add + three-way
 // min loop; per iteration and thread alu_probe_instr_per_iter() VALU instructions that perform the

@@ -134,7 +134,7 @@ struct WsLayout {
     size_t w, head, keys, result, args, slots, total;
     size_t desc, desc_bytes;                                   // descriptor block
     size_t offs, offs_bytes;                                   // row / table offsets, at the start of the block
-    size_t node_desc, edge_desc, src_ptrs, pair_desc, singles, undo, comps, tile_begin;   // offsets inside the block
+    size_t node_desc, edge_desc, src_ptrs, pair_desc, singles, undo, comps, tile_begin, tiny_rounds;   // offsets inside the block
     int32_t n_ranges;
 };
 
@@ -162,6 +162,7 @@ WsLayout layout_workspace(const Plan& plan, const Layout& L, int32_t n_nodes, in
         o.undo = sub((size_t)plan.n_node_steps * sizeof(UndoDesc));
         o.comps = sub(plan.comps.size() * sizeof(CompDesc));
         o.tile_begin = sub((2 * (size_t)plan.n_node_steps + 2) * sizeof(int32_t));   // launches of mixed shapes
+        o.tiny_rounds = sub(((size_t)plan.n_rounds + 1) * sizeof(TinyRound));         // a small search in one launch
         o.desc_bytes = std::max<size_t>(b, 16);
     }
     o.desc = put(o.desc_bytes);
@@ -219,6 +220,7 @@ public:
     lwp_status finish(int32_t* out_cost, int32_t* out_strategy) const;   // after the stream has drained
 
 private:
+    lwp_status enqueue_tiny();                   // the whole search as one launch of one workgroup
     lwp_status upload_offsets();                 // per-node counts only: row / table offsets, ahead of the descriptors
     lwp_status measure_inputs();                 // w = t_c + t_s, ranges of w and of every input table
     lwp_status write_descriptors(int arith);     // descriptors, launch list; arith: see kArith*
@@ -266,6 +268,10 @@ private:
     std::vector<RoundWork> rounds_;
     std::vector<unsigned long long> comp_prefix_;
     int32_t pair_max_rows_ = 1, single_max_c_ = 1;
+    // A search whose whole work is a few million simple operations (the paper's own sizes: a handful
+    // of devices, tens of configurations per layer) runs in one launch of one workgroup: the dozen
+    // dependent launches of the general path would cost several times its arithmetic.
+    bool tiny_ = false;
 };
 
 lwp_status Search::plan() {
@@ -281,6 +287,22 @@ lwp_status Search::plan() {
     pin_desc_ = 0;
     pin_result_ = pin_desc_ + align_up(W_.desc_bytes, 256);
     n_comp_ = (int32_t)(plan_.pairs.size() + plan_.singles.size() + plan_.comps.size());
+    {
+        // operations one workgroup would have to do (1024 threads: 2^22 operations are about 4000 each)
+        constexpr double kTinyWork = 4194304.0, kTinyEnumeration = 65536.0;
+        double work = (double)L_.node_off[n_nodes_];
+        for (size_t q = 0; q < L_.node_A.size(); ++q) work += (double)L_.node_A[q].rows * L_.node_A[q].cols * L_.node_B[q].cols;
+        for (size_t g = 0; g < L_.groups.size(); ++g) work += (double)L_.group_out[g].cells() * L_.group_src[g].size();
+        for (auto& t : L_.final_table) work += (double)t.cells();
+        bool small_enumerations = true;
+        for (auto& c : plan_.comps) {
+            double n = 1;
+            for (int32_t v : c.nodes) n *= Cn_[v];
+            small_enumerations = small_enumerations && n <= kTinyEnumeration;
+            work += n * (double)(c.nodes.size() + c.edges.size());
+        }
+        tiny_ = small_enumerations && work <= kTinyWork && (!ctx_ || ctx_->single_launch);
+    }
     // index of the range pair of: input edge e | w of node v | output of node step | output of group
     rng_w0_ = n_edges_;
     rng_node0_ = n_edges_ + n_nodes_;
@@ -309,6 +331,13 @@ void Search::bind(char* ws, char* pin) {
 }
 
 lwp_status Search::run(int32_t* out_cost, int32_t* out_strategy) {
+    if (tiny_) {
+        if (lwp_status s = write_descriptors(stored_ ? kArithPlain : kArithValue)) return s;
+        if (lwp_status s = upload_descriptors()) return s;
+        if (lwp_status s = enqueue_tiny()) return s;
+        LWP_HIP(ctx_, hipStreamSynchronize(stream_));
+        return finish(out_cost, out_strategy);
+    }
     int64_t updates = 0;
     for (size_t q = 0; q < L_.node_A.size(); ++q) updates += (int64_t)L_.node_A[q].rows * L_.node_A[q].cols * L_.node_B[q].cols;
     // Below this size launches are bound by latency, not arithmetic, and the kernel with the least
@@ -345,10 +374,31 @@ lwp_status Search::prepare_replay() {
 }
 
 lwp_status Search::enqueue_all() {
+    if (tiny_) return enqueue_tiny();
     if (lwp_status s = measure_inputs()) return s;
     if (lwp_status s = enqueue_eliminations()) return s;
     if (lwp_status s = enqueue_residual_and_undo()) return s;
     return enqueue_result_copy();
+}
+
+lwp_status Search::enqueue_tiny() {
+    TinyArgs a{};
+    a.tc = d_tc_; a.ts = d_ts_; a.w = d_w_; a.n_w = L_.node_off[n_nodes_];
+    a.rounds = reinterpret_cast<const TinyRound*>(db_ + W_.tiny_rounds);
+    a.n_rounds = (int32_t)rounds_.size();
+    a.nodes = reinterpret_cast<const NodeDesc*>(db_ + W_.node_desc);
+    a.edges = reinterpret_cast<const EdgeDesc*>(db_ + W_.edge_desc);
+    a.srcs = reinterpret_cast<const int32_t* const*>(db_ + W_.src_ptrs);
+    a.pairs = reinterpret_cast<const PairDesc*>(db_ + W_.pair_desc);
+    a.singles = reinterpret_cast<const SingleDesc*>(db_ + W_.singles);
+    a.comps = reinterpret_cast<const CompDesc*>(db_ + W_.comps);
+    a.n_pairs = (int32_t)plan_.pairs.size(); a.n_singles = (int32_t)plan_.singles.size(); a.n_comps = (int32_t)plan_.comps.size();
+    a.keys = d_keys_;
+    a.undo = reinterpret_cast<const UndoDesc*>(db_ + W_.undo);
+    a.n_undo = plan_.n_node_steps; a.n_nodes = n_nodes_;
+    a.flag = d_flag_; a.result = d_result_; a.host_result = h_result_;
+    LWP_HIP(ctx_, launch_tiny_search(a, stream_));
+    return LWP_OK;
 }
 
 lwp_status Search::upload_offsets() {
@@ -495,6 +545,7 @@ lwp_status Search::write_descriptors(int arith) {
             a = b;
         }
         for (size_t q = 0; q < order.size(); ++q) nd[n0 + q] = work[order[q]].d;
+        reinterpret_cast<TinyRound*>(hb_ + W_.tiny_rounds)[rounds_.size()] = {(int32_t)rw_.g0, (int32_t)rw_.g1, (int32_t)n0, (int32_t)ni};
         rounds_.push_back(std::move(rw_));
     }
 

@@ -346,7 +346,7 @@ __global__ __launch_bounds__(kThreads) void component_min_kernel(const CompDesc*
 // ---- undo (Alg. 1: S^(i) = S^(i+1) + c_j, c_j the stored argmin of Eq. 2 at (c_i, c_k)) ---------
 // One workgroup of 1024 threads: the recomputing form keeps 16 wavefronts busy per round.
 constexpr int kUndoThreads = 1024;
-__global__ __launch_bounds__(kUndoThreads) void back_substitute_kernel(
+__device__ __forceinline__ void back_substitute_body(
     const PairDesc* __restrict__ pairs, int32_t n_pairs, const SingleDesc* __restrict__ singles, int32_t n_singles,
     const CompDesc* __restrict__ comps, int32_t n_comps,
     const unsigned long long* __restrict__ keys, const UndoDesc* __restrict__ undo, int32_t n_undo,
@@ -432,6 +432,129 @@ __global__ __launch_bounds__(kUndoThreads) void back_substitute_kernel(
         __syncthreads();
         for (int t = threadIdx.x; t < 3 + n_nodes; t += kUndoThreads) host_result[t] = result[t];
     }
+}
+
+__global__ __launch_bounds__(kUndoThreads) void back_substitute_kernel(
+    const PairDesc* __restrict__ pairs, int32_t n_pairs, const SingleDesc* __restrict__ singles, int32_t n_singles,
+    const CompDesc* __restrict__ comps, int32_t n_comps,
+    const unsigned long long* __restrict__ keys, const UndoDesc* __restrict__ undo, int32_t n_undo,
+    int32_t n_nodes, const int32_t* __restrict__ flag, const int32_t* __restrict__ wstats,
+    int32_t* __restrict__ result, int32_t* __restrict__ host_result) {
+    back_substitute_body(pairs, n_pairs, singles, n_singles, comps, n_comps, keys, undo, n_undo, n_nodes, flag, wstats, result,
+                         host_result);
+}
+
+// ---- a whole small search in one workgroup ------------------------------------------------------
+// Alg. 1 from the sum t_c + t_s to the strategy, for searches so small (the paper's own sizes: a
+// handful of devices, tens of configurations per layer) that the launches of the general path --
+// a dozen dependent kernels of a few microseconds each -- cost far more than the arithmetic.  One
+// workgroup of 1024 threads walks the same descriptors the general path uses: per round the edge
+// sums (Eq. 3) and the node eliminations (Eq. 2, one output cell per thread, candidates in ascending
+// c with a strict '<'), then the residual minima and the undo pass.  A workgroup barrier separates
+// the phases: all tables involved were written by this workgroup through its own compute unit.
+// Sums are formed in 64 bits, so overflow is found exactly (a sum that really leaves int32).
+__device__ __forceinline__ unsigned long long block_min_u64(unsigned long long v, unsigned long long* sm) {
+    v = wave_min_u64(v);
+    __syncthreads();                                  // sm may still be read from the previous call
+    if ((threadIdx.x & 63) == 0) sm[threadIdx.x >> 6] = v;
+    __syncthreads();
+    unsigned long long r = sm[0];
+    for (int q = 1; q < kUndoThreads / 64; ++q) r = sm[q] < r ? sm[q] : r;
+    return r;
+}
+
+__global__ __launch_bounds__(kUndoThreads) void tiny_search_kernel(const TinyArgs a) {
+    __shared__ unsigned long long smin[kUndoThreads / 64];
+    const int tid = threadIdx.x;
+    bool bad = false;
+    if (tid == 0) *a.flag = 0;
+    for (int64_t x = tid; x < a.n_w; x += kUndoThreads) {
+        const long long s = (long long)a.tc[x] + (long long)a.ts[x];
+        bad |= (s != (long long)(int32_t)s);
+        a.w[x] = (int32_t)s;
+    }
+    __syncthreads();
+    for (int r = 0; r < a.n_rounds; ++r) {
+        const TinyRound rd = a.rounds[r];
+        for (int g = rd.g0; g < rd.g1; ++g) {                      // Eq. 3, k-way
+            const EdgeDesc d = a.edges[g];
+            const int32_t* const* sp = a.srcs + d.first_src;
+            for (int64_t x = tid; x < d.cells; x += kUndoThreads) {
+                long long acc = sp[0][x];
+                for (int q = 1; q < d.n_src; ++q) acc += sp[q][x];
+                bad |= (acc != (long long)(int32_t)acc);
+                d.out[x] = (int32_t)acc;
+            }
+        }
+        if (rd.g1 > rd.g0) __syncthreads();
+        for (int n = rd.n0; n < rd.n1; ++n) {                      // Eq. 2
+            const NodeDesc d = a.nodes[n];
+            const int cells = d.Ci * d.Ck;
+            for (int x = tid; x < cells; x += kUndoThreads) {
+                const int ra = x / d.Ck, cb = x - ra * d.Ck;
+                const int32_t* Arow = d.A + (int64_t)ra * d.Cj;
+                long long best = 0;
+                int arg = 0;
+                for (int c = 0; c < d.Cj; ++c) {
+                    const long long s = (long long)Arow[c] + d.w[c] + d.B[(int64_t)c * d.Ck + cb];
+                    bad |= (s != (long long)(int32_t)s);
+                    if (c == 0 || s < best) { best = s; arg = c; }
+                }
+                d.out[x] = (int32_t)best;
+                if (d.arg) d.arg[x] = arg;
+            }
+        }
+        __syncthreads();
+    }
+    // residual graph: a 64-bit (cost, flat index) minimum per component
+    for (int p = 0; p < a.n_pairs; ++p) {
+        const PairDesc d = a.pairs[p];
+        unsigned long long best = ~0ull;
+        for (int x = tid; x < d.Ci * d.Ck; x += kUndoThreads) {
+            const int ra = x / d.Ck, cb = x - ra * d.Ck;
+            const long long s = (long long)d.wi[ra] + d.T[x] + d.wk[cb];
+            bad |= (s != (long long)(int32_t)s);
+            const unsigned long long k = make_key((int32_t)s, (uint32_t)x);
+            best = k < best ? k : best;
+        }
+        best = block_min_u64(best, smin);
+        if (tid == 0) a.keys[p] = best;
+    }
+    for (int q = 0; q < a.n_singles; ++q) {
+        const SingleDesc d = a.singles[q];
+        unsigned long long best = ~0ull;
+        for (int x = tid; x < d.C; x += kUndoThreads) {
+            const unsigned long long k = make_key(d.w[x], (uint32_t)x);
+            best = k < best ? k : best;
+        }
+        best = block_min_u64(best, smin);
+        if (tid == 0) a.keys[a.n_pairs + q] = best;
+    }
+    for (int q = 0; q < a.n_comps; ++q) {
+        const CompDesc* cd = a.comps + q;
+        const int K = cd->K;
+        unsigned long long total = 1;
+        for (int z = 0; z < K; ++z) total *= (unsigned)cd->Cn[z];
+        unsigned long long best = ~0ull;
+        for (unsigned long long f = tid; f < total; f += kUndoThreads) {
+            int digit[kCompMaxNodes];
+            unsigned long long rem = f;
+            for (int z = K - 1; z >= 0; --z) { digit[z] = (int)(rem % (unsigned)cd->Cn[z]); rem /= (unsigned)cd->Cn[z]; }
+            long long t = 0;
+            for (int z = 0; z < K; ++z) t += cd->w[z][digit[z]];
+            for (int e = 0; e < cd->n_edges; ++e)
+                t += cd->tab[e][(int64_t)digit[cd->src_pos[e]] * cd->Cn[cd->dst_pos[e]] + digit[cd->dst_pos[e]]];
+            bad |= (t != (long long)(int32_t)t);
+            const unsigned long long k = make_key((int32_t)t, (uint32_t)f);
+            best = k < best ? k : best;
+        }
+        best = block_min_u64(best, smin);
+        if (tid == 0) a.keys[a.n_pairs + a.n_singles + q] = best;
+    }
+    if (bad) atomicOr(a.flag, 1);
+    __syncthreads();
+    back_substitute_body(a.pairs, a.n_pairs, a.singles, a.n_singles, a.comps, a.n_comps, a.keys, a.undo, a.n_undo, a.n_nodes,
+                         a.flag, nullptr, a.result, a.host_result);
 }
 
 // ---- VALU issue-rate probe ----------------------------------------------------------------------
@@ -569,6 +692,11 @@ hipError_t launch_component_min(const CompDesc* d_comp, unsigned long long n_pre
     unsigned long long blocks = (n_prefix + kThreads - 1) / kThreads;
     if (blocks > 65536) blocks = 65536;
     hipLaunchKernelGGL(component_min_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, stream, d_comp, n_prefix, d_key, d_flag);
+    return hipGetLastError();
+}
+
+hipError_t launch_tiny_search(const TinyArgs& args, hipStream_t stream) {
+    hipLaunchKernelGGL(tiny_search_kernel, dim3(1), dim3(kUndoThreads), 0, stream, args);
     return hipGetLastError();
 }
 

@@ -385,10 +385,17 @@ def run_search(ctx, p, schedule=None):
     schedule = p["schedule"] if schedule is None else schedule
     ref = oracle.search(p["n_nodes"], p["edges"], p["C"], p["tc"], p["ts"], p["tx"], schedule)
     d_tc, d_ts, d_tx = dev(p["tc"]), dev(p["ts"]), dev(p["tx"])
-    for undo in (UNDO_STORED, UNDO_RECOMPUTE):
-        cost, S = ctx.search_graph(p["n_nodes"], p["edges"], p["C"], d_tc, d_ts, d_tx, schedule, undo)
-        assert cost == ref["cost"], undo
-        assert np.array_equal(S, ref["strategy"]), undo
+    # a search of a few million operations runs as one launch of one workgroup unless told otherwise:
+    # such searches are checked down both paths
+    nodes_gone = len(ref["steps"]) and int((ref["steps"]["kind"] == 0).sum())
+    both = nodes_gone * p["C"] ** 3 <= (1 << 22)
+    for single in ((True, False) if both else (True,)):
+        ctx.set_single_launch(single)
+        for undo in (UNDO_STORED, UNDO_RECOMPUTE):
+            cost, S = ctx.search_graph(p["n_nodes"], p["edges"], p["C"], d_tc, d_ts, d_tx, schedule, undo)
+            assert cost == ref["cost"], (undo, single)
+            assert np.array_equal(S, ref["strategy"]), (undo, single)
+    ctx.set_single_launch(True)
     assert oracle.strategy_cost(p["n_nodes"], p["edges"], p["C"], p["tc"], p["ts"], p["tx"], S) == cost
     return cost, S
 
@@ -571,7 +578,7 @@ def test_search_picks_its_arithmetic_without_reading_values_back():
     from paper_1802_04924_amd import Context
     with Context(0) as c:
         c.profile_enable(True)
-        for n_layers, C, expect in ((4, 96, "plain"), (5, 512, "plain"), (6, 512, "keyed")):   # 3 * 2^27 and 4 * 2^27 updates
+        for n_layers, C, expect in ((4, 160, "plain"), (5, 512, "plain"), (6, 512, "keyed")):   # 3 * 2^27 and 4 * 2^27 updates
             p = wl.chain_problem(n_layers, C, n_layers, tc_range=(0, 1000), ts_range=(0, 1000), tx_range=(0, 1000))
             ref = oracle.search(p["n_nodes"], p["edges"], C, p["tc"], p["ts"], p["tx"])
             c.profile_reset()

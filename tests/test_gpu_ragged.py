@@ -31,10 +31,14 @@ def run_ragged(ctx, n_nodes, edges, Cn, seed, hi, schedules=(wl.SCHEDULE_ROUNDS,
     d_tc, d_ts, d_tx = dev(tc), dev(ts), dev(tx)
     for schedule in schedules:
         ref = oracle.search_ragged(n_nodes, edges, Cn, tc, ts, tx, schedule)
-        for undo in (UNDO_STORED, UNDO_RECOMPUTE):
-            cost, S = ctx.search_graph_ragged(n_nodes, edges, Cn, d_tc, d_ts, d_tx, schedule, undo)
-            assert cost == ref["cost"], (schedule, undo)
-            assert np.array_equal(S, ref["strategy"]), (schedule, undo)
+        # small searches run as one launch of one workgroup unless told otherwise: both paths are checked
+        for single in ((True, False) if int(np.max(Cn)) <= 64 else (True,)):
+            ctx.set_single_launch(single)
+            for undo in (UNDO_STORED, UNDO_RECOMPUTE):
+                cost, S = ctx.search_graph_ragged(n_nodes, edges, Cn, d_tc, d_ts, d_tx, schedule, undo)
+                assert cost == ref["cost"], (schedule, undo, single)
+                assert np.array_equal(S, ref["strategy"]), (schedule, undo, single)
+        ctx.set_single_launch(True)
         assert oracle.strategy_cost_ragged(n_nodes, edges, Cn, tc, ts, tx, S) == cost
         assert (S >= 0).all() and (S < np.asarray(Cn)).all()
     return cost, S
