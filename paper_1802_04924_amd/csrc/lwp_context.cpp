@@ -60,13 +60,21 @@ lwp_status ensure_split_buffers(lwp_ctx* ctx) {
 }
 
 lwp_status ensure_state(lwp_ctx* ctx) {
-    if (ctx->dstate) return LWP_OK;
-    void* p = nullptr;
-    hipError_t e = hipMalloc(&p, 256);
-    if (e != hipSuccess) { (void)hipGetLastError(); return fail(ctx, LWP_E_NOMEM, std::string("device state words: ") + hipGetErrorString(e)); }
-    ctx->dstate = static_cast<int32_t*>(p);
-    LWP_HIP(ctx, hipMemsetAsync(ctx->dstate, 0, 256, ctx->stream));
-    return ensure_pinned(ctx, 4096);       // lwp_synchronize reads the error bits back through it
+    if (ctx->dstate && ctx->hstate) return LWP_OK;
+    if (!ctx->hstate) {
+        void* h = nullptr;
+        hipError_t e = hipHostMalloc(&h, 64, hipHostMallocDefault);
+        if (e != hipSuccess) { (void)hipGetLastError(); return fail(ctx, LWP_E_NOMEM, std::string("pinned state word: ") + hipGetErrorString(e)); }
+        ctx->hstate = static_cast<int32_t*>(h);
+    }
+    if (!ctx->dstate) {
+        void* p = nullptr;
+        hipError_t e = hipMalloc(&p, 256);
+        if (e != hipSuccess) { (void)hipGetLastError(); return fail(ctx, LWP_E_NOMEM, std::string("device state words: ") + hipGetErrorString(e)); }
+        ctx->dstate = static_cast<int32_t*>(p);
+        LWP_HIP(ctx, hipMemsetAsync(p, 0, 256, ctx->stream));
+    }
+    return LWP_OK;
 }
 
 void set_split(lwp_ctx* ctx, NodeArgs& a, Split split) {
@@ -150,6 +158,7 @@ void lwp_destroy(lwp_ctx* ctx) {
     if (ctx->pin) (void)hipHostFree(ctx->pin);
     if (ctx->split) (void)hipFree(ctx->split);
     if (ctx->dstate) (void)hipFree(ctx->dstate);
+    if (ctx->hstate) (void)hipHostFree(ctx->hstate);
     delete ctx;
 }
 
@@ -164,13 +173,13 @@ lwp_status lwp_set_option(lwp_ctx* ctx, int32_t option, int32_t value) {
 
 lwp_status lwp_synchronize(lwp_ctx* ctx) {
     if (lwp_status s = check_ctx(ctx)) return s;
-    if (!ctx->dstate) {
+    if (!ctx->dstate || !ctx->hstate) {
         LWP_HIP(ctx, hipStreamSynchronize(ctx->stream));
         return LWP_OK;
     }
     // what the kernels of lwp_eliminate_node / _edge found since the last call: the word is copied
     // behind them on the stream into pinned memory, so one wait covers both
-    int32_t* bits_p = reinterpret_cast<int32_t*>(ctx->pin);
+    int32_t* bits_p = ctx->hstate;
     LWP_HIP(ctx, hipMemcpyAsync(bits_p, ctx->dstate, sizeof(int32_t), hipMemcpyDeviceToHost, ctx->stream));
     LWP_HIP(ctx, hipStreamSynchronize(ctx->stream));
     const int32_t bits = *bits_p;

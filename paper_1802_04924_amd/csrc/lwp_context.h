@@ -25,6 +25,7 @@ struct lwp_ctx {
     // kernels (1: a sum may leave int32, 2: an element outside the ranges the caller promised),
     // reported and cleared by lwp_synchronize; [1 + mode] products that ran on each kernel variant
     int32_t* dstate = nullptr;
+    int32_t* hstate = nullptr;     // pinned host word lwp_synchronize reads the error bits back through
     // a search on this context met tables too wide for packed keys on global offsets: later searches
     // do not try those first (see Search::run)
     bool keys_failed = false;
