@@ -47,6 +47,11 @@ def pmc_traffic_bytes():
         return None
 
 
+def oracle_threads():
+    import oracle
+    return oracle.omp_threads()
+
+
 def viterbi_chain(tc, ts, tx):
     """Layered shortest path: the optimum of Eq. 1 on a chain, by the textbook recurrence."""
     w = tc.astype(np.int64) + ts.astype(np.int64)
@@ -237,15 +242,19 @@ class Workload:
         import oracle
         if self.name == "cfg3":
             A, w, B = self.host
+            oracle_s = 0.0
             for fn, what in ((self.step, "promised ranges"), (self.step_measured, "measured ranges")):
                 self.out.zero_(); self.arg.zero_()
                 fn()
                 out, arg = self.out.cpu().numpy(), self.arg.cpu().numpy()
                 for b in range(A.shape[0]):
+                    t0 = time.perf_counter()
                     ro, ra = oracle.minplus_argmin(A[b], w[b], B[b])
+                    oracle_s += time.perf_counter() - t0
                     if not (np.array_equal(out[b], ro) and np.array_equal(arg[b], ra)):
                         return {"ok": False, "how": f"product {b} differs from the oracle ({what})"}
-            return {"ok": True, "how": f"all {A.shape[0]} products, minima and argmins, equal to the oracle's on both entry points"}
+            return {"ok": True, "oracle_ms": oracle_s / 2 * 1e3,
+                    "how": f"all {A.shape[0]} products, minima and argmins, equal to the oracle's on both entry points"}
         self.step()
         cost, S = self.result["cost"], self.result["S"]
         p = self.p
@@ -254,14 +263,16 @@ class Workload:
                 oracle.strategy_cost(p["n_nodes"], p["edges"], p["C"], p["tc"], p["ts"], p["tx"], S) == cost
             return {"ok": bool(ok), "how": "cost equals the layered shortest path and Eq. 1 of the returned strategy "
                                            "(the oracle's whole search takes minutes; the test-suite checks every elimination)"}
+        t0 = time.perf_counter()
         if "Cn" in p:
             ref = oracle.search_ragged(p["n_nodes"], p["edges"], p["Cn"], p["tc"], p["ts"], p["tx"], p["schedule"])
         elif self.name == "resid" and p["C"] ** 4 > (1 << 32):
             return {"ok": None, "how": "more strategies than the oracle enumerates"}
         else:
             ref = oracle.search(p["n_nodes"], p["edges"], p["C"], p["tc"], p["ts"], p["tx"], p["schedule"])
+        oracle_ms = (time.perf_counter() - t0) * 1e3
         ok = cost == ref["cost"] and np.array_equal(S, ref["strategy"])
-        return {"ok": bool(ok), "how": "cost and every configuration equal to the oracle's whole search"}
+        return {"ok": bool(ok), "oracle_ms": oracle_ms, "how": "cost and every configuration equal to the oracle's whole search"}
 
     def close(self):
         if self.plan is not None:
@@ -364,6 +375,9 @@ def main():
             par = wk.parity()
             entry["parity"] = par["ok"]
             entry["parity_how"] = par["how"]
+            # the parity check runs the oracle on the whole configuration: its time on the host cores
+            entry["oracle_ms"] = par.get("oracle_ms")
+            entry["oracle_cores"] = oracle_threads()
             others[name] = entry
             wk.close()
             del wk

@@ -86,14 +86,6 @@ lwp_status drain_profile(lwp_ctx* ctx);
 struct Range { int64_t lo, hi; };
 inline bool fits(int64_t v) { return v >= kI32Min && v <= kI32Max; }
 
-// Spread the packed-key arithmetic must represent for one product (see minplus.hip): re-based
-// A + w, clamped just above the largest possible result where that is tighter, plus re-based B.
-inline int64_t keyed_spread(Range rA, Range rw, Range rB) {
-    const int64_t a_max = rA.hi + rw.hi - (rA.lo + rw.lo);
-    const int64_t out_max = (rA.hi - rA.lo) + (rB.hi - rB.lo);
-    return std::min(a_max, out_max + 1) + (rB.hi - rB.lo);
-}
-
 // The same for keys re-based per output row: the row's minimum re-bases to 0 and everything more
 // than B's spread above it is clamped, so only B's spread counts.
 inline int64_t keyed_row_spread(Range rB) { return 2 * (rB.hi - rB.lo) + 1; }
