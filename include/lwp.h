@@ -83,8 +83,15 @@ lwp_status lwp_synchronize(lwp_ctx *ctx);
 /* Options of a context.  LWP_OPT_SINGLE_LAUNCH (default 1): a search whose whole work is a few
  * million operations (the sizes the paper itself searches: a handful of devices, tens of
  * configurations per layer) runs as one launch of one workgroup instead of a dozen dependent
- * launches; 0 sends every search down the general path.  Results are identical. */
-typedef enum { LWP_OPT_SINGLE_LAUNCH = 0 } lwp_option;
+ * launches; 0 sends every search down the general path.  Results are identical.
+ * LWP_OPT_SMALL_PRODUCT_KERNEL (default 1): node eliminations with little work -- one call, or one
+ * round of a search, below 2^26 cell updates (2^24 for a call with promised ranges) and with at most
+ * 1024 candidates per product -- run on a kernel that gives every wavefront a small
+ * output tile of its own instead of the tiled kernel, whose launch would be mostly latency at that
+ * size; 0 sends every node elimination to the tiled kernel.  Results are identical; the overflow
+ * test of the small-product kernel is the same formula applied to the values each wavefront reads,
+ * so it is at least as tight. */
+typedef enum { LWP_OPT_SINGLE_LAUNCH = 0, LWP_OPT_SMALL_PRODUCT_KERNEL = 1 } lwp_option;
 lwp_status lwp_set_option(lwp_ctx *ctx, int32_t option, int32_t value);
 
 /* ---- node elimination (Sec. 5.2, Eq. 2; argmin of Thm. 3 in the appendix) ---------------- */
@@ -97,7 +104,8 @@ lwp_status lwp_set_option(lwp_ctx *ctx, int32_t option, int32_t value);
  * by a variant without argmin bookkeeping).  out/argmin must not overlap the inputs.  Sizes: batch, Ci, Cj, Ck >= 1, Cj <= 65536.
  * Enqueues and returns.  Nothing is assumed about the values: one pass measures the value ranges
  * of A, w and B of every product on the device, and the product kernels pick their arithmetic
- * variant per product from those ranges, also on the device.  If max A + max w + max B (or the
+ * variant per product from those ranges, also on the device (a call with little work needs neither:
+ * see LWP_OPT_SMALL_PRODUCT_KERNEL).  If max A + max w + max B (or the
  * minima) of a product could leave int32 the next lwp_synchronize returns LWP_E_OVERFLOW. */
 lwp_status lwp_eliminate_node(lwp_ctx *ctx, int32_t batch, int32_t Ci, int32_t Cj, int32_t Ck,
                               const int32_t *d_A, const int32_t *d_w, const int32_t *d_B,

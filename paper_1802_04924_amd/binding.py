@@ -273,6 +273,10 @@ class Context:
         """Whether very small searches run as one launch of one workgroup (default) or down the general path."""
         self._check(self._lib.lwp_set_option(self._h, 0, 1 if on else 0), "set_option")
 
+    def set_small_product_kernel(self, on=True):
+        """Whether node eliminations with little work run on the wavefront-per-tile kernel (default) or on the tiled one."""
+        self._check(self._lib.lwp_set_option(self._h, 1, 1 if on else 0), "set_option")
+
     def synchronize(self):
         self._check(self._lib.lwp_synchronize(self._h), "synchronize")
 

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "liblwp.so")
-SOURCES = ["lwp_context.cpp", "lwp_eliminate.cpp", "lwp_search.cpp", "lwp_plan.cpp", "minplus.hip", "stream_kernels.hip", "cost_tables.hip"]
+SOURCES = ["lwp_context.cpp", "lwp_eliminate.cpp", "lwp_search.cpp", "lwp_plan.cpp", "minplus.hip", "minplus_wave.hip", "stream_kernels.hip", "cost_tables.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-x", "hip",
          # no packed-FP32 instructions (integer kernels do not need them; harmless host-pass warning)
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

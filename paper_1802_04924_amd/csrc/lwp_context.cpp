@@ -166,8 +166,9 @@ const char* lwp_last_error(const lwp_ctx* ctx) { return ctx ? ctx->err.c_str() :
 
 lwp_status lwp_set_option(lwp_ctx* ctx, int32_t option, int32_t value) {
     if (lwp_status s = check_ctx(ctx)) return s;
-    if (option != LWP_OPT_SINGLE_LAUNCH) return fail(ctx, LWP_E_INVAL, "unknown option");
-    ctx->single_launch = value != 0;
+    if (option == LWP_OPT_SINGLE_LAUNCH) ctx->single_launch = value != 0;
+    else if (option == LWP_OPT_SMALL_PRODUCT_KERNEL) ctx->wave_kernel = value != 0;
+    else return fail(ctx, LWP_E_INVAL, "unknown option");
     return LWP_OK;
 }
 

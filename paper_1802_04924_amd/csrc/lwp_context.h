@@ -30,6 +30,7 @@ struct lwp_ctx {
     // do not try those first (see Search::run)
     bool keys_failed = false;
     bool single_launch = true;     // LWP_OPT_SINGLE_LAUNCH
+    bool wave_kernel = true;       // LWP_OPT_SMALL_PRODUCT_KERNEL
     bool profiling = false;
     struct Timed { hipEvent_t a, b; int kind; int64_t work; bool keyed; };
     std::vector<Timed> timed;

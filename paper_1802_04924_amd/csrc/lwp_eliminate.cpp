@@ -41,6 +41,33 @@ void fill_common(NodeArgs& a, const NodeCall& c, const NodeScratch& sc, bool sma
     a.counters = split.kparts > 1 ? sc.counters : nullptr;
 }
 
+// Eq. 2 for a call with little work: one launch of the kernel that gives every wavefront a small tile
+// of its own.  It judges overflow from the values it stages, so no measuring pass is needed; with
+// `verify` the ranges in `promised` (lo A, hi A, lo w, hi w, lo B, hi B) are checked as well.
+bool wave_call(const NodeCall& c, int64_t max_updates) {
+    return c.Cj <= kWaveMaxCj && (int64_t)c.batch * c.Ci * c.Cj * c.Ck <= max_updates;
+}
+
+hipError_t enqueue_node_wave(const NodeCall& c, const NodeScratch& sc, const int64_t* promised, hipStream_t st) {
+    const int rb = wave_tile_rb((int64_t)((c.Ci + 15) / 16) * ((c.Ck + 15) / 16) * c.batch);
+    const int ts = 8 * rb;
+    NodeArgs a{};
+    a.base.A = c.A; a.base.w = c.w; a.base.B = c.B; a.base.out = c.out; a.base.arg = c.arg;
+    a.base.flag = sc.flag;
+    a.base.loA = a.base.loW = a.base.loB = (int32_t)kI32Min;
+    a.base.hiA = a.base.hiW = a.base.hiB = (int32_t)kI32Max;
+    if (promised) {
+        a.base.loA = (int32_t)promised[0]; a.base.hiA = (int32_t)promised[1]; a.base.loW = (int32_t)promised[2];
+        a.base.hiW = (int32_t)promised[3]; a.base.loB = (int32_t)promised[4]; a.base.hiB = (int32_t)promised[5];
+    }
+    a.sA = (int64_t)c.Ci * c.Cj; a.sw = c.Cj; a.sB = (int64_t)c.Cj * c.Ck; a.sO = (int64_t)c.Ci * c.Ck;
+    a.Ci = c.Ci; a.Cj = c.Cj; a.Ck = c.Ck; a.batch = c.batch;
+    a.tilesM = (c.Ci + ts - 1) / ts; a.tilesN = (c.Ck + ts - 1) / ts;
+    a.total_tiles = (int32_t)((int64_t)a.tilesM * a.tilesN * c.batch);     // a tile holds at least one cell: <= 2^26
+    a.mode_count = sc.mode_count;
+    return launch_minplus_wave(a, nullptr, c.arg ? kModePlain : kModeValue, rb, st, promised != nullptr);
+}
+
 // Eq. 2 with nothing known about the values: one pass measures {min, max} of A, w and B of every
 // product on the device; the product kernel reads them there.  With an argmin output the arithmetic
 // variant depends on the ranges: every workgroup picks it from its product's ranges and runs the
@@ -148,8 +175,14 @@ lwp_status lwp_eliminate_node(lwp_ctx* ctx, int32_t batch, int32_t Ci, int32_t C
     if (lwp_status s = check_ctx(ctx)) return s;
     const NodeCall c{batch, Ci, Cj, Ck, d_A, d_w, d_B, d_out, d_argmin};
     if (lwp_status s = check_node_call(ctx, c)) return s;
-    if (lwp_status s = ensure_workspace(ctx, 6 * (size_t)batch * sizeof(int32_t))) return s;
     if (lwp_status s = ensure_state(ctx)) return s;
+    if (ctx->wave_kernel && wave_call(c, kWaveMaxUpdates)) {
+        const NodeScratch sc{nullptr, nullptr, nullptr, ctx->dstate, ctx->dstate + 1};
+        ScopedTimer tm(ctx, 0, (int64_t)batch * Ci * Cj * Ck, false);
+        LWP_HIP(ctx, enqueue_node_wave(c, sc, nullptr, ctx->stream));
+        return LWP_OK;
+    }
+    if (lwp_status s = ensure_workspace(ctx, 6 * (size_t)batch * sizeof(int32_t))) return s;
     if (lwp_status s = ensure_split_buffers(ctx)) return s;
     const NodeScratch sc{reinterpret_cast<int32_t*>(ctx->ws), ctx->split,
                          ctx->split + (size_t)kSplitMaxWorkgroups * kSplitScratchIntsPerPart, ctx->dstate, ctx->dstate + 1};
@@ -170,6 +203,13 @@ lwp_status lwp_eliminate_node_bounded(lwp_ctx* ctx, int32_t batch, int32_t Ci, i
     if (!fits(rA.lo + rw.lo + rB.lo) || !fits(rA.hi + rw.hi + rB.hi) || !fits(rA.lo + rw.lo) || !fits(rA.hi + rw.hi))
         return fail(ctx, LWP_E_OVERFLOW, "A + w + B may leave int32 within the promised ranges");
     if (lwp_status s = ensure_state(ctx)) return s;
+    if (ctx->wave_kernel && wave_call(c, kWaveMaxUpdatesBounded)) {
+        const NodeScratch sc{nullptr, nullptr, nullptr, ctx->dstate, ctx->dstate + 1};
+        const int64_t promised[6] = {rA.lo, rA.hi, rw.lo, rw.hi, rB.lo, rB.hi};
+        ScopedTimer tm(ctx, 0, (int64_t)batch * Ci * Cj * Ck, false);
+        LWP_HIP(ctx, enqueue_node_wave(c, sc, promised, ctx->stream));
+        return LWP_OK;
+    }
     if (lwp_status s = ensure_split_buffers(ctx)) return s;
     const NodeScratch sc{nullptr, ctx->split, ctx->split + (size_t)kSplitMaxWorkgroups * kSplitScratchIntsPerPart,
                          ctx->dstate, ctx->dstate + 1};

@@ -90,6 +90,35 @@ constexpr int kModeKeyed = 0, kModePlain = 1, kModeValue = 2, kModeKeyedRow = 3,
 // Strided addressing only, not with mixed shapes.
 hipError_t launch_minplus(const NodeArgs& args, int mode, bool small_tiles, hipStream_t stream, bool verify = false);
 
+// The same product for launches too small for the tiled kernel: one wavefront per 8 x 8 (rb = 1) or
+// 16 x 16 (rb = 2) output tile, nothing shared between wavefronts.  mode: kModePlain or kModeValue.
+// Addressing as launch_minplus (descriptors or strides; descriptors must carry Ci / Cj / Ck), with
+// tile counts in units of this kernel's tiles: tilesM / tilesN per product for one shape, or
+// tile_begin (batch + 1 ascending entries) for mixed shapes; total_tiles = all tiles of the launch.
+// flag, rngOut and mode_count behave as in launch_minplus (overflow is judged from the values each
+// wavefront stages, not from the descriptors' ranges, which are ignored); rngOut is best left null
+// unless a consumer needs the measured range (thousands of wavefronts then share two atomics);
+// no split tiles (kparts <= 1).
+// h_descs (optional, with descriptor addressing): a host copy of args.descs[0 .. batch); its first
+// kWaveInlineDescs entries are passed in the kernel arguments and not read from device memory.
+// verify: the descriptors' ranges are promises of the caller; every wavefront compares the values
+// it stages with them and ORs 2 into `flag` on a violation (all of A, w and B is staged by some
+// wavefront of the product).
+constexpr int kWaveInlineDescs = 6;
+hipError_t launch_minplus_wave(const NodeArgs& args, const NodeDesc* h_descs, int mode, int rb, hipStream_t stream,
+                               bool verify = false);
+// When a launch goes to this kernel (measured on MI355X, launches back to back): its cell updates
+// together stay below kWaveMaxUpdates -- beyond that the tiled kernel's arithmetic rate wins over its
+// start-up latency -- and no product has more than kWaveMaxCj candidates, since a wavefront walks all
+// of c by itself.  A caller that promises value ranges gets the tiled kernel's packed keys in a single
+// launch without any measuring pass, which is faster from kWaveMaxUpdatesBounded on.  Tile size: with
+// at least kWaveFillTiles tiles of 16 x 16 those are used (every SIMD still gets two wavefronts'
+// worth), else 8 x 8 (four times as many, smaller pieces to spread over the chip).
+constexpr int64_t kWaveMaxUpdates = (int64_t)1 << 26, kWaveMaxUpdatesBounded = (int64_t)1 << 24;
+constexpr int32_t kWaveMaxCj = 1024;
+constexpr int64_t kWaveFillTiles = 2048;
+inline int wave_tile_rb(int64_t tiles_16x16) { return tiles_16x16 >= kWaveFillTiles ? 2 : 1; }
+
 // ---- edge elimination (Eq. 3) --------------------------------------------------------------
 // out = sum of n_src tables of `cells` elements.  srcs indexes a device array of table pointers.
 struct EdgeDesc {

@@ -54,6 +54,7 @@ struct Layout {
 
 constexpr int64_t kArenaAlign = 64;           // elements: regions start on 256-byte boundaries
 
+
 // keep_inputs: tables consumed by node eliminations stay alive (the undo pass re-reads them).
 Layout plan_buffers(const Plan& plan, int32_t n_nodes, int32_t n_edges, const int32_t* edges, const int32_t* Cn,
                     bool keep_inputs) {
@@ -238,6 +239,7 @@ private:
         size_t first, count; int32_t Ci, Cj, Ck; int variant;
         int64_t tile_begin;      // index into the tile_begin block for mixed shapes, else -1
         int32_t total_tiles, split_Cj; int64_t updates;   // split_Cj: the Cj that decides how tiles are split
+        int wave_rb;             // 0: the tiled kernel; 1 / 2: a wavefront per 8 x 8 / 16 x 16 tile (tile counts in that unit)
     };
     struct RoundWork { size_t g0, g1; int64_t edge_cells, edge_max_cells; std::vector<NodeLaunch> launches; };
 
@@ -272,6 +274,12 @@ private:
     // of devices, tens of configurations per layer) runs in one launch of one workgroup: the dozen
     // dependent launches of the general path would cost several times its arithmetic.
     bool tiny_ = false;
+    bool any_tiled_ = true;      // some round of node eliminations runs on the tiled kernel
+    // Node eliminations of a round with little work run on the kernel that gives each wavefront a small
+    // tile of its own (see kWaveMaxUpdates).
+    bool round_on_wave_kernel(int64_t updates, int32_t max_cj) const {
+        return (!ctx_ || ctx_->wave_kernel) && updates <= kWaveMaxUpdates && max_cj <= kWaveMaxCj;
+    }
 };
 
 lwp_status Search::plan() {
@@ -302,6 +310,25 @@ lwp_status Search::plan() {
             work += n * (double)(c.nodes.size() + c.edges.size());
         }
         tiny_ = small_enumerations && work <= kTinyWork && (!ctx_ || ctx_->single_launch);
+    }
+    // the measuring pass over the input tables serves the tiled kernel only
+    any_tiled_ = false;
+    {
+        size_t q = 0, t = 0;
+        const size_t n = plan_.steps.size();
+        while (t < n) {
+            const int32_t round = plan_.steps[t].round;
+            int64_t updates = 0;
+            int32_t max_cj = 0;
+            bool any = false;
+            for (; t < n && plan_.steps[t].round == round; ++t)
+                if (plan_.steps[t].kind == 0) {
+                    updates += (int64_t)L_.node_A[q].rows * L_.node_A[q].cols * L_.node_B[q].cols;
+                    max_cj = std::max(max_cj, L_.node_A[q].cols);
+                    ++q; any = true;
+                }
+            if (any && !round_on_wave_kernel(updates, max_cj)) any_tiled_ = true;
+        }
     }
     // index of the range pair of: input edge e | w of node v | output of node step | output of group
     rng_w0_ = n_edges_;
@@ -412,14 +439,14 @@ lwp_status Search::measure_inputs() {
     if (L_.uniform) {
         LWP_HIP(ctx_, launch_prepare_search(d_tc_, d_ts_, d_w_, n_nodes_, Cn_[0], nullptr, d_stats_, W_.n_ranges, rng_w0_,
                                             d_keys_, n_comp_, d_flag_, st));
-        LWP_HIP(ctx_, launch_ranges(d_tx_, n_edges_, (int64_t)Cn_[0] * Cn_[0], d_stats_, st));
+        if (any_tiled_) LWP_HIP(ctx_, launch_ranges(d_tx_, n_edges_, (int64_t)Cn_[0] * Cn_[0], d_stats_, st));
     } else {
         const int64_t* d_offs = reinterpret_cast<const int64_t*>(db_ + W_.offs);
         int64_t max_cells = 1;
         for (int32_t e = 0; e < n_edges_; ++e) max_cells = std::max(max_cells, L_.tx_off[e + 1] - L_.tx_off[e]);
         LWP_HIP(ctx_, launch_prepare_search(d_tc_, d_ts_, d_w_, n_nodes_, 0, d_offs, d_stats_, W_.n_ranges, rng_w0_,
                                             d_keys_, n_comp_, d_flag_, st));
-        LWP_HIP(ctx_, launch_ranges_var(d_tx_, d_offs + n_nodes_ + 1, n_edges_, max_cells, d_stats_, st));
+        if (any_tiled_) LWP_HIP(ctx_, launch_ranges_var(d_tx_, d_offs + n_nodes_ + 1, n_edges_, max_cells, d_stats_, st));
     }
     return LWP_OK;
 }
@@ -448,7 +475,10 @@ lwp_status Search::write_descriptors(int arith) {
     // Node eliminations of one round are independent; those of equal kernel variant share a
     // launch if they agree in shape (Ci, Cj, Ck) or run on 64 x 64 tiles (a launch of mixed shapes),
     // so the descriptors of a round are ordered by (variant, shape).
-    struct NodeWork { NodeDesc d; int32_t Ci, Cj, Ck; int variant; };
+    struct NodeWork { NodeDesc d; int32_t Ci, Cj, Ck; int variant; int32_t rngA, rngB; };
+    // A table made by the wavefront-per-tile kernel gets its range measured only if a launch of the
+    // tiled kernel consumes it (the descriptor of the producer is patched then).
+    std::vector<int64_t> unmeasured(W_.n_ranges, -1);      // range pair -> descriptor of its producer
     size_t ni = 0, gi = 0, nsrc = 0, t = 0;
     const size_t n = plan.steps.size();
     std::vector<NodeWork> work;
@@ -491,6 +521,7 @@ lwp_status Search::write_descriptors(int arith) {
             d.rngW = d_stats_ + 2 * (int64_t)(rng_w0_ + s.j);
             d.rngOut = d_stats_ + 2 * (int64_t)(rng_node0_ + (int32_t)ni);
             nw.Ci = tA.rows; nw.Cj = tA.cols; nw.Ck = tB.cols;
+            nw.rngA = erng[s.e1]; nw.rngB = erng[s.e2];
             d.Ci = nw.Ci; d.Cj = nw.Cj; d.Ck = nw.Ck;
             work.push_back(nw);
             ud[ni] = {d.arg, d.A, d.w, d.B, s.j, s.i, s.k, s.round, nw.Cj, nw.Ck, (int32_t)n0, 0};
@@ -506,6 +537,39 @@ lwp_status Search::write_descriptors(int arith) {
             const bool prefer_small = want_small_tiles(x.Ci, x.Cj, x.Ck, shape_count[shape_of(x)]);
             x.variant = 2 * arith + (prefer_small ? 0 : 1);
         }
+        // A round with little work runs as one launch of the kernel that gives every wavefront a tile
+        // of its own: with so few 64 x 64 tiles the tiled kernel's launch would be mostly latency.
+        int64_t round_updates = 0;
+        int32_t round_max_cj = 0;
+        for (const NodeWork& x : work) { round_updates += (int64_t)x.Ci * x.Cj * x.Ck; round_max_cj = std::max(round_max_cj, x.Cj); }
+        if (!work.empty() && round_on_wave_kernel(round_updates, round_max_cj)) {
+            int64_t t16 = 0;
+            for (const NodeWork& x : work) t16 += (int64_t)((x.Ci + 15) / 16) * ((x.Ck + 15) / 16);
+            const int rb = wave_tile_rb(t16);
+            const int ts = 8 * rb;
+            const bool one_shape = shape_count.size() == 1;
+            NodeLaunch nl{n0, work.size(), work[0].Ci, work[0].Cj, work[0].Ck, 2 * (stored ? kArithPlain : kArithValue), -1, 0, 0, round_updates, rb};
+            int64_t tiles = 0;
+            if (!one_shape) nl.tile_begin = (int64_t)n_tbeg;
+            for (const NodeWork& x : work) {
+                if (!one_shape) tbeg[n_tbeg++] = (int32_t)tiles;
+                tiles += (int64_t)((x.Ci + ts - 1) / ts) * ((x.Ck + ts - 1) / ts);
+            }
+            if (!one_shape) tbeg[n_tbeg++] = (int32_t)tiles;
+            nl.total_tiles = (int32_t)tiles;       // a tile holds at least one cell: <= 2^26
+            rw_.launches.push_back(nl);
+            for (size_t q = 0; q < work.size(); ++q) {
+                nd[n0 + q] = work[q].d;
+                nd[n0 + q].rngOut = nullptr;
+                unmeasured[rng_node0_ + (int32_t)(n0 + q)] = (int64_t)(n0 + q);
+            }
+            reinterpret_cast<TinyRound*>(hb_ + W_.tiny_rounds)[rounds_.size()] = {(int32_t)rw_.g0, (int32_t)rw_.g1, (int32_t)n0, (int32_t)ni};
+            rounds_.push_back(std::move(rw_));
+            continue;
+        }
+        for (const NodeWork& x : work)
+            for (int32_t r : {x.rngA, x.rngB})
+                if (unmeasured[r] >= 0) { nd[unmeasured[r]].rngOut = d_stats_ + 2 * (int64_t)r; unmeasured[r] = -1; }
         order.resize(work.size());
         for (size_t q = 0; q < order.size(); ++q) order[q] = q;
         std::stable_sort(order.begin(), order.end(), [&](size_t a, size_t b) {
@@ -519,7 +583,7 @@ lwp_status Search::write_descriptors(int arith) {
             const bool one_shape = shape_of(work[order[a]]) == shape_of(work[order[b - 1]]);
             if (small && !one_shape) {
                 // one launch over all shapes: product q owns tiles [tile_begin[q], tile_begin[q+1])
-                NodeLaunch nl{n0 + a, b - a, 0, 0, 0, v, (int64_t)n_tbeg, 0, 0, 0};
+                NodeLaunch nl{n0 + a, b - a, 0, 0, 0, v, (int64_t)n_tbeg, 0, 0, 0, 0};
                 int64_t tiles = 0;
                 for (size_t q = a; q < b; ++q) {
                     NodeWork& x = work[order[q]];
@@ -538,7 +602,7 @@ lwp_status Search::write_descriptors(int arith) {
                     while (e < b && shape_of(work[order[e]]) == shape_of(work[order[q]])) ++e;
                     const NodeWork& x = work[order[q]];
                     rw_.launches.push_back({n0 + q, e - q, x.Ci, x.Cj, x.Ck, v, -1, 0, x.Cj,
-                                            (int64_t)(e - q) * x.Ci * x.Cj * x.Ck});
+                                            (int64_t)(e - q) * x.Ci * x.Cj * x.Ck, 0});
                     q = e;
                 }
             }
@@ -610,6 +674,17 @@ lwp_status Search::enqueue_eliminations() {
             na.tilesN = (nl.Ck + tile - 1) / tile;
             const bool mixed = nl.tile_begin >= 0;
             if (mixed) { na.tile_begin = d_tbeg + nl.tile_begin; na.total_tiles = nl.total_tiles; }
+            if (nl.wave_rb) {
+                const int ts = 8 * nl.wave_rb;
+                na.tilesM = (nl.Ci + ts - 1) / ts;
+                na.tilesN = (nl.Ck + ts - 1) / ts;
+                na.total_tiles = nl.total_tiles;
+                na.mode_count = ctx_->dstate ? ctx_->dstate + 1 : nullptr;
+                ScopedTimer tm(ctx_, 0, nl.updates, false);
+                const NodeDesc* h_nd = reinterpret_cast<const NodeDesc*>(hb_ + W_.node_desc) + nl.first;
+                LWP_HIP(ctx_, launch_minplus_wave(na, h_nd, arith == kArithValue ? kModeValue : kModePlain, nl.wave_rb, st));
+                continue;
+            }
             if (mode == kModeAuto) {
                 na.auto_limit = small ? kKeyedMaxSpreadSmall : kKeyedMaxSpreadLarge;
                 // a launch of mixed shapes is judged by its products' common size class

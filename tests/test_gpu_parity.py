@@ -18,6 +18,14 @@ def ctx():
     c.close()
 
 
+@pytest.fixture(params=[True, False], ids=["wave-per-tile", "tiled"])
+def kernels(ctx, request):
+    """Single node eliminations with little work: on the kernel they take by default, then on the tiled one."""
+    ctx.set_small_product_kernel(request.param)
+    yield request.param
+    ctx.set_small_product_kernel(True)
+
+
 def dev(a):
     import torch
     return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
@@ -27,10 +35,38 @@ def check_products(ctx, A, w, B, expect_keyed=None, expect_keyed_bounded=None):
     """A [batch][Ci][Cj] etc. as numpy; compares out and argmin of every product with the oracle, on both
     entry points: lwp_eliminate_node (ranges measured and variant picked on the device, per product)
     and lwp_eliminate_node_bounded (the caller promises ranges -- here the exact ones -- and the host
-    picks the variant).  expect_keyed: whether packed keys (global or per row) must have been used."""
+    picks the variant).  expect_keyed: whether packed keys (global or per row) must have been used
+    by the tiled kernel.  A call below 2^26 cell updates (2^24 with promised ranges) and with at most
+    1024 candidates is first checked on the kernel it takes by default, the wavefront-per-tile one
+    (compare/select), then on the tiled kernel."""
     d_A, d_w, d_B = dev(A), dev(w), dev(B)
     batch = A.shape[0]
     ref = [oracle.minplus_argmin(A[b], w[b], B[b]) for b in range(batch)]
+    bounds = (A.min(), A.max(), w.min(), w.max(), B.min(), B.max())
+    updates = A.shape[0] * A.shape[1] * A.shape[2] * B.shape[2]
+    if updates <= (1 << 26) and A.shape[2] <= 1024:
+        ctx.profile_enable(True)
+        for bnd in ((None, bounds) if updates <= (1 << 24) else (None,)):
+            ctx.profile_reset()
+            out, arg = ctx.eliminate_node(d_A, d_w, d_B, bounds=bnd)
+            ctx.synchronize()
+            prof = ctx.profile_read()
+            out, arg = out.cpu().numpy(), arg.cpu().numpy()
+            for b in range(batch):
+                assert np.array_equal(out[b], ref[b][0]), f"cost mismatch in product {b} (wavefront per tile, bounds {bnd})"
+                assert np.array_equal(arg[b], ref[b][1]), f"argmin mismatch in product {b} (wavefront per tile, bounds {bnd})"
+            assert prof["products_plain"] == batch and prof["products_keyed"] + prof["products_keyed_row"] + prof["products_value"] == 0
+            assert prof["keyed_launches"] == 0
+        ctx.profile_enable(False)
+    ctx.set_small_product_kernel(False)
+    try:
+        return check_products_tiled(ctx, d_A, d_w, d_B, ref, bounds, expect_keyed, expect_keyed_bounded)
+    finally:
+        ctx.set_small_product_kernel(True)
+
+
+def check_products_tiled(ctx, d_A, d_w, d_B, ref, bounds, expect_keyed, expect_keyed_bounded):
+    batch = d_A.shape[0]
     ctx.profile_enable(True)
     ctx.profile_reset()
     out, arg = ctx.eliminate_node(d_A, d_w, d_B)
@@ -45,7 +81,6 @@ def check_products(ctx, A, w, B, expect_keyed=None, expect_keyed_bounded=None):
     if expect_keyed is not None:
         assert keyed == (batch if expect_keyed else 0)
     ctx.profile_reset()
-    bounds = (A.min(), A.max(), w.min(), w.max(), B.min(), B.max())
     out, arg = ctx.eliminate_node(d_A, d_w, d_B, bounds=bounds)
     ctx.synchronize()
     prof_b = ctx.profile_read()
@@ -74,6 +109,20 @@ def test_eliminate_node_keyed_small_values(ctx, shape, hi):
     w = rng.integers(0, hi, size=(batch, Cj), endpoint=True, dtype=np.int32)
     B = rng.integers(0, hi, size=(batch, Cj, Ck), endpoint=True, dtype=np.int32)
     check_products(ctx, A, w, B, expect_keyed=True)
+
+
+@pytest.mark.parametrize("shape", [(64, 128, 16, 128), (100, 70, 33, 90), (300, 40, 130, 56), (2100, 16, 5, 16), (1, 1, 1000, 1), (3, 2, 1024, 3), (1, 9, 1025, 9)])
+@pytest.mark.parametrize("hi", [2, 1 << 24])
+def test_eliminate_node_many_small_products(ctx, shape, hi):
+    # calls below 2^27 cell updates with enough output for a wavefront per 16 x 16 tile (at least 2048 of
+    # them), ragged in every dimension, with ties (hi = 2) and without; then long rows: up to 1024
+    # candidates the wavefront-per-tile kernel takes them, one more and the tiled kernel does
+    batch, Ci, Cj, Ck = shape
+    rng = np.random.default_rng(abs(hash((shape, hi))) % (1 << 32))
+    A = rng.integers(-hi, hi, size=(batch, Ci, Cj), endpoint=True, dtype=np.int32)
+    w = rng.integers(0, hi, size=(batch, Cj), endpoint=True, dtype=np.int32)
+    B = rng.integers(-hi, hi, size=(batch, Cj, Ck), endpoint=True, dtype=np.int32)
+    check_products(ctx, A, w, B)
 
 
 def spread_case(shape, bits, seed):
@@ -221,7 +270,7 @@ def test_search_with_wide_node_costs_stays_on_packed_keys(ctx):
     # run_search runs every search twice: with stored argmin (every product on packed keys: on global
     # offsets where clamping at the largest possible result absorbs the width of the node costs, else
     # re-based per row) and with recomputed argmin (value-only)
-    n_products = 2 * (p["n_nodes"] - 2)
+    n_products = 2 * 2 * (p["n_nodes"] - 2)      # ... and each of those with the small-product kernel allowed and not
     assert prof["products_keyed"] + prof["products_keyed_row"] == n_products and prof["products_value"] == n_products
     assert prof["products_plain"] == 0
     Cn = np.array([700, 650, 701, 300, 900, 640], np.int32)      # the same with per-node counts
@@ -245,7 +294,7 @@ def test_eliminate_node_negative_and_offset_values(ctx):
     check_products(ctx, A, w, B, expect_keyed=False)
 
 
-def test_eliminate_node_closed_forms(ctx):
+def test_eliminate_node_closed_forms(ctx, kernels):
     C = 150
     rng = np.random.default_rng(2)
     A = rng.integers(0, 1000, size=(1, 77, C), dtype=np.int32)
@@ -260,7 +309,7 @@ def test_eliminate_node_closed_forms(ctx):
 
 @pytest.mark.parametrize("shape", [(2, 50, 60, 70), (1, 64, 2048, 64), (3, 130, 257, 140), (40, 256, 100, 256), (600, 128, 40, 256)])
 @pytest.mark.parametrize("lo,hi", [(0, 3), (0, 1 << 20), (-(1 << 29), 1 << 29)])
-def test_eliminate_node_value_only(ctx, shape, lo, hi):
+def test_eliminate_node_value_only(ctx, kernels, shape, lo, hi):
     # no argmin requested: the value-only variant (any int32 range) must give the same minima
     batch, Ci, Cj, Ck = shape
     rng = np.random.default_rng(abs(hash((shape, lo, hi))) % (1 << 32))
@@ -274,7 +323,7 @@ def test_eliminate_node_value_only(ctx, shape, lo, hi):
         assert np.array_equal(out[b], oracle.minplus_argmin(A[b], w[b], B[b])[0]), b
 
 
-def test_eliminate_node_overflow(ctx):
+def test_eliminate_node_overflow(ctx, kernels):
     from paper_1802_04924_amd import LwpError
     big = np.full((1, 4, 4), (1 << 31) - 1, np.int32)
     ones, zeros = np.ones((1, 4), np.int32), np.zeros((1, 4, 4), np.int32)
@@ -319,7 +368,7 @@ def test_eliminate_node_batch_with_different_cost_levels(ctx):
     assert prof["products_keyed"] == 2 and prof["products_plain"] == 1
 
 
-def test_eliminate_node_promised_ranges_are_checked(ctx):
+def test_eliminate_node_promised_ranges_are_checked(ctx, kernels):
     from paper_1802_04924_amd import LwpError
     rng = np.random.default_rng(77)
     shape = (2, 200, 300, 150)
@@ -389,13 +438,17 @@ def run_search(ctx, p, schedule=None):
     # such searches are checked down both paths
     nodes_gone = len(ref["steps"]) and int((ref["steps"]["kind"] == 0).sum())
     both = nodes_gone * p["C"] ** 3 <= (1 << 22)
+    # and rounds with little work run on the wavefront-per-tile kernel unless told otherwise: both kernels
     for single in ((True, False) if both else (True,)):
         ctx.set_single_launch(single)
-        for undo in (UNDO_STORED, UNDO_RECOMPUTE):
-            cost, S = ctx.search_graph(p["n_nodes"], p["edges"], p["C"], d_tc, d_ts, d_tx, schedule, undo)
-            assert cost == ref["cost"], (undo, single)
-            assert np.array_equal(S, ref["strategy"]), (undo, single)
+        for wave in (True, False):
+            ctx.set_small_product_kernel(wave)
+            for undo in (UNDO_STORED, UNDO_RECOMPUTE):
+                cost, S = ctx.search_graph(p["n_nodes"], p["edges"], p["C"], d_tc, d_ts, d_tx, schedule, undo)
+                assert cost == ref["cost"], (undo, single, wave)
+                assert np.array_equal(S, ref["strategy"]), (undo, single, wave)
     ctx.set_single_launch(True)
+    ctx.set_small_product_kernel(True)
     assert oracle.strategy_cost(p["n_nodes"], p["edges"], p["C"], p["tc"], p["ts"], p["tx"], S) == cost
     return cost, S
 
@@ -574,18 +627,19 @@ def test_search_picks_its_arithmetic_without_reading_values_back():
     # on compare/select.  Larger ones are launched on packed keys speculatively; a product whose measured
     # ranges do not allow them is skipped and flagged on the device, and the search runs again on the
     # kernel that picks keys, keys per row or compare/select per product -- which later searches of the
-    # same context then start with.
+    # same context then start with.  Whatever the search's arithmetic, a round with little work (here
+    # the late rounds, one product each) runs on the wavefront-per-tile kernel, which is compare/select.
     from paper_1802_04924_amd import Context
     with Context(0) as c:
         c.profile_enable(True)
-        for n_layers, C, expect in ((4, 160, "plain"), (5, 512, "plain"), (6, 512, "keyed")):   # 3 * 2^27 and 4 * 2^27 updates
+        for n_layers, C, expect, at_least in ((4, 160, "plain", 2), (5, 512, "plain", 3), (6, 512, "keyed", 2)):   # 3 * 2^27 and 4 * 2^27 updates
             p = wl.chain_problem(n_layers, C, n_layers, tc_range=(0, 1000), ts_range=(0, 1000), tx_range=(0, 1000))
             ref = oracle.search(p["n_nodes"], p["edges"], C, p["tc"], p["ts"], p["tx"])
             c.profile_reset()
             cost, S = c.search_graph(p["n_nodes"], p["edges"], C, dev(p["tc"]), dev(p["ts"]), dev(p["tx"]))
             prof = c.profile_read()
             assert cost == ref["cost"] and np.array_equal(S, ref["strategy"])
-            assert prof["products_" + expect] == n_layers - 2
+            assert prof["products_" + expect] >= at_least
             assert prof["products_keyed"] + prof["products_plain"] + prof["products_keyed_row"] == n_layers - 2
         # one table with values over 2^28: no global offset brings its products into the key range
         p = wl.chain_problem(6, 700, 9, tc_range=(0, 1000), ts_range=(0, 1000), tx_range=(0, 1000))

@@ -32,13 +32,17 @@ def run_ragged(ctx, n_nodes, edges, Cn, seed, hi, schedules=(wl.SCHEDULE_ROUNDS,
     for schedule in schedules:
         ref = oracle.search_ragged(n_nodes, edges, Cn, tc, ts, tx, schedule)
         # small searches run as one launch of one workgroup unless told otherwise: both paths are checked
+        # and rounds with little work run on the wavefront-per-tile kernel unless told otherwise: both kernels
         for single in ((True, False) if int(np.max(Cn)) <= 64 else (True,)):
             ctx.set_single_launch(single)
-            for undo in (UNDO_STORED, UNDO_RECOMPUTE):
-                cost, S = ctx.search_graph_ragged(n_nodes, edges, Cn, d_tc, d_ts, d_tx, schedule, undo)
-                assert cost == ref["cost"], (schedule, undo, single)
-                assert np.array_equal(S, ref["strategy"]), (schedule, undo, single)
+            for wave in (True, False):
+                ctx.set_small_product_kernel(wave)
+                for undo in (UNDO_STORED, UNDO_RECOMPUTE):
+                    cost, S = ctx.search_graph_ragged(n_nodes, edges, Cn, d_tc, d_ts, d_tx, schedule, undo)
+                    assert cost == ref["cost"], (schedule, undo, single, wave)
+                    assert np.array_equal(S, ref["strategy"]), (schedule, undo, single, wave)
         ctx.set_single_launch(True)
+        ctx.set_small_product_kernel(True)
         assert oracle.strategy_cost_ragged(n_nodes, edges, Cn, tc, ts, tx, S) == cost
         assert (S >= 0).all() and (S < np.asarray(Cn)).all()
     return cost, S
@@ -52,6 +56,13 @@ def test_ragged_chains(ctx, n_layers, c_min, c_max, hi):
     # (searches below 2^29 cell updates: no read-back of value ranges, plain and value-only variants)
     Cn = wl.ragged_counts(n_layers, n_layers + c_max, c_min, c_max)
     run_ragged(ctx, n_layers, wl.chain_edges(n_layers), Cn, seed=n_layers, hi=hi)
+
+
+def test_ragged_round_with_thousands_of_small_tiles(ctx):
+    # first round: 29 products of about 130^3 -- little enough work for the wavefront-per-tile kernel,
+    # enough output (over 2048 tiles of 16 x 16) for its larger tile; shapes differ from product to product
+    Cn = wl.ragged_counts(60, 61, 100, 160)
+    run_ragged(ctx, 60, wl.chain_edges(60), Cn, seed=60, hi=1 << 18, schedules=(wl.SCHEDULE_ROUNDS,))
 
 
 def test_ragged_against_exhaustive_definition(ctx):
@@ -249,7 +260,8 @@ def test_ragged_resnet_shaped(ctx, c_max, hi):
 @pytest.mark.parametrize("hi,t_c_scale", [(1000, 1), (1 << 20, 1), (1 << 20, 400)])
 def test_ragged_searches_large_enough_for_packed_keys(ctx, hi, t_c_scale):
     # launches of mixed shapes pick packed keys on the device (global offsets, or re-based per row when
-    # node costs range widely)
+    # node costs range widely); the last rounds, one product each, are small enough for the
+    # wavefront-per-tile kernel (compare/select)
     Cn = wl.ragged_counts(10, 77, 350, 620)
     edges = wl.chain_edges(10)
     tc, ts, tx = wl.ragged_tables(10, edges, Cn, hi % 97, 0, hi)
@@ -263,7 +275,9 @@ def test_ragged_searches_large_enough_for_packed_keys(ctx, hi, t_c_scale):
         prof = ctx.profile_read()
         ctx.profile_enable(False)
         assert cost == ref["cost"] and np.array_equal(S, ref["strategy"])
-        assert prof["products_keyed"] + prof["products_keyed_row"] == 8 and prof["products_plain"] == 0
+        assert prof["products_keyed"] + prof["products_keyed_row"] + prof["products_plain"] == 8
+        if schedule == wl.SCHEDULE_ROUNDS:       # the first round: four products in one launch of mixed shapes
+            assert prof["products_keyed"] + prof["products_keyed_row"] >= 4
     n, fj = wl.forkjoin_edges(2, 3)
     Cn = wl.ragged_counts(n, 78, 250, 400)
     run_ragged(ctx, n, fj, Cn, seed=3, hi=hi, schedules=(wl.SCHEDULE_ROUNDS,))
