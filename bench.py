@@ -116,6 +116,8 @@ class Workload:
         from paper_1802_04924_amd import Context, workloads as wl
         self.name, self.args = name, args
         self.ctx = Context(0)
+        if args.tiled_only:
+            self.ctx.set_small_product_kernel(False)
         self.result = {}
         self.plan = None
         undo = 1 if args.undo == "recompute" else 0
@@ -328,6 +330,8 @@ def main():
     ap.add_argument("--configs", type=int, default=0, help="override C of the workload")
     ap.add_argument("--undo", default="stored", choices=["stored", "recompute"],
                     help="undo pass: look up stored argmin tables, or recompute the argmin as Alg. 1 does")
+    ap.add_argument("--tiled-only", action="store_true",
+                    help="keep every node elimination on the tiled kernel (no wavefront-per-tile kernel for small rounds)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-events", action="store_true",
                     help="diagnostic: do not bracket the elimination launches with HIP events (no roofline figures)")
