@@ -20,8 +20,11 @@
  *     lwp_eliminate_edge only enqueue and return (the first call of a size may grow a buffer of
  *     the context, which waits for the stream once); what their kernels find on the device -- a
  *     sum that may leave int32, a value outside promised ranges -- is reported by the next
- *     lwp_synchronize.  lwp_search_graph and lwp_build_cost_tables return after the stream has
- *     drained.
+ *     lwp_synchronize.  lwp_build_cost_tables returns after the stream has drained; a search
+ *     returns once its last kernel has delivered the result to the host (the kernel writes it
+ *     into pinned memory, the status word last, and the host waits for that word): nothing of
+ *     the search is still reading the caller's tables then, though the kernel may not have
+ *     retired yet -- later work on the stream is ordered behind it as usual.
  *   - Errors are return codes; on error the outputs are untouched unless stated.  Argument
  *     and graph validation happen before any GPU work.  lwp_last_error gives the reason.
  *   - A context must not be used from two threads at once.

@@ -111,10 +111,25 @@ def load():
 
 
 def _np_i32(a, shape=None):
-    a = np.ascontiguousarray(a, dtype=np.int32)
+    if not (type(a) is np.ndarray and a.dtype == np.int32 and a.flags.c_contiguous):
+        a = np.ascontiguousarray(a, dtype=np.int32)
     if shape is not None:
         a = a.reshape(shape)
     return a
+
+
+def _ptr(a):
+    """Address of a numpy array's data (a search of tens of microseconds feels `a.ctypes.data`, which builds a helper object)."""
+    try:
+        return ctypes.addressof(ctypes.c_char.from_buffer(a))
+    except (TypeError, ValueError):           # read-only or empty
+        return a.ctypes.data
+
+
+def _result_buffer(n):
+    """int32 [n] the library writes a strategy into: (numpy view, address)."""
+    buf = (ctypes.c_int32 * n)()
+    return np.frombuffer(buf, dtype=np.int32), ctypes.addressof(buf)
 
 
 def plan_graph(n_nodes, edges, schedule=SCHEDULE_ROUNDS):
@@ -216,8 +231,8 @@ class SearchPlan:
     def run(self):
         """Returns (cost, strategy[n_nodes]) for what the tables hold now."""
         cost = ctypes.c_int32(0)
-        S = np.empty(self.n_nodes, np.int32)
-        rc = self._lib.lwp_search_plan_run(self._h, ctypes.byref(cost), S.ctypes.data)
+        S, S_ptr = _result_buffer(self.n_nodes)
+        rc = self._lib.lwp_search_plan_run(self._h, ctypes.byref(cost), S_ptr)
         self._ctx._check(rc, "search_plan_run")
         return cost.value, S
 
@@ -330,10 +345,10 @@ class Context:
         if E and tuple(tx.shape) != (E, C, C):
             raise ValueError("t_x must be [n_edges][C][C]")
         cost = ctypes.c_int32(0)
-        S = np.empty(n_nodes, np.int32)
-        rc = self._lib.lwp_search_graph_ex(self._h, n_nodes, E, edges.ctypes.data, C, _dev(tc, "tc"), _dev(ts, "ts"),
+        S, S_ptr = _result_buffer(n_nodes)
+        rc = self._lib.lwp_search_graph_ex(self._h, n_nodes, E, _ptr(edges), C, _dev(tc, "tc"), _dev(ts, "ts"),
                                            _dev(tx, "tx") if E else None, int(schedule), int(undo), ctypes.byref(cost),
-                                           S.ctypes.data)
+                                           S_ptr)
         self._check(rc, "search_graph")
         return cost.value, S
 
@@ -353,10 +368,10 @@ class Context:
             if ok and (tx.dim() != 1 or tx.numel() != n_x):
                 raise ValueError("t_x must be flat with sum(C_src * C_dst) entries")
         cost = ctypes.c_int32(0)
-        S = np.empty(n_nodes, np.int32)
-        rc = self._lib.lwp_search_graph_ragged(self._h, n_nodes, E, edges.ctypes.data, C_node.ctypes.data,
+        S, S_ptr = _result_buffer(n_nodes)
+        rc = self._lib.lwp_search_graph_ragged(self._h, n_nodes, E, _ptr(edges), _ptr(C_node),
                                                _dev(tc, "tc"), _dev(ts, "ts"), _dev(tx, "tx") if E else None,
-                                               int(schedule), int(undo), ctypes.byref(cost), S.ctypes.data)
+                                               int(schedule), int(undo), ctypes.byref(cost), S_ptr)
         self._check(rc, "search_graph_ragged")
         return cost.value, S
 

@@ -225,6 +225,10 @@ hipError_t launch_back_substitute(const PairDesc* d_pairs, int32_t n_pairs, cons
 // rngOut and per-descriptor flags are ignored (overflow is found exactly and OR-ed into *flag, which
 // the kernel first clears).  w receives t_c + t_s for all n_w entries.  keys: one per component.
 // result / host_result as launch_back_substitute.
+// A descriptor block of at most kTinyInlineBytes can travel in the kernel arguments instead of device
+// memory (inline_block = 1): the search then needs no upload before its one launch.  The eight
+// descriptor pointers (rounds ... undo) are then byte offsets into that block, cast to pointers.
+constexpr int kTinyInlineBytes = 3584;
 struct TinyRound { int32_t g0, g1, n0, n1; };
 struct TinyArgs {
     const int32_t* tc;
@@ -246,8 +250,14 @@ struct TinyArgs {
     int32_t* flag;
     int32_t* result;
     int32_t* host_result;
+    int32_t inline_block, pad;
 };
-hipError_t launch_tiny_search(const TinyArgs& args, hipStream_t stream);
+// d_block / h_block: the descriptor block on the device (what the pointers in args point into) and its
+// host copy, block_bytes long.  If h_block is given and the block is small enough it is passed in the
+// kernel arguments and the device copy is not read (it need not have been uploaded).
+constexpr bool tiny_block_fits_arguments(size_t block_bytes) { return block_bytes <= (size_t)kTinyInlineBytes; }
+hipError_t launch_tiny_search(const TinyArgs& args, const void* d_block, const void* h_block, size_t block_bytes,
+                              hipStream_t stream);
 
 // ---- VALU issue-rate probe ---------------------------------------------------------------------
 // `blocks` workgroups of 256 threads each run `iters` iterations of a register-only add + three-way

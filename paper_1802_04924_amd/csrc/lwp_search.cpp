@@ -1,5 +1,7 @@
 // Alg. 1 behind the C ABI: buffer planning, value-range analysis, descriptors and the launch
 // sequence of a whole search (eliminate -> solve the residual graph -> undo).
+#include <atomic>
+#include <chrono>
 #include <cstring>
 #include <map>
 #include <new>
@@ -218,7 +220,10 @@ public:
     // The pieces of run() for a caller that prepares once and runs many times.
     lwp_status prepare_replay();                 // descriptors for any int32 input, uploaded; synchronises
     lwp_status enqueue_all();                    // everything between the tables and the result copy
-    lwp_status finish(int32_t* out_cost, int32_t* out_strategy) const;   // after the stream has drained
+    lwp_status finish(int32_t* out_cost, int32_t* out_strategy) const;   // after the result has arrived
+    void mark_result_pending() { h_result_[2 + n_nodes_] = kResultPending; }   // before enqueue_all
+    lwp_status wait_for_result();                // until the undo kernel's last word has arrived
+    static constexpr int32_t kResultPending = 0x40000000;   // no status word has this bit
 
 private:
     lwp_status enqueue_tiny();                   // the whole search as one launch of one workgroup
@@ -360,9 +365,11 @@ void Search::bind(char* ws, char* pin) {
 lwp_status Search::run(int32_t* out_cost, int32_t* out_strategy) {
     if (tiny_) {
         if (lwp_status s = write_descriptors(stored_ ? kArithPlain : kArithValue)) return s;
-        if (lwp_status s = upload_descriptors()) return s;
+        // a block that fits the kernel arguments travels there: no upload
+        if (!tiny_block_fits_arguments(W_.desc_bytes)) { if (lwp_status s = upload_descriptors()) return s; }
+        mark_result_pending();
         if (lwp_status s = enqueue_tiny()) return s;
-        LWP_HIP(ctx_, hipStreamSynchronize(stream_));
+        if (lwp_status s = wait_for_result()) return s;
         return finish(out_cost, out_strategy);
     }
     int64_t updates = 0;
@@ -374,6 +381,7 @@ lwp_status Search::run(int32_t* out_cost, int32_t* out_strategy) {
     for (;;) {
         // the measuring pass needs no descriptor (only, with per-node counts, the offsets, which go
         // ahead): it runs on the device while the host writes the descriptors
+        mark_result_pending();
         if (lwp_status s = upload_offsets()) return s;
         if (lwp_status s = measure_inputs()) return s;
         if (lwp_status s = write_descriptors(arith)) return s;
@@ -381,7 +389,7 @@ lwp_status Search::run(int32_t* out_cost, int32_t* out_strategy) {
         if (lwp_status s = enqueue_eliminations()) return s;
         if (lwp_status s = enqueue_residual_and_undo()) return s;
         if (lwp_status s = enqueue_result_copy()) return s;
-        LWP_HIP(ctx_, hipStreamSynchronize(stream_));
+        if (lwp_status s = wait_for_result()) return s;
         if (arith == kArithKeyed && (h_result_[2 + n_nodes_] & 4)) {
             // some table's values range too widely for packed keys on global offsets: once more with
             // the kernel that picks per product; later searches of this context start there
@@ -424,7 +432,7 @@ lwp_status Search::enqueue_tiny() {
     a.undo = reinterpret_cast<const UndoDesc*>(db_ + W_.undo);
     a.n_undo = plan_.n_node_steps; a.n_nodes = n_nodes_;
     a.flag = d_flag_; a.result = d_result_; a.host_result = h_result_;
-    LWP_HIP(ctx_, launch_tiny_search(a, stream_));
+    LWP_HIP(ctx_, launch_tiny_search(a, db_, hb_, W_.desc_bytes, stream_));
     return LWP_OK;
 }
 
@@ -725,6 +733,22 @@ lwp_status Search::enqueue_result_copy() {
     return LWP_OK;       // the undo kernel writes the result into the pinned host buffer itself
 }
 
+// Waits for the result: the undo kernel writes it into the pinned buffer, the status word last, so the
+// host polls that word (a wake-up through the runtime's stream wait costs several microseconds more);
+// after a while without it the ordinary wait takes over.
+lwp_status Search::wait_for_result() {
+    volatile int32_t* word = h_result_ + 2 + n_nodes_;
+    const auto t0 = std::chrono::steady_clock::now();
+    for (int spins = 0; *word == kResultPending; ++spins) {
+        if ((spins & 255) == 255 && std::chrono::steady_clock::now() - t0 > std::chrono::microseconds(300)) {
+            LWP_HIP(ctx_, hipStreamSynchronize(stream_));
+            break;
+        }
+    }
+    std::atomic_thread_fence(std::memory_order_acquire);
+    return LWP_OK;
+}
+
 lwp_status Search::finish(int32_t* out_cost, int32_t* out_strategy) const {
     if (h_result_[2 + n_nodes_] & 3) return fail(ctx_, LWP_E_OVERFLOW, "a sum may leave int32 (found on the device from the tables' actual ranges)");
     // the total is formed in 64 bits on the device
@@ -802,8 +826,9 @@ lwp_status lwp_search_plan_run(lwp_search_plan* plan, int32_t* out_cost, int32_t
     lwp_ctx* ctx = plan->ctx;
     if (lwp_status s = check_ctx(ctx)) return s;
     if (!out_cost || !out_strategy) return fail(ctx, LWP_E_INVAL, "null pointer");
+    plan->search->mark_result_pending();
     if (lwp_status s = plan->search->enqueue_all()) return s;
-    LWP_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    if (lwp_status s = plan->search->wait_for_result()) return s;
     return plan->search->finish(out_cost, out_strategy);
 }
 

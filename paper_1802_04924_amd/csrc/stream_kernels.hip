@@ -2,6 +2,9 @@
 // ranges of the input tables, the residual-graph minimum (Alg. 1, enumeration of the final graph
 // with K <= 2 per component) and the undo pass (Alg. 1, last loop).  All of these move each
 // table element once; they are bound by HBM bandwidth or by dependent-load latency, not by ALUs.
+#include <cstddef>
+#include <cstring>
+
 #include "lwp_kernels.h"
 
 namespace lwp {
@@ -428,9 +431,14 @@ __device__ __forceinline__ void back_substitute_body(
     if (threadIdx.x == 0) result[2 + n_nodes] = (flag ? *flag : 0) | wbad;
     // the result goes straight to the caller's pinned host buffer (posted writes over the host
     // link, complete when the kernel is): one dependent copy fewer at the end of every search
+    // The last word is the one a host that polls the buffer waits for: it is written after a
+    // system-scope fence behind everything else.
     if (host_result) {
         __syncthreads();
-        for (int t = threadIdx.x; t < 3 + n_nodes; t += kUndoThreads) host_result[t] = result[t];
+        for (int t = threadIdx.x; t < 2 + n_nodes; t += kUndoThreads) host_result[t] = result[t];
+        __threadfence_system();
+        __syncthreads();
+        if (threadIdx.x == 0) host_result[2 + n_nodes] = result[2 + n_nodes];
     }
 }
 
@@ -463,10 +471,32 @@ __device__ __forceinline__ unsigned long long block_min_u64(unsigned long long v
     return r;
 }
 
-__global__ __launch_bounds__(kUndoThreads) void tiny_search_kernel(const TinyArgs a) {
+struct TinyLaunch {
+    TinyArgs a;
+    alignas(16) unsigned char block[kTinyInlineBytes];
+};
+static_assert(sizeof(TinyLaunch) <= 4096, "kernel arguments");
+
+constexpr int kTinyPrefix = 256;     // products of a round whose cells are dealt out together
+__global__ __launch_bounds__(kUndoThreads) void tiny_search_kernel(const TinyLaunch t) {
     __shared__ unsigned long long smin[kUndoThreads / 64];
+    __shared__ int cell_begin[kTinyPrefix + 1];
     const int tid = threadIdx.x;
     bool bad = false;
+    TinyArgs a = t.a;
+    if (a.inline_block) {
+        // the descriptors are in the kernel-argument segment: turn the offsets into pointers
+        using kaptr = const char __attribute__((address_space(4)))*;
+        const char* blk = (const char*)((kaptr)__builtin_amdgcn_kernarg_segment_ptr() + offsetof(TinyLaunch, block));
+        a.rounds = (const TinyRound*)(blk + (uintptr_t)a.rounds);
+        a.nodes = (const NodeDesc*)(blk + (uintptr_t)a.nodes);
+        a.edges = (const EdgeDesc*)(blk + (uintptr_t)a.edges);
+        a.srcs = (const int32_t* const*)(blk + (uintptr_t)a.srcs);
+        a.pairs = (const PairDesc*)(blk + (uintptr_t)a.pairs);
+        a.singles = (const SingleDesc*)(blk + (uintptr_t)a.singles);
+        a.comps = (const CompDesc*)(blk + (uintptr_t)a.comps);
+        a.undo = (const UndoDesc*)(blk + (uintptr_t)a.undo);
+    }
     if (tid == 0) *a.flag = 0;
     for (int64_t x = tid; x < a.n_w; x += kUndoThreads) {
         const long long s = (long long)a.tc[x] + (long long)a.ts[x];
@@ -487,21 +517,59 @@ __global__ __launch_bounds__(kUndoThreads) void tiny_search_kernel(const TinyArg
             }
         }
         if (rd.g1 > rd.g0) __syncthreads();
-        for (int n = rd.n0; n < rd.n1; ++n) {                      // Eq. 2
-            const NodeDesc d = a.nodes[n];
-            const int cells = d.Ci * d.Ck;
-            for (int x = tid; x < cells; x += kUndoThreads) {
-                const int ra = x / d.Ck, cb = x - ra * d.Ck;
-                const int32_t* Arow = d.A + (int64_t)ra * d.Cj;
-                long long best = 0;
-                int arg = 0;
-                for (int c = 0; c < d.Cj; ++c) {
-                    const long long s = (long long)Arow[c] + d.w[c] + d.B[(int64_t)c * d.Ck + cb];
-                    bad |= (s != (long long)(int32_t)s);
-                    if (c == 0 || s < best) { best = s; arg = c; }
+        // Eq. 2.  The cells of all products of the round are dealt to the threads together (a prefix of
+        // cell counts in LDS tells a thread which product its cell belongs to): product after product
+        // would cost the workgroup one chain of dependent loads per product instead of one per round.
+        auto one_cell = [&](const NodeDesc& d, int x) {
+            const int ra = x / d.Ck, cb = x - ra * d.Ck;
+            const int32_t* Arow = d.A + (int64_t)ra * d.Cj;
+            long long best = 0;
+            int arg = 0;
+            // four candidates' loads in flight at a time (clamped loads repeat the last candidate)
+            for (int c0 = 0; c0 < d.Cj; c0 += 4) {
+                int32_t av[4], wv[4], bv[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int c = min(c0 + u, d.Cj - 1);
+                    av[u] = Arow[c]; wv[u] = d.w[c]; bv[u] = d.B[(int64_t)c * d.Ck + cb];
                 }
-                d.out[x] = (int32_t)best;
-                if (d.arg) d.arg[x] = arg;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int c = c0 + u;
+                    const long long s = (long long)av[u] + wv[u] + bv[u];
+                    if (c < d.Cj) {
+                        bad |= (s != (long long)(int32_t)s);
+                        if (c == 0 || s < best) { best = s; arg = c; }
+                    }
+                }
+            }
+            d.out[x] = (int32_t)best;
+            if (d.arg) d.arg[x] = arg;
+        };
+        const int n_prod = rd.n1 - rd.n0;
+        if (n_prod > 1 && n_prod <= kTinyPrefix) {
+            if (tid < n_prod) cell_begin[tid + 1] = a.nodes[rd.n0 + tid].Ci * a.nodes[rd.n0 + tid].Ck;
+            __syncthreads();
+            if (tid == 0) {
+                cell_begin[0] = 0;
+                for (int q = 0; q < n_prod; ++q) cell_begin[q + 1] += cell_begin[q];
+            }
+            __syncthreads();
+            const int total = cell_begin[n_prod];
+            for (int x = tid; x < total; x += kUndoThreads) {
+                int lo = 0, hi = n_prod;
+                while (hi - lo > 1) {
+                    const int mid = (lo + hi) >> 1;
+                    if (cell_begin[mid] <= x) lo = mid; else hi = mid;
+                }
+                const NodeDesc d = a.nodes[rd.n0 + lo];
+                one_cell(d, x - cell_begin[lo]);
+            }
+        } else {
+            for (int n = rd.n0; n < rd.n1; ++n) {
+                const NodeDesc d = a.nodes[n];
+                const int cells = d.Ci * d.Ck;
+                for (int x = tid; x < cells; x += kUndoThreads) one_cell(d, x);
             }
         }
         __syncthreads();
@@ -695,8 +763,25 @@ hipError_t launch_component_min(const CompDesc* d_comp, unsigned long long n_pre
     return hipGetLastError();
 }
 
-hipError_t launch_tiny_search(const TinyArgs& args, hipStream_t stream) {
-    hipLaunchKernelGGL(tiny_search_kernel, dim3(1), dim3(kUndoThreads), 0, stream, args);
+hipError_t launch_tiny_search(const TinyArgs& args, const void* d_block, const void* h_block, size_t block_bytes,
+                              hipStream_t stream) {
+    TinyLaunch t;            // (the launch copies the arguments)
+    t.a = args;
+    t.a.inline_block = 0;
+    if (h_block && d_block && tiny_block_fits_arguments(block_bytes)) {
+        std::memcpy(t.block, h_block, block_bytes);
+        auto off = [&](const void* p) { return (uintptr_t)((const char*)p - (const char*)d_block); };
+        t.a.rounds = (const TinyRound*)off(args.rounds);
+        t.a.nodes = (const NodeDesc*)off(args.nodes);
+        t.a.edges = (const EdgeDesc*)off(args.edges);
+        t.a.srcs = (const int32_t* const*)off(args.srcs);
+        t.a.pairs = (const PairDesc*)off(args.pairs);
+        t.a.singles = (const SingleDesc*)off(args.singles);
+        t.a.comps = (const CompDesc*)off(args.comps);
+        t.a.undo = (const UndoDesc*)off(args.undo);
+        t.a.inline_block = 1;
+    }
+    hipLaunchKernelGGL(tiny_search_kernel, dim3(1), dim3(kUndoThreads), 0, stream, t);
     return hipGetLastError();
 }
 

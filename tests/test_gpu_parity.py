@@ -462,6 +462,16 @@ def test_search_config0(ctx):
     run_search(ctx, p, wl.SCHEDULE_LEFT_FOLD)
 
 
+def test_small_search_with_hundreds_of_products_per_round(ctx):
+    # a search small enough for one launch of one workgroup whose rounds hold 349, 174, 87, ... node
+    # eliminations: more than, and fewer than, the products whose cells that kernel deals out together;
+    # its descriptors (90 KB) do not fit the kernel arguments, those of the 12-layer chain do
+    for n_layers, C in ((700, 3), (12, 5), (300, 2)):
+        p = wl.chain_problem(n_layers, C, n_layers, tx_range=(0, 3))       # heavy ties
+        run_search(ctx, p)
+        run_search(ctx, p, wl.SCHEDULE_LEFT_FOLD)
+
+
 def test_search_graph_entry_point_itself(ctx):
     # lwp_search_graph as the header declares it (stored argmin), called through ctypes directly
     import ctypes
