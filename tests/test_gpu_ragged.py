@@ -65,6 +65,15 @@ def test_ragged_round_with_thousands_of_small_tiles(ctx):
     run_ragged(ctx, 60, wl.chain_edges(60), Cn, seed=60, hi=1 << 18, schedules=(wl.SCHEDULE_ROUNDS,))
 
 
+@pytest.mark.parametrize("big,hi", [(600, 1 << 16), (900, 1 << 16), (900, 1 << 28)])
+def test_ragged_small_round_feeds_a_large_one(ctx, big, hi):
+    # round 1: two products of big x 4 x big (the wavefront-per-tile kernel); round 2: one product of big^3
+    # on the tiled kernel (compare/select at 600, packed keys at 900: 2^29 cell updates and more), whose
+    # operands are both outputs of round 1 -- their value ranges must have been measured there
+    Cn = np.array([big, 4, big, 4, big], np.int32)
+    run_ragged(ctx, 5, wl.chain_edges(5), Cn, seed=big, hi=hi, schedules=(wl.SCHEDULE_ROUNDS,))
+
+
 def test_ragged_against_exhaustive_definition(ctx):
     from oracle import brute
     edges = np.array([(0, 1), (1, 2), (0, 2), (2, 3), (3, 4), (2, 4)], np.int32)
