@@ -431,14 +431,15 @@ __device__ __forceinline__ void back_substitute_body(
     if (threadIdx.x == 0) result[2 + n_nodes] = (flag ? *flag : 0) | wbad;
     // the result goes straight to the caller's pinned host buffer (posted writes over the host
     // link, complete when the kernel is): one dependent copy fewer at the end of every search
-    // The last word is the one a host that polls the buffer waits for: it is written after a
-    // system-scope fence behind everything else.
+    // The last word is the one a host that polls the buffer waits for: one thread stores it with
+    // system-scope release semantics after a barrier behind everybody's stores (a release is
+    // cumulative over the barrier; one wavefront pays for it instead of sixteen fencing each).
     if (host_result) {
         __syncthreads();
         for (int t = threadIdx.x; t < 2 + n_nodes; t += kUndoThreads) host_result[t] = result[t];
-        __threadfence_system();
         __syncthreads();
-        if (threadIdx.x == 0) host_result[2 + n_nodes] = result[2 + n_nodes];
+        if (threadIdx.x == 0)
+            __hip_atomic_store(&host_result[2 + n_nodes], result[2 + n_nodes], __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
     }
 }
 
