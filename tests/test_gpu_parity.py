@@ -368,10 +368,12 @@ def test_eliminate_node_batch_with_different_cost_levels(ctx):
     assert prof["products_keyed"] == 2 and prof["products_plain"] == 1
 
 
-def test_eliminate_node_promised_ranges_are_checked(ctx, kernels):
+@pytest.mark.parametrize("shape", [(2, 200, 300, 150), (2, 100, 150, 75), (600, 32, 20, 32)])
+def test_eliminate_node_promised_ranges_are_checked(ctx, kernels, shape):
+    # (the first shape is past the size up to which a call with promised ranges takes the wavefront-per-tile
+    # kernel, the second is within it, the third within it on that kernel's 16 x 16 tiles)
     from paper_1802_04924_amd import LwpError
     rng = np.random.default_rng(77)
-    shape = (2, 200, 300, 150)
     A = rng.integers(0, 1000, size=shape[:3], dtype=np.int32)
     w = rng.integers(0, 1000, size=(shape[0], shape[2]), dtype=np.int32)
     B = rng.integers(0, 1000, size=(shape[0], shape[2], shape[3]), dtype=np.int32)
@@ -386,7 +388,9 @@ def test_eliminate_node_promised_ranges_are_checked(ctx, kernels):
                 assert np.array_equal(out[b].cpu().numpy(), ro)
                 assert arg is None or np.array_equal(arg[b].cpu().numpy(), ra)
     # one element outside the promise, in any operand, anywhere: found on the device
-    for which, idx in (("A", (1, 199, 299)), ("A", (0, 0, 0)), ("w", (1, 150)), ("B", (0, 299, 149)), ("B", (1, 3, 70))):
+    b, Ci, Cj, Ck = shape
+    for which, idx in (("A", (b - 1, Ci - 1, Cj - 1)), ("A", (0, 0, 0)), ("w", (b - 1, Cj // 2)), ("B", (0, Cj - 1, Ck - 1)),
+                       ("B", (b - 1, 3, Ck // 2))):
         for value in (1000, -1, (1 << 31) - 1, -(1 << 31)):
             X = {"A": A.copy(), "w": w.copy(), "B": B.copy()}
             X[which][idx] = value
