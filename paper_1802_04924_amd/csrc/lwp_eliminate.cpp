@@ -63,7 +63,7 @@ hipError_t enqueue_node_wave(const NodeCall& c, const NodeScratch& sc, const int
     a.sA = (int64_t)c.Ci * c.Cj; a.sw = c.Cj; a.sB = (int64_t)c.Cj * c.Ck; a.sO = (int64_t)c.Ci * c.Ck;
     a.Ci = c.Ci; a.Cj = c.Cj; a.Ck = c.Ck; a.batch = c.batch;
     a.tilesM = (c.Ci + ts - 1) / ts; a.tilesN = (c.Ck + ts - 1) / ts;
-    a.total_tiles = (int32_t)((int64_t)a.tilesM * a.tilesN * c.batch);     // a tile holds at least one cell: <= 2^26
+    a.total_tiles = (int32_t)((int64_t)a.tilesM * a.tilesN * c.batch);     // a tile holds at least one cell: <= 2^27
     a.mode_count = sc.mode_count;
     return launch_minplus_wave(a, nullptr, c.arg ? kModePlain : kModeValue, rb, st, promised != nullptr);
 }

@@ -114,7 +114,7 @@ hipError_t launch_minplus_wave(const NodeArgs& args, const NodeDesc* h_descs, in
 // launch without any measuring pass, which is faster from kWaveMaxUpdatesBounded on.  Tile size: with
 // at least kWaveFillTiles tiles of 16 x 16 those are used (every SIMD still gets two wavefronts'
 // worth), else 8 x 8 (four times as many, smaller pieces to spread over the chip).
-constexpr int64_t kWaveMaxUpdates = (int64_t)1 << 26, kWaveMaxUpdatesBounded = (int64_t)1 << 24;
+constexpr int64_t kWaveMaxUpdates = (int64_t)3 << 25, kWaveMaxUpdatesBounded = (int64_t)1 << 24;
 constexpr int32_t kWaveMaxCj = 1024;
 constexpr int64_t kWaveFillTiles = 2048;
 inline int wave_tile_rb(int64_t tiles_16x16) { return tiles_16x16 >= kWaveFillTiles ? 2 : 1; }

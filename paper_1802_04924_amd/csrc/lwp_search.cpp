@@ -564,7 +564,7 @@ lwp_status Search::write_descriptors(int arith) {
                 tiles += (int64_t)((x.Ci + ts - 1) / ts) * ((x.Ck + ts - 1) / ts);
             }
             if (!one_shape) tbeg[n_tbeg++] = (int32_t)tiles;
-            nl.total_tiles = (int32_t)tiles;       // a tile holds at least one cell: <= 2^26
+            nl.total_tiles = (int32_t)tiles;       // a tile holds at least one cell: <= 2^27
             rw_.launches.push_back(nl);
             for (size_t q = 0; q < work.size(); ++q) {
                 nd[n0 + q] = work[q].d;

@@ -22,6 +22,7 @@ namespace lwp {
 namespace {
 
 constexpr int kWaveGroup = 256;            // threads per workgroup: 4 independent wavefronts
+constexpr int kWaveLongChunkTiles = 4096;  // launches of at most this many 8 x 8 tiles stage 128 candidates at a time
 constexpr int kWavesPerGroup = kWaveGroup / 64;
 
 using gcptr = const int32_t __attribute__((address_space(1)))*;
@@ -47,16 +48,19 @@ struct WaveArgs {
     NodeDesc inl[kWaveInlineDescs];
 };
 
-template <int RB, bool VALUE>
+template <int RB, int KC, bool VALUE>
 __global__ __launch_bounds__(kWaveGroup, 4) void minplus_wave_kernel(const WaveArgs wa) {
     const NodeArgs& p = wa.a;
     constexpr int TS = 8 * RB;             // output tile of one wavefront: TS x TS
-    constexpr int KC = 128 / RB;           // candidates per chunk
+    // KC: candidates per chunk.  128 with 8 x 8 tiles when every wavefront of the launch has a SIMD to
+    // itself or nearly (fewer, longer chunks: nobody else hides the latency of its loads); 64 otherwise
+    // (half the LDS and half the registers in flight, so that 7 instead of 4 wavefronts fit a SIMD and a
+    // launch of up to 7168 wavefronts is resident at once instead of running in two generations).
     constexpr int AST = KC + 4;            // row stride of the A stage: 16-byte rows, banks staggered by 4
     constexpr int NL = TS * KC / 64;       // loads per lane and chunk, for A and for B
     constexpr int NLW = KC / 64;
     constexpr int RPL = 64 / TS;           // rows of B one load instruction covers
-    static_assert(NL == 16 && KC % 64 == 0 && 64 % TS == 0, "staging assignment");
+    static_assert(NL % 2 == 0 && KC % 64 == 0 && KC % 16 == 0 && 64 % TS == 0, "staging assignment");
     __shared__ __attribute__((aligned(16))) int32_t lds[kWavesPerGroup][TS * AST + KC * TS];
 
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -171,10 +175,10 @@ __global__ __launch_bounds__(kWaveGroup, 4) void minplus_wave_kernel(const WaveA
 #pragma unroll
         for (int j = 0; j < RB; ++j) { best[i][j] = 0x7fffffff; arg[i][j] = 0; }
 
-    // One chunk's arithmetic on what the stage holds.  Groups of 8 candidates, read from LDS four at
+    // One chunk's arithmetic on what the stage holds.  Groups of 16 candidates, read from LDS four at
     // a time, the next four before the arithmetic of the current four (a wavefront alone on its SIMD
     // has nobody else to hide the latency).  The stage always holds KC valid candidates, so reading
-    // ahead never leaves it.  Within a group a cell records the position (0..7, constants that cost
+    // ahead never leaves it.  Within a group a cell records the position (0..15, constants that cost
     // no register) of its last strict improvement; the group's first index is added once per group.
     auto compute = [&](int c0) {
         const int kc = min(KC, Cj - c0);
@@ -220,25 +224,25 @@ __global__ __launch_bounds__(kWaveGroup, 4) void minplus_wave_kernel(const WaveA
             }
         };
         lds_read(0, av[0], bv[0]);
-        for (int cc = 0; cc < kc; cc += 8) {
-            lds_read(cc + 4, av[1], bv[1]);
-            __builtin_amdgcn_sched_barrier(0);
+        for (int cc = 0; cc < kc; cc += 16) {
 #pragma unroll
             for (int i = 0; i < RB; ++i)
 #pragma unroll
-                for (int j = 0; j < RB; ++j) rel[i][j] = 8;
-            update(0, av[0], bv[0]);
-            __builtin_amdgcn_sched_barrier(0);
-            lds_read(min(cc + 8, KC - 4), av[0], bv[0]);
-            __builtin_amdgcn_sched_barrier(0);
-            update(4, av[1], bv[1]);
+                for (int j = 0; j < RB; ++j) rel[i][j] = 16;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                // the reads of the next four candidates go out before the arithmetic of these four
+                lds_read(min(cc + 4 * g + 4, KC - 4), av[(g + 1) & 1], bv[(g + 1) & 1]);
+                __builtin_amdgcn_sched_barrier(0);
+                update(4 * g, av[g & 1], bv[g & 1]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
             if (!VALUE) {
 #pragma unroll
                 for (int i = 0; i < RB; ++i)
 #pragma unroll
-                    for (int j = 0; j < RB; ++j) arg[i][j] = rel[i][j] < 8 ? c0 + cc + rel[i][j] : arg[i][j];
+                    for (int j = 0; j < RB; ++j) arg[i][j] = rel[i][j] < 16 ? c0 + cc + rel[i][j] : arg[i][j];
             }
-            __builtin_amdgcn_sched_barrier(0);
         }
     };
 
@@ -333,12 +337,16 @@ hipError_t launch_minplus_wave(const NodeArgs& args, const NodeDesc* h_descs, in
         wa.n_inline = args.batch < kWaveInlineDescs ? args.batch : kWaveInlineDescs;
         for (int q = 0; q < wa.n_inline; ++q) wa.inl[q] = h_descs[q];
     }
+    // 8 x 8 tiles: long chunks while the launch's wavefronts have a SIMD each (1024 SIMDs, 4 deep)
+    const bool long_chunks = rb == 1 && args.total_tiles <= kWaveLongChunkTiles;
     if (mode == kModeValue) {
-        if (rb == 1) hipLaunchKernelGGL((minplus_wave_kernel<1, true>), grid, block, 0, stream, wa);
-        else hipLaunchKernelGGL((minplus_wave_kernel<2, true>), grid, block, 0, stream, wa);
+        if (long_chunks) hipLaunchKernelGGL((minplus_wave_kernel<1, 128, true>), grid, block, 0, stream, wa);
+        else if (rb == 1) hipLaunchKernelGGL((minplus_wave_kernel<1, 64, true>), grid, block, 0, stream, wa);
+        else hipLaunchKernelGGL((minplus_wave_kernel<2, 64, true>), grid, block, 0, stream, wa);
     } else {
-        if (rb == 1) hipLaunchKernelGGL((minplus_wave_kernel<1, false>), grid, block, 0, stream, wa);
-        else hipLaunchKernelGGL((minplus_wave_kernel<2, false>), grid, block, 0, stream, wa);
+        if (long_chunks) hipLaunchKernelGGL((minplus_wave_kernel<1, 128, false>), grid, block, 0, stream, wa);
+        else if (rb == 1) hipLaunchKernelGGL((minplus_wave_kernel<1, 64, false>), grid, block, 0, stream, wa);
+        else hipLaunchKernelGGL((minplus_wave_kernel<2, 64, false>), grid, block, 0, stream, wa);
     }
     return hipGetLastError();
 }

@@ -36,7 +36,7 @@ def check_products(ctx, A, w, B, expect_keyed=None, expect_keyed_bounded=None):
     entry points: lwp_eliminate_node (ranges measured and variant picked on the device, per product)
     and lwp_eliminate_node_bounded (the caller promises ranges -- here the exact ones -- and the host
     picks the variant).  expect_keyed: whether packed keys (global or per row) must have been used
-    by the tiled kernel.  A call below 2^26 cell updates (2^24 with promised ranges) and with at most
+    by the tiled kernel.  A call below 3 * 2^25 cell updates (2^24 with promised ranges) and with at most
     1024 candidates is first checked on the kernel it takes by default, the wavefront-per-tile one
     (compare/select), then on the tiled kernel."""
     d_A, d_w, d_B = dev(A), dev(w), dev(B)
@@ -44,7 +44,7 @@ def check_products(ctx, A, w, B, expect_keyed=None, expect_keyed_bounded=None):
     ref = [oracle.minplus_argmin(A[b], w[b], B[b]) for b in range(batch)]
     bounds = (A.min(), A.max(), w.min(), w.max(), B.min(), B.max())
     updates = A.shape[0] * A.shape[1] * A.shape[2] * B.shape[2]
-    if updates <= (1 << 26) and A.shape[2] <= 1024:
+    if updates <= (3 << 25) and A.shape[2] <= 1024:
         ctx.profile_enable(True)
         for bnd in ((None, bounds) if updates <= (1 << 24) else (None,)):
             ctx.profile_reset()
