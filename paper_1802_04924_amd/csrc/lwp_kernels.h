@@ -157,9 +157,13 @@ hipError_t launch_ranges_var(const int32_t* d_tables, const int64_t* d_off, int3
 // w_pair0 + v receives {min, max} of row v of w, or {INT32_MAX, INT32_MIN} if a sum of that row
 // leaves int32; all other of the n_pairs stats pairs are initialised for atomic min/max and
 // keys[0..n_keys) to all ones.  *d_flag (optional) is set to 0.
+// Optionally the launch also copies up_bytes (a multiple of 16, both addresses 16-byte aligned) from
+// up_src -- pinned host memory the device can read -- to up_dst: a small descriptor block then needs no
+// copy of its own.  The range must not hold d_node_off (other workgroups of the launch read that).
 hipError_t launch_prepare_search(const int32_t* tc, const int32_t* ts, int32_t* w, int32_t n_nodes, int32_t C,
                                  const int64_t* d_node_off, int32_t* d_stats, int32_t n_pairs, int32_t w_pair0,
-                                 unsigned long long* d_keys, int32_t n_keys, int32_t* d_flag, hipStream_t stream);
+                                 unsigned long long* d_keys, int32_t n_keys, int32_t* d_flag, hipStream_t stream,
+                                 const void* up_src = nullptr, void* up_dst = nullptr, size_t up_bytes = 0);
 
 // ---- residual graph and back-substitution (Alg. 1, enumeration of the final graph and undo) --
 struct PairDesc {       // residual component with two nodes joined by one edge

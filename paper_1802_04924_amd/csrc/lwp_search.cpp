@@ -280,6 +280,8 @@ private:
     // dependent launches of the general path would cost several times its arithmetic.
     bool tiny_ = false;
     bool any_tiled_ = true;      // some round of node eliminations runs on the tiled kernel
+    bool upload_with_prepare_ = false;   // measure_inputs() also copies the descriptor block to the device
+    static constexpr size_t kUploadWithPrepare = 16384;
     // Node eliminations of a round with little work run on the kernel that gives each wavefront a small
     // tile of its own (see kWaveMaxUpdates).
     bool round_on_wave_kernel(int64_t updates, int32_t max_cj) const {
@@ -383,9 +385,19 @@ lwp_status Search::run(int32_t* out_cost, int32_t* out_strategy) {
         // ahead): it runs on the device while the host writes the descriptors
         mark_result_pending();
         if (lwp_status s = upload_offsets()) return s;
-        if (lwp_status s = measure_inputs()) return s;
-        if (lwp_status s = write_descriptors(arith)) return s;
-        if (lwp_status s = upload_descriptors()) return s;
+        // A large descriptor block is written while the measuring pass runs and uploaded by a copy of
+        // its own; a small one is written first (a microsecond) and uploaded by the first launch.
+        upload_with_prepare_ = W_.desc_bytes <= kUploadWithPrepare && W_.desc_bytes % 16 == 0;
+        if (upload_with_prepare_) {
+            if (lwp_status s = write_descriptors(arith)) return s;
+            const lwp_status s = measure_inputs();
+            upload_with_prepare_ = false;
+            if (s) return s;
+        } else {
+            if (lwp_status s = measure_inputs()) return s;
+            if (lwp_status s = write_descriptors(arith)) return s;
+            if (lwp_status s = upload_descriptors()) return s;
+        }
         if (lwp_status s = enqueue_eliminations()) return s;
         if (lwp_status s = enqueue_residual_and_undo()) return s;
         if (lwp_status s = enqueue_result_copy()) return s;
@@ -444,16 +456,21 @@ lwp_status Search::upload_offsets() {
 
 lwp_status Search::measure_inputs() {
     hipStream_t st = stream_;
+    // a small descriptor block (already written then) rides along with the first launch
+    const size_t up_skip = align_up(W_.offs_bytes, 16);
+    const void* up_src = upload_with_prepare_ ? hb_ + up_skip : nullptr;
+    void* up_dst = upload_with_prepare_ ? db_ + up_skip : nullptr;
+    const size_t up_bytes = upload_with_prepare_ ? W_.desc_bytes - up_skip : 0;
     if (L_.uniform) {
         LWP_HIP(ctx_, launch_prepare_search(d_tc_, d_ts_, d_w_, n_nodes_, Cn_[0], nullptr, d_stats_, W_.n_ranges, rng_w0_,
-                                            d_keys_, n_comp_, d_flag_, st));
+                                            d_keys_, n_comp_, d_flag_, st, up_src, up_dst, up_bytes));
         if (any_tiled_) LWP_HIP(ctx_, launch_ranges(d_tx_, n_edges_, (int64_t)Cn_[0] * Cn_[0], d_stats_, st));
     } else {
         const int64_t* d_offs = reinterpret_cast<const int64_t*>(db_ + W_.offs);
         int64_t max_cells = 1;
         for (int32_t e = 0; e < n_edges_; ++e) max_cells = std::max(max_cells, L_.tx_off[e + 1] - L_.tx_off[e]);
         LWP_HIP(ctx_, launch_prepare_search(d_tc_, d_ts_, d_w_, n_nodes_, 0, d_offs, d_stats_, W_.n_ranges, rng_w0_,
-                                            d_keys_, n_comp_, d_flag_, st));
+                                            d_keys_, n_comp_, d_flag_, st, up_src, up_dst, up_bytes));
         if (any_tiled_) LWP_HIP(ctx_, launch_ranges_var(d_tx_, d_offs + n_nodes_ + 1, n_edges_, max_cells, d_stats_, st));
     }
     return LWP_OK;

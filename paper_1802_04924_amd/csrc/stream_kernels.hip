@@ -188,12 +188,17 @@ __global__ __launch_bounds__(kThreads) void prepare_search_kernel(const int32_t*
                                                                   const int64_t* __restrict__ node_off,
                                                                   int32_t* __restrict__ stats, int32_t n_pairs,
                                                                   int32_t w_pair0, unsigned long long* __restrict__ keys,
-                                                                  int32_t n_keys, int32_t* __restrict__ flag) {
+                                                                  int32_t n_keys, int32_t* __restrict__ flag,
+                                                                  const uint4* __restrict__ up_src, uint4* __restrict__ up_dst,
+                                                                  int32_t up_n16) {
     if ((int)blockIdx.x >= n_nodes) {
         const int t = ((int)blockIdx.x - n_nodes) * kThreads + threadIdx.x;
         if (t == 0 && flag) *flag = 0;
         if (t < n_pairs && (t < w_pair0 || t >= w_pair0 + n_nodes)) { stats[2 * t] = 0x7fffffff; stats[2 * t + 1] = (int32_t)0x80000000; }
         if (t < n_keys) keys[t] = ~0ull;
+        // the search's descriptors, from the pinned host mirror into device memory (small blocks only)
+        const int stride = ((int)gridDim.x - n_nodes) * kThreads;
+        for (int i = t; i < up_n16; i += stride) up_dst[i] = up_src[i];
         return;
     }
     __shared__ int smin[kThreads / 64], smax[kThreads / 64], sbad[kThreads / 64];
@@ -727,11 +732,15 @@ hipError_t launch_ranges_var(const int32_t* d_tables, const int64_t* d_off, int3
 
 hipError_t launch_prepare_search(const int32_t* tc, const int32_t* ts, int32_t* w, int32_t n_nodes, int32_t C,
                                  const int64_t* d_node_off, int32_t* d_stats, int32_t n_pairs, int32_t w_pair0,
-                                 unsigned long long* d_keys, int32_t n_keys, int32_t* d_flag, hipStream_t stream) {
-    const int n_init = (n_pairs > n_keys ? n_pairs : n_keys) + 1;
+                                 unsigned long long* d_keys, int32_t n_keys, int32_t* d_flag, hipStream_t stream,
+                                 const void* up_src, void* up_dst, size_t up_bytes) {
+    if (up_bytes % 16 || ((uintptr_t)up_src | (uintptr_t)up_dst) % 16 || up_bytes > ((size_t)1 << 24)) return hipErrorInvalidValue;
+    int n_init = (n_pairs > n_keys ? n_pairs : n_keys) + 1;
+    if ((int)(up_bytes / 16) > n_init) n_init = (int)(up_bytes / 16);
     dim3 grid((unsigned)(n_nodes + (n_init + kThreads - 1) / kThreads));
     hipLaunchKernelGGL(prepare_search_kernel, grid, dim3(kThreads), 0, stream, tc, ts, w, n_nodes, C, d_node_off, d_stats,
-                       n_pairs, w_pair0, d_keys, n_keys, d_flag);
+                       n_pairs, w_pair0, d_keys, n_keys, d_flag, static_cast<const uint4*>(up_src), static_cast<uint4*>(up_dst),
+                       (int32_t)(up_bytes / 16));
     return hipGetLastError();
 }
 
