@@ -176,11 +176,20 @@ def search_workspace_bytes_ragged(n_nodes, edges, C_node, schedule=SCHEDULE_ROUN
                                                      int(schedule), int(undo)))
 
 
+_I32 = None      # torch.int32, looked up once (torch is imported on first use only)
+
+
 def _dev(t, what):
-    import torch
-    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.int32 and t.is_contiguous()):
-        raise TypeError(f"{what} must be a contiguous int32 CUDA tensor")
-    return t.data_ptr()
+    global _I32
+    if _I32 is None:
+        import torch
+        _I32 = torch.int32
+    try:
+        if t.is_cuda and t.dtype is _I32 and t.is_contiguous():
+            return t.data_ptr()
+    except AttributeError:
+        pass
+    raise TypeError(f"{what} must be a contiguous int32 CUDA tensor")
 
 
 def eliminate_node_noalloc(A, w, B, out, argmin=None, status=None, stream=None):
