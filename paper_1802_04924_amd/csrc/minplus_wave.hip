@@ -23,6 +23,7 @@ namespace {
 
 constexpr int kWaveGroup = 256;            // threads per workgroup: 4 independent wavefronts
 constexpr int kWaveLongChunkTiles = 4096;  // launches of at most this many 8 x 8 tiles stage 128 candidates at a time
+constexpr int kWaveSplitTiles = 1024;      // launches of at most this many 8 x 8 tiles: four wavefronts per tile
 constexpr int kWavesPerGroup = kWaveGroup / 64;
 
 using gcptr = const int32_t __attribute__((address_space(1)))*;
@@ -48,7 +49,10 @@ struct WaveArgs {
     NodeDesc inl[kWaveInlineDescs];
 };
 
-template <int RB, int KC, bool VALUE>
+// SPLIT: the four wavefronts of a workgroup share ONE tile, each with a quarter of the candidates, and
+// merge through LDS (for launches so small that a tile per wavefront would leave three SIMDs in four
+// idle: a wavefront issues one instruction per four cycles however idle the rest of the chip is).
+template <int RB, int KC, bool VALUE, bool SPLIT>
 __global__ __launch_bounds__(kWaveGroup, 4) void minplus_wave_kernel(const WaveArgs wa) {
     const NodeArgs& p = wa.a;
     constexpr int TS = 8 * RB;             // output tile of one wavefront: TS x TS
@@ -63,10 +67,12 @@ __global__ __launch_bounds__(kWaveGroup, 4) void minplus_wave_kernel(const WaveA
     static_assert(NL % 2 == 0 && KC % 64 == 0 && KC % 16 == 0 && 64 % TS == 0, "staging assignment");
     __shared__ __attribute__((aligned(16))) int32_t lds[kWavesPerGroup][TS * AST + KC * TS];
 
+    static_assert(!SPLIT || RB == 1, "shared tiles are 8 x 8");
+    __shared__ int32_t merge[SPLIT ? kWavesPerGroup : 1][SPLIT ? 2 * 64 + 8 : 1];
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = threadIdx.x & 63;
-    const int item = blockIdx.x * kWavesPerGroup + wave;
-    if (item >= p.total_tiles) return;     // whole wavefronts leave; the kernel has no barrier
+    const int item = SPLIT ? (int)blockIdx.x : (int)blockIdx.x * kWavesPerGroup + wave;
+    if (!SPLIT && item >= p.total_tiles) return;     // whole wavefronts leave; without SPLIT the kernel has no barrier
 
     // ---- which product, which tile (uniform) ----
     int bi, tl;
@@ -112,6 +118,13 @@ __global__ __launch_bounds__(kWaveGroup, 4) void minplus_wave_kernel(const WaveA
     const int tilesN = (Ck + TS - 1) / TS;
     const int tm = tl / tilesN, tn = tl - tm * tilesN;
     const int a0 = tm * TS, b0 = tn * TS;
+    // this wavefront's share of the candidates: all of them, or a quarter
+    int cbeg = 0, cend = Cj;
+    if (SPLIT) {
+        const int per = (Cj + kWavesPerGroup - 1) / kWavesPerGroup;
+        cbeg = min(wave * per, Cj);
+        cend = min(cbeg + per, Cj);
+    }
 
     const gcptr A = (gcptr)(uintptr_t)d.A;
     const gcptr W = (gcptr)(uintptr_t)d.w;
@@ -133,7 +146,7 @@ __global__ __launch_bounds__(kWaveGroup, 4) void minplus_wave_kernel(const WaveA
     const uint32_t bcol4 = (uint32_t)min(b0 + (lane % TS), Ck - 1) * 4u;   // clamped column, fixed for the tile
     const uint32_t Ck4 = (uint32_t)Ck * 4u;                  // <= 2^18
     auto fetch = [&](int c0) {
-        const int last = Cj - 1 - c0;                        // the chunk's last valid candidate (>= 0)
+        const int last = cend - 1 - c0;                      // the chunk's last valid candidate (>= 0)
         uint32_t offA[NLW], offB[NL];
 #pragma unroll
         for (int j = 0; j < NLW; ++j) offA[j] = (uint32_t)min(lane, max(last - j * 64, 0)) * 4u;
@@ -181,7 +194,7 @@ __global__ __launch_bounds__(kWaveGroup, 4) void minplus_wave_kernel(const WaveA
     // ahead never leaves it.  Within a group a cell records the position (0..15, constants that cost
     // no register) of its last strict improvement; the group's first index is added once per group.
     auto compute = [&](int c0) {
-        const int kc = min(KC, Cj - c0);
+        const int kc = min(KC, cend - c0);
         int32_t av[2][RB][4], bv[2][4][RB];
         auto lds_read = [&](int cc, int32_t (&a)[RB][4], int32_t (&b)[4][RB]) {
 #pragma unroll
@@ -249,10 +262,10 @@ __global__ __launch_bounds__(kWaveGroup, 4) void minplus_wave_kernel(const WaveA
     // The loads of chunk s are in flight while chunk s - 1 is worked on; then they are written to the
     // stage.  The stage is this wavefront's own and its LDS operations complete in order; the fences
     // keep the compiler from moving the writes across the reads of the chunk before.
-    const int nch = (Cj + KC - 1) / KC;
+    const int nch = (cend - cbeg + KC - 1) / KC;      // 0 for a wavefront whose share of the candidates is empty
     for (int s = 0; s <= nch; ++s) {
-        if (s < nch) fetch(s * KC);
-        if (s > 0) compute((s - 1) * KC);
+        if (s < nch) fetch(cbeg + s * KC);
+        if (s > 0) compute(cbeg + (s - 1) * KC);
         if (s < nch) {
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
 #pragma unroll
@@ -271,6 +284,31 @@ __global__ __launch_bounds__(kWaveGroup, 4) void minplus_wave_kernel(const WaveA
         }
     }
 
+    if (SPLIT) {
+        // the wavefronts' shares ascend in c: folding them in that order with a strict '<' keeps the
+        // lowest index among equal candidates
+        int32_t sl[6] = {loA, hiA, loW, hiW, loB, hiB};
+        if (d.flag) {
+            sl[0] = wave_min_i32(loA); sl[1] = wave_max_i32(hiA); sl[2] = wave_min_i32(loW);
+            sl[3] = wave_max_i32(hiW); sl[4] = wave_min_i32(loB); sl[5] = wave_max_i32(hiB);
+        }
+        merge[wave][lane] = best[0][0];
+        merge[wave][64 + lane] = arg[0][0];
+        if (lane < 6) merge[wave][128 + lane] = sl[lane];
+        __syncthreads();
+        if (wave != 0) return;
+#pragma unroll
+        for (int q = 1; q < kWavesPerGroup; ++q) {
+            const int32_t ob = merge[q][lane], oa = merge[q][64 + lane];
+            const bool lt = ob < best[0][0];
+            best[0][0] = lt ? ob : best[0][0];
+            arg[0][0] = lt ? oa : arg[0][0];
+            loA = min(sl[0], merge[q][128]); hiA = max(sl[1], merge[q][129]); loW = min(sl[2], merge[q][130]);
+            hiW = max(sl[3], merge[q][131]); loB = min(sl[4], merge[q][132]); hiB = max(sl[5], merge[q][133]);
+            sl[0] = loA; sl[1] = hiA; sl[2] = loW; sl[3] = hiW; sl[4] = loB; sl[5] = hiB;
+        }
+        loA = sl[0]; hiA = sl[1]; loW = sl[2]; hiW = sl[3]; loB = sl[4]; hiB = sl[5];     // uniform already
+    }
     if (d.flag) {
         const long long xloA = wave_min_i32(loA), xhiA = wave_max_i32(hiA), xloB = wave_min_i32(loB), xhiB = wave_max_i32(hiB),
                         xloW = wave_min_i32(loW), xhiW = wave_max_i32(hiW);
@@ -337,17 +375,21 @@ hipError_t launch_minplus_wave(const NodeArgs& args, const NodeDesc* h_descs, in
         wa.n_inline = args.batch < kWaveInlineDescs ? args.batch : kWaveInlineDescs;
         for (int q = 0; q < wa.n_inline; ++q) wa.inl[q] = h_descs[q];
     }
-    // 8 x 8 tiles: long chunks while the launch's wavefronts have a SIMD each (1024 SIMDs, 4 deep)
-    const bool long_chunks = rb == 1 && args.total_tiles <= kWaveLongChunkTiles;
-    if (mode == kModeValue) {
-        if (long_chunks) hipLaunchKernelGGL((minplus_wave_kernel<1, 128, true>), grid, block, 0, stream, wa);
-        else if (rb == 1) hipLaunchKernelGGL((minplus_wave_kernel<1, 64, true>), grid, block, 0, stream, wa);
-        else hipLaunchKernelGGL((minplus_wave_kernel<2, 64, true>), grid, block, 0, stream, wa);
-    } else {
-        if (long_chunks) hipLaunchKernelGGL((minplus_wave_kernel<1, 128, false>), grid, block, 0, stream, wa);
-        else if (rb == 1) hipLaunchKernelGGL((minplus_wave_kernel<1, 64, false>), grid, block, 0, stream, wa);
-        else hipLaunchKernelGGL((minplus_wave_kernel<2, 64, false>), grid, block, 0, stream, wa);
-    }
+    // 8 x 8 tiles: up to kWaveSplitTiles of them, four wavefronts share a tile (a workgroup per tile);
+    // up to kWaveLongChunkTiles a wavefront each with long chunks; beyond, short chunks
+    const bool split = rb == 1 && args.total_tiles <= kWaveSplitTiles;
+    const bool long_chunks = rb == 1 && !split && args.total_tiles <= kWaveLongChunkTiles;
+    if (split) grid = dim3((unsigned)args.total_tiles);
+#define LWP_WAVE(RB, KC, SPLIT) \
+    do { \
+        if (mode == kModeValue) hipLaunchKernelGGL((minplus_wave_kernel<RB, KC, true, SPLIT>), grid, block, 0, stream, wa); \
+        else hipLaunchKernelGGL((minplus_wave_kernel<RB, KC, false, SPLIT>), grid, block, 0, stream, wa); \
+    } while (0)
+    if (split) LWP_WAVE(1, 64, true);
+    else if (long_chunks) LWP_WAVE(1, 128, false);
+    else if (rb == 1) LWP_WAVE(1, 64, false);
+    else LWP_WAVE(2, 64, false);
+#undef LWP_WAVE
     return hipGetLastError();
 }
 
