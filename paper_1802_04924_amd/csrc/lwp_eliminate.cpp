@@ -45,7 +45,7 @@ void fill_common(NodeArgs& a, const NodeCall& c, const NodeScratch& sc, bool sma
 // of its own.  It judges overflow from the values it stages, so no measuring pass is needed; with
 // `verify` the ranges in `promised` (lo A, hi A, lo w, hi w, lo B, hi B) are checked as well.
 bool wave_call(const NodeCall& c, int64_t max_updates) {
-    return c.Cj <= kWaveMaxCj && (int64_t)c.batch * c.Ci * c.Cj * c.Ck <= max_updates;
+    return (int64_t)c.batch * c.Ci * c.Cj * c.Ck <= max_updates;
 }
 
 hipError_t enqueue_node_wave(const NodeCall& c, const NodeScratch& sc, const int64_t* promised, hipStream_t st) {

@@ -109,13 +109,13 @@ hipError_t launch_minplus_wave(const NodeArgs& args, const NodeDesc* h_descs, in
                                bool verify = false);
 // When a launch goes to this kernel (measured on MI355X, launches back to back): its cell updates
 // together stay below kWaveMaxUpdates -- beyond that the tiled kernel's arithmetic rate wins over its
-// start-up latency -- and no product has more than kWaveMaxCj candidates, since a wavefront walks all
-// of c by itself.  A caller that promises value ranges gets the tiled kernel's packed keys in a single
-// launch without any measuring pass, which is faster from kWaveMaxUpdatesBounded on.  Tile size: with
-// at least kWaveFillTiles tiles of 16 x 16 those are used (every SIMD still gets two wavefronts'
-// worth), else 8 x 8 (four times as many, smaller pieces to spread over the chip).
+// start-up latency.  (However long the products' rows: a launch within that limit with many candidates
+// has few tiles, and then four wavefronts share each.)  A caller that promises value ranges gets the
+// tiled kernel's packed keys in a single launch without any measuring pass, which is faster from
+// kWaveMaxUpdatesBounded on.  Tile size: with at least kWaveFillTiles tiles of 16 x 16 those are used
+// (every SIMD still gets two wavefronts' worth), else 8 x 8 (four times as many, smaller pieces to
+// spread over the chip).
 constexpr int64_t kWaveMaxUpdates = (int64_t)3 << 25, kWaveMaxUpdatesBounded = (int64_t)1 << 24;
-constexpr int32_t kWaveMaxCj = 1024;
 constexpr int64_t kWaveFillTiles = 2048;
 inline int wave_tile_rb(int64_t tiles_16x16) { return tiles_16x16 >= kWaveFillTiles ? 2 : 1; }
 

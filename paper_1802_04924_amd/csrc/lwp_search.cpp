@@ -284,8 +284,8 @@ private:
     static constexpr size_t kUploadWithPrepare = 16384;
     // Node eliminations of a round with little work run on the kernel that gives each wavefront a small
     // tile of its own (see kWaveMaxUpdates).
-    bool round_on_wave_kernel(int64_t updates, int32_t max_cj) const {
-        return (!ctx_ || ctx_->wave_kernel) && updates <= kWaveMaxUpdates && max_cj <= kWaveMaxCj;
+    bool round_on_wave_kernel(int64_t updates) const {
+        return (!ctx_ || ctx_->wave_kernel) && updates <= kWaveMaxUpdates;
     }
 };
 
@@ -326,15 +326,13 @@ lwp_status Search::plan() {
         while (t < n) {
             const int32_t round = plan_.steps[t].round;
             int64_t updates = 0;
-            int32_t max_cj = 0;
             bool any = false;
             for (; t < n && plan_.steps[t].round == round; ++t)
                 if (plan_.steps[t].kind == 0) {
                     updates += (int64_t)L_.node_A[q].rows * L_.node_A[q].cols * L_.node_B[q].cols;
-                    max_cj = std::max(max_cj, L_.node_A[q].cols);
                     ++q; any = true;
                 }
-            if (any && !round_on_wave_kernel(updates, max_cj)) any_tiled_ = true;
+            if (any && !round_on_wave_kernel(updates)) any_tiled_ = true;
         }
     }
     // index of the range pair of: input edge e | w of node v | output of node step | output of group
@@ -565,9 +563,8 @@ lwp_status Search::write_descriptors(int arith) {
         // A round with little work runs as one launch of the kernel that gives every wavefront a tile
         // of its own: with so few 64 x 64 tiles the tiled kernel's launch would be mostly latency.
         int64_t round_updates = 0;
-        int32_t round_max_cj = 0;
-        for (const NodeWork& x : work) { round_updates += (int64_t)x.Ci * x.Cj * x.Ck; round_max_cj = std::max(round_max_cj, x.Cj); }
-        if (!work.empty() && round_on_wave_kernel(round_updates, round_max_cj)) {
+        for (const NodeWork& x : work) round_updates += (int64_t)x.Ci * x.Cj * x.Ck;
+        if (!work.empty() && round_on_wave_kernel(round_updates)) {
             int64_t t16 = 0;
             for (const NodeWork& x : work) t16 += (int64_t)((x.Ci + 15) / 16) * ((x.Ck + 15) / 16);
             const int rb = wave_tile_rb(t16);

@@ -36,15 +36,14 @@ def check_products(ctx, A, w, B, expect_keyed=None, expect_keyed_bounded=None):
     entry points: lwp_eliminate_node (ranges measured and variant picked on the device, per product)
     and lwp_eliminate_node_bounded (the caller promises ranges -- here the exact ones -- and the host
     picks the variant).  expect_keyed: whether packed keys (global or per row) must have been used
-    by the tiled kernel.  A call below 3 * 2^25 cell updates (2^24 with promised ranges) and with at most
-    1024 candidates is first checked on the kernel it takes by default, the wavefront-per-tile one
+    by the tiled kernel.  A call below 3 * 2^25 cell updates (2^24 with promised ranges) is first checked on the kernel it takes by default, the wavefront-per-tile one
     (compare/select), then on the tiled kernel."""
     d_A, d_w, d_B = dev(A), dev(w), dev(B)
     batch = A.shape[0]
     ref = [oracle.minplus_argmin(A[b], w[b], B[b]) for b in range(batch)]
     bounds = (A.min(), A.max(), w.min(), w.max(), B.min(), B.max())
     updates = A.shape[0] * A.shape[1] * A.shape[2] * B.shape[2]
-    if updates <= (3 << 25) and A.shape[2] <= 1024:
+    if updates <= (3 << 25):
         ctx.profile_enable(True)
         for bnd in ((None, bounds) if updates <= (1 << 24) else (None,)):
             ctx.profile_reset()
@@ -111,12 +110,12 @@ def test_eliminate_node_keyed_small_values(ctx, shape, hi):
     check_products(ctx, A, w, B, expect_keyed=True)
 
 
-@pytest.mark.parametrize("shape", [(64, 128, 16, 128), (100, 70, 33, 90), (300, 40, 130, 56), (2100, 16, 5, 16), (1, 1, 1000, 1), (3, 2, 1024, 3), (1, 9, 1025, 9)])
+@pytest.mark.parametrize("shape", [(64, 128, 16, 128), (100, 70, 33, 90), (300, 40, 130, 56), (2100, 16, 5, 16), (1, 1, 1000, 1), (3, 2, 1024, 3), (1, 9, 1025, 9), (1, 3, 40000, 2)])
 @pytest.mark.parametrize("hi", [2, 1 << 24])
 def test_eliminate_node_many_small_products(ctx, shape, hi):
     # calls below 2^27 cell updates with enough output for a wavefront per 16 x 16 tile (at least 2048 of
-    # them), ragged in every dimension, with ties (hi = 2) and without; then long rows: up to 1024
-    # candidates the wavefront-per-tile kernel takes them, one more and the tiled kernel does
+    # them), ragged in every dimension, with ties (hi = 2) and without; then long rows, where four
+    # wavefronts share a tile, their shares of the candidates ragged
     batch, Ci, Cj, Ck = shape
     rng = np.random.default_rng(abs(hash((shape, hi))) % (1 << 32))
     A = rng.integers(-hi, hi, size=(batch, Ci, Cj), endpoint=True, dtype=np.int32)
