@@ -110,12 +110,13 @@ def test_eliminate_node_keyed_small_values(ctx, shape, hi):
     check_products(ctx, A, w, B, expect_keyed=True)
 
 
-@pytest.mark.parametrize("shape", [(64, 128, 16, 128), (100, 70, 33, 90), (300, 40, 130, 56), (2100, 16, 5, 16), (1, 1, 1000, 1), (3, 2, 1024, 3), (1, 9, 1025, 9), (1, 3, 40000, 2)])
+@pytest.mark.parametrize("shape", [(64, 128, 16, 128), (100, 70, 33, 90), (300, 40, 130, 56), (2100, 16, 5, 16), (1, 1, 1000, 1), (3, 2, 1024, 3), (1, 9, 1025, 9), (1, 3, 40000, 2), (7, 250, 40, 250), (4, 200, 60, 200)])
 @pytest.mark.parametrize("hi", [2, 1 << 24])
 def test_eliminate_node_many_small_products(ctx, shape, hi):
     # calls below 2^27 cell updates with enough output for a wavefront per 16 x 16 tile (at least 2048 of
     # them), ragged in every dimension, with ties (hi = 2) and without; then long rows, where four
-    # wavefronts share a tile, their shares of the candidates ragged
+    # wavefronts share a tile, their shares of the candidates ragged; the last two: between 4096 and 8192
+    # tiles of 8 x 8 (short chunks, a tile per wavefront) and between 1024 and 4096 (long chunks)
     batch, Ci, Cj, Ck = shape
     rng = np.random.default_rng(abs(hash((shape, hi))) % (1 << 32))
     A = rng.integers(-hi, hi, size=(batch, Ci, Cj), endpoint=True, dtype=np.int32)
@@ -306,7 +307,8 @@ def test_eliminate_node_closed_forms(ctx, kernels):
     assert (out.cpu().numpy() == 7).all() and (arg.cpu().numpy() == 0).all()
 
 
-@pytest.mark.parametrize("shape", [(2, 50, 60, 70), (1, 64, 2048, 64), (3, 130, 257, 140), (40, 256, 100, 256), (600, 128, 40, 256)])
+@pytest.mark.parametrize("shape", [(2, 50, 60, 70), (1, 64, 2048, 64), (3, 130, 257, 140), (40, 256, 100, 256), (600, 128, 40, 256),
+                                   (7, 250, 40, 250), (4, 200, 60, 200)])
 @pytest.mark.parametrize("lo,hi", [(0, 3), (0, 1 << 20), (-(1 << 29), 1 << 29)])
 def test_eliminate_node_value_only(ctx, kernels, shape, lo, hi):
     # no argmin requested: the value-only variant (any int32 range) must give the same minima
