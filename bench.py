@@ -29,7 +29,7 @@ PEAK_LANE_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 # One cell update of Eq. 2 is one add and one min.  A three-way min retires two mins, so the fewest
 # instructions a kernel can issue per update is 1 add + 1/2 min3 = 1.5: the issue ceiling is
 # 39.32 / 1.5 = 26.2 T cell updates/s.  (Counting 2 operations per update against the same 39.32 T
-# would let a kernel pass 1.0; that figure is kept as frac_2op for comparison with the survey's.)
+# would let a kernel pass 1.0; that figure is kept as frac_2op.)
 INSTR_PER_UPDATE = 1.5
 PMC_SUMMARY = os.path.join(ROOT, "profiles", "minplus_kernel_C4096_pmc.txt")
 

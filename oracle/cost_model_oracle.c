@@ -2,8 +2,8 @@
  * CPU oracle of the analytic cost model (TEST INFRASTRUCTURE, not the product).
  *
  * Sec. 5.1 defines three cost functions; the paper measures t_c on the device and does not
- * print formulas for t_x and t_s beyond "size of the data to be moved / known bandwidth".
- * The readings implemented here (also listed in the design notes):
+ * print formulas for t_x and t_s beyond saying that each is a data volume divided by a known
+ * bandwidth.  The readings implemented here:
  *
  *   configuration (Sec. 4): degrees (n, h, w, c) over the sample, height, width and channel
  *     dimensions of the layer's OUTPUT tensor, equal partitioning: part t of g over an extent

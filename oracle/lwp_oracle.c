@@ -13,7 +13,7 @@
  *   orc_edge_sum         Eq. 3   (edge elimination)
  *   orc_search           Alg. 1  (eliminate, solve the residual graph, undo in reverse)
  *
- * Readings where the paper is silent (each is also listed in the design notes):
+ * Readings where the paper is silent:
  *   - costs are int32 nanoseconds, sums are exact; a sum that leaves int32 is an error;
  *   - every min takes the LOWEST index among equal candidates (strict '<' in ascending order);
  *   - the order of eliminations is the written canonical schedule implemented in orc_search;

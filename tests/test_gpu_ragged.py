@@ -67,9 +67,9 @@ def test_ragged_round_with_thousands_of_small_tiles(ctx):
 
 @pytest.mark.parametrize("big,hi", [(600, 1 << 16), (900, 1 << 16), (900, 1 << 28)])
 def test_ragged_small_round_feeds_a_large_one(ctx, big, hi):
-    # round 1: two products of big x 4 x big (the wavefront-per-tile kernel); round 2: one product of big^3
-    # on the tiled kernel (compare/select at 600, packed keys at 900: 2^29 cell updates and more), whose
-    # operands are both outputs of round 1 -- their value ranges must have been measured there
+    # first round of the search: two products of big x 4 x big (the wavefront-per-tile kernel); second: one
+    # product of big^3 on the tiled kernel (compare/select at 600, packed keys at 900: 2^29 cell updates and
+    # more), whose operands are both outputs of the first -- their value ranges must have been measured there
     Cn = np.array([big, 4, big, 4, big], np.int32)
     run_ragged(ctx, 5, wl.chain_edges(5), Cn, seed=big, hi=hi, schedules=(wl.SCHEDULE_ROUNDS,))
 
