@@ -281,7 +281,7 @@ private:
     bool tiny_ = false;
     bool any_tiled_ = true;      // some round of node eliminations runs on the tiled kernel
     bool upload_with_prepare_ = false;   // measure_inputs() also copies the descriptor block to the device
-    static constexpr size_t kUploadWithPrepare = 16384;
+    static constexpr size_t kUploadWithPrepare = (size_t)1 << 20;
     // Node eliminations of a round with little work run on the kernel that gives each wavefront a small
     // tile of its own (see kWaveMaxUpdates).
     bool round_on_wave_kernel(int64_t updates) const {
@@ -383,8 +383,10 @@ lwp_status Search::run(int32_t* out_cost, int32_t* out_strategy) {
         // ahead): it runs on the device while the host writes the descriptors
         mark_result_pending();
         if (lwp_status s = upload_offsets()) return s;
-        // A large descriptor block is written while the measuring pass runs and uploaded by a copy of
-        // its own; a small one is written first (a microsecond) and uploaded by the first launch.
+        // A descriptor block of up to a megabyte is written first (microseconds: 4 for the 120-node
+        // Inception-shaped graph) and copied from the pinned mirror by the first launch: a copy of its
+        // own goes through the DMA engine from a few kilobytes on and holds the stream up for 15 us.
+        // A larger block is written while the measuring pass runs and uploaded by such a copy.
         upload_with_prepare_ = W_.desc_bytes <= kUploadWithPrepare && W_.desc_bytes % 16 == 0;
         if (upload_with_prepare_) {
             if (lwp_status s = write_descriptors(arith)) return s;
