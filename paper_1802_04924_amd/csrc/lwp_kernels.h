@@ -138,6 +138,10 @@ hipError_t launch_edge_sum_pair(const int32_t* e1, const int32_t* e2, int32_t* o
 
 // p[0..n) = value (a fill kernel: also safe inside a captured graph, unlike a memset node).
 hipError_t launch_fill_i32(int32_t* d_p, int64_t n, int32_t value, hipStream_t stream);
+// dst[0..bytes) = src[0..bytes) by a kernel (bytes a multiple of 16, both 16-byte aligned); src may be
+// pinned host memory the device can read.  For small blocks on the critical path of a search: a
+// runtime copy of more than a few kilobytes goes through the DMA engine and takes about 15 us.
+hipError_t launch_copy_block(const void* src, void* dst, size_t bytes, hipStream_t stream);
 
 // ---- value ranges ----------------------------------------------------------------------------
 // One launch that prepares a search: stats[2*t] = INT32_MAX, stats[2*t+1] = INT32_MIN for

@@ -670,7 +670,10 @@ lwp_status Search::write_descriptors(int arith) {
 }
 
 lwp_status Search::upload_descriptors() {
-    LWP_HIP(ctx_, hipMemcpyAsync(db_, hb_, W_.desc_bytes, hipMemcpyHostToDevice, stream_));
+    if (W_.desc_bytes <= kUploadWithPrepare && W_.desc_bytes % 16 == 0)
+        LWP_HIP(ctx_, launch_copy_block(hb_, db_, W_.desc_bytes, stream_));
+    else
+        LWP_HIP(ctx_, hipMemcpyAsync(db_, hb_, W_.desc_bytes, hipMemcpyHostToDevice, stream_));
     return LWP_OK;
 }
 

@@ -2,6 +2,7 @@
 // ranges of the input tables, the residual-graph minimum (Alg. 1, enumeration of the final graph
 // with K <= 2 per component) and the undo pass (Alg. 1, last loop).  All of these move each
 // table element once; they are bound by HBM bandwidth or by dependent-load latency, not by ALUs.
+#include <algorithm>
 #include <cstddef>
 #include <cstring>
 
@@ -135,6 +136,11 @@ __global__ void init_workspace_kernel(int32_t* stats, int32_t n_tables, int32_t*
 __global__ void fill_i32_kernel(int32_t* p, int64_t n, int32_t value) {
     const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (t < n) p[t] = value;
+}
+
+__global__ void copy_block_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, int64_t n16) {
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < n16; t += stride) dst[t] = src[t];
 }
 
 constexpr int kRangeLoads = 8;      // 16-byte loads a thread keeps in flight
@@ -701,6 +707,16 @@ hipError_t launch_init_workspace(int32_t* d_stats, int32_t n_tables, int32_t* d_
 hipError_t launch_fill_i32(int32_t* d_p, int64_t n, int32_t value, hipStream_t stream) {
     if (n <= 0) return hipSuccess;
     hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, d_p, n, value);
+    return hipGetLastError();
+}
+
+hipError_t launch_copy_block(const void* src, void* dst, size_t bytes, hipStream_t stream) {
+    if (bytes == 0) return hipSuccess;
+    if (bytes % 16 || ((uintptr_t)src | (uintptr_t)dst) % 16) return hipErrorInvalidValue;
+    const int64_t n16 = (int64_t)(bytes / 16);
+    const unsigned blocks = (unsigned)std::min<int64_t>((n16 + 255) / 256, 1024);
+    hipLaunchKernelGGL(copy_block_kernel, dim3(blocks), dim3(256), 0, stream, static_cast<const uint4*>(src),
+                       static_cast<uint4*>(dst), n16);
     return hipGetLastError();
 }
 
