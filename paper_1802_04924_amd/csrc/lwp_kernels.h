@@ -28,7 +28,10 @@ struct NodeDesc {
     int32_t* flag;     // optional: OR-ed with 1 if max A + max w + max B (measured) may leave int32
                        // (2: a promised range broken, 4: skipped by a speculative launch; see NodeArgs)
     int32_t Ci, Cj, Ck;   // shape of this product; read only by launches of mixed shapes
-    int32_t pad[3];
+    // Within the round a search runs the product in: output cells, and operand words (A, w, B), of the
+    // products before this one (each saturating at 2^30).  Read only by the single-workgroup search.
+    int32_t cell_begin, word_begin;
+    int32_t pad;
 };
 static_assert(sizeof(NodeDesc) == 128, "descriptor layout");
 
@@ -237,12 +240,18 @@ hipError_t launch_back_substitute(const PairDesc* d_pairs, int32_t n_pairs, cons
 // memory (inline_block = 1): the search then needs no upload before its one launch.  The eight
 // descriptor pointers (rounds ... undo) are then byte offsets into that block, cast to pointers.
 constexpr int kTinyInlineBytes = 3584;
+// All tables of such a search together (t_c + t_s rows, the caller's t_x, the intermediate tables) must
+// fit this many words: the workgroup keeps them in LDS.
+constexpr int kTinyLdsWords = 32768;
 struct TinyRound { int32_t g0, g1, n0, n1; };
 struct TinyArgs {
     const int32_t* tc;
     const int32_t* ts;
     int32_t* w;
     int64_t n_w;
+    const int32_t* tx;       // the caller's edge tables, and the intermediate tables: where they start
+    const int32_t* slots;    // and how many words they have
+    int64_t n_tx, n_slots;
     const TinyRound* rounds;
     int32_t n_rounds;
     const NodeDesc* nodes;

@@ -303,8 +303,10 @@ lwp_status Search::plan() {
     pin_result_ = pin_desc_ + align_up(W_.desc_bytes, 256);
     n_comp_ = (int32_t)(plan_.pairs.size() + plan_.singles.size() + plan_.comps.size());
     {
-        // operations one workgroup would have to do (1024 threads: 2^22 operations are about 4000 each)
-        constexpr double kTinyWork = 4194304.0, kTinyEnumeration = 65536.0;
+        // Operations one workgroup would have to do.  Measured on chains of 6 to 400 nodes: with the
+        // tables in LDS one compute unit is level with the general path's launches at about 2^18
+        // operations (a search of 60 nodes with 16 configurations each), and well ahead below.
+        constexpr double kTinyWork = 262144.0, kTinyEnumeration = 65536.0;
         double work = (double)L_.node_off[n_nodes_];
         for (size_t q = 0; q < L_.node_A.size(); ++q) work += (double)L_.node_A[q].rows * L_.node_A[q].cols * L_.node_B[q].cols;
         for (size_t g = 0; g < L_.groups.size(); ++g) work += (double)L_.group_out[g].cells() * L_.group_src[g].size();
@@ -316,7 +318,8 @@ lwp_status Search::plan() {
             small_enumerations = small_enumerations && n <= kTinyEnumeration;
             work += n * (double)(c.nodes.size() + c.edges.size());
         }
-        tiny_ = small_enumerations && work <= kTinyWork && (!ctx_ || ctx_->single_launch);
+        const int64_t table_words = L_.node_off[n_nodes_] + L_.tx_off[n_edges_] + L_.slot_elems;
+        tiny_ = small_enumerations && work <= kTinyWork && table_words <= kTinyLdsWords && (!ctx_ || ctx_->single_launch);
     }
     // the measuring pass over the input tables serves the tiled kernel only
     any_tiled_ = false;
@@ -431,6 +434,7 @@ lwp_status Search::enqueue_all() {
 lwp_status Search::enqueue_tiny() {
     TinyArgs a{};
     a.tc = d_tc_; a.ts = d_ts_; a.w = d_w_; a.n_w = L_.node_off[n_nodes_];
+    a.tx = d_tx_; a.n_tx = L_.tx_off[n_edges_]; a.slots = d_slots_; a.n_slots = L_.slot_elems;
     a.rounds = reinterpret_cast<const TinyRound*>(db_ + W_.tiny_rounds);
     a.n_rounds = (int32_t)rounds_.size();
     a.nodes = reinterpret_cast<const NodeDesc*>(db_ + W_.node_desc);
@@ -504,6 +508,18 @@ lwp_status Search::write_descriptors(int arith) {
     // A table made by the wavefront-per-tile kernel gets its range measured only if a launch of the
     // tiled kernel consumes it (the descriptor of the producer is patched then).
     std::vector<int64_t> unmeasured(W_.n_ranges, -1);      // range pair -> descriptor of its producer
+    // positions of a round's products among its output cells and operand words (single-workgroup search)
+    auto number_round = [&](size_t first, size_t last) {
+        constexpr int64_t cap = int64_t(1) << 30;
+        int64_t cells = 0, words = 0;
+        for (size_t q = first; q < last; ++q) {
+            NodeDesc& d = nd[q];
+            d.cell_begin = (int32_t)std::min(cells, cap);
+            d.word_begin = (int32_t)std::min(words, cap);
+            cells += (int64_t)d.Ci * d.Ck;
+            words += (int64_t)d.Ci * d.Cj + d.Cj + (int64_t)d.Cj * d.Ck;
+        }
+    };
     size_t ni = 0, gi = 0, nsrc = 0, t = 0;
     const size_t n = plan.steps.size();
     std::vector<NodeWork> work;
@@ -587,6 +603,7 @@ lwp_status Search::write_descriptors(int arith) {
                 nd[n0 + q].rngOut = nullptr;
                 unmeasured[rng_node0_ + (int32_t)(n0 + q)] = (int64_t)(n0 + q);
             }
+            number_round(n0, ni);
             reinterpret_cast<TinyRound*>(hb_ + W_.tiny_rounds)[rounds_.size()] = {(int32_t)rw_.g0, (int32_t)rw_.g1, (int32_t)n0, (int32_t)ni};
             rounds_.push_back(std::move(rw_));
             continue;
@@ -633,6 +650,7 @@ lwp_status Search::write_descriptors(int arith) {
             a = b;
         }
         for (size_t q = 0; q < order.size(); ++q) nd[n0 + q] = work[order[q]].d;
+        number_round(n0, ni);
         reinterpret_cast<TinyRound*>(hb_ + W_.tiny_rounds)[rounds_.size()] = {(int32_t)rw_.g0, (int32_t)rw_.g1, (int32_t)n0, (int32_t)ni};
         rounds_.push_back(std::move(rw_));
     }

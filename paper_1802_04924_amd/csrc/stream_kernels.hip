@@ -472,7 +472,8 @@ __global__ __launch_bounds__(kUndoThreads) void back_substitute_kernel(
 // sums (Eq. 3) and the node eliminations (Eq. 2, one output cell per thread, candidates in ascending
 // c with a strict '<'), then the residual minima and the undo pass.  A workgroup barrier separates
 // the phases: all tables involved were written by this workgroup through its own compute unit.
-// Sums are formed in 64 bits, so overflow is found exactly (a sum that really leaves int32).
+// Overflow is found exactly (a sum that really leaves int32): 64-bit sums, or the carries of the
+// 32-bit additions in the node eliminations.
 __device__ __forceinline__ unsigned long long block_min_u64(unsigned long long v, unsigned long long* sm) {
     v = wave_min_u64(v);
     __syncthreads();                                  // sm may still be read from the previous call
@@ -489,10 +490,26 @@ struct TinyLaunch {
 };
 static_assert(sizeof(TinyLaunch) <= 4096, "kernel arguments");
 
-constexpr int kTinyPrefix = 256;     // products of a round whose cells are dealt out together
+constexpr int kTinyPrefix = 256;          // products whose cells are dealt to the threads together
+constexpr uint32_t kTinyBias = 0x80000000u;
+// Every table of the search (the rows of t_c + t_s, the caller's t_x, the intermediate tables: at most
+// kTinyLdsWords words together, which the host checks) has a copy in LDS, at the table's offset in
+// (w | t_x | intermediates): operands are read from LDS only, results go to LDS and to global memory
+// (the residual and undo phases, and nothing else, read them there).  A round is then bound by the
+// compute unit's instruction rate rather than by chains of memory round trips.
+// LDS holds v ^ 2^31 (the value plus 2^31 as an unsigned number): the sum of three such words is
+// a + w + b + 3 * 2^31, so the two carries of its 32-bit additions tell exactly whether a + w + b
+// fits int32 (it does iff exactly one of them carries), the low word is the biased sum, and unsigned
+// order on it is the order of the sums -- five vector instructions per candidate instead of the
+// sixteen of 64-bit sums and compares.
 __global__ __launch_bounds__(kUndoThreads) void tiny_search_kernel(const TinyLaunch t) {
     __shared__ unsigned long long smin[kUndoThreads / 64];
+    __shared__ uint32_t stage[kTinyLdsWords];
     __shared__ int cell_begin[kTinyPrefix + 1];
+    __shared__ int prod_a[kTinyPrefix], prod_w[kTinyPrefix], prod_b[kTinyPrefix], prod_o[kTinyPrefix];
+    __shared__ int prod_cj[kTinyPrefix], prod_ck[kTinyPrefix];
+    __shared__ int32_t* prod_out[kTinyPrefix];
+    __shared__ int32_t* prod_arg[kTinyPrefix];
     const int tid = threadIdx.x;
     bool bad = false;
     TinyArgs a = t.a;
@@ -509,62 +526,55 @@ __global__ __launch_bounds__(kUndoThreads) void tiny_search_kernel(const TinyLau
         a.comps = (const CompDesc*)(blk + (uintptr_t)a.comps);
         a.undo = (const UndoDesc*)(blk + (uintptr_t)a.undo);
     }
+    const int n_w = (int)a.n_w, n_tx = (int)a.n_tx;
+    // LDS word of a table that starts at p
+    auto lds_word = [&](const int32_t* p) -> int {
+        int64_t o = ((intptr_t)p - (intptr_t)a.w) >> 2;
+        if (o >= 0 && o < a.n_w) return (int)o;
+        o = ((intptr_t)p - (intptr_t)a.tx) >> 2;
+        if (o >= 0 && o < a.n_tx) return n_w + (int)o;
+        return n_w + n_tx + (int)(((intptr_t)p - (intptr_t)a.slots) >> 2);
+    };
     if (tid == 0) *a.flag = 0;
     for (int64_t x = tid; x < a.n_w; x += kUndoThreads) {
         const long long s = (long long)a.tc[x] + (long long)a.ts[x];
         bad |= (s != (long long)(int32_t)s);
         a.w[x] = (int32_t)s;
+        stage[x] = (uint32_t)(int32_t)s ^ kTinyBias;
     }
+#pragma unroll 8
+    for (int x = tid; x < n_tx; x += kUndoThreads) stage[n_w + x] = (uint32_t)a.tx[x] ^ kTinyBias;
     __syncthreads();
     for (int r = 0; r < a.n_rounds; ++r) {
         const TinyRound rd = a.rounds[r];
         for (int g = rd.g0; g < rd.g1; ++g) {                      // Eq. 3, k-way
             const EdgeDesc d = a.edges[g];
             const int32_t* const* sp = a.srcs + d.first_src;
-            for (int64_t x = tid; x < d.cells; x += kUndoThreads) {
-                long long acc = sp[0][x];
-                for (int q = 1; q < d.n_src; ++q) acc += sp[q][x];
+            const int oo = lds_word(d.out);                        // may be the first source: a cell is
+            for (int x = tid; x < (int)d.cells; x += kUndoThreads) {   // read and written by one thread
+                long long acc = 0;
+                for (int q = 0; q < d.n_src; ++q) acc += (long long)(int32_t)(stage[lds_word(sp[q]) + x] ^ kTinyBias);
                 bad |= (acc != (long long)(int32_t)acc);
                 d.out[x] = (int32_t)acc;
+                stage[oo + x] = (uint32_t)(int32_t)acc ^ kTinyBias;
             }
         }
         if (rd.g1 > rd.g0) __syncthreads();
-        // Eq. 2.  The cells of all products of the round are dealt to the threads together (a prefix of
-        // cell counts in LDS tells a thread which product its cell belongs to): product after product
-        // would cost the workgroup one chain of dependent loads per product instead of one per round.
-        auto one_cell = [&](const NodeDesc& d, int x) {
-            const int ra = x / d.Ck, cb = x - ra * d.Ck;
-            const int32_t* Arow = d.A + (int64_t)ra * d.Cj;
-            long long best = 0;
-            int arg = 0;
-            // four candidates' loads in flight at a time (clamped loads repeat the last candidate)
-            for (int c0 = 0; c0 < d.Cj; c0 += 4) {
-                int32_t av[4], wv[4], bv[4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int c = min(c0 + u, d.Cj - 1);
-                    av[u] = Arow[c]; wv[u] = d.w[c]; bv[u] = d.B[(int64_t)c * d.Ck + cb];
-                }
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int c = c0 + u;
-                    const long long s = (long long)av[u] + wv[u] + bv[u];
-                    if (c < d.Cj) {
-                        bad |= (s != (long long)(int32_t)s);
-                        if (c == 0 || s < best) { best = s; arg = c; }
-                    }
-                }
-            }
-            d.out[x] = (int32_t)best;
-            if (d.arg) d.arg[x] = arg;
-        };
-        const int n_prod = rd.n1 - rd.n0;
-        if (n_prod > 1 && n_prod <= kTinyPrefix) {
-            if (tid < n_prod) cell_begin[tid + 1] = a.nodes[rd.n0 + tid].Ci * a.nodes[rd.n0 + tid].Ck;
-            __syncthreads();
-            if (tid == 0) {
-                cell_begin[0] = 0;
-                for (int q = 0; q < n_prod; ++q) cell_begin[q + 1] += cell_begin[q];
+        // Eq. 2.  The cells of all products of the round are dealt to the threads together (the host
+        // numbered them; the numbers, in LDS, tell a thread which product its cell belongs to):
+        // product after product would cost the workgroup one chain of dependent loads per product
+        // instead of one per round.
+        for (int q0 = rd.n0; q0 < rd.n1; q0 += kTinyPrefix) {
+            const int n_prod = min(kTinyPrefix, rd.n1 - q0);
+            if (q0 > rd.n0) __syncthreads();                       // the arrays below are in use until here
+            if (tid < n_prod) {
+                const NodeDesc d = a.nodes[q0 + tid];
+                const int first = a.nodes[q0].cell_begin;
+                cell_begin[tid] = d.cell_begin - first;
+                if (tid == n_prod - 1) cell_begin[n_prod] = d.cell_begin - first + d.Ci * d.Ck;
+                prod_a[tid] = lds_word(d.A); prod_w[tid] = lds_word(d.w); prod_b[tid] = lds_word(d.B);
+                prod_o[tid] = lds_word(d.out);
+                prod_cj[tid] = d.Cj; prod_ck[tid] = d.Ck; prod_out[tid] = d.out; prod_arg[tid] = d.arg;
             }
             __syncthreads();
             const int total = cell_begin[n_prod];
@@ -574,14 +584,42 @@ __global__ __launch_bounds__(kUndoThreads) void tiny_search_kernel(const TinyLau
                     const int mid = (lo + hi) >> 1;
                     if (cell_begin[mid] <= x) lo = mid; else hi = mid;
                 }
-                const NodeDesc d = a.nodes[rd.n0 + lo];
-                one_cell(d, x - cell_begin[lo]);
-            }
-        } else {
-            for (int n = rd.n0; n < rd.n1; ++n) {
-                const NodeDesc d = a.nodes[n];
-                const int cells = d.Ci * d.Ck;
-                for (int x = tid; x < cells; x += kUndoThreads) one_cell(d, x);
+                const int cell = x - cell_begin[lo];
+                const int Cj = prod_cj[lo], Ck = prod_ck[lo];
+                const int ra = cell / Ck, cb = cell - ra * Ck;
+                const uint32_t* As = stage + prod_a[lo] + ra * Cj;
+                const uint32_t* Ws = stage + prod_w[lo];
+                const uint32_t* Bs = stage + prod_b[lo] + cb;
+                uint32_t best = ~0u;        // no candidate is above it, and the lowest c wins ties
+                int arg = 0;
+                auto candidate = [&](uint32_t av, uint32_t wv, uint32_t bv, int c) {
+                    uint32_t s1, v;
+                    const bool c1 = __builtin_add_overflow(av, wv, &s1);
+                    const bool c2 = __builtin_add_overflow(s1, bv, &v);
+                    bad |= (c1 == c2);
+                    if (v < best) { best = v; arg = c; }
+                };
+                // the LDS reads of eight (then four) candidates are issued before the first is used
+                int c = 0;
+                for (; c + 8 <= Cj; c += 8) {
+                    uint32_t av[8], wv[8], bv[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) { av[u] = As[c + u]; wv[u] = Ws[c + u]; bv[u] = Bs[(c + u) * Ck]; }
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) candidate(av[u], wv[u], bv[u], c + u);
+                }
+                if (c + 4 <= Cj) {
+                    uint32_t av[4], wv[4], bv[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) { av[u] = As[c + u]; wv[u] = Ws[c + u]; bv[u] = Bs[(c + u) * Ck]; }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) candidate(av[u], wv[u], bv[u], c + u);
+                    c += 4;
+                }
+                for (; c < Cj; ++c) candidate(As[c], Ws[c], Bs[c * Ck], c);
+                prod_out[lo][cell] = (int32_t)(best ^ kTinyBias);
+                stage[prod_o[lo] + cell] = best;
+                if (prod_arg[lo]) prod_arg[lo][cell] = arg;
             }
         }
         __syncthreads();
@@ -791,6 +829,8 @@ hipError_t launch_component_min(const CompDesc* d_comp, unsigned long long n_pre
 
 hipError_t launch_tiny_search(const TinyArgs& args, const void* d_block, const void* h_block, size_t block_bytes,
                               hipStream_t stream) {
+    if (args.n_w < 0 || args.n_tx < 0 || args.n_slots < 0 || args.n_w + args.n_tx + args.n_slots > (int64_t)kTinyLdsWords)
+        return hipErrorInvalidValue;     // the kernel's LDS copy of the tables has that many words
     TinyLaunch t;            // (the launch copies the arguments)
     t.a = args;
     t.a.inline_block = 0;
