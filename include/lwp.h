@@ -83,10 +83,11 @@ const char *lwp_status_string(lwp_status s);
  * an elimination are invalid.  The record is cleared by the call. */
 lwp_status lwp_synchronize(lwp_ctx *ctx);
 
-/* Options of a context.  LWP_OPT_SINGLE_LAUNCH (default 1): a search whose whole work is a few
- * million operations (the sizes the paper itself searches: a handful of devices, tens of
- * configurations per layer) runs as one launch of one workgroup instead of a dozen dependent
- * launches; 0 sends every search down the general path.  Results are identical.
+/* Options of a context.  LWP_OPT_SINGLE_LAUNCH (default 1): a search whose whole work is below
+ * 2^18 operations and whose tables fit 32768 words together (the sizes the paper itself searches: a
+ * handful of devices, tens of configurations per layer) runs as one launch of one workgroup
+ * instead of a dozen dependent launches; 0 sends every search down the general path.  Results are
+ * identical.
  * LWP_OPT_SMALL_PRODUCT_KERNEL (default 1): node eliminations with little work -- one call, or one
  * round of a search, below 100 million (3 * 2^25) cell updates (2^24 for a call with promised ranges)
  * -- run on a kernel that gives every wavefront a small

@@ -275,9 +275,10 @@ private:
     std::vector<RoundWork> rounds_;
     std::vector<unsigned long long> comp_prefix_;
     int32_t pair_max_rows_ = 1, single_max_c_ = 1;
-    // A search whose whole work is a few million simple operations (the paper's own sizes: a handful
-    // of devices, tens of configurations per layer) runs in one launch of one workgroup: the dozen
-    // dependent launches of the general path would cost several times its arithmetic.
+    // A search whose whole work is a few hundred thousand simple operations on tables that fit LDS
+    // together (the paper's own sizes: a handful of devices, tens of configurations per layer) runs
+    // in one launch of one workgroup: the dozen dependent launches of the general path would cost
+    // several times its arithmetic.
     bool tiny_ = false;
     bool any_tiled_ = true;      // some round of node eliminations runs on the tiled kernel
     bool upload_with_prepare_ = false;   // measure_inputs() also copies the descriptor block to the device

@@ -439,8 +439,8 @@ def run_search(ctx, p, schedule=None):
     schedule = p["schedule"] if schedule is None else schedule
     ref = oracle.search(p["n_nodes"], p["edges"], p["C"], p["tc"], p["ts"], p["tx"], schedule)
     d_tc, d_ts, d_tx = dev(p["tc"]), dev(p["ts"]), dev(p["tx"])
-    # a search of a few million operations runs as one launch of one workgroup unless told otherwise:
-    # such searches are checked down both paths
+    # a small search runs as one launch of one workgroup unless told otherwise (the library decides;
+    # the bound here is wider than its own): such searches are checked down both paths
     nodes_gone = len(ref["steps"]) and int((ref["steps"]["kind"] == 0).sum())
     both = nodes_gone * p["C"] ** 3 <= (1 << 22)
     # and rounds with little work run on the wavefront-per-tile kernel unless told otherwise: both kernels
@@ -468,13 +468,26 @@ def test_search_config0(ctx):
 
 
 def test_small_search_with_hundreds_of_products_per_round(ctx):
-    # a search small enough for one launch of one workgroup whose rounds hold 349, 174, 87, ... node
-    # eliminations: more than, and fewer than, the products whose cells that kernel deals out together;
-    # its descriptors (90 KB) do not fit the kernel arguments, those of the 12-layer chain do
-    for n_layers, C in ((700, 3), (12, 5), (300, 2)):
+    # a search small enough for one launch of one workgroup (with stored argmin tables its tables fit
+    # that kernel's LDS) whose rounds hold 259, 130, 65, ... node eliminations: more than, and fewer
+    # than, the 256 products whose cells that kernel deals out together; its descriptors (70 KB) do
+    # not fit the kernel arguments, those of the 12-layer chain do
+    for n_layers, C in ((520, 2), (12, 5), (300, 2)):
         p = wl.chain_problem(n_layers, C, n_layers, tx_range=(0, 3))       # heavy ties
         run_search(ctx, p)
         run_search(ctx, p, wl.SCHEDULE_LEFT_FOLD)
+        # the one launch is not a min-plus launch: a search down that path records none
+        ctx.profile_enable(True)
+        ctx.profile_reset()
+        ctx.search_graph(p["n_nodes"], p["edges"], p["C"], dev(p["tc"]), dev(p["ts"]), dev(p["tx"]))
+        single = ctx.profile_read()["node_launches"]
+        ctx.set_single_launch(False)
+        ctx.profile_reset()
+        ctx.search_graph(p["n_nodes"], p["edges"], p["C"], dev(p["tc"]), dev(p["ts"]), dev(p["tx"]))
+        general = ctx.profile_read()["node_launches"]
+        ctx.set_single_launch(True)
+        ctx.profile_enable(False)
+        assert single == 0 and general > 0
 
 
 def test_search_graph_entry_point_itself(ctx):
@@ -698,6 +711,53 @@ def test_search_overflow_found_on_the_device(ctx):
     with pytest.raises(LwpError) as e:
         ctx.search_graph(2, edges, 8, dev(tc), dev(ts), dev(tx))
     assert e.value.code == -4
+
+
+def test_small_search_sums_at_the_edges_of_int32(ctx):
+    # The single-workgroup search reads overflow off the carries of its 32-bit additions: a sum of
+    # three whose first two terms leave int32 while the total fits must pass, a total of exactly
+    # INT32_MAX or INT32_MIN must pass, one beyond must be reported.  Three-layer chains, the middle
+    # layer eliminated (Eq. 2); the end layers cost nothing, so the residual sums add nothing.
+    from paper_1802_04924_amd import LwpError
+    edges = np.array([[0, 1], [1, 2]], np.int32)
+    C = 3
+    def problem(a, w, b):
+        tc = np.zeros((3, C), np.int32); ts = np.zeros((3, C), np.int32)
+        tc[1] = w
+        tx = np.stack([np.asarray(a, np.int64), np.asarray(b, np.int64)]).astype(np.int32)
+        return dict(n_nodes=3, edges=edges, C=C, tc=tc, ts=ts, tx=tx, schedule=wl.SCHEDULE_ROUNDS)
+    jitter = np.arange(C * C).reshape(C, C)
+    fits = [
+        # A + w = 2.4e9 leaves int32, A + w + B = 0.9e9 does not
+        (1_200_000_000 + jitter, np.full(C, 1_200_000_000) + np.arange(C), -1_500_000_000 - jitter.T),
+        # A + w = -2.4e9, total -0.9e9
+        (-1_200_000_000 - jitter, np.full(C, -1_200_000_000) - np.arange(C), 1_500_000_000 + jitter),
+        # the largest sum is exactly INT32_MAX, the smallest exactly INT32_MIN
+        (np.full((C, C), 2**31 - 1 - 10) - jitter, np.full(C, 4), np.full((C, C), 6)),
+        (np.full((C, C), -2**31 + 10) + jitter, np.full(C, -4), np.full((C, C), -6)),
+    ]
+    for a, w, b in fits:
+        p = problem(a, w, b)
+        ref = oracle.search(3, edges, C, p["tc"], p["ts"], p["tx"])
+        ctx.set_single_launch(True)
+        cost, S = ctx.search_graph(3, edges, C, dev(p["tc"]), dev(p["ts"]), dev(p["tx"]))
+        assert cost == ref["cost"] and np.array_equal(S, ref["strategy"])
+    beyond = [
+        (np.full((C, C), 2**31 - 1 - 10) - jitter, np.full(C, 4), np.full((C, C), 6) + (jitter == 0)),     # one cell: 2^31
+        (np.full((C, C), -2**31 + 10) + jitter, np.full(C, -4), np.full((C, C), -6) - (jitter == 0)),      # one cell: -2^31 - 1
+        (np.full((C, C), 2**31 - 1), np.full(C, 2**31 - 1), np.full((C, C), 2**31 - 1)),                   # both additions carry
+        (np.full((C, C), -2**31), np.full(C, -2**31), np.full((C, C), -2**31)),                            # neither does
+    ]
+    for a, w, b in beyond:
+        p = problem(a, w, b)
+        with pytest.raises(oracle.OracleError):
+            oracle.search(3, edges, C, p["tc"], p["ts"], p["tx"])
+        for single in (True, False):
+            ctx.set_single_launch(single)
+            with pytest.raises(LwpError) as e:
+                ctx.search_graph(3, edges, C, dev(p["tc"]), dev(p["ts"]), dev(p["tx"]))
+            assert e.value.code == -4
+    ctx.set_single_launch(True)
 
 
 def test_search_errors(ctx):
