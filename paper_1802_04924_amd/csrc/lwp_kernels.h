@@ -267,12 +267,18 @@ struct TinyArgs {
     int32_t* flag;
     int32_t* result;
     int32_t* host_result;
-    int32_t inline_block, pad;
+    int32_t inline_block;
+    int32_t up_n16;          // set by launch_tiny_search: 16-byte words of the descriptor block the kernel
+    const void* up_src;      // copies from up_src (host, pinned) to up_dst (device) before it starts
+    void* up_dst;
 };
 // d_block / h_block: the descriptor block on the device (what the pointers in args point into) and its
 // host copy, block_bytes long.  If h_block is given and the block is small enough it is passed in the
 // kernel arguments and the device copy is not read (it need not have been uploaded).
 constexpr bool tiny_block_fits_arguments(size_t block_bytes) { return block_bytes <= (size_t)kTinyInlineBytes; }
+// A larger block (of whole 16-byte words, up to a megabyte) the kernel copies itself from h_block (pinned
+// host memory) to d_block; only a block that is neither needs uploading before the launch.
+constexpr bool tiny_block_copied_by_kernel(size_t block_bytes) { return block_bytes % 16 == 0 && block_bytes <= ((size_t)1 << 20); }
 hipError_t launch_tiny_search(const TinyArgs& args, const void* d_block, const void* h_block, size_t block_bytes,
                               hipStream_t stream);
 

@@ -280,6 +280,7 @@ private:
     // in one launch of one workgroup: the dozen dependent launches of the general path would cost
     // several times its arithmetic.
     bool tiny_ = false;
+    bool block_on_device_ = false;   // the descriptor block has been uploaded and is not rewritten (a replayed plan)
     bool any_tiled_ = true;      // some round of node eliminations runs on the tiled kernel
     bool upload_with_prepare_ = false;   // measure_inputs() also copies the descriptor block to the device
     static constexpr size_t kUploadWithPrepare = (size_t)1 << 20;
@@ -369,8 +370,10 @@ void Search::bind(char* ws, char* pin) {
 lwp_status Search::run(int32_t* out_cost, int32_t* out_strategy) {
     if (tiny_) {
         if (lwp_status s = write_descriptors(stored_ ? kArithPlain : kArithValue)) return s;
-        // a block that fits the kernel arguments travels there: no upload
-        if (!tiny_block_fits_arguments(W_.desc_bytes)) { if (lwp_status s = upload_descriptors()) return s; }
+        // a block that fits the kernel arguments travels there, a larger one the kernel fetches itself
+        if (!tiny_block_fits_arguments(W_.desc_bytes) && !tiny_block_copied_by_kernel(W_.desc_bytes)) {
+            if (lwp_status s = upload_descriptors()) return s;
+        }
         mark_result_pending();
         if (lwp_status s = enqueue_tiny()) return s;
         if (lwp_status s = wait_for_result()) return s;
@@ -421,6 +424,7 @@ lwp_status Search::prepare_replay() {
     if (lwp_status s = write_descriptors(stored_ ? kArithAuto : kArithValue)) return s;
     if (lwp_status s = upload_descriptors()) return s;
     LWP_HIP(ctx_, hipStreamSynchronize(stream_));
+    block_on_device_ = true;
     return LWP_OK;
 }
 
@@ -449,7 +453,9 @@ lwp_status Search::enqueue_tiny() {
     a.undo = reinterpret_cast<const UndoDesc*>(db_ + W_.undo);
     a.n_undo = plan_.n_node_steps; a.n_nodes = n_nodes_;
     a.flag = d_flag_; a.result = d_result_; a.host_result = h_result_;
-    LWP_HIP(ctx_, launch_tiny_search(a, db_, hb_, W_.desc_bytes, stream_));
+    // (a block that is on the device already and does not fit the kernel arguments is read where it is)
+    const bool read_in_place = block_on_device_ && !tiny_block_fits_arguments(W_.desc_bytes);
+    LWP_HIP(ctx_, launch_tiny_search(a, db_, read_in_place ? nullptr : hb_, W_.desc_bytes, stream_));
     return LWP_OK;
 }
 

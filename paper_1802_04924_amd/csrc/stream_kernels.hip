@@ -365,9 +365,10 @@ __device__ __forceinline__ void back_substitute_body(
     const CompDesc* __restrict__ comps, int32_t n_comps,
     const unsigned long long* __restrict__ keys, const UndoDesc* __restrict__ undo, int32_t n_undo,
     int32_t n_nodes, const int32_t* __restrict__ flag, const int32_t* __restrict__ wstats,
-    int32_t* __restrict__ result, int32_t* __restrict__ host_result) {
+    int32_t* __restrict__ result, int32_t* __restrict__ host_result, int32_t* S) {
+    // S: where the strategy is built up, n_nodes words: result + 2 itself, or memory that is quicker to
+    // reach for this workgroup (LDS), copied to result + 2 at the end
     __shared__ long long ssum[kUndoThreads / 64];
-    int32_t* S = result + 2;
     long long cost = 0;
     for (int t = threadIdx.x; t < n_pairs + n_singles + n_comps; t += kUndoThreads) {
         const unsigned long long k = keys[t];
@@ -431,6 +432,8 @@ __device__ __forceinline__ void back_substitute_body(
         __syncthreads();
         hi = lo;
     }
+    if (S != result + 2)
+        for (int t = threadIdx.x; t < n_nodes; t += kUndoThreads) result[2 + t] = S[t];
     // a row of t_c + t_s that left int32 was recorded as the impossible range {INT32_MAX, INT32_MIN}
     __shared__ int wbad;
     if (threadIdx.x == 0) wbad = 0;
@@ -461,7 +464,7 @@ __global__ __launch_bounds__(kUndoThreads) void back_substitute_kernel(
     int32_t n_nodes, const int32_t* __restrict__ flag, const int32_t* __restrict__ wstats,
     int32_t* __restrict__ result, int32_t* __restrict__ host_result) {
     back_substitute_body(pairs, n_pairs, singles, n_singles, comps, n_comps, keys, undo, n_undo, n_nodes, flag, wstats, result,
-                         host_result);
+                         host_result, result + 2);
 }
 
 // ---- a whole small search in one workgroup ------------------------------------------------------
@@ -525,6 +528,15 @@ __global__ __launch_bounds__(kUndoThreads) void tiny_search_kernel(const TinyLau
         a.singles = (const SingleDesc*)(blk + (uintptr_t)a.singles);
         a.comps = (const CompDesc*)(blk + (uintptr_t)a.comps);
         a.undo = (const UndoDesc*)(blk + (uintptr_t)a.undo);
+    }
+    if (a.up_n16) {
+        // the descriptor block did not fit the kernel arguments: it is copied from the host's pinned
+        // mirror to where the pointers above point, by this workgroup, before anything reads it
+        const uint4* src = reinterpret_cast<const uint4*>(a.up_src);
+        uint4* dst = reinterpret_cast<uint4*>(a.up_dst);
+#pragma unroll 4
+        for (int x = tid; x < a.up_n16; x += kUndoThreads) dst[x] = src[x];
+        __syncthreads();
     }
     const int n_w = (int)a.n_w, n_tx = (int)a.n_tx;
     // LDS word of a table that starts at p
@@ -671,8 +683,9 @@ __global__ __launch_bounds__(kUndoThreads) void tiny_search_kernel(const TinyLau
     }
     if (bad) atomicOr(a.flag, 1);
     __syncthreads();
+    // the tables in LDS have done their service: the strategy is built up there
     back_substitute_body(a.pairs, a.n_pairs, a.singles, a.n_singles, a.comps, a.n_comps, a.keys, a.undo, a.n_undo, a.n_nodes,
-                         a.flag, nullptr, a.result, a.host_result);
+                         a.flag, nullptr, a.result, a.host_result, reinterpret_cast<int32_t*>(stage));
 }
 
 // ---- VALU issue-rate probe ----------------------------------------------------------------------
@@ -834,6 +847,7 @@ hipError_t launch_tiny_search(const TinyArgs& args, const void* d_block, const v
     TinyLaunch t;            // (the launch copies the arguments)
     t.a = args;
     t.a.inline_block = 0;
+    t.a.up_src = nullptr; t.a.up_dst = nullptr; t.a.up_n16 = 0;
     if (h_block && d_block && tiny_block_fits_arguments(block_bytes)) {
         std::memcpy(t.block, h_block, block_bytes);
         auto off = [&](const void* p) { return (uintptr_t)((const char*)p - (const char*)d_block); };
@@ -846,6 +860,8 @@ hipError_t launch_tiny_search(const TinyArgs& args, const void* d_block, const v
         t.a.comps = (const CompDesc*)off(args.comps);
         t.a.undo = (const UndoDesc*)off(args.undo);
         t.a.inline_block = 1;
+    } else if (h_block && d_block && tiny_block_copied_by_kernel(block_bytes)) {
+        t.a.up_src = h_block; t.a.up_dst = const_cast<void*>(d_block); t.a.up_n16 = (int32_t)(block_bytes / 16);
     }
     hipLaunchKernelGGL(tiny_search_kernel, dim3(1), dim3(kUndoThreads), 0, stream, t);
     return hipGetLastError();
