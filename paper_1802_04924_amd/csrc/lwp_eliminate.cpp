@@ -49,7 +49,7 @@ bool wave_call(const NodeCall& c, int64_t max_updates) {
 }
 
 hipError_t enqueue_node_wave(const NodeCall& c, const NodeScratch& sc, const int64_t* promised, hipStream_t st) {
-    const int rb = wave_tile_rb((int64_t)((c.Ci + 15) / 16) * ((c.Ck + 15) / 16) * c.batch);
+    const int rb = wave_tile_rb((int64_t)((c.Ci + 15) / 16) * ((c.Ck + 15) / 16) * c.batch, c.Cj);
     const int ts = 8 * rb;
     NodeArgs a{};
     a.base.A = c.A; a.base.w = c.w; a.base.B = c.B; a.base.out = c.out; a.base.arg = c.arg;

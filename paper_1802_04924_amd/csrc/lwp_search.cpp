@@ -592,7 +592,9 @@ lwp_status Search::write_descriptors(int arith) {
         if (!work.empty() && round_on_wave_kernel(round_updates)) {
             int64_t t16 = 0;
             for (const NodeWork& x : work) t16 += (int64_t)((x.Ci + 15) / 16) * ((x.Ck + 15) / 16);
-            const int rb = wave_tile_rb(t16);
+            int64_t round_cells = 0;
+            for (const NodeWork& x : work) round_cells += (int64_t)x.Ci * x.Ck;
+            const int rb = wave_tile_rb(t16, round_updates / round_cells);
             const int ts = 8 * rb;
             const bool one_shape = shape_count.size() == 1;
             NodeLaunch nl{n0, work.size(), work[0].Ci, work[0].Cj, work[0].Ck, 2 * (stored ? kArithPlain : kArithValue), -1, 0, 0, round_updates, rb};

@@ -23,7 +23,6 @@ namespace {
 
 constexpr int kWaveGroup = 256;            // threads per workgroup: 4 independent wavefronts
 constexpr int kWaveLongChunkTiles = 4096;  // launches of at most this many 8 x 8 tiles stage 128 candidates at a time
-constexpr int kWaveSplitTiles = 1024;      // launches of at most this many 8 x 8 tiles: four wavefronts per tile
 constexpr int kWavesPerGroup = kWaveGroup / 64;
 
 using gcptr = const int32_t __attribute__((address_space(1)))*;
@@ -67,8 +66,8 @@ __global__ __launch_bounds__(kWaveGroup, 4) void minplus_wave_kernel(const WaveA
     static_assert(NL % 2 == 0 && KC % 64 == 0 && KC % 16 == 0 && 64 % TS == 0, "staging assignment");
     __shared__ __attribute__((aligned(16))) int32_t lds[kWavesPerGroup][TS * AST + KC * TS];
 
-    static_assert(!SPLIT || RB == 1, "shared tiles are 8 x 8");
-    __shared__ int32_t merge[SPLIT ? kWavesPerGroup : 1][SPLIT ? 2 * 64 + 8 : 1];
+    constexpr int CELLS = RB * RB;         // output cells per lane
+    __shared__ int32_t merge[SPLIT ? kWavesPerGroup : 1][SPLIT ? 2 * 64 * CELLS + 8 : 1];
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = threadIdx.x & 63;
     const int item = SPLIT ? (int)blockIdx.x : (int)blockIdx.x * kWavesPerGroup + wave;
@@ -292,19 +291,30 @@ __global__ __launch_bounds__(kWaveGroup, 4) void minplus_wave_kernel(const WaveA
             sl[0] = wave_min_i32(loA); sl[1] = wave_max_i32(hiA); sl[2] = wave_min_i32(loW);
             sl[3] = wave_max_i32(hiW); sl[4] = wave_min_i32(loB); sl[5] = wave_max_i32(hiB);
         }
-        merge[wave][lane] = best[0][0];
-        merge[wave][64 + lane] = arg[0][0];
-        if (lane < 6) merge[wave][128 + lane] = sl[lane];
+        constexpr int ST = 2 * 64 * CELLS;     // where the six range words sit
+#pragma unroll
+        for (int i = 0; i < RB; ++i)
+#pragma unroll
+            for (int j = 0; j < RB; ++j) {
+                merge[wave][(i * RB + j) * 64 + lane] = best[i][j];
+                merge[wave][(CELLS + i * RB + j) * 64 + lane] = arg[i][j];
+            }
+        if (lane < 6) merge[wave][ST + lane] = sl[lane];
         __syncthreads();
         if (wave != 0) return;
 #pragma unroll
         for (int q = 1; q < kWavesPerGroup; ++q) {
-            const int32_t ob = merge[q][lane], oa = merge[q][64 + lane];
-            const bool lt = ob < best[0][0];
-            best[0][0] = lt ? ob : best[0][0];
-            arg[0][0] = lt ? oa : arg[0][0];
-            loA = min(sl[0], merge[q][128]); hiA = max(sl[1], merge[q][129]); loW = min(sl[2], merge[q][130]);
-            hiW = max(sl[3], merge[q][131]); loB = min(sl[4], merge[q][132]); hiB = max(sl[5], merge[q][133]);
+#pragma unroll
+            for (int i = 0; i < RB; ++i)
+#pragma unroll
+                for (int j = 0; j < RB; ++j) {
+                    const int32_t ob = merge[q][(i * RB + j) * 64 + lane], oa = merge[q][(CELLS + i * RB + j) * 64 + lane];
+                    const bool lt = ob < best[i][j];
+                    best[i][j] = lt ? ob : best[i][j];
+                    arg[i][j] = lt ? oa : arg[i][j];
+                }
+            loA = min(sl[0], merge[q][ST]); hiA = max(sl[1], merge[q][ST + 1]); loW = min(sl[2], merge[q][ST + 2]);
+            hiW = max(sl[3], merge[q][ST + 3]); loB = min(sl[4], merge[q][ST + 4]); hiB = max(sl[5], merge[q][ST + 5]);
             sl[0] = loA; sl[1] = hiA; sl[2] = loW; sl[3] = hiW; sl[4] = loB; sl[5] = hiB;
         }
         loA = sl[0]; hiA = sl[1]; loW = sl[2]; hiW = sl[3]; loB = sl[4]; hiB = sl[5];     // uniform already
@@ -375,9 +385,9 @@ hipError_t launch_minplus_wave(const NodeArgs& args, const NodeDesc* h_descs, in
         wa.n_inline = args.batch < kWaveInlineDescs ? args.batch : kWaveInlineDescs;
         for (int q = 0; q < wa.n_inline; ++q) wa.inl[q] = h_descs[q];
     }
-    // 8 x 8 tiles: up to kWaveSplitTiles of them, four wavefronts share a tile (a workgroup per tile);
-    // up to kWaveLongChunkTiles a wavefront each with long chunks; beyond, short chunks
-    const bool split = rb == 1 && args.total_tiles <= kWaveSplitTiles;
+    // up to kWaveSplitTiles tiles, of either size: four wavefronts share a tile (a workgroup per tile);
+    // 8 x 8 tiles: up to kWaveLongChunkTiles a wavefront each with long chunks; beyond, short chunks
+    const bool split = args.total_tiles <= kWaveSplitTiles;
     const bool long_chunks = rb == 1 && !split && args.total_tiles <= kWaveLongChunkTiles;
     if (split) grid = dim3((unsigned)args.total_tiles);
 #define LWP_WAVE(RB, KC, SPLIT) \
@@ -385,7 +395,8 @@ hipError_t launch_minplus_wave(const NodeArgs& args, const NodeDesc* h_descs, in
         if (mode == kModeValue) hipLaunchKernelGGL((minplus_wave_kernel<RB, KC, true, SPLIT>), grid, block, 0, stream, wa); \
         else hipLaunchKernelGGL((minplus_wave_kernel<RB, KC, false, SPLIT>), grid, block, 0, stream, wa); \
     } while (0)
-    if (split) LWP_WAVE(1, 64, true);
+    if (split && rb == 2) LWP_WAVE(2, 64, true);
+    else if (split) LWP_WAVE(1, 64, true);
     else if (long_chunks) LWP_WAVE(1, 128, false);
     else if (rb == 1) LWP_WAVE(1, 64, false);
     else LWP_WAVE(2, 64, false);

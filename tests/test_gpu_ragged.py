@@ -65,6 +65,15 @@ def test_ragged_round_with_thousands_of_small_tiles(ctx):
     run_ragged(ctx, 60, wl.chain_edges(60), Cn, seed=60, hi=1 << 18, schedules=(wl.SCHEDULE_ROUNDS,))
 
 
+def test_ragged_rounds_of_a_few_products_with_long_rows(ctx):
+    # rounds of 4, 2, 1 products of about 200^3, every shape its own: a few hundred tiles of 16 x 16 and
+    # rows of 201 to 290 candidates, where four wavefronts share a 16 x 16 tile, each with a ragged
+    # quarter of the candidates; heavy ties (hi = 2) and none
+    Cn = np.array([211, 270, 250, 283, 222, 295, 201, 249, 204], np.int32)
+    for hi in (2, 1 << 20):
+        run_ragged(ctx, 9, wl.chain_edges(9), Cn, seed=9 + hi, hi=hi)
+
+
 @pytest.mark.parametrize("big,hi", [(600, 1 << 16), (900, 1 << 16), (900, 1 << 28)])
 def test_ragged_small_round_feeds_a_large_one(ctx, big, hi):
     # first round of the search: two products of big x 4 x big (the wavefront-per-tile kernel); second: one
