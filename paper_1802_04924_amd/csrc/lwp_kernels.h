@@ -116,18 +116,19 @@ hipError_t launch_minplus_wave(const NodeArgs& args, const NodeDesc* h_descs, in
 // has few tiles, and then four wavefronts share each.)  A caller that promises value ranges gets the
 // tiled kernel's packed keys in a single launch without any measuring pass, which is faster from
 // kWaveMaxUpdatesBounded on.  Tile size: with at least kWaveFillTiles tiles of 16 x 16 those are used
-// (every SIMD still gets two wavefronts' worth); so are they when there are few of them (up to the
-// number four wavefronts share, see launch_minplus_wave) and rows are long enough that a quarter of
+// (every SIMD still gets two wavefronts' worth); so are they when there are few of them (up to
+// kWaveSplitTiles16, which four wavefronts share each) and rows are long enough that a quarter of
 // the candidates still fills a wavefront's pipeline -- a 16 x 16 tile loads half as much per update;
 // else 8 x 8 (four times as many, smaller pieces to spread over the chip).
 constexpr int64_t kWaveMaxUpdates = (int64_t)3 << 25, kWaveMaxUpdatesBounded = (int64_t)1 << 24;
 constexpr int64_t kWaveFillTiles = 2048;
-constexpr int kWaveSplitTiles = 1024;      // a launch of at most this many tiles (of either size): four wavefronts per tile
+// four wavefronts per tile: a launch of at most this many tiles of 8 x 8, or of 16 x 16
+constexpr int kWaveSplitTiles = 1024, kWaveSplitTiles16 = 1536;
 constexpr int64_t kWaveSharedMinTiles = 64, kWaveSharedMinCj = 200;
 // mean_cj: candidates per output cell, averaged over the launch
 inline int wave_tile_rb(int64_t tiles_16x16, int64_t mean_cj) {
     if (tiles_16x16 >= kWaveFillTiles) return 2;
-    if (tiles_16x16 > kWaveSharedMinTiles && tiles_16x16 <= kWaveSplitTiles && mean_cj >= kWaveSharedMinCj) return 2;
+    if (tiles_16x16 > kWaveSharedMinTiles && tiles_16x16 <= kWaveSplitTiles16 && mean_cj >= kWaveSharedMinCj) return 2;
     return 1;
 }
 

@@ -385,9 +385,9 @@ hipError_t launch_minplus_wave(const NodeArgs& args, const NodeDesc* h_descs, in
         wa.n_inline = args.batch < kWaveInlineDescs ? args.batch : kWaveInlineDescs;
         for (int q = 0; q < wa.n_inline; ++q) wa.inl[q] = h_descs[q];
     }
-    // up to kWaveSplitTiles tiles, of either size: four wavefronts share a tile (a workgroup per tile);
+    // up to kWaveSplitTiles tiles (kWaveSplitTiles16 of the larger size): four wavefronts share a tile (a workgroup per tile);
     // 8 x 8 tiles: up to kWaveLongChunkTiles a wavefront each with long chunks; beyond, short chunks
-    const bool split = args.total_tiles <= kWaveSplitTiles;
+    const bool split = args.total_tiles <= (rb == 2 ? kWaveSplitTiles16 : kWaveSplitTiles);
     const bool long_chunks = rb == 1 && !split && args.total_tiles <= kWaveLongChunkTiles;
     if (split) grid = dim3((unsigned)args.total_tiles);
 #define LWP_WAVE(RB, KC, SPLIT) \

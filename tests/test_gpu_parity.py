@@ -111,14 +111,14 @@ def test_eliminate_node_keyed_small_values(ctx, shape, hi):
 
 
 @pytest.mark.parametrize("shape", [(64, 128, 16, 128), (100, 70, 33, 90), (300, 40, 130, 56), (2100, 16, 5, 16), (1, 1, 1000, 1), (3, 2, 1024, 3), (1, 9, 1025, 9), (1, 3, 40000, 2), (7, 250, 40, 250), (4, 200, 60, 200),
-                                   (3, 250, 201, 250), (1, 130, 1000, 140), (2, 33, 203, 500)])
+                                   (3, 250, 201, 250), (1, 130, 1000, 140), (2, 33, 203, 500), (5, 250, 210, 250)])
 @pytest.mark.parametrize("hi", [2, 1 << 24])
 def test_eliminate_node_many_small_products(ctx, shape, hi):
     # calls below 2^27 cell updates with enough output for a wavefront per 16 x 16 tile (at least 2048 of
     # them), ragged in every dimension, with ties (hi = 2) and without; then long rows, where four
     # wavefronts share an 8 x 8 tile, their shares of the candidates ragged; then two: between 4096 and
     # 8192 tiles of 8 x 8 (short chunks, a tile per wavefront) and between 1024 and 4096 (long chunks);
-    # the last three: 64 to 1024 tiles of 16 x 16 with rows of at least 200 candidates, where four
+    # the last four: 64 to 1536 tiles of 16 x 16 with rows of at least 200 candidates, where four
     # wavefronts share a 16 x 16 tile (shares of 51, 51, 51, 48; of 250 each in chunks of 64; 51, 51, 51, 50)
     batch, Ci, Cj, Ck = shape
     rng = np.random.default_rng(abs(hash((shape, hi))) % (1 << 32))
