@@ -360,6 +360,7 @@ __global__ __launch_bounds__(kThreads) void component_min_kernel(const CompDesc*
 // ---- undo (Alg. 1: S^(i) = S^(i+1) + c_j, c_j the stored argmin of Eq. 2 at (c_i, c_k)) ---------
 // One workgroup of 1024 threads: the recomputing form keeps 16 wavefronts busy per round.
 constexpr int kUndoThreads = 1024;
+constexpr int kUndoLdsNodes = 4096;
 __device__ __forceinline__ void back_substitute_body(
     const PairDesc* __restrict__ pairs, int32_t n_pairs, const SingleDesc* __restrict__ singles, int32_t n_singles,
     const CompDesc* __restrict__ comps, int32_t n_comps,
@@ -369,6 +370,16 @@ __device__ __forceinline__ void back_substitute_body(
     // S: where the strategy is built up, n_nodes words: result + 2 itself, or memory that is quicker to
     // reach for this workgroup (LDS), copied to result + 2 at the end
     __shared__ long long ssum[kUndoThreads / 64];
+    // A log of up to one entry per thread is fetched here, all entries at once and before anything
+    // waits: a round of the walk below then costs one trip to memory (the argmin table) instead of
+    // three dependent ones (where the round starts, whether argmin tables were stored, the entry).
+    __shared__ int first_of[kUndoThreads];     // entry -> first entry of its round; sign bit: no stored argmin
+    const bool log_in_registers = n_undo <= kUndoThreads;
+    UndoDesc mine{};
+    if (log_in_registers && (int)threadIdx.x < n_undo) {
+        mine = undo[threadIdx.x];
+        first_of[threadIdx.x] = mine.first | (mine.arg ? 0 : (int)0x80000000);
+    }
     long long cost = 0;
     for (int t = threadIdx.x; t < n_pairs + n_singles + n_comps; t += kUndoThreads) {
         const unsigned long long k = keys[t];
@@ -406,8 +417,13 @@ __device__ __forceinline__ void back_substitute_body(
     // walk the rounds backwards; node eliminations of one round never depend on each other
     int hi = n_undo;
     while (hi > 0) {
-        const int lo = undo[hi - 1].first;
-        if (undo[lo].arg) {
+        const int word = log_in_registers ? first_of[hi - 1] : undo[hi - 1].first;     // (ssum's barrier covers first_of)
+        const int lo = word & 0x7fffffff;
+        const bool stored = log_in_registers ? word >= 0 : undo[lo].arg != nullptr;
+        if (stored && log_in_registers) {
+            const int t = threadIdx.x;
+            if (t >= lo && t < hi) S[mine.j] = ((gi32c)(uintptr_t)mine.arg)[(int64_t)S[mine.i] * mine.Ck + S[mine.k]];
+        } else if (stored) {
             for (int t = lo + threadIdx.x; t < hi; t += kUndoThreads) {
                 const UndoDesc u = undo[t];
                 S[u.j] = ((gi32c)(uintptr_t)u.arg)[(int64_t)S[u.i] * u.Ck + S[u.k]];
@@ -463,8 +479,10 @@ __global__ __launch_bounds__(kUndoThreads) void back_substitute_kernel(
     const unsigned long long* __restrict__ keys, const UndoDesc* __restrict__ undo, int32_t n_undo,
     int32_t n_nodes, const int32_t* __restrict__ flag, const int32_t* __restrict__ wstats,
     int32_t* __restrict__ result, int32_t* __restrict__ host_result) {
+    // the strategy is built up in LDS when it fits (the walk reads two entries of it per elimination)
+    __shared__ int32_t s_lds[kUndoLdsNodes];
     back_substitute_body(pairs, n_pairs, singles, n_singles, comps, n_comps, keys, undo, n_undo, n_nodes, flag, wstats, result,
-                         host_result, result + 2);
+                         host_result, n_nodes <= kUndoLdsNodes ? s_lds : result + 2);
 }
 
 // ---- a whole small search in one workgroup ------------------------------------------------------
