@@ -83,8 +83,8 @@ const char *lwp_status_string(lwp_status s);
  * an elimination are invalid.  The record is cleared by the call. */
 lwp_status lwp_synchronize(lwp_ctx *ctx);
 
-/* Options of a context.  LWP_OPT_SINGLE_LAUNCH (default 1): a search whose whole work is below
- * 2^18 operations and whose tables fit 32768 words together (the sizes the paper itself searches: a
+/* Options of a context.  LWP_OPT_SINGLE_LAUNCH (default 1): a search whose whole work is a few
+ * hundred thousand operations and whose tables fit 32768 words together (the sizes the paper itself searches: a
  * handful of devices, tens of configurations per layer) runs as one launch of one workgroup
  * instead of a dozen dependent launches; 0 sends every search down the general path.  Results are
  * identical.

@@ -305,10 +305,12 @@ lwp_status Search::plan() {
     pin_result_ = pin_desc_ + align_up(W_.desc_bytes, 256);
     n_comp_ = (int32_t)(plan_.pairs.size() + plan_.singles.size() + plan_.comps.size());
     {
-        // Operations one workgroup would have to do.  Measured on chains of 6 to 400 nodes: with the
-        // tables in LDS one compute unit is level with the general path's launches at about 2^18
-        // operations (a search of 60 nodes with 16 configurations each), and well ahead below.
-        constexpr double kTinyWork = 262144.0, kTinyEnumeration = 65536.0;
+        // Operations one workgroup would have to do.  Measured on chains of 6 to 400 nodes with 8 to 64
+        // configurations: with the tables in LDS one compute unit does about 14 500 operations per
+        // microsecond and spends 2.5 us per round, the general path 4.5 us per round and 8 us more at
+        // the start; the two are level where operations = 116 000 + 29 000 x rounds.
+        constexpr double kTinyWorkBase = 116000.0, kTinyWorkPerRound = 29000.0, kTinyEnumeration = 65536.0;
+        const double kTinyWork = kTinyWorkBase + kTinyWorkPerRound * plan_.n_rounds;
         double work = (double)L_.node_off[n_nodes_];
         for (size_t q = 0; q < L_.node_A.size(); ++q) work += (double)L_.node_A[q].rows * L_.node_A[q].cols * L_.node_B[q].cols;
         for (size_t g = 0; g < L_.groups.size(); ++g) work += (double)L_.group_out[g].cells() * L_.group_src[g].size();
