@@ -161,14 +161,15 @@ hipError_t launch_copy_block(const void* src, void* dst, size_t bytes, hipStream
 // t < n_tables; *flag = 0 (if given); keys[k] = all ones for k < n_keys (if given).
 hipError_t launch_init_workspace(int32_t* d_stats, int32_t n_tables, int32_t* d_flag, unsigned long long* d_keys,
                                  int32_t n_keys, hipStream_t stream);
-// stats[2*t] = min, stats[2*t+1] = max of table t (n_tables tables of `cells` elements each,
-// dense one after another), by atomics onto initialised pairs.
+// stats[2*t] = min, stats[2*t+1] = max of table t (tables of `cells` elements each, dense one
+// after another), by atomics onto initialised pairs: for t < n_tables, or, if d_which (device array of
+// n_tables table numbers) is given, for the tables it lists.
 hipError_t launch_ranges(const int32_t* d_tables, int32_t n_tables, int64_t cells, int32_t* d_stats,
-                         hipStream_t stream);
+                         hipStream_t stream, const int32_t* d_which = nullptr);
 // The same for tables of different sizes: table t is elements [d_off[t], d_off[t+1]) of d_tables
-// (d_off: device array of n_tables + 1 offsets); max_cells sizes the grid.
+// (d_off: device array of offsets, one more than there are tables); max_cells sizes the grid.
 hipError_t launch_ranges_var(const int32_t* d_tables, const int64_t* d_off, int32_t n_tables, int64_t max_cells,
-                             int32_t* d_stats, hipStream_t stream);
+                             int32_t* d_stats, hipStream_t stream, const int32_t* d_which = nullptr);
 // First launch of a search: w = tc + ts, row by row; row v is elements [v*C, (v+1)*C), or
 // [d_node_off[v], d_node_off[v+1]) if d_node_off (device, n_nodes + 1 offsets) is given.  Stats pair
 // w_pair0 + v receives {min, max} of row v of w, or {INT32_MAX, INT32_MIN} if a sum of that row

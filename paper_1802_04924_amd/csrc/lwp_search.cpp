@@ -137,7 +137,7 @@ struct WsLayout {
     size_t w, head, keys, result, args, slots, total;
     size_t desc, desc_bytes;                                   // descriptor block
     size_t offs, offs_bytes;                                   // row / table offsets, at the start of the block
-    size_t node_desc, edge_desc, src_ptrs, pair_desc, singles, undo, comps, tile_begin, tiny_rounds;   // offsets inside the block
+    size_t node_desc, edge_desc, src_ptrs, pair_desc, singles, undo, comps, tile_begin, tiny_rounds, range_list;   // offsets inside the block
     int32_t n_ranges;
 };
 
@@ -166,6 +166,7 @@ WsLayout layout_workspace(const Plan& plan, const Layout& L, int32_t n_nodes, in
         o.comps = sub(plan.comps.size() * sizeof(CompDesc));
         o.tile_begin = sub((2 * (size_t)plan.n_node_steps + 2) * sizeof(int32_t));   // launches of mixed shapes
         o.tiny_rounds = sub(((size_t)plan.n_rounds + 1) * sizeof(TinyRound));         // a small search in one launch
+        o.range_list = sub((size_t)n_edges * sizeof(int32_t));                         // input tables whose value range is measured
         o.desc_bytes = std::max<size_t>(b, 16);
     }
     o.desc = put(o.desc_bytes);
@@ -282,6 +283,9 @@ private:
     bool tiny_ = false;
     bool block_on_device_ = false;   // the descriptor block has been uploaded and is not rewritten (a replayed plan)
     bool any_tiled_ = true;      // some round of node eliminations runs on the tiled kernel
+    // Input tables that are an operand of a node elimination as they are.  Only these need a measured
+    // value range: a table that is first summed into another (Eq. 3) is covered by the range of the sum.
+    std::vector<int32_t> direct_tables_;
     bool upload_with_prepare_ = false;   // measure_inputs() also copies the descriptor block to the device
     static constexpr size_t kUploadWithPrepare = (size_t)1 << 20;
     // Node eliminations of a round with little work run on the kernel that gives each wavefront a small
@@ -327,20 +331,33 @@ lwp_status Search::plan() {
     }
     // the measuring pass over the input tables serves the tiled kernel only
     any_tiled_ = false;
+    direct_tables_.clear();
     {
         size_t q = 0, t = 0;
         const size_t n = plan_.steps.size();
+        std::vector<char> direct((size_t)n_edges_, 0);
         while (t < n) {
             const int32_t round = plan_.steps[t].round;
             int64_t updates = 0;
-            bool any = false;
+            const size_t q_first = q;
             for (; t < n && plan_.steps[t].round == round; ++t)
                 if (plan_.steps[t].kind == 0) {
                     updates += (int64_t)L_.node_A[q].rows * L_.node_A[q].cols * L_.node_B[q].cols;
-                    ++q; any = true;
+                    ++q;
                 }
-            if (any && !round_on_wave_kernel(updates)) any_tiled_ = true;
+            if (q > q_first && !round_on_wave_kernel(updates)) {
+                any_tiled_ = true;
+                // its operands that are still the caller's tables (these start at the table offsets)
+                for (size_t x = q_first; x < q; ++x)
+                    for (const TableRef* r : {&L_.node_A[x], &L_.node_B[x]})
+                        if (!r->is_slot) {
+                            const auto it = std::lower_bound(L_.tx_off.begin(), L_.tx_off.end() - 1, r->off);
+                            direct[(size_t)(it - L_.tx_off.begin())] = 1;
+                        }
+            }
         }
+        for (int32_t e = 0; e < n_edges_; ++e)
+            if (direct[(size_t)e]) direct_tables_.push_back(e);
     }
     // index of the range pair of: input edge e | w of node v | output of node step | output of group
     rng_w0_ = n_edges_;
@@ -474,17 +491,22 @@ lwp_status Search::measure_inputs() {
     const void* up_src = upload_with_prepare_ ? hb_ + up_skip : nullptr;
     void* up_dst = upload_with_prepare_ ? db_ + up_skip : nullptr;
     const size_t up_bytes = upload_with_prepare_ ? W_.desc_bytes - up_skip : 0;
+    // Which input tables are measured: those the tiled kernel will read as they are, if the list of them
+    // (part of the descriptor block) is on the device by the time the measuring kernel runs; else all.
+    const bool listed = upload_with_prepare_ || block_on_device_;
+    const int32_t* d_which = listed ? reinterpret_cast<const int32_t*>(db_ + W_.range_list) : nullptr;
+    const int32_t n_listed = listed ? (int32_t)direct_tables_.size() : n_edges_;
     if (L_.uniform) {
         LWP_HIP(ctx_, launch_prepare_search(d_tc_, d_ts_, d_w_, n_nodes_, Cn_[0], nullptr, d_stats_, W_.n_ranges, rng_w0_,
                                             d_keys_, n_comp_, d_flag_, st, up_src, up_dst, up_bytes));
-        if (any_tiled_) LWP_HIP(ctx_, launch_ranges(d_tx_, n_edges_, (int64_t)Cn_[0] * Cn_[0], d_stats_, st));
+        if (any_tiled_) LWP_HIP(ctx_, launch_ranges(d_tx_, n_listed, (int64_t)Cn_[0] * Cn_[0], d_stats_, st, d_which));
     } else {
         const int64_t* d_offs = reinterpret_cast<const int64_t*>(db_ + W_.offs);
         int64_t max_cells = 1;
         for (int32_t e = 0; e < n_edges_; ++e) max_cells = std::max(max_cells, L_.tx_off[e + 1] - L_.tx_off[e]);
         LWP_HIP(ctx_, launch_prepare_search(d_tc_, d_ts_, d_w_, n_nodes_, 0, d_offs, d_stats_, W_.n_ranges, rng_w0_,
                                             d_keys_, n_comp_, d_flag_, st, up_src, up_dst, up_bytes));
-        if (any_tiled_) LWP_HIP(ctx_, launch_ranges_var(d_tx_, d_offs + n_nodes_ + 1, n_edges_, max_cells, d_stats_, st));
+        if (any_tiled_) LWP_HIP(ctx_, launch_ranges_var(d_tx_, d_offs + n_nodes_ + 1, n_listed, max_cells, d_stats_, st, d_which));
     }
     return LWP_OK;
 }
@@ -506,6 +528,8 @@ lwp_status Search::write_descriptors(int arith) {
     CompDesc* cd = reinterpret_cast<CompDesc*>(hb_ + W_.comps);
     int32_t* tbeg = reinterpret_cast<int32_t*>(hb_ + W_.tile_begin);
     size_t n_tbeg = 0;
+    if (!direct_tables_.empty())
+        std::memcpy(hb_ + W_.range_list, direct_tables_.data(), direct_tables_.size() * sizeof(int32_t));
     rounds_.clear();
 
     std::vector<int32_t> erng(n_edges_);          // range-pair index of the edge's current table

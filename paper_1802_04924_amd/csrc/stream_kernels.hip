@@ -144,13 +144,16 @@ __global__ void copy_block_kernel(const uint4* __restrict__ src, uint4* __restri
 }
 
 constexpr int kRangeLoads = 8;      // 16-byte loads a thread keeps in flight
-// Table blockIdx.y is elements [y*cells, (y+1)*cells), or [off[y], off[y+1]) if off is given.
+// Table y is elements [y*cells, (y+1)*cells), or [off[y], off[y+1]) if off is given; row blockIdx.y of the
+// grid measures table y = y0 + blockIdx.y, or which[y0 + blockIdx.y] if a list of tables is given.
 __global__ __launch_bounds__(kThreads) void ranges_kernel(const int32_t* __restrict__ tables, int64_t cells,
                                                           const int64_t* __restrict__ off,
-                                                          int32_t* __restrict__ stats) {
+                                                          int32_t* __restrict__ stats, int32_t y0,
+                                                          const int32_t* __restrict__ which) {
     __shared__ int smin[kThreads / 64], smax[kThreads / 64];
-    const int32_t* T = tables + (off ? off[blockIdx.y] : (int64_t)blockIdx.y * cells);
-    if (off) cells = off[blockIdx.y + 1] - off[blockIdx.y];
+    const int y = which ? which[y0 + blockIdx.y] : y0 + (int)blockIdx.y;
+    const int32_t* T = tables + (off ? off[y] : (int64_t)y * cells);
+    if (off) cells = off[y + 1] - off[y];
     int lo = 0x7fffffff, hi = (int32_t)0x80000000;
     const int64_t stride = (int64_t)gridDim.x * kThreads;
     const int64_t t0 = (int64_t)blockIdx.x * kThreads + threadIdx.x;
@@ -179,8 +182,8 @@ __global__ __launch_bounds__(kThreads) void ranges_kernel(const int32_t* __restr
     __syncthreads();
     if (threadIdx.x == 0) {
         for (int q = 1; q < kThreads / 64; ++q) { lo = min(lo, smin[q]); hi = max(hi, smax[q]); }
-        atomicMin(&stats[2 * blockIdx.y], lo);
-        atomicMax(&stats[2 * blockIdx.y + 1], hi);
+        atomicMin(&stats[2 * y], lo);
+        atomicMax(&stats[2 * y + 1], hi);
     }
 }
 
@@ -790,27 +793,26 @@ hipError_t launch_copy_block(const void* src, void* dst, size_t bytes, hipStream
 }
 
 hipError_t launch_ranges(const int32_t* d_tables, int32_t n_tables, int64_t cells, int32_t* d_stats,
-                         hipStream_t stream) {
+                         hipStream_t stream, const int32_t* d_which) {
     if (n_tables <= 0) return hipSuccess;
     unsigned cap = n_tables >= 64 ? 64u : (n_tables >= 8 ? 512u : 4096u);
     for (int32_t t0 = 0; t0 < n_tables; t0 += 65535) {
         const int32_t n = (n_tables - t0) < 65535 ? (n_tables - t0) : 65535;
         dim3 grid(blocks_for(cells, 4 * kRangeLoads, cap), (unsigned)n);
-        hipLaunchKernelGGL(ranges_kernel, grid, dim3(kThreads), 0, stream, d_tables + (int64_t)t0 * cells, cells,
-                           (const int64_t*)nullptr, d_stats + 2 * (int64_t)t0);
+        hipLaunchKernelGGL(ranges_kernel, grid, dim3(kThreads), 0, stream, d_tables, cells, (const int64_t*)nullptr, d_stats, t0,
+                           d_which);
     }
     return hipGetLastError();
 }
 
 hipError_t launch_ranges_var(const int32_t* d_tables, const int64_t* d_off, int32_t n_tables, int64_t max_cells,
-                             int32_t* d_stats, hipStream_t stream) {
+                             int32_t* d_stats, hipStream_t stream, const int32_t* d_which) {
     if (n_tables <= 0) return hipSuccess;
     unsigned cap = n_tables >= 64 ? 64u : (n_tables >= 8 ? 512u : 4096u);
     for (int32_t t0 = 0; t0 < n_tables; t0 += 65535) {
         const int32_t n = (n_tables - t0) < 65535 ? (n_tables - t0) : 65535;
         dim3 grid(blocks_for(max_cells, 4 * kRangeLoads, cap), (unsigned)n);
-        hipLaunchKernelGGL(ranges_kernel, grid, dim3(kThreads), 0, stream, d_tables, (int64_t)0, d_off + t0,
-                           d_stats + 2 * (int64_t)t0);
+        hipLaunchKernelGGL(ranges_kernel, grid, dim3(kThreads), 0, stream, d_tables, (int64_t)0, d_off, d_stats, t0, d_which);
     }
     return hipGetLastError();
 }
