@@ -763,6 +763,27 @@ def test_small_search_sums_at_the_edges_of_int32(ctx):
     ctx.set_single_launch(True)
 
 
+def test_search_with_tables_that_are_only_ever_summed(ctx):
+    # One Inception-shaped module with 512 configurations: its first round runs on the tiled kernel,
+    # whose key widths follow value ranges measured on the device.  A table that is first added into a
+    # parallel edge (Eq. 3) is not measured itself, only the sum is.  Here those tables (8 of 18) lie far
+    # outside the range of all others, half of them negative: a range taken from the wrong table, or
+    # none, would give wrong keys.
+    from paper_1802_04924_amd import plan_graph
+    p = wl.forkjoin_problem(1, 512, 7, lo=0, hi=1000)
+    touched, direct, summed = set(), set(), set()
+    for s in plan_graph(p["n_nodes"], p["edges"], p["schedule"])["steps"]:
+        for e in (int(s["e1"]), int(s["e2"])):
+            if e not in touched:
+                (summed if s["kind"] == 1 else direct).add(e)
+        touched.update((int(s["e1"]), int(s["e2"])))
+    only_summed = sorted(summed - direct)
+    assert len(only_summed) >= 4
+    for q, e in enumerate(only_summed):
+        p["tx"][e] += 3_000_000 if q % 2 == 0 else -5_000_000
+    run_search(ctx, p)
+
+
 def test_search_errors(ctx):
     from paper_1802_04924_amd import LwpError
     edges = np.array([[0, 1], [0, 2], [0, 3]], np.int32)
