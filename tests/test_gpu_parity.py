@@ -199,6 +199,22 @@ def test_eliminate_node_last_round_of_workgroups_shares_its_tiles(ctx, shape, hi
         assert np.array_equal(out[b].cpu().numpy(), oracle.minplus_argmin(A[b], w[b], B[b])[0])
 
 
+@pytest.mark.parametrize("shape", [(9, 512, 200, 512), (13, 512, 100, 500), (1, 1600, 300, 1550), (25, 500, 300, 510)])
+@pytest.mark.parametrize("hi", [3, 1 << 20, (1 << 28) - 1])
+def test_eliminate_node_tiles_left_over_after_whole_rounds_are_shared(ctx, shape, hi):
+    # launches whose last round of 1024 workgroup slots is more than half full: what is left once every
+    # compute unit has had the same number of whole tiles (tiles modulo 256, here 64, 64, 113, 64) is
+    # shared by several workgroups each, the rest of the launch is whole tiles
+    batch, Ci, Cj, Ck = shape
+    tiles = batch * (-(-Ci // 64)) * (-(-Ck // 64))
+    assert tiles % 1024 > 512 and 0 < tiles % 256 <= 128
+    rng = np.random.default_rng(tiles + hi % 1000)
+    A = rng.integers(0, hi, size=(batch, Ci, Cj), endpoint=True, dtype=np.int32)
+    w = rng.integers(0, hi, size=(batch, Cj), endpoint=True, dtype=np.int32)
+    B = rng.integers(0, hi, size=(batch, Cj, Ck), endpoint=True, dtype=np.int32)
+    check_products(ctx, A, w, B)
+
+
 def test_split_tiles_never_read_a_previous_launchs_partials(ctx):
     # the parts of a tile meet in scratch memory that every launch reuses: with fresh data per launch
     # a part published too late (or read too early) would show as a result of the launch before
