@@ -126,7 +126,10 @@ inline Split choose_split(int64_t tiles, int32_t Cj, bool small_tiles) {
     int64_t shared = tiles <= kSplitMaxTiles ? tiles : tiles % kWorkgroupSlots;
     if (shared > kSplitMaxTiles) shared %= kComputeUnits;
     if (shared == 0 || shared > kSplitMaxTiles) return {1, tiles};
-    const int64_t k = std::min<int64_t>({kSplitMaxParts, kSplitMaxWorkgroups / shared, nstages / 2});
+    // parts per tile: enough for a part on every compute unit, no more (more parts only add to the
+    // merging: one 512^3 product 19.8 -> 18.4 us with 4 instead of 8, two 28.6 -> 26.0 with 2)
+    const int64_t fill = std::max<int64_t>(2, (kComputeUnits + shared - 1) / shared);
+    const int64_t k = std::min<int64_t>({kSplitMaxParts, kSplitMaxWorkgroups / shared, nstages / 2, fill});
     if (k < 2) return {1, tiles};
     return {(int)k, tiles - shared};
 }
