@@ -110,30 +110,38 @@ inline bool want_small_tiles(int32_t Ci, int32_t Cj, int32_t Ck, int64_t batch) 
 
 // Split tiles: a launch with few 64 x 64 tiles lets several workgroups share a tile, each with a
 // part of the c range of at least two stages of 32 candidates.
-// Measured: splitting pays while tiles x parts stays around 1024 workgroups (4 per compute unit).
-// A launch of more tiles runs in rounds of kWorkgroupSlots workgroups; if its last round is less than
-// half full, the tiles of that round are shared instead, so that the round ends sooner (a launch of
-// 4160 tiles would otherwise take five rounds for the work of 4.06).  A compute unit works a tile off
-// in the same time however many workgroups keep it company (the kernel is bound by instruction
-// issue), so a launch really takes as long as the compute unit with the most tiles: of a last round
-// that is more than half full, the tiles left over once every compute unit has had the same number
-// of whole ones are shared (576 tiles of 512 candidates: 90 -> 69 us).
-constexpr int64_t kWorkgroupSlots = 1024;      // 256 compute units x 4 resident workgroups of 64 x 64 tiles
+// The kernel is bound by instruction issue: a compute unit works a tile off in the same time however
+// many workgroups keep it company (512 candidates: 21 us), so a launch takes as long as the compute
+// unit with the most tiles -- measured: 512 tiles 63 us, 576 to 768 tiles 86, 832 to 1024 106.  A
+// launch of more tiles than compute units therefore gives every unit the same number of whole tiles
+// and shares the tiles left over (a launch of 4160 tiles: 64 of them), with the number of parts that
+// spreads them most evenly; each further part adds to the merging, which the small term below stands
+// for.  (576 tiles: 90 -> 69 us; 320: 53 -> 43; 1344: 139 -> 130.)
+// Up to one tile per compute unit, all tiles are shared: enough parts for one on every unit and no
+// more (one 512^3 product, 64 tiles: 19.8 -> 18.4 us with 4 parts instead of 8), or the few more that
+// put the same number on every unit (192 tiles: 4 parts instead of 2, 38 -> 32 us).
 constexpr int64_t kComputeUnits = 256;
 inline Split choose_split(int64_t tiles, int32_t Cj, bool small_tiles) {
     if (!small_tiles) return {1, tiles};
     const int64_t nstages = (Cj + 31) / 32;
-    int64_t shared = tiles <= kSplitMaxTiles ? tiles : tiles % kWorkgroupSlots;
-    if (shared > kSplitMaxTiles) shared %= kComputeUnits;
-    if (shared == 0 || shared > kSplitMaxTiles) return {1, tiles};
-    // parts per tile: enough for a part on every compute unit, no more (more parts only add to the
-    // merging: one 512^3 product 19.8 -> 18.4 us with 4 instead of 8, two 28.6 -> 26.0 with 2), or
-    // the few more that put the same number of parts on every compute unit (192 tiles: 2 parts each
-    // make 384 = one or two per unit, 4 make three per unit: 38 -> 32 us)
-    int64_t fill = std::max<int64_t>(2, (kComputeUnits + shared - 1) / shared);
-    for (int64_t k2 = 2; k2 <= kSplitMaxParts; ++k2)
-        if ((shared * k2) % kComputeUnits == 0) { fill = std::max(fill, k2); break; }   // the same number of parts on every compute unit
-    const int64_t k = std::min<int64_t>({kSplitMaxParts, kSplitMaxWorkgroups / shared, nstages / 2, fill});
+    const bool leftover = tiles > kComputeUnits && tiles % kComputeUnits != 0;
+    // (two whole tiles per unit come out slightly behind four halves: 64 against 62 us)
+    const int64_t shared = leftover ? tiles % kComputeUnits : (tiles <= kSplitMaxTiles ? tiles : 0);
+    if (shared == 0) return {1, tiles};
+    const int64_t kmax = std::min<int64_t>({kSplitMaxParts, kSplitMaxWorkgroups / shared, nstages / 2});
+    int64_t k = 1;
+    if (leftover) {
+        double best = 1.0;       // unshared, the leftover tiles cost one more tile's time
+        for (int64_t q = 2; q <= kmax; ++q) {
+            const double cost = (double)((shared * q + kComputeUnits - 1) / kComputeUnits) / (double)q + 0.03 * (double)(q - 1);
+            if (cost < best - 1e-9) { best = cost; k = q; }
+        }
+    } else {
+        int64_t fill = std::max<int64_t>(2, (kComputeUnits + shared - 1) / shared);
+        for (int64_t q = 2; q <= kSplitMaxParts; ++q)
+            if ((shared * q) % kComputeUnits == 0) { fill = std::max(fill, q); break; }
+        k = std::min(kmax, fill);
+    }
     if (k < 2) return {1, tiles};
     return {(int)k, tiles - shared};
 }

@@ -182,12 +182,13 @@ def test_eliminate_node_split_tiles_repeatedly(ctx):
 @pytest.mark.parametrize("shape", [(17, 512, 100, 512), (1, 2100, 300, 2100), (3, 1200, 2050, 1230), (65, 256, 512, 256)])
 @pytest.mark.parametrize("hi", [3, 1 << 20, (1 << 28) - 1])
 def test_eliminate_node_last_round_of_workgroups_shares_its_tiles(ctx, shape, hi):
-    # launches of a few more tiles than a multiple of 1024 workgroup slots: the tiles beyond the last full
-    # round are shared by several workgroups each (one launch with whole and shared tiles side by side);
-    # heavy ties / packed keys / compare-select, ragged edges, a batch whose last product is cut in two
+    # launches of a few more tiles than a multiple of the 256 compute units: the tiles left over once
+    # every unit has the same number of whole ones are shared by several workgroups each (one launch with
+    # whole and shared tiles side by side); heavy ties / packed keys / compare-select, ragged edges, a
+    # batch whose last product is cut in two
     batch, Ci, Cj, Ck = shape
     tiles = batch * (-(-Ci // 64)) * (-(-Ck // 64))
-    assert tiles > 1024 and 0 < tiles % 1024 <= 512
+    assert tiles > 1024 and 0 < tiles % 256 <= 128
     rng = np.random.default_rng(tiles + hi % 1000)
     A = rng.integers(0, hi, size=(batch, Ci, Cj), endpoint=True, dtype=np.int32)
     w = rng.integers(0, hi, size=(batch, Cj), endpoint=True, dtype=np.int32)
@@ -202,17 +203,32 @@ def test_eliminate_node_last_round_of_workgroups_shares_its_tiles(ctx, shape, hi
 @pytest.mark.parametrize("shape", [(9, 512, 200, 512), (13, 512, 100, 500), (1, 1600, 300, 1550), (25, 500, 300, 510)])
 @pytest.mark.parametrize("hi", [3, 1 << 20, (1 << 28) - 1])
 def test_eliminate_node_tiles_left_over_after_whole_rounds_are_shared(ctx, shape, hi):
-    # launches whose last round of 1024 workgroup slots is more than half full: what is left once every
-    # compute unit has had the same number of whole tiles (tiles modulo 256, here 64, 64, 113, 64) is
-    # shared by several workgroups each, the rest of the launch is whole tiles
+    # launches of two to six tiles per compute unit and a few more: what is left once every unit has had
+    # the same number of whole tiles (tiles modulo 256, here 64, 64, 113, 64) is shared by several
+    # workgroups each, the rest of the launch is whole tiles
     batch, Ci, Cj, Ck = shape
     tiles = batch * (-(-Ci // 64)) * (-(-Ck // 64))
-    assert tiles % 1024 > 512 and 0 < tiles % 256 <= 128
+    assert tiles > 512 and 0 < tiles % 256 <= 128
     rng = np.random.default_rng(tiles + hi % 1000)
     A = rng.integers(0, hi, size=(batch, Ci, Cj), endpoint=True, dtype=np.int32)
     w = rng.integers(0, hi, size=(batch, Cj), endpoint=True, dtype=np.int32)
     B = rng.integers(0, hi, size=(batch, Cj, Ck), endpoint=True, dtype=np.int32)
     check_products(ctx, A, w, B)
+
+
+@pytest.mark.parametrize("shape", [(5, 512, 300, 512), (7, 500, 200, 512), (1, 1100, 520, 1150), (21, 512, 130, 512)])
+def test_eliminate_node_one_to_five_whole_tiles_per_unit_and_leftovers(ctx, shape):
+    # 320, 448, 324 and 1344 tiles: one whole tile (five in the last case) per compute unit, the other 64,
+    # 192, 68 and 64 tiles shared -- 4, 4, 4 and 2 parts each
+    batch, Ci, Cj, Ck = shape
+    tiles = batch * (-(-Ci // 64)) * (-(-Ck // 64))
+    assert tiles > 256 and tiles % 256 != 0
+    rng = np.random.default_rng(tiles)
+    for hi in (3, 1 << 20):
+        A = rng.integers(0, hi, size=(batch, Ci, Cj), endpoint=True, dtype=np.int32)
+        w = rng.integers(0, hi, size=(batch, Cj), endpoint=True, dtype=np.int32)
+        B = rng.integers(0, hi, size=(batch, Cj, Ck), endpoint=True, dtype=np.int32)
+        check_products(ctx, A, w, B)
 
 
 def test_split_tiles_never_read_a_previous_launchs_partials(ctx):
