@@ -943,6 +943,9 @@ def test_search_long_chains(ctx):
     run_search(ctx, p, wl.SCHEDULE_ROUNDS)
     p = wl.chain_problem(1200, 5, seed=31, tc_range=(0, 1000), ts_range=(0, 1000), tx_range=(0, 1000))
     run_search(ctx, p, wl.SCHEDULE_LEFT_FOLD)
+    # more layers than the undo pass keeps in LDS (4096) and more eliminations than it has threads (1024)
+    p = wl.chain_problem(5000, 2, seed=32, tc_range=(0, 3), ts_range=(0, 3), tx_range=(0, 3))
+    run_search(ctx, p, wl.SCHEDULE_ROUNDS)
     Cn = wl.ragged_counts(2500, 32, 1, 6)
     edges = wl.chain_edges(2500)
     tc, ts, tx = wl.ragged_tables(2500, edges, Cn, 33, 0, 50)
