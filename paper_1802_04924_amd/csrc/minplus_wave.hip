@@ -67,7 +67,11 @@ __global__ __launch_bounds__(kWaveGroup, 4) void minplus_wave_kernel(const WaveA
     __shared__ __attribute__((aligned(16))) int32_t lds[kWavesPerGroup][TS * AST + KC * TS];
 
     constexpr int CELLS = RB * RB;         // output cells per lane
-    __shared__ int32_t merge[SPLIT ? kWavesPerGroup : 1][SPLIT ? 2 * 64 * CELLS + 8 : 1];
+    // Where the wavefronts that share a tile leave their results for the merge: each in its own
+    // stage, which it has finished with by then (a separate array would cost a 16 x 16 launch one
+    // resident workgroup in four).
+    static_assert(2 * 64 * CELLS + 8 <= TS * AST + KC * TS, "a wavefront's results fit its stage");
+    int32_t (*merge)[TS * AST + KC * TS] = lds;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = threadIdx.x & 63;
     const int item = SPLIT ? (int)blockIdx.x : (int)blockIdx.x * kWavesPerGroup + wave;
