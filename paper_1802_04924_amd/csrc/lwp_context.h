@@ -117,9 +117,8 @@ inline bool want_small_tiles(int32_t Ci, int32_t Cj, int32_t Ck, int64_t batch) 
 // and shares the tiles left over (a launch of 4160 tiles: 64 of them), with the number of parts that
 // spreads them most evenly; each further part adds to the merging, which the small term below stands
 // for.  (576 tiles: 90 -> 69 us; 320: 53 -> 43; 1344: 139 -> 130.)
-// Up to one tile per compute unit, all tiles are shared: enough parts for one on every unit and no
-// more (one 512^3 product, 64 tiles: 19.8 -> 18.4 us with 4 parts instead of 8), or the few more that
-// put the same number on every unit (192 tiles: 4 parts instead of 2, 38 -> 32 us).
+// Up to two tiles per compute unit in whole rounds, all tiles are shared, by the same rule (one 512^3
+// product, 64 tiles: 19.8 -> 18.4 us with 4 parts instead of 8; 192 tiles: 4 parts instead of 2, 38 -> 32 us).
 constexpr int64_t kComputeUnits = 256;
 inline Split choose_split(int64_t tiles, int32_t Cj, bool small_tiles) {
     if (!small_tiles) return {1, tiles};
@@ -129,18 +128,15 @@ inline Split choose_split(int64_t tiles, int32_t Cj, bool small_tiles) {
     const int64_t shared = leftover ? tiles % kComputeUnits : (tiles <= kSplitMaxTiles ? tiles : 0);
     if (shared == 0) return {1, tiles};
     const int64_t kmax = std::min<int64_t>({kSplitMaxParts, kSplitMaxWorkgroups / shared, nstages / 2});
+    // time of the shared tiles in units of one tile's: the compute unit with the most parts, plus a
+    // little for every further part to merge.  Leftover tiles may also stay whole (one more tile's
+    // time); a launch of at most a tile per unit is always split (a lone workgroup does not keep a
+    // compute unit busy).
     int64_t k = 1;
-    if (leftover) {
-        double best = 1.0;       // unshared, the leftover tiles cost one more tile's time
-        for (int64_t q = 2; q <= kmax; ++q) {
-            const double cost = (double)((shared * q + kComputeUnits - 1) / kComputeUnits) / (double)q + 0.03 * (double)(q - 1);
-            if (cost < best - 1e-9) { best = cost; k = q; }
-        }
-    } else {
-        int64_t fill = std::max<int64_t>(2, (kComputeUnits + shared - 1) / shared);
-        for (int64_t q = 2; q <= kSplitMaxParts; ++q)
-            if ((shared * q) % kComputeUnits == 0) { fill = std::max(fill, q); break; }
-        k = std::min(kmax, fill);
+    double best = leftover ? 1.0 : 1e9;
+    for (int64_t q = 2; q <= kmax; ++q) {
+        const double cost = (double)((shared * q + kComputeUnits - 1) / kComputeUnits) / (double)q + 0.03 * (double)(q - 1);
+        if (cost < best - 1e-9) { best = cost; k = q; }
     }
     if (k < 2) return {1, tiles};
     return {(int)k, tiles - shared};
