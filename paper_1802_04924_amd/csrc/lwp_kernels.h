@@ -28,10 +28,10 @@ struct NodeDesc {
     int32_t* flag;     // optional: OR-ed with 1 if max A + max w + max B (measured) may leave int32
                        // (2: a promised range broken, 4: skipped by a speculative launch; see NodeArgs)
     int32_t Ci, Cj, Ck;   // shape of this product; read only by launches of mixed shapes
-    // Within the round a search runs the product in: output cells, and operand words (A, w, B), of the
-    // products before this one (each saturating at 2^30).  Read only by the single-workgroup search.
-    int32_t cell_begin, word_begin;
-    int32_t pad;
+    // Output cells of the products before this one within the round a search runs it in (saturating
+    // at 2^30).  Read only by the single-workgroup search, which deals a round's cells to its threads.
+    int32_t cell_begin;
+    int32_t pad[2];
 };
 static_assert(sizeof(NodeDesc) == 128, "descriptor layout");
 
@@ -243,9 +243,11 @@ hipError_t launch_back_substitute(const PairDesc* d_pairs, int32_t n_pairs, cons
 
 // ---- a whole small search in one launch (one workgroup) -------------------------------------------
 // The descriptors are those of the general path; rounds[r] names the edge-sum groups and the node
-// eliminations of round r (ranges into `edges` / `nodes`).  NodeDesc.Ci/Cj/Ck must be set; ranges,
-// rngOut and per-descriptor flags are ignored (overflow is found exactly and OR-ed into *flag, which
-// the kernel first clears).  w receives t_c + t_s for all n_w entries.  keys: one per component.
+// eliminations of round r (ranges into `edges` / `nodes`).  NodeDesc.Ci/Cj/Ck and cell_begin must be
+// set; ranges, rngOut and per-descriptor flags are ignored (overflow is found exactly and OR-ed into
+// *flag, which the kernel first clears).  w receives t_c + t_s for all n_w entries.  Every table a
+// descriptor points at must lie in w, in tx (the caller's tables) or in slots (the intermediate
+// ones): the kernel works on copies of the three regions in LDS.  keys: one per component.
 // result / host_result as launch_back_substitute.
 // A descriptor block of at most kTinyInlineBytes can travel in the kernel arguments instead of device
 // memory (inline_block = 1): the search then needs no upload before its one launch.  The eight

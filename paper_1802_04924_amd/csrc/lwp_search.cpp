@@ -541,16 +541,14 @@ lwp_status Search::write_descriptors(int arith) {
     // A table made by the wavefront-per-tile kernel gets its range measured only if a launch of the
     // tiled kernel consumes it (the descriptor of the producer is patched then).
     std::vector<int64_t> unmeasured(W_.n_ranges, -1);      // range pair -> descriptor of its producer
-    // positions of a round's products among its output cells and operand words (single-workgroup search)
+    // positions of a round's products among its output cells (single-workgroup search)
     auto number_round = [&](size_t first, size_t last) {
         constexpr int64_t cap = int64_t(1) << 30;
-        int64_t cells = 0, words = 0;
+        int64_t cells = 0;
         for (size_t q = first; q < last; ++q) {
             NodeDesc& d = nd[q];
             d.cell_begin = (int32_t)std::min(cells, cap);
-            d.word_begin = (int32_t)std::min(words, cap);
             cells += (int64_t)d.Ci * d.Ck;
-            words += (int64_t)d.Ci * d.Cj + d.Cj + (int64_t)d.Cj * d.Ck;
         }
     };
     size_t ni = 0, gi = 0, nsrc = 0, t = 0;

@@ -524,7 +524,8 @@ constexpr uint32_t kTinyBias = 0x80000000u;
 // LDS holds v ^ 2^31 (the value plus 2^31 as an unsigned number): the sum of three such words is
 // a + w + b + 3 * 2^31, so the two carries of its 32-bit additions tell exactly whether a + w + b
 // fits int32 (it does iff exactly one of them carries), the low word is the biased sum, and unsigned
-// order on it is the order of the sums -- five vector instructions per candidate instead of the
+// order on it is the order of the sums -- seven vector instructions per candidate (two additions,
+// compare, minimum, select, two for addresses; the carries land in scalar registers) instead of the
 // sixteen of 64-bit sums and compares.
 __global__ __launch_bounds__(kUndoThreads) void tiny_search_kernel(const TinyLaunch t) {
     __shared__ unsigned long long smin[kUndoThreads / 64];
