@@ -128,14 +128,21 @@ inline Split choose_split(int64_t tiles, int32_t Cj, bool small_tiles) {
     const int64_t shared = leftover ? tiles % kComputeUnits : (tiles <= kSplitMaxTiles ? tiles : 0);
     if (shared == 0) return {1, tiles};
     const int64_t kmax = std::min<int64_t>({kSplitMaxParts, kSplitMaxWorkgroups / shared, nstages / 2});
-    // time of the shared tiles in units of one tile's: the compute unit with the most parts, plus a
-    // little for every further part to merge.  Leftover tiles may also stay whole (one more tile's
+    // time of the shared tiles in units of one tile's: the compute unit with the most parts (a part is
+    // a whole number of stages), plus a little for every further part to merge.  Leftover tiles may also stay whole (one more tile's
     // time); a launch of at most a tile per unit is always split (a lone workgroup does not keep a
     // compute unit busy).
+    // (A compute unit with one workgroup runs at 0.77 of the rate it reaches with four, with two at
+    // 0.95: slopes of launch time over the number of candidates, 64 / 256 / 1024 tiles.)
     int64_t k = 1;
     double best = leftover ? 1.0 : 1e9;
+    const int64_t whole_per_unit = (tiles - shared) / kComputeUnits;
     for (int64_t q = 2; q <= kmax; ++q) {
-        const double cost = (double)((shared * q + kComputeUnits - 1) / kComputeUnits) / (double)q + 0.03 * (double)(q - 1);
+        const int64_t parts = (shared * q + kComputeUnits - 1) / kComputeUnits;      // on the fullest unit
+        const int64_t resident = whole_per_unit + parts;
+        const double rate = resident >= 3 ? 1.0 : (resident == 2 ? 0.95 : 0.77);
+        const double part = (double)((nstages + q - 1) / q) / (double)nstages;        // of a tile: whole stages
+        const double cost = (double)parts * part / rate + 0.03 * (double)(q - 1);
         if (cost < best - 1e-9) { best = cost; k = q; }
     }
     if (k < 2) return {1, tiles};
