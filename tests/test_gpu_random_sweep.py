@@ -82,3 +82,28 @@ def test_random_searches(ctx, seed0):
                             (case, seed, c_max, hi, schedule, single, wave, undo)
     ctx.set_single_launch(True)
     ctx.set_small_product_kernel(True)
+
+
+def test_random_searches_with_one_count_for_all_nodes(ctx):
+    # the uniform entry point (one C for every node) on the same kind of graphs
+    from paper_1802_04924_amd import plan_graph
+    rng = np.random.default_rng(7)
+    for case in range(600):
+        seed = int(rng.integers(0, 1 << 30))
+        n_ops = int(rng.integers(2, 50))
+        C = int(rng.choice([1, 2, 3, 7, 16, 33, 64, 100]))
+        n, edges = wl.series_parallel_edges(n_ops, seed, p_branch=float(rng.choice([0.0, 0.1])))
+        k = plan_graph(n, edges)["n_residual_nodes"]
+        if k > 2 and float(C) ** k > (1 << 26):
+            C = 3
+        hi = int(rng.choice([1, 1000, 1 << 22]))
+        tc, ts, tx = wl.random_tables(n, edges, C, seed + 3, (0, hi), (0, hi), (0, hi))
+        d = (dev(tc), dev(ts), dev(tx))
+        for schedule in (wl.SCHEDULE_ROUNDS, wl.SCHEDULE_LEFT_FOLD):
+            ref = oracle.search(n, edges, C, tc, ts, tx, schedule)
+            for single in (True, False):
+                ctx.set_single_launch(single)
+                for undo in (0, 1):
+                    cost, S = ctx.search_graph(n, edges, C, *d, schedule, undo)
+                    assert cost == ref["cost"] and np.array_equal(S, ref["strategy"]), (case, seed, C, hi, schedule, single, undo)
+    ctx.set_single_launch(True)
