@@ -49,44 +49,67 @@ lwp_status make_plan(int32_t n_nodes, int32_t n_edges, const int32_t* edges, int
         if ((int32_t)order.size() != n_nodes) { err = "graph has a cycle"; return LWP_E_GRAPH; }
     }
 
+    // Every round walks only what is still alive: the live edges (ascending id) and the nodes not yet
+    // eliminated (ascending id), both compacted after the round -- a schedule in rounds halves a chain
+    // every time, so the whole plan costs about what its first round does.
     std::vector<char> gone(n_nodes, 0), taken(n_nodes, 0);
-    std::vector<int32_t> n_in(n_nodes), n_out(n_nodes), e_in(n_nodes), e_out(n_nodes);
+    std::vector<int32_t> n_in(n_nodes, 0), n_out(n_nodes, 0), e_in(n_nodes), e_out(n_nodes), start_of(n_nodes);
+    std::vector<int32_t> live_e(n_edges), live_v(n_nodes), by_src(n_edges), chosen;
+    for (int32_t e = 0; e < n_edges; ++e) live_e[e] = e;
+    for (int32_t v = 0; v < n_nodes; ++v) live_v[v] = v;
+    // degrees and, where the degree is one, the edge (n_in / n_out of live nodes are zero beforehand)
+    auto count_degrees = [&]() {
+        bool several_out = false;
+        for (int32_t e : live_e) if (E[e].live) {
+            const int32_t s = E[e].src, d = E[e].dst;
+            several_out |= (++n_out[s] == 2);
+            e_out[s] = e;
+            ++n_in[d];
+            e_in[d] = e;
+        }
+        return several_out;
+    };
     int32_t round = 0;
     plan.steps.reserve(n_edges);
-    struct Key { int32_t src, dst, id; };
-    std::vector<Key> keys;
-    keys.reserve(n_edges);
-    std::vector<int32_t> chosen;
     for (;;) {
         // the exhaustive baseline (Sec. 5.2, Table 3) searches the original graph: no eliminations
         if (schedule == LWP_SCHEDULE_NONE) break;
         bool worked = false;
-        // E-phase: live edges ordered by (src, dst, id); equal (src, dst) form a group
-        keys.clear();
-        for (int32_t e = 0; e < n_edges; ++e) if (E[e].live) keys.push_back({E[e].src, E[e].dst, e});
-        std::sort(keys.begin(), keys.end(), [](const Key& a, const Key& b) {
-            return a.src != b.src ? a.src < b.src : (a.dst != b.dst ? a.dst < b.dst : a.id < b.id);
-        });
-        for (size_t g0 = 0; g0 < keys.size();) {
-            size_t g1 = g0 + 1;
-            while (g1 < keys.size() && keys[g1].src == keys[g0].src && keys[g1].dst == keys[g0].dst) ++g1;
-            for (size_t z = g0 + 1; z < g1; ++z) {
-                plan.steps.push_back({1, -1, keys[g0].src, keys[g0].dst, keys[g0].id, keys[z].id, round});
-                E[keys[z].id].live = false;
-                ++plan.n_edge_steps;
-                worked = true;
+        // E-phase.  Parallel edges need a source with several live out-edges; then: the live edges of
+        // every source, ascending id, ordered by destination; equal (src, dst) form a group.  Sources
+        // ascending, destinations ascending within a source.
+        if (count_degrees()) {
+            int32_t run = 0;
+            for (int32_t v : live_v) { run += n_out[v]; start_of[v] = run; }
+            for (size_t x = live_e.size(); x-- > 0;) by_src[--start_of[E[live_e[x]].src]] = live_e[x];
+            bool merged = false;
+            for (int32_t v : live_v) {
+                const int32_t cnt = n_out[v];
+                if (cnt < 2) continue;
+                int32_t* first = by_src.data() + start_of[v];
+                std::stable_sort(first, first + cnt, [&](int32_t a, int32_t b2) { return E[a].dst < E[b2].dst; });
+                for (int32_t g0 = 0; g0 < cnt;) {
+                    int32_t g1 = g0 + 1;
+                    while (g1 < cnt && E[first[g1]].dst == E[first[g0]].dst) ++g1;
+                    for (int32_t z = g0 + 1; z < g1; ++z) {
+                        plan.steps.push_back({1, -1, v, E[first[g0]].dst, first[g0], first[z], round});
+                        E[first[z]].live = false;
+                        ++plan.n_edge_steps;
+                        merged = true;
+                    }
+                    g0 = g1;
+                }
             }
-            g0 = g1;
+            if (merged) {               // the degrees again, without the merged edges
+                worked = true;
+                for (int32_t v : live_v) n_in[v] = n_out[v] = 0;
+                count_degrees();
+            }
         }
         // N-phase
-        for (int32_t v = 0; v < n_nodes; ++v) { n_in[v] = n_out[v] = 0; taken[v] = 0; }
-        for (int32_t e = 0; e < n_edges; ++e) if (E[e].live) {
-            n_out[E[e].src]++; e_out[E[e].src] = e;
-            n_in[E[e].dst]++;  e_in[E[e].dst] = e;
-        }
         chosen.clear();
-        for (int32_t j = 0; j < n_nodes; ++j) {
-            if (gone[j] || n_in[j] != 1 || n_out[j] != 1) continue;
+        for (int32_t j : live_v) {
+            if (n_in[j] != 1 || n_out[j] != 1) continue;
             int32_t i = E[e_in[j]].src, k = E[e_out[j]].dst;
             if (taken[i] || taken[k]) continue;
             taken[j] = 1;
@@ -104,6 +127,15 @@ lwp_status make_plan(int32_t n_nodes, int32_t n_edges, const int32_t* edges, int
             worked = true;
         }
         if (!worked) break;
+        live_e.erase(std::remove_if(live_e.begin(), live_e.end(), [&](int32_t e) { return !E[e].live; }), live_e.end());
+        size_t keep = 0;
+        for (int32_t v : live_v) {
+            if (gone[v]) continue;
+            n_in[v] = n_out[v] = 0;
+            taken[v] = 0;
+            live_v[keep++] = v;
+        }
+        live_v.resize(keep);
         ++round;
     }
     plan.n_rounds = round;

@@ -69,6 +69,8 @@ Layout plan_buffers(const Plan& plan, int32_t n_nodes, int32_t n_edges, const in
         if (Cn[v] != Cn[0]) L.uniform = false;
     }
     std::vector<TableRef> cur(n_edges);
+    L.node_A.reserve(plan.n_node_steps); L.node_B.reserve(plan.n_node_steps); L.node_out.reserve(plan.n_node_steps);
+    L.node_arg_off.reserve(plan.n_node_steps);
     L.tx_off[0] = 0;
     for (int32_t e = 0; e < n_edges; ++e) {
         cur[e] = {false, L.tx_off[e], Cn[edges[2 * e]], Cn[edges[2 * e + 1]]};
@@ -86,10 +88,11 @@ Layout plan_buffers(const Plan& plan, int32_t n_nodes, int32_t n_edges, const in
     auto give_back = [&](const std::vector<TableRef>& rs) { for (auto& r : rs) free_regions[r.cells()].push_back(r.off); };
     size_t t = 0;
     const size_t n = plan.steps.size();
+    std::vector<TableRef> release;
     while (t < n) {
         const int32_t round = plan.steps[t].round;
         // E-phase of this round
-        std::vector<TableRef> release;
+        release.clear();
         while (t < n && plan.steps[t].round == round && plan.steps[t].kind == 1) {
             EdgeGroup g{plan.steps[t].e1, {}, round};
             while (t < n && plan.steps[t].round == round && plan.steps[t].kind == 1 && plan.steps[t].e1 == g.keep) {
@@ -100,7 +103,7 @@ Layout plan_buffers(const Plan& plan, int32_t n_nodes, int32_t n_edges, const in
             for (int32_t o : g.others) { src.push_back(cur[o]); if (cur[o].is_slot) release.push_back(cur[o]); }
             const TableRef out = cur[g.keep].is_slot ? cur[g.keep] : take(cur[g.keep].rows, cur[g.keep].cols);   // in place when possible
             cur[g.keep] = out;
-            L.groups.push_back(g); L.group_src.push_back(src); L.group_out.push_back(out);
+            L.groups.push_back(std::move(g)); L.group_src.push_back(std::move(src)); L.group_out.push_back(out);
         }
         give_back(release);
         release.clear();
