@@ -606,10 +606,12 @@ lwp_status Search::write_descriptors(int arith) {
         // kernel variant per product: the search's arithmetic, and the tile size from the number of
         // tiles the products of that shape make
         auto shape_of = [](const NodeWork& a) { return std::make_tuple(a.Ci, a.Cj, a.Ck); };
+        // (with one count for all nodes every product has the same shape: no table needed)
         std::map<std::tuple<int32_t, int32_t, int32_t>, int64_t> shape_count;
-        for (const NodeWork& x : work) ++shape_count[shape_of(x)];
+        if (!L.uniform) for (const NodeWork& x : work) ++shape_count[shape_of(x)];
+        const size_t n_shapes = L.uniform ? (work.empty() ? 0 : 1) : shape_count.size();
         for (NodeWork& x : work) {
-            const bool prefer_small = want_small_tiles(x.Ci, x.Cj, x.Ck, shape_count[shape_of(x)]);
+            const bool prefer_small = want_small_tiles(x.Ci, x.Cj, x.Ck, L.uniform ? (int64_t)work.size() : shape_count[shape_of(x)]);
             x.variant = 2 * arith + (prefer_small ? 0 : 1);
         }
         // A round with little work runs as one launch of the kernel that gives every wavefront a tile
@@ -623,7 +625,7 @@ lwp_status Search::write_descriptors(int arith) {
             for (const NodeWork& x : work) round_cells += (int64_t)x.Ci * x.Ck;
             const int rb = wave_tile_rb(t16, round_updates / round_cells);
             const int ts = 8 * rb;
-            const bool one_shape = shape_count.size() == 1;
+            const bool one_shape = n_shapes == 1;
             NodeLaunch nl{n0, work.size(), work[0].Ci, work[0].Cj, work[0].Ck, 2 * (stored ? kArithPlain : kArithValue), -1, 0, 0, round_updates, rb};
             int64_t tiles = 0;
             if (!one_shape) nl.tile_begin = (int64_t)n_tbeg;
