@@ -182,6 +182,8 @@ class Workload:
                 p = wl.config4(args.layers, args.configs or 4096)
             elif name in ("cfg1", "vgg16"):
                 # tables of the AlexNet- / VGG-16-shaped chain come from the library's own cost-model kernels
+                if args.configs:
+                    raise SystemExit(f"bench.py: {name} takes its 256 configurations per layer from the cost model; --configs does not apply")
                 p = wl.config1() if name == "cfg1" else wl.vgg16_problem()
                 with Context(0) as c1:
                     tabs = c1.build_cost_tables(p["layers"], p["edges"], p["configs"], p["machine"])
