@@ -89,7 +89,7 @@ lwp_status lwp_synchronize(lwp_ctx *ctx);
  * instead of a dozen dependent launches; 0 sends every search down the general path.  Results are
  * identical.
  * LWP_OPT_SMALL_PRODUCT_KERNEL (default 1): node eliminations with little work -- one call, or one
- * round of a search, below 100 million (3 * 2^25) cell updates (2^24 for a call with promised ranges)
+ * round of a search, below 100 million (3 * 2^25) cell updates (2^25 for a call with promised ranges)
  * -- run on a kernel that gives every wavefront a small
  * output tile of its own instead of the tiled kernel, whose launch would be mostly latency at that
  * size; 0 sends every node elimination to the tiled kernel.  Results are identical; the overflow

@@ -36,7 +36,7 @@ def check_products(ctx, A, w, B, expect_keyed=None, expect_keyed_bounded=None):
     entry points: lwp_eliminate_node (ranges measured and variant picked on the device, per product)
     and lwp_eliminate_node_bounded (the caller promises ranges -- here the exact ones -- and the host
     picks the variant).  expect_keyed: whether packed keys (global or per row) must have been used
-    by the tiled kernel.  A call below 3 * 2^25 cell updates (2^24 with promised ranges) is first checked on the kernel it takes by default, the wavefront-per-tile one
+    by the tiled kernel.  A call below 3 * 2^25 cell updates (2^25 with promised ranges) is first checked on the kernel it takes by default, the wavefront-per-tile one
     (compare/select), then on the tiled kernel."""
     d_A, d_w, d_B = dev(A), dev(w), dev(B)
     batch = A.shape[0]
@@ -45,7 +45,7 @@ def check_products(ctx, A, w, B, expect_keyed=None, expect_keyed_bounded=None):
     updates = A.shape[0] * A.shape[1] * A.shape[2] * B.shape[2]
     if updates <= (3 << 25):
         ctx.profile_enable(True)
-        for bnd in ((None, bounds) if updates <= (1 << 24) else (None,)):
+        for bnd in ((None, bounds) if updates <= (1 << 25) else (None,)):
             ctx.profile_reset()
             out, arg = ctx.eliminate_node(d_A, d_w, d_B, bounds=bnd)
             ctx.synchronize()
