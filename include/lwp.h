@@ -89,10 +89,10 @@ lwp_status lwp_synchronize(lwp_ctx *ctx);
  * instead of a dozen dependent launches; 0 sends every search down the general path.  Results are
  * identical.
  * LWP_OPT_SMALL_PRODUCT_KERNEL (default 1): node eliminations with little work -- one call, or one
- * round of a search, below 100 million (3 * 2^25) cell updates (2^25 for a call with promised ranges)
- * -- run on a kernel that gives every wavefront a small
- * output tile of its own instead of the tiled kernel, whose launch would be mostly latency at that
- * size; 0 sends every node elimination to the tiled kernel.  Results are identical; the overflow
+ * round of a search, below 100 million (3 * 2^25) cell updates (2^25 for a call with promised
+ * ranges and more than four 64 x 64 output tiles) -- run on a kernel that gives every wavefront a
+ * small output tile of its own instead of the tiled kernel, whose launch would be mostly latency
+ * at that size; 0 sends every node elimination to the tiled kernel.  Results are identical; the overflow
  * test of the small-product kernel is the same formula applied to the values each wavefront reads,
  * so it is at least as tight. */
 typedef enum { LWP_OPT_SINGLE_LAUNCH = 0, LWP_OPT_SMALL_PRODUCT_KERNEL = 1 } lwp_option;

@@ -203,7 +203,10 @@ lwp_status lwp_eliminate_node_bounded(lwp_ctx* ctx, int32_t batch, int32_t Ci, i
     if (!fits(rA.lo + rw.lo + rB.lo) || !fits(rA.hi + rw.hi + rB.hi) || !fits(rA.lo + rw.lo) || !fits(rA.hi + rw.hi))
         return fail(ctx, LWP_E_OVERFLOW, "A + w + B may leave int32 within the promised ranges");
     if (lwp_status s = ensure_state(ctx)) return s;
-    if (ctx->wave_kernel && wave_call(c, kWaveMaxUpdatesBounded)) {
+    // (a call of at most four 64 x 64 tiles with long rows stays there up to the general limit: with so
+    // few tiles the tiled kernel cannot spread the rows over the chip -- 64 x 16384 x 64: 107 against 167 us)
+    const int64_t tiles64 = (int64_t)((Ci + 63) / 64) * ((Ck + 63) / 64) * batch;
+    if (ctx->wave_kernel && wave_call(c, tiles64 <= kWaveFewTiles ? kWaveMaxUpdates : kWaveMaxUpdatesBounded)) {
         const NodeScratch sc{nullptr, nullptr, nullptr, ctx->dstate, ctx->dstate + 1};
         const int64_t promised[6] = {rA.lo, rA.hi, rw.lo, rw.hi, rB.lo, rB.hi};
         ScopedTimer tm(ctx, 0, (int64_t)batch * Ci * Cj * Ck, false);

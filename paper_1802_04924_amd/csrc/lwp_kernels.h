@@ -121,6 +121,7 @@ hipError_t launch_minplus_wave(const NodeArgs& args, const NodeDesc* h_descs, in
 // the candidates still fills a wavefront's pipeline -- a 16 x 16 tile loads half as much per update;
 // else 8 x 8 (four times as many, smaller pieces to spread over the chip).
 constexpr int64_t kWaveMaxUpdates = (int64_t)3 << 25, kWaveMaxUpdatesBounded = (int64_t)1 << 25;
+constexpr int64_t kWaveFewTiles = 4;       // calls with promised ranges and at most this many 64 x 64 tiles: kWaveMaxUpdates
 constexpr int64_t kWaveFillTiles = 2048;
 // four wavefronts per tile: a launch of at most this many tiles of 8 x 8, or of 16 x 16
 constexpr int kWaveSplitTiles = 1024, kWaveSplitTiles16 = 1536;

@@ -36,7 +36,7 @@ def check_products(ctx, A, w, B, expect_keyed=None, expect_keyed_bounded=None):
     entry points: lwp_eliminate_node (ranges measured and variant picked on the device, per product)
     and lwp_eliminate_node_bounded (the caller promises ranges -- here the exact ones -- and the host
     picks the variant).  expect_keyed: whether packed keys (global or per row) must have been used
-    by the tiled kernel.  A call below 3 * 2^25 cell updates (2^25 with promised ranges) is first checked on the kernel it takes by default, the wavefront-per-tile one
+    by the tiled kernel.  A call below 3 * 2^25 cell updates (2^25 with promised ranges, unless it has at most four 64 x 64 tiles) is first checked on the kernel it takes by default, the wavefront-per-tile one
     (compare/select), then on the tiled kernel."""
     d_A, d_w, d_B = dev(A), dev(w), dev(B)
     batch = A.shape[0]
@@ -45,7 +45,8 @@ def check_products(ctx, A, w, B, expect_keyed=None, expect_keyed_bounded=None):
     updates = A.shape[0] * A.shape[1] * A.shape[2] * B.shape[2]
     if updates <= (3 << 25):
         ctx.profile_enable(True)
-        for bnd in ((None, bounds) if updates <= (1 << 25) else (None,)):
+        tiles64 = batch * -(-A.shape[1] // 64) * -(-B.shape[2] // 64)
+        for bnd in ((None, bounds) if updates <= (1 << 25) or tiles64 <= 4 else (None,)):
             ctx.profile_reset()
             out, arg = ctx.eliminate_node(d_A, d_w, d_B, bounds=bnd)
             ctx.synchronize()
@@ -111,14 +112,16 @@ def test_eliminate_node_keyed_small_values(ctx, shape, hi):
 
 
 @pytest.mark.parametrize("shape", [(64, 128, 16, 128), (100, 70, 33, 90), (300, 40, 130, 56), (2100, 16, 5, 16), (1, 1, 1000, 1), (3, 2, 1024, 3), (1, 9, 1025, 9), (1, 3, 40000, 2), (7, 250, 40, 250), (4, 200, 60, 200),
-                                   (3, 250, 201, 250), (1, 130, 1000, 140), (2, 33, 203, 500), (5, 250, 210, 250)])
+                                   (3, 250, 201, 250), (1, 130, 1000, 140), (2, 33, 203, 500), (5, 250, 210, 250),
+                                   (1, 64, 12000, 70)])
 @pytest.mark.parametrize("hi", [2, 1 << 24])
 def test_eliminate_node_many_small_products(ctx, shape, hi):
     # calls below 2^27 cell updates with enough output for a wavefront per 16 x 16 tile (at least 2048 of
     # them), ragged in every dimension, with ties (hi = 2) and without; then long rows, where four
     # wavefronts share an 8 x 8 tile, their shares of the candidates ragged; then two: between 4096 and
     # 8192 tiles of 8 x 8 (short chunks, a tile per wavefront) and between 1024 and 4096 (long chunks);
-    # the last four: 64 to 1536 tiles of 16 x 16 with rows of at least 200 candidates, where four
+    # (the very last: two 64 x 64 tiles with rows of 12000, beyond 2^25 cell updates -- on the wavefront-per-tile
+    # kernel also with promised ranges); the four before it: 64 to 1536 tiles of 16 x 16 with rows of at least 200 candidates, where four
     # wavefronts share a 16 x 16 tile (shares of 51, 51, 51, 48; of 250 each in chunks of 64; 51, 51, 51, 50)
     batch, Ci, Cj, Ck = shape
     rng = np.random.default_rng(abs(hash((shape, hi))) % (1 << 32))
