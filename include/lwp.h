@@ -106,11 +106,13 @@ lwp_status lwp_set_option(lwp_ctx *ctx, int32_t option, int32_t value);
  * DEVICE, dense, row-major: A [batch][Ci][Cj], w [batch][Cj], B [batch][Cj][Ck],
  * out [batch][Ci][Ck], argmin [batch][Ci][Ck] (may be NULL: then only the minimum is computed,
  * by a variant without argmin bookkeeping).  out/argmin must not overlap the inputs.  Sizes: batch, Ci, Cj, Ck >= 1, Cj <= 65536.
- * Enqueues and returns.  Nothing is assumed about the values: one pass measures the value ranges
- * of A, w and B of every product on the device, and the product kernels pick their arithmetic
- * variant per product from those ranges, also on the device (a call with little work needs neither:
- * see LWP_OPT_SMALL_PRODUCT_KERNEL).  If max A + max w + max B (or the
- * minima) of a product could leave int32 the next lwp_synchronize returns LWP_E_OVERFLOW. */
+ * Enqueues and returns.  Nothing is assumed about the values: their ranges are measured on the
+ * device -- by one pass over A, w and B of every product, or, where that is cheaper (few output
+ * tiles, or products of at most two tiles a side), by every workgroup of the product kernel over
+ * the rows of A, the columns of B and the w that its tile reads -- and the product kernel picks
+ * its arithmetic variant from them, also on the device (a call with little work needs neither:
+ * see LWP_OPT_SMALL_PRODUCT_KERNEL).  If max A + max w + max B (or the minima) over what was
+ * measured could leave int32 the next lwp_synchronize returns LWP_E_OVERFLOW. */
 lwp_status lwp_eliminate_node(lwp_ctx *ctx, int32_t batch, int32_t Ci, int32_t Cj, int32_t Ck,
                               const int32_t *d_A, const int32_t *d_w, const int32_t *d_B,
                               int32_t *d_out, int32_t *d_argmin);

@@ -65,6 +65,10 @@ struct NodeArgs {
     int64_t auto_limit;
     // optional: element `mode` is incremented once per product that this launch works on
     int32_t* mode_count;
+    // non-zero: nothing is known or has been measured about the values; every workgroup takes the
+    // ranges of the strips of A and B and of the w its tile reads, in place of the descriptor's bounds
+    // and measured ranges (which are ignored).  Not with promised ranges (verify).
+    int32_t self_measure;
 };
 constexpr int64_t kSplitScratchIntsPerPart = 2 * 16 * 256;
 // Capacity of the split-tile buffers every caller of launch_minplus provides: scratch for

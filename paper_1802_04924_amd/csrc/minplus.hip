@@ -133,6 +133,95 @@ __device__ __forceinline__ void decode_work(const NodeArgs& p, TileWork& w) {
     }
 }
 
+// Origin of tile `tl` of a product with tilesM x tilesN tiles: tiles are walked in panels of 8 tile
+// rows, column by column (see decode_work).
+__device__ __forceinline__ void tile_origin(int tl, int tilesM, int tilesN, int& tmi, int& tni) {
+    constexpr int PANEL = 8;
+    const int panel = tl / (PANEL * tilesN);
+    const int prow0 = panel * PANEL;
+    const int prows = min(PANEL, tilesM - prow0);
+    const int within = tl - panel * PANEL * tilesN;
+    tni = within / prows;
+    tmi = prow0 + (within - tni * prows);
+}
+
+// A call that knows nothing about its values and has measured nothing: the workgroup takes {min, max}
+// of what ITS tile reads -- the TM rows of A, all of w, the TN columns of B -- and puts them where the
+// caller's bounds would be.  Everything derived from ranges (overflow test, variant, key width, the
+// clamp) then holds for this tile: its sums are sums of these elements, and the minimum of w is
+// attained at some c of the product, where A and B are within the strips' ranges.  The pass reads
+// what the main loop reads again right after (from L2); it replaces a launch of its own over all of
+// A, w and B.  All parts of a shared tile scan the whole strips and so agree on every parameter.
+// red: 24 words of LDS, free until the first stage is stored.
+struct StripRanges { int loA, hiA, loW, hiW, loB, hiB; };
+// (Not inlined: the scan runs once per workgroup before anything else, and inlined into the tile
+// function it took registers from the main loop.)
+template <int TM>
+__device__ __noinline__ StripRanges measure_strips(const int32_t* A_, const int32_t* W_, const int32_t* B_, int Ci, int Cj,
+                                                   int Ck, int a0, int b0, int* red) {
+    constexpr int TN = TM;
+    using gcptr = const int32_t __attribute__((address_space(1)))*;
+    const gcptr A = (gcptr)(uintptr_t)A_;
+    const gcptr W = (gcptr)(uintptr_t)W_;
+    const gcptr B = (gcptr)(uintptr_t)B_;
+    const int tid = threadIdx.x;
+    int loA = 0x7fffffff, hiA = (int)0x80000000, loW = loA, hiW = hiA, loB = loA, hiB = hiA;
+    auto take4 = [](const v4i x, int& lo, int& hi) {
+        lo = min(min(lo, x.x), min(x.y, min(x.z, x.w)));
+        hi = max(max(hi, x.x), max(x.y, max(x.z, x.w)));
+    };
+    {   // A: NT / TM threads per row (rows past the end repeat the last one)
+        constexpr int TPRM = NT / TM;
+        const gcptr Arow = A + (int64_t)min(a0 + tid / TPRM, Ci - 1) * Cj;
+        const int seg = tid % TPRM;
+        if (((Cj & 3) == 0) && ((((uintptr_t)A_) & 15) == 0)) {
+#pragma unroll 8
+            for (int c = seg * 4; c < Cj; c += TPRM * 4) take4(*(gv4cptr)(Arow + c), loA, hiA);
+        } else {
+#pragma unroll 8
+            for (int c = seg; c < Cj; c += TPRM) { const int v = Arow[c]; loA = min(loA, v); hiA = max(hiA, v); }
+        }
+    }
+#pragma unroll 4
+    for (int c = tid; c < Cj; c += NT) { const int v = W[c]; loW = min(loW, v); hiW = max(hiW, v); }
+    if (((Ck & 3) == 0) && ((((uintptr_t)B_) & 15) == 0) && (b0 + TN <= Ck)) {
+        constexpr int TPB = TN / 4;               // threads per row of the strip
+        const gcptr Bcol = B + b0 + (tid % TPB) * 4;
+#pragma unroll 8
+        for (int c = tid / TPB; c < Cj; c += NT / TPB) take4(*(gv4cptr)(Bcol + (int64_t)c * Ck), loB, hiB);
+    } else {
+        const gcptr Bcol = B + min(b0 + tid % TN, Ck - 1);          // columns past the end repeat the last one
+#pragma unroll 8
+        for (int c = tid / TN; c < Cj; c += NT / TN) { const int v = Bcol[(int64_t)c * Ck]; loB = min(loB, v); hiB = max(hiB, v); }
+    }
+    loA = wave_min_i32(loA); hiA = wave_max_i32(hiA); loW = wave_min_i32(loW); hiW = wave_max_i32(hiW);
+    loB = wave_min_i32(loB); hiB = wave_max_i32(hiB);
+    if ((tid & 63) == 0) {
+        int* r = red + 6 * (tid >> 6);
+        r[0] = loA; r[1] = hiA; r[2] = loW; r[3] = hiW; r[4] = loB; r[5] = hiB;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < NT / 64; ++q) {
+        loA = min(loA, red[6 * q]); hiA = max(hiA, red[6 * q + 1]); loW = min(loW, red[6 * q + 2]);
+        hiW = max(hiW, red[6 * q + 3]); loB = min(loB, red[6 * q + 4]); hiB = max(hiB, red[6 * q + 5]);
+    }
+    __syncthreads();                              // red is part of the first stage's buffer
+    return {loA, hiA, loW, hiW, loB, hiB};
+}
+template <int RB, bool MIXED>
+__device__ __forceinline__ void measure_own_strips(const NodeArgs& p, TileWork& work, int* red) {
+    constexpr int TM = 16 * RB, TN = 16 * RB;
+    NodeDesc& d = work.d;
+    const int Ci = MIXED ? d.Ci : p.Ci, Cj = MIXED ? d.Cj : p.Cj, Ck = MIXED ? d.Ck : p.Ck;
+    const int tilesM = MIXED ? (Ci + TM - 1) / TM : p.tilesM, tilesN = MIXED ? (Ck + TN - 1) / TN : p.tilesN;
+    int tmi, tni;
+    tile_origin(work.tl, tilesM, tilesN, tmi, tni);
+    const StripRanges r = measure_strips<TM>(d.A, d.w, d.B, Ci, Cj, Ck, tmi * TM, tni * TN, red);
+    d.loA = r.loA; d.hiA = r.hiA; d.loW = r.loW; d.hiW = r.hiW; d.loB = r.loB; d.hiB = r.hiB;
+    d.rngA = nullptr; d.rngW = nullptr; d.rngB = nullptr;
+}
+
 // One workgroup's tile (or part of a shared tile).  smA / smB: the double-buffered LDS stages
 // (2 * TK * 16 RB words each), smRow: 16 RB words (row-rebased keys only), smMisc: 16 words.
 template <int MODE, int RB, int TK, bool MIXED, bool VERIFY>
@@ -164,13 +253,8 @@ __device__ __forceinline__ void minplus_tile(const NodeArgs& p, const TileWork& 
     __builtin_amdgcn_s_setprio(3);
     const int Ci = MIXED ? d.Ci : p.Ci, Cj = MIXED ? d.Cj : p.Cj, Ck = MIXED ? d.Ck : p.Ck;
     const int tilesM = MIXED ? (Ci + TM - 1) / TM : p.tilesM, tilesN = MIXED ? (Ck + TN - 1) / TN : p.tilesN;
-    constexpr int PANEL = 8;
-    const int panel = tl / (PANEL * tilesN);
-    const int prow0 = panel * PANEL;
-    const int prows = min(PANEL, tilesM - prow0);
-    const int within = tl - panel * PANEL * tilesN;
-    const int tni = within / prows;
-    const int tmi = prow0 + (within - tni * prows);
+    int tmi, tni;
+    tile_origin(tl, tilesM, tilesN, tmi, tni);
     const int a0 = tmi * TM, b0 = tni * TN;
 
     // Pointers read from a descriptor are generic to the compiler; say that they are global memory,
@@ -607,7 +691,7 @@ __device__ __forceinline__ void minplus_tile(const NodeArgs& p, const TileWork& 
     }
 }
 
-template <int MODE, int RB, int TK, bool MIXED = false, bool VERIFY = false>
+template <int MODE, int RB, int TK, bool MIXED = false, bool VERIFY = false, bool SELF = false>
 __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) void minplus_kernel(const NodeArgs p) {
     __shared__ __attribute__((aligned(16))) uint32_t smA[2 * TK * 16 * RB];
     __shared__ __attribute__((aligned(16))) uint32_t smB[2 * TK * 16 * RB];
@@ -615,6 +699,7 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
     __shared__ int smMisc[16];
     TileWork work;
     decode_work<RB, MIXED>(p, work);
+    if (SELF) measure_own_strips<RB, MIXED>(p, work, reinterpret_cast<int*>(smA));
     minplus_tile<MODE, RB, TK, MIXED, VERIFY>(p, work, smA, smB, smRow, smMisc);
 }
 
@@ -622,7 +707,7 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : (MODE == kModePlain ? 1 : 2)) voi
 // then needs to know nothing about the tables' values and no value has to travel back to it.
 // auto_limit: largest spread packed keys on global offsets may have at this tile size; auto_row:
 // keys re-based per row are a candidate (64 x 64 tiles, launches large enough for their extra pass).
-template <int RB, int TK, bool MIXED = false>
+template <int RB, int TK, bool MIXED = false, bool SELF = false>
 __global__ __launch_bounds__(NT, RB == 4 ? 4 : 2) void minplus_auto_kernel(const NodeArgs p) {
     __shared__ __attribute__((aligned(16))) uint32_t smA[2 * TK * 16 * RB];
     __shared__ __attribute__((aligned(16))) uint32_t smB[2 * TK * 16 * RB];
@@ -630,6 +715,7 @@ __global__ __launch_bounds__(NT, RB == 4 ? 4 : 2) void minplus_auto_kernel(const
     __shared__ int smMisc[16];
     TileWork work;
     decode_work<RB, MIXED>(p, work);
+    if (SELF) measure_own_strips<RB, MIXED>(p, work, reinterpret_cast<int*>(smA));   // (a kernel of its own: the others stay as they are)
     using gcptr = const int32_t __attribute__((address_space(1)))*;
     const NodeDesc& d = work.d;
     long long loA = d.loA, hiA = d.hiA, loB = d.loB, hiB = d.hiB, loW = d.loW, hiW = d.hiW;
@@ -660,10 +746,18 @@ hipError_t launch_minplus(const NodeArgs& args, int mode, bool small_tiles, hipS
     if (mixed && (!small_tiles || !args.descs)) return hipErrorInvalidValue;
     if (mode == kModeKeyedRow && !small_tiles) return hipErrorInvalidValue;
     if (verify && (mixed || args.descs || mode == kModeAuto || args.base.rngA || args.base.rngW || args.base.rngB)) return hipErrorInvalidValue;
+    // tile-local measurement: the kernel that picks the variant, or the value-only kernel
+    if (args.self_measure && (verify || mixed || (mode != kModeAuto && mode != kModeValue))) return hipErrorInvalidValue;
     dim3 grid((unsigned)blocks), block(NT);
 #define LWP_LAUNCH(MODE, RB, TK, MIXED, VERIFY) \
     hipLaunchKernelGGL((minplus_kernel<MODE, RB, TK, MIXED, VERIFY>), grid, block, 0, stream, args)
-    if (mode == kModeAuto) {
+    if (mode == kModeValue && args.self_measure) {
+        if (small_tiles) hipLaunchKernelGGL((minplus_kernel<kModeValue, 4, 32, false, false, true>), grid, block, 0, stream, args);
+        else hipLaunchKernelGGL((minplus_kernel<kModeValue, 8, 16, false, false, true>), grid, block, 0, stream, args);
+    } else if (mode == kModeAuto && args.self_measure) {
+        if (small_tiles) hipLaunchKernelGGL((minplus_auto_kernel<4, 32, false, true>), grid, block, 0, stream, args);
+        else hipLaunchKernelGGL((minplus_auto_kernel<8, 16, false, true>), grid, block, 0, stream, args);
+    } else if (mode == kModeAuto) {
         if (mixed) hipLaunchKernelGGL((minplus_auto_kernel<4, 32, true>), grid, block, 0, stream, args);
         else if (small_tiles) hipLaunchKernelGGL((minplus_auto_kernel<4, 32, false>), grid, block, 0, stream, args);
         else hipLaunchKernelGGL((minplus_auto_kernel<8, 16, false>), grid, block, 0, stream, args);

@@ -234,6 +234,38 @@ def test_eliminate_node_one_to_five_whole_tiles_per_unit_and_leftovers(ctx, shap
         check_products(ctx, A, w, B)
 
 
+@pytest.mark.parametrize("want_argmin", [True, False])
+def test_eliminate_node_ranges_taken_tile_by_tile(ctx, want_argmin):
+    # lwp_eliminate_node with few output tiles: every workgroup measures the rows of A, the columns of B and
+    # the w its own tile reads, and picks its arithmetic from them.  Here the tiles of one product differ:
+    # rows 0..63 of A and columns 0..63 of B are narrow (packed keys), the rest spreads over 2^28 (compare /
+    # select), one block is negative; ties within the narrow blocks; three products at different levels.
+    # The tiled kernel is forced (the call is small enough for the other one); then a batch of 700 products
+    # of one tile each, the form batches of small products take.
+    rng = np.random.default_rng(64)
+    batch, Ci, Cj, Ck = 3, 200, 300, 260
+    A = rng.integers(0, 3, size=(batch, Ci, Cj), endpoint=True, dtype=np.int32)
+    A[:, 64:128] = rng.integers(0, 1 << 28, size=(batch, 64, Cj), dtype=np.int32)
+    A[:, 128:] = rng.integers(-(1 << 27), 0, size=(batch, Ci - 128, Cj), dtype=np.int32)
+    w = rng.integers(0, 5, size=(batch, Cj), endpoint=True, dtype=np.int32) + np.arange(batch, dtype=np.int32)[:, None] * 100000
+    B = rng.integers(0, 3, size=(batch, Cj, Ck), endpoint=True, dtype=np.int32)
+    B[:, :, 64:192] = rng.integers(0, 1 << 28, size=(batch, Cj, 128), dtype=np.int32)
+    ctx.set_small_product_kernel(False)
+    try:
+        for a, ww, b in ((A, w, B), (A[:, :40, :33].repeat(234, axis=0)[:700] + 0, w[:, :33].repeat(234, axis=0)[:700] + 0,
+                                     B[:, :33, 60:110].repeat(234, axis=0)[:700] + 0)):
+            out, arg = ctx.eliminate_node(dev(a), dev(ww), dev(b), want_argmin=want_argmin)
+            ctx.synchronize()
+            out = out.cpu().numpy()
+            for q in range(0, a.shape[0], max(1, a.shape[0] // 7)):
+                ro, ra = oracle.minplus_argmin(a[q], ww[q], b[q])
+                assert np.array_equal(out[q], ro)
+                if want_argmin:
+                    assert np.array_equal(arg[q].cpu().numpy(), ra)
+    finally:
+        ctx.set_small_product_kernel(True)
+
+
 def test_split_tiles_never_read_a_previous_launchs_partials(ctx):
     # the parts of a tile meet in scratch memory that every launch reuses: with fresh data per launch
     # a part published too late (or read too early) would show as a result of the launch before
